@@ -1,0 +1,259 @@
+/*
+ * gpuos.h -- C ABI of the MI355X-native GPUOS hot path.
+ *
+ * One long-lived ("persistent") HIP worker kernel drains a host-fed ring of
+ * task descriptors and executes small tensor operations (elementwise ops and
+ * last-dim reductions over <=6-D strided / broadcast tensors) through a
+ * versioned dual-slot operator table.  The design follows the paper's
+ * Section 4.1 (ring buffer channel, persistent kernel executor, dynamic
+ * operator table), Section 4.2 (task submission protocol: acquire slot,
+ * write, commit with a store-release; device poll with a load-acquire) and
+ * Section 5.4 / Table 1 (host runtime calls init, fuse, set_yield_every,
+ * peek_queue, worker_alive, shutdown).
+ *
+ * Conventions that hold for every call below
+ *   - plain C types only; `void*` tensor pointers are DEVICE pointers that the
+ *     caller owns (allocated beforehand, paper Section 4.3) and keeps alive
+ *     and unmodified until gpuos_wait() has covered the ticket;
+ *   - every call returns 0 (GPUOS_OK) or a negative gpuos_status; nothing
+ *     throws or aborts across this boundary;
+ *   - a context has ONE producer thread (the paper's single-producer ring);
+ *     gpuos_swap_op may be called from that thread between submits;
+ *   - while a context is alive the worker kernel is resident on its own
+ *     non-blocking stream: the caller must not call hipDeviceSynchronize(),
+ *     hipFree() or anything else that waits for "all streams" before
+ *     gpuos_shutdown(), or the process deadlocks.
+ */
+#ifndef GPUOS_H_
+#define GPUOS_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GPUOS_MAX_DIMS   6      /* generic tensor descriptor: up to 6 dims        */
+#define GPUOS_MAX_INPUTS 3
+#define GPUOS_MAX_OPS    256    /* logical operator ids are 0 .. 255              */
+#define GPUOS_ALL        (~0ull)/* gpuos_wait: every ticket submitted so far      */
+
+typedef struct gpuos_ctx gpuos_ctx;   /* opaque; owned by the library */
+
+/* ---- status codes ------------------------------------------------------ */
+enum gpuos_status {
+  GPUOS_OK        =  0,
+  GPUOS_E_INVAL   = -1,   /* malformed argument or descriptor                     */
+  GPUOS_E_FULL    = -2,   /* non-blocking submit: not enough free ring slots      */
+  GPUOS_E_BADOP   = -3,   /* unknown / unregistered / failed operator             */
+  GPUOS_E_TIMEOUT = -4,   /* a bounded wait ran out                               */
+  GPUOS_E_DEAD    = -5,   /* worker kernel is not running (shutdown / watchdog)   */
+  GPUOS_E_HIP     = -6,   /* a HIP runtime call failed (see gpuos_last_hip_error) */
+  GPUOS_E_NOMEM   = -7,
+  GPUOS_E_VERSION = -8    /* device found a table entry whose version differs from
+                             the one the task claimed (protocol violation)        */
+};
+
+/* ---- element types ------------------------------------------------------ */
+enum gpuos_dtype { GPUOS_F32 = 0, GPUOS_F16 = 1, GPUOS_BF16 = 2, GPUOS_I32 = 3 };
+
+/* ---- built-in device implementations an operator-table entry can name -----
+ * (operator library, paper Section 5.2: elementwise add / mul / ReLU / GELU and
+ * sum / max / min reductions, plus what the task streams need).  x, y, z are
+ * the inputs converted to fp32, a = task.alpha.  All float math is IEEE
+ * binary32 round-to-nearest-even with denormals kept; the result is rounded
+ * once more to the output dtype.  EXP / GELU are the mathematical functions
+ * (the device evaluates them so that the fp32 result is within 2 ulp).
+ *   ADD x+y  SUB x-y  MUL x*y  DIV x/y  RELU (x>0 ? x : +0, NaN->NaN)
+ *   EXP e^x  GELU_ERF 0.5 x erfc(-x/sqrt 2)  GELU_TANH x/(1+e^(-2u)),
+ *   u = sqrt(2/pi)(x+0.044715 x^3)  SCALE x*a  FMA fma(x,y,z)
+ *   SUB_EXP e^(fl32(x-y))  COPY x (bit copy when dtypes match)
+ *   SUM_LAST / MAX_LAST / MIN_LAST reduce the last dim (fp32 accumulator for
+ *   floats, two's-complement wrap for I32; max/min propagate NaN)
+ *   FAIL: kill-switch stub (paper Section 5.3): completes at once with
+ *   status GPUOS_E_BADOP and writes nothing.
+ * I32 tensors are accepted by ADD SUB MUL COPY SUM_LAST MAX_LAST MIN_LAST only,
+ * and only when every tensor of the task is I32. */
+enum gpuos_impl {
+  GPUOS_IMPL_NONE = 0,
+  GPUOS_IMPL_ADD = 1, GPUOS_IMPL_SUB = 2, GPUOS_IMPL_MUL = 3, GPUOS_IMPL_DIV = 4,
+  GPUOS_IMPL_RELU = 5, GPUOS_IMPL_EXP = 6, GPUOS_IMPL_GELU_ERF = 7,
+  GPUOS_IMPL_GELU_TANH = 8, GPUOS_IMPL_SCALE = 9, GPUOS_IMPL_FMA = 10,
+  GPUOS_IMPL_SUB_EXP = 11, GPUOS_IMPL_COPY = 12,
+  GPUOS_IMPL_SUM_LAST = 13, GPUOS_IMPL_MAX_LAST = 14, GPUOS_IMPL_MIN_LAST = 15,
+  GPUOS_IMPL_FAIL = 16,
+  GPUOS_IMPL_COUNT = 17
+};
+
+/* ---- task flags --------------------------------------------------------- */
+#define GPUOS_FLAG_FENCE   1u  /* start only after EVERY earlier ticket completed  */
+#define GPUOS_FLAG_KEEPDIM 2u  /* reductions: output keeps a trailing dim of size 1
+                                  (its stride is ignored)                          */
+
+/* ---- generic tensor descriptor (paper abstract / Section 5.2: arbitrary
+ * shapes, strides, dtypes and broadcasting) -------------------------------- */
+typedef struct gpuos_tensor {
+  void*   ptr;                      /* device address of the element at index 0     */
+  int64_t stride[GPUOS_MAX_DIMS];   /* in ELEMENTS, >= 0; entries >= ndim ignored   */
+  uint8_t dtype;                    /* enum gpuos_dtype                             */
+  uint8_t bcast_mask;               /* bit d set: dim d is broadcast (stride := 0)  */
+  uint8_t reserved[6];
+} gpuos_tensor;                     /* 64 bytes */
+
+/* ---- task descriptor as the caller fills it (paper Section 4.2 listing:
+ * op id, input / output pointers, size; extended to the generic tensor layer).
+ * gpuos_submit validates it, coalesces dims and packs it into a fixed 256-byte
+ * ring record; the caller's copy is not referenced after submit returns. ----- */
+typedef struct gpuos_task {
+  uint16_t op_id;                   /* logical operator id (index into the table)   */
+  uint8_t  ndim;                    /* 1 .. 6                                       */
+  uint8_t  n_inputs;                /* must equal the arity of the op's impl        */
+  uint32_t flags;                   /* GPUOS_FLAG_*                                 */
+  int64_t  size[GPUOS_MAX_DIMS];    /* elementwise: iteration (= output) shape;
+                                       reductions: the INPUT shape, the last dim is
+                                       reduced, output shape = size[0 .. ndim-2]    */
+  gpuos_tensor in[GPUOS_MAX_INPUTS];
+  gpuos_tensor out;
+  float    alpha;                   /* SCALE multiplier                             */
+  uint16_t dep[3];                  /* 0 = none; k = wait for ticket (mine - k)     */
+  uint16_t reserved[3];
+} gpuos_task;                       /* 328 bytes */
+
+/* per-ticket completion record (paper Section 5.3 tracepoint fields: task id,
+ * operator-table version; timestamps are host steady_clock nanoseconds) */
+typedef struct gpuos_completion {
+  uint64_t ticket;
+  int32_t  status;                  /* gpuos_status reported by the device          */
+  uint32_t op_version;              /* table version the task claimed               */
+  uint64_t t_submit_ns;             /* doorbell time of the batch that published it */
+  uint64_t t_done_ns;               /* time the host first saw the completion word  */
+} gpuos_completion;                 /* 32 bytes */
+
+/* paper Table 1 peek_queue(): head, tail, processed counts */
+typedef struct gpuos_queue_state {
+  uint64_t head_submitted;          /* tickets written into the ring by the host    */
+  uint64_t tail_published;          /* tickets made visible by the last doorbell    */
+  uint64_t claimed;                 /* tickets the device has dequeued from the ring*/
+  uint64_t completed;               /* completed-in-order floor seen by the host    */
+  uint64_t heartbeat;               /* worker poll-loop counter (liveness)          */
+  uint32_t capacity;
+  uint32_t workgroups;              /* resident worker workgroups                   */
+} gpuos_queue_state;
+
+typedef struct gpuos_config {
+  int32_t  device;                  /* HIP device ordinal                           */
+  uint32_t threads_per_workgroup;   /* paper's threads_per_block; 0 => 256 (only 256
+                                       is supported by the built kernel)            */
+  uint32_t workgroups_per_cu;       /* 0 => 4; clamped to what is co-resident       */
+  uint32_t nonblocking_submit;      /* 1: a full ring returns GPUOS_E_FULL          */
+  uint32_t harvester_thread;        /* 1: a pinned host thread harvests completions
+                                       and time-stamps them (latency measurement)   */
+  uint32_t defer_op_check;          /* 1: do not reject unknown op ids at submit;
+                                       the device bounds-checks and reports them    */
+  uint32_t idle_exit_ms;            /* worker exits by itself after this long with
+                                       an empty ring (0 = never, the paper's mode)  */
+  uint32_t wait_timeout_ms;         /* bound on every internal blocking wait
+                                       (0 => 30000)                                 */
+  uint32_t completion_log;          /* tickets kept for gpuos_get_completions
+                                       (0 => 1<<21; rounded up to a power of two)   */
+  uint32_t reserved[7];
+} gpuos_config;
+
+/* Fill *cfg with the defaults named above. */
+void gpuos_default_config(gpuos_config* cfg);
+
+/* Paper Table 1 init(capacity, threads_per_block): allocate the ring (host
+ * memory, fine-grained coherent, mapped to the device), the device-side mirror
+ * and operator table, and launch the persistent worker once.
+ * queue_capacity: power of two in [2, 65536]; 0 => 4096 (the paper's default).
+ * cfg: NULL => defaults on the current device.  *out receives the context. */
+int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* cfg);
+
+/* Operator table (paper Section 4.1 "Dynamic Operator Table"; dual-slot
+ * update protocol).  Each logical op id owns two slots {impl, version} and a
+ * version word; the active slot is version & 1.
+ * register_op: first binding of op_id; fills the active slot, version = 1.
+ * swap_op: writes {impl, version+1} into the INACTIVE slot, then publishes
+ * version+1 with a store-release.  The worker never stops.  A task keeps the
+ * slot and version it claimed; before a slot is overwritten the call waits
+ * (bounded by wait_timeout_ms) until no unfinished task can still hold it.
+ * The new impl must have the arity and kind (elementwise / reduction) of the
+ * old one, or be GPUOS_IMPL_FAIL.  *out_version (nullable) gets the version.
+ * Tasks submitted after the call returns observe a version >= *out_version. */
+int gpuos_register_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t impl_id, uint32_t* out_version);
+int gpuos_swap_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t impl_id, uint32_t* out_version);
+
+/* Paper Section 4.2: acquire n consecutive tickets, write the packed records
+ * into their slots (slot = ticket & (capacity-1)).  tasks: HOST array of n
+ * descriptors holding DEVICE tensor pointers.  All n are validated before
+ * anything is written: on GPUOS_E_INVAL / GPUOS_E_BADOP nothing is enqueued.
+ * The records become visible to the device at the next gpuos_flush (the
+ * paper's fuse(): one aggregated submission).  When the ring is full the call
+ * publishes what it has written and blocks until slots free up (or returns
+ * GPUOS_E_FULL with nothing enqueued in non-blocking mode).
+ * *out_first_ticket (nullable) receives the ticket of tasks[0]. */
+int gpuos_submit(gpuos_ctx* ctx, const gpuos_task* tasks, uint32_t n, uint64_t* out_first_ticket);
+
+/* Doorbell: one store-release of the tail cursor publishes every record
+ * written so far.  Never waits for the device. */
+int gpuos_flush(gpuos_ctx* ctx);
+
+/* Flush, then block until `ticket` and every earlier ticket completed
+ * (GPUOS_ALL: everything submitted).  timeout_ns == 0 uses wait_timeout_ms.
+ * Returns the ticket's device status (for GPUOS_ALL: the first non-OK status
+ * among tickets completed since the previous GPUOS_ALL wait), or
+ * GPUOS_E_TIMEOUT / GPUOS_E_DEAD. */
+int gpuos_wait(gpuos_ctx* ctx, uint64_t ticket, uint64_t timeout_ns);
+
+/* Copy the completion records of tickets [first_ticket, first_ticket + n) to
+ * the HOST array out.  Every ticket must be complete and still inside the
+ * completion log, else GPUOS_E_INVAL. */
+int gpuos_get_completions(gpuos_ctx* ctx, uint64_t first_ticket, uint32_t n, gpuos_completion* out);
+
+/* Paper Table 1: peek_queue(), worker_alive() (1 alive, 0 not),
+ * set_yield_every(every): every `every` polls with an empty ring the workers
+ * sleep longer (0 = never yield: pure spin with short back-off). */
+int gpuos_peek_queue(gpuos_ctx* ctx, gpuos_queue_state* out);
+int gpuos_worker_alive(gpuos_ctx* ctx);
+int gpuos_set_yield_every(gpuos_ctx* ctx, uint32_t every);
+
+/* Paper Table 1 shutdown(): drain everything submitted, signal the worker to
+ * exit, join the kernel, free the library's memory.  Idempotent on NULL. */
+int gpuos_shutdown(gpuos_ctx* ctx);
+
+/* Milliseconds the worker kernel ran, from HIP events on its stream (valid
+ * after the worker has exited, i.e. call it on a context being shut down via
+ * gpuos_stop_worker).  gpuos_stop_worker drains and joins the kernel but keeps
+ * the context so that timing and logs can still be read; gpuos_shutdown frees. */
+int gpuos_stop_worker(gpuos_ctx* ctx);
+int gpuos_worker_elapsed_ms(gpuos_ctx* ctx, float* out_ms);
+
+/* The comparison the paper's evaluation is built on (Section 6: the same
+ * operations issued as ordinary kernel launches): run the stream as ONE
+ * hipLaunchKernel per task on one stream of `device`, with the library's own
+ * operator code.  impl_of_op: HOST array of GPUOS_MAX_OPS impl ids (the table
+ * contents to use).  sync_each = 0: one stream synchronize at the end;
+ * 1: synchronize after every launch and store per-task launch->done host
+ * nanoseconds into lat_ns (HOST array of n, nullable).  *out_seconds gets the
+ * wall time of the whole stream. */
+int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n,
+                        const uint32_t* impl_of_op, int32_t sync_each,
+                        uint64_t* lat_ns, double* out_seconds);
+
+/* Algorithmic HBM bytes of a task (tensor bytes the operation itself must
+ * move: each distinct input element once, each output element once). */
+int gpuos_task_bytes(const gpuos_task* task, uint32_t impl_id, uint64_t* out_bytes);
+
+const char* gpuos_strerror(int status);
+const char* gpuos_last_hip_error(void);   /* text of the last failed HIP call     */
+
+/* sizeof / offsetof facts of this ABI, for bindings to check their mirror of
+ * the structs: out[0..7] = sizeof(gpuos_task), sizeof(gpuos_tensor),
+ * offsetof(task,size), offsetof(task,in), offsetof(task,out),
+ * offsetof(task,alpha), offsetof(task,dep), sizeof(gpuos_completion). */
+void gpuos_abi_layout(uint32_t out[8]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPUOS_H_ */

@@ -1,0 +1,98 @@
+/*
+ * oracle.h -- CPU oracle for the GPUOS task streams.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, single-threaded executor of the same task descriptors the
+ * GPU library takes: tasks are run one after the other in ticket order, each
+ * to completion (the eager-execution semantics the paper's Section 1.3 says
+ * the method retains).  No queue, no table, no chunking, no contiguity or
+ * coalescing shortcuts: every element is reached through the row-major
+ * index -> per-dim index -> strided offset definition.
+ *
+ * It shares no code with the HIP path.  The two struct layouts below repeat
+ * the GPU library's descriptor layout on purpose (the interface has to be the
+ * same for the same seeded task arrays to drive both); the tests compare the
+ * two layouts through orc_abi_layout().
+ *
+ * Only tests/, the smoke check and the benchmark's cpu_baseline leg may load
+ * this library.  Parity status: every function here is pinned by CPU tests
+ * (hand values, numpy strided views, exhaustive 16-bit conversions, closed
+ * forms); nothing is "parity unpinned".
+ */
+#ifndef GPUOS_ORACLE_H_
+#define GPUOS_ORACLE_H_
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ORC_MAX_DIMS = 6 };
+enum { ORC_F32 = 0, ORC_F16 = 1, ORC_BF16 = 2, ORC_I32 = 3 };
+enum {
+  ORC_ADD = 1, ORC_SUB = 2, ORC_MUL = 3, ORC_DIV = 4, ORC_RELU = 5, ORC_EXP = 6,
+  ORC_GELU_ERF = 7, ORC_GELU_TANH = 8, ORC_SCALE = 9, ORC_FMA = 10,
+  ORC_SUB_EXP = 11, ORC_COPY = 12, ORC_SUM_LAST = 13, ORC_MAX_LAST = 14,
+  ORC_MIN_LAST = 15, ORC_FAIL = 16
+};
+enum { ORC_OK = 0, ORC_E_INVAL = -1, ORC_E_BADOP = -3 };
+enum { ORC_FLAG_FENCE = 1, ORC_FLAG_KEEPDIM = 2 };
+
+/* transcendental cores: 0 = evaluate in double from the fp32 input, round once
+ * to fp32 (the definition the GPU is gated against); 1 = glibc fp32 routines */
+enum { ORC_MODE_F64CORE = 0, ORC_MODE_F32LIBM = 1 };
+
+typedef struct orc_tensor {
+  void*   ptr;                  /* HOST address of element 0 */
+  int64_t stride[ORC_MAX_DIMS]; /* elements */
+  uint8_t dtype;
+  uint8_t bcast_mask;
+  uint8_t reserved[6];
+} orc_tensor;
+
+typedef struct orc_task {
+  uint16_t op_id;
+  uint8_t  ndim;
+  uint8_t  n_inputs;
+  uint32_t flags;
+  int64_t  size[ORC_MAX_DIMS];
+  orc_tensor in[3];
+  orc_tensor out;
+  float    alpha;
+  uint16_t dep[3];
+  uint16_t reserved[3];
+} orc_task;
+
+/* Validate one descriptor against `impl` (same host-detectable rules as the
+ * library's submit).  Returns ORC_OK / ORC_E_INVAL / ORC_E_BADOP. */
+int orc_validate(const orc_task* t, int impl);
+
+/* Execute one task with implementation `impl`.  FAIL writes nothing and
+ * returns ORC_E_BADOP. */
+int orc_run_task(const orc_task* t, int impl, int mode);
+
+/* Execute tasks[0..n) in order.  impl[i] is the implementation of task i (the
+ * harness resolves logical op + recorded version -> impl).  status (nullable)
+ * receives the per-task result.  Returns the number of tasks whose status is
+ * not ORC_OK. */
+int64_t orc_run_stream(const orc_task* tasks, int64_t n, const int32_t* impl,
+                       int mode, int32_t* status);
+
+/* For a SUM_LAST task: per output row, the sum accumulated in double and the
+ * L1 norm of the row (inputs converted to fp32 first).  Both arrays have one
+ * entry per outer index in row-major order.  Used for the reduction
+ * tolerance |g - o| <= 1e-5 * max(|o|, L1/sqrt(n)). */
+int orc_sum_last_f64(const orc_task* t, double* sum, double* l1);
+
+/* scalar conversions, exported so the tests can sweep all 65536 patterns */
+float    orc_f16_to_f32(uint16_t h);
+uint16_t orc_f32_to_f16(float f);
+float    orc_bf16_to_f32(uint16_t h);
+uint16_t orc_f32_to_bf16(float f);
+/* one elementwise result in fp32 (before rounding to the output dtype) */
+float    orc_scalar_op(int impl, float x, float y, float z, float alpha, int mode);
+
+void orc_abi_layout(uint32_t out[8]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
