@@ -1,0 +1,141 @@
+// gpuos_internal.h -- layouts shared by the host runtime and the device code of
+// the library: the packed 256-byte ring record, the control blocks and the
+// operator-table entries.  Not part of the public ABI.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIP__)
+#define GPUOS_HD __host__ __device__
+#else
+#define GPUOS_HD
+#endif
+
+namespace gpuos {
+
+// How the executor walks a task (decided on the host after dim coalescing).
+enum Path : uint8_t {
+  PATH_NOP = 0,          // empty tensor: completes without touching memory
+  PATH_CONTIG = 1,       // every operand contiguous 1-D, same dtype
+  PATH_ROW2D = 2,        // [R, C] contiguous output; each input is full, a row vector
+                         // broadcast over rows, or one scalar per row
+  PATH_GENERIC = 3,      // index decomposition over <= 6 dims, any strides / dtypes
+  PATH_RED_CONTIG = 4,   // last-dim reduction of a contiguous [rows, n] input
+  PATH_RED_GENERIC = 5,  // last-dim reduction, any strides
+  PATH_TILE2D = 6        // [R, C] contiguous output, >= 1 input stored transposed:
+                         // gathered through an LDS tile
+};
+
+enum RecFlag : uint8_t {
+  RF_FENCE = 1,          // dispatcher: publish only after every earlier ticket is done
+  RF_VEC = 2,            // 16-byte vector access is safe (alignment and extents checked)
+  RF_INT = 4             // all tensors are I32
+};
+
+enum OperandKind : uint8_t { K_FULL = 0, K_ROWVEC = 1, K_ROWSCALAR = 2, K_TRANSPOSED = 3 };
+
+constexpr uint32_t kMaxChunksPerTask = 1024;   // unit ring holds capacity * this entries
+constexpr uint32_t kChunkElems = 16384;        // minimum elements per chunk
+constexpr uint32_t kDispatchBatch = 64;        // records mirrored per dispatcher pass
+constexpr uint32_t kThreads = 256;             // threads per workgroup of the worker
+
+// The ring record ("compact descriptor", paper Section 4.1).  Written by the
+// host into the host ring; the dispatcher copies it into the device mirror and
+// fills impl / version / sel / status from the operator table.
+struct alignas(16) Record {
+  uint16_t op_id;
+  uint8_t  path;
+  uint8_t  ndim;             // after coalescing
+  uint8_t  n_inputs;
+  uint8_t  dtype[4];         // in0, in1, in2, out
+  uint8_t  rflags;
+  uint8_t  okind[3];         // PATH_ROW2D / PATH_TILE2D: OperandKind per input
+  uint8_t  sel;              // table slot the task claimed            (dispatcher)
+  uint16_t pad0;
+  uint32_t impl;             // implementation id                     (dispatcher)
+  uint32_t version;          // table version the task claimed        (dispatcher)
+  int32_t  status;           // 0, or the error the task completes with (dispatcher)
+  uint32_t nchunks;
+  uint32_t chunk;            // elements (elementwise) or rows (reduction) per chunk
+  uint32_t numel;            // elementwise: output elements; reduction: output rows
+  uint32_t red_n;            // reduction length
+  float    alpha;
+  uint16_t dep[3];
+  uint16_t pad1;
+  uint64_t ticket;
+  uint64_t ptr[4];           // in0, in1, in2, out (device addresses)
+  uint32_t size[6];          // coalesced iteration shape (reductions: outer dims)
+  uint32_t stride[4][6];     // elements; 0 on broadcast dims; reductions: stride[0][5]
+                             // is the input stride along the reduced dim
+  uint32_t pad2[10];
+};
+static_assert(sizeof(Record) == 256, "ring record must be 256 bytes");
+
+// Completion word (8 bytes, one atomic store to host memory):
+//   bits 0..31  low half of ticket+1, bits 32..39 status (int8), bits 40..63 version
+GPUOS_HD inline uint64_t pack_completion(uint64_t ticket, int32_t status, uint32_t version) {
+  return ((ticket + 1) & 0xffffffffull) | ((uint64_t)(uint8_t)(int8_t)status << 32) |
+         ((uint64_t)(version & 0xffffffu) << 40);
+}
+
+// Operator-table entry: {impl, version} in one 64-bit word so that it can never tear.
+GPUOS_HD inline uint64_t pack_entry(uint32_t impl, uint32_t version) { return ((uint64_t)version << 32) | impl; }
+
+struct OpSlots {             // one logical operator: two slots + the version word
+  uint64_t slot[2];          // active slot = version & 1
+  uint32_t version;          // 0 = unregistered
+  uint32_t pad;
+};
+
+// Host-coherent control block (fine-grained pinned memory, mapped to the device).
+struct HostCtl {
+  alignas(64) uint64_t tail;         // host -> device: tickets published (doorbell)
+  alignas(64) uint64_t epoch_word;   // host -> device: epoch << 12 | op << 4 | stop bit;
+                                     // op = 0xff: refresh every entry
+  alignas(64) uint64_t dispatched;   // device -> host: tickets dequeued from the host ring
+  alignas(64) uint64_t heartbeat;    // device -> host: dispatcher poll counter
+  alignas(64) uint32_t exit_code;    // device -> host: 0 running, 1 stop seen, 2 idle exit
+  alignas(64) uint32_t yield_every;  // host -> device
+};
+
+struct DevCtl {                      // device memory
+  alignas(128) uint64_t claim;       // next work unit to hand out (fetch-add)
+  alignas(128) uint64_t tail_units;  // work units published by the dispatcher
+  alignas(128) uint64_t done_count;  // tasks completed
+  alignas(128) uint32_t stop_dev;    // dispatcher -> workers
+  uint32_t yield_every;
+};
+
+struct SlotState {                   // device memory, one per ring slot
+  uint64_t done_seq;                 // ticket+1 of the last task completed in this slot
+  uint32_t chunks_done;
+  uint32_t pad;
+};
+
+// Work-unit entry: bits 0..19 chunk, 20..35 ring slot, 36..43 op id, 44 table slot,
+// 45 op id valid.
+GPUOS_HD inline uint64_t pack_unit(uint32_t chunk, uint32_t slot, uint32_t op, uint32_t sel, uint32_t valid) {
+  return (uint64_t)chunk | ((uint64_t)slot << 20) | ((uint64_t)(op & 0xff) << 36) |
+         ((uint64_t)(sel & 1) << 44) | ((uint64_t)(valid & 1) << 45);
+}
+
+struct WorkerArgs {
+  HostCtl*   h;
+  const Record* hring;       // host ring (device-visible address)
+  uint64_t*  hcomp;          // host completion words, one per slot
+  const OpSlots* htable;     // host operator table
+  DevCtl*    d;
+  Record*    dring;          // device mirror of the ring
+  uint64_t*  units;          // work-unit ring
+  SlotState* st;
+  OpSlots*   dtable;         // device-resident operator table
+  uint32_t   cap_mask;
+  uint32_t   unit_mask;
+  uint64_t   idle_exit_ticks;   // 0 = never; 100 MHz ticks
+};
+
+// implemented in gpuos_kernels.hip
+int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream);
+int worker_max_blocks_per_cu(int* out);
+int launch_single(const Record& r, void* stream);   // one ordinary kernel launch for one task
+
+}  // namespace gpuos

@@ -1,0 +1,808 @@
+// gpuos_kernels.hip -- device side of the GPUOS hot path for gfx950 (CDNA4).
+//
+//  * gpuos_worker_kernel: the persistent kernel (paper Section 4.1 "Persistent
+//    Kernel Executor", device loop of Section 4.2).  Workgroup 0 is the
+//    dispatcher: it is the single reader of the host ring (one PCIe poller
+//    instead of hundreds), mirrors new records into device memory, resolves
+//    each task's operator-table slot and version once ("claim time"), expands
+//    tasks into work units (chunks) and publishes them with an agent-scope
+//    store-release.  Every other workgroup is a worker: one elected lane claims
+//    a work unit with an atomic fetch-add, the 4 wavefronts of the workgroup
+//    execute the chunk together, and the last finisher of a task publishes its
+//    completion (device-side done word for dependants, one 8-byte completion
+//    word to host memory).
+//  * gpuos_single_task_kernel: the same chunk executor as an ordinary kernel,
+//    one launch per task (the per-op-launch comparison of the paper's Section 6).
+//
+// Wavefronts are 64 lanes; a workgroup is 256 threads.  Nothing here is a dense
+// contraction, so there is no MFMA: the paths are bandwidth- or latency-bound
+// and use 16-byte-per-lane global accesses, LDS for descriptor broadcast and
+// cross-wave combines, and DPP / permute wave reductions.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/gpuos.h"
+#include "gpuos_internal.h"
+
+namespace gpuos {
+
+#define SC_AGENT __HIP_MEMORY_SCOPE_AGENT
+#define SC_SYSTEM __HIP_MEMORY_SCOPE_SYSTEM
+
+#define DEV __device__ __forceinline__
+
+// ---------------------------------------------------------------------------
+// element conversions (fp16 / bf16 <-> fp32; RNE, denormals kept)
+// ---------------------------------------------------------------------------
+DEV float h2f(uint32_t b) { return (float)__builtin_bit_cast(_Float16, (uint16_t)b); }
+DEV uint32_t f2h(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f); }
+DEV float b2f(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+DEV uint32_t f2b(float f) {
+  // round-to-nearest-even on the upper 16 bits; NaN stays a (quiet) NaN
+  const uint32_t x = __builtin_bit_cast(uint32_t, f);
+  if ((x & 0x7fffffffu) > 0x7f800000u) return (x >> 16) | 0x40u;
+  return (x + 0x7fffu + ((x >> 16) & 1u)) >> 16;
+}
+
+template <int DT> struct Elem;
+template <> struct Elem<GPUOS_F32> {
+  static constexpr int V = 4, ES = 4;
+  static DEV float get(const uint4& q, int k) { return __builtin_bit_cast(float, (&q.x)[k]); }
+  static DEV void put(uint4& q, int k, float f) { (&q.x)[k] = __builtin_bit_cast(uint32_t, f); }
+  static DEV float load1(const void* p, uint32_t i) { return ((const float*)p)[i]; }
+  static DEV void store1(void* p, uint32_t i, float f) { ((float*)p)[i] = f; }
+};
+template <> struct Elem<GPUOS_F16> {
+  static constexpr int V = 8, ES = 2;
+  static DEV float get(const uint4& q, int k) { return h2f(((&q.x)[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
+  static DEV void put(uint4& q, int k, float f) {
+    uint32_t& w = (&q.x)[k >> 1];
+    w = (k & 1) ? ((w & 0xffffu) | (f2h(f) << 16)) : ((w & 0xffff0000u) | f2h(f));
+  }
+  static DEV float load1(const void* p, uint32_t i) { return h2f(((const uint16_t*)p)[i]); }
+  static DEV void store1(void* p, uint32_t i, float f) { ((uint16_t*)p)[i] = (uint16_t)f2h(f); }
+};
+template <> struct Elem<GPUOS_BF16> {
+  static constexpr int V = 8, ES = 2;
+  static DEV float get(const uint4& q, int k) { return b2f(((&q.x)[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
+  static DEV void put(uint4& q, int k, float f) {
+    uint32_t& w = (&q.x)[k >> 1];
+    w = (k & 1) ? ((w & 0xffffu) | (f2b(f) << 16)) : ((w & 0xffff0000u) | f2b(f));
+  }
+  static DEV float load1(const void* p, uint32_t i) { return b2f(((const uint16_t*)p)[i]); }
+  static DEV void store1(void* p, uint32_t i, float f) { ((uint16_t*)p)[i] = (uint16_t)f2b(f); }
+};
+
+DEV float load_rt(const void* p, uint32_t i, uint32_t dt) {   // runtime dtype
+  if (dt == GPUOS_F32) return ((const float*)p)[i];
+  if (dt == GPUOS_F16) return h2f(((const uint16_t*)p)[i]);
+  return b2f(((const uint16_t*)p)[i]);
+}
+DEV void store_rt(void* p, uint32_t i, uint32_t dt, float f) {
+  if (dt == GPUOS_F32) ((float*)p)[i] = f;
+  else if (dt == GPUOS_F16) ((uint16_t*)p)[i] = (uint16_t)f2h(f);
+  else ((uint16_t*)p)[i] = (uint16_t)f2b(f);
+}
+
+// ---------------------------------------------------------------------------
+// operator library (paper Section 5.2).  fp32 in, fp32 out; the caller rounds
+// to the output dtype.  GELU is evaluated in fp64 in a cancellation-free form
+// and rounded once: an fp32 evaluation cannot hold 2 ulp for x < 0, where
+// 1 + tanh(u) and 1 + erf(u) cancel.
+// ---------------------------------------------------------------------------
+template <int IMPL> struct Op;
+template <> struct Op<GPUOS_IMPL_ADD> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x + y; } };
+template <> struct Op<GPUOS_IMPL_SUB> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x - y; } };
+template <> struct Op<GPUOS_IMPL_MUL> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x * y; } };
+template <> struct Op<GPUOS_IMPL_DIV> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x / y; } };
+template <> struct Op<GPUOS_IMPL_RELU> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return (x != x) ? x : (x > 0.0f ? x : 0.0f); } };
+template <> struct Op<GPUOS_IMPL_EXP> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return expf(x); } };
+template <> struct Op<GPUOS_IMPL_GELU_ERF> {
+  static constexpr int N = 1;
+  static DEV float f(float x, float, float, float) {
+    const double xd = (double)x;
+    return (float)(0.5 * xd * erfc(-xd * 0.70710678118654752440));
+  }
+};
+template <> struct Op<GPUOS_IMPL_GELU_TANH> {
+  static constexpr int N = 1;
+  static DEV float f(float x, float, float, float) {
+    const double xd = (double)x;
+    const double u = 0.79788456080286535588 * (xd + 0.044715 * xd * xd * xd);
+    return (float)(xd / (1.0 + exp(-2.0 * u)));
+  }
+};
+template <> struct Op<GPUOS_IMPL_SCALE> { static constexpr int N = 1; static DEV float f(float x, float, float, float a) { return x * a; } };
+template <> struct Op<GPUOS_IMPL_FMA> { static constexpr int N = 3; static DEV float f(float x, float y, float z, float) { return __builtin_fmaf(x, y, z); } };
+template <> struct Op<GPUOS_IMPL_SUB_EXP> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { const float d = x - y; return expf(d); } };
+template <> struct Op<GPUOS_IMPL_COPY> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return x; } };
+
+template <int IMPL> DEV uint32_t int_op(uint32_t x, uint32_t y) {
+  if (IMPL == GPUOS_IMPL_ADD) return x + y;
+  if (IMPL == GPUOS_IMPL_SUB) return x - y;
+  if (IMPL == GPUOS_IMPL_MUL) return x * y;
+  return x;
+}
+
+DEV uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+DEV const char* uni_ptr(uint64_t p) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
+  return (const char*)(((uint64_t)hi << 32) | lo);
+}
+
+// ---------------------------------------------------------------------------
+// PATH_CONTIG: out[i] = f(a[i], b[i], c[i]), all operands the same dtype.
+// 16 bytes per lane per access, four accesses in flight per operand.
+// ---------------------------------------------------------------------------
+template <int IMPL, int DT>
+DEV void ew_contig(const Record* r, uint32_t begin, uint32_t end) {
+  using E = Elem<DT>;
+  constexpr int V = E::V, N = Op<IMPL>::N, U = 4;
+  const char* pa = uni_ptr(r->ptr[0]);
+  const char* pb = N > 1 ? uni_ptr(r->ptr[1]) : pa;
+  const char* pc = N > 2 ? uni_ptr(r->ptr[2]) : pa;
+  char* po = (char*)uni_ptr(r->ptr[3]);
+  const float alpha = r->alpha;
+  const uint32_t tid = threadIdx.x;
+  if (r->rflags & RF_VEC) {
+    const uint32_t v0 = begin / V, v1 = end / V;      // begin is a multiple of V
+    const uint4* a = (const uint4*)pa; const uint4* b = (const uint4*)pb; const uint4* c = (const uint4*)pc;
+    uint4* o = (uint4*)po;
+    uint32_t v = v0 + tid;
+    for (; v + (U - 1) * kThreads < v1; v += U * kThreads) {
+      uint4 qa[U], qb[U], qc[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        qa[u] = a[v + u * kThreads];
+        if (N > 1) qb[u] = b[v + u * kThreads];
+        if (N > 2) qc[u] = c[v + u * kThreads];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        uint4 q;
+        if (IMPL == GPUOS_IMPL_COPY) q = qa[u];
+        else {
+#pragma unroll
+          for (int k = 0; k < V; ++k)
+            E::put(q, k, Op<IMPL>::f(E::get(qa[u], k), N > 1 ? E::get(qb[u], k) : 0.f, N > 2 ? E::get(qc[u], k) : 0.f, alpha));
+        }
+        o[v + u * kThreads] = q;
+      }
+    }
+    for (; v < v1; v += kThreads) {
+      const uint4 qa = a[v];
+      uint4 qb, qc, q;
+      if (N > 1) qb = b[v];
+      if (N > 2) qc = c[v];
+      if (IMPL == GPUOS_IMPL_COPY) q = qa;
+      else {
+#pragma unroll
+        for (int k = 0; k < V; ++k)
+          E::put(q, k, Op<IMPL>::f(E::get(qa, k), N > 1 ? E::get(qb, k) : 0.f, N > 2 ? E::get(qc, k) : 0.f, alpha));
+      }
+      o[v] = q;
+    }
+    begin = v1 * V;                                   // ragged tail below
+  }
+  for (uint32_t i = begin + tid; i < end; i += kThreads) {
+    if (IMPL == GPUOS_IMPL_COPY) {
+      if (E::ES == 4) ((uint32_t*)po)[i] = ((const uint32_t*)pa)[i];
+      else ((uint16_t*)po)[i] = ((const uint16_t*)pa)[i];
+    } else {
+      E::store1(po, i, Op<IMPL>::f(E::load1(pa, i), N > 1 ? E::load1(pb, i) : 0.f, N > 2 ? E::load1(pc, i) : 0.f, alpha));
+    }
+  }
+}
+
+template <int IMPL>
+DEV void ew_contig_int(const Record* r, uint32_t begin, uint32_t end) {
+  const uint32_t* a = (const uint32_t*)uni_ptr(r->ptr[0]);
+  const uint32_t* b = r->n_inputs > 1 ? (const uint32_t*)uni_ptr(r->ptr[1]) : a;
+  uint32_t* o = (uint32_t*)uni_ptr(r->ptr[3]);
+  for (uint32_t i = begin + threadIdx.x; i < end; i += kThreads) o[i] = int_op<IMPL>(a[i], b[i]);
+}
+
+// ---------------------------------------------------------------------------
+// PATH_ROW2D: contiguous [R, C] output of dtype DT, C a multiple of the vector
+// width; each input is a full [R, C] tensor (dtype DT), a row vector [C]
+// broadcast over rows (dtype DT), or one scalar per row (any float dtype).
+// ---------------------------------------------------------------------------
+template <int IMPL, int DT>
+DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
+  using E = Elem<DT>;
+  constexpr int V = E::V, N = Op<IMPL>::N;
+  const uint32_t C = uni(r->size[1]);
+  const char* p[3];
+  uint32_t kind[3], dt[3], st0[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    p[k] = uni_ptr(r->ptr[k < N ? k : 0]);
+    kind[k] = uni(r->okind[k < N ? k : 0]);
+    dt[k] = uni(r->dtype[k < N ? k : 0]);
+    st0[k] = uni(r->stride[k < N ? k : 0][0]);
+  }
+  uint4* o = (uint4*)uni_ptr(r->ptr[3]);
+  const float alpha = r->alpha;
+  const uint32_t v1 = end / V;
+  for (uint32_t v = begin / V + threadIdx.x; v < v1; v += kThreads) {
+    const uint32_t i = v * V;
+    const uint32_t row = i / C, col = i - row * C;
+    uint4 q[3];
+    float s[3];
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      if (kind[k] == K_FULL) q[k] = ((const uint4*)p[k])[v];
+      else if (kind[k] == K_ROWVEC) q[k] = ((const uint4*)p[k])[col / V];
+      else s[k] = load_rt(p[k], row * st0[k], dt[k]);
+    }
+    uint4 res;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      float x[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < N; ++k) x[k] = (kind[k] == K_ROWSCALAR) ? s[k] : E::get(q[k], e);
+      E::put(res, e, Op<IMPL>::f(x[0], x[1], x[2], alpha));
+    }
+    o[v] = res;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// PATH_GENERIC: row-major index decomposition over <= 6 coalesced dims, per
+// operand strides (0 on broadcast dims), per operand dtype.
+// ---------------------------------------------------------------------------
+template <int IMPL, bool INT>
+DEV void ew_generic(const Record* r, uint32_t begin, uint32_t end) {
+  constexpr int N = INT ? 2 : Op<IMPL>::N;
+  const int nd = (int)uni(r->ndim);
+  const int nin = (int)uni(r->n_inputs);
+  uint32_t size[GPUOS_MAX_DIMS], st[4][GPUOS_MAX_DIMS];
+#pragma unroll
+  for (int d = 0; d < GPUOS_MAX_DIMS; ++d) {
+    size[d] = uni(r->size[d]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) st[k][d] = uni(r->stride[k][d]);
+  }
+  const char* p[3];
+  uint32_t dt[4];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) { p[k] = uni_ptr(r->ptr[k]); dt[k] = uni(r->dtype[k]); }
+  dt[3] = uni(r->dtype[3]);
+  char* po = (char*)uni_ptr(r->ptr[3]);
+  const float alpha = r->alpha;
+  for (uint32_t i = begin + threadIdx.x; i < end; i += kThreads) {
+    uint32_t rem = i, off[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int d = GPUOS_MAX_DIMS - 1; d >= 0; --d) {
+      if (d < nd) {
+        const uint32_t q = rem / size[d];
+        const uint32_t idx = rem - q * size[d];
+        rem = q;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) off[k] += idx * st[k][d];
+      }
+    }
+    if (INT) {
+      const uint32_t x = ((const uint32_t*)p[0])[off[0]];
+      const uint32_t y = nin > 1 ? ((const uint32_t*)p[1])[off[1]] : 0u;
+      ((uint32_t*)po)[off[3]] = int_op<IMPL>(x, y);
+    } else if (IMPL == GPUOS_IMPL_COPY && dt[0] == dt[3]) {
+      if (dt[0] == GPUOS_F32) ((uint32_t*)po)[off[3]] = ((const uint32_t*)p[0])[off[0]];
+      else ((uint16_t*)po)[off[3]] = ((const uint16_t*)p[0])[off[0]];
+    } else {
+      const float x = load_rt(p[0], off[0], dt[0]);
+      const float y = N > 1 ? load_rt(p[1], off[1], dt[1]) : 0.f;
+      const float z = N > 2 ? load_rt(p[2], off[2], dt[2]) : 0.f;
+      store_rt(po, off[3], dt[3], Op<IMPL>::f(x, y, z, alpha));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// reductions over the last dim
+// ---------------------------------------------------------------------------
+template <int RIMPL> DEV float red_identity() {
+  return RIMPL == GPUOS_IMPL_SUM_LAST ? 0.0f : (RIMPL == GPUOS_IMPL_MAX_LAST ? -__builtin_inff() : __builtin_inff());
+}
+template <int RIMPL> DEV float red_combine(float a, float b) {
+  if (RIMPL == GPUOS_IMPL_SUM_LAST) return a + b;
+  if (a != a) return a;                               // max / min propagate NaN
+  if (b != b) return b;
+  if (RIMPL == GPUOS_IMPL_MAX_LAST) return a > b ? a : b;
+  return a < b ? a : b;
+}
+template <int RIMPL> DEV int32_t red_identity_i() {
+  return RIMPL == GPUOS_IMPL_SUM_LAST ? 0 : (RIMPL == GPUOS_IMPL_MAX_LAST ? (int32_t)0x80000000 : 0x7fffffff);
+}
+template <int RIMPL> DEV int32_t red_combine_i(int32_t a, int32_t b) {
+  if (RIMPL == GPUOS_IMPL_SUM_LAST) return (int32_t)((uint32_t)a + (uint32_t)b);
+  if (RIMPL == GPUOS_IMPL_MAX_LAST) return a > b ? a : b;
+  return a < b ? a : b;
+}
+
+// xor-butterfly over the `width` lanes (power of two <= 64) a lane belongs to
+template <int RIMPL> DEV float wave_reduce(float acc, uint32_t width) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1)
+    if ((uint32_t)off < width) acc = red_combine<RIMPL>(acc, __shfl_xor(acc, off, 64));
+  return acc;
+}
+template <int RIMPL> DEV int32_t wave_reduce_i(int32_t acc, uint32_t width) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1)
+    if ((uint32_t)off < width) acc = red_combine_i<RIMPL>(acc, __shfl_xor(acc, off, 64));
+  return acc;
+}
+
+// PATH_RED_CONTIG: input is a contiguous [rows, n] matrix of dtype DT, output a
+// contiguous vector [rows] of any float dtype.
+template <int RIMPL, int DT>
+DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_red) {
+  using E = Elem<DT>;
+  constexpr int V = E::V;
+  const uint32_t n = uni(r->red_n);
+  const char* pin = uni_ptr(r->ptr[0]);
+  char* po = (char*)uni_ptr(r->ptr[3]);
+  const uint32_t odt = uni(r->dtype[3]);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const bool vec = (r->rflags & RF_VEC) != 0;
+  const uint32_t L = n / V;                           // vectors per row when vec
+  if (vec && L <= 64u) {
+    // several rows per wave pass: P = lanes per row (power of two >= L)
+    uint32_t P = 1;
+    while (P < L) P <<= 1;
+    const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
+    const uint32_t rows_per_pass = rpw * 4u;
+    for (uint32_t base = row_begin; base < row_end; base += rows_per_pass) {
+      const uint32_t row = base + wave * rpw + sub;
+      float acc = red_identity<RIMPL>();
+      if (row < row_end && j < L) {
+        const uint4 q = ((const uint4*)pin)[(uint64_t)row * L + j];
+#pragma unroll
+        for (int k = 0; k < V; ++k) acc = red_combine<RIMPL>(acc, E::get(q, k));
+      }
+      acc = wave_reduce<RIMPL>(acc, P);
+      if (row < row_end && j == 0) store_rt(po, row, odt, acc);
+    }
+    return;
+  }
+  // one row at a time, the whole workgroup on it
+  for (uint32_t row = row_begin; row < row_end; ++row) {
+    float acc0 = red_identity<RIMPL>(), acc1 = acc0, acc2 = acc0, acc3 = acc0;
+    if (vec) {
+      const uint4* src = (const uint4*)pin + (uint64_t)row * L;
+      uint32_t v = tid;
+      for (; v + 3 * kThreads < L; v += 4 * kThreads) {
+        const uint4 q0 = src[v], q1 = src[v + kThreads], q2 = src[v + 2 * kThreads], q3 = src[v + 3 * kThreads];
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+          acc0 = red_combine<RIMPL>(acc0, E::get(q0, k));
+          acc1 = red_combine<RIMPL>(acc1, E::get(q1, k));
+          acc2 = red_combine<RIMPL>(acc2, E::get(q2, k));
+          acc3 = red_combine<RIMPL>(acc3, E::get(q3, k));
+        }
+      }
+      for (; v < L; v += kThreads) {
+        const uint4 q0 = src[v];
+#pragma unroll
+        for (int k = 0; k < V; ++k) acc0 = red_combine<RIMPL>(acc0, E::get(q0, k));
+      }
+    } else {
+      const uint64_t rb = (uint64_t)row * n;
+      for (uint32_t jx = tid; jx < n; jx += kThreads)
+        acc0 = red_combine<RIMPL>(acc0, load_rt(pin + rb * E::ES, jx, DT));
+    }
+    float acc = red_combine<RIMPL>(red_combine<RIMPL>(acc0, acc1), red_combine<RIMPL>(acc2, acc3));
+    acc = wave_reduce<RIMPL>(acc, 64);
+    if (lane == 0) s_red[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+      const float t = red_combine<RIMPL>(red_combine<RIMPL>(s_red[0], s_red[1]), red_combine<RIMPL>(s_red[2], s_red[3]));
+      store_rt(po, row, odt, t);
+    }
+    __syncthreads();
+  }
+}
+
+// PATH_RED_GENERIC: one wave per output row; outer index decomposed over the
+// coalesced outer dims; stride[0][5] walks the reduced dim.
+template <int RIMPL, bool INT>
+DEV void red_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
+  const int nd = (int)uni(r->ndim);                   // outer dims
+  const uint32_t n = uni(r->red_n), sl = uni(r->stride[0][5]);
+  const char* pin = uni_ptr(r->ptr[0]);
+  char* po = (char*)uni_ptr(r->ptr[3]);
+  const uint32_t idt = uni(r->dtype[0]), odt = uni(r->dtype[3]);
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  for (uint32_t row = row_begin + wave; row < row_end; row += 4) {
+    uint32_t rem = row, ioff = 0, ooff = 0;
+#pragma unroll
+    for (int d = GPUOS_MAX_DIMS - 2; d >= 0; --d) {
+      if (d < nd) {
+        const uint32_t sz = uni(r->size[d]);
+        const uint32_t q = rem / sz, idx = rem - q * sz;
+        rem = q;
+        ioff += idx * uni(r->stride[0][d]);
+        ooff += idx * uni(r->stride[3][d]);
+      }
+    }
+    if (INT) {
+      int32_t acc = red_identity_i<RIMPL>();
+      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine_i<RIMPL>(acc, ((const int32_t*)pin)[ioff + jx * sl]);
+      acc = wave_reduce_i<RIMPL>(acc, 64);
+      if (lane == 0) ((int32_t*)po)[ooff] = acc;
+    } else {
+      float acc = red_identity<RIMPL>();
+      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine<RIMPL>(acc, load_rt(pin, ioff + jx * sl, idt));
+      acc = wave_reduce<RIMPL>(acc, 64);
+      if (lane == 0) store_rt(po, ooff, odt, acc);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// chunk executor: operator dispatch by implementation id (the role of the
+// paper's function-pointer table call, Section 4.1; here a switch over
+// precompiled implementations selected by the table entry).
+// ---------------------------------------------------------------------------
+template <int IMPL>
+DEV void run_elementwise(const Record* r, uint32_t chunk) {
+  const uint32_t per = uni(r->chunk), numel = uni(r->numel);
+  const uint32_t begin = chunk * per;
+  const uint32_t end = (numel - begin < per) ? numel : begin + per;
+  const uint32_t path = uni(r->path), dt = uni(r->dtype[3]);
+  constexpr bool int_ok = IMPL == GPUOS_IMPL_ADD || IMPL == GPUOS_IMPL_SUB || IMPL == GPUOS_IMPL_MUL || IMPL == GPUOS_IMPL_COPY;
+  if (r->rflags & RF_INT) {
+    if (int_ok) {
+      if (path == PATH_CONTIG) ew_contig_int<IMPL>(r, begin, end);
+      else ew_generic<int_ok ? IMPL : GPUOS_IMPL_COPY, true>(r, begin, end);
+    }
+    return;
+  }
+  if (path == PATH_CONTIG) {
+    if (dt == GPUOS_F32) ew_contig<IMPL, GPUOS_F32>(r, begin, end);
+    else if (dt == GPUOS_F16) ew_contig<IMPL, GPUOS_F16>(r, begin, end);
+    else ew_contig<IMPL, GPUOS_BF16>(r, begin, end);
+  } else if (path == PATH_ROW2D && Op<IMPL>::N >= 2) {
+    constexpr int I2 = Op<IMPL>::N >= 2 ? IMPL : GPUOS_IMPL_ADD;
+    if (dt == GPUOS_F32) ew_row2d<I2, GPUOS_F32>(r, begin, end);
+    else if (dt == GPUOS_F16) ew_row2d<I2, GPUOS_F16>(r, begin, end);
+    else ew_row2d<I2, GPUOS_BF16>(r, begin, end);
+  } else {
+    ew_generic<IMPL, false>(r, begin, end);
+  }
+}
+
+template <int RIMPL>
+DEV void run_reduction(const Record* r, uint32_t chunk, float* s_red) {
+  const uint32_t per = uni(r->chunk), rows = uni(r->numel);
+  const uint32_t begin = chunk * per;
+  const uint32_t end = (rows - begin < per) ? rows : begin + per;
+  const uint32_t path = uni(r->path), dt = uni(r->dtype[0]);
+  if (r->rflags & RF_INT) { red_generic<RIMPL, true>(r, begin, end); return; }
+  if (path == PATH_RED_CONTIG) {
+    if (dt == GPUOS_F32) red_contig<RIMPL, GPUOS_F32>(r, begin, end, s_red);
+    else if (dt == GPUOS_F16) red_contig<RIMPL, GPUOS_F16>(r, begin, end, s_red);
+    else red_contig<RIMPL, GPUOS_BF16>(r, begin, end, s_red);
+  } else {
+    red_generic<RIMPL, false>(r, begin, end);
+  }
+}
+
+// returns the task status contribution of this chunk (0 or an error)
+DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_red) {
+  if (uni(r->path) == PATH_NOP) return impl == GPUOS_IMPL_FAIL ? GPUOS_E_BADOP : GPUOS_OK;
+  switch (impl) {
+    case GPUOS_IMPL_ADD: run_elementwise<GPUOS_IMPL_ADD>(r, chunk); break;
+    case GPUOS_IMPL_SUB: run_elementwise<GPUOS_IMPL_SUB>(r, chunk); break;
+    case GPUOS_IMPL_MUL: run_elementwise<GPUOS_IMPL_MUL>(r, chunk); break;
+    case GPUOS_IMPL_DIV: run_elementwise<GPUOS_IMPL_DIV>(r, chunk); break;
+    case GPUOS_IMPL_RELU: run_elementwise<GPUOS_IMPL_RELU>(r, chunk); break;
+    case GPUOS_IMPL_EXP: run_elementwise<GPUOS_IMPL_EXP>(r, chunk); break;
+    case GPUOS_IMPL_GELU_ERF: run_elementwise<GPUOS_IMPL_GELU_ERF>(r, chunk); break;
+    case GPUOS_IMPL_GELU_TANH: run_elementwise<GPUOS_IMPL_GELU_TANH>(r, chunk); break;
+    case GPUOS_IMPL_SCALE: run_elementwise<GPUOS_IMPL_SCALE>(r, chunk); break;
+    case GPUOS_IMPL_FMA: run_elementwise<GPUOS_IMPL_FMA>(r, chunk); break;
+    case GPUOS_IMPL_SUB_EXP: run_elementwise<GPUOS_IMPL_SUB_EXP>(r, chunk); break;
+    case GPUOS_IMPL_COPY: run_elementwise<GPUOS_IMPL_COPY>(r, chunk); break;
+    case GPUOS_IMPL_SUM_LAST: run_reduction<GPUOS_IMPL_SUM_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_MAX_LAST: run_reduction<GPUOS_IMPL_MAX_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_MIN_LAST: run_reduction<GPUOS_IMPL_MIN_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_FAIL: return GPUOS_E_BADOP;       // kill-switch stub: fail fast, write nothing
+    default: return GPUOS_E_BADOP;
+  }
+  return GPUOS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// dispatcher (workgroup 0)
+// ---------------------------------------------------------------------------
+struct DispShared {
+  Record rec[kDispatchBatch];          // 16 KB staging of the batch being mirrored
+  uint64_t entry[GPUOS_MAX_OPS];       // shadow of the device table: current {impl, version}
+  uint32_t ubeg[kDispatchBatch + 1];   // exclusive prefix of nchunks
+  uint64_t tail, epoch_word;
+  uint32_t n, stop, refresh_op;
+};
+
+DEV void dispatcher_refresh_table(const WorkerArgs& a, DispShared* s, uint32_t only_op) {
+  // copy entries host table -> device table with the dual-slot protocol: the
+  // inactive slot is written first, then the version is published (release).
+  for (uint32_t op = threadIdx.x; op < GPUOS_MAX_OPS; op += kThreads) {
+    if (only_op != 0xffu && op != only_op) continue;
+    const uint32_t ver = __hip_atomic_load(&a.htable[op].version, __ATOMIC_ACQUIRE, SC_SYSTEM);
+    if (ver == 0) continue;
+    const uint64_t e = __hip_atomic_load(&a.htable[op].slot[ver & 1u], __ATOMIC_RELAXED, SC_SYSTEM);
+    if (e == s->entry[op]) continue;
+    const uint32_t ev = (uint32_t)(e >> 32);
+    __hip_atomic_store(&a.dtable[op].slot[ev & 1u], e, __ATOMIC_RELAXED, SC_AGENT);
+    __hip_atomic_store(&a.dtable[op].version, ev, __ATOMIC_RELEASE, SC_AGENT);
+    s->entry[op] = e;
+  }
+}
+
+DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
+  const uint32_t tid = threadIdx.x;
+  uint64_t mirrored = 0, units_w = 0, seen_epoch = 0;
+  for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) s->entry[op] = 0;
+  __syncthreads();
+  uint64_t idle_since = wall_clock64();
+  uint64_t polls = 0;
+  bool stopping = false;
+  while (true) {
+    // ---- poll the host ring (one lane; the only PCIe poller of the kernel) ----
+    if (tid == 0) {
+      uint64_t t, e;
+      while (true) {
+        t = __hip_atomic_load(&a.h->tail, __ATOMIC_RELAXED, SC_SYSTEM);
+        e = __hip_atomic_load(&a.h->epoch_word, __ATOMIC_RELAXED, SC_SYSTEM);
+        ++polls;
+        if ((polls & 63u) == 0) __hip_atomic_store(&a.h->heartbeat, polls, __ATOMIC_RELAXED, SC_SYSTEM);
+        if (t != mirrored || e != seen_epoch || stopping) break;
+        if (a.idle_exit_ticks != 0 && wall_clock64() - idle_since > a.idle_exit_ticks) {
+          e |= 2u;                                  // behave as if the host had asked to stop
+          break;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
+      if (e & 3u) {                                 // stop: take the final tail after the flag
+        t = __hip_atomic_load(&a.h->tail, __ATOMIC_ACQUIRE, SC_SYSTEM);
+      }
+      s->tail = t;
+      s->epoch_word = e;
+    }
+    __syncthreads();
+    const uint64_t tail = s->tail, ew = s->epoch_word;
+    __syncthreads();
+    if ((ew >> 12) != (seen_epoch >> 12)) {
+      const uint32_t hinted = (uint32_t)((ew >> 4) & 0xffu);
+      const bool one = ((ew >> 12) - (seen_epoch >> 12)) == 1 && hinted != 0xffu;
+      dispatcher_refresh_table(a, s, one ? hinted : 0xffu);
+      if (tid == 0) {
+        const uint32_t y = __hip_atomic_load(&a.h->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
+        __hip_atomic_store(&a.d->yield_every, y, __ATOMIC_RELAXED, SC_AGENT);
+      }
+      __syncthreads();
+    }
+    seen_epoch = ew & ~3ull;
+    if (ew & 3u) stopping = true;
+
+    // ---- mirror new records, batch by batch ----
+    while (mirrored < tail) {
+      uint32_t n = (uint32_t)((tail - mirrored) < kDispatchBatch ? (tail - mirrored) : kDispatchBatch);
+      // stage: 16 pieces of 16 bytes per record
+      for (uint32_t p = tid; p < n * 16u; p += kThreads) {
+        const uint32_t rix = p >> 4, part = p & 15u;
+        const uint4* src = (const uint4*)&a.hring[(mirrored + rix) & a.cap_mask];
+        ((uint4*)&s->rec[rix])[part] = src[part];
+      }
+      __syncthreads();
+      // a FENCE task starts a batch of its own: cut the batch in front of it
+      if (tid == 0) {
+        uint32_t cut = n;
+        for (uint32_t i = 1; i < n; ++i)
+          if (s->rec[i].rflags & RF_FENCE) { cut = i; break; }
+        s->n = cut;
+      }
+      __syncthreads();
+      n = s->n;
+      // resolve the operator table ("claim time"): slot, version, impl, status
+      if (tid < n) {
+        Record& rc = s->rec[tid];
+        const uint32_t op = rc.op_id;
+        int32_t status = GPUOS_OK;
+        uint64_t e = 0;
+        if (op >= GPUOS_MAX_OPS) status = GPUOS_E_BADOP;          // bounds check on the op id
+        else {
+          e = s->entry[op];
+          if (e == 0) status = GPUOS_E_BADOP;                      // never registered
+        }
+        rc.impl = (uint32_t)e;
+        rc.version = (uint32_t)(e >> 32);
+        rc.sel = (uint8_t)((e >> 32) & 1u);
+        rc.status = status;
+        if (status != GPUOS_OK || rc.nchunks == 0) rc.nchunks = 1; // one unit reports the task
+        rc.ticket = mirrored + tid;
+        s->ubeg[tid + 1] = rc.nchunks;
+      }
+      if (tid == 0) s->ubeg[0] = 0;
+      __syncthreads();
+      if (tid == 0) {                                              // <= 64 entries: serial scan
+        uint32_t acc = 0;
+        for (uint32_t i = 1; i <= n; ++i) { acc += s->ubeg[i]; s->ubeg[i] = acc; }
+      }
+      __syncthreads();
+      // a leading FENCE: wait until every earlier ticket has completed
+      if (tid == 0 && (s->rec[0].rflags & RF_FENCE)) {
+        while (__hip_atomic_load(&a.d->done_count, __ATOMIC_RELAXED, SC_AGENT) < mirrored)
+          __builtin_amdgcn_s_sleep(4);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
+      // write the records into the device mirror
+      for (uint32_t p = tid; p < n * 16u; p += kThreads) {
+        const uint32_t rix = p >> 4, part = p & 15u;
+        uint4* dst = (uint4*)&a.dring[(mirrored + rix) & a.cap_mask];
+        dst[part] = ((const uint4*)&s->rec[rix])[part];
+      }
+      // expand into work units
+      const uint32_t total = s->ubeg[n];
+      for (uint32_t u = tid; u < total; u += kThreads) {
+        uint32_t lo = 0, hi = n;                                   // ubeg[lo] <= u < ubeg[hi]
+        while (hi - lo > 1) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (s->ubeg[mid] <= u) lo = mid; else hi = mid;
+        }
+        const Record& rc = s->rec[lo];
+        a.units[(units_w + u) & a.unit_mask] =
+            pack_unit(u - s->ubeg[lo], (uint32_t)((mirrored + lo) & a.cap_mask), rc.op_id, rc.sel,
+                      rc.status == GPUOS_OK ? 1u : 0u);
+      }
+      __syncthreads();                                             // every store above is issued and done
+      units_w += total;
+      mirrored += n;
+      if (tid == 0) {
+        __hip_atomic_store(&a.d->tail_units, units_w, __ATOMIC_RELEASE, SC_AGENT);
+        __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
+      }
+      idle_since = wall_clock64();
+    }
+    if (stopping) {
+      if (tid == 0) {
+        __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELEASE, SC_AGENT);
+        __hip_atomic_store(&a.h->exit_code, (ew & 2u) ? 2u : 1u, __ATOMIC_RELEASE, SC_SYSTEM);
+      }
+      return;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// worker (every workgroup but 0)
+// ---------------------------------------------------------------------------
+struct WorkShared {
+  Record rec;
+  uint64_t unit, entry;
+  int32_t exit_flag;
+  float red[4];
+};
+
+DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
+  const uint32_t tid = threadIdx.x;
+  while (true) {
+    // ---- claim one work unit (elected lane, atomic fetch-add) ----
+    if (tid == 0) {
+      const uint64_t g = __hip_atomic_fetch_add(&a.d->claim, 1ull, __ATOMIC_RELAXED, SC_AGENT);
+      int32_t ex = 0;
+      uint32_t polls = 0;
+      while (__hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_AGENT) <= g) {
+        if (__hip_atomic_load(&a.d->stop_dev, __ATOMIC_ACQUIRE, SC_AGENT)) {
+          if (__hip_atomic_load(&a.d->tail_units, __ATOMIC_ACQUIRE, SC_AGENT) <= g) { ex = 1; break; }
+          continue;
+        }
+        // polling policy (paper Section 4.1): short back-off while spinning, longer
+        // pauses every yield_every-th empty poll when the host asked for them
+        ++polls;
+        const uint32_t y = __hip_atomic_load(&a.d->yield_every, __ATOMIC_RELAXED, SC_AGENT);
+        if (y != 0 && (polls % y) == 0) { for (int k = 0; k < 16; ++k) __builtin_amdgcn_s_sleep(127); }
+        else if (polls < 64) __builtin_amdgcn_s_sleep(2);
+        else __builtin_amdgcn_s_sleep(16);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      s->exit_flag = ex;
+      if (!ex) s->unit = a.units[g & a.unit_mask];
+    }
+    __syncthreads();
+    if (s->exit_flag) return;
+    const uint64_t unit = s->unit;
+    const uint32_t chunk = (uint32_t)(unit & 0xfffffu);
+    const uint32_t slot = (uint32_t)((unit >> 20) & 0xffffu);
+    const uint32_t op = (uint32_t)((unit >> 36) & 0xffu), sel = (uint32_t)((unit >> 44) & 1u);
+    const bool op_valid = ((unit >> 45) & 1u) != 0;
+    // ---- fetch the descriptor (16 lanes x 16 bytes) and the claimed table slot ----
+    if (tid < 16) ((uint4*)&s->rec)[tid] = ((const uint4*)&a.dring[slot])[tid];
+    if (tid == 16) s->entry = op_valid ? __hip_atomic_load(&a.dtable[op].slot[sel], __ATOMIC_RELAXED, SC_AGENT) : 0ull;
+    __syncthreads();
+    const Record* r = &s->rec;
+    int32_t status = r->status;
+    const uint32_t impl = r->impl;
+    if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
+    // ---- dependencies: earlier tickets named by back-distance ----
+    if (r->dep[0] | r->dep[1] | r->dep[2]) {
+      if (tid == 0) {
+        const uint64_t ticket = r->ticket;
+        for (int k = 0; k < 3; ++k) {
+          const uint32_t back = r->dep[k];
+          if (back == 0 || back > ticket) continue;
+          const uint64_t want = ticket - back + 1;
+          const uint64_t* w = &a.st[(ticket - back) & a.cap_mask].done_seq;
+          while (__hip_atomic_load(w, __ATOMIC_RELAXED, SC_AGENT) < want) __builtin_amdgcn_s_sleep(1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
+      __syncthreads();
+    }
+    // ---- execute ----
+    if (status == GPUOS_OK) status = exec_chunk(r, impl, chunk, s->red);
+    __syncthreads();                  // all stores of the workgroup are complete past this point
+    // ---- complete ----
+    if (tid == 0) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");       // outputs visible to device and host
+      const uint32_t nchunks = r->nchunks;
+      bool last = true;
+      if (nchunks > 1) {
+        const uint32_t prev = __hip_atomic_fetch_add(&a.st[slot].chunks_done, 1u, __ATOMIC_RELAXED, SC_AGENT);
+        last = (prev + 1 == nchunks);
+        if (last) {
+          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "");   // take over the other chunks' releases
+          __hip_atomic_store(&a.st[slot].chunks_done, 0u, __ATOMIC_RELAXED, SC_AGENT);
+        }
+      }
+      if (last) {
+        const uint64_t ticket = r->ticket;
+        __hip_atomic_store(&a.st[slot].done_seq, ticket + 1, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_store(&a.hcomp[slot], pack_completion(ticket, status, r->version), __ATOMIC_RELAXED, SC_SYSTEM);
+        __hip_atomic_fetch_add(&a.d->done_count, 1ull, __ATOMIC_RELAXED, SC_AGENT);
+      }
+    }
+    __syncthreads();                  // the descriptor in LDS may be overwritten after this
+  }
+}
+
+union KernelShared {
+  DispShared disp;
+  WorkShared work;
+};
+
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) gpuos_worker_kernel(WorkerArgs a) {
+  __shared__ KernelShared sh;
+  if (blockIdx.x == 0) run_dispatcher(a, &sh.disp);
+  else run_worker(a, &sh.work);
+}
+
+// one ordinary launch per task: block b executes chunk b
+__global__ void __launch_bounds__(kThreads) gpuos_single_task_kernel(Record rec) {
+  __shared__ Record s_rec;
+  __shared__ float s_red[4];
+  if (threadIdx.x == 0) s_rec = rec;
+  __syncthreads();
+  exec_chunk(&s_rec, s_rec.impl, blockIdx.x, s_red);
+}
+
+int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream) {
+  hipLaunchKernelGGL(gpuos_worker_kernel, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, a);
+  return (int)hipGetLastError();
+}
+
+int worker_max_blocks_per_cu(int* out) {
+  return (int)hipOccupancyMaxActiveBlocksPerMultiprocessor(out, gpuos_worker_kernel, (int)kThreads, 0);
+}
+
+int launch_single(const Record& r, void* stream) {
+  const uint32_t grid = r.nchunks ? r.nchunks : 1u;
+  hipLaunchKernelGGL(gpuos_single_task_kernel, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, r);
+  return (int)hipGetLastError();
+}
+
+}  // namespace gpuos

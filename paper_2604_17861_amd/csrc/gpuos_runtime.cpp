@@ -1,0 +1,823 @@
+// gpuos_runtime.cpp -- host side of the GPUOS hot path: the C ABI of
+// include/gpuos.h.  Descriptor validation / coalescing / packing, the ring
+// producer (paper Section 4.2: acquire slot, write, commit with a store-release),
+// completion harvesting, the dual-slot operator table (Section 4.1) and the
+// lifecycle of the persistent worker (Section 5.4 / Table 1).
+
+#include <hip/hip_runtime_api.h>
+
+#include <atomic>
+#include <chrono>
+#include <cstddef>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include <pthread.h>
+#include <sched.h>
+
+#include "../../include/gpuos.h"
+#include "gpuos_internal.h"
+
+using namespace gpuos;
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+bool hip_ok(hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return false;
+}
+#define HIP_TRY(call) do { if (!hip_ok((call), #call)) return GPUOS_E_HIP; } while (0)
+
+inline uint64_t now_ns() {
+  return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+             std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+// ---- static facts about the implementations -------------------------------------
+int impl_arity(uint32_t impl) {
+  switch (impl) {
+    case GPUOS_IMPL_ADD: case GPUOS_IMPL_SUB: case GPUOS_IMPL_MUL: case GPUOS_IMPL_DIV:
+    case GPUOS_IMPL_SUB_EXP: return 2;
+    case GPUOS_IMPL_FMA: return 3;
+    case GPUOS_IMPL_RELU: case GPUOS_IMPL_EXP: case GPUOS_IMPL_GELU_ERF: case GPUOS_IMPL_GELU_TANH:
+    case GPUOS_IMPL_SCALE: case GPUOS_IMPL_COPY: case GPUOS_IMPL_SUM_LAST: case GPUOS_IMPL_MAX_LAST:
+    case GPUOS_IMPL_MIN_LAST: return 1;
+    default: return -1;
+  }
+}
+bool impl_is_reduction(uint32_t impl) {
+  return impl == GPUOS_IMPL_SUM_LAST || impl == GPUOS_IMPL_MAX_LAST || impl == GPUOS_IMPL_MIN_LAST;
+}
+bool impl_takes_int(uint32_t impl) {
+  return impl == GPUOS_IMPL_ADD || impl == GPUOS_IMPL_SUB || impl == GPUOS_IMPL_MUL ||
+         impl == GPUOS_IMPL_COPY || impl_is_reduction(impl);
+}
+inline uint32_t dtype_size(uint32_t dt) { return (dt == GPUOS_F32 || dt == GPUOS_I32) ? 4u : 2u; }
+
+constexpr int64_t kMaxExtent = 2147483647LL;
+
+struct Operand {              // one tensor after masking broadcast dims
+  uint64_t ptr;
+  int64_t stride[GPUOS_MAX_DIMS];
+  uint32_t dtype;
+};
+
+int check_operand(const gpuos_tensor& t, int ndim, const int64_t* size, bool is_out, Operand* o) {
+  if (t.ptr == nullptr || t.dtype > GPUOS_I32) return GPUOS_E_INVAL;
+  if (is_out && t.bcast_mask != 0) return GPUOS_E_INVAL;
+  int64_t max_off = 0;
+  o->ptr = (uint64_t)t.ptr;
+  o->dtype = t.dtype;
+  for (int d = 0; d < GPUOS_MAX_DIMS; ++d) o->stride[d] = 0;
+  for (int d = 0; d < ndim; ++d) {
+    if (t.stride[d] < 0) return GPUOS_E_INVAL;
+    const int64_t s = ((t.bcast_mask >> d) & 1) ? 0 : t.stride[d];
+    if (size[d] > 1) {
+      if (is_out && s == 0) return GPUOS_E_INVAL;        // output would overlap itself
+      if (s > kMaxExtent) return GPUOS_E_INVAL;
+      max_off += (size[d] - 1) * s;
+      if (max_off > kMaxExtent) return GPUOS_E_INVAL;
+      o->stride[d] = s;
+    }
+  }
+  return GPUOS_OK;
+}
+
+// Merge adjacent dims that every operand walks as one: outer stride == inner
+// stride * inner size for all operands.  Size-1 dims are dropped first.
+int coalesce(int nd, int64_t* size, Operand* ops, int nops) {
+  int64_t sz[GPUOS_MAX_DIMS];
+  int64_t st[5][GPUOS_MAX_DIMS];
+  int m = 0;
+  for (int d = 0; d < nd; ++d) {
+    if (size[d] == 1) continue;
+    sz[m] = size[d];
+    for (int k = 0; k < nops; ++k) st[k][m] = ops[k].stride[d];
+    ++m;
+  }
+  if (m == 0) {                                   // a single element
+    sz[0] = 1;
+    for (int k = 0; k < nops; ++k) st[k][0] = 1;
+    m = 1;
+  }
+  int w = 0;                                      // index of the dim being grown (outermost so far)
+  for (int d = 1; d < m; ++d) {
+    bool merge = true;
+    for (int k = 0; k < nops; ++k)
+      if (st[k][w] != st[k][d] * sz[d]) { merge = false; break; }
+    if (merge) {
+      sz[w] *= sz[d];
+      for (int k = 0; k < nops; ++k) st[k][w] = st[k][d];
+    } else {
+      ++w;
+      sz[w] = sz[d];
+      for (int k = 0; k < nops; ++k) st[k][w] = st[k][d];
+    }
+  }
+  m = w + 1;
+  for (int d = 0; d < GPUOS_MAX_DIMS; ++d) {
+    size[d] = d < m ? sz[d] : 1;
+    for (int k = 0; k < nops; ++k) ops[k].stride[d] = d < m ? st[k][d] : 0;
+  }
+  return m;
+}
+
+inline bool aligned16(uint64_t p) { return (p & 15u) == 0; }
+
+// Validate `t` for implementation `impl` and pack it.  Nothing is written to
+// *r unless the result is GPUOS_OK.
+int pack_task(const gpuos_task& t, uint32_t impl, Record* r) {
+  Record rec;
+  std::memset(&rec, 0, sizeof(rec));
+  rec.op_id = t.op_id;
+  rec.alpha = t.alpha;
+  rec.impl = impl;
+  rec.dep[0] = t.dep[0]; rec.dep[1] = t.dep[1]; rec.dep[2] = t.dep[2];
+  if (t.flags & ~(GPUOS_FLAG_FENCE | GPUOS_FLAG_KEEPDIM)) return GPUOS_E_INVAL;
+  if (t.flags & GPUOS_FLAG_FENCE) rec.rflags |= RF_FENCE;
+  if (impl == GPUOS_IMPL_FAIL) {                   // executes nothing; one unit reports it
+    rec.path = PATH_NOP;
+    rec.nchunks = 1;
+    *r = rec;
+    return GPUOS_OK;
+  }
+  const int ar = impl_arity(impl);
+  if (ar < 0) return GPUOS_E_BADOP;
+  if (t.ndim < 1 || t.ndim > GPUOS_MAX_DIMS || t.n_inputs != ar) return GPUOS_E_INVAL;
+  int64_t size[GPUOS_MAX_DIMS];
+  int64_t numel = 1;
+  for (int d = 0; d < GPUOS_MAX_DIMS; ++d) size[d] = 1;
+  for (int d = 0; d < t.ndim; ++d) {
+    if (t.size[d] < 0 || t.size[d] > kMaxExtent) return GPUOS_E_INVAL;
+    size[d] = t.size[d];
+    numel *= size[d];
+    if (numel > kMaxExtent) return GPUOS_E_INVAL;
+  }
+  const bool red = impl_is_reduction(impl);
+  const int nd_out = red ? t.ndim - 1 : t.ndim;
+  Operand ops[4];                                   // inputs 0..ar-1, then the output
+  for (int k = 0; k < ar; ++k) {
+    const int rc = check_operand(t.in[k], t.ndim, size, false, &ops[k]);
+    if (rc != GPUOS_OK) return rc;
+  }
+  {
+    const int rc = check_operand(t.out, nd_out, size, true, &ops[ar]);
+    if (rc != GPUOS_OK) return rc;
+  }
+  bool any_int = ops[ar].dtype == GPUOS_I32, all_int = any_int, same_dt = true;
+  for (int k = 0; k < ar; ++k) {
+    any_int = any_int || ops[k].dtype == GPUOS_I32;
+    all_int = all_int && ops[k].dtype == GPUOS_I32;
+    same_dt = same_dt && ops[k].dtype == ops[ar].dtype;
+  }
+  if (any_int && (!all_int || !impl_takes_int(impl))) return GPUOS_E_INVAL;
+  if (all_int) rec.rflags |= RF_INT;
+  rec.n_inputs = (uint8_t)ar;
+  for (int k = 0; k < ar; ++k) { rec.dtype[k] = (uint8_t)ops[k].dtype; rec.ptr[k] = ops[k].ptr; }
+  rec.dtype[3] = (uint8_t)ops[ar].dtype;
+  rec.ptr[3] = ops[ar].ptr;
+
+  if (!red) {
+    if (numel == 0) { rec.path = PATH_NOP; rec.nchunks = 1; *r = rec; return GPUOS_OK; }
+    const int nd = coalesce(t.ndim, size, ops, ar + 1);
+    rec.ndim = (uint8_t)nd;
+    for (int d = 0; d < nd; ++d) {
+      rec.size[d] = (uint32_t)size[d];
+      for (int k = 0; k < ar; ++k) rec.stride[k][d] = (uint32_t)ops[k].stride[d];
+      rec.stride[3][d] = (uint32_t)ops[ar].stride[d];
+    }
+    rec.numel = (uint32_t)numel;
+    const uint32_t V = 16u / dtype_size(ops[ar].dtype);
+    bool all_unit = nd == 1;
+    bool all_aligned = aligned16(ops[ar].ptr);
+    for (int k = 0; k <= ar && all_unit; ++k) all_unit = ops[k].stride[0] == 1 || numel == 1;
+    rec.path = PATH_GENERIC;
+    if (all_unit && same_dt) {
+      rec.path = PATH_CONTIG;
+      for (int k = 0; k < ar; ++k) all_aligned = all_aligned && aligned16(ops[k].ptr);
+      if (all_aligned) rec.rflags |= RF_VEC;
+    } else if (!all_int && nd == 2 && ar >= 2 && ops[ar].stride[1] == 1 && ops[ar].stride[0] == size[1] &&
+               size[1] % V == 0 && all_aligned) {
+      bool ok = true;
+      for (int k = 0; k < ar && ok; ++k) {
+        const int64_t s0 = ops[k].stride[0], s1 = ops[k].stride[1];
+        if (s1 == 1 && s0 == size[1] && ops[k].dtype == ops[ar].dtype && aligned16(ops[k].ptr)) rec.okind[k] = K_FULL;
+        else if (s1 == 1 && s0 == 0 && ops[k].dtype == ops[ar].dtype && aligned16(ops[k].ptr)) rec.okind[k] = K_ROWVEC;
+        else if (s1 == 0) rec.okind[k] = K_ROWSCALAR;
+        else ok = false;
+      }
+      if (ok) { rec.path = PATH_ROW2D; rec.rflags |= RF_VEC; }
+    }
+    uint64_t per = ((uint64_t)numel + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
+    per = (per + 1023) / 1024 * 1024;
+    if (per < kChunkElems) per = kChunkElems;
+    rec.chunk = (uint32_t)per;
+    rec.nchunks = (uint32_t)(((uint64_t)numel + per - 1) / per);
+    *r = rec;
+    return GPUOS_OK;
+  }
+
+  // ---- reduction over the last dim ----
+  const int64_t n = size[t.ndim - 1];
+  int64_t rows = 1;
+  for (int d = 0; d + 1 < t.ndim; ++d) rows *= size[d];
+  if (n == 0 && rows != 0) return GPUOS_E_INVAL;    // empty reduced dim: no defined result
+  if (rows == 0 || n == 0) { rec.path = PATH_NOP; rec.nchunks = 1; *r = rec; return GPUOS_OK; }
+  const int64_t s_last = n > 1 ? ops[0].stride[t.ndim - 1] : 1;
+  int64_t osz[GPUOS_MAX_DIMS];
+  Operand oo[2] = {ops[0], ops[1]};
+  for (int d = 0; d < GPUOS_MAX_DIMS; ++d) osz[d] = d < t.ndim - 1 ? size[d] : 1;
+  for (int d = t.ndim - 1; d < GPUOS_MAX_DIMS; ++d) { oo[0].stride[d] = 0; oo[1].stride[d] = 0; }
+  int nd = 0;
+  if (t.ndim > 1) nd = coalesce(t.ndim - 1, osz, oo, 2);
+  else { osz[0] = 1; oo[0].stride[0] = 0; oo[1].stride[0] = 0; nd = 1; }
+  rec.ndim = (uint8_t)nd;
+  for (int d = 0; d < nd; ++d) {
+    rec.size[d] = (uint32_t)osz[d];
+    rec.stride[0][d] = (uint32_t)oo[0].stride[d];
+    rec.stride[3][d] = (uint32_t)oo[1].stride[d];
+  }
+  rec.stride[0][5] = (uint32_t)s_last;
+  rec.red_n = (uint32_t)n;
+  rec.numel = (uint32_t)rows;
+  const uint32_t V = 16u / dtype_size(ops[0].dtype);
+  const bool rows_contig = rows == 1 || (nd == 1 && oo[0].stride[0] == n && oo[1].stride[0] == 1);
+  if (!all_int && s_last == 1 && rows_contig) {
+    rec.path = PATH_RED_CONTIG;
+    if (n % V == 0 && aligned16(ops[0].ptr)) rec.rflags |= RF_VEC;
+  } else {
+    rec.path = PATH_RED_GENERIC;
+  }
+  uint64_t rpc = kChunkElems / (uint64_t)n;
+  if (rpc < 1) rpc = 1;
+  if (n <= 512) rpc = (rpc + 255) / 256 * 256;
+  const uint64_t min_rpc = ((uint64_t)rows + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
+  if (rpc < min_rpc) rpc = min_rpc;
+  rec.chunk = (uint32_t)rpc;
+  rec.nchunks = (uint32_t)(((uint64_t)rows + rpc - 1) / rpc);
+  *r = rec;
+  return GPUOS_OK;
+}
+
+struct OpInfo {
+  uint32_t impl = 0;
+  uint32_t version = 0;            // 0 = unregistered
+  uint64_t prev_swap_head = 0;     // tickets submitted before the previous swap returned
+};
+
+}  // namespace
+
+struct gpuos_ctx {
+  gpuos_config cfg;
+  int device = 0;
+  hipStream_t stream = nullptr;
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  uint32_t cap = 0, mask = 0, workgroups = 0;
+  // host-coherent
+  HostCtl* h = nullptr;
+  Record* hring = nullptr;
+  uint64_t* hcomp = nullptr;
+  OpSlots* htable = nullptr;
+  // device
+  DevCtl* d = nullptr;
+  Record* dring = nullptr;
+  uint64_t* units = nullptr;
+  SlotState* st = nullptr;
+  OpSlots* dtable = nullptr;
+  // producer state
+  uint64_t head = 0;                         // tickets written
+  std::atomic<uint64_t> published{0};        // tickets behind the doorbell
+  std::atomic<uint64_t> floor{0};            // completed in order
+  std::atomic<int32_t> first_error{0};
+  uint64_t epoch = 0;
+  OpInfo ops[GPUOS_MAX_OPS];
+  // completion log
+  std::vector<gpuos_completion> log;
+  uint64_t log_mask = 0;
+  // harvester
+  std::thread harvester;
+  std::atomic<bool> harvester_run{false};
+  bool worker_running = false;
+  bool worker_joined = false;
+  uint64_t wait_ns = 0;
+};
+
+namespace {
+
+std::mutex g_live_mu;
+std::vector<gpuos_ctx*> g_live;
+bool g_atexit_registered = false;
+
+// Harvest completion words in ticket order (single consumer).
+uint64_t harvest(gpuos_ctx* c) {
+  uint64_t f = c->floor.load(std::memory_order_relaxed);
+  const uint64_t pub = c->published.load(std::memory_order_acquire);
+  uint64_t t_done = 0;
+  uint64_t n = 0;
+  while (f < pub) {
+    const uint64_t w = __atomic_load_n(&c->hcomp[f & c->mask], __ATOMIC_ACQUIRE);
+    if ((uint32_t)w != (uint32_t)(f + 1)) break;
+    if (t_done == 0) t_done = now_ns();
+    gpuos_completion& e = c->log[f & c->log_mask];
+    e.ticket = f;
+    e.status = (int32_t)(int8_t)(uint8_t)(w >> 32);
+    e.op_version = (uint32_t)(w >> 40);
+    e.t_done_ns = t_done;
+    if (e.status != 0) {
+      int32_t zero = 0;
+      c->first_error.compare_exchange_strong(zero, e.status);
+    }
+    ++f;
+    ++n;
+  }
+  if (n) c->floor.store(f, std::memory_order_release);
+  return n;
+}
+
+void harvester_main(gpuos_ctx* c) {
+  // pin to the last allowed core so that it does not share one with the producer
+  cpu_set_t set;
+  if (sched_getaffinity(0, sizeof(set), &set) == 0) {
+    int last = -1;
+    for (int i = 0; i < CPU_SETSIZE; ++i) if (CPU_ISSET(i, &set)) last = i;
+    if (last >= 0) { cpu_set_t one; CPU_ZERO(&one); CPU_SET(last, &one); pthread_setaffinity_np(pthread_self(), sizeof(one), &one); }
+  }
+  while (c->harvester_run.load(std::memory_order_acquire)) {
+    if (harvest(c) == 0) __builtin_ia32_pause();
+  }
+  harvest(c);
+}
+
+inline bool worker_exited(gpuos_ctx* c) { return __atomic_load_n(&c->h->exit_code, __ATOMIC_ACQUIRE) != 0; }
+
+// Spin until floor >= target.  Returns OK / TIMEOUT / DEAD.
+int wait_floor(gpuos_ctx* c, uint64_t target, uint64_t timeout_ns) {
+  const uint64_t t0 = now_ns();
+  uint32_t spins = 0;
+  while (true) {
+    if (!c->harvester_run.load(std::memory_order_relaxed)) harvest(c);
+    if (c->floor.load(std::memory_order_acquire) >= target) return GPUOS_OK;
+    if ((++spins & 1023u) == 0) {
+      if (worker_exited(c)) {
+        if (!c->harvester_run.load(std::memory_order_relaxed)) harvest(c);
+        return c->floor.load(std::memory_order_acquire) >= target ? GPUOS_OK : GPUOS_E_DEAD;
+      }
+      if (now_ns() - t0 > timeout_ns) return GPUOS_E_TIMEOUT;
+    }
+    __builtin_ia32_pause();
+  }
+}
+
+void doorbell(gpuos_ctx* c) {
+  const uint64_t pub = c->published.load(std::memory_order_relaxed);
+  if (pub == c->head) return;
+  const uint64_t t = now_ns();
+  for (uint64_t i = pub; i < c->head; ++i) c->log[i & c->log_mask].t_submit_ns = t;
+  c->published.store(c->head, std::memory_order_release);
+  __atomic_store_n(&c->h->tail, c->head, __ATOMIC_RELEASE);     // the commit: one store-release
+}
+
+void bump_epoch(gpuos_ctx* c, uint32_t op_hint, bool stop) {
+  ++c->epoch;
+  const uint64_t w = (c->epoch << 12) | ((uint64_t)(op_hint & 0xffu) << 4) | (stop ? 1u : 0u);
+  __atomic_store_n(&c->h->epoch_word, w, __ATOMIC_RELEASE);
+}
+
+void free_all(gpuos_ctx* c) {
+  if (c->h) (void)hipHostFree(c->h);
+  if (c->hring) (void)hipHostFree(c->hring);
+  if (c->hcomp) (void)hipHostFree(c->hcomp);
+  if (c->htable) (void)hipHostFree(c->htable);
+  if (c->d) (void)hipFree(c->d);
+  if (c->dring) (void)hipFree(c->dring);
+  if (c->units) (void)hipFree(c->units);
+  if (c->st) (void)hipFree(c->st);
+  if (c->dtable) (void)hipFree(c->dtable);
+  if (c->ev_start) (void)hipEventDestroy(c->ev_start);
+  if (c->ev_stop) (void)hipEventDestroy(c->ev_stop);
+  if (c->stream) (void)hipStreamDestroy(c->stream);
+  c->h = nullptr; c->hring = nullptr; c->hcomp = nullptr; c->htable = nullptr;
+  c->d = nullptr; c->dring = nullptr; c->units = nullptr; c->st = nullptr; c->dtable = nullptr;
+  c->ev_start = nullptr; c->ev_stop = nullptr; c->stream = nullptr;
+}
+
+int stop_worker(gpuos_ctx* c) {
+  if (c->worker_joined) return GPUOS_OK;
+  int rc = GPUOS_OK;
+  if (c->worker_running) {
+    doorbell(c);
+    rc = wait_floor(c, c->head, c->wait_ns);                  // drain
+    bump_epoch(c, 0xff, true);                                // signal worker exit
+    const uint64_t t0 = now_ns();
+    hipError_t q;
+    while ((q = hipStreamQuery(c->stream)) == hipErrorNotReady) {
+      if (now_ns() - t0 > c->wait_ns) break;
+      std::this_thread::sleep_for(std::chrono::microseconds(50));
+    }
+    if (q == hipErrorNotReady) rc = GPUOS_E_TIMEOUT;
+    else if (q != hipSuccess) { hip_ok(q, "worker kernel"); rc = GPUOS_E_HIP; }
+    c->worker_running = false;
+    if (rc != GPUOS_E_TIMEOUT) c->worker_joined = true;
+  }
+  if (c->harvester_run.load()) {
+    c->harvester_run.store(false, std::memory_order_release);
+    if (c->harvester.joinable()) c->harvester.join();
+  }
+  if (c->worker_joined) harvest(c);
+  return rc;
+}
+
+void shutdown_all_at_exit() {
+  std::vector<gpuos_ctx*> live;
+  {
+    std::lock_guard<std::mutex> lk(g_live_mu);
+    live = g_live;
+  }
+  for (gpuos_ctx* c : live) (void)stop_worker(c);
+}
+
+}  // namespace
+
+extern "C" {
+
+void gpuos_default_config(gpuos_config* cfg) {
+  if (!cfg) return;
+  std::memset(cfg, 0, sizeof(*cfg));
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  cfg->device = dev;
+  cfg->threads_per_workgroup = kThreads;
+  cfg->workgroups_per_cu = 4;
+  cfg->wait_timeout_ms = 30000;
+  cfg->completion_log = 1u << 20;
+}
+
+int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* user_cfg) {
+  if (!out) return GPUOS_E_INVAL;
+  *out = nullptr;
+  gpuos_config cfg;
+  if (user_cfg) cfg = *user_cfg; else gpuos_default_config(&cfg);
+  if (cfg.threads_per_workgroup == 0) cfg.threads_per_workgroup = kThreads;
+  if (cfg.threads_per_workgroup != kThreads) return GPUOS_E_INVAL;
+  if (cfg.workgroups_per_cu == 0) cfg.workgroups_per_cu = 4;
+  if (cfg.wait_timeout_ms == 0) cfg.wait_timeout_ms = 30000;
+  if (cfg.completion_log == 0) cfg.completion_log = 1u << 20;
+  uint32_t cap = queue_capacity ? queue_capacity : 4096u;
+  if (cap < 2 || cap > 65536 || (cap & (cap - 1)) != 0) return GPUOS_E_INVAL;
+  const char* env_idle = std::getenv("GPUOS_IDLE_EXIT_MS");
+  if (env_idle && cfg.idle_exit_ms == 0) cfg.idle_exit_ms = (uint32_t)std::strtoul(env_idle, nullptr, 10);
+
+  gpuos_ctx* c = new (std::nothrow) gpuos_ctx();
+  if (!c) return GPUOS_E_NOMEM;
+  c->cfg = cfg;
+  c->device = cfg.device;
+  c->cap = cap;
+  c->mask = cap - 1;
+  c->wait_ns = (uint64_t)cfg.wait_timeout_ms * 1000000ull;
+  uint64_t logcap = 1;
+  while (logcap < cfg.completion_log || logcap < cap) logcap <<= 1;
+  c->log.assign(logcap, gpuos_completion{});
+  c->log_mask = logcap - 1;
+
+  auto fail = [&](int rc) { free_all(c); delete c; return rc; };
+  if (!hip_ok(hipSetDevice(cfg.device), "hipSetDevice")) return fail(GPUOS_E_HIP);
+  hipDeviceProp_t prop;
+  if (!hip_ok(hipGetDeviceProperties(&prop, cfg.device), "hipGetDeviceProperties")) return fail(GPUOS_E_HIP);
+  const unsigned hflags = hipHostMallocCoherent | hipHostMallocMapped;
+  const size_t n_units = (size_t)cap * kMaxChunksPerTask;
+  if (!hip_ok(hipHostMalloc((void**)&c->h, sizeof(HostCtl), hflags), "hipHostMalloc(ctl)") ||
+      !hip_ok(hipHostMalloc((void**)&c->hring, sizeof(Record) * cap, hflags), "hipHostMalloc(ring)") ||
+      !hip_ok(hipHostMalloc((void**)&c->hcomp, sizeof(uint64_t) * cap, hflags), "hipHostMalloc(comp)") ||
+      !hip_ok(hipHostMalloc((void**)&c->htable, sizeof(OpSlots) * GPUOS_MAX_OPS, hflags), "hipHostMalloc(table)") ||
+      !hip_ok(hipMalloc((void**)&c->d, sizeof(DevCtl)), "hipMalloc(ctl)") ||
+      !hip_ok(hipMalloc((void**)&c->dring, sizeof(Record) * cap), "hipMalloc(ring)") ||
+      !hip_ok(hipMalloc((void**)&c->units, sizeof(uint64_t) * n_units), "hipMalloc(units)") ||
+      !hip_ok(hipMalloc((void**)&c->st, sizeof(SlotState) * cap), "hipMalloc(slots)") ||
+      !hip_ok(hipMalloc((void**)&c->dtable, sizeof(OpSlots) * GPUOS_MAX_OPS), "hipMalloc(table)"))
+    return fail(GPUOS_E_HIP);
+  std::memset(c->h, 0, sizeof(HostCtl));
+  std::memset(c->hring, 0, sizeof(Record) * cap);
+  std::memset(c->hcomp, 0, sizeof(uint64_t) * cap);
+  std::memset(c->htable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS);
+  if (!hip_ok(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking), "hipStreamCreateWithFlags") ||
+      !hip_ok(hipEventCreate(&c->ev_start), "hipEventCreate") ||
+      !hip_ok(hipEventCreate(&c->ev_stop), "hipEventCreate") ||
+      !hip_ok(hipMemsetAsync(c->d, 0, sizeof(DevCtl), c->stream), "hipMemsetAsync") ||
+      !hip_ok(hipMemsetAsync(c->st, 0, sizeof(SlotState) * cap, c->stream), "hipMemsetAsync") ||
+      !hip_ok(hipMemsetAsync(c->dtable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS, c->stream), "hipMemsetAsync") ||
+      !hip_ok(hipStreamSynchronize(c->stream), "hipStreamSynchronize"))
+    return fail(GPUOS_E_HIP);
+
+  // size the grid to what is co-resident: every workgroup must be running for
+  // the spin-waits (claims, dependencies) to be deadlock-free
+  int occ = 0;
+  if (!hip_ok((hipError_t)worker_max_blocks_per_cu(&occ), "hipOccupancyMaxActiveBlocksPerMultiprocessor")) return fail(GPUOS_E_HIP);
+  if (occ < 1) return fail(GPUOS_E_HIP);
+  uint32_t per_cu = cfg.workgroups_per_cu;
+  if (per_cu > (uint32_t)occ) per_cu = (uint32_t)occ;
+  c->workgroups = (uint32_t)prop.multiProcessorCount * per_cu;
+  if (c->workgroups < 2) c->workgroups = 2;
+  c->cfg.workgroups_per_cu = per_cu;
+
+  WorkerArgs a;
+  a.h = c->h; a.hring = c->hring; a.hcomp = c->hcomp; a.htable = c->htable;
+  a.d = c->d; a.dring = c->dring; a.units = c->units; a.st = c->st; a.dtable = c->dtable;
+  a.cap_mask = c->mask;
+  a.unit_mask = (uint32_t)(n_units - 1);
+  a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
+  if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
+  if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);
+  if (!hip_ok(hipEventRecord(c->ev_stop, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
+  c->worker_running = true;
+
+  // wait for the first heartbeat so that init returns with a live worker
+  {
+    const uint64_t t0 = now_ns();
+    while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
+      if (now_ns() - t0 > c->wait_ns) { (void)stop_worker(c); return fail(GPUOS_E_TIMEOUT); }
+      if (hipStreamQuery(c->stream) != hipErrorNotReady) { return fail(GPUOS_E_DEAD); }
+      __builtin_ia32_pause();
+    }
+  }
+  if (cfg.harvester_thread) {
+    c->harvester_run.store(true);
+    c->harvester = std::thread(harvester_main, c);
+  }
+  {
+    std::lock_guard<std::mutex> lk(g_live_mu);
+    g_live.push_back(c);
+    if (!g_atexit_registered) { std::atexit(shutdown_all_at_exit); g_atexit_registered = true; }
+  }
+  *out = c;
+  return GPUOS_OK;
+}
+
+int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
+  if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
+  if (impl_id == GPUOS_IMPL_NONE || impl_id >= GPUOS_IMPL_COUNT) return GPUOS_E_BADOP;
+  if (c->ops[op_id].version != 0) return GPUOS_E_INVAL;            // already bound: use swap_op
+  if (!c->worker_running) return GPUOS_E_DEAD;
+  OpInfo& o = c->ops[op_id];
+  o.impl = impl_id;
+  o.version = 1;
+  o.prev_swap_head = 0;
+  __atomic_store_n(&c->htable[op_id].slot[1], pack_entry(impl_id, 1), __ATOMIC_RELAXED);
+  __atomic_store_n(&c->htable[op_id].version, 1u, __ATOMIC_RELEASE);
+  bump_epoch(c, op_id, false);
+  if (out_version) *out_version = 1;
+  return GPUOS_OK;
+}
+
+int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
+  if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
+  if (impl_id == GPUOS_IMPL_NONE || impl_id >= GPUOS_IMPL_COUNT) return GPUOS_E_BADOP;
+  OpInfo& o = c->ops[op_id];
+  if (o.version == 0) return GPUOS_E_BADOP;
+  if (!c->worker_running) return GPUOS_E_DEAD;
+  if (impl_id != GPUOS_IMPL_FAIL && o.impl != GPUOS_IMPL_FAIL &&
+      (impl_arity(impl_id) != impl_arity(o.impl) || impl_is_reduction(impl_id) != impl_is_reduction(o.impl)))
+    return GPUOS_E_INVAL;
+  // The inactive slot still holds version-1's predecessor.  A task can only hold
+  // that entry if it was submitted before the previous swap returned: wait for those.
+  if (o.prev_swap_head > c->floor.load(std::memory_order_acquire)) {
+    doorbell(c);
+    const int rc = wait_floor(c, o.prev_swap_head, c->wait_ns);
+    if (rc != GPUOS_OK) return rc;
+  }
+  const uint32_t v = o.version + 1;
+  __atomic_store_n(&c->htable[op_id].slot[v & 1u], pack_entry(impl_id, v), __ATOMIC_RELAXED);  // inactive slot
+  __atomic_store_n(&c->htable[op_id].version, v, __ATOMIC_RELEASE);                           // flip
+  bump_epoch(c, op_id, false);
+  o.impl = impl_id;
+  o.version = v;
+  o.prev_swap_head = c->head;
+  if (out_version) *out_version = v;
+  return GPUOS_OK;
+}
+
+int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* out_first_ticket) {
+  if (!c || (!tasks && n)) return GPUOS_E_INVAL;
+  if (!c->worker_running || worker_exited(c)) return GPUOS_E_DEAD;
+  if (out_first_ticket) *out_first_ticket = c->head;
+  if (n == 0) return GPUOS_OK;
+  // pass 1: validate everything (all-or-nothing)
+  static thread_local std::vector<Record> staged;
+  staged.resize(n);
+  for (uint32_t i = 0; i < n; ++i) {
+    const gpuos_task& t = tasks[i];
+    uint32_t impl = GPUOS_IMPL_NONE;
+    if (t.op_id < GPUOS_MAX_OPS) impl = c->ops[t.op_id].version ? c->ops[t.op_id].impl : GPUOS_IMPL_NONE;
+    int rc;
+    if (impl == GPUOS_IMPL_NONE) {
+      if (!c->cfg.defer_op_check) return GPUOS_E_BADOP;
+      rc = pack_task(t, GPUOS_IMPL_FAIL, &staged[i]);             // the device reports the bad op id
+    } else {
+      rc = pack_task(t, impl, &staged[i]);
+    }
+    if (rc != GPUOS_OK) return rc;
+    for (int k = 0; k < 3; ++k) {
+      const uint64_t back = t.dep[k];
+      if (back >= c->cap || back > c->head + i) return GPUOS_E_INVAL;
+    }
+  }
+  if (c->cfg.nonblocking_submit) {
+    if (!c->harvester_run.load(std::memory_order_relaxed)) harvest(c);
+    if ((uint64_t)n > c->cap - (c->head - c->floor.load(std::memory_order_acquire))) return GPUOS_E_FULL;
+  }
+  // pass 2: write the records into their slots
+  for (uint32_t i = 0; i < n; ++i) {
+    if (c->head - c->floor.load(std::memory_order_acquire) >= c->cap) {
+      doorbell(c);                                                // publish so that the device can make room
+      const int rc = wait_floor(c, c->head - c->cap + 1, c->wait_ns);
+      if (rc != GPUOS_OK) return rc;
+    }
+    std::memcpy(&c->hring[c->head & c->mask], &staged[i], sizeof(Record));
+    ++c->head;
+  }
+  return GPUOS_OK;
+}
+
+int gpuos_flush(gpuos_ctx* c) {
+  if (!c) return GPUOS_E_INVAL;
+  if (!c->worker_running) return GPUOS_E_DEAD;
+  doorbell(c);
+  return GPUOS_OK;
+}
+
+int gpuos_wait(gpuos_ctx* c, uint64_t ticket, uint64_t timeout_ns) {
+  if (!c) return GPUOS_E_INVAL;
+  if (c->worker_running) doorbell(c);
+  const bool all = ticket == GPUOS_ALL;
+  if (!all && ticket >= c->head) return GPUOS_E_INVAL;
+  const uint64_t target = all ? c->head : ticket + 1;
+  if (c->floor.load(std::memory_order_acquire) < target) {
+    if (!c->worker_running) return GPUOS_E_DEAD;
+    const int rc = wait_floor(c, target, timeout_ns ? timeout_ns : c->wait_ns);
+    if (rc != GPUOS_OK) return rc;
+  }
+  if (all) return c->first_error.exchange(0);
+  if (c->head - ticket > c->log_mask + 1) return GPUOS_OK;        // fell out of the log
+  return c->log[ticket & c->log_mask].status;
+}
+
+int gpuos_get_completions(gpuos_ctx* c, uint64_t first, uint32_t n, gpuos_completion* out) {
+  if (!c || (!out && n)) return GPUOS_E_INVAL;
+  const uint64_t fl = c->floor.load(std::memory_order_acquire);
+  if (first + n > fl) return GPUOS_E_INVAL;
+  if (fl - first > c->log_mask + 1) return GPUOS_E_INVAL;
+  for (uint32_t i = 0; i < n; ++i) out[i] = c->log[(first + i) & c->log_mask];
+  return GPUOS_OK;
+}
+
+int gpuos_peek_queue(gpuos_ctx* c, gpuos_queue_state* out) {
+  if (!c || !out) return GPUOS_E_INVAL;
+  if (c->worker_running && !c->harvester_run.load(std::memory_order_relaxed)) harvest(c);
+  out->head_submitted = c->head;
+  out->tail_published = c->published.load(std::memory_order_acquire);
+  out->claimed = c->h ? __atomic_load_n(&c->h->dispatched, __ATOMIC_ACQUIRE) : 0;
+  out->completed = c->floor.load(std::memory_order_acquire);
+  out->heartbeat = c->h ? __atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) : 0;
+  out->capacity = c->cap;
+  out->workgroups = c->workgroups;
+  return GPUOS_OK;
+}
+
+int gpuos_worker_alive(gpuos_ctx* c) {
+  if (!c || !c->worker_running || !c->h) return 0;
+  if (worker_exited(c)) return 0;
+  // the dispatcher bumps the heartbeat every 64 polls (a few hundred microseconds at most)
+  const uint64_t hb0 = __atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE);
+  const uint64_t t0 = now_ns();
+  while (now_ns() - t0 < 50000000ull) {
+    if (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) != hb0) return 1;
+    if (hipStreamQuery(c->stream) != hipErrorNotReady) return 0;
+  }
+  // no poll for 50 ms: the dispatcher may be busy mirroring; the kernel is still resident
+  return hipStreamQuery(c->stream) == hipErrorNotReady ? 1 : 0;
+}
+
+int gpuos_set_yield_every(gpuos_ctx* c, uint32_t every) {
+  if (!c) return GPUOS_E_INVAL;
+  if (!c->worker_running) return GPUOS_E_DEAD;
+  __atomic_store_n(&c->h->yield_every, every, __ATOMIC_RELEASE);
+  bump_epoch(c, 0xff, false);
+  return GPUOS_OK;
+}
+
+int gpuos_stop_worker(gpuos_ctx* c) {
+  if (!c) return GPUOS_E_INVAL;
+  return stop_worker(c);
+}
+
+int gpuos_worker_elapsed_ms(gpuos_ctx* c, float* out_ms) {
+  if (!c || !out_ms) return GPUOS_E_INVAL;
+  if (!c->worker_joined) return GPUOS_E_INVAL;
+  HIP_TRY(hipEventElapsedTime(out_ms, c->ev_start, c->ev_stop));
+  return GPUOS_OK;
+}
+
+int gpuos_shutdown(gpuos_ctx* c) {
+  if (!c) return GPUOS_OK;
+  const int rc = stop_worker(c);
+  {
+    std::lock_guard<std::mutex> lk(g_live_mu);
+    for (size_t i = 0; i < g_live.size(); ++i)
+      if (g_live[i] == c) { g_live.erase(g_live.begin() + (long)i); break; }
+  }
+  if (rc == GPUOS_E_TIMEOUT) return rc;     // the kernel may still be running: leak rather than free under it
+  (void)hipSetDevice(c->device);
+  free_all(c);
+  delete c;
+  return rc;
+}
+
+int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n, const uint32_t* impl_of_op,
+                        int32_t sync_each, uint64_t* lat_ns, double* out_seconds) {
+  if ((!tasks && n) || !impl_of_op) return GPUOS_E_INVAL;
+  HIP_TRY(hipSetDevice(device));
+  hipStream_t s;
+  HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+  int rc = GPUOS_OK;
+  const uint64_t t0 = now_ns();
+  for (uint32_t i = 0; i < n && rc == GPUOS_OK; ++i) {
+    const uint64_t ta = sync_each ? now_ns() : 0;
+    Record r;
+    const uint32_t impl = tasks[i].op_id < GPUOS_MAX_OPS ? impl_of_op[tasks[i].op_id] : 0u;
+    if (impl == GPUOS_IMPL_NONE) { rc = GPUOS_E_BADOP; break; }
+    rc = pack_task(tasks[i], impl, &r);
+    if (rc != GPUOS_OK) break;
+    if (r.path != PATH_NOP && !hip_ok((hipError_t)launch_single(r, s), "launch per op")) { rc = GPUOS_E_HIP; break; }
+    if (sync_each) {
+      if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) { rc = GPUOS_E_HIP; break; }
+      if (lat_ns) lat_ns[i] = now_ns() - ta;
+    }
+  }
+  if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize") && rc == GPUOS_OK) rc = GPUOS_E_HIP;
+  if (out_seconds) *out_seconds = (double)(now_ns() - t0) * 1e-9;
+  (void)hipStreamDestroy(s);
+  return rc;
+}
+
+int gpuos_task_bytes(const gpuos_task* t, uint32_t impl, uint64_t* out_bytes) {
+  if (!t || !out_bytes) return GPUOS_E_INVAL;
+  Record r;
+  const int rc = pack_task(*t, impl, &r);
+  if (rc != GPUOS_OK) return rc;
+  *out_bytes = 0;
+  if (impl == GPUOS_IMPL_FAIL) return GPUOS_OK;
+  const int ar = impl_arity(impl);
+  const bool red = impl_is_reduction(impl);
+  uint64_t out_elems = 1;
+  for (int d = 0; d < (red ? t->ndim - 1 : t->ndim); ++d) out_elems *= (uint64_t)t->size[d];
+  uint64_t total = out_elems * dtype_size(t->out.dtype);
+  for (int k = 0; k < ar; ++k) {
+    uint64_t distinct = 1;
+    for (int d = 0; d < t->ndim; ++d) {
+      const bool bc = ((t->in[k].bcast_mask >> d) & 1) || t->in[k].stride[d] == 0;
+      if (!bc) distinct *= (uint64_t)t->size[d];
+      else if (t->size[d] == 0) distinct = 0;
+    }
+    total += distinct * dtype_size(t->in[k].dtype);
+  }
+  *out_bytes = total;
+  return GPUOS_OK;
+}
+
+const char* gpuos_strerror(int status) {
+  switch (status) {
+    case GPUOS_OK: return "ok";
+    case GPUOS_E_INVAL: return "invalid argument or descriptor";
+    case GPUOS_E_FULL: return "ring full";
+    case GPUOS_E_BADOP: return "unknown, unregistered or failed operator";
+    case GPUOS_E_TIMEOUT: return "timed out";
+    case GPUOS_E_DEAD: return "worker kernel is not running";
+    case GPUOS_E_HIP: return "HIP runtime error";
+    case GPUOS_E_NOMEM: return "out of memory";
+    case GPUOS_E_VERSION: return "operator-table version mismatch";
+    default: return "unknown status";
+  }
+}
+
+const char* gpuos_last_hip_error(void) { return g_hip_error.c_str(); }
+
+void gpuos_abi_layout(uint32_t out[8]) {
+  out[0] = (uint32_t)sizeof(gpuos_task);
+  out[1] = (uint32_t)sizeof(gpuos_tensor);
+  out[2] = (uint32_t)offsetof(gpuos_task, size);
+  out[3] = (uint32_t)offsetof(gpuos_task, in);
+  out[4] = (uint32_t)offsetof(gpuos_task, out);
+  out[5] = (uint32_t)offsetof(gpuos_task, alpha);
+  out[6] = (uint32_t)offsetof(gpuos_task, dep);
+  out[7] = (uint32_t)sizeof(gpuos_completion);
+}
+
+}  // extern "C"

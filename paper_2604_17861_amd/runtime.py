@@ -1,0 +1,273 @@
+"""Thin ctypes binding of include/gpuos.h: same names, argument marshalling only.
+
+Every step of the hot path runs in the HIP library.  There is no CPU fallback: if libgpuos.so is
+missing or fails to load, importing a symbol raises.  Tensor memory and streams come from
+PyTorch (or any other allocator); the binding only passes raw device addresses through.
+
+While a Runtime is alive its persistent worker kernel is resident on the GPU.  Do not call
+torch.cuda.synchronize() (hipDeviceSynchronize waits for that kernel too) before shutdown();
+synchronize the stream you are using instead, e.g. torch.cuda.current_stream().synchronize().
+"""
+import atexit
+import ctypes
+import os
+import weakref
+
+import numpy as np
+
+from . import streams as S
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgpuos.so")
+
+OK, E_INVAL, E_FULL, E_BADOP, E_TIMEOUT, E_DEAD, E_HIP, E_NOMEM, E_VERSION = 0, -1, -2, -3, -4, -5, -6, -7, -8
+ALL = (1 << 64) - 1
+MAX_OPS = 256
+
+
+class Config(ctypes.Structure):
+    _fields_ = [("device", ctypes.c_int32), ("threads_per_workgroup", ctypes.c_uint32),
+                ("workgroups_per_cu", ctypes.c_uint32), ("nonblocking_submit", ctypes.c_uint32),
+                ("harvester_thread", ctypes.c_uint32), ("defer_op_check", ctypes.c_uint32),
+                ("idle_exit_ms", ctypes.c_uint32), ("wait_timeout_ms", ctypes.c_uint32),
+                ("completion_log", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 7)]
+
+
+class QueueState(ctypes.Structure):
+    _fields_ = [("head_submitted", ctypes.c_uint64), ("tail_published", ctypes.c_uint64),
+                ("claimed", ctypes.c_uint64), ("completed", ctypes.c_uint64),
+                ("heartbeat", ctypes.c_uint64), ("capacity", ctypes.c_uint32),
+                ("workgroups", ctypes.c_uint32)]
+
+
+class GpuosError(RuntimeError):
+    def __init__(self, status, what=""):
+        self.status = status
+        msg = "%s: %s (%d)" % (what, strerror(status), status)
+        if status == E_HIP:
+            msg += " [" + last_hip_error() + "]"
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def lib():
+    """Load libgpuos.so (built in-tree by paper_2604_17861_amd.build).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            LIB_PATH + " is not built; run `python -m paper_2604_17861_amd.build` (there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, u32, u64, i32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int32
+    P = ctypes.POINTER
+    sig = {
+        "gpuos_default_config": (None, [P(Config)]),
+        "gpuos_init": (ctypes.c_int, [P(vp), u32, P(Config)]),
+        "gpuos_register_op": (ctypes.c_int, [vp, u32, u32, P(u32)]),
+        "gpuos_swap_op": (ctypes.c_int, [vp, u32, u32, P(u32)]),
+        "gpuos_submit": (ctypes.c_int, [vp, vp, u32, P(u64)]),
+        "gpuos_flush": (ctypes.c_int, [vp]),
+        "gpuos_wait": (ctypes.c_int, [vp, u64, u64]),
+        "gpuos_get_completions": (ctypes.c_int, [vp, u64, u32, vp]),
+        "gpuos_peek_queue": (ctypes.c_int, [vp, P(QueueState)]),
+        "gpuos_worker_alive": (ctypes.c_int, [vp]),
+        "gpuos_set_yield_every": (ctypes.c_int, [vp, u32]),
+        "gpuos_shutdown": (ctypes.c_int, [vp]),
+        "gpuos_stop_worker": (ctypes.c_int, [vp]),
+        "gpuos_worker_elapsed_ms": (ctypes.c_int, [vp, P(ctypes.c_float)]),
+        "gpuos_launch_per_op": (ctypes.c_int, [i32, vp, u32, vp, i32, vp, P(ctypes.c_double)]),
+        "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
+        "gpuos_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+        "gpuos_last_hip_error": (ctypes.c_char_p, []),
+        "gpuos_abi_layout": (None, [vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)          # AttributeError if the library does not export it
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
+           "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
+           "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
+           "gpuos_worker_elapsed_ms", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_strerror",
+           "gpuos_last_hip_error", "gpuos_abi_layout"]
+
+
+def strerror(status):
+    return lib().gpuos_strerror(int(status)).decode()
+
+
+def last_hip_error():
+    return lib().gpuos_last_hip_error().decode()
+
+
+def abi_layout():
+    out = np.zeros(8, dtype=np.uint32)
+    lib().gpuos_abi_layout(out.ctypes.data)
+    return out
+
+
+def default_config():
+    cfg = Config()
+    lib().gpuos_default_config(ctypes.byref(cfg))
+    return cfg
+
+
+def _check(rc, what):
+    if rc != OK:
+        raise GpuosError(rc, what)
+    return rc
+
+
+def _tasks_ptr(tasks, first=0):
+    assert tasks.dtype == S.TASK_DT and tasks.flags["C_CONTIGUOUS"]
+    return tasks.ctypes.data + first * S.TASK_DT.itemsize
+
+
+_live = weakref.WeakSet()
+
+
+class Runtime:
+    """One GPUOS context: gpuos_init ... gpuos_shutdown."""
+
+    def __init__(self, queue_capacity=0, **cfg_fields):
+        L = lib()
+        cfg = default_config()
+        for k, v in cfg_fields.items():
+            if not hasattr(cfg, k):
+                raise TypeError("unknown config field " + k)
+            setattr(cfg, k, v)
+        self._ctx = ctypes.c_void_p()
+        _check(L.gpuos_init(ctypes.byref(self._ctx), queue_capacity, ctypes.byref(cfg)), "gpuos_init")
+        self.cfg = cfg
+        _live.add(self)
+
+    # -- operator table ------------------------------------------------------
+    def register_op(self, op_id, impl_id):
+        v = ctypes.c_uint32()
+        _check(lib().gpuos_register_op(self._ctx, op_id, impl_id, ctypes.byref(v)), "gpuos_register_op")
+        return v.value
+
+    def swap_op(self, op_id, impl_id):
+        v = ctypes.c_uint32()
+        _check(lib().gpuos_swap_op(self._ctx, op_id, impl_id, ctypes.byref(v)), "gpuos_swap_op")
+        return v.value
+
+    def register_table(self, table):
+        for op, impl in table.items():
+            self.register_op(op, impl)
+
+    # -- submission ----------------------------------------------------------
+    def submit(self, tasks, first=0, count=None, flush=True, check=True):
+        """gpuos_submit (+ gpuos_flush).  Returns the first ticket; with check=False returns
+        (status, first ticket) instead of raising."""
+        n = len(tasks) - first if count is None else count
+        t0 = ctypes.c_uint64()
+        rc = lib().gpuos_submit(self._ctx, _tasks_ptr(tasks, first), n, ctypes.byref(t0))
+        if rc == OK and flush:
+            rc = lib().gpuos_flush(self._ctx)
+        if not check:
+            return rc, t0.value
+        _check(rc, "gpuos_submit")
+        return t0.value
+
+    def flush(self):
+        _check(lib().gpuos_flush(self._ctx), "gpuos_flush")
+
+    def wait(self, ticket=ALL, timeout_ns=0, check=True):
+        rc = lib().gpuos_wait(self._ctx, ticket, timeout_ns)
+        if check:
+            _check(rc, "gpuos_wait")
+        return rc
+
+    def completions(self, first, n):
+        out = np.zeros(n, dtype=S.COMPLETION_DT)
+        _check(lib().gpuos_get_completions(self._ctx, first, n, out.ctypes.data), "gpuos_get_completions")
+        return out
+
+    # -- introspection ---------------------------------------------------------
+    def peek_queue(self):
+        q = QueueState()
+        _check(lib().gpuos_peek_queue(self._ctx, ctypes.byref(q)), "gpuos_peek_queue")
+        return q
+
+    def worker_alive(self):
+        return bool(self._ctx) and lib().gpuos_worker_alive(self._ctx) == 1
+
+    def set_yield_every(self, every):
+        _check(lib().gpuos_set_yield_every(self._ctx, every), "gpuos_set_yield_every")
+
+    # -- lifecycle ------------------------------------------------------------------
+    def stop_worker(self, check=True):
+        rc = lib().gpuos_stop_worker(self._ctx)
+        if check:
+            _check(rc, "gpuos_stop_worker")
+        return rc
+
+    def worker_elapsed_ms(self):
+        ms = ctypes.c_float()
+        _check(lib().gpuos_worker_elapsed_ms(self._ctx, ctypes.byref(ms)), "gpuos_worker_elapsed_ms")
+        return ms.value
+
+    def shutdown(self, check=True):
+        if not self._ctx:
+            return OK
+        ctx, self._ctx = self._ctx, ctypes.c_void_p()
+        rc = lib().gpuos_shutdown(ctx)
+        if check:
+            _check(rc, "gpuos_shutdown")
+        return rc
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.shutdown(check=exc[0] is None)
+        return False
+
+    def __del__(self):
+        try:
+            self.shutdown(check=False)
+        except Exception:
+            pass
+
+
+def launch_per_op(tasks, table, device=0, sync_each=False, first=0, count=None):
+    """gpuos_launch_per_op: the stream as one ordinary kernel launch per task.
+    Returns (seconds, per-task latencies in ns or None)."""
+    n = len(tasks) - first if count is None else count
+    impl = np.zeros(MAX_OPS, dtype=np.uint32)
+    for op, im in table.items():
+        impl[op] = im
+    lat = np.zeros(n, dtype=np.uint64) if sync_each else None
+    secs = ctypes.c_double()
+    rc = lib().gpuos_launch_per_op(device, _tasks_ptr(tasks, first), n, impl.ctypes.data, 1 if sync_each else 0,
+                                   lat.ctypes.data if sync_each else None, ctypes.byref(secs))
+    _check(rc, "gpuos_launch_per_op")
+    return secs.value, lat
+
+
+def task_bytes(tasks, impls):
+    """Algorithmic HBM bytes of every task (gpuos_task_bytes)."""
+    out = np.zeros(len(tasks), dtype=np.uint64)
+    b = ctypes.c_uint64()
+    L = lib()
+    for i in range(len(tasks)):
+        _check(L.gpuos_task_bytes(_tasks_ptr(tasks, i), int(impls[i]), ctypes.byref(b)), "gpuos_task_bytes")
+        out[i] = b.value
+    return out
+
+
+@atexit.register
+def _shutdown_live():
+    for rt in list(_live):
+        try:
+            rt.shutdown(check=False)
+        except Exception:
+            pass

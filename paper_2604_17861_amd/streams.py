@@ -88,16 +88,18 @@ class Stream:
     def __len__(self):
         return len(self.tasks)
 
-    def materialize(self, bases) -> np.ndarray:
-        """Copy of the task array with absolute pointers: ptr = bases[pool] + offset."""
+    def materialize(self, bases, out_bases=None) -> np.ndarray:
+        """Copy of the task array with absolute pointers: ptr = bases[pool] + offset.
+        out_bases (optional) gives different base addresses for the output tensors."""
         out = self.tasks.copy()
         bases = np.asarray(bases, dtype=np.uint64)
+        obases = bases if out_bases is None else np.asarray(out_bases, dtype=np.uint64)
         for k in range(3):
             used = self.pool_of[:, k] >= 0
             idx = np.where(used, self.pool_of[:, k], 0)
             out["inp"]["ptr"][:, k] = np.where(used, bases[idx] + self.tasks["inp"]["ptr"][:, k], 0)
         idx = self.pool_of[:, 3]
-        out["out"]["ptr"] = bases[idx] + self.tasks["out"]["ptr"]
+        out["out"]["ptr"] = obases[idx] + self.tasks["out"]["ptr"]
         return out
 
     def impl_for(self, versions=None) -> np.ndarray:

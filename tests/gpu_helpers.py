@@ -1,0 +1,148 @@
+"""GPU-side test plumbing: pools in device memory (torch is used for allocation and copies only),
+running a stream through the C ABI binding, and the element-by-element comparison against the
+CPU oracle with the tolerances the build states."""
+import math
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2604_17861_amd import runtime as R
+from paper_2604_17861_amd import streams as S
+from helpers import ulp_distance, np_dtype, bf16_bits_to_f32
+
+EXACT = {S.IMPL[n] for n in ("ADD", "SUB", "MUL", "DIV", "RELU", "SCALE", "FMA", "COPY", "MAX_LAST", "MIN_LAST")}
+TRANSCENDENTAL = {S.IMPL[n] for n in ("EXP", "SUB_EXP", "GELU_ERF", "GELU_TANH")}
+ULP_TOL = 2            # elementwise float results: within 2 ulp of the output dtype
+RED_REL = 1e-5         # fp32 reductions: |g - o| <= 1e-5 * max(|o|, L1 / sqrt(n))
+
+
+class DevicePools:
+    def __init__(self, stream, device="cuda:0"):
+        self.stream = stream
+        self.tensors = []
+        for p in stream.pools:
+            if p.data is None and p.tile is None:
+                t = torch.zeros(p.nbytes, dtype=torch.uint8, device=device)
+            else:
+                t = torch.from_numpy(np.ascontiguousarray(p.host_image())).to(device)
+            self.tensors.append(t)
+        torch.cuda.current_stream().synchronize()
+        self.bases = [t.data_ptr() for t in self.tensors]
+        self.tasks = stream.materialize(self.bases)
+
+    def download(self, pools=None):
+        out = []
+        for k, t in enumerate(self.tensors):
+            out.append(t.cpu().numpy() if pools is None or k in pools else None)
+        return out
+
+
+def run_stream(stream, rt, dp, first=0, count=None, wait=True):
+    """Submit tasks[first:first+count] in the stream's batch size, applying its hot swaps at the
+    task indices they are scheduled for.  Returns the first ticket."""
+    n = len(stream) - first if count is None else count
+    batch = stream.batch or n
+    swaps = {t: (op, impl) for t, op, impl in stream.swaps}
+    t0 = None
+    i = first
+    while i < first + n:
+        m = min(batch, first + n - i)
+        for t in range(i, i + m):
+            if t in swaps and t > first:
+                m = t - i
+                break
+        if i in swaps and i > 0:
+            rt.swap_op(*swaps[i])
+        tk = rt.submit(dp.tasks, i, m)
+        if t0 is None:
+            t0 = tk
+        i += m
+    if wait:
+        rt.wait()
+    return t0
+
+
+def _strided(buf, dt_code, byte_off, shape, strides_elems):
+    dt = np_dtype(dt_code)
+    es = np.dtype(dt).itemsize
+    arr = buf[byte_off:].view(np.uint8)
+    need = (1 + sum((s - 1) * st for s, st in zip(shape, strides_elems))) * es if all(s > 0 for s in shape) else 0
+    base = np.frombuffer(arr[:need].tobytes(), dtype=dt) if False else arr[:need].view(dt)
+    return np.lib.stride_tricks.as_strided(base, shape=shape, strides=[st * es for st in strides_elems],
+                                           writeable=False)
+
+
+def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, mode=oracle.MODE_F64CORE):
+    """Per task: run the oracle on the inputs the GPU saw (gpu_images) into a scratch copy of the
+    pools and compare the task's output elements.  Returns a stats dict; raises AssertionError on
+    any violation."""
+    n = len(stream) - first if count is None else count
+    impls = stream.impl_for(versions)
+    gpu = [np.ascontiguousarray(a) for a in gpu_images]
+    orc = [a.copy() for a in gpu]
+    in_bases = [a.ctypes.data for a in gpu]
+    out_bases = [a.ctypes.data for a in orc]
+    tasks = stream.materialize(in_bases, out_bases)
+    st = oracle.run_stream(tasks, impls, mode, first, n)
+    assert np.all(st == 0), "oracle rejected tasks: %s" % np.nonzero(st)[0][:10]
+    stats = dict(max_ulp=0, max_red_ratio=0.0, tasks=n, elements=0)
+    T = stream.tasks
+    for i in range(first, first + n):
+        impl = int(impls[i])
+        nd = int(T["ndim"][i])
+        size = [int(x) for x in T["size"][i][:nd]]
+        red = impl in S.REDUCTIONS
+        oshape = size[:-1] if red else size
+        ostr = [int(x) for x in T["out"]["stride"][i][:len(oshape)]]
+        if not oshape:
+            oshape, ostr = [1], [1]
+        if any(s == 0 for s in oshape):
+            continue
+        pool, off, dt = int(stream.pool_of[i, 3]), int(T["out"]["ptr"][i]), int(T["out"]["dtype"][i])
+        g = _strided(gpu[pool], dt, off, oshape, ostr)
+        o = _strided(orc[pool], dt, off, oshape, ostr)
+        stats["elements"] += g.size
+        if dt == S.I32:
+            assert np.array_equal(g, o), "task %d (%s): integer mismatch" % (i, S.IMPL_NAME[impl])
+            continue
+        bits = np.uint32 if dt == S.F32 else np.uint16
+        gb, ob = np.ascontiguousarray(g).view(bits), np.ascontiguousarray(o).view(bits)
+        if impl == S.IMPL["SUM_LAST"]:
+            nrows = int(np.prod(oshape))
+            s64, l1 = oracle.sum_last_f64(tasks, i, nrows)
+            gv = _as_f64(gb, dt).reshape(-1)
+            tol = RED_REL * np.maximum(np.abs(s64), l1 / math.sqrt(size[-1]))
+            if dt != S.F32:
+                tol = tol + _ulp_size(s64, dt)
+            err = np.abs(gv - s64)
+            fin = np.isfinite(s64)
+            ratio = float((err[fin] / np.maximum(tol[fin], 1e-300)).max()) if fin.any() else 0.0
+            stats["max_red_ratio"] = max(stats["max_red_ratio"], ratio)
+            assert ratio <= 1.0, "task %d SUM_LAST: error %.3g x tolerance" % (i, ratio)
+            assert np.array_equal(np.isnan(gv[~fin]), np.isnan(s64[~fin]))
+            continue
+        d = ulp_distance(gb, ob, dt)
+        mx = int(d.max()) if d.size else 0
+        lim = 0 if impl in EXACT else ULP_TOL
+        stats["max_ulp"] = max(stats["max_ulp"], mx)
+        if mx > lim:
+            k = int(np.argmax(d))
+            raise AssertionError("task %d (%s, dtype %d): %d ulp at flat index %d: gpu %r oracle %r" % (
+                i, S.IMPL_NAME[impl], dt, mx, k, gb.reshape(-1)[k], ob.reshape(-1)[k]))
+    return stats
+
+
+def _as_f64(bits, dt):
+    if dt == S.F32:
+        return bits.view(np.float32).astype(np.float64)
+    if dt == S.F16:
+        return bits.view(np.float16).astype(np.float64)
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def _ulp_size(v, dt):
+    """Spacing of the 16-bit output format near |v| (fp16: 10 fraction bits, bf16: 7)."""
+    frac = 10 if dt == S.F16 else 7
+    a = np.maximum(np.abs(v), 2.0 ** -14 if dt == S.F16 else 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(a)) - frac)
