@@ -36,7 +36,13 @@ namespace gpuos {
 // element conversions (fp16 / bf16 <-> fp32; RNE, denormals kept)
 // ---------------------------------------------------------------------------
 DEV float h2f(uint32_t b) { return (float)__builtin_bit_cast(_Float16, (uint16_t)b); }
-DEV uint32_t f2h(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f); }
+DEV uint32_t f2h(float f) {
+  // The empty asm keeps the fp32 value opaque: without it the compiler folds the producing
+  // multiply / fma and this conversion into one mixed-precision instruction that rounds the
+  // exact result straight to fp16 (one rounding), while the defined result is fp32 first.
+  asm("" : "+v"(f));
+  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
 DEV float b2f(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
 DEV uint32_t f2b(float f) {
   // round-to-nearest-even on the upper 16 bits; NaN stays a (quiet) NaN

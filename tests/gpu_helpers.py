@@ -19,6 +19,9 @@ RED_REL = 1e-5         # fp32 reductions: |g - o| <= 1e-5 * max(|o|, L1 / sqrt(n
 
 class DevicePools:
     def __init__(self, stream, device="cuda:0"):
+        from parity_cases import stream_extent_violations
+        bad = stream_extent_violations(stream)        # never hand the GPU a tensor outside its pool
+        assert not bad, "tasks naming memory outside their pool: %s" % bad[:10]
         self.stream = stream
         self.tensors = []
         for p in stream.pools:
@@ -47,13 +50,14 @@ def run_stream(stream, rt, dp, first=0, count=None, wait=True):
     t0 = None
     i = first
     while i < first + n:
-        m = min(batch, first + n - i)
-        for t in range(i, i + m):
-            if t in swaps and t > first:
-                m = t - i
-                break
         if i in swaps and i > 0:
             rt.swap_op(*swaps[i])
+        m = min(batch, first + n - i)
+        for t in range(i + 1, i + m):               # a batch ends in front of the next scheduled swap
+            if t in swaps:
+                m = t - i
+                break
+        assert m > 0
         tk = rt.submit(dp.tasks, i, m)
         if t0 is None:
             t0 = tk

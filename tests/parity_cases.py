@@ -1,0 +1,253 @@
+"""Stream builders for the parity tests.  Each returns a Stream; the CPU suite checks that every
+tensor a case names lies inside its pool and that the oracle accepts and runs it, the GPU suite
+runs it through the library and compares with the oracle."""
+import numpy as np
+
+from paper_2604_17861_amd import streams as S
+from helpers import Builder
+
+ELEMENTWISE = ["ADD", "SUB", "MUL", "DIV", "RELU", "EXP", "GELU_ERF", "GELU_TANH", "SCALE", "FMA", "SUB_EXP", "COPY"]
+
+
+def to_dtype(v32, code):
+    if code == S.F32:
+        return v32.astype(np.float32)
+    if code == S.F16:
+        with np.errstate(over="ignore"):
+            return v32.astype(np.float16)
+    return (v32.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+def special_values():
+    return np.array([0.0, -0.0, 1.0, -1.0, 0.5, 3.0, -3.0, 6.0, -6.0, 10.0, -10.0, 65504.0, -65504.0, 1e-8, -1e-8,
+                     6e-5, 88.0, -88.0, 100.0, -100.0, np.inf, -np.inf, np.nan, 2049.0, 1.0009766], dtype=np.float32)
+
+
+def stream_extent_violations(stream):
+    """Indices of tasks naming memory outside their pool (host-side bounds check)."""
+    bad = []
+    T = stream.tasks
+    red_ops = {S.OP["SUM_LAST"], S.OP["MAX_LAST"], S.OP["MIN_LAST"]}
+    for i in range(len(T)):
+        nd = int(T["ndim"][i])
+        size = [int(x) for x in T["size"][i][:nd]]
+        if any(s == 0 for s in size):
+            continue
+        for k in range(4):
+            p = int(stream.pool_of[i, k])
+            if p < 0:
+                continue
+            rec = T["inp"][i, k] if k < 3 else T["out"][i]
+            dims = nd - 1 if (k == 3 and int(T["op_id"][i]) in red_ops) else nd
+            es = S.ELEM_SIZE[int(rec["dtype"])]
+            span = 0
+            for d in range(dims):
+                st = 0 if (int(rec["bcast_mask"]) >> d) & 1 else int(rec["stride"][d])
+                span += (size[d] - 1) * st
+            lo = int(rec["ptr"])
+            if lo < 0 or lo + (span + 1) * es > stream.pools[p].nbytes:
+                bad.append(i)
+                break
+    return bad
+
+
+def elementwise_contiguous(code):
+    """All elementwise implementations on contiguous tensors: sizes 1, 7 (scalar tail only), 1000,
+    16384 (exactly one chunk), 40003 (three chunks, ragged vector tail), special values, and an
+    unaligned base pointer (scalar fallback)."""
+    rng = np.random.default_rng(21 + code)
+    b = Builder()
+    for n in (1, 7, 1000, 16384, 40003):
+        vals = rng.standard_normal(n).astype(np.float32) * 2
+        if n > 30:
+            vals[: len(special_values())] = special_values()
+        x = b.pool(to_dtype(vals, code))
+        y = b.pool(to_dtype(rng.standard_normal(n).astype(np.float32), code))
+        z = b.pool(to_dtype(rng.standard_normal(n).astype(np.float32), code))
+        for name in ELEMENTWISE:
+            o = b.pool(np.zeros(n, x.dtype))
+            b.add(name, o, [x, y, z][: S.ARITY[S.IMPL[name]]], alpha=0.37)
+    big = b.pool(to_dtype(rng.standard_normal(5001).astype(np.float32), code))
+    o = b.pool(np.zeros(5001, big.dtype))
+    b.add("MUL", o[1:], [big[1:], big[:-1]])
+    return b.stream("elementwise_contiguous_%d" % code)
+
+
+def all_16bit_patterns(code):
+    """Every 16-bit pattern through each unary implementation, same-dtype and fp32 outputs."""
+    bits = np.arange(65536, dtype=np.uint16)
+    src = bits.view(np.float16) if code == S.F16 else bits
+    b = Builder()
+    X = b.pool(src.copy())
+    for name in ("COPY", "RELU", "SCALE", "EXP", "GELU_ERF", "GELU_TANH"):
+        o = b.pool(np.zeros(65536, src.dtype))
+        b.add(name, o, [X], alpha=-1.7)
+        o32 = b.pool(np.zeros(65536, np.float32))
+        b.add(name, o32, [X], alpha=-1.7)
+    return b.stream("all_16bit_%d" % code)
+
+
+def fp32_transcendental_sweep():
+    rng = np.random.default_rng(5)
+    grids = [np.linspace(-6, 6, 200001), np.linspace(-104, 89, 200001), rng.uniform(-3, 3, 200000),
+             rng.standard_normal(200000), np.linspace(-20, 20, 100001)]
+    b = Builder()
+    for g in grids:
+        x = b.pool(g.astype(np.float32))
+        y = b.pool(rng.standard_normal(len(g)).astype(np.float32))
+        for name in ("EXP", "GELU_ERF", "GELU_TANH", "SUB_EXP"):
+            o = b.pool(np.zeros(len(g), np.float32))
+            b.add(name, o, [x, y][: S.ARITY[S.IMPL[name]]])
+    return b.stream("fp32_transcendental")
+
+
+def random_view(rng, base, shape, p_bcast=0.25):
+    """A random strided / broadcast view of `base` (as_strided), checked to stay inside it."""
+    nd = len(shape)
+    perm = rng.permutation(nd)
+    strides = [0] * nd
+    acc = 1
+    for d in perm:
+        if shape[d] == 1 or rng.random() < p_bcast:
+            continue
+        strides[d] = acc * int(rng.integers(1, 3))
+        acc = strides[d] * shape[d]
+    start = int(rng.integers(0, 4))
+    need = start + sum((shape[d] - 1) * strides[d] for d in range(nd)) + 1
+    assert need <= base.size, (need, base.size)
+    return np.lib.stride_tricks.as_strided(base[start:], shape=shape, strides=[s * base.itemsize for s in strides],
+                                           writeable=False)
+
+
+def random_strided_views(seed):
+    """Random <= 6-D shapes (at most 2^15 elements) with permuted / gapped / broadcast input strides,
+    permuted output layouts and mixed dtypes."""
+    rng = np.random.default_rng(300 + seed)
+    b = Builder()
+    bases = {c: b.pool(to_dtype(rng.standard_normal(1 << 21).astype(np.float32), c)) for c in (S.F32, S.F16, S.BF16)}
+    names = ["ADD", "SUB", "MUL", "DIV", "FMA", "RELU", "SCALE", "COPY", "SUB_EXP", "GELU_TANH"]
+    for _ in range(120):
+        nd = int(rng.integers(1, 7))
+        shape = [int(rng.integers(1, 9)) for _ in range(nd)]
+        while int(np.prod(shape)) > (1 << 15):
+            shape[int(np.argmax(shape))] //= 2
+        name = names[int(rng.integers(len(names)))]
+        ar = S.ARITY[S.IMPL[name]]
+        ins = [random_view(rng, bases[int(rng.integers(3))], shape) for _ in range(ar)]
+        ocode = int(rng.integers(3))
+        obuf = b.pool(np.zeros(int(np.prod(shape)) + 8, bases[ocode].dtype))
+        perm = rng.permutation(nd)
+        st = [0] * nd
+        acc = 1
+        for d in perm:
+            st[d] = acc
+            acc *= shape[d]
+        o = np.lib.stride_tricks.as_strided(obuf[int(rng.integers(0, 4)):], shape=shape,
+                                            strides=[s * obuf.itemsize for s in st])
+        b.add(name, o, ins, alpha=1.25)
+    return b.stream("random_views_%d" % seed)
+
+
+def broadcast_2d():
+    """[R, C] op row vector / column vector / per-row scalar of another dtype, C a multiple of the
+    vector width and not; several chunks."""
+    rng = np.random.default_rng(8)
+    b = Builder()
+    for code in (S.F32, S.F16, S.BF16):
+        for (R_, C_) in ((5, 64), (300, 256), (33, 1000), (130, 520), (7, 77)):
+            a = b.pool(to_dtype(rng.standard_normal((R_, C_)).astype(np.float32), code))
+            row = b.pool(to_dtype(rng.standard_normal(C_).astype(np.float32), code))
+            col = b.pool(to_dtype(rng.standard_normal(R_).astype(np.float32), code))
+            col32 = b.pool(rng.standard_normal(R_).astype(np.float32))
+            for name, ins in (("ADD", [a, np.broadcast_to(row, (R_, C_))]),
+                              ("SUB", [np.broadcast_to(row, (R_, C_)), a]),
+                              ("MUL", [a, np.broadcast_to(col[:, None], (R_, C_))]),
+                              ("SUB_EXP", [a, np.broadcast_to(col32[:, None], (R_, C_))]),
+                              ("DIV", [a, np.broadcast_to(col32[:, None], (R_, C_))]),
+                              ("FMA", [a, np.broadcast_to(row, (R_, C_)), np.broadcast_to(col[:, None], (R_, C_))])):
+                o = b.pool(np.zeros((R_, C_), a.dtype))
+                b.add(name, o, ins)
+    return b.stream("broadcast_2d")
+
+
+def reductions():
+    """SUM / MAX / MIN over the last dim: row lengths from 1 to 20000 (sub-wave rows, one workgroup
+    per row, scalar fallback for odd lengths), all float dtypes, fp32 and same-dtype outputs,
+    strided / transposed inputs, keepdim, NaN and -inf rows."""
+    rng = np.random.default_rng(9)
+    b = Builder()
+    for code in (S.F32, S.F16, S.BF16):
+        for rows, n in ((3, 1), (700, 8), (513, 64), (300, 128), (77, 256), (50, 100), (9, 1000), (5, 4096), (3, 20000),
+                        (2, 16388), (1100, 32)):
+            x32 = rng.uniform(-1, 1, (rows, n)).astype(np.float32)
+            if n >= 64:
+                x32[0, 3] = np.nan
+                x32[1 % rows, :] = -np.inf
+            x = b.pool(to_dtype(x32, code))
+            for name in ("SUM_LAST", "MAX_LAST", "MIN_LAST"):
+                o = b.pool(np.zeros(rows, np.float32)); b.add(name, o, [x])
+                o2 = b.pool(np.zeros(rows, x.dtype)); b.add(name, o2, [x])
+    t = b.pool(rng.standard_normal((37, 50)).astype(np.float32))
+    o = b.pool(np.zeros(50, np.float32)); b.add("SUM_LAST", o, [t.T])
+    g = b.pool(rng.standard_normal((6, 5, 4, 66)).astype(np.float16))
+    o = b.pool(np.zeros((4, 5, 6), np.float32))
+    b.add("MAX_LAST", o.transpose(2, 1, 0), [g[..., ::2]], shape=[6, 5, 4, 33])
+    k = b.pool(np.zeros((9, 1), np.float32))
+    x = b.pool(rng.standard_normal((9, 300)).astype(np.float32))
+    b.add("SUM_LAST", k[:, 0], [x], flags=S.FLAG_KEEPDIM)
+    one = b.pool(np.ones((3, 4097), np.float32)); o1 = b.pool(np.zeros(3, np.float32)); b.add("SUM_LAST", o1, [one])
+    return b.stream("reductions")
+
+
+def int32_ops():
+    rng = np.random.default_rng(10)
+    b = Builder()
+    a = b.pool(rng.integers(-2 ** 31, 2 ** 31 - 1, 50000, dtype=np.int64).astype(np.int32))
+    c = b.pool(rng.integers(-2 ** 31, 2 ** 31 - 1, 50000, dtype=np.int64).astype(np.int32))
+    for name in ("ADD", "SUB", "MUL", "COPY"):
+        ar = S.ARITY[S.IMPL[name]]
+        o = b.pool(np.zeros(50000, np.int32)); b.add(name, o, [a, c][:ar])
+        o = b.pool(np.zeros((100, 250), np.int32))
+        b.add(name, o, [a.reshape(250, 200)[:, ::2].T, np.broadcast_to(c[:250], (100, 250))][:ar])
+    m = a.reshape(100, 500)
+    for name in ("SUM_LAST", "MAX_LAST", "MIN_LAST"):
+        o = b.pool(np.zeros(100, np.int32)); b.add(name, o, [m])
+        o = b.pool(np.zeros(500, np.int32)); b.add(name, o, [m.T])
+    return b.stream("int32")
+
+
+def config2_reduced():
+    return S.config2(n_tasks=2000, in_pool_elems=1 << 21)
+
+
+def config3_reduced():
+    return S.config3(n_chains=12, buffer_sets=1)
+
+
+def config4_reduced():
+    return S.config4(n_tasks=30000, swap_every=2000, window=15000, in_pool_elems=1 << 20)
+
+
+def config5_reduced():
+    return S.config5(n_tasks=300, rows_range=(64, 1024), cols_range=(256, 4096), max_numel=1 << 20,
+                     in_pool_bytes=1 << 28, out_slots=300, tile_elems=1 << 22)
+
+
+CPU_CHECKED = {
+    "elementwise_f32": lambda: elementwise_contiguous(S.F32),
+    "elementwise_f16": lambda: elementwise_contiguous(S.F16),
+    "elementwise_bf16": lambda: elementwise_contiguous(S.BF16),
+    "all_16bit_f16": lambda: all_16bit_patterns(S.F16),
+    "all_16bit_bf16": lambda: all_16bit_patterns(S.BF16),
+    "fp32_transcendental": fp32_transcendental_sweep,
+    "random_views_0": lambda: random_strided_views(0),
+    "random_views_1": lambda: random_strided_views(1),
+    "random_views_2": lambda: random_strided_views(2),
+    "broadcast_2d": broadcast_2d,
+    "reductions": reductions,
+    "int32": int32_ops,
+    "config2_reduced": config2_reduced,
+    "config3_reduced": config3_reduced,
+    "config4_reduced": config4_reduced,
+    "config5_reduced": config5_reduced,
+}

@@ -12,6 +12,7 @@ pytestmark = pytest.mark.gpu
 
 def _run_and_check(stream, capacity=0, **cfg):
     from gpu_helpers import DevicePools, run_stream, compare_with_oracle
+    print("case", stream.name, "tasks", len(stream), flush=True)
     dp = DevicePools(stream)
     with R.Runtime(capacity, idle_exit_ms=20000, wait_timeout_ms=20000, **cfg) as rt:
         rt.register_table(stream.table)
@@ -29,3 +30,77 @@ def test_config1_full_bit_exact():
     stats, comps = _run_and_check(S.config1())
     assert stats["max_ulp"] == 0 and stats["elements"] == 1000 * 1024
     assert np.all(comps["op_version"] == 1)
+
+
+import parity_cases as C
+
+
+@pytest.mark.parametrize("code", [S.F32, S.F16, S.BF16])
+def test_every_elementwise_op_contiguous(code):
+    stats, _ = _run_and_check(C.elementwise_contiguous(code))
+    print(stats, flush=True)
+
+
+@pytest.mark.parametrize("code", [S.F16, S.BF16])
+def test_all_16bit_patterns_through_unary_ops(code):
+    stats, _ = _run_and_check(C.all_16bit_patterns(code))
+    print(stats, flush=True)
+
+
+def test_fp32_transcendental_dense_sweep():
+    stats, _ = _run_and_check(C.fp32_transcendental_sweep())
+    print(stats, flush=True)
+    assert stats["max_ulp"] <= 2
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_strided_broadcast_views(seed):
+    stats, _ = _run_and_check(C.random_strided_views(seed))
+    print(stats, flush=True)
+
+
+def test_row_and_column_broadcast_2d_fast_path():
+    stats, _ = _run_and_check(C.broadcast_2d())
+    print(stats, flush=True)
+
+
+def test_last_dim_reductions():
+    stats, _ = _run_and_check(C.reductions())
+    print(stats, flush=True)
+
+
+def test_int32_ops_bit_exact():
+    stats, _ = _run_and_check(C.int32_ops())
+    print(stats, flush=True)
+
+
+# ---- the five configurations at reduced length ---------------------------------------
+def test_config2_reduced():
+    stats, _ = _run_and_check(C.config2_reduced())
+    print(stats, flush=True)
+
+
+def test_config3_reduced_all_pairs():
+    stats, _ = _run_and_check(C.config3_reduced())
+    print(stats, flush=True)
+
+
+def test_config4_reduced_hot_swap():
+    """Hot swap under load: versions recorded at claim time decide which GELU the oracle evaluates;
+    the version invariants hold for every task."""
+    s = C.config4_reduced()
+    stats, comps = _run_and_check(s)
+    print(stats, flush=True)
+    v = comps["op_version"].astype(np.int64)
+    gelu = s.tasks["op_id"] == S.OP_GELU
+    assert np.all(v[~gelu] == 1)
+    n_swaps = len(s.swaps)
+    assert v[gelu].min() >= 1 and v[gelu].max() <= n_swaps + 1
+    for k, (t, _, _) in enumerate(s.swaps):        # submitted after swap k returned => version >= k + 2
+        assert np.all(v[t:][gelu[t:]] >= k + 2), k
+    assert len(np.unique(v[gelu])) == n_swaps + 1  # every version was actually used
+
+
+def test_config5_reduced():
+    stats, _ = _run_and_check(C.config5_reduced())
+    print(stats, flush=True)

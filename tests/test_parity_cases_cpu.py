@@ -1,0 +1,27 @@
+"""CPU checks of the streams the GPU parity tests submit: every tensor lies inside its pool (no GPU
+run may name memory outside its buffers) and the oracle accepts and runs every task."""
+import numpy as np
+import pytest
+
+import oracle
+import parity_cases as C
+from helpers import HostPools
+
+
+@pytest.mark.parametrize("name", sorted(C.CPU_CHECKED))
+def test_case_is_in_bounds_and_valid(name):
+    s = C.CPU_CHECKED[name]()
+    assert C.stream_extent_violations(s) == []
+    hp = HostPools(s)
+    impl = s.impl_for()
+    bad = [i for i in range(len(s)) if oracle.validate(hp.tasks, i, impl[i]) != 0]
+    assert bad == []
+    if name not in ("config3_reduced", "config5_reduced"):      # these two take long on the CPU; the GPU suite runs them
+        st = oracle.run_stream(hp.tasks, impl)
+        assert np.all(st == 0)
+
+
+def test_extent_check_catches_a_view_past_its_pool():
+    s = C.config2_reduced()
+    s.tasks["inp"]["ptr"][5, 0] = s.pools[int(s.pool_of[5, 0])].nbytes - 8
+    assert C.stream_extent_violations(s) == [5]
