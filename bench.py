@@ -1,0 +1,270 @@
+#!/usr/bin/env python3
+"""Benchmark of the GPUOS hot path on one MI355X.
+
+A step is one pass of the whole hot path (descriptor packing, ring submission, persistent-kernel
+dispatch, execution, completion harvesting) over the second configuration's stream: 10,000 mixed
+elementwise tasks submitted in batches of 64.  `value` is persistent-queue tasks/s on that stream
+with all tensors resident in HBM.  The same JSON line carries
+  * the same stream issued as one ordinary kernel launch per task (throughput and latency mode),
+  * p50 / p99 submit->done latency of the persistent path (loaded, and unloaded ping-pong),
+  * the other small-op streams (first and fourth configuration) against per-op launches,
+  * "roofline": the persistent kernel over the fifth configuration (bandwidth stream): algorithmic
+    bytes / kernel duration from HIP events on the worker's stream, against 8 TB/s,
+  * "cpu_baseline": the CPU oracle timed on a bounded sample of the same stream on one host core.
+Inputs are seeded and synthetic (paper_2604_17861_amd/streams.py).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class DevicePools:
+    """Pools of a stream in device memory (torch only allocates and copies)."""
+
+    def __init__(self, stream, torch, device="cuda:0"):
+        self.tensors = []
+        for p in stream.pools:
+            if p.tile is not None:
+                t = torch.from_numpy(np.ascontiguousarray(p.tile)).to(device)
+                reps = -(-p.nbytes // p.tile.nbytes)
+                t = t.repeat(reps)[: p.nbytes].contiguous()
+            elif p.data is not None:
+                t = torch.from_numpy(np.ascontiguousarray(p.data)).to(device)
+            else:
+                t = torch.zeros(p.nbytes, dtype=torch.uint8, device=device)
+            self.tensors.append(t)
+        torch.cuda.current_stream().synchronize()
+        self.bases = [t.data_ptr() for t in self.tensors]
+        self.tasks = stream.materialize(self.bases)
+
+
+def submit_pass(rt, stream, tasks):
+    """One pass over the stream: batches of stream.batch, hot swaps where scheduled, then wait."""
+    n = len(tasks)
+    batch = stream.batch or n
+    swaps = {t: (op, impl) for t, op, impl in stream.swaps}
+    i = 0
+    first = None
+    while i < n:
+        if i in swaps and i > 0:
+            rt.swap_op(*swaps[i])
+        m = min(batch, n - i)
+        if swaps:
+            for t in range(i + 1, i + m):
+                if t in swaps:
+                    m = t - i
+                    break
+        tk = rt.submit(tasks, i, m)
+        if first is None:
+            first = tk
+        i += m
+    rt.wait()
+    return first
+
+
+def percentile_us(ns, q):
+    return float(np.percentile(ns, q)) / 1e3 if len(ns) else None
+
+
+def bench_persistent(R, stream, dp, steps, warmup, harvester=True, capacity=0):
+    with R.Runtime(capacity, harvester_thread=1 if harvester else 0, idle_exit_ms=60000,
+                   completion_log=max(1 << 20, 1 << int(np.ceil(np.log2(len(stream) + 1))))) as rt:
+        rt.register_table(stream.table)
+        for _ in range(warmup):
+            submit_pass(rt, stream, dp.tasks)
+            _reset_swaps(rt, stream)
+        lat = []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            first = submit_pass(rt, stream, dp.tasks)
+            _reset_swaps(rt, stream)
+            if len(stream) <= (1 << 20):
+                c = rt.completions(first, len(stream))
+                lat.append((c["t_done_ns"] - c["t_submit_ns"]).astype(np.int64))
+        dt = time.perf_counter() - t0
+        q = rt.peek_queue()
+        wg = q.workgroups
+    lat = np.concatenate(lat) if lat else np.zeros(0, np.int64)
+    return dict(tasks_per_s=steps * len(stream) / dt, seconds=dt, p50_us=percentile_us(lat, 50),
+                p99_us=percentile_us(lat, 99), workgroups=wg)
+
+
+def _reset_swaps(rt, stream):
+    """After a pass with an odd number of swaps put the table back to its initial binding."""
+    if stream.swaps and len(stream.swaps) % 2 == 1:
+        op = stream.swaps[0][1]
+        rt.swap_op(op, stream.table[op])
+
+
+def bench_pingpong(R, stream, dp, n=5000):
+    with R.Runtime(0, idle_exit_ms=60000) as rt:
+        rt.register_table(stream.table)
+        for i in range(200):
+            rt.submit(dp.tasks, i % len(stream), 1)
+            rt.wait()
+        lat = np.zeros(n)
+        for i in range(n):
+            k = i % len(stream)
+            t0 = time.perf_counter_ns()
+            rt.submit(dp.tasks, k, 1)
+            rt.wait()
+            lat[i] = time.perf_counter_ns() - t0
+    return percentile_us(lat, 50), percentile_us(lat, 99)
+
+
+def bench_roofline(R, stream, dp, impls):
+    """The persistent kernel alone over the bandwidth stream: one worker lifetime that holds
+    nothing but this stream, timed by HIP events on the worker's own stream."""
+    nbytes = int(R.task_bytes(dp.tasks, impls).sum())
+    with R.Runtime(0, idle_exit_ms=60000) as rt:
+        rt.register_table(stream.table)
+        t0 = time.perf_counter()
+        submit_pass(rt, stream, dp.tasks)
+        wall = time.perf_counter() - t0
+        rt.stop_worker()
+        kernel_ms = rt.worker_elapsed_ms()
+        wg = rt.peek_queue().workgroups
+    return dict(bytes=nbytes, wall_s=wall, kernel_ms=kernel_ms, workgroups=wg)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--skip-extras", action="store_true", help="only the headline stream and the roofline leg")
+    ap.add_argument("--cfg5-tasks", type=int, default=20000)
+    ap.add_argument("--cfg4-tasks", type=int, default=1000000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU (one ring, one persistent kernel and one operator table "
+                 "per GPU; there is no multi-GPU path to measure). Use --gpus 1.")
+
+    import torch
+    from paper_2604_17861_amd import runtime as R
+    from paper_2604_17861_amd import streams as S
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (the HIP path has no CPU fallback)")
+    R.lib()
+    prop = torch.cuda.get_device_properties(0)
+    log("device:", prop.name, "CUs:", prop.multi_processor_count, "mem GiB: %.0f" % (prop.total_memory / 2 ** 30))
+    log("host cores:", os.cpu_count(), "affinity:", len(os.sched_getaffinity(0)))
+
+    out = {}
+    # ---- headline: second configuration --------------------------------------------------
+    s2 = S.config2()
+    dp2 = DevicePools(s2, torch)
+    res = bench_persistent(R, s2, dp2, args.steps, args.warmup)
+    log("config2 persistent:", res)
+    secs, _ = R.launch_per_op(dp2.tasks, s2.table)                       # warm-up pass
+    t0 = time.perf_counter()
+    for _ in range(max(1, args.steps // 4)):
+        secs, _ = R.launch_per_op(dp2.tasks, s2.table)
+    per_launch_tps = max(1, args.steps // 4) * len(s2) / (time.perf_counter() - t0)
+    _, lat = R.launch_per_op(dp2.tasks, s2.table, sync_each=True, count=3000)
+    log("config2 per-launch: %.0f tasks/s, p50 %.1f us" % (per_launch_tps, percentile_us(lat, 50)))
+    out.update(value=res["tasks_per_s"], ms_per_step=1e3 * res["seconds"] / args.steps,
+               per_launch_tasks_per_s=per_launch_tps, speedup_vs_per_launch=res["tasks_per_s"] / per_launch_tps,
+               p50_us=res["p50_us"], p99_us=res["p99_us"],
+               per_launch_p50_us=percentile_us(lat, 50), per_launch_p99_us=percentile_us(lat, 99),
+               workgroups=res["workgroups"])
+
+    extras = {}
+    if not args.skip_extras:
+        # ---- unloaded latency: one task at a time ---------------------------------------
+        s1 = S.config1()
+        dp1 = DevicePools(s1, torch)
+        p50, p99 = bench_pingpong(R, s1, dp1)
+        _, lat1 = R.launch_per_op(dp1.tasks, s1.table, sync_each=True)
+        extras["pingpong"] = dict(persistent_p50_us=p50, persistent_p99_us=p99,
+                                  per_launch_p50_us=percentile_us(lat1, 50), per_launch_p99_us=percentile_us(lat1, 99))
+        log("pingpong:", extras["pingpong"])
+        # ---- first configuration ----------------------------------------------------------
+        r1 = bench_persistent(R, s1, dp1, max(20, args.steps), args.warmup)
+        R.launch_per_op(dp1.tasks, s1.table)
+        t0 = time.perf_counter()
+        for _ in range(10):
+            R.launch_per_op(dp1.tasks, s1.table)
+        pl1 = 10 * len(s1) / (time.perf_counter() - t0)
+        extras["config1"] = dict(persistent_tasks_per_s=r1["tasks_per_s"], per_launch_tasks_per_s=pl1,
+                                 speedup=r1["tasks_per_s"] / pl1, p50_us=r1["p50_us"], p99_us=r1["p99_us"])
+        log("config1:", extras["config1"])
+        del dp1
+        # ---- fourth configuration (hot swaps while running) -----------------------------------
+        s4 = S.config4(n_tasks=args.cfg4_tasks)
+        dp4 = DevicePools(s4, torch)
+        r4 = bench_persistent(R, s4, dp4, 1, 0)
+        t0 = time.perf_counter()
+        R.launch_per_op(dp4.tasks, s4.table, count=min(len(s4), 200000))
+        pl4 = min(len(s4), 200000) / (time.perf_counter() - t0)
+        extras["config4"] = dict(persistent_tasks_per_s=r4["tasks_per_s"], per_launch_tasks_per_s=pl4,
+                                 speedup=r4["tasks_per_s"] / pl4, swaps=len(s4.swaps), tasks=len(s4),
+                                 p50_us=r4["p50_us"], p99_us=r4["p99_us"])
+        log("config4:", extras["config4"])
+        del dp4
+    del dp2
+
+    # ---- roofline: fifth configuration through the persistent kernel ---------------------------
+    s5 = S.config5(n_tasks=args.cfg5_tasks)
+    dp5 = DevicePools(s5, torch)
+    impl5 = s5.impl_for()
+    rf = bench_roofline(R, s5, dp5, impl5)
+    achieved = rf["bytes"] / (rf["kernel_ms"] * 1e-3) / 1e9
+    log("config5 roofline:", rf, "-> %.1f GB/s by kernel time, %.1f GB/s by wall" % (achieved, rf["bytes"] / rf["wall_s"] / 1e9))
+    t0 = time.perf_counter()
+    R.launch_per_op(dp5.tasks, s5.table, count=min(len(s5), 4000))
+    pl5 = sum(R.task_bytes(dp5.tasks[: min(len(s5), 4000)], impl5)) / (time.perf_counter() - t0) / 1e9
+    extras["config5"] = dict(persistent_gbps_wall=rf["bytes"] / rf["wall_s"] / 1e9, per_launch_gbps=float(pl5),
+                             tasks=len(s5), tasks_per_s=len(s5) / rf["wall_s"])
+    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
+                    traffic=None, kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"],
+                    algorithmic_bytes=rf["bytes"], workload="config5: %d bandwidth tasks" % len(s5))
+    del dp5
+
+    # ---- CPU oracle on a bounded sample of the headline stream (one core) ------------------------
+    import oracle
+    sample = np.arange(0, len(s2), 4)
+    host_arrays = [np.array(p.host_image(), dtype=np.uint8, copy=True) for p in s2.pools]
+    hp_tasks = s2.materialize([a.ctypes.data for a in host_arrays])
+    impl2 = s2.impl_for()
+    t0 = time.perf_counter()
+    L = oracle.lib()
+    for i in sample:
+        L.orc_run_task(hp_tasks.ctypes.data + int(i) * hp_tasks.dtype.itemsize, int(impl2[i]), 0)
+    cpu_s = time.perf_counter() - t0
+    cpu_baseline = dict(value=len(sample) / cpu_s, unit="tasks/s", cores=1, kind="oracle",
+                        sample="every 4th task of the second configuration's 10,000-task stream (%d tasks, %.1f s)" % (
+                            len(sample), cpu_s))
+    log("cpu oracle:", cpu_baseline)
+
+    line = dict(metric="small-op tasks/sec and p50 submit->done latency vs per-op launch; HBM GB/s",
+                value=out["value"], unit="tasks/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+                ms_per_step=out["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
+                dtype="f32", data="synthetic",
+                config=dict(workload="config2: 10,000 mixed elementwise tasks (fp32/fp16/bf16 50/25/25, numel "
+                                     "log-uniform 256..65536, 30% strided inputs, 20% broadcast), batches of 64",
+                            queue_capacity=4096, workgroups=out["workgroups"]),
+                per_launch_tasks_per_s=out["per_launch_tasks_per_s"],
+                speedup_vs_per_launch=out["speedup_vs_per_launch"],
+                p50_us=out["p50_us"], p99_us=out["p99_us"], per_launch_p50_us=out["per_launch_p50_us"],
+                per_launch_p99_us=out["per_launch_p99_us"], extras=extras,
+                roofline=roofline, cpu_baseline=cpu_baseline)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

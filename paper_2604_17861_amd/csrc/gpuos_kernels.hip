@@ -33,6 +33,64 @@ namespace gpuos {
 #define DEV __device__ __forceinline__
 
 // ---------------------------------------------------------------------------
+// memory access policy
+//
+// The persistent kernel never reaches a kernel boundary, and the 8 XCDs have
+// one L2 each that are not coherent with each other for ordinary accesses.
+// Agent-scope acquire / release fences would make a task's data visible, but
+// they write back / invalidate a whole L2 on every chunk, which costs more than
+// half of the HBM bandwidth when a thousand workgroups do it.  Instead every
+// access to task data, descriptors and work units made by the persistent
+// kernel carries the system-scope cache policy (sc0 sc1: stores write through
+// to memory, loads do not hit stale lines), plus nt on the 16-byte streaming
+// accesses.  With that, "release" is: wait until this wave's stores are
+// acknowledged (s_waitcnt), then publish with a relaxed atomic store; "acquire"
+// is: observe the flag with a relaxed atomic load, then read with the same
+// policy.  No L2-wide maintenance happens in the steady state.
+//
+// 16-byte accesses go through buffer instructions whose resource is rebased to
+// the chunk being processed: the hardware bounds-checks them (out-of-range
+// loads return 0, stores are dropped).  The ordinary one-launch-per-task kernel
+// uses POL_PLAIN (non-temporal, kernel-boundary coherence as for any kernel).
+// ---------------------------------------------------------------------------
+enum { POL_PLAIN = 0, POL_COHERENT = 1 };
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+DEV rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+template <int POL> struct Mem {
+  static constexpr int AUX = POL == POL_COHERENT ? 19 : 2;     // sc0|sc1|nt  or  nt
+  static DEV v4i ld16(rsrc_t r, uint32_t off) { return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, AUX); }
+  static DEV void st16(rsrc_t r, uint32_t off, v4i q) { __builtin_amdgcn_raw_buffer_store_b128(q, r, (int)off, 0, AUX); }
+  static DEV uint32_t ld4(const void* p, uint32_t i) {
+    if (POL == POL_COHERENT) return __hip_atomic_load((const uint32_t*)p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    return ((const uint32_t*)p)[i];
+  }
+  static DEV uint32_t ld2(const void* p, uint32_t i) {
+    if (POL == POL_COHERENT) return __hip_atomic_load((const uint16_t*)p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    return ((const uint16_t*)p)[i];
+  }
+  static DEV void st4(void* p, uint32_t i, uint32_t v) {
+    if (POL == POL_COHERENT) __hip_atomic_store((uint32_t*)p + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    else ((uint32_t*)p)[i] = v;
+  }
+  static DEV void st2(void* p, uint32_t i, uint32_t v) {
+    if (POL == POL_COHERENT) __hip_atomic_store((uint16_t*)p + i, (uint16_t)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    else ((uint16_t*)p)[i] = (uint16_t)v;
+  }
+};
+
+// This wave's stores (all write-through) have been acknowledged when this returns.
+DEV void drain_stores() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // keeps the compiler from moving stores below
+  __builtin_amdgcn_s_waitcnt(0);                           // vmcnt = expcnt = lgkmcnt = 0
+}
+DEV void order_loads() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
+
+// ---------------------------------------------------------------------------
 // element conversions (fp16 / bf16 <-> fp32; RNE, denormals kept)
 // ---------------------------------------------------------------------------
 DEV float h2f(uint32_t b) { return (float)__builtin_bit_cast(_Float16, (uint16_t)b); }
@@ -54,41 +112,47 @@ DEV uint32_t f2b(float f) {
 template <int DT> struct Elem;
 template <> struct Elem<GPUOS_F32> {
   static constexpr int V = 4, ES = 4;
-  static DEV float get(const uint4& q, int k) { return __builtin_bit_cast(float, (&q.x)[k]); }
-  static DEV void put(uint4& q, int k, float f) { (&q.x)[k] = __builtin_bit_cast(uint32_t, f); }
-  static DEV float load1(const void* p, uint32_t i) { return ((const float*)p)[i]; }
-  static DEV void store1(void* p, uint32_t i, float f) { ((float*)p)[i] = f; }
+  static DEV float get(const v4i& q, int k) {
+    const int w = q[k];      // read the lane into a scalar first: bit-casting the element lvalue directly reads lane 0
+    return __builtin_bit_cast(float, w);
+  }
+  static DEV void put(v4i& q, int k, float f) { q[k] = __builtin_bit_cast(int, f); }
+  template <int POL> static DEV float load1(const void* p, uint32_t i) { return __builtin_bit_cast(float, Mem<POL>::ld4(p, i)); }
+  template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st4(p, i, __builtin_bit_cast(uint32_t, f)); }
+  template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st4(o, i, Mem<POL>::ld4(a, i)); }
 };
 template <> struct Elem<GPUOS_F16> {
   static constexpr int V = 8, ES = 2;
-  static DEV float get(const uint4& q, int k) { return h2f(((&q.x)[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
-  static DEV void put(uint4& q, int k, float f) {
-    uint32_t& w = (&q.x)[k >> 1];
-    w = (k & 1) ? ((w & 0xffffu) | (f2h(f) << 16)) : ((w & 0xffff0000u) | f2h(f));
+  static DEV float get(const v4i& q, int k) { return h2f(((uint32_t)q[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
+  static DEV void put(v4i& q, int k, float f) {
+    const uint32_t w = (uint32_t)q[k >> 1];
+    q[k >> 1] = (int)((k & 1) ? ((w & 0xffffu) | (f2h(f) << 16)) : ((w & 0xffff0000u) | f2h(f)));
   }
-  static DEV float load1(const void* p, uint32_t i) { return h2f(((const uint16_t*)p)[i]); }
-  static DEV void store1(void* p, uint32_t i, float f) { ((uint16_t*)p)[i] = (uint16_t)f2h(f); }
+  template <int POL> static DEV float load1(const void* p, uint32_t i) { return h2f(Mem<POL>::ld2(p, i)); }
+  template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st2(p, i, f2h(f)); }
+  template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st2(o, i, Mem<POL>::ld2(a, i)); }
 };
 template <> struct Elem<GPUOS_BF16> {
   static constexpr int V = 8, ES = 2;
-  static DEV float get(const uint4& q, int k) { return b2f(((&q.x)[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
-  static DEV void put(uint4& q, int k, float f) {
-    uint32_t& w = (&q.x)[k >> 1];
-    w = (k & 1) ? ((w & 0xffffu) | (f2b(f) << 16)) : ((w & 0xffff0000u) | f2b(f));
+  static DEV float get(const v4i& q, int k) { return b2f(((uint32_t)q[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
+  static DEV void put(v4i& q, int k, float f) {
+    const uint32_t w = (uint32_t)q[k >> 1];
+    q[k >> 1] = (int)((k & 1) ? ((w & 0xffffu) | (f2b(f) << 16)) : ((w & 0xffff0000u) | f2b(f)));
   }
-  static DEV float load1(const void* p, uint32_t i) { return b2f(((const uint16_t*)p)[i]); }
-  static DEV void store1(void* p, uint32_t i, float f) { ((uint16_t*)p)[i] = (uint16_t)f2b(f); }
+  template <int POL> static DEV float load1(const void* p, uint32_t i) { return b2f(Mem<POL>::ld2(p, i)); }
+  template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st2(p, i, f2b(f)); }
+  template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st2(o, i, Mem<POL>::ld2(a, i)); }
 };
 
-DEV float load_rt(const void* p, uint32_t i, uint32_t dt) {   // runtime dtype
-  if (dt == GPUOS_F32) return ((const float*)p)[i];
-  if (dt == GPUOS_F16) return h2f(((const uint16_t*)p)[i]);
-  return b2f(((const uint16_t*)p)[i]);
+template <int POL> DEV float load_rt(const void* p, uint32_t i, uint32_t dt) {   // runtime dtype
+  if (dt == GPUOS_F32) return __builtin_bit_cast(float, Mem<POL>::ld4(p, i));
+  if (dt == GPUOS_F16) return h2f(Mem<POL>::ld2(p, i));
+  return b2f(Mem<POL>::ld2(p, i));
 }
-DEV void store_rt(void* p, uint32_t i, uint32_t dt, float f) {
-  if (dt == GPUOS_F32) ((float*)p)[i] = f;
-  else if (dt == GPUOS_F16) ((uint16_t*)p)[i] = (uint16_t)f2h(f);
-  else ((uint16_t*)p)[i] = (uint16_t)f2b(f);
+template <int POL> DEV void store_rt(void* p, uint32_t i, uint32_t dt, float f) {
+  if (dt == GPUOS_F32) Mem<POL>::st4(p, i, __builtin_bit_cast(uint32_t, f));
+  else if (dt == GPUOS_F16) Mem<POL>::st2(p, i, f2h(f));
+  else Mem<POL>::st2(p, i, f2b(f));
 }
 
 // ---------------------------------------------------------------------------
@@ -142,9 +206,10 @@ DEV const char* uni_ptr(uint64_t p) {
 // PATH_CONTIG: out[i] = f(a[i], b[i], c[i]), all operands the same dtype.
 // 16 bytes per lane per access, four accesses in flight per operand.
 // ---------------------------------------------------------------------------
-template <int IMPL, int DT>
+template <int POL, int IMPL, int DT>
 DEV void ew_contig(const Record* r, uint32_t begin, uint32_t end) {
   using E = Elem<DT>;
+  using M = Mem<POL>;
   constexpr int V = E::V, N = Op<IMPL>::N, U = 4;
   const char* pa = uni_ptr(r->ptr[0]);
   const char* pb = N > 1 ? uni_ptr(r->ptr[1]) : pa;
@@ -153,61 +218,63 @@ DEV void ew_contig(const Record* r, uint32_t begin, uint32_t end) {
   const float alpha = r->alpha;
   const uint32_t tid = threadIdx.x;
   if (r->rflags & RF_VEC) {
-    const uint32_t v0 = begin / V, v1 = end / V;      // begin is a multiple of V
-    const uint4* a = (const uint4*)pa; const uint4* b = (const uint4*)pb; const uint4* c = (const uint4*)pc;
-    uint4* o = (uint4*)po;
-    uint32_t v = v0 + tid;
-    for (; v + (U - 1) * kThreads < v1; v += U * kThreads) {
-      uint4 qa[U], qb[U], qc[U];
+    // buffer resources rebased to this chunk; begin is a multiple of V
+    const uint32_t nvec = (end - begin) / V;
+    const uint32_t bytes = nvec * 16u;
+    const uint64_t boff = (uint64_t)begin * E::ES;
+    const rsrc_t ra = make_rsrc(pa + boff, bytes), rb = make_rsrc(pb + boff, bytes), rc = make_rsrc(pc + boff, bytes);
+    const rsrc_t ro = make_rsrc(po + boff, bytes);
+    uint32_t v = tid;
+    for (; v + (U - 1) * kThreads < nvec; v += U * kThreads) {
+      v4i qa[U], qb[U], qc[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        qa[u] = a[v + u * kThreads];
-        if (N > 1) qb[u] = b[v + u * kThreads];
-        if (N > 2) qc[u] = c[v + u * kThreads];
+        qa[u] = M::ld16(ra, (v + u * kThreads) * 16u);
+        if (N > 1) qb[u] = M::ld16(rb, (v + u * kThreads) * 16u);
+        if (N > 2) qc[u] = M::ld16(rc, (v + u * kThreads) * 16u);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        uint4 q;
+        v4i q;
         if (IMPL == GPUOS_IMPL_COPY) q = qa[u];
         else {
 #pragma unroll
           for (int k = 0; k < V; ++k)
             E::put(q, k, Op<IMPL>::f(E::get(qa[u], k), N > 1 ? E::get(qb[u], k) : 0.f, N > 2 ? E::get(qc[u], k) : 0.f, alpha));
         }
-        o[v + u * kThreads] = q;
+        M::st16(ro, (v + u * kThreads) * 16u, q);
       }
     }
-    for (; v < v1; v += kThreads) {
-      const uint4 qa = a[v];
-      uint4 qb, qc, q;
-      if (N > 1) qb = b[v];
-      if (N > 2) qc = c[v];
+    for (; v < nvec; v += kThreads) {
+      const v4i qa = M::ld16(ra, v * 16u);
+      v4i qb, qc, q;
+      if (N > 1) qb = M::ld16(rb, v * 16u);
+      if (N > 2) qc = M::ld16(rc, v * 16u);
       if (IMPL == GPUOS_IMPL_COPY) q = qa;
       else {
 #pragma unroll
         for (int k = 0; k < V; ++k)
           E::put(q, k, Op<IMPL>::f(E::get(qa, k), N > 1 ? E::get(qb, k) : 0.f, N > 2 ? E::get(qc, k) : 0.f, alpha));
       }
-      o[v] = q;
+      M::st16(ro, v * 16u, q);
     }
-    begin = v1 * V;                                   // ragged tail below
+    begin += nvec * V;                                // ragged tail below
   }
   for (uint32_t i = begin + tid; i < end; i += kThreads) {
-    if (IMPL == GPUOS_IMPL_COPY) {
-      if (E::ES == 4) ((uint32_t*)po)[i] = ((const uint32_t*)pa)[i];
-      else ((uint16_t*)po)[i] = ((const uint16_t*)pa)[i];
-    } else {
-      E::store1(po, i, Op<IMPL>::f(E::load1(pa, i), N > 1 ? E::load1(pb, i) : 0.f, N > 2 ? E::load1(pc, i) : 0.f, alpha));
-    }
+    if (IMPL == GPUOS_IMPL_COPY) E::template copy1<POL>(po, pa, i);
+    else
+      E::template store1<POL>(po, i, Op<IMPL>::f(E::template load1<POL>(pa, i), N > 1 ? E::template load1<POL>(pb, i) : 0.f,
+                                                 N > 2 ? E::template load1<POL>(pc, i) : 0.f, alpha));
   }
 }
 
-template <int IMPL>
+template <int POL, int IMPL>
 DEV void ew_contig_int(const Record* r, uint32_t begin, uint32_t end) {
-  const uint32_t* a = (const uint32_t*)uni_ptr(r->ptr[0]);
-  const uint32_t* b = r->n_inputs > 1 ? (const uint32_t*)uni_ptr(r->ptr[1]) : a;
-  uint32_t* o = (uint32_t*)uni_ptr(r->ptr[3]);
-  for (uint32_t i = begin + threadIdx.x; i < end; i += kThreads) o[i] = int_op<IMPL>(a[i], b[i]);
+  const char* a = uni_ptr(r->ptr[0]);
+  const char* b = r->n_inputs > 1 ? uni_ptr(r->ptr[1]) : a;
+  char* o = (char*)uni_ptr(r->ptr[3]);
+  for (uint32_t i = begin + threadIdx.x; i < end; i += kThreads)
+    Mem<POL>::st4(o, i, int_op<IMPL>(Mem<POL>::ld4(a, i), Mem<POL>::ld4(b, i)));
 }
 
 // ---------------------------------------------------------------------------
@@ -215,35 +282,41 @@ DEV void ew_contig_int(const Record* r, uint32_t begin, uint32_t end) {
 // width; each input is a full [R, C] tensor (dtype DT), a row vector [C]
 // broadcast over rows (dtype DT), or one scalar per row (any float dtype).
 // ---------------------------------------------------------------------------
-template <int IMPL, int DT>
+template <int POL, int IMPL, int DT>
 DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
   using E = Elem<DT>;
+  using M = Mem<POL>;
   constexpr int V = E::V, N = Op<IMPL>::N;
   const uint32_t C = uni(r->size[1]);
   const char* p[3];
   uint32_t kind[3], dt[3], st0[3];
+  rsrc_t rs[3];
+  const uint32_t nvec = (end - begin) / V;
+  const uint64_t boff = (uint64_t)begin * E::ES;
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
-    p[k] = uni_ptr(r->ptr[k < N ? k : 0]);
-    kind[k] = uni(r->okind[k < N ? k : 0]);
-    dt[k] = uni(r->dtype[k < N ? k : 0]);
-    st0[k] = uni(r->stride[k < N ? k : 0][0]);
+    const int kk = k < N ? k : 0;
+    p[k] = uni_ptr(r->ptr[kk]);
+    kind[k] = uni(r->okind[kk]);
+    dt[k] = uni(r->dtype[kk]);
+    st0[k] = uni(r->stride[kk][0]);
+    // full operands: rebased to the chunk; row vectors: the whole vector
+    rs[k] = kind[k] == K_FULL ? make_rsrc(p[k] + boff, nvec * 16u) : make_rsrc(p[k], C * E::ES);
   }
-  uint4* o = (uint4*)uni_ptr(r->ptr[3]);
+  const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + boff, nvec * 16u);
   const float alpha = r->alpha;
-  const uint32_t v1 = end / V;
-  for (uint32_t v = begin / V + threadIdx.x; v < v1; v += kThreads) {
-    const uint32_t i = v * V;
+  for (uint32_t v = threadIdx.x; v < nvec; v += kThreads) {
+    const uint32_t i = begin + v * V;
     const uint32_t row = i / C, col = i - row * C;
-    uint4 q[3];
+    v4i q[3];
     float s[3];
 #pragma unroll
     for (int k = 0; k < N; ++k) {
-      if (kind[k] == K_FULL) q[k] = ((const uint4*)p[k])[v];
-      else if (kind[k] == K_ROWVEC) q[k] = ((const uint4*)p[k])[col / V];
-      else s[k] = load_rt(p[k], row * st0[k], dt[k]);
+      if (kind[k] == K_FULL) q[k] = M::ld16(rs[k], v * 16u);
+      else if (kind[k] == K_ROWVEC) q[k] = M::ld16(rs[k], col * E::ES);
+      else s[k] = load_rt<POL>(p[k], row * st0[k], dt[k]);
     }
-    uint4 res;
+    v4i res;
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       float x[3] = {0.f, 0.f, 0.f};
@@ -251,7 +324,7 @@ DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
       for (int k = 0; k < N; ++k) x[k] = (kind[k] == K_ROWSCALAR) ? s[k] : E::get(q[k], e);
       E::put(res, e, Op<IMPL>::f(x[0], x[1], x[2], alpha));
     }
-    o[v] = res;
+    M::st16(ro, v * 16u, res);
   }
 }
 
@@ -259,8 +332,9 @@ DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
 // PATH_GENERIC: row-major index decomposition over <= 6 coalesced dims, per
 // operand strides (0 on broadcast dims), per operand dtype.
 // ---------------------------------------------------------------------------
-template <int IMPL, bool INT>
+template <int POL, int IMPL, bool INT>
 DEV void ew_generic(const Record* r, uint32_t begin, uint32_t end) {
+  using M = Mem<POL>;
   constexpr int N = INT ? 2 : Op<IMPL>::N;
   const int nd = (int)uni(r->ndim);
   const int nin = (int)uni(r->n_inputs);
@@ -291,17 +365,17 @@ DEV void ew_generic(const Record* r, uint32_t begin, uint32_t end) {
       }
     }
     if (INT) {
-      const uint32_t x = ((const uint32_t*)p[0])[off[0]];
-      const uint32_t y = nin > 1 ? ((const uint32_t*)p[1])[off[1]] : 0u;
-      ((uint32_t*)po)[off[3]] = int_op<IMPL>(x, y);
+      const uint32_t x = M::ld4(p[0], off[0]);
+      const uint32_t y = nin > 1 ? M::ld4(p[1], off[1]) : 0u;
+      M::st4(po, off[3], int_op<IMPL>(x, y));
     } else if (IMPL == GPUOS_IMPL_COPY && dt[0] == dt[3]) {
-      if (dt[0] == GPUOS_F32) ((uint32_t*)po)[off[3]] = ((const uint32_t*)p[0])[off[0]];
-      else ((uint16_t*)po)[off[3]] = ((const uint16_t*)p[0])[off[0]];
+      if (dt[0] == GPUOS_F32) M::st4(po, off[3], M::ld4(p[0], off[0]));
+      else M::st2(po, off[3], M::ld2(p[0], off[0]));
     } else {
-      const float x = load_rt(p[0], off[0], dt[0]);
-      const float y = N > 1 ? load_rt(p[1], off[1], dt[1]) : 0.f;
-      const float z = N > 2 ? load_rt(p[2], off[2], dt[2]) : 0.f;
-      store_rt(po, off[3], dt[3], Op<IMPL>::f(x, y, z, alpha));
+      const float x = load_rt<POL>(p[0], off[0], dt[0]);
+      const float y = N > 1 ? load_rt<POL>(p[1], off[1], dt[1]) : 0.f;
+      const float z = N > 2 ? load_rt<POL>(p[2], off[2], dt[2]) : 0.f;
+      store_rt<POL>(po, off[3], dt[3], Op<IMPL>::f(x, y, z, alpha));
     }
   }
 }
@@ -344,9 +418,10 @@ template <int RIMPL> DEV int32_t wave_reduce_i(int32_t acc, uint32_t width) {
 
 // PATH_RED_CONTIG: input is a contiguous [rows, n] matrix of dtype DT, output a
 // contiguous vector [rows] of any float dtype.
-template <int RIMPL, int DT>
+template <int POL, int RIMPL, int DT>
 DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_red) {
   using E = Elem<DT>;
+  using M = Mem<POL>;
   constexpr int V = E::V;
   const uint32_t n = uni(r->red_n);
   const char* pin = uni_ptr(r->ptr[0]);
@@ -355,6 +430,8 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   const bool vec = (r->rflags & RF_VEC) != 0;
   const uint32_t L = n / V;                           // vectors per row when vec
+  // the rows of this chunk as one buffer (the host keeps a chunk below 2 GiB)
+  const rsrc_t rin = make_rsrc(pin + (uint64_t)row_begin * n * E::ES, (row_end - row_begin) * n * E::ES);
   if (vec && L <= 64u) {
     // several rows per wave pass: P = lanes per row (power of two >= L)
     uint32_t P = 1;
@@ -365,12 +442,12 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
       const uint32_t row = base + wave * rpw + sub;
       float acc = red_identity<RIMPL>();
       if (row < row_end && j < L) {
-        const uint4 q = ((const uint4*)pin)[(uint64_t)row * L + j];
+        const v4i q = M::ld16(rin, ((row - row_begin) * L + j) * 16u);
 #pragma unroll
         for (int k = 0; k < V; ++k) acc = red_combine<RIMPL>(acc, E::get(q, k));
       }
       acc = wave_reduce<RIMPL>(acc, P);
-      if (row < row_end && j == 0) store_rt(po, row, odt, acc);
+      if (row < row_end && j == 0) store_rt<POL>(po, row, odt, acc);
     }
     return;
   }
@@ -378,10 +455,11 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
   for (uint32_t row = row_begin; row < row_end; ++row) {
     float acc0 = red_identity<RIMPL>(), acc1 = acc0, acc2 = acc0, acc3 = acc0;
     if (vec) {
-      const uint4* src = (const uint4*)pin + (uint64_t)row * L;
+      const uint32_t rb = (row - row_begin) * L;
       uint32_t v = tid;
       for (; v + 3 * kThreads < L; v += 4 * kThreads) {
-        const uint4 q0 = src[v], q1 = src[v + kThreads], q2 = src[v + 2 * kThreads], q3 = src[v + 3 * kThreads];
+        const v4i q0 = M::ld16(rin, (rb + v) * 16u), q1 = M::ld16(rin, (rb + v + kThreads) * 16u);
+        const v4i q2 = M::ld16(rin, (rb + v + 2 * kThreads) * 16u), q3 = M::ld16(rin, (rb + v + 3 * kThreads) * 16u);
 #pragma unroll
         for (int k = 0; k < V; ++k) {
           acc0 = red_combine<RIMPL>(acc0, E::get(q0, k));
@@ -391,14 +469,14 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
         }
       }
       for (; v < L; v += kThreads) {
-        const uint4 q0 = src[v];
+        const v4i q0 = M::ld16(rin, (rb + v) * 16u);
 #pragma unroll
         for (int k = 0; k < V; ++k) acc0 = red_combine<RIMPL>(acc0, E::get(q0, k));
       }
     } else {
-      const uint64_t rb = (uint64_t)row * n;
+      const char* prow = pin + (uint64_t)row * n * E::ES;
       for (uint32_t jx = tid; jx < n; jx += kThreads)
-        acc0 = red_combine<RIMPL>(acc0, load_rt(pin + rb * E::ES, jx, DT));
+        acc0 = red_combine<RIMPL>(acc0, E::template load1<POL>(prow, jx));
     }
     float acc = red_combine<RIMPL>(red_combine<RIMPL>(acc0, acc1), red_combine<RIMPL>(acc2, acc3));
     acc = wave_reduce<RIMPL>(acc, 64);
@@ -406,7 +484,7 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
     __syncthreads();
     if (tid == 0) {
       const float t = red_combine<RIMPL>(red_combine<RIMPL>(s_red[0], s_red[1]), red_combine<RIMPL>(s_red[2], s_red[3]));
-      store_rt(po, row, odt, t);
+      store_rt<POL>(po, row, odt, t);
     }
     __syncthreads();
   }
@@ -414,8 +492,9 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
 
 // PATH_RED_GENERIC: one wave per output row; outer index decomposed over the
 // coalesced outer dims; stride[0][5] walks the reduced dim.
-template <int RIMPL, bool INT>
+template <int POL, int RIMPL, bool INT>
 DEV void red_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
+  using M = Mem<POL>;
   const int nd = (int)uni(r->ndim);                   // outer dims
   const uint32_t n = uni(r->red_n), sl = uni(r->stride[0][5]);
   const char* pin = uni_ptr(r->ptr[0]);
@@ -436,14 +515,14 @@ DEV void red_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
     }
     if (INT) {
       int32_t acc = red_identity_i<RIMPL>();
-      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine_i<RIMPL>(acc, ((const int32_t*)pin)[ioff + jx * sl]);
+      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine_i<RIMPL>(acc, (int32_t)M::ld4(pin, ioff + jx * sl));
       acc = wave_reduce_i<RIMPL>(acc, 64);
-      if (lane == 0) ((int32_t*)po)[ooff] = acc;
+      if (lane == 0) M::st4(po, ooff, (uint32_t)acc);
     } else {
       float acc = red_identity<RIMPL>();
-      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine<RIMPL>(acc, load_rt(pin, ioff + jx * sl, idt));
+      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine<RIMPL>(acc, load_rt<POL>(pin, ioff + jx * sl, idt));
       acc = wave_reduce<RIMPL>(acc, 64);
-      if (lane == 0) store_rt(po, ooff, odt, acc);
+      if (lane == 0) store_rt<POL>(po, ooff, odt, acc);
     }
   }
 }
@@ -453,7 +532,7 @@ DEV void red_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
 // paper's function-pointer table call, Section 4.1; here a switch over
 // precompiled implementations selected by the table entry).
 // ---------------------------------------------------------------------------
-template <int IMPL>
+template <int POL, int IMPL>
 DEV void run_elementwise(const Record* r, uint32_t chunk) {
   const uint32_t per = uni(r->chunk), numel = uni(r->numel);
   const uint32_t begin = chunk * per;
@@ -462,60 +541,61 @@ DEV void run_elementwise(const Record* r, uint32_t chunk) {
   constexpr bool int_ok = IMPL == GPUOS_IMPL_ADD || IMPL == GPUOS_IMPL_SUB || IMPL == GPUOS_IMPL_MUL || IMPL == GPUOS_IMPL_COPY;
   if (r->rflags & RF_INT) {
     if (int_ok) {
-      if (path == PATH_CONTIG) ew_contig_int<IMPL>(r, begin, end);
-      else ew_generic<int_ok ? IMPL : GPUOS_IMPL_COPY, true>(r, begin, end);
+      if (path == PATH_CONTIG) ew_contig_int<POL, IMPL>(r, begin, end);
+      else ew_generic<POL, int_ok ? IMPL : GPUOS_IMPL_COPY, true>(r, begin, end);
     }
     return;
   }
   if (path == PATH_CONTIG) {
-    if (dt == GPUOS_F32) ew_contig<IMPL, GPUOS_F32>(r, begin, end);
-    else if (dt == GPUOS_F16) ew_contig<IMPL, GPUOS_F16>(r, begin, end);
-    else ew_contig<IMPL, GPUOS_BF16>(r, begin, end);
+    if (dt == GPUOS_F32) ew_contig<POL, IMPL, GPUOS_F32>(r, begin, end);
+    else if (dt == GPUOS_F16) ew_contig<POL, IMPL, GPUOS_F16>(r, begin, end);
+    else ew_contig<POL, IMPL, GPUOS_BF16>(r, begin, end);
   } else if (path == PATH_ROW2D && Op<IMPL>::N >= 2) {
     constexpr int I2 = Op<IMPL>::N >= 2 ? IMPL : GPUOS_IMPL_ADD;
-    if (dt == GPUOS_F32) ew_row2d<I2, GPUOS_F32>(r, begin, end);
-    else if (dt == GPUOS_F16) ew_row2d<I2, GPUOS_F16>(r, begin, end);
-    else ew_row2d<I2, GPUOS_BF16>(r, begin, end);
+    if (dt == GPUOS_F32) ew_row2d<POL, I2, GPUOS_F32>(r, begin, end);
+    else if (dt == GPUOS_F16) ew_row2d<POL, I2, GPUOS_F16>(r, begin, end);
+    else ew_row2d<POL, I2, GPUOS_BF16>(r, begin, end);
   } else {
-    ew_generic<IMPL, false>(r, begin, end);
+    ew_generic<POL, IMPL, false>(r, begin, end);
   }
 }
 
-template <int RIMPL>
+template <int POL, int RIMPL>
 DEV void run_reduction(const Record* r, uint32_t chunk, float* s_red) {
   const uint32_t per = uni(r->chunk), rows = uni(r->numel);
   const uint32_t begin = chunk * per;
   const uint32_t end = (rows - begin < per) ? rows : begin + per;
   const uint32_t path = uni(r->path), dt = uni(r->dtype[0]);
-  if (r->rflags & RF_INT) { red_generic<RIMPL, true>(r, begin, end); return; }
+  if (r->rflags & RF_INT) { red_generic<POL, RIMPL, true>(r, begin, end); return; }
   if (path == PATH_RED_CONTIG) {
-    if (dt == GPUOS_F32) red_contig<RIMPL, GPUOS_F32>(r, begin, end, s_red);
-    else if (dt == GPUOS_F16) red_contig<RIMPL, GPUOS_F16>(r, begin, end, s_red);
-    else red_contig<RIMPL, GPUOS_BF16>(r, begin, end, s_red);
+    if (dt == GPUOS_F32) red_contig<POL, RIMPL, GPUOS_F32>(r, begin, end, s_red);
+    else if (dt == GPUOS_F16) red_contig<POL, RIMPL, GPUOS_F16>(r, begin, end, s_red);
+    else red_contig<POL, RIMPL, GPUOS_BF16>(r, begin, end, s_red);
   } else {
-    red_generic<RIMPL, false>(r, begin, end);
+    red_generic<POL, RIMPL, false>(r, begin, end);
   }
 }
 
 // returns the task status contribution of this chunk (0 or an error)
+template <int POL>
 DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_red) {
   if (uni(r->path) == PATH_NOP) return impl == GPUOS_IMPL_FAIL ? GPUOS_E_BADOP : GPUOS_OK;
   switch (impl) {
-    case GPUOS_IMPL_ADD: run_elementwise<GPUOS_IMPL_ADD>(r, chunk); break;
-    case GPUOS_IMPL_SUB: run_elementwise<GPUOS_IMPL_SUB>(r, chunk); break;
-    case GPUOS_IMPL_MUL: run_elementwise<GPUOS_IMPL_MUL>(r, chunk); break;
-    case GPUOS_IMPL_DIV: run_elementwise<GPUOS_IMPL_DIV>(r, chunk); break;
-    case GPUOS_IMPL_RELU: run_elementwise<GPUOS_IMPL_RELU>(r, chunk); break;
-    case GPUOS_IMPL_EXP: run_elementwise<GPUOS_IMPL_EXP>(r, chunk); break;
-    case GPUOS_IMPL_GELU_ERF: run_elementwise<GPUOS_IMPL_GELU_ERF>(r, chunk); break;
-    case GPUOS_IMPL_GELU_TANH: run_elementwise<GPUOS_IMPL_GELU_TANH>(r, chunk); break;
-    case GPUOS_IMPL_SCALE: run_elementwise<GPUOS_IMPL_SCALE>(r, chunk); break;
-    case GPUOS_IMPL_FMA: run_elementwise<GPUOS_IMPL_FMA>(r, chunk); break;
-    case GPUOS_IMPL_SUB_EXP: run_elementwise<GPUOS_IMPL_SUB_EXP>(r, chunk); break;
-    case GPUOS_IMPL_COPY: run_elementwise<GPUOS_IMPL_COPY>(r, chunk); break;
-    case GPUOS_IMPL_SUM_LAST: run_reduction<GPUOS_IMPL_SUM_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_MAX_LAST: run_reduction<GPUOS_IMPL_MAX_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_MIN_LAST: run_reduction<GPUOS_IMPL_MIN_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_ADD: run_elementwise<POL, GPUOS_IMPL_ADD>(r, chunk); break;
+    case GPUOS_IMPL_SUB: run_elementwise<POL, GPUOS_IMPL_SUB>(r, chunk); break;
+    case GPUOS_IMPL_MUL: run_elementwise<POL, GPUOS_IMPL_MUL>(r, chunk); break;
+    case GPUOS_IMPL_DIV: run_elementwise<POL, GPUOS_IMPL_DIV>(r, chunk); break;
+    case GPUOS_IMPL_RELU: run_elementwise<POL, GPUOS_IMPL_RELU>(r, chunk); break;
+    case GPUOS_IMPL_EXP: run_elementwise<POL, GPUOS_IMPL_EXP>(r, chunk); break;
+    case GPUOS_IMPL_GELU_ERF: run_elementwise<POL, GPUOS_IMPL_GELU_ERF>(r, chunk); break;
+    case GPUOS_IMPL_GELU_TANH: run_elementwise<POL, GPUOS_IMPL_GELU_TANH>(r, chunk); break;
+    case GPUOS_IMPL_SCALE: run_elementwise<POL, GPUOS_IMPL_SCALE>(r, chunk); break;
+    case GPUOS_IMPL_FMA: run_elementwise<POL, GPUOS_IMPL_FMA>(r, chunk); break;
+    case GPUOS_IMPL_SUB_EXP: run_elementwise<POL, GPUOS_IMPL_SUB_EXP>(r, chunk); break;
+    case GPUOS_IMPL_COPY: run_elementwise<POL, GPUOS_IMPL_COPY>(r, chunk); break;
+    case GPUOS_IMPL_SUM_LAST: run_reduction<POL, GPUOS_IMPL_SUM_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_MAX_LAST: run_reduction<POL, GPUOS_IMPL_MAX_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_MIN_LAST: run_reduction<POL, GPUOS_IMPL_MIN_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_FAIL: return GPUOS_E_BADOP;       // kill-switch stub: fail fast, write nothing
     default: return GPUOS_E_BADOP;
   }
@@ -530,21 +610,23 @@ struct DispShared {
   uint64_t entry[GPUOS_MAX_OPS];       // shadow of the device table: current {impl, version}
   uint32_t ubeg[kDispatchBatch + 1];   // exclusive prefix of nchunks
   uint64_t tail, epoch_word;
-  uint32_t n, stop, refresh_op;
+  uint32_t n;
 };
 
 DEV void dispatcher_refresh_table(const WorkerArgs& a, DispShared* s, uint32_t only_op) {
   // copy entries host table -> device table with the dual-slot protocol: the
-  // inactive slot is written first, then the version is published (release).
+  // inactive slot is written first, then the version is published.
   for (uint32_t op = threadIdx.x; op < GPUOS_MAX_OPS; op += kThreads) {
     if (only_op != 0xffu && op != only_op) continue;
-    const uint32_t ver = __hip_atomic_load(&a.htable[op].version, __ATOMIC_ACQUIRE, SC_SYSTEM);
+    const uint32_t ver = __hip_atomic_load(&a.htable[op].version, __ATOMIC_RELAXED, SC_SYSTEM);
     if (ver == 0) continue;
+    order_loads();
     const uint64_t e = __hip_atomic_load(&a.htable[op].slot[ver & 1u], __ATOMIC_RELAXED, SC_SYSTEM);
     if (e == s->entry[op]) continue;
     const uint32_t ev = (uint32_t)(e >> 32);
-    __hip_atomic_store(&a.dtable[op].slot[ev & 1u], e, __ATOMIC_RELAXED, SC_AGENT);
-    __hip_atomic_store(&a.dtable[op].version, ev, __ATOMIC_RELEASE, SC_AGENT);
+    __hip_atomic_store(&a.dtable[op].slot[ev & 1u], e, __ATOMIC_RELAXED, SC_SYSTEM);
+    drain_stores();
+    __hip_atomic_store(&a.dtable[op].version, ev, __ATOMIC_RELAXED, SC_SYSTEM);
     s->entry[op] = e;
   }
 }
@@ -572,9 +654,10 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
           break;
         }
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
+      order_loads();
       if (e & 3u) {                                 // stop: take the final tail after the flag
-        t = __hip_atomic_load(&a.h->tail, __ATOMIC_ACQUIRE, SC_SYSTEM);
+        t = __hip_atomic_load(&a.h->tail, __ATOMIC_RELAXED, SC_SYSTEM);
+        order_loads();
       }
       s->tail = t;
       s->epoch_word = e;
@@ -588,7 +671,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       dispatcher_refresh_table(a, s, one ? hinted : 0xffu);
       if (tid == 0) {
         const uint32_t y = __hip_atomic_load(&a.h->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
-        __hip_atomic_store(&a.d->yield_every, y, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_store(&a.d->yield_every, y, __ATOMIC_RELAXED, SC_SYSTEM);
       }
       __syncthreads();
     }
@@ -598,11 +681,15 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
     // ---- mirror new records, batch by batch ----
     while (mirrored < tail) {
       uint32_t n = (uint32_t)((tail - mirrored) < kDispatchBatch ? (tail - mirrored) : kDispatchBatch);
-      // stage: 16 pieces of 16 bytes per record
-      for (uint32_t p = tid; p < n * 16u; p += kThreads) {
-        const uint32_t rix = p >> 4, part = p & 15u;
-        const uint4* src = (const uint4*)&a.hring[(mirrored + rix) & a.cap_mask];
-        ((uint4*)&s->rec[rix])[part] = src[part];
+      // stage: 16 pieces of 16 bytes per record.  System-scope loads: an ordinary load of host
+      // memory may hit a line the CU's vector cache kept from the previous lap of the ring.
+      {
+        const rsrc_t rh = make_rsrc(a.hring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
+        for (uint32_t p = tid; p < n * 16u; p += kThreads) {
+          const uint32_t rix = p >> 4, part = p & 15u;
+          const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
+          ((v4i*)&s->rec[rix])[part] = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
+        }
       }
       __syncthreads();
       // a FENCE task starts a batch of its own: cut the batch in front of it
@@ -642,15 +729,18 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       __syncthreads();
       // a leading FENCE: wait until every earlier ticket has completed
       if (tid == 0 && (s->rec[0].rflags & RF_FENCE)) {
-        while (__hip_atomic_load(&a.d->done_count, __ATOMIC_RELAXED, SC_AGENT) < mirrored)
+        while (__hip_atomic_load(&a.d->done_count, __ATOMIC_RELAXED, SC_SYSTEM) < mirrored)
           __builtin_amdgcn_s_sleep(4);
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        order_loads();
       }
-      // write the records into the device mirror
-      for (uint32_t p = tid; p < n * 16u; p += kThreads) {
-        const uint32_t rix = p >> 4, part = p & 15u;
-        uint4* dst = (uint4*)&a.dring[(mirrored + rix) & a.cap_mask];
-        dst[part] = ((const uint4*)&s->rec[rix])[part];
+      // write the records into the device mirror (write-through stores)
+      {
+        const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
+        for (uint32_t p = tid; p < n * 16u; p += kThreads) {
+          const uint32_t rix = p >> 4, part = p & 15u;
+          const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
+          Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, ((const v4i*)&s->rec[rix])[part]);
+        }
       }
       // expand into work units
       const uint32_t total = s->ubeg[n];
@@ -661,23 +751,26 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
           if (s->ubeg[mid] <= u) lo = mid; else hi = mid;
         }
         const Record& rc = s->rec[lo];
-        a.units[(units_w + u) & a.unit_mask] =
-            pack_unit(u - s->ubeg[lo], (uint32_t)((mirrored + lo) & a.cap_mask), rc.op_id, rc.sel,
-                      rc.status == GPUOS_OK ? 1u : 0u);
+        __hip_atomic_store(&a.units[(units_w + u) & a.unit_mask],
+                           pack_unit(u - s->ubeg[lo], (uint32_t)((mirrored + lo) & a.cap_mask), rc.op_id, rc.sel,
+                                     rc.status == GPUOS_OK ? 1u : 0u),
+                           __ATOMIC_RELAXED, SC_SYSTEM);
       }
-      __syncthreads();                                             // every store above is issued and done
+      drain_stores();                                              // this wave's records and units are in memory
+      __syncthreads();                                             // ... and so are every other wave's
       units_w += total;
       mirrored += n;
       if (tid == 0) {
-        __hip_atomic_store(&a.d->tail_units, units_w, __ATOMIC_RELEASE, SC_AGENT);
+        __hip_atomic_store(&a.d->tail_units, units_w, __ATOMIC_RELAXED, SC_SYSTEM);   // publish
         __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
       }
       idle_since = wall_clock64();
     }
     if (stopping) {
       if (tid == 0) {
-        __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELEASE, SC_AGENT);
-        __hip_atomic_store(&a.h->exit_code, (ew & 2u) ? 2u : 1u, __ATOMIC_RELEASE, SC_SYSTEM);
+        drain_stores();
+        __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELAXED, SC_SYSTEM);
+        __hip_atomic_store(&a.h->exit_code, (ew & 2u) ? 2u : 1u, __ATOMIC_RELAXED, SC_SYSTEM);
       }
       return;
     }
@@ -696,28 +789,30 @@ struct WorkShared {
 
 DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
   const uint32_t tid = threadIdx.x;
+  const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   while (true) {
     // ---- claim one work unit (elected lane, atomic fetch-add) ----
     if (tid == 0) {
       const uint64_t g = __hip_atomic_fetch_add(&a.d->claim, 1ull, __ATOMIC_RELAXED, SC_AGENT);
       int32_t ex = 0;
       uint32_t polls = 0;
-      while (__hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_AGENT) <= g) {
-        if (__hip_atomic_load(&a.d->stop_dev, __ATOMIC_ACQUIRE, SC_AGENT)) {
-          if (__hip_atomic_load(&a.d->tail_units, __ATOMIC_ACQUIRE, SC_AGENT) <= g) { ex = 1; break; }
+      while (__hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM) <= g) {
+        if (__hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) {
+          order_loads();
+          if (__hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM) <= g) { ex = 1; break; }
           continue;
         }
         // polling policy (paper Section 4.1): short back-off while spinning, longer
         // pauses every yield_every-th empty poll when the host asked for them
         ++polls;
-        const uint32_t y = __hip_atomic_load(&a.d->yield_every, __ATOMIC_RELAXED, SC_AGENT);
+        const uint32_t y = __hip_atomic_load(&a.d->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
         if (y != 0 && (polls % y) == 0) { for (int k = 0; k < 16; ++k) __builtin_amdgcn_s_sleep(127); }
         else if (polls < 64) __builtin_amdgcn_s_sleep(2);
         else __builtin_amdgcn_s_sleep(16);
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      order_loads();
       s->exit_flag = ex;
-      if (!ex) s->unit = a.units[g & a.unit_mask];
+      if (!ex) s->unit = __hip_atomic_load(&a.units[g & a.unit_mask], __ATOMIC_RELAXED, SC_SYSTEM);
     }
     __syncthreads();
     if (s->exit_flag) return;
@@ -727,8 +822,8 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
     const uint32_t op = (uint32_t)((unit >> 36) & 0xffu), sel = (uint32_t)((unit >> 44) & 1u);
     const bool op_valid = ((unit >> 45) & 1u) != 0;
     // ---- fetch the descriptor (16 lanes x 16 bytes) and the claimed table slot ----
-    if (tid < 16) ((uint4*)&s->rec)[tid] = ((const uint4*)&a.dring[slot])[tid];
-    if (tid == 16) s->entry = op_valid ? __hip_atomic_load(&a.dtable[op].slot[sel], __ATOMIC_RELAXED, SC_AGENT) : 0ull;
+    if (tid < 16) ((v4i*)&s->rec)[tid] = Mem<POL_COHERENT>::ld16(rd, slot * (uint32_t)sizeof(Record) + tid * 16u);
+    if (tid == 16) s->entry = op_valid ? __hip_atomic_load(&a.dtable[op].slot[sel], __ATOMIC_RELAXED, SC_SYSTEM) : 0ull;
     __syncthreads();
     const Record* r = &s->rec;
     int32_t status = r->status;
@@ -743,31 +838,28 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
           if (back == 0 || back > ticket) continue;
           const uint64_t want = ticket - back + 1;
           const uint64_t* w = &a.st[(ticket - back) & a.cap_mask].done_seq;
-          while (__hip_atomic_load(w, __ATOMIC_RELAXED, SC_AGENT) < want) __builtin_amdgcn_s_sleep(1);
+          while (__hip_atomic_load(w, __ATOMIC_RELAXED, SC_SYSTEM) < want) __builtin_amdgcn_s_sleep(1);
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        order_loads();
       }
       __syncthreads();
     }
     // ---- execute ----
-    if (status == GPUOS_OK) status = exec_chunk(r, impl, chunk, s->red);
-    __syncthreads();                  // all stores of the workgroup are complete past this point
+    if (status == GPUOS_OK) status = exec_chunk<POL_COHERENT>(r, impl, chunk, s->red);
+    drain_stores();                   // this wave's (write-through) stores have reached memory
+    __syncthreads();                  // ... and so have the other three waves'
     // ---- complete ----
     if (tid == 0) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");       // outputs visible to device and host
       const uint32_t nchunks = r->nchunks;
       bool last = true;
       if (nchunks > 1) {
         const uint32_t prev = __hip_atomic_fetch_add(&a.st[slot].chunks_done, 1u, __ATOMIC_RELAXED, SC_AGENT);
         last = (prev + 1 == nchunks);
-        if (last) {
-          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "");   // take over the other chunks' releases
-          __hip_atomic_store(&a.st[slot].chunks_done, 0u, __ATOMIC_RELAXED, SC_AGENT);
-        }
+        if (last) __hip_atomic_store(&a.st[slot].chunks_done, 0u, __ATOMIC_RELAXED, SC_SYSTEM);
       }
       if (last) {
         const uint64_t ticket = r->ticket;
-        __hip_atomic_store(&a.st[slot].done_seq, ticket + 1, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_store(&a.st[slot].done_seq, ticket + 1, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.hcomp[slot], pack_completion(ticket, status, r->version), __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_fetch_add(&a.d->done_count, 1ull, __ATOMIC_RELAXED, SC_AGENT);
       }
@@ -793,7 +885,7 @@ __global__ void __launch_bounds__(kThreads) gpuos_single_task_kernel(Record rec)
   __shared__ float s_red[4];
   if (threadIdx.x == 0) s_rec = rec;
   __syncthreads();
-  exec_chunk(&s_rec, s_rec.impl, blockIdx.x, s_red);
+  exec_chunk<POL_PLAIN>(&s_rec, s_rec.impl, blockIdx.x, s_red);
 }
 
 int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream) {

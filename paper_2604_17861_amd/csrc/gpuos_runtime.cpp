@@ -206,7 +206,7 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r) {
       for (int k = 0; k < ar; ++k) all_aligned = all_aligned && aligned16(ops[k].ptr);
       if (all_aligned) rec.rflags |= RF_VEC;
     } else if (!all_int && nd == 2 && ar >= 2 && ops[ar].stride[1] == 1 && ops[ar].stride[0] == size[1] &&
-               size[1] % V == 0 && all_aligned) {
+               size[1] % V == 0 && all_aligned && size[1] * 4 < kMaxExtent) {   // a row fits one buffer resource
       bool ok = true;
       for (int k = 0; k < ar && ok; ++k) {
         const int64_t s0 = ops[k].stride[0], s1 = ops[k].stride[1];
@@ -251,7 +251,7 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r) {
   rec.numel = (uint32_t)rows;
   const uint32_t V = 16u / dtype_size(ops[0].dtype);
   const bool rows_contig = rows == 1 || (nd == 1 && oo[0].stride[0] == n && oo[1].stride[0] == 1);
-  if (!all_int && s_last == 1 && rows_contig) {
+  if (!all_int && s_last == 1 && rows_contig && n * 4 < kMaxExtent) {            // a row fits one buffer resource
     rec.path = PATH_RED_CONTIG;
     if (n % V == 0 && aligned16(ops[0].ptr)) rec.rflags |= RF_VEC;
   } else {
