@@ -156,7 +156,9 @@ typedef struct gpuos_config {
                                        (0 => 30000)                                 */
   uint32_t completion_log;          /* tickets kept for gpuos_get_completions
                                        (0 => 1<<21; rounded up to a power of two)   */
-  uint32_t reserved[7];
+  uint32_t chunk_elems;             /* elements of a task one workgroup takes at a time
+                                       (0 => 16384; rounded up to a multiple of 1024)  */
+  uint32_t reserved[6];
 } gpuos_config;
 
 /* Fill *cfg with the defaults named above. */
@@ -220,6 +222,14 @@ int gpuos_set_yield_every(gpuos_ctx* ctx, uint32_t every);
 /* Paper Table 1 shutdown(): drain everything submitted, signal the worker to
  * exit, join the kernel, free the library's memory.  Idempotent on NULL. */
 int gpuos_shutdown(gpuos_ctx* ctx);
+
+/* Performance counters of the persistent kernel (paper Section 5.3), valid after
+ * gpuos_stop_worker.  out[0..15] (HOST array): dispatcher batches, records, work
+ * units, then dispatcher time staging / resolving / writing / busy in 10 ns ticks,
+ * dispatcher polls; then summed over all worker workgroups: work units executed
+ * and 10 ns ticks spent waiting for work, fetching descriptors, waiting for
+ * dependencies, executing, completing, and alive in total; out[15] is 0. */
+int gpuos_worker_stats(gpuos_ctx* ctx, uint64_t out[16]);
 
 /* Milliseconds the worker kernel ran, from HIP events on its stream (valid
  * after the worker has exited, i.e. call it on a context being shut down via

@@ -103,6 +103,14 @@ struct DevCtl {                      // device memory
   alignas(128) uint64_t done_count;  // tasks completed
   alignas(128) uint32_t stop_dev;    // dispatcher -> workers
   uint32_t yield_every;
+  // performance counters (paper Section 5.3), 100 MHz ticks; workers add theirs when they exit
+  alignas(128) uint64_t stat[16];
+};
+enum StatIndex {
+  ST_DISP_BATCHES = 0, ST_DISP_RECORDS, ST_DISP_UNITS, ST_DISP_TICKS_STAGE, ST_DISP_TICKS_RESOLVE,
+  ST_DISP_TICKS_WRITE, ST_DISP_TICKS_TOTAL_BUSY, ST_DISP_POLLS,
+  ST_WORK_UNITS = 8, ST_WORK_TICKS_WAIT, ST_WORK_TICKS_FETCH, ST_WORK_TICKS_DEP, ST_WORK_TICKS_EXEC,
+  ST_WORK_TICKS_COMPLETE, ST_WORK_TICKS_TOTAL
 };
 
 struct SlotState {                   // device memory, one per ring slot

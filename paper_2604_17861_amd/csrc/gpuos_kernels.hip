@@ -417,76 +417,196 @@ template <int RIMPL> DEV int32_t wave_reduce_i(int32_t acc, uint32_t width) {
 }
 
 // PATH_RED_CONTIG: input is a contiguous [rows, n] matrix of dtype DT, output a
-// contiguous vector [rows] of any float dtype.
-template <int POL, int RIMPL, int DT>
-DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_red) {
+// contiguous vector [rows] of any float dtype.  The rows of a chunk are read as one flat
+// run of 16-byte vectors aligned to the tensor base, whatever n is: a vector that straddles
+// a row boundary is loaded by both rows and masked per element.  Three shapes of work:
+//   short rows  (span <= 64 vectors): P lanes per row, 64 / P rows per wavefront pass,
+//               four passes in flight;
+//   medium rows: one wavefront per row, RA rows at a time, UN loads per row in flight;
+//   long rows   (>= 1024 vectors): the four wavefronts take a quarter of each row, partial
+//               results meet in LDS once per chunk (one barrier per chunk, not per row).
+template <int RIMPL, int DT>
+DEV float red_vector(const v4i& q, uint32_t f0, uint32_t lo, uint32_t hi, bool edge, float acc) {
+  // q holds elements f0 .. f0+V-1 of the flat run; the row is [lo, hi)
+  using E = Elem<DT>;
+  if (!edge) {
+#pragma unroll
+    for (int k = 0; k < E::V; ++k) acc = red_combine<RIMPL>(acc, E::get(q, k));
+  } else {
+#pragma unroll
+    for (int k = 0; k < E::V; ++k)
+      if (f0 + k >= lo && f0 + k < hi) acc = red_combine<RIMPL>(acc, E::get(q, k));
+  }
+  return acc;
+}
+
+struct RedRun {        // the chunk's rows as a flat run of vectors
+  rsrc_t rin;
+  uint32_t base_elem;  // first element of the run (multiple of V), relative to the tensor
+  uint32_t n;
+};
+
+template <int POL, int RIMPL, int DT, int RA, int UN>
+DEV void red_rows_wave(const RedRun& run, char* po, uint32_t odt, uint32_t row_begin, uint32_t row_end) {
   using E = Elem<DT>;
   using M = Mem<POL>;
-  constexpr int V = E::V;
+  constexpr uint32_t V = E::V;
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t n = run.n;
+  // wave w takes rows row_begin + w, + 4, + 8, ... ; RA of them at a time
+  for (uint32_t row0 = row_begin + wave; row0 < row_end; row0 += 4 * RA) {
+    float acc[RA];
+    uint32_t lo[RA], hi[RA], j0[RA], j1[RA];
+    uint32_t span = 0;
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+      acc[i] = red_identity<RIMPL>();
+      const uint32_t row = row0 + 4 * i;
+      lo[i] = row * n - run.base_elem;
+      hi[i] = lo[i] + n;
+      j0[i] = lo[i] / V;
+      j1[i] = (hi[i] - 1) / V;
+      if (row >= row_end) { hi[i] = lo[i]; j1[i] = j0[i]; }
+      const uint32_t sp = j1[i] - j0[i] + 1;
+      span = sp > span ? sp : span;
+    }
+    for (uint32_t v = lane; v < span; v += 64 * UN) {
+      v4i q[RA][UN];
+#pragma unroll
+      for (int i = 0; i < RA; ++i)
+#pragma unroll
+        for (int u = 0; u < UN; ++u)   // loads past the run are clamped by the buffer bounds and masked below
+          q[i][u] = M::ld16(run.rin, (j0[i] + v + u * 64) * 16u);
+#pragma unroll
+      for (int i = 0; i < RA; ++i)
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const uint32_t j = j0[i] + v + u * 64;
+          if (j <= j1[i] && hi[i] > lo[i])
+            acc[i] = red_vector<RIMPL, DT>(q[i][u], j * V, lo[i], hi[i], j == j0[i] || j == j1[i], acc[i]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+      const float t = wave_reduce<RIMPL>(acc[i], 64);
+      if (lane == 0 && row0 + 4 * i < row_end) store_rt<POL>(po, row0 + 4 * i, odt, t);
+    }
+  }
+}
+
+constexpr uint32_t kRedPartialRows = 64;   // rows of partial results the LDS scratch holds
+
+template <int POL, int RIMPL, int DT>
+DEV void red_rows_quarter(const RedRun& run, char* po, uint32_t odt, uint32_t row_begin, uint32_t row_end,
+                          float* s_part) {
+  using E = Elem<DT>;
+  using M = Mem<POL>;
+  constexpr uint32_t V = E::V;
+  constexpr int UN = 8;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t n = run.n;
+  for (uint32_t row = row_begin; row < row_end; ++row) {
+    const uint32_t lo = row * n - run.base_elem, hi = lo + n;
+    const uint32_t j0 = lo / V, j1 = (hi - 1) / V;
+    const uint32_t span = j1 - j0 + 1, sq = (span + 3u) / 4u;          // vectors per quarter
+    const uint32_t q_begin = j0 + wave * sq;
+    const uint32_t q_end = (q_begin + sq <= j1 + 1) ? q_begin + sq : j1 + 1;
+    float a0 = red_identity<RIMPL>(), a1 = a0;
+    for (uint32_t v = q_begin + lane; v < q_end; v += 64 * UN) {
+      v4i q[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) q[u] = M::ld16(run.rin, (v + u * 64) * 16u);
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const uint32_t j = v + u * 64;
+        if (j < q_end) {
+          if ((u & 1) == 0) a0 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a0);
+          else a1 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a1);
+        }
+      }
+    }
+    const float t = wave_reduce<RIMPL>(red_combine<RIMPL>(a0, a1), 64);
+    if (lane == 0) s_part[(row - row_begin) * 4 + wave] = t;
+  }
+  __syncthreads();
+  const uint32_t nrows = row_end - row_begin;
+  if (tid < nrows) {
+    const float* p = s_part + tid * 4;
+    const float t = red_combine<RIMPL>(red_combine<RIMPL>(p[0], p[1]), red_combine<RIMPL>(p[2], p[3]));
+    store_rt<POL>(po, row_begin + tid, odt, t);
+  }
+  __syncthreads();
+}
+
+template <int POL, int RIMPL, int DT>
+DEV void red_rows_short(const RedRun& run, char* po, uint32_t odt, uint32_t row_begin, uint32_t row_end,
+                        uint32_t max_span) {
+  using E = Elem<DT>;
+  using M = Mem<POL>;
+  constexpr uint32_t V = E::V;
+  constexpr int UP = 4;
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t n = run.n;
+  uint32_t P = 1;                                     // lanes per row: power of two >= the widest span
+  while (P < max_span) P <<= 1;
+  const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
+  for (uint32_t base = row_begin + wave * rpw * UP; base < row_end; base += 4 * rpw * UP) {
+    v4i q[UP];
+    uint32_t lo[UP], hi[UP], j0[UP], j1[UP];
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+      const uint32_t row = base + u * rpw + sub;
+      lo[u] = row * n - run.base_elem;
+      hi[u] = lo[u] + n;
+      j0[u] = lo[u] / V;
+      j1[u] = (hi[u] - 1) / V;
+      q[u] = M::ld16(run.rin, (j0[u] + j) * 16u);
+    }
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+      const uint32_t row = base + u * rpw + sub;
+      const uint32_t jj = j0[u] + j;
+      float acc = red_identity<RIMPL>();
+      if (row < row_end && jj <= j1[u])
+        acc = red_vector<RIMPL, DT>(q[u], jj * V, lo[u], hi[u], jj == j0[u] || jj == j1[u], acc);
+      acc = wave_reduce<RIMPL>(acc, P);
+      if (row < row_end && j == 0) store_rt<POL>(po, row, odt, acc);
+    }
+  }
+}
+
+template <int POL, int RIMPL, int DT>
+DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_part) {
+  using E = Elem<DT>;
+  constexpr uint32_t V = E::V;
   const uint32_t n = uni(r->red_n);
   const char* pin = uni_ptr(r->ptr[0]);
   char* po = (char*)uni_ptr(r->ptr[3]);
   const uint32_t odt = uni(r->dtype[3]);
-  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-  const bool vec = (r->rflags & RF_VEC) != 0;
-  const uint32_t L = n / V;                           // vectors per row when vec
-  // the rows of this chunk as one buffer (the host keeps a chunk below 2 GiB)
-  const rsrc_t rin = make_rsrc(pin + (uint64_t)row_begin * n * E::ES, (row_end - row_begin) * n * E::ES);
-  if (vec && L <= 64u) {
-    // several rows per wave pass: P = lanes per row (power of two >= L)
-    uint32_t P = 1;
-    while (P < L) P <<= 1;
-    const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
-    const uint32_t rows_per_pass = rpw * 4u;
-    for (uint32_t base = row_begin; base < row_end; base += rows_per_pass) {
-      const uint32_t row = base + wave * rpw + sub;
-      float acc = red_identity<RIMPL>();
-      if (row < row_end && j < L) {
-        const v4i q = M::ld16(rin, ((row - row_begin) * L + j) * 16u);
-#pragma unroll
-        for (int k = 0; k < V; ++k) acc = red_combine<RIMPL>(acc, E::get(q, k));
-      }
-      acc = wave_reduce<RIMPL>(acc, P);
-      if (row < row_end && j == 0) store_rt<POL>(po, row, odt, acc);
-    }
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  if (r->rflags & RF_VEC) {                           // tensor base is 16-byte aligned
+    RedRun run;
+    run.n = n;
+    run.base_elem = (row_begin * n) / V * V;          // chunk start, aligned down to a vector
+    // end rounded up to a whole vector (the base is 16-byte aligned, so the padding stays inside
+    // the 16-byte block that holds the last element); vector loads further out read zeros; both
+    // are masked per element
+    run.rin = make_rsrc(pin + (uint64_t)run.base_elem * E::ES, ((row_end * n - run.base_elem) * E::ES + 15u) & ~15u);
+    const uint32_t max_span = (n % V == 0 && run.base_elem == row_begin * n) ? n / V : (n + V - 2) / V + 1;
+    if (max_span <= 64u) red_rows_short<POL, RIMPL, DT>(run, po, odt, row_begin, row_end, max_span);
+    else if (max_span >= 1024u && row_end - row_begin <= kRedPartialRows)
+      red_rows_quarter<POL, RIMPL, DT>(run, po, odt, row_begin, row_end, s_part);
+    else if (max_span < 256u) red_rows_wave<POL, RIMPL, DT, 4, 2>(run, po, odt, row_begin, row_end);
+    else red_rows_wave<POL, RIMPL, DT, 2, 4>(run, po, odt, row_begin, row_end);
     return;
   }
-  // one row at a time, the whole workgroup on it
-  for (uint32_t row = row_begin; row < row_end; ++row) {
-    float acc0 = red_identity<RIMPL>(), acc1 = acc0, acc2 = acc0, acc3 = acc0;
-    if (vec) {
-      const uint32_t rb = (row - row_begin) * L;
-      uint32_t v = tid;
-      for (; v + 3 * kThreads < L; v += 4 * kThreads) {
-        const v4i q0 = M::ld16(rin, (rb + v) * 16u), q1 = M::ld16(rin, (rb + v + kThreads) * 16u);
-        const v4i q2 = M::ld16(rin, (rb + v + 2 * kThreads) * 16u), q3 = M::ld16(rin, (rb + v + 3 * kThreads) * 16u);
-#pragma unroll
-        for (int k = 0; k < V; ++k) {
-          acc0 = red_combine<RIMPL>(acc0, E::get(q0, k));
-          acc1 = red_combine<RIMPL>(acc1, E::get(q1, k));
-          acc2 = red_combine<RIMPL>(acc2, E::get(q2, k));
-          acc3 = red_combine<RIMPL>(acc3, E::get(q3, k));
-        }
-      }
-      for (; v < L; v += kThreads) {
-        const v4i q0 = M::ld16(rin, (rb + v) * 16u);
-#pragma unroll
-        for (int k = 0; k < V; ++k) acc0 = red_combine<RIMPL>(acc0, E::get(q0, k));
-      }
-    } else {
-      const char* prow = pin + (uint64_t)row * n * E::ES;
-      for (uint32_t jx = tid; jx < n; jx += kThreads)
-        acc0 = red_combine<RIMPL>(acc0, E::template load1<POL>(prow, jx));
-    }
-    float acc = red_combine<RIMPL>(red_combine<RIMPL>(acc0, acc1), red_combine<RIMPL>(acc2, acc3));
+  // tensor base not 16-byte aligned: one wave per row, element loads
+  for (uint32_t row = row_begin + wave; row < row_end; row += 4) {
+    const char* prow = pin + (uint64_t)row * n * E::ES;
+    float acc = red_identity<RIMPL>();
+    for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine<RIMPL>(acc, E::template load1<POL>(prow, jx));
     acc = wave_reduce<RIMPL>(acc, 64);
-    if (lane == 0) s_red[wave] = acc;
-    __syncthreads();
-    if (tid == 0) {
-      const float t = red_combine<RIMPL>(red_combine<RIMPL>(s_red[0], s_red[1]), red_combine<RIMPL>(s_red[2], s_red[3]));
-      store_rt<POL>(po, row, odt, t);
-    }
-    __syncthreads();
+    if (lane == 0) store_rt<POL>(po, row, odt, acc);
   }
 }
 
@@ -639,6 +759,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   uint64_t idle_since = wall_clock64();
   uint64_t polls = 0;
   bool stopping = false;
+  uint64_t st_batches = 0, st_records = 0, st_units = 0, st_stage = 0, st_resolve = 0, st_write = 0, st_busy = 0;
   while (true) {
     // ---- poll the host ring (one lane; the only PCIe poller of the kernel) ----
     if (tid == 0) {
@@ -680,6 +801,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
 
     // ---- mirror new records, batch by batch ----
     while (mirrored < tail) {
+      const uint64_t tk0 = wall_clock64();
       uint32_t n = (uint32_t)((tail - mirrored) < kDispatchBatch ? (tail - mirrored) : kDispatchBatch);
       // stage: 16 pieces of 16 bytes per record.  System-scope loads: an ordinary load of host
       // memory may hit a line the CU's vector cache kept from the previous lap of the ring.
@@ -692,6 +814,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         }
       }
       __syncthreads();
+      const uint64_t tk1 = wall_clock64();
       // a FENCE task starts a batch of its own: cut the batch in front of it
       if (tid == 0) {
         uint32_t cut = n;
@@ -733,6 +856,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
           __builtin_amdgcn_s_sleep(4);
         order_loads();
       }
+      const uint64_t tk2 = wall_clock64();
       // write the records into the device mirror (write-through stores)
       {
         const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
@@ -765,9 +889,15 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
       }
       idle_since = wall_clock64();
+      st_batches += 1; st_records += n; st_units += total;
+      st_stage += tk1 - tk0; st_resolve += tk2 - tk1; st_write += idle_since - tk2; st_busy += idle_since - tk0;
     }
     if (stopping) {
       if (tid == 0) {
+        uint64_t* st = a.d->stat;
+        st[ST_DISP_BATCHES] = st_batches; st[ST_DISP_RECORDS] = st_records; st[ST_DISP_UNITS] = st_units;
+        st[ST_DISP_TICKS_STAGE] = st_stage; st[ST_DISP_TICKS_RESOLVE] = st_resolve; st[ST_DISP_TICKS_WRITE] = st_write;
+        st[ST_DISP_TICKS_TOTAL_BUSY] = st_busy; st[ST_DISP_POLLS] = polls;
         drain_stores();
         __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.h->exit_code, (ew & 2u) ? 2u : 1u, __ATOMIC_RELAXED, SC_SYSTEM);
@@ -784,13 +914,16 @@ struct WorkShared {
   Record rec;
   uint64_t unit, entry;
   int32_t exit_flag;
-  float red[4];
+  float red[4 * kRedPartialRows];
 };
 
 DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
   const uint32_t tid = threadIdx.x;
   const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
+  uint64_t w_units = 0, w_wait = 0, w_fetch = 0, w_dep = 0, w_exec = 0, w_done = 0;
+  const uint64_t w_start = wall_clock64();
   while (true) {
+    const uint64_t c0 = wall_clock64();
     // ---- claim one work unit (elected lane, atomic fetch-add) ----
     if (tid == 0) {
       const uint64_t g = __hip_atomic_fetch_add(&a.d->claim, 1ull, __ATOMIC_RELAXED, SC_AGENT);
@@ -815,8 +948,23 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       if (!ex) s->unit = __hip_atomic_load(&a.units[g & a.unit_mask], __ATOMIC_RELAXED, SC_SYSTEM);
     }
     __syncthreads();
-    if (s->exit_flag) return;
-    const uint64_t unit = s->unit;
+    if (s->exit_flag) {
+      if (tid == 0) {
+        uint64_t* st = a.d->stat;
+        __hip_atomic_fetch_add(&st[ST_WORK_UNITS], w_units, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_WAIT], w_wait, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_FETCH], w_fetch, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_DEP], w_dep, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_EXEC], w_exec, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_COMPLETE], w_done, __ATOMIC_RELAXED, SC_AGENT);
+        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_TOTAL], c0 - w_start, __ATOMIC_RELAXED, SC_AGENT);
+      }
+      return;
+    }
+    const uint64_t c1 = wall_clock64();
+    // the unit is the same for the whole workgroup: keep its fields in scalar registers
+    const uint32_t unit_lo = uni((uint32_t)s->unit), unit_hi = uni((uint32_t)(s->unit >> 32));
+    const uint64_t unit = ((uint64_t)unit_hi << 32) | unit_lo;
     const uint32_t chunk = (uint32_t)(unit & 0xfffffu);
     const uint32_t slot = (uint32_t)((unit >> 20) & 0xffffu);
     const uint32_t op = (uint32_t)((unit >> 36) & 0xffu), sel = (uint32_t)((unit >> 44) & 1u);
@@ -827,8 +975,9 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
     __syncthreads();
     const Record* r = &s->rec;
     int32_t status = r->status;
-    const uint32_t impl = r->impl;
+    const uint32_t impl = uni(r->impl);
     if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
+    const uint64_t c2 = wall_clock64();
     // ---- dependencies: earlier tickets named by back-distance ----
     if (r->dep[0] | r->dep[1] | r->dep[2]) {
       if (tid == 0) {
@@ -844,10 +993,12 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       }
       __syncthreads();
     }
+    const uint64_t c3 = wall_clock64();
     // ---- execute ----
     if (status == GPUOS_OK) status = exec_chunk<POL_COHERENT>(r, impl, chunk, s->red);
     drain_stores();                   // this wave's (write-through) stores have reached memory
     __syncthreads();                  // ... and so have the other three waves'
+    const uint64_t c4 = wall_clock64();
     // ---- complete ----
     if (tid == 0) {
       const uint32_t nchunks = r->nchunks;
@@ -865,6 +1016,8 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       }
     }
     __syncthreads();                  // the descriptor in LDS may be overwritten after this
+    const uint64_t c5 = wall_clock64();
+    w_units += 1; w_wait += c1 - c0; w_fetch += c2 - c1; w_dep += c3 - c2; w_exec += c4 - c3; w_done += c5 - c4;
   }
 }
 
@@ -882,7 +1035,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
 // one ordinary launch per task: block b executes chunk b
 __global__ void __launch_bounds__(kThreads) gpuos_single_task_kernel(Record rec) {
   __shared__ Record s_rec;
-  __shared__ float s_red[4];
+  __shared__ float s_red[4 * kRedPartialRows];
   if (threadIdx.x == 0) s_rec = rec;
   __syncthreads();
   exec_chunk<POL_PLAIN>(&s_rec, s_rec.impl, blockIdx.x, s_red);

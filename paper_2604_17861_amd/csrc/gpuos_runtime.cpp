@@ -135,7 +135,7 @@ inline bool aligned16(uint64_t p) { return (p & 15u) == 0; }
 
 // Validate `t` for implementation `impl` and pack it.  Nothing is written to
 // *r unless the result is GPUOS_OK.
-int pack_task(const gpuos_task& t, uint32_t impl, Record* r) {
+int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elems = kChunkElems) {
   Record rec;
   std::memset(&rec, 0, sizeof(rec));
   rec.op_id = t.op_id;
@@ -217,9 +217,14 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r) {
       }
       if (ok) { rec.path = PATH_ROW2D; rec.rflags |= RF_VEC; }
     }
+    // chunk_elems is quoted for 12 bytes of traffic per element (an fp32 binary op); scale it so
+    // that a chunk of any op moves about the same number of bytes
+    uint64_t traffic = dtype_size(ops[ar].dtype);
+    for (int k = 0; k < ar; ++k) traffic += dtype_size(ops[k].dtype);
+    uint64_t base_per = ((uint64_t)chunk_elems * 12 / traffic + 1023) / 1024 * 1024;
     uint64_t per = ((uint64_t)numel + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
     per = (per + 1023) / 1024 * 1024;
-    if (per < kChunkElems) per = kChunkElems;
+    if (per < base_per) per = base_per;
     rec.chunk = (uint32_t)per;
     rec.nchunks = (uint32_t)(((uint64_t)numel + per - 1) / per);
     *r = rec;
@@ -253,13 +258,14 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r) {
   const bool rows_contig = rows == 1 || (nd == 1 && oo[0].stride[0] == n && oo[1].stride[0] == 1);
   if (!all_int && s_last == 1 && rows_contig && n * 4 < kMaxExtent) {            // a row fits one buffer resource
     rec.path = PATH_RED_CONTIG;
-    if (n % V == 0 && aligned16(ops[0].ptr)) rec.rflags |= RF_VEC;
+    if (aligned16(ops[0].ptr)) rec.rflags |= RF_VEC;    // rows are read as aligned vectors whatever n is
   } else {
     rec.path = PATH_RED_GENERIC;
   }
-  uint64_t rpc = kChunkElems / (uint64_t)n;
+  // same traffic per chunk as an elementwise chunk: chunk_elems * 12 bytes of input rows
+  uint64_t rpc = (uint64_t)chunk_elems * 12 / ((uint64_t)n * dtype_size(ops[0].dtype));
   if (rpc < 1) rpc = 1;
-  if (n <= 512) rpc = (rpc + 255) / 256 * 256;
+  if (rpc >= 16) rpc = (rpc + 15) / 16 * 16;          // whole passes of the row-per-wave kernels
   const uint64_t min_rpc = ((uint64_t)rows + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
   if (rpc < min_rpc) rpc = min_rpc;
   rec.chunk = (uint32_t)rpc;
@@ -459,6 +465,7 @@ void gpuos_default_config(gpuos_config* cfg) {
   cfg->workgroups_per_cu = 4;
   cfg->wait_timeout_ms = 30000;
   cfg->completion_log = 1u << 20;
+  cfg->chunk_elems = kChunkElems;
 }
 
 int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* user_cfg) {
@@ -471,6 +478,8 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   if (cfg.workgroups_per_cu == 0) cfg.workgroups_per_cu = 4;
   if (cfg.wait_timeout_ms == 0) cfg.wait_timeout_ms = 30000;
   if (cfg.completion_log == 0) cfg.completion_log = 1u << 20;
+  if (cfg.chunk_elems == 0) cfg.chunk_elems = kChunkElems;
+  cfg.chunk_elems = (cfg.chunk_elems + 1023u) / 1024u * 1024u;
   uint32_t cap = queue_capacity ? queue_capacity : 4096u;
   if (cap < 2 || cap > 65536 || (cap & (cap - 1)) != 0) return GPUOS_E_INVAL;
   const char* env_idle = std::getenv("GPUOS_IDLE_EXIT_MS");
@@ -619,9 +628,9 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
     int rc;
     if (impl == GPUOS_IMPL_NONE) {
       if (!c->cfg.defer_op_check) return GPUOS_E_BADOP;
-      rc = pack_task(t, GPUOS_IMPL_FAIL, &staged[i]);             // the device reports the bad op id
+      rc = pack_task(t, GPUOS_IMPL_FAIL, &staged[i], c->cfg.chunk_elems);   // the device reports the bad op id
     } else {
-      rc = pack_task(t, impl, &staged[i]);
+      rc = pack_task(t, impl, &staged[i], c->cfg.chunk_elems);
     }
     if (rc != GPUOS_OK) return rc;
     for (int k = 0; k < 3; ++k) {
@@ -722,6 +731,14 @@ int gpuos_worker_elapsed_ms(gpuos_ctx* c, float* out_ms) {
   if (!c || !out_ms) return GPUOS_E_INVAL;
   if (!c->worker_joined) return GPUOS_E_INVAL;
   HIP_TRY(hipEventElapsedTime(out_ms, c->ev_start, c->ev_stop));
+  return GPUOS_OK;
+}
+
+int gpuos_worker_stats(gpuos_ctx* c, uint64_t out[16]) {
+  if (!c || !out) return GPUOS_E_INVAL;
+  if (!c->worker_joined) return GPUOS_E_INVAL;
+  HIP_TRY(hipSetDevice(c->device));
+  HIP_TRY(hipMemcpy(out, c->d->stat, sizeof(uint64_t) * 16, hipMemcpyDeviceToHost));
   return GPUOS_OK;
 }
 

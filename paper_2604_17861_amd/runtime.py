@@ -30,7 +30,8 @@ class Config(ctypes.Structure):
                 ("workgroups_per_cu", ctypes.c_uint32), ("nonblocking_submit", ctypes.c_uint32),
                 ("harvester_thread", ctypes.c_uint32), ("defer_op_check", ctypes.c_uint32),
                 ("idle_exit_ms", ctypes.c_uint32), ("wait_timeout_ms", ctypes.c_uint32),
-                ("completion_log", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 7)]
+                ("completion_log", ctypes.c_uint32), ("chunk_elems", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32 * 6)]
 
 
 class QueueState(ctypes.Structure):
@@ -78,6 +79,7 @@ def lib():
         "gpuos_shutdown": (ctypes.c_int, [vp]),
         "gpuos_stop_worker": (ctypes.c_int, [vp]),
         "gpuos_worker_elapsed_ms": (ctypes.c_int, [vp, P(ctypes.c_float)]),
+        "gpuos_worker_stats": (ctypes.c_int, [vp, vp]),
         "gpuos_launch_per_op": (ctypes.c_int, [i32, vp, u32, vp, i32, vp, P(ctypes.c_double)]),
         "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
         "gpuos_strerror": (ctypes.c_char_p, [ctypes.c_int]),
@@ -95,7 +97,7 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_strerror",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
 
@@ -214,6 +216,17 @@ class Runtime:
         ms = ctypes.c_float()
         _check(lib().gpuos_worker_elapsed_ms(self._ctx, ctypes.byref(ms)), "gpuos_worker_elapsed_ms")
         return ms.value
+
+    STAT_NAMES = ["disp_batches", "disp_records", "disp_units", "disp_ticks_stage", "disp_ticks_resolve",
+                  "disp_ticks_write", "disp_ticks_busy", "disp_polls", "work_units", "work_ticks_wait",
+                  "work_ticks_fetch", "work_ticks_dep", "work_ticks_exec", "work_ticks_complete",
+                  "work_ticks_total", "reserved"]
+
+    def worker_stats(self):
+        """Counters of the persistent kernel (after stop_worker); ticks are 10 ns."""
+        out = np.zeros(16, dtype=np.uint64)
+        _check(lib().gpuos_worker_stats(self._ctx, out.ctypes.data), "gpuos_worker_stats")
+        return dict(zip(self.STAT_NAMES, (int(x) for x in out)))
 
     def shutdown(self, check=True):
         if not self._ctx:
