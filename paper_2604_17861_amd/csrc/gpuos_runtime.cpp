@@ -552,7 +552,13 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   {
     const uint64_t t0 = now_ns();
     while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
-      if (now_ns() - t0 > c->wait_ns) { (void)stop_worker(c); return fail(GPUOS_E_TIMEOUT); }
+      if (now_ns() - t0 > c->wait_ns) {
+        // The kernel never started (its hardware queue is busy).  Ask it to exit as soon as it
+        // does; if it still has not finished, keep its memory alive: freeing under a queued
+        // kernel would fault when it finally runs.
+        if (stop_worker(c) == GPUOS_E_TIMEOUT) return GPUOS_E_TIMEOUT;
+        return fail(GPUOS_E_TIMEOUT);
+      }
       if (hipStreamQuery(c->stream) != hipErrorNotReady) { return fail(GPUOS_E_DEAD); }
       __builtin_ia32_pause();
     }

@@ -1,0 +1,275 @@
+"""GPU tests of the queue protocol, the operator table and failure handling.  Every wait is bounded
+(wait_timeout_ms) and every kernel exits normally; error conditions are forced from the host."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_17861_amd import runtime as R
+from paper_2604_17861_amd import streams as S
+from helpers import Builder, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+CFG = dict(idle_exit_ms=20000, wait_timeout_ms=20000)
+
+
+def _dev(stream):
+    from gpu_helpers import DevicePools
+    return DevicePools(stream)
+
+
+def _simple_adds(n_tasks, numel, seed=0):
+    s = S.config1(n_tasks=n_tasks, numel=numel, seed=seed)
+    return s
+
+
+def test_tiny_ring_wraps_and_back_pressures():
+    """Capacity 4 and 16: hundreds of laps of the ring, blocking back-pressure, single- and
+    multi-chunk tasks; results bit-exact."""
+    from gpu_helpers import compare_with_oracle
+    for cap, numel in ((4, 1024), (16, 50000), (2, 300)):
+        print("ring capacity", cap, flush=True)
+        s = _simple_adds(600, numel, seed=cap)
+        dp = _dev(s)
+        with R.Runtime(cap, **CFG) as rt:
+            rt.register_table(s.table)
+            for i in range(0, len(s), 7):                      # batches larger than the ring
+                rt.submit(dp.tasks, i, min(7, len(s) - i))
+            rt.wait()
+            q = rt.peek_queue()
+            assert q.capacity == cap and q.completed == 600 and q.head_submitted == 600 and q.claimed == 600
+            comps = rt.completions(0, 600)
+        assert np.all(comps["status"] == 0)
+        stats = compare_with_oracle(s, dp.download())
+        assert stats["max_ulp"] == 0
+
+
+def test_nonblocking_submit_reports_full_and_enqueues_nothing():
+    s = _simple_adds(64, 1 << 16)
+    dp = _dev(s)
+    with R.Runtime(8, nonblocking_submit=1, **CFG) as rt:
+        rt.register_table(s.table)
+        rc, _ = rt.submit(dp.tasks, 0, 9, check=False)           # more than the whole ring
+        assert rc == R.E_FULL
+        assert rt.peek_queue().head_submitted == 0
+        rc, t0 = rt.submit(dp.tasks, 0, 8, check=False)
+        assert rc == R.OK and t0 == 0
+        rt.wait()
+        rc, t1 = rt.submit(dp.tasks, 8, 8, check=False)
+        assert rc == R.OK and t1 == 8
+        rt.wait()
+
+
+def test_malformed_descriptors_are_rejected_before_anything_is_enqueued():
+    s = _simple_adds(8, 1024)
+    dp = _dev(s)
+    with R.Runtime(0, **CFG) as rt:
+        rt.register_table(s.table)
+        def bad(mutate):
+            t = dp.tasks.copy()
+            mutate(t)
+            rc, _ = rt.submit(t, 0, 8, check=False)
+            assert rt.peek_queue().head_submitted == 0, "a rejected batch must leave the ring untouched"
+            return rc
+        assert bad(lambda t: t["ndim"].__setitem__(5, 7)) == R.E_INVAL
+        assert bad(lambda t: t["ndim"].__setitem__(0, 0)) == R.E_INVAL
+        assert bad(lambda t: t["inp"]["stride"].__setitem__((3, 0, 0), -1)) == R.E_INVAL
+        assert bad(lambda t: t["out"]["stride"].__setitem__((7, 0), 0)) == R.E_INVAL
+        assert bad(lambda t: t["out"]["bcast_mask"].__setitem__(2, 1)) == R.E_INVAL
+        assert bad(lambda t: t["inp"]["ptr"].__setitem__((4, 1), 0)) == R.E_INVAL
+        assert bad(lambda t: t["inp"]["dtype"].__setitem__((4, 1), S.I32)) == R.E_INVAL
+        assert bad(lambda t: t["n_inputs"].__setitem__(1, 1)) == R.E_INVAL
+        assert bad(lambda t: t["flags"].__setitem__(1, 64)) == R.E_INVAL
+        assert bad(lambda t: t["dep"].__setitem__((0, 0), 1)) == R.E_INVAL          # before ticket 0
+        assert bad(lambda t: t["dep"].__setitem__((7, 2), 4096)) == R.E_INVAL       # >= capacity
+        assert bad(lambda t: t["op_id"].__setitem__(6, 200)) == R.E_BADOP           # never registered
+        assert bad(lambda t: t["op_id"].__setitem__(6, 300)) == R.E_BADOP           # out of range
+        assert bad(lambda t: t["size"].__setitem__((6, 0), 1 << 31)) == R.E_INVAL
+        rt.submit(dp.tasks)                                                          # the intact batch still runs
+        rt.wait()
+        assert rt.wait(3) == R.OK
+        assert rt.wait(8, check=False) == R.E_INVAL                                  # never submitted
+        with pytest.raises(R.GpuosError):
+            rt.register_op(S.OP["ADD"], S.IMPL["MUL"])                               # already bound
+        with pytest.raises(R.GpuosError):
+            rt.swap_op(S.OP["ADD"], S.IMPL["RELU"])                                  # arity differs
+        with pytest.raises(R.GpuosError):
+            rt.swap_op(199, S.IMPL["RELU"])                                          # unregistered
+        with pytest.raises(R.GpuosError):
+            rt.register_op(300, S.IMPL["RELU"])
+
+
+def test_device_bounds_check_reports_bad_op_ids():
+    """With the host-side op check deferred, the device rejects unknown and out-of-range op ids at
+    claim time and reports them; neighbours are unaffected."""
+    from gpu_helpers import compare_with_oracle
+    s = _simple_adds(40, 2048)
+    dp = _dev(s)
+    t = dp.tasks.copy()
+    t["op_id"][5] = 200
+    t["op_id"][17] = 999
+    with R.Runtime(0, defer_op_check=1, **CFG) as rt:
+        rt.register_table(s.table)
+        rt.submit(t)
+        assert rt.wait(check=False) == R.E_BADOP
+        c = rt.completions(0, 40)
+        assert rt.wait(5, check=False) == R.E_BADOP and rt.wait(6, check=False) == R.OK
+    bad = np.zeros(40, bool); bad[[5, 17]] = True
+    assert np.all(c["status"][bad] == R.E_BADOP) and np.all(c["status"][~bad] == 0)
+    imgs = dp.download()
+    out = imgs[2].view(np.float32).reshape(40, 2048)
+    assert not out[5].any() and not out[17].any()                 # rejected tasks wrote nothing
+    keep = np.nonzero(~bad)[0]
+    for i in keep[:3]:
+        a = imgs[0].view(np.float32).reshape(40, 2048)[i]; b = imgs[1].view(np.float32).reshape(40, 2048)[i]
+        assert np.array_equal(out[i], a + b)
+
+
+def test_kill_switch_fails_fast_and_can_be_lifted():
+    s = _simple_adds(30, 4096)
+    dp = _dev(s)
+    with R.Runtime(0, **CFG) as rt:
+        rt.register_table(s.table)
+        rt.submit(dp.tasks, 0, 10); rt.wait()
+        v = rt.swap_op(S.OP["ADD"], S.IMPL["FAIL"])
+        assert v == 2
+        rt.submit(dp.tasks, 10, 10)
+        assert rt.wait(check=False) == R.E_BADOP
+        v = rt.swap_op(S.OP["ADD"], S.IMPL["ADD"])
+        assert v == 3
+        rt.submit(dp.tasks, 20, 10); rt.wait()
+        c = rt.completions(0, 30)
+    assert np.all(c["status"][:10] == 0) and np.all(c["status"][10:20] == R.E_BADOP) and np.all(c["status"][20:] == 0)
+    assert c["op_version"].tolist() == [1] * 10 + [2] * 10 + [3] * 10
+    out = dp.download()[2].view(np.float32).reshape(30, 4096)
+    assert out[:10].any(axis=1).all() and not out[10:20].any() and out[20:].any(axis=1).all()
+
+
+@pytest.mark.parametrize("numel", [4096, 100003])
+def test_dependency_chain_hand_offs(numel):
+    """x_{i+1} = x_i + 1 through 1500 dependent tasks (single- and multi-chunk): every hand-off crosses
+    workgroups and XCDs; the result is exact only if each task saw its predecessor's output."""
+    n = 1500
+    b = Builder()
+    buf = b.pool(np.zeros((n + 1, numel), np.float32))
+    buf[0] = np.arange(numel, dtype=np.float32) % 97
+    ones = b.pool(np.ones(numel, np.float32))
+    for i in range(n):
+        b.add("ADD", buf[i + 1], [buf[i], ones], dep=(1 if i else 0, 0, 0))
+    s = b.stream()
+    dp = _dev(s)
+    with R.Runtime(0, **CFG) as rt:
+        rt.register_table(s.table)
+        rt.submit(dp.tasks); rt.wait()
+    out = dp.download()[0].view(np.float32).reshape(n + 1, numel)
+    assert np.array_equal(out[n], out[0] + n)
+    assert np.array_equal(out[n // 2], out[0] + n // 2)
+
+
+def test_fence_and_in_place_updates():
+    """40 independent tasks write rows; a FENCE task then sums over all rows; in-place SCALE on the
+    result depends on it."""
+    b = Builder()
+    rows = b.pool(np.zeros((40, 3000), np.float32))
+    src = b.pool(np.random.default_rng(1).standard_normal((40, 3000)).astype(np.float32))
+    tot = b.pool(np.zeros(3000, np.float32))
+    for i in range(40):
+        b.add("SCALE", rows[i], [src[i]], alpha=2.0)
+    b.add("SUM_LAST", tot, [rows.T], flags=S.FLAG_FENCE)          # column sums need every row
+    b.add("SCALE", tot, [tot], alpha=0.5, dep=(1, 0, 0))            # in place
+    s = b.stream()
+    dp = _dev(s)
+    with R.Runtime(0, **CFG) as rt:
+        rt.register_table(s.table)
+        rt.submit(dp.tasks); rt.wait()
+    imgs = dp.download()
+    hp, st = run_oracle(s)
+    assert np.array_equal(imgs[0], hp.arrays[0])
+    np.testing.assert_allclose(imgs[2].view(np.float32), hp.arrays[2].view(np.float32), rtol=1e-5, atol=1e-5)
+
+
+def test_introspection_yield_policy_and_stats():
+    s = _simple_adds(200, 8192)
+    dp = _dev(s)
+    with R.Runtime(0, **CFG) as rt:
+        assert rt.worker_alive()
+        q = rt.peek_queue()
+        assert q.capacity == 4096 and q.workgroups >= 256 and q.head_submitted == 0 and q.heartbeat > 0
+        rt.register_table(s.table)
+        rt.set_yield_every(4)                                       # workers pause on every 4th empty poll
+        rt.submit(dp.tasks, 0, 100, flush=False)
+        assert rt.peek_queue().tail_published == 0 and rt.peek_queue().head_submitted == 100
+        rt.flush()
+        rt.wait()
+        rt.set_yield_every(0)
+        rt.submit(dp.tasks, 100, 100); rt.wait()
+        q = rt.peek_queue()
+        assert q.completed == 200 and q.claimed == 200 and q.tail_published == 200
+        assert rt.worker_alive()
+        c = rt.completions(0, 200)
+        assert np.all(c["t_done_ns"] >= c["t_submit_ns"]) and np.all(c["t_submit_ns"] > 0)
+        rt.stop_worker()
+        assert not rt.worker_alive()
+        st = rt.worker_stats()
+        assert st["work_units"] == 200 and st["disp_records"] == 200 and st["work_ticks_exec"] > 0
+        assert rt.worker_elapsed_ms() > 0
+        rc, _ = rt.submit(dp.tasks, 0, 1, check=False)
+        assert rc == R.E_DEAD
+    from gpu_helpers import compare_with_oracle
+    assert compare_with_oracle(s, dp.download())["max_ulp"] == 0
+
+
+def test_shutdown_drains_tasks_in_flight_and_is_idempotent():
+    s = _simple_adds(3000, 30000)
+    dp = _dev(s)
+    rt = R.Runtime(0, **CFG)
+    rt.register_table(s.table)
+    rt.submit(dp.tasks)                          # no wait: shutdown has to drain
+    assert rt.shutdown() == R.OK
+    assert rt.shutdown() == R.OK                 # second call is a no-op
+    from gpu_helpers import compare_with_oracle
+    assert compare_with_oracle(s, dp.download())["max_ulp"] == 0
+
+
+def test_idle_watchdog_exits_the_worker():
+    s = _simple_adds(4, 1024)
+    dp = _dev(s)
+    with R.Runtime(0, idle_exit_ms=200, wait_timeout_ms=5000) as rt:
+        rt.register_table(s.table)
+        rt.submit(dp.tasks, 0, 2); rt.wait()
+        time.sleep(0.6)
+        assert not rt.worker_alive()
+        rc, _ = rt.submit(dp.tasks, 2, 2, check=False)
+        assert rc == R.E_DEAD
+
+
+def test_per_op_launch_path_matches_the_oracle():
+    """The comparison path (one ordinary launch per task) runs the same stream to the same results."""
+    import parity_cases as C
+    from gpu_helpers import compare_with_oracle
+    for s in (C.config2_reduced(), S.config3(n_chains=3, buffer_sets=1, Bs=(1, 2), Ss=(64, 128)),
+              C.config5_reduced()):
+        dp = _dev(s)
+        secs, lat = R.launch_per_op(dp.tasks, s.table, sync_each=False)
+        torch.cuda.synchronize()
+        stats = compare_with_oracle(s, dp.download())
+        print(s.name, stats, "%.1f ms" % (secs * 1e3), flush=True)
+    s = _simple_adds(50, 1024)
+    dp = _dev(s)
+    secs, lat = R.launch_per_op(dp.tasks, s.table, sync_each=True)
+    assert len(lat) == 50 and np.all(lat > 0)
+
+
+def test_two_contexts_side_by_side():
+    s1, s2 = _simple_adds(300, 5000, seed=1), _simple_adds(300, 5000, seed=2)
+    d1, d2 = _dev(s1), _dev(s2)
+    from gpu_helpers import compare_with_oracle
+    with R.Runtime(64, workgroups_per_cu=1, **CFG) as a, R.Runtime(64, workgroups_per_cu=1, **CFG) as b:
+        a.register_table(s1.table); b.register_table(s2.table)
+        for i in range(0, 300, 50):
+            a.submit(d1.tasks, i, 50); b.submit(d2.tasks, i, 50)
+        a.wait(); b.wait()
+    assert compare_with_oracle(s1, d1.download())["max_ulp"] == 0
+    assert compare_with_oracle(s2, d2.download())["max_ulp"] == 0
