@@ -140,12 +140,31 @@ def bench_roofline(R, stream, dp, impls):
     return dict(bytes=nbytes, wall_s=wall, kernel_ms=kernel_ms, workgroups=wg)
 
 
+def measured_traffic(n_tasks):
+    """HBM bytes of the persistent kernel over the bandwidth stream as measured with rocprofv3
+    counters (summary under profiles/, from two --pmc runs scaled by a copy kernel of known
+    size); None if no measurement for this task count is on file."""
+    path = os.path.join(ROOT, "profiles", "gpuos_worker_kernel_config5_hbm_traffic.md")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "tasks:" and f[2] == "hbm_bytes_per_launch:" and int(f[1]) == n_tasks:
+                return int(f[3])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-extras", action="store_true", help="only the headline stream and the roofline leg")
+    ap.add_argument("--only-roofline", action="store_true",
+                    help="run nothing but the bandwidth stream through the persistent kernel (for profiler runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run one ordinary COPY kernel over 1 GiB (counter calibration for profiler runs) and exit")
     ap.add_argument("--cfg5-tasks", type=int, default=20000)
     ap.add_argument("--cfg4-tasks", type=int, default=1000000)
     args = ap.parse_args()
@@ -164,7 +183,31 @@ def main():
     log("device:", prop.name, "CUs:", prop.multi_processor_count, "mem GiB: %.0f" % (prop.total_memory / 2 ** 30))
     log("host cores:", os.cpu_count(), "affinity:", len(os.sched_getaffinity(0)))
 
+    if args.copy_calibration:
+        n = 1 << 28                                            # 1 GiB of fp32 in, 1 GiB out
+        src = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty(n, dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        t, pool_of = S.new_tasks(1)
+        S.set_head(t, 0, S.OP["COPY"], [n], 1)
+        S.set_tensor(t, pool_of, 0, 0, 0, src.data_ptr(), [1], S.F32)
+        S.set_tensor(t, pool_of, 0, 3, 0, dst.data_ptr(), [1], S.F32)
+        for _ in range(3):
+            secs, _ = R.launch_per_op(t, S.default_table())
+        print(json.dumps(dict(calibration="one gpuos_single_task_kernel COPY launch", read_bytes=4 * n, write_bytes=4 * n,
+                              seconds=secs, gbps=8 * n / secs / 1e9)), flush=True)
+        return
+
     out = {}
+    if args.only_roofline:
+        s5 = S.config5(n_tasks=args.cfg5_tasks)
+        dp5 = DevicePools(s5, torch)
+        rf = bench_roofline(R, s5, dp5, s5.impl_for())
+        achieved = rf["bytes"] / (rf["kernel_ms"] * 1e-3) / 1e9
+        print(json.dumps(dict(workload="config5: %d bandwidth tasks" % len(s5), roofline=dict(
+            bound="hbm", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
+            kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"], algorithmic_bytes=rf["bytes"]))), flush=True)
+        return
     # ---- headline: second configuration --------------------------------------------------
     s2 = S.config2()
     dp2 = DevicePools(s2, torch)
@@ -231,7 +274,7 @@ def main():
     extras["config5"] = dict(persistent_gbps_wall=rf["bytes"] / rf["wall_s"] / 1e9, per_launch_gbps=float(pl5),
                              tasks=len(s5), tasks_per_s=len(s5) / rf["wall_s"])
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
-                    traffic=None, kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"],
+                    traffic=measured_traffic(len(s5)), kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"],
                     algorithmic_bytes=rf["bytes"], workload="config5: %d bandwidth tasks" % len(s5))
     del dp5
 
