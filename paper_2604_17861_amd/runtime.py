@@ -58,6 +58,13 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
+    try:
+        # PyTorch ships its own copy of the HIP runtime.  If this library were loaded first it would
+        # bring in the system copy, and the process would end up with two runtimes that do not see
+        # each other's devices and streams.  Loading torch first makes both use the same one.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             LIB_PATH + " is not built; run `python -m paper_2604_17861_amd.build` (there is no CPU fallback)")
