@@ -247,6 +247,20 @@ def main():
                                  speedup=r1["tasks_per_s"] / pl1, p50_us=r1["p50_us"], p99_us=r1["p99_us"])
         log("config1:", extras["config1"])
         del dp1
+        # ---- third configuration (dependent softmax chains) -------------------------------------
+        s3 = S.config3()
+        dp3 = DevicePools(s3, torch)
+        b3 = int(R.task_bytes(dp3.tasks, s3.impl_for()).sum())
+        r3 = bench_persistent(R, s3, dp3, 2, 1)
+        R.launch_per_op(dp3.tasks, s3.table, count=1200)
+        t0 = time.perf_counter()
+        R.launch_per_op(dp3.tasks, s3.table)
+        pl3 = time.perf_counter() - t0
+        extras["config3"] = dict(persistent_tasks_per_s=r3["tasks_per_s"], per_launch_tasks_per_s=len(s3) / pl3,
+                                 speedup=r3["tasks_per_s"] / (len(s3) / pl3), persistent_gbps=b3 * r3["tasks_per_s"] / len(s3) / 1e9,
+                                 per_launch_gbps=b3 / pl3 / 1e9, chains=len(s3) // 6)
+        log("config3:", extras["config3"])
+        del dp3
         # ---- fourth configuration (hot swaps while running) -----------------------------------
         s4 = S.config4(n_tasks=args.cfg4_tasks)
         dp4 = DevicePools(s4, torch)

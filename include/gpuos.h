@@ -228,7 +228,8 @@ int gpuos_shutdown(gpuos_ctx* ctx);
  * units, then dispatcher time staging / resolving / writing / busy in 10 ns ticks,
  * dispatcher polls; then summed over all worker workgroups: work units executed
  * and 10 ns ticks spent waiting for work, fetching descriptors, waiting for
- * dependencies, executing, completing, and alive in total; out[15] is 0. */
+ * dependencies, executing, completing, and alive in total; out[15]: tasks the
+ * dispatcher held back until their dependencies had completed. */
 int gpuos_worker_stats(gpuos_ctx* ctx, uint64_t out[16]);
 
 /* Milliseconds the worker kernel ran, from HIP events on its stream (valid

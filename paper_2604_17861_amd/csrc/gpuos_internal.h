@@ -28,7 +28,8 @@ enum Path : uint8_t {
 enum RecFlag : uint8_t {
   RF_FENCE = 1,          // dispatcher: publish only after every earlier ticket is done
   RF_VEC = 2,            // 16-byte vector access is safe (alignment and extents checked)
-  RF_INT = 4             // all tensors are I32
+  RF_INT = 4,            // all tensors are I32
+  RF_DEPS_RESOLVED = 8   // set by the dispatcher: published only after the dependencies completed
 };
 
 enum OperandKind : uint8_t { K_FULL = 0, K_ROWVEC = 1, K_ROWSCALAR = 2, K_TRANSPOSED = 3 };
@@ -110,7 +111,7 @@ enum StatIndex {
   ST_DISP_BATCHES = 0, ST_DISP_RECORDS, ST_DISP_UNITS, ST_DISP_TICKS_STAGE, ST_DISP_TICKS_RESOLVE,
   ST_DISP_TICKS_WRITE, ST_DISP_TICKS_TOTAL_BUSY, ST_DISP_POLLS,
   ST_WORK_UNITS = 8, ST_WORK_TICKS_WAIT, ST_WORK_TICKS_FETCH, ST_WORK_TICKS_DEP, ST_WORK_TICKS_EXEC,
-  ST_WORK_TICKS_COMPLETE, ST_WORK_TICKS_TOTAL
+  ST_WORK_TICKS_COMPLETE, ST_WORK_TICKS_TOTAL, ST_DISP_DEFERRED
 };
 
 struct SlotState {                   // device memory, one per ring slot

@@ -282,8 +282,10 @@ DEV void ew_contig_int(const Record* r, uint32_t begin, uint32_t end) {
 // width; each input is a full [R, C] tensor (dtype DT), a row vector [C]
 // broadcast over rows (dtype DT), or one scalar per row (any float dtype).
 // ---------------------------------------------------------------------------
+constexpr uint32_t kScratchFloats = 2048;   // LDS scratch per workgroup (broadcast staging, reduction partials)
+
 template <int POL, int IMPL, int DT>
-DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
+DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end, float* s_scratch) {
   using E = Elem<DT>;
   using M = Mem<POL>;
   constexpr int V = E::V, N = Op<IMPL>::N;
@@ -293,6 +295,7 @@ DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
   rsrc_t rs[3];
   const uint32_t nvec = (end - begin) / V;
   const uint64_t boff = (uint64_t)begin * E::ES;
+  uint32_t n_scalar = 0;
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
     const int kk = k < N ? k : 0;
@@ -302,18 +305,37 @@ DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
     st0[k] = uni(r->stride[kk][0]);
     // full operands: rebased to the chunk; row vectors: the whole vector
     rs[k] = kind[k] == K_FULL ? make_rsrc(p[k] + boff, nvec * 16u) : make_rsrc(p[k], C * E::ES);
+    if (k < N && kind[k] == K_ROWSCALAR) ++n_scalar;
   }
   const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + boff, nvec * 16u);
   const float alpha = r->alpha;
+  // Per-row scalars (x - rowmax, e / rowsum): the rows of this chunk are gathered once into LDS
+  // with coalesced loads and broadcast from there; without the staging every 16-byte vector would
+  // cost one more uncached 4-byte memory request.
+  const uint32_t row_first = begin / C, row_cnt = (end - 1) / C - row_first + 1;
+  const bool staged = n_scalar != 0 && row_cnt * n_scalar <= kScratchFloats;
+  if (staged) {
+    uint32_t region = 0;
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+      if (kind[k] == K_ROWSCALAR) {
+        for (uint32_t t = threadIdx.x; t < row_cnt; t += kThreads)
+          s_scratch[region + t] = load_rt<POL>(p[k], (row_first + t) * st0[k], dt[k]);
+        region += row_cnt;
+      }
+    __syncthreads();
+  }
   for (uint32_t v = threadIdx.x; v < nvec; v += kThreads) {
     const uint32_t i = begin + v * V;
     const uint32_t row = i / C, col = i - row * C;
     v4i q[3];
     float s[3];
+    uint32_t region = 0;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
       if (kind[k] == K_FULL) q[k] = M::ld16(rs[k], v * 16u);
       else if (kind[k] == K_ROWVEC) q[k] = M::ld16(rs[k], col * E::ES);
+      else if (staged) { s[k] = s_scratch[region + row - row_first]; region += row_cnt; }
       else s[k] = load_rt<POL>(p[k], row * st0[k], dt[k]);
     }
     v4i res;
@@ -326,6 +348,7 @@ DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end) {
     }
     M::st16(ro, v * 16u, res);
   }
+  if (staged) __syncthreads();        // the scratch may be reused by the next chunk
 }
 
 // ---------------------------------------------------------------------------
@@ -653,7 +676,7 @@ DEV void red_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
 // precompiled implementations selected by the table entry).
 // ---------------------------------------------------------------------------
 template <int POL, int IMPL>
-DEV void run_elementwise(const Record* r, uint32_t chunk) {
+DEV void run_elementwise(const Record* r, uint32_t chunk, float* s_scratch) {
   const uint32_t per = uni(r->chunk), numel = uni(r->numel);
   const uint32_t begin = chunk * per;
   const uint32_t end = (numel - begin < per) ? numel : begin + per;
@@ -672,9 +695,9 @@ DEV void run_elementwise(const Record* r, uint32_t chunk) {
     else ew_contig<POL, IMPL, GPUOS_BF16>(r, begin, end);
   } else if (path == PATH_ROW2D && Op<IMPL>::N >= 2) {
     constexpr int I2 = Op<IMPL>::N >= 2 ? IMPL : GPUOS_IMPL_ADD;
-    if (dt == GPUOS_F32) ew_row2d<POL, I2, GPUOS_F32>(r, begin, end);
-    else if (dt == GPUOS_F16) ew_row2d<POL, I2, GPUOS_F16>(r, begin, end);
-    else ew_row2d<POL, I2, GPUOS_BF16>(r, begin, end);
+    if (dt == GPUOS_F32) ew_row2d<POL, I2, GPUOS_F32>(r, begin, end, s_scratch);
+    else if (dt == GPUOS_F16) ew_row2d<POL, I2, GPUOS_F16>(r, begin, end, s_scratch);
+    else ew_row2d<POL, I2, GPUOS_BF16>(r, begin, end, s_scratch);
   } else {
     ew_generic<POL, IMPL, false>(r, begin, end);
   }
@@ -701,18 +724,18 @@ template <int POL>
 DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_red) {
   if (uni(r->path) == PATH_NOP) return impl == GPUOS_IMPL_FAIL ? GPUOS_E_BADOP : GPUOS_OK;
   switch (impl) {
-    case GPUOS_IMPL_ADD: run_elementwise<POL, GPUOS_IMPL_ADD>(r, chunk); break;
-    case GPUOS_IMPL_SUB: run_elementwise<POL, GPUOS_IMPL_SUB>(r, chunk); break;
-    case GPUOS_IMPL_MUL: run_elementwise<POL, GPUOS_IMPL_MUL>(r, chunk); break;
-    case GPUOS_IMPL_DIV: run_elementwise<POL, GPUOS_IMPL_DIV>(r, chunk); break;
-    case GPUOS_IMPL_RELU: run_elementwise<POL, GPUOS_IMPL_RELU>(r, chunk); break;
-    case GPUOS_IMPL_EXP: run_elementwise<POL, GPUOS_IMPL_EXP>(r, chunk); break;
-    case GPUOS_IMPL_GELU_ERF: run_elementwise<POL, GPUOS_IMPL_GELU_ERF>(r, chunk); break;
-    case GPUOS_IMPL_GELU_TANH: run_elementwise<POL, GPUOS_IMPL_GELU_TANH>(r, chunk); break;
-    case GPUOS_IMPL_SCALE: run_elementwise<POL, GPUOS_IMPL_SCALE>(r, chunk); break;
-    case GPUOS_IMPL_FMA: run_elementwise<POL, GPUOS_IMPL_FMA>(r, chunk); break;
-    case GPUOS_IMPL_SUB_EXP: run_elementwise<POL, GPUOS_IMPL_SUB_EXP>(r, chunk); break;
-    case GPUOS_IMPL_COPY: run_elementwise<POL, GPUOS_IMPL_COPY>(r, chunk); break;
+    case GPUOS_IMPL_ADD: run_elementwise<POL, GPUOS_IMPL_ADD>(r, chunk, s_red); break;
+    case GPUOS_IMPL_SUB: run_elementwise<POL, GPUOS_IMPL_SUB>(r, chunk, s_red); break;
+    case GPUOS_IMPL_MUL: run_elementwise<POL, GPUOS_IMPL_MUL>(r, chunk, s_red); break;
+    case GPUOS_IMPL_DIV: run_elementwise<POL, GPUOS_IMPL_DIV>(r, chunk, s_red); break;
+    case GPUOS_IMPL_RELU: run_elementwise<POL, GPUOS_IMPL_RELU>(r, chunk, s_red); break;
+    case GPUOS_IMPL_EXP: run_elementwise<POL, GPUOS_IMPL_EXP>(r, chunk, s_red); break;
+    case GPUOS_IMPL_GELU_ERF: run_elementwise<POL, GPUOS_IMPL_GELU_ERF>(r, chunk, s_red); break;
+    case GPUOS_IMPL_GELU_TANH: run_elementwise<POL, GPUOS_IMPL_GELU_TANH>(r, chunk, s_red); break;
+    case GPUOS_IMPL_SCALE: run_elementwise<POL, GPUOS_IMPL_SCALE>(r, chunk, s_red); break;
+    case GPUOS_IMPL_FMA: run_elementwise<POL, GPUOS_IMPL_FMA>(r, chunk, s_red); break;
+    case GPUOS_IMPL_SUB_EXP: run_elementwise<POL, GPUOS_IMPL_SUB_EXP>(r, chunk, s_red); break;
+    case GPUOS_IMPL_COPY: run_elementwise<POL, GPUOS_IMPL_COPY>(r, chunk, s_red); break;
     case GPUOS_IMPL_SUM_LAST: run_reduction<POL, GPUOS_IMPL_SUM_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_MAX_LAST: run_reduction<POL, GPUOS_IMPL_MAX_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_MIN_LAST: run_reduction<POL, GPUOS_IMPL_MIN_LAST>(r, chunk, s_red); break;
@@ -724,13 +747,44 @@ DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_
 
 // ---------------------------------------------------------------------------
 // dispatcher (workgroup 0)
+//
+// Besides mirroring the host ring it is the scheduler of dependent work: units
+// are claimed in publication order and a worker that claimed a unit whose
+// dependency is not complete can only wait, so a large dependent task published
+// too early would park hundreds of workgroups while ready work of other chains
+// sits behind it.  A task with more than kSmallTaskChunks chunks whose
+// dependencies are not complete when it is dequeued is therefore held on a
+// pending list and its units are published when the done words say so; small
+// dependent tasks are published at once (their few workgroups wait on the done
+// word, which is the shortest hand-off for sequential chains of small ops).
 // ---------------------------------------------------------------------------
+constexpr uint32_t kPendMax = 128;         // tasks held back at a time
+constexpr uint64_t kLookaheadUnits = 8192; // work units kept published ahead of the claim counter
+constexpr uint32_t kSmallTaskChunks = 4;
+
+struct PubEntry {                          // what it takes to publish a task's work units
+  uint32_t slot;
+  uint32_t nchunks;
+  uint32_t opinfo;                         // op id | table slot << 8 | valid << 9
+  uint32_t pad;
+};
+struct PendEntry {
+  uint64_t ticket;
+  PubEntry pub;
+  uint16_t dep[3];
+  uint16_t pad;
+};
+
 struct DispShared {
-  Record rec[kDispatchBatch];          // 16 KB staging of the batch being mirrored
-  uint64_t entry[GPUOS_MAX_OPS];       // shadow of the device table: current {impl, version}
-  uint32_t ubeg[kDispatchBatch + 1];   // exclusive prefix of nchunks
+  Record rec[kDispatchBatch];              // 16 KB staging of the batch being mirrored
+  uint64_t entry[GPUOS_MAX_OPS];           // shadow of the device table: current {impl, version}
+  PubEntry pub[kDispatchBatch];            // tasks whose units are published in this pass (<= 64)
+  uint32_t ubeg[kDispatchBatch + 1];       // exclusive prefix of their nchunks
+  PendEntry pend[kPendMax];
+  uint32_t defer[kDispatchBatch];          // per record of the batch: held back
+  uint32_t ready[kPendMax];                // per pending entry: dependencies complete
   uint64_t tail, epoch_word;
-  uint32_t n;
+  uint32_t n, npend, npub;
 };
 
 DEV void dispatcher_refresh_table(const WorkerArgs& a, DispShared* s, uint32_t only_op) {
@@ -751,25 +805,101 @@ DEV void dispatcher_refresh_table(const WorkerArgs& a, DispShared* s, uint32_t o
   }
 }
 
+DEV bool deps_complete(const WorkerArgs& a, uint64_t ticket, const uint16_t* dep) {
+  bool ok = true;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const uint32_t back = dep[k];
+    if (back != 0 && back <= ticket) {
+      const uint64_t want = ticket - back + 1;
+      ok = ok && __hip_atomic_load(&a.st[(ticket - back) & a.cap_mask].done_seq, __ATOMIC_RELAXED, SC_SYSTEM) >= want;
+    }
+  }
+  return ok;
+}
+
+// Write the work units of s->pub[0 .. npub) and make them claimable.  Called by the whole
+// workgroup; returns the number of units published.
+DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npub, uint64_t units_w) {
+  const uint32_t tid = threadIdx.x;
+  if (tid < 64) {                                  // wave 0: inclusive scan of nchunks
+    uint32_t v = tid < npub ? s->pub[tid].nchunks : 0u;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t t = __shfl_up(v, off, 64);
+      if ((int)tid >= off) v += t;
+    }
+    if (tid < npub) s->ubeg[tid + 1] = v;
+    if (tid == 0) s->ubeg[0] = 0;
+  }
+  __syncthreads();
+  const uint32_t total = s->ubeg[npub];
+  for (uint32_t u = tid; u < total; u += kThreads) {
+    uint32_t lo = 0, hi = npub;                    // ubeg[lo] <= u < ubeg[hi]
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (s->ubeg[mid] <= u) lo = mid; else hi = mid;
+    }
+    const PubEntry pe = s->pub[lo];
+    __hip_atomic_store(&a.units[(units_w + u) & a.unit_mask],
+                       pack_unit(u - s->ubeg[lo], pe.slot, pe.opinfo & 0xffu, (pe.opinfo >> 8) & 1u, (pe.opinfo >> 9) & 1u),
+                       __ATOMIC_RELAXED, SC_SYSTEM);
+  }
+  drain_stores();                                  // this wave's records and units are in memory
+  __syncthreads();                                 // ... and so are every other wave's
+  if (tid == 0 && total != 0)
+    __hip_atomic_store(&a.d->tail_units, units_w + total, __ATOMIC_RELAXED, SC_SYSTEM);   // publish
+  return total;
+}
+
+// Publish the pending tasks whose dependencies have completed.  Returns the units published.
+DEV uint32_t dispatcher_service_pending(const WorkerArgs& a, DispShared* s, uint64_t units_w) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t np = s->npend;
+  if (np == 0) return 0;
+  if (tid < np) s->ready[tid] = deps_complete(a, s->pend[tid].ticket, s->pend[tid].dep) ? 1u : 0u;
+  __syncthreads();
+  if (tid == 0) {                                  // split into ready (at most 64 per call) / still pending
+    uint32_t k = 0, j = 0;
+    for (uint32_t i = 0; i < np; ++i) {
+      if (s->ready[i] && k < kDispatchBatch) s->pub[k++] = s->pend[i].pub;   // the rest waits for the next call
+      else { if (j != i) s->pend[j] = s->pend[i]; ++j; }
+    }
+    s->npub = k;
+    s->npend = j;
+  }
+  __syncthreads();
+  const uint32_t npub = s->npub;
+  if (npub == 0) return 0;
+  order_loads();
+  return dispatcher_publish(a, s, npub, units_w);
+}
+
 DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   const uint32_t tid = threadIdx.x;
   uint64_t mirrored = 0, units_w = 0, seen_epoch = 0;
   for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) s->entry[op] = 0;
+  if (tid == 0) s->npend = 0;
   __syncthreads();
   uint64_t idle_since = wall_clock64();
   uint64_t polls = 0;
   bool stopping = false;
   uint64_t st_batches = 0, st_records = 0, st_units = 0, st_stage = 0, st_resolve = 0, st_write = 0, st_busy = 0;
+  uint64_t st_deferred = 0;
+  uint64_t claimed = 0;                    // last value read from the claim counter (thread 0)
+  const rsrc_t rh = make_rsrc(a.hring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
+  const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   while (true) {
     // ---- poll the host ring (one lane; the only PCIe poller of the kernel) ----
     if (tid == 0) {
       uint64_t t, e;
+      const bool have_pending = s->npend != 0;
       while (true) {
         t = __hip_atomic_load(&a.h->tail, __ATOMIC_RELAXED, SC_SYSTEM);
         e = __hip_atomic_load(&a.h->epoch_word, __ATOMIC_RELAXED, SC_SYSTEM);
         ++polls;
         if ((polls & 63u) == 0) __hip_atomic_store(&a.h->heartbeat, polls, __ATOMIC_RELAXED, SC_SYSTEM);
-        if (t != mirrored || e != seen_epoch || stopping) break;
+        if (t != mirrored || e != seen_epoch || stopping || have_pending) break;
         if (a.idle_exit_ticks != 0 && wall_clock64() - idle_since > a.idle_exit_ticks) {
           e |= 2u;                                  // behave as if the host had asked to stop
           break;
@@ -799,35 +929,53 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
     seen_epoch = ew & ~3ull;
     if (ew & 3u) stopping = true;
 
+    units_w += dispatcher_service_pending(a, s, units_w);
+
     // ---- mirror new records, batch by batch ----
     while (mirrored < tail) {
+      // Dequeue only a bounded distance ahead of execution: the dependency state seen at dequeue
+      // time is then close to what the workers will see, and the pending list stays short.
+      if (tid == 0) {
+        // the claim counter only grows: re-read it only when the cached value says "too far ahead"
+        if (units_w > claimed && units_w - claimed >= kLookaheadUnits)
+          claimed = __hip_atomic_load(&a.d->claim, __ATOMIC_RELAXED, SC_SYSTEM);
+        const uint32_t room = kPendMax - s->npend;
+        uint32_t take = (uint32_t)((tail - mirrored) < kDispatchBatch ? (tail - mirrored) : kDispatchBatch);
+        if (take > room) take = room;
+        if (units_w > claimed && units_w - claimed >= kLookaheadUnits) take = 0;
+        s->n = take;
+      }
+      __syncthreads();
+      uint32_t n = s->n;
+      __syncthreads();
+      if (n == 0) {                                                // throttled: let the workers catch up
+        units_w += dispatcher_service_pending(a, s, units_w);
+        if (s->npend == 0) __builtin_amdgcn_s_sleep(8);
+        break;                                                     // back to the poll loop (stop, table, heartbeat)
+      }
       const uint64_t tk0 = wall_clock64();
-      uint32_t n = (uint32_t)((tail - mirrored) < kDispatchBatch ? (tail - mirrored) : kDispatchBatch);
       // stage: 16 pieces of 16 bytes per record.  System-scope loads: an ordinary load of host
       // memory may hit a line the CU's vector cache kept from the previous lap of the ring.
-      {
-        const rsrc_t rh = make_rsrc(a.hring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
-        for (uint32_t p = tid; p < n * 16u; p += kThreads) {
-          const uint32_t rix = p >> 4, part = p & 15u;
-          const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
-          ((v4i*)&s->rec[rix])[part] = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
-        }
+      for (uint32_t p = tid; p < n * 16u; p += kThreads) {
+        const uint32_t rix = p >> 4, part = p & 15u;
+        const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
+        ((v4i*)&s->rec[rix])[part] = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
       }
       __syncthreads();
       const uint64_t tk1 = wall_clock64();
-      // a FENCE task starts a batch of its own: cut the batch in front of it
-      if (tid == 0) {
-        uint32_t cut = n;
-        for (uint32_t i = 1; i < n; ++i)
-          if (s->rec[i].rflags & RF_FENCE) { cut = i; break; }
-        s->n = cut;
+      // a FENCE task starts a batch of its own: cut the batch in front of the first one after slot 0
+      if (tid < 64) {
+        const bool f = tid >= 1 && tid < n && (s->rec[tid].rflags & RF_FENCE);
+        const uint64_t m = __ballot(f);
+        if (tid == 0) s->n = m ? (uint32_t)__builtin_ctzll(m) : n;
       }
       __syncthreads();
       n = s->n;
-      // resolve the operator table ("claim time"): slot, version, impl, status
+      // resolve the operator table ("claim time": slot, version, impl, status) and the dependencies
       if (tid < n) {
         Record& rc = s->rec[tid];
         const uint32_t op = rc.op_id;
+        const uint64_t ticket = mirrored + tid;
         int32_t status = GPUOS_OK;
         uint64_t e = 0;
         if (op >= GPUOS_MAX_OPS) status = GPUOS_E_BADOP;          // bounds check on the op id
@@ -840,64 +988,73 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         rc.sel = (uint8_t)((e >> 32) & 1u);
         rc.status = status;
         if (status != GPUOS_OK || rc.nchunks == 0) rc.nchunks = 1; // one unit reports the task
-        rc.ticket = mirrored + tid;
-        s->ubeg[tid + 1] = rc.nchunks;
+        rc.ticket = ticket;
+        uint32_t defer = 0;
+        if ((rc.dep[0] | rc.dep[1] | rc.dep[2]) != 0 && rc.nchunks > kSmallTaskChunks) {
+          // a large dependent task: its workers never wait; it is published once its
+          // dependencies are complete (now, or later from the pending list)
+          rc.rflags |= RF_DEPS_RESOLVED;
+          defer = deps_complete(a, ticket, rc.dep) ? 0u : 1u;
+        }
+        s->defer[tid] = defer;
       }
-      if (tid == 0) s->ubeg[0] = 0;
       __syncthreads();
-      if (tid == 0) {                                              // <= 64 entries: serial scan
-        uint32_t acc = 0;
-        for (uint32_t i = 1; i <= n; ++i) { acc += s->ubeg[i]; s->ubeg[i] = acc; }
+      // a leading FENCE: everything earlier must be published and complete first
+      if (s->rec[0].rflags & RF_FENCE) {
+        while (s->npend != 0) units_w += dispatcher_service_pending(a, s, units_w);
+        if (tid == 0) {
+          while (__hip_atomic_load(&a.d->done_count, __ATOMIC_RELAXED, SC_SYSTEM) < mirrored)
+            __builtin_amdgcn_s_sleep(4);
+          order_loads();
+        }
+        __syncthreads();
+      }
+      if (tid == 0) {                                              // <= 64 records: split publish / pending
+        uint32_t k = 0, j = s->npend;
+        for (uint32_t i = 0; i < n; ++i) {
+          const Record& rc = s->rec[i];
+          PubEntry pe;
+          pe.slot = (uint32_t)((mirrored + i) & a.cap_mask);
+          pe.nchunks = rc.nchunks;
+          pe.opinfo = (rc.op_id & 0xffu) | ((uint32_t)rc.sel << 8) | ((rc.status == GPUOS_OK ? 1u : 0u) << 9);
+          pe.pad = 0;
+          if (s->defer[i]) {
+            PendEntry& pd = s->pend[j++];
+            pd.ticket = mirrored + i;
+            pd.pub = pe;
+            pd.dep[0] = rc.dep[0]; pd.dep[1] = rc.dep[1]; pd.dep[2] = rc.dep[2];
+          } else {
+            s->pub[k++] = pe;
+          }
+        }
+        st_deferred += j - s->npend;
+        s->npend = j;
+        s->npub = k;
       }
       __syncthreads();
-      // a leading FENCE: wait until every earlier ticket has completed
-      if (tid == 0 && (s->rec[0].rflags & RF_FENCE)) {
-        while (__hip_atomic_load(&a.d->done_count, __ATOMIC_RELAXED, SC_SYSTEM) < mirrored)
-          __builtin_amdgcn_s_sleep(4);
-        order_loads();
-      }
       const uint64_t tk2 = wall_clock64();
-      // write the records into the device mirror (write-through stores)
-      {
-        const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
-        for (uint32_t p = tid; p < n * 16u; p += kThreads) {
-          const uint32_t rix = p >> 4, part = p & 15u;
-          const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
-          Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, ((const v4i*)&s->rec[rix])[part]);
-        }
+      // write the records into the device mirror (write-through stores), held-back ones included
+      for (uint32_t p = tid; p < n * 16u; p += kThreads) {
+        const uint32_t rix = p >> 4, part = p & 15u;
+        const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
+        Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, ((const v4i*)&s->rec[rix])[part]);
       }
-      // expand into work units
-      const uint32_t total = s->ubeg[n];
-      for (uint32_t u = tid; u < total; u += kThreads) {
-        uint32_t lo = 0, hi = n;                                   // ubeg[lo] <= u < ubeg[hi]
-        while (hi - lo > 1) {
-          const uint32_t mid = (lo + hi) >> 1;
-          if (s->ubeg[mid] <= u) lo = mid; else hi = mid;
-        }
-        const Record& rc = s->rec[lo];
-        __hip_atomic_store(&a.units[(units_w + u) & a.unit_mask],
-                           pack_unit(u - s->ubeg[lo], (uint32_t)((mirrored + lo) & a.cap_mask), rc.op_id, rc.sel,
-                                     rc.status == GPUOS_OK ? 1u : 0u),
-                           __ATOMIC_RELAXED, SC_SYSTEM);
-      }
-      drain_stores();                                              // this wave's records and units are in memory
-      __syncthreads();                                             // ... and so are every other wave's
+      const uint32_t total = dispatcher_publish(a, s, s->npub, units_w);   // drains the stores above as well
       units_w += total;
       mirrored += n;
-      if (tid == 0) {
-        __hip_atomic_store(&a.d->tail_units, units_w, __ATOMIC_RELAXED, SC_SYSTEM);   // publish
-        __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
-      }
+      if (tid == 0) __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
       idle_since = wall_clock64();
       st_batches += 1; st_records += n; st_units += total;
       st_stage += tk1 - tk0; st_resolve += tk2 - tk1; st_write += idle_since - tk2; st_busy += idle_since - tk0;
+      units_w += dispatcher_service_pending(a, s, units_w);
     }
-    if (stopping) {
+    if (stopping && mirrored >= tail) {
+      while (s->npend != 0) units_w += dispatcher_service_pending(a, s, units_w);   // nothing is left behind
       if (tid == 0) {
         uint64_t* st = a.d->stat;
         st[ST_DISP_BATCHES] = st_batches; st[ST_DISP_RECORDS] = st_records; st[ST_DISP_UNITS] = st_units;
         st[ST_DISP_TICKS_STAGE] = st_stage; st[ST_DISP_TICKS_RESOLVE] = st_resolve; st[ST_DISP_TICKS_WRITE] = st_write;
-        st[ST_DISP_TICKS_TOTAL_BUSY] = st_busy; st[ST_DISP_POLLS] = polls;
+        st[ST_DISP_TICKS_TOTAL_BUSY] = st_busy; st[ST_DISP_POLLS] = polls; st[ST_DISP_DEFERRED] = st_deferred;
         drain_stores();
         __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.h->exit_code, (ew & 2u) ? 2u : 1u, __ATOMIC_RELAXED, SC_SYSTEM);
@@ -914,7 +1071,7 @@ struct WorkShared {
   Record rec;
   uint64_t unit, entry;
   int32_t exit_flag;
-  float red[4 * kRedPartialRows];
+  float red[kScratchFloats];
 };
 
 DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
@@ -979,7 +1136,7 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
     if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
     const uint64_t c2 = wall_clock64();
     // ---- dependencies: earlier tickets named by back-distance ----
-    if (r->dep[0] | r->dep[1] | r->dep[2]) {
+    if ((r->dep[0] | r->dep[1] | r->dep[2]) != 0 && !(r->rflags & RF_DEPS_RESOLVED)) {
       if (tid == 0) {
         const uint64_t ticket = r->ticket;
         for (int k = 0; k < 3; ++k) {
@@ -1035,7 +1192,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
 // one ordinary launch per task: block b executes chunk b
 __global__ void __launch_bounds__(kThreads) gpuos_single_task_kernel(Record rec) {
   __shared__ Record s_rec;
-  __shared__ float s_red[4 * kRedPartialRows];
+  __shared__ float s_red[kScratchFloats];
   if (threadIdx.x == 0) s_rec = rec;
   __syncthreads();
   exec_chunk<POL_PLAIN>(&s_rec, s_rec.impl, blockIdx.x, s_red);

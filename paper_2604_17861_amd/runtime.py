@@ -227,7 +227,7 @@ class Runtime:
     STAT_NAMES = ["disp_batches", "disp_records", "disp_units", "disp_ticks_stage", "disp_ticks_resolve",
                   "disp_ticks_write", "disp_ticks_busy", "disp_polls", "work_units", "work_ticks_wait",
                   "work_ticks_fetch", "work_ticks_dep", "work_ticks_exec", "work_ticks_complete",
-                  "work_ticks_total", "reserved"]
+                  "work_ticks_total", "disp_deferred"]
 
     def worker_stats(self):
         """Counters of the persistent kernel (after stop_worker); ticks are 10 ns."""
