@@ -109,19 +109,13 @@ def _reset_swaps(rt, stream):
         rt.swap_op(op, stream.table[op])
 
 
-def bench_pingpong(R, stream, dp, n=5000):
-    with R.Runtime(0, idle_exit_ms=60000) as rt:
+def bench_pingpong(R, stream, dp, n=5000, **cfg):
+    """Unloaded latency: one task at a time, timed inside the library (gpuos_run_serial), the same
+    way the per-launch path times launch + synchronize."""
+    with R.Runtime(0, idle_exit_ms=60000, **cfg) as rt:
         rt.register_table(stream.table)
-        for i in range(200):
-            rt.submit(dp.tasks, i % len(stream), 1)
-            rt.wait()
-        lat = np.zeros(n)
-        for i in range(n):
-            k = i % len(stream)
-            t0 = time.perf_counter_ns()
-            rt.submit(dp.tasks, k, 1)
-            rt.wait()
-            lat[i] = time.perf_counter_ns() - t0
+        rt.run_serial(dp.tasks, 0, min(200, len(stream)))
+        lat = np.concatenate([rt.run_serial(dp.tasks, 0, min(len(stream), n - k)) for k in range(0, n, len(stream))])
     return percentile_us(lat, 50), percentile_us(lat, 99)
 
 

@@ -158,7 +158,11 @@ typedef struct gpuos_config {
                                        (0 => 1<<21; rounded up to a power of two)   */
   uint32_t chunk_elems;             /* elements of a task one workgroup takes at a time
                                        (0 => 16384; rounded up to a multiple of 1024)  */
-  uint32_t reserved[6];
+  uint32_t push_ring;               /* 0: ring, doorbell and table source in fine-grained
+                                       host memory, polled by the device over PCIe;
+                                       1: in device memory, written by the host through
+                                       the PCIe BAR (needs a host-visible BAR)          */
+  uint32_t reserved[5];
 } gpuos_config;
 
 /* Fill *cfg with the defaults named above. */
@@ -238,6 +242,12 @@ int gpuos_worker_stats(gpuos_ctx* ctx, uint64_t out[16]);
  * the context so that timing and logs can still be read; gpuos_shutdown frees. */
 int gpuos_stop_worker(gpuos_ctx* ctx);
 int gpuos_worker_elapsed_ms(gpuos_ctx* ctx, float* out_ms);
+
+/* Submit tasks[0..n) one at a time, waiting for each before the next is submitted, and
+ * store each task's submit -> completion-seen host nanoseconds into lat_ns (HOST array of n,
+ * nullable): the unloaded per-operation latency (paper Section 6.2), measured the same way as
+ * the sync_each mode of gpuos_launch_per_op. */
+int gpuos_run_serial(gpuos_ctx* ctx, const gpuos_task* tasks, uint32_t n, uint64_t* lat_ns);
 
 /* The comparison the paper's evaluation is built on (Section 6: the same
  * operations issued as ordinary kernel launches): run the stream as ONE

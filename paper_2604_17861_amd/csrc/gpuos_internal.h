@@ -67,9 +67,13 @@ struct alignas(16) Record {
   uint32_t size[6];          // coalesced iteration shape (reductions: outer dims)
   uint32_t stride[4][6];     // elements; 0 on broadcast dims; reductions: stride[0][5]
                              // is the input stride along the reduced dim
-  uint32_t pad2[10];
+  uint32_t pad2[9];
+  uint32_t check;            // xor of the 63 words above ^ record_check_seed(ticket): set by the host
 };
 static_assert(sizeof(Record) == 256, "ring record must be 256 bytes");
+
+// The value the xor of all 64 words of an intact record of `ticket` gives (check included).
+GPUOS_HD inline uint32_t record_check_seed(uint64_t ticket) { return 0x9E3779B9u ^ (uint32_t)ticket ^ (uint32_t)(ticket >> 32); }
 
 // Completion word (8 bytes, one atomic store to host memory):
 //   bits 0..31  low half of ticket+1, bits 32..39 status (int8), bits 40..63 version
@@ -87,14 +91,19 @@ struct OpSlots {             // one logical operator: two slots + the version wo
   uint32_t pad;
 };
 
-// Host-coherent control block (fine-grained pinned memory, mapped to the device).
+// Control words.  HostCtl is written by the device and read by the host: it always lives in
+// fine-grained host memory.  DoorbellCtl is written by the host and polled by the dispatcher: it
+// lives in fine-grained host memory (the device polls over PCIe) or, in push mode, in device
+// memory that the host writes through the PCIe BAR (the device polls its own HBM).
 struct HostCtl {
+  alignas(64) uint64_t dispatched;   // device -> host: tickets dequeued from the ring
+  alignas(64) uint64_t heartbeat;    // device -> host: dispatcher poll counter
+  alignas(64) uint32_t exit_code;    // device -> host: 0 running, 1 stop seen, 2 idle exit
+};
+struct DoorbellCtl {
   alignas(64) uint64_t tail;         // host -> device: tickets published (doorbell)
   alignas(64) uint64_t epoch_word;   // host -> device: epoch << 12 | op << 4 | stop bit;
                                      // op = 0xff: refresh every entry
-  alignas(64) uint64_t dispatched;   // device -> host: tickets dequeued from the host ring
-  alignas(64) uint64_t heartbeat;    // device -> host: dispatcher poll counter
-  alignas(64) uint32_t exit_code;    // device -> host: 0 running, 1 stop seen, 2 idle exit
   alignas(64) uint32_t yield_every;  // host -> device
 };
 
@@ -129,6 +138,7 @@ GPUOS_HD inline uint64_t pack_unit(uint32_t chunk, uint32_t slot, uint32_t op, u
 
 struct WorkerArgs {
   HostCtl*   h;
+  const DoorbellCtl* bell;
   const Record* hring;       // host ring (device-visible address)
   uint64_t*  hcomp;          // host completion words, one per slot
   const OpSlots* htable;     // host operator table

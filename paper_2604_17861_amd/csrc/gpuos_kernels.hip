@@ -761,6 +761,7 @@ DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_
 constexpr uint32_t kPendMax = 128;         // tasks held back at a time
 constexpr uint64_t kLookaheadUnits = 8192; // work units kept published ahead of the claim counter
 constexpr uint32_t kSmallTaskChunks = 4;
+constexpr uint32_t kStageRetries = 4096;   // re-reads of a record that fails its check word (~ms) before it is failed
 
 struct PubEntry {                          // what it takes to publish a task's work units
   uint32_t slot;
@@ -782,6 +783,8 @@ struct DispShared {
   uint32_t ubeg[kDispatchBatch + 1];       // exclusive prefix of their nchunks
   PendEntry pend[kPendMax];
   uint32_t defer[kDispatchBatch];          // per record of the batch: held back
+  uint32_t bad[kDispatchBatch], ok[kDispatchBatch];   // staging: record still fails its check / passed on this read
+  uint32_t nbad;
   uint32_t ready[kPendMax];                // per pending entry: dependencies complete
   uint64_t tail, epoch_word;
   uint32_t n, npend, npub;
@@ -895,8 +898,8 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       uint64_t t, e;
       const bool have_pending = s->npend != 0;
       while (true) {
-        t = __hip_atomic_load(&a.h->tail, __ATOMIC_RELAXED, SC_SYSTEM);
-        e = __hip_atomic_load(&a.h->epoch_word, __ATOMIC_RELAXED, SC_SYSTEM);
+        t = __hip_atomic_load(&a.bell->tail, __ATOMIC_RELAXED, SC_SYSTEM);
+        e = __hip_atomic_load(&a.bell->epoch_word, __ATOMIC_RELAXED, SC_SYSTEM);
         ++polls;
         if ((polls & 63u) == 0) __hip_atomic_store(&a.h->heartbeat, polls, __ATOMIC_RELAXED, SC_SYSTEM);
         if (t != mirrored || e != seen_epoch || stopping || have_pending) break;
@@ -907,7 +910,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       }
       order_loads();
       if (e & 3u) {                                 // stop: take the final tail after the flag
-        t = __hip_atomic_load(&a.h->tail, __ATOMIC_RELAXED, SC_SYSTEM);
+        t = __hip_atomic_load(&a.bell->tail, __ATOMIC_RELAXED, SC_SYSTEM);
         order_loads();
       }
       s->tail = t;
@@ -921,7 +924,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       const bool one = ((ew >> 12) - (seen_epoch >> 12)) == 1 && hinted != 0xffu;
       dispatcher_refresh_table(a, s, one ? hinted : 0xffu);
       if (tid == 0) {
-        const uint32_t y = __hip_atomic_load(&a.h->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
+        const uint32_t y = __hip_atomic_load(&a.bell->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.d->yield_every, y, __ATOMIC_RELAXED, SC_SYSTEM);
       }
       __syncthreads();
@@ -956,12 +959,35 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       const uint64_t tk0 = wall_clock64();
       // stage: 16 pieces of 16 bytes per record.  System-scope loads: an ordinary load of host
       // memory may hit a line the CU's vector cache kept from the previous lap of the ring.
-      for (uint32_t p = tid; p < n * 16u; p += kThreads) {
-        const uint32_t rix = p >> 4, part = p & 15u;
-        const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
-        ((v4i*)&s->rec[rix])[part] = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
-      }
+      // Every record carries a check word (xor of its other 63 words, its ticket and a constant):
+      // a record that has not landed completely yet, or is left over from the previous lap,
+      // fails the check and is read again; one that never passes is completed with an error
+      // instead of being executed.
+      if (tid < kDispatchBatch) s->bad[tid] = tid < n ? 1u : 0u;
       __syncthreads();
+      for (uint32_t attempt = 0; attempt < kStageRetries; ++attempt) {
+        for (uint32_t p = tid; p < n * 16u; p += kThreads) {
+          const uint32_t rix = p >> 4, part = p & 15u;
+          if (s->bad[rix]) {                                       // uniform over the 16 lanes of a record
+            const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
+            const v4i q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
+            ((v4i*)&s->rec[rix])[part] = q;
+            uint32_t x = (uint32_t)(q[0] ^ q[1] ^ q[2] ^ q[3]);
+            x ^= __shfl_xor(x, 8, 16); x ^= __shfl_xor(x, 4, 16); x ^= __shfl_xor(x, 2, 16); x ^= __shfl_xor(x, 1, 16);
+            if (part == 0) s->ok[rix] = (x == record_check_seed(mirrored + rix)) ? 1u : 0u;
+          }
+        }
+        __syncthreads();
+        if (tid < 64) {
+          const bool still_bad = tid < n && s->bad[tid] && !s->ok[tid];
+          if (tid < n && s->bad[tid] && s->ok[tid]) s->bad[tid] = 0;
+          const uint64_t m = __ballot(still_bad);
+          if (tid == 0) s->nbad = (uint32_t)__popcll(m);
+        }
+        __syncthreads();
+        if (s->nbad == 0) break;
+        __builtin_amdgcn_s_sleep(16);
+      }
       const uint64_t tk1 = wall_clock64();
       // a FENCE task starts a batch of its own: cut the batch in front of the first one after slot 0
       if (tid < 64) {
@@ -978,7 +1004,10 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         const uint64_t ticket = mirrored + tid;
         int32_t status = GPUOS_OK;
         uint64_t e = 0;
-        if (op >= GPUOS_MAX_OPS) status = GPUOS_E_BADOP;          // bounds check on the op id
+        if (s->bad[tid]) {                                         // never passed its check: do not trust any field
+          status = GPUOS_E_INVAL;
+          rc.path = PATH_NOP; rc.nchunks = 1; rc.dep[0] = rc.dep[1] = rc.dep[2] = 0; rc.rflags = 0;
+        } else if (op >= GPUOS_MAX_OPS) status = GPUOS_E_BADOP;   // bounds check on the op id
         else {
           e = s->entry[op];
           if (e == 0) status = GPUOS_E_BADOP;                      // never registered
@@ -1009,27 +1038,33 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         }
         __syncthreads();
       }
-      if (tid == 0) {                                              // <= 64 records: split publish / pending
-        uint32_t k = 0, j = s->npend;
-        for (uint32_t i = 0; i < n; ++i) {
-          const Record& rc = s->rec[i];
+      if (tid < 64) {                                              // wave 0 holds all n <= 64 records: split by ballot
+        const uint32_t npend0 = s->npend;
+        const bool mine = tid < n;
+        const bool held = mine && s->defer[tid] != 0;
+        const uint64_t m_pub = __ballot(mine && !held), m_def = __ballot(held);
+        const uint64_t below = (1ull << tid) - 1ull;
+        if (mine) {
+          const Record& rc = s->rec[tid];
           PubEntry pe;
-          pe.slot = (uint32_t)((mirrored + i) & a.cap_mask);
+          pe.slot = (uint32_t)((mirrored + tid) & a.cap_mask);
           pe.nchunks = rc.nchunks;
           pe.opinfo = (rc.op_id & 0xffu) | ((uint32_t)rc.sel << 8) | ((rc.status == GPUOS_OK ? 1u : 0u) << 9);
           pe.pad = 0;
-          if (s->defer[i]) {
-            PendEntry& pd = s->pend[j++];
-            pd.ticket = mirrored + i;
+          if (held) {
+            PendEntry& pd = s->pend[npend0 + (uint32_t)__popcll(m_def & below)];
+            pd.ticket = mirrored + tid;
             pd.pub = pe;
             pd.dep[0] = rc.dep[0]; pd.dep[1] = rc.dep[1]; pd.dep[2] = rc.dep[2];
           } else {
-            s->pub[k++] = pe;
+            s->pub[(uint32_t)__popcll(m_pub & below)] = pe;
           }
         }
-        st_deferred += j - s->npend;
-        s->npend = j;
-        s->npub = k;
+        if (tid == 0) {
+          st_deferred += (uint32_t)__popcll(m_def);
+          s->npend = npend0 + (uint32_t)__popcll(m_def);
+          s->npub = (uint32_t)__popcll(m_pub);
+        }
       }
       __syncthreads();
       const uint64_t tk2 = wall_clock64();

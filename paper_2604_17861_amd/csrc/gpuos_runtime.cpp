@@ -18,6 +18,7 @@
 #include <thread>
 #include <vector>
 
+#include <immintrin.h>
 #include <pthread.h>
 #include <sched.h>
 
@@ -290,6 +291,8 @@ struct gpuos_ctx {
   uint32_t cap = 0, mask = 0, workgroups = 0;
   // host-coherent
   HostCtl* h = nullptr;
+  DoorbellCtl* bell = nullptr;               // host or device memory (push mode)
+  bool push = false;
   Record* hring = nullptr;
   uint64_t* hcomp = nullptr;
   OpSlots* htable = nullptr;
@@ -349,13 +352,14 @@ uint64_t harvest(gpuos_ctx* c) {
   return n;
 }
 
-void harvester_main(gpuos_ctx* c) {
-  // pin to the last allowed core so that it does not share one with the producer
+void harvester_main(gpuos_ctx* c, int producer_cpu) {
+  // pin to the last allowed core that is not the one the producer was running on when it created
+  // the context: a spinning harvester on the producer's core would starve it for whole time slices
   cpu_set_t set;
   if (sched_getaffinity(0, sizeof(set), &set) == 0) {
-    int last = -1;
-    for (int i = 0; i < CPU_SETSIZE; ++i) if (CPU_ISSET(i, &set)) last = i;
-    if (last >= 0) { cpu_set_t one; CPU_ZERO(&one); CPU_SET(last, &one); pthread_setaffinity_np(pthread_self(), sizeof(one), &one); }
+    int pick = -1;
+    for (int i = 0; i < CPU_SETSIZE; ++i) if (CPU_ISSET(i, &set) && i != producer_cpu) pick = i;
+    if (pick >= 0) { cpu_set_t one; CPU_ZERO(&one); CPU_SET(pick, &one); pthread_setaffinity_np(pthread_self(), sizeof(one), &one); }
   }
   while (c->harvester_run.load(std::memory_order_acquire)) {
     if (harvest(c) == 0) __builtin_ia32_pause();
@@ -389,20 +393,31 @@ void doorbell(gpuos_ctx* c) {
   const uint64_t t = now_ns();
   for (uint64_t i = pub; i < c->head; ++i) c->log[i & c->log_mask].t_submit_ns = t;
   c->published.store(c->head, std::memory_order_release);
-  __atomic_store_n(&c->h->tail, c->head, __ATOMIC_RELEASE);     // the commit: one store-release
+  if (c->push) _mm_sfence();                                    // records (write-combined BAR stores) before the doorbell
+  __atomic_store_n(&c->bell->tail, c->head, __ATOMIC_RELEASE);  // the commit: one store-release
+  if (c->push) _mm_sfence();                                    // ... and push the doorbell out of the write-combining buffer
 }
 
 void bump_epoch(gpuos_ctx* c, uint32_t op_hint, bool stop) {
   ++c->epoch;
   const uint64_t w = (c->epoch << 12) | ((uint64_t)(op_hint & 0xffu) << 4) | (stop ? 1u : 0u);
-  __atomic_store_n(&c->h->epoch_word, w, __ATOMIC_RELEASE);
+  if (c->push) _mm_sfence();
+  __atomic_store_n(&c->bell->epoch_word, w, __ATOMIC_RELEASE);
+  if (c->push) _mm_sfence();
 }
 
 void free_all(gpuos_ctx* c) {
   if (c->h) (void)hipHostFree(c->h);
-  if (c->hring) (void)hipHostFree(c->hring);
   if (c->hcomp) (void)hipHostFree(c->hcomp);
-  if (c->htable) (void)hipHostFree(c->htable);
+  if (c->push) {
+    if (c->bell) (void)hipFree(c->bell);
+    if (c->hring) (void)hipFree(c->hring);
+    if (c->htable) (void)hipFree(c->htable);
+  } else {
+    if (c->bell) (void)hipHostFree(c->bell);
+    if (c->hring) (void)hipHostFree(c->hring);
+    if (c->htable) (void)hipHostFree(c->htable);
+  }
   if (c->d) (void)hipFree(c->d);
   if (c->dring) (void)hipFree(c->dring);
   if (c->units) (void)hipFree(c->units);
@@ -411,7 +426,7 @@ void free_all(gpuos_ctx* c) {
   if (c->ev_start) (void)hipEventDestroy(c->ev_start);
   if (c->ev_stop) (void)hipEventDestroy(c->ev_stop);
   if (c->stream) (void)hipStreamDestroy(c->stream);
-  c->h = nullptr; c->hring = nullptr; c->hcomp = nullptr; c->htable = nullptr;
+  c->h = nullptr; c->bell = nullptr; c->hring = nullptr; c->hcomp = nullptr; c->htable = nullptr;
   c->d = nullptr; c->dring = nullptr; c->units = nullptr; c->st = nullptr; c->dtable = nullptr;
   c->ev_start = nullptr; c->ev_stop = nullptr; c->stream = nullptr;
 }
@@ -503,10 +518,17 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   if (!hip_ok(hipGetDeviceProperties(&prop, cfg.device), "hipGetDeviceProperties")) return fail(GPUOS_E_HIP);
   const unsigned hflags = hipHostMallocCoherent | hipHostMallocMapped;
   const size_t n_units = (size_t)cap * kMaxChunksPerTask;
+  c->push = cfg.push_ring != 0;
+  auto to_device_alloc = [&](void** p, size_t n, const char* what) {
+    // memory the host writes and the device reads: pinned host memory, or (push mode) device
+    // memory that the host reaches through the BAR
+    return c->push ? hip_ok(hipMalloc(p, n), what) : hip_ok(hipHostMalloc(p, n, hflags), what);
+  };
   if (!hip_ok(hipHostMalloc((void**)&c->h, sizeof(HostCtl), hflags), "hipHostMalloc(ctl)") ||
-      !hip_ok(hipHostMalloc((void**)&c->hring, sizeof(Record) * cap, hflags), "hipHostMalloc(ring)") ||
+      !to_device_alloc((void**)&c->bell, sizeof(DoorbellCtl), "alloc(doorbell)") ||
+      !to_device_alloc((void**)&c->hring, sizeof(Record) * cap, "alloc(ring)") ||
       !hip_ok(hipHostMalloc((void**)&c->hcomp, sizeof(uint64_t) * cap, hflags), "hipHostMalloc(comp)") ||
-      !hip_ok(hipHostMalloc((void**)&c->htable, sizeof(OpSlots) * GPUOS_MAX_OPS, hflags), "hipHostMalloc(table)") ||
+      !to_device_alloc((void**)&c->htable, sizeof(OpSlots) * GPUOS_MAX_OPS, "alloc(table)") ||
       !hip_ok(hipMalloc((void**)&c->d, sizeof(DevCtl)), "hipMalloc(ctl)") ||
       !hip_ok(hipMalloc((void**)&c->dring, sizeof(Record) * cap), "hipMalloc(ring)") ||
       !hip_ok(hipMalloc((void**)&c->units, sizeof(uint64_t) * n_units), "hipMalloc(units)") ||
@@ -514,9 +536,17 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       !hip_ok(hipMalloc((void**)&c->dtable, sizeof(OpSlots) * GPUOS_MAX_OPS), "hipMalloc(table)"))
     return fail(GPUOS_E_HIP);
   std::memset(c->h, 0, sizeof(HostCtl));
-  std::memset(c->hring, 0, sizeof(Record) * cap);
   std::memset(c->hcomp, 0, sizeof(uint64_t) * cap);
-  std::memset(c->htable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS);
+  if (c->push) {
+    if (!hip_ok(hipMemset(c->bell, 0, sizeof(DoorbellCtl)), "hipMemset") ||
+        !hip_ok(hipMemset(c->hring, 0, sizeof(Record) * cap), "hipMemset") ||
+        !hip_ok(hipMemset(c->htable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS), "hipMemset"))
+      return fail(GPUOS_E_HIP);
+  } else {
+    std::memset(c->bell, 0, sizeof(DoorbellCtl));
+    std::memset(c->hring, 0, sizeof(Record) * cap);
+    std::memset(c->htable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS);
+  }
   if (!hip_ok(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking), "hipStreamCreateWithFlags") ||
       !hip_ok(hipEventCreate(&c->ev_start), "hipEventCreate") ||
       !hip_ok(hipEventCreate(&c->ev_stop), "hipEventCreate") ||
@@ -538,7 +568,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   c->cfg.workgroups_per_cu = per_cu;
 
   WorkerArgs a;
-  a.h = c->h; a.hring = c->hring; a.hcomp = c->hcomp; a.htable = c->htable;
+  a.h = c->h; a.bell = c->bell; a.hring = c->hring; a.hcomp = c->hcomp; a.htable = c->htable;
   a.d = c->d; a.dring = c->dring; a.units = c->units; a.st = c->st; a.dtable = c->dtable;
   a.cap_mask = c->mask;
   a.unit_mask = (uint32_t)(n_units - 1);
@@ -565,7 +595,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   }
   if (cfg.harvester_thread) {
     c->harvester_run.store(true);
-    c->harvester = std::thread(harvester_main, c);
+    c->harvester = std::thread(harvester_main, c, sched_getcpu());
   }
   {
     std::lock_guard<std::mutex> lk(g_live_mu);
@@ -586,6 +616,7 @@ int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* 
   o.version = 1;
   o.prev_swap_head = 0;
   __atomic_store_n(&c->htable[op_id].slot[1], pack_entry(impl_id, 1), __ATOMIC_RELAXED);
+  if (c->push) _mm_sfence();                 // write-combined stores: the slot before the version
   __atomic_store_n(&c->htable[op_id].version, 1u, __ATOMIC_RELEASE);
   bump_epoch(c, op_id, false);
   if (out_version) *out_version = 1;
@@ -610,6 +641,7 @@ int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_
   }
   const uint32_t v = o.version + 1;
   __atomic_store_n(&c->htable[op_id].slot[v & 1u], pack_entry(impl_id, v), __ATOMIC_RELAXED);  // inactive slot
+  if (c->push) _mm_sfence();                 // write-combined stores: the slot before the version
   __atomic_store_n(&c->htable[op_id].version, v, __ATOMIC_RELEASE);                           // flip
   bump_epoch(c, op_id, false);
   o.impl = impl_id;
@@ -655,7 +687,13 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
       const int rc = wait_floor(c, c->head - c->cap + 1, c->wait_ns);
       if (rc != GPUOS_OK) return rc;
     }
-    std::memcpy(&c->hring[c->head & c->mask], &staged[i], sizeof(Record));
+    Record& rec = staged[i];
+    rec.ticket = c->head;
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(&rec);
+    uint32_t x = record_check_seed(c->head);
+    for (int k = 0; k < 63; ++k) x ^= w[k];
+    rec.check = x;                                                // xor over all 64 words == the seed
+    std::memcpy(&c->hring[c->head & c->mask], &rec, sizeof(Record));
     ++c->head;
   }
   return GPUOS_OK;
@@ -723,7 +761,7 @@ int gpuos_worker_alive(gpuos_ctx* c) {
 int gpuos_set_yield_every(gpuos_ctx* c, uint32_t every) {
   if (!c) return GPUOS_E_INVAL;
   if (!c->worker_running) return GPUOS_E_DEAD;
-  __atomic_store_n(&c->h->yield_every, every, __ATOMIC_RELEASE);
+  __atomic_store_n(&c->bell->yield_every, every, __ATOMIC_RELEASE);
   bump_epoch(c, 0xff, false);
   return GPUOS_OK;
 }
@@ -761,6 +799,19 @@ int gpuos_shutdown(gpuos_ctx* c) {
   free_all(c);
   delete c;
   return rc;
+}
+
+int gpuos_run_serial(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* lat_ns) {
+  if (!c || (!tasks && n)) return GPUOS_E_INVAL;
+  for (uint32_t i = 0; i < n; ++i) {
+    const uint64_t t0 = now_ns();
+    uint64_t ticket = 0;
+    int rc = gpuos_submit(c, &tasks[i], 1, &ticket);
+    if (rc == GPUOS_OK) rc = gpuos_wait(c, ticket, 0);
+    if (rc != GPUOS_OK) return rc;
+    if (lat_ns) lat_ns[i] = now_ns() - t0;
+  }
+  return GPUOS_OK;
 }
 
 int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n, const uint32_t* impl_of_op,

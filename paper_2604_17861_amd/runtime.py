@@ -31,7 +31,7 @@ class Config(ctypes.Structure):
                 ("harvester_thread", ctypes.c_uint32), ("defer_op_check", ctypes.c_uint32),
                 ("idle_exit_ms", ctypes.c_uint32), ("wait_timeout_ms", ctypes.c_uint32),
                 ("completion_log", ctypes.c_uint32), ("chunk_elems", ctypes.c_uint32),
-                ("reserved", ctypes.c_uint32 * 6)]
+                ("push_ring", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 5)]
 
 
 class QueueState(ctypes.Structure):
@@ -87,6 +87,7 @@ def lib():
         "gpuos_stop_worker": (ctypes.c_int, [vp]),
         "gpuos_worker_elapsed_ms": (ctypes.c_int, [vp, P(ctypes.c_float)]),
         "gpuos_worker_stats": (ctypes.c_int, [vp, vp]),
+        "gpuos_run_serial": (ctypes.c_int, [vp, vp, u32, vp]),
         "gpuos_launch_per_op": (ctypes.c_int, [i32, vp, u32, vp, i32, vp, P(ctypes.c_double)]),
         "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
         "gpuos_strerror": (ctypes.c_char_p, [ctypes.c_int]),
@@ -104,7 +105,7 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_strerror",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
 
@@ -199,6 +200,13 @@ class Runtime:
         out = np.zeros(n, dtype=S.COMPLETION_DT)
         _check(lib().gpuos_get_completions(self._ctx, first, n, out.ctypes.data), "gpuos_get_completions")
         return out
+
+    def run_serial(self, tasks, first=0, count=None):
+        """gpuos_run_serial: one task at a time; returns per-task latencies in ns."""
+        n = len(tasks) - first if count is None else count
+        lat = np.zeros(n, dtype=np.uint64)
+        _check(lib().gpuos_run_serial(self._ctx, _tasks_ptr(tasks, first), n, lat.ctypes.data), "gpuos_run_serial")
+        return lat
 
     # -- introspection ---------------------------------------------------------
     def peek_queue(self):
