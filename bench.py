@@ -79,8 +79,8 @@ def percentile_us(ns, q):
     return float(np.percentile(ns, q)) / 1e3 if len(ns) else None
 
 
-def bench_persistent(R, stream, dp, steps, warmup, harvester=True, capacity=0):
-    with R.Runtime(capacity, harvester_thread=1 if harvester else 0, idle_exit_ms=60000,
+def bench_persistent(R, stream, dp, steps, warmup, harvester=True, capacity=0, **cfg):
+    with R.Runtime(capacity, harvester_thread=1 if harvester else 0, idle_exit_ms=60000, **cfg,
                    completion_log=max(1 << 20, 1 << int(np.ceil(np.log2(len(stream) + 1))))) as rt:
         rt.register_table(stream.table)
         for _ in range(warmup):
@@ -230,6 +230,11 @@ def main():
         extras["pingpong"] = dict(persistent_p50_us=p50, persistent_p99_us=p99,
                                   per_launch_p50_us=percentile_us(lat1, 50), per_launch_p99_us=percentile_us(lat1, 99))
         log("pingpong:", extras["pingpong"])
+        # ---- push mode: ring in device memory, host writes through the PCIe BAR -------------------
+        pp50, pp99 = bench_pingpong(R, s1, dp1, push_ring=1)
+        rpush = bench_persistent(R, s2, dp2, max(4, args.steps // 2), 1, push_ring=1)
+        extras["push_mode"] = dict(config2_tasks_per_s=rpush["tasks_per_s"], pingpong_p50_us=pp50, pingpong_p99_us=pp99)
+        log("push mode:", extras["push_mode"])
         # ---- first configuration ----------------------------------------------------------
         r1 = bench_persistent(R, s1, dp1, max(20, args.steps), args.warmup)
         R.launch_per_op(dp1.tasks, s1.table)

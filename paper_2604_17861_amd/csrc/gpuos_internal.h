@@ -130,10 +130,12 @@ struct SlotState {                   // device memory, one per ring slot
 };
 
 // Work-unit entry: bits 0..19 chunk, 20..35 ring slot, 36..43 op id, 44 table slot,
-// 45 op id valid.
-GPUOS_HD inline uint64_t pack_unit(uint32_t chunk, uint32_t slot, uint32_t op, uint32_t sel, uint32_t valid) {
+// 45 op id valid, 46..63 stamp.  The stamp is the lap of the unit ring plus one (18 bits): the
+// entry doubles as its own ready flag, so a worker that claimed unit g polls just that entry.
+GPUOS_HD inline uint64_t unit_stamp(uint64_t g, uint32_t unit_shift) { return ((g >> unit_shift) + 1) & 0x3ffffull; }
+GPUOS_HD inline uint64_t pack_unit(uint32_t chunk, uint32_t slot, uint32_t op, uint32_t sel, uint32_t valid, uint64_t stamp) {
   return (uint64_t)chunk | ((uint64_t)slot << 20) | ((uint64_t)(op & 0xff) << 36) |
-         ((uint64_t)(sel & 1) << 44) | ((uint64_t)(valid & 1) << 45);
+         ((uint64_t)(sel & 1) << 44) | ((uint64_t)(valid & 1) << 45) | (stamp << 46);
 }
 
 struct WorkerArgs {
@@ -149,6 +151,7 @@ struct WorkerArgs {
   OpSlots*   dtable;         // device-resident operator table
   uint32_t   cap_mask;
   uint32_t   unit_mask;
+  uint32_t   unit_shift;     // log2 of the unit ring size
   uint64_t   idle_exit_ticks;   // 0 = never; 100 MHz ticks
 };
 

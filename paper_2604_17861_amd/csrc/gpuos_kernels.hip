@@ -761,6 +761,7 @@ DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_
 constexpr uint32_t kPendMax = 128;         // tasks held back at a time
 constexpr uint64_t kLookaheadUnits = 8192; // work units kept published ahead of the claim counter
 constexpr uint32_t kSmallTaskChunks = 4;
+constexpr uint32_t kPrefetch = 4;          // records read together with every doorbell poll (4 x 16 lanes)
 constexpr uint32_t kStageRetries = 4096;   // re-reads of a record that fails its check word (~ms) before it is failed
 
 struct PubEntry {                          // what it takes to publish a task's work units
@@ -785,6 +786,7 @@ struct DispShared {
   uint32_t defer[kDispatchBatch];          // per record of the batch: held back
   uint32_t bad[kDispatchBatch], ok[kDispatchBatch];   // staging: record still fails its check / passed on this read
   uint32_t nbad;
+  uint32_t pre[kPrefetch];                 // prefetched with the poll and valid
   uint32_t ready[kPendMax];                // per pending entry: dependencies complete
   uint64_t tail, epoch_word;
   uint32_t n, npend, npub;
@@ -837,6 +839,8 @@ DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npu
   }
   __syncthreads();
   const uint32_t total = s->ubeg[npub];
+  drain_stores();                                  // the records written before this call are in memory ...
+  __syncthreads();                                 // ... every wave's, before any unit that names them appears
   for (uint32_t u = tid; u < total; u += kThreads) {
     uint32_t lo = 0, hi = npub;                    // ubeg[lo] <= u < ubeg[hi]
     while (hi - lo > 1) {
@@ -844,14 +848,14 @@ DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npu
       if (s->ubeg[mid] <= u) lo = mid; else hi = mid;
     }
     const PubEntry pe = s->pub[lo];
-    __hip_atomic_store(&a.units[(units_w + u) & a.unit_mask],
-                       pack_unit(u - s->ubeg[lo], pe.slot, pe.opinfo & 0xffu, (pe.opinfo >> 8) & 1u, (pe.opinfo >> 9) & 1u),
+    const uint64_t g = units_w + u;
+    // one 8-byte store publishes the unit: the stamp makes it claimable
+    __hip_atomic_store(&a.units[g & a.unit_mask],
+                       pack_unit(u - s->ubeg[lo], pe.slot, pe.opinfo & 0xffu, (pe.opinfo >> 8) & 1u, (pe.opinfo >> 9) & 1u,
+                                 unit_stamp(g, a.unit_shift)),
                        __ATOMIC_RELAXED, SC_SYSTEM);
   }
-  drain_stores();                                  // this wave's records and units are in memory
-  __syncthreads();                                 // ... and so are every other wave's
-  if (tid == 0 && total != 0)
-    __hip_atomic_store(&a.d->tail_units, units_w + total, __ATOMIC_RELAXED, SC_SYSTEM);   // publish
+  __syncthreads();                                 // s->pub / s->ubeg may be rewritten after this
   return total;
 }
 
@@ -893,15 +897,22 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   const rsrc_t rh = make_rsrc(a.hring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   while (true) {
-    // ---- poll the host ring (one lane; the only PCIe poller of the kernel) ----
-    if (tid == 0) {
+    // ---- poll the host ring (wavefront 0; the only PCIe poller of the kernel) ----
+    // Every poll also reads the next kPrefetch records of the ring in the same round trip.  When
+    // the doorbell then shows them published and their check words hold, they are already staged:
+    // a lone task reaches the workers after one PCIe read latency instead of two.
+    if (tid < 64) {
       uint64_t t, e;
+      v4i q;
+      const uint32_t g = tid >> 4, part = tid & 15u;               // record g of the prefetch window, 16-byte piece
       const bool have_pending = s->npend != 0;
       while (true) {
+        const uint32_t slot = (uint32_t)((mirrored + g) & a.cap_mask);
         t = __hip_atomic_load(&a.bell->tail, __ATOMIC_RELAXED, SC_SYSTEM);
         e = __hip_atomic_load(&a.bell->epoch_word, __ATOMIC_RELAXED, SC_SYSTEM);
+        q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
         ++polls;
-        if ((polls & 63u) == 0) __hip_atomic_store(&a.h->heartbeat, polls, __ATOMIC_RELAXED, SC_SYSTEM);
+        if (tid == 0 && (polls & 63u) == 0) __hip_atomic_store(&a.h->heartbeat, polls, __ATOMIC_RELAXED, SC_SYSTEM);
         if (t != mirrored || e != seen_epoch || stopping || have_pending) break;
         if (a.idle_exit_ticks != 0 && wall_clock64() - idle_since > a.idle_exit_ticks) {
           e |= 2u;                                  // behave as if the host had asked to stop
@@ -909,12 +920,21 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         }
       }
       order_loads();
+      // keep the prefetched records whose check word holds and that the doorbell value read in the
+      // same round covers
+      uint32_t x = (uint32_t)(q[0] ^ q[1] ^ q[2] ^ q[3]);
+      x ^= __shfl_xor(x, 8, 16); x ^= __shfl_xor(x, 4, 16); x ^= __shfl_xor(x, 2, 16); x ^= __shfl_xor(x, 1, 16);
+      const bool good = mirrored + g < t && x == record_check_seed(mirrored + g);
+      if (good) ((v4i*)&s->rec[g])[part] = q;
+      if (part == 0) s->pre[g] = good ? 1u : 0u;
       if (e & 3u) {                                 // stop: take the final tail after the flag
         t = __hip_atomic_load(&a.bell->tail, __ATOMIC_RELAXED, SC_SYSTEM);
         order_loads();
       }
-      s->tail = t;
-      s->epoch_word = e;
+      if (tid == 0) {
+        s->tail = t;
+        s->epoch_word = e;
+      }
     }
     __syncthreads();
     const uint64_t tail = s->tail, ew = s->epoch_word;
@@ -935,6 +955,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
     units_w += dispatcher_service_pending(a, s, units_w);
 
     // ---- mirror new records, batch by batch ----
+    bool first_batch = true;                       // the prefetched records belong to the first batch after a poll
     while (mirrored < tail) {
       // Dequeue only a bounded distance ahead of execution: the dependency state seen at dequeue
       // time is then close to what the workers will see, and the pending list stays short.
@@ -963,7 +984,8 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       // a record that has not landed completely yet, or is left over from the previous lap,
       // fails the check and is read again; one that never passes is completed with an error
       // instead of being executed.
-      if (tid < kDispatchBatch) s->bad[tid] = tid < n ? 1u : 0u;
+      if (tid < kDispatchBatch) s->bad[tid] = (tid < n && !(first_batch && tid < kPrefetch && s->pre[tid])) ? 1u : 0u;
+      first_batch = false;
       __syncthreads();
       for (uint32_t attempt = 0; attempt < kStageRetries; ++attempt) {
         for (uint32_t p = tid; p < n * 16u; p += kThreads) {
@@ -1085,11 +1107,14 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
     }
     if (stopping && mirrored >= tail) {
       while (s->npend != 0) units_w += dispatcher_service_pending(a, s, units_w);   // nothing is left behind
+      drain_stores();                                  // every unit store of every wave has landed ...
+      __syncthreads();                                 // ... before the stop flag can be seen
       if (tid == 0) {
         uint64_t* st = a.d->stat;
         st[ST_DISP_BATCHES] = st_batches; st[ST_DISP_RECORDS] = st_records; st[ST_DISP_UNITS] = st_units;
         st[ST_DISP_TICKS_STAGE] = st_stage; st[ST_DISP_TICKS_RESOLVE] = st_resolve; st[ST_DISP_TICKS_WRITE] = st_write;
         st[ST_DISP_TICKS_TOTAL_BUSY] = st_busy; st[ST_DISP_POLLS] = polls; st[ST_DISP_DEFERRED] = st_deferred;
+        __hip_atomic_store(&a.d->tail_units, units_w, __ATOMIC_RELAXED, SC_SYSTEM);
         drain_stores();
         __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.h->exit_code, (ew & 2u) ? 2u : 1u, __ATOMIC_RELAXED, SC_SYSTEM);
@@ -1119,25 +1144,33 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
     // ---- claim one work unit (elected lane, atomic fetch-add) ----
     if (tid == 0) {
       const uint64_t g = __hip_atomic_fetch_add(&a.d->claim, 1ull, __ATOMIC_RELAXED, SC_AGENT);
+      const uint64_t* up = &a.units[g & a.unit_mask];
+      const uint64_t want = unit_stamp(g, a.unit_shift);
       int32_t ex = 0;
-      uint32_t polls = 0;
-      while (__hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM) <= g) {
-        if (__hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) {
-          order_loads();
-          if (__hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM) <= g) { ex = 1; break; }
-          continue;
+      uint32_t polls = 0, yield_every = 0;
+      uint64_t u;
+      // Poll the claimed entry itself (its stamp is the ready flag): one load per poll, and every
+      // waiting workgroup polls a different address.
+      while (((u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM)) >> 46) != want) {
+        ++polls;
+        if ((polls & 31u) == 0) {
+          if (__hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) {
+            order_loads();                             // every unit was stored before the stop flag
+            u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM);
+            if ((u >> 46) != want) ex = 1;
+            break;
+          }
+          yield_every = __hip_atomic_load(&a.d->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
         }
         // polling policy (paper Section 4.1): short back-off while spinning, longer
         // pauses every yield_every-th empty poll when the host asked for them
-        ++polls;
-        const uint32_t y = __hip_atomic_load(&a.d->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
-        if (y != 0 && (polls % y) == 0) { for (int k = 0; k < 16; ++k) __builtin_amdgcn_s_sleep(127); }
-        else if (polls < 64) __builtin_amdgcn_s_sleep(2);
-        else __builtin_amdgcn_s_sleep(16);
+        if (yield_every != 0 && (polls % yield_every) == 0) { for (int k = 0; k < 16; ++k) __builtin_amdgcn_s_sleep(127); }
+        else if (polls < 64) __builtin_amdgcn_s_sleep(1);
+        else __builtin_amdgcn_s_sleep(8);
       }
       order_loads();
       s->exit_flag = ex;
-      if (!ex) s->unit = __hip_atomic_load(&a.units[g & a.unit_mask], __ATOMIC_RELAXED, SC_SYSTEM);
+      s->unit = u;
     }
     __syncthreads();
     if (s->exit_flag) {

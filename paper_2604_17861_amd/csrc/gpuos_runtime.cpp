@@ -552,6 +552,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       !hip_ok(hipEventCreate(&c->ev_stop), "hipEventCreate") ||
       !hip_ok(hipMemsetAsync(c->d, 0, sizeof(DevCtl), c->stream), "hipMemsetAsync") ||
       !hip_ok(hipMemsetAsync(c->st, 0, sizeof(SlotState) * cap, c->stream), "hipMemsetAsync") ||
+      !hip_ok(hipMemsetAsync(c->units, 0, sizeof(uint64_t) * n_units, c->stream), "hipMemsetAsync") ||
       !hip_ok(hipMemsetAsync(c->dtable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS, c->stream), "hipMemsetAsync") ||
       !hip_ok(hipStreamSynchronize(c->stream), "hipStreamSynchronize"))
     return fail(GPUOS_E_HIP);
@@ -572,6 +573,8 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   a.d = c->d; a.dring = c->dring; a.units = c->units; a.st = c->st; a.dtable = c->dtable;
   a.cap_mask = c->mask;
   a.unit_mask = (uint32_t)(n_units - 1);
+  a.unit_shift = 0;
+  while (((size_t)1 << a.unit_shift) < n_units) ++a.unit_shift;
   a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
   if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
   if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);

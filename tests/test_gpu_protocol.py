@@ -273,3 +273,26 @@ def test_two_contexts_side_by_side():
         a.wait(); b.wait()
     assert compare_with_oracle(s1, d1.download())["max_ulp"] == 0
     assert compare_with_oracle(s2, d2.download())["max_ulp"] == 0
+
+
+def test_push_mode_ring_in_device_memory():
+    """push_ring = 1: ring, doorbell and table source live in device memory and the host writes them
+    through the PCIe BAR.  Same results, same version invariants, wrap-around included."""
+    import parity_cases as C
+    from gpu_helpers import compare_with_oracle, run_stream
+    for s, cap in ((C.config2_reduced(), 0), (C.config4_reduced(), 64), (S.config3(n_chains=6, buffer_sets=1, Bs=(1, 2), Ss=(64, 128)), 32)):
+        print("push mode", s.name, "capacity", cap or 4096, flush=True)
+        dp = _dev(s)
+        with R.Runtime(cap, push_ring=1, **CFG) as rt:
+            rt.register_table(s.table)
+            t0 = run_stream(s, rt, dp)
+            comps = rt.completions(t0, len(s))
+            lat = rt.run_serial(dp.tasks, 0, 20)
+        assert np.all(comps["status"] == 0) and np.all(lat > 0)
+        stats = compare_with_oracle(s, dp.download(), versions=comps["op_version"])
+        print(stats, flush=True)
+        if s.swaps:
+            v = comps["op_version"].astype(np.int64)
+            gelu = s.tasks["op_id"] == S.OP_GELU
+            for k, (t, _, _) in enumerate(s.swaps):
+                assert np.all(v[t:][gelu[t:]] >= k + 2)
