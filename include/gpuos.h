@@ -265,6 +265,16 @@ int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n,
  * move: each distinct input element once, each output element once). */
 int gpuos_task_bytes(const gpuos_task* task, uint32_t impl_id, uint64_t* out_bytes);
 
+/* How the host would hand this task to the workers (no GPU needed): out[0] =
+ * execution path (0 nothing to do, 1 contiguous vector, 2 [rows, cols]
+ * with row-vector / per-row-scalar operands, 3 generic strided walk,
+ * 4 contiguous-row reduction, 5 generic reduction, 6 LDS-tiled transposed
+ * gather),
+ * out[1] = work units (chunks) the task is split into, out[2] = size of one
+ * unit in the path's own unit (elements, rows or 32 x 32 tiles), out[3] =
+ * dims left after merging adjacent dims.  For tests and for sizing. */
+int gpuos_task_plan(const gpuos_task* task, uint32_t impl_id, uint32_t out[4]);
+
 const char* gpuos_strerror(int status);
 const char* gpuos_last_hip_error(void);   /* text of the last failed HIP call     */
 

@@ -282,7 +282,7 @@ DEV void ew_contig_int(const Record* r, uint32_t begin, uint32_t end) {
 // width; each input is a full [R, C] tensor (dtype DT), a row vector [C]
 // broadcast over rows (dtype DT), or one scalar per row (any float dtype).
 // ---------------------------------------------------------------------------
-constexpr uint32_t kScratchFloats = 2048;   // LDS scratch per workgroup (broadcast staging, reduction partials)
+constexpr uint32_t kScratchFloats = 3200;   // LDS scratch per workgroup (broadcast staging, transpose tiles, reduction partials)
 
 template <int POL, int IMPL, int DT>
 DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end, float* s_scratch) {
@@ -349,6 +349,69 @@ DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end, float* s_scratc
     M::st16(ro, v * 16u, res);
   }
   if (staged) __syncthreads();        // the scratch may be reused by the next chunk
+}
+
+// ---------------------------------------------------------------------------
+// PATH_TILE2D: contiguous [B, R, C] output where at least one input is stored with R as its
+// unit-stride dim (a transposed view).  Such an input is gathered through a 32 x 32 LDS tile:
+// it is read along ITS contiguous dim (coalesced), written to LDS, and read back transposed
+// (pitch 33: no bank conflicts), so neither side of the transpose touches memory with a stride.
+// Row-major inputs (unit stride along C, any row pitch, including 0 for a broadcast row) are
+// read directly.  Any float dtype per operand.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kTile = 32, kTilePitch = 33;
+
+template <int POL, int IMPL>
+DEV void ew_tile2d(const Record* r, uint32_t tile_begin, uint32_t tile_end, float* s_scratch) {
+  constexpr int N = Op<IMPL>::N;
+  const uint32_t R = uni(r->size[1]), C = uni(r->size[2]);
+  const uint32_t tr = (R + kTile - 1) / kTile, tc = (C + kTile - 1) / kTile;
+  const char* p[3];
+  uint32_t kind[3], dt[3], sb[3], sr[3], sc[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int kk = k < N ? k : 0;
+    p[k] = uni_ptr(r->ptr[kk]);
+    kind[k] = uni(r->okind[kk]);
+    dt[k] = uni(r->dtype[kk]);
+    sb[k] = uni(r->stride[kk][0]); sr[k] = uni(r->stride[kk][1]); sc[k] = uni(r->stride[kk][2]);
+  }
+  char* po = (char*)uni_ptr(r->ptr[3]);
+  const uint32_t odt = uni(r->dtype[3]);
+  const float alpha = r->alpha;
+  const uint32_t tid = threadIdx.x;
+  for (uint32_t t = tile_begin; t < tile_end; ++t) {
+    const uint32_t b = t / (tr * tc), rem = t - b * tr * tc;
+    const uint32_t ti = rem / tc, tj = rem - ti * tc;
+    const uint32_t r0 = ti * kTile, c0 = tj * kTile;
+    // stage the transposed operands: lanes run along r (their contiguous dim)
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+      if (kind[k] == K_TRANSPOSED) {
+        float* tile = s_scratch + k * (kTile * kTilePitch);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t idx = tid + i * kThreads, rr = idx & (kTile - 1), cc = idx / kTile;
+          if (r0 + rr < R && c0 + cc < C)
+            tile[cc * kTilePitch + rr] = load_rt<POL>(p[k], b * sb[k] + (r0 + rr) + (c0 + cc) * sc[k], dt[k]);
+        }
+      }
+    __syncthreads();
+    // compute: lanes run along c (the output's contiguous dim)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t idx = tid + i * kThreads, cc = idx & (kTile - 1), rr = idx / kTile;
+      if (r0 + rr < R && c0 + cc < C) {
+        float x[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < N; ++k)
+          x[k] = kind[k] == K_TRANSPOSED ? s_scratch[k * (kTile * kTilePitch) + cc * kTilePitch + rr]
+                                         : load_rt<POL>(p[k], b * sb[k] + (r0 + rr) * sr[k] + (c0 + cc), dt[k]);
+        store_rt<POL>(po, (b * R + r0 + rr) * C + c0 + cc, odt, Op<IMPL>::f(x[0], x[1], x[2], alpha));
+      }
+    }
+    __syncthreads();                  // the tiles are rewritten by the next iteration
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -698,6 +761,8 @@ DEV void run_elementwise(const Record* r, uint32_t chunk, float* s_scratch) {
     if (dt == GPUOS_F32) ew_row2d<POL, I2, GPUOS_F32>(r, begin, end, s_scratch);
     else if (dt == GPUOS_F16) ew_row2d<POL, I2, GPUOS_F16>(r, begin, end, s_scratch);
     else ew_row2d<POL, I2, GPUOS_BF16>(r, begin, end, s_scratch);
+  } else if (path == PATH_TILE2D) {
+    ew_tile2d<POL, IMPL>(r, begin, end, s_scratch);      // begin / end count tiles here
   } else {
     ew_generic<POL, IMPL, false>(r, begin, end);
   }

@@ -220,6 +220,46 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
     }
     // chunk_elems is quoted for 12 bytes of traffic per element (an fp32 binary op); scale it so
     // that a chunk of any op moves about the same number of bytes
+    // [B, R, C] contiguous output with an input whose unit stride runs along R (a transposed
+    // view): gathered through LDS tiles.  COPY between equal dtypes stays on the generic path,
+    // which moves raw bits (NaN payloads survive).
+    if (rec.path == PATH_GENERIC && !all_int && (nd == 2 || nd == 3) &&
+        !(impl == GPUOS_IMPL_COPY && same_dt)) {
+      const int o = nd - 2;                                      // index of R
+      const int64_t R = size[o], C = size[o + 1], B = nd == 3 ? size[0] : 1;
+      const Operand& out = ops[ar];
+      bool ok = R >= 8 && C >= 8 && out.stride[o + 1] == 1 && out.stride[o] == C &&
+                (nd == 2 || B == 1 || out.stride[0] == R * C);
+      bool any_t = false;
+      uint8_t kinds[3] = {0, 0, 0};
+      for (int k = 0; k < ar && ok; ++k) {
+        const int64_t sr = ops[k].stride[o], sc = ops[k].stride[o + 1];
+        if (sc == 1) kinds[k] = K_FULL;
+        else if (sr == 1) { kinds[k] = K_TRANSPOSED; any_t = true; }
+        else ok = false;
+      }
+      if (ok && any_t) {
+        rec.path = PATH_TILE2D;
+        rec.ndim = 3;
+        rec.size[0] = (uint32_t)B; rec.size[1] = (uint32_t)R; rec.size[2] = (uint32_t)C;
+        for (int k = 0; k <= ar; ++k) {
+          const int kk = k < ar ? k : 3;
+          rec.stride[kk][0] = nd == 3 ? (uint32_t)ops[k].stride[0] : 0u;
+          rec.stride[kk][1] = (uint32_t)ops[k].stride[o];
+          rec.stride[kk][2] = (uint32_t)ops[k].stride[o + 1];
+          if (k < ar) rec.okind[k] = kinds[k];
+        }
+        const uint64_t tiles = (uint64_t)B * ((R + 31) / 32) * ((C + 31) / 32);
+        uint64_t per_t = (tiles + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
+        const uint64_t want = chunk_elems / 1024 ? chunk_elems / 1024 : 1;    // tiles of 1024 elements
+        if (per_t < want) per_t = want;
+        rec.numel = (uint32_t)tiles;
+        rec.chunk = (uint32_t)per_t;
+        rec.nchunks = (uint32_t)((tiles + per_t - 1) / per_t);
+        *r = rec;
+        return GPUOS_OK;
+      }
+    }
     uint64_t traffic = dtype_size(ops[ar].dtype);
     for (int k = 0; k < ar; ++k) traffic += dtype_size(ops[k].dtype);
     uint64_t base_per = ((uint64_t)chunk_elems * 12 / traffic + 1023) / 1024 * 1024;
@@ -842,6 +882,15 @@ int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n, con
   if (out_seconds) *out_seconds = (double)(now_ns() - t0) * 1e-9;
   (void)hipStreamDestroy(s);
   return rc;
+}
+
+int gpuos_task_plan(const gpuos_task* t, uint32_t impl, uint32_t out[4]) {
+  if (!t || !out) return GPUOS_E_INVAL;
+  Record r;
+  const int rc = pack_task(*t, impl, &r);
+  if (rc != GPUOS_OK) return rc;
+  out[0] = r.path; out[1] = r.nchunks; out[2] = r.chunk; out[3] = r.ndim;
+  return GPUOS_OK;
 }
 
 int gpuos_task_bytes(const gpuos_task* t, uint32_t impl, uint64_t* out_bytes) {

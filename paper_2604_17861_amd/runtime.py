@@ -90,6 +90,7 @@ def lib():
         "gpuos_run_serial": (ctypes.c_int, [vp, vp, u32, vp]),
         "gpuos_launch_per_op": (ctypes.c_int, [i32, vp, u32, vp, i32, vp, P(ctypes.c_double)]),
         "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
+        "gpuos_task_plan": (ctypes.c_int, [vp, u32, vp]),
         "gpuos_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "gpuos_last_hip_error": (ctypes.c_char_p, []),
         "gpuos_abi_layout": (None, [vp]),
@@ -105,7 +106,7 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_strerror",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
 
@@ -290,6 +291,16 @@ def task_bytes(tasks, impls):
         _check(L.gpuos_task_bytes(_tasks_ptr(tasks, i), int(impls[i]), ctypes.byref(b)), "gpuos_task_bytes")
         out[i] = b.value
     return out
+
+
+PATHS = ("NOP", "CONTIG", "ROW2D", "GENERIC", "RED_CONTIG", "RED_GENERIC", "TILE2D")
+
+
+def task_plan(tasks, i, impl):
+    """(path name, chunks, chunk size, merged dims) the host packs task i into (gpuos_task_plan)."""
+    out = (ctypes.c_uint32 * 4)()
+    _check(lib().gpuos_task_plan(_tasks_ptr(tasks, i), int(impl), out), "gpuos_task_plan")
+    return PATHS[out[0]], int(out[1]), int(out[2]), int(out[3])
 
 
 @atexit.register

@@ -4,7 +4,7 @@ runs it through the library and compares with the oracle."""
 import numpy as np
 
 from paper_2604_17861_amd import streams as S
-from helpers import Builder
+from helpers import Builder, np_dtype
 
 ELEMENTWISE = ["ADD", "SUB", "MUL", "DIV", "RELU", "EXP", "GELU_ERF", "GELU_TANH", "SCALE", "FMA", "SUB_EXP", "COPY"]
 
@@ -170,6 +170,38 @@ def broadcast_2d():
     return b.stream("broadcast_2d")
 
 
+def transposed_2d():
+    """Contiguous [B, R, C] outputs whose inputs mix transposed views (unit stride along R, column
+    pitch >= R), row-major views with a row pitch, broadcast rows and broadcast columns: the
+    LDS-tiled gather.  Sizes below, at and across the 32 x 32 tile with ragged edges, several
+    chunks, every float dtype pair."""
+    rng = np.random.default_rng(9)
+    b = Builder()
+    shapes = ((1, 8, 8), (1, 33, 65), (3, 40, 31), (2, 100, 260), (1, 257, 1030), (5, 64, 64), (1, 9, 3000))
+    for n, (B_, R_, C_) in enumerate(shapes):
+        for code in (S.F32, S.F16, S.BF16):
+            ocode = (S.F32, S.F16, S.BF16)[(n + code) % 3]
+            pad = int(rng.integers(0, 5))
+            # stored [B, C, R + pad]: viewed as [B, R, C] its unit stride runs along R
+            at = b.pool(to_dtype(rng.standard_normal((B_, C_, R_ + pad)).astype(np.float32), code))
+            a_t = at[:, :, :R_].transpose(0, 2, 1)
+            bt = b.pool(rng.standard_normal((B_, C_, R_)).astype(np.float32))
+            b_t = bt.transpose(0, 2, 1)
+            full = b.pool(to_dtype(rng.standard_normal((B_, R_, C_ + 3)).astype(np.float32), code))[:, :, :C_]
+            row = np.broadcast_to(b.pool(to_dtype(rng.standard_normal(C_).astype(np.float32), code)), (B_, R_, C_))
+            col = np.broadcast_to(b.pool(rng.standard_normal(R_).astype(np.float32))[None, :, None], (B_, R_, C_))
+            bsame = np.broadcast_to(b_t[:1], (B_, R_, C_))          # batch stride 0 on a transposed operand
+            for name, ins in (("COPY", [a_t]), ("GELU_TANH", [a_t]), ("ADD", [a_t, full]), ("SUB", [full, a_t]),
+                              ("MUL", [a_t, b_t]), ("DIV", [a_t, row]), ("SUB_EXP", [a_t, col]),
+                              ("FMA", [a_t, b_t, full]), ("FMA", [row, bsame, a_t]), ("SCALE", [b_t])):
+                o = b.pool(np.zeros((B_, R_, C_), np_dtype(ocode)))
+                if B_ == 1 and name in ("ADD", "MUL"):
+                    b.add(name, o[0], [v[0] for v in ins], alpha=0.75)      # rank 2
+                else:
+                    b.add(name, o, ins, alpha=0.75)
+    return b.stream("transposed_2d")
+
+
 def reductions():
     """SUM / MAX / MIN over the last dim: row lengths from 1 to 20000 (sub-wave rows, one workgroup
     per row, scalar fallback for odd lengths), all float dtypes, fp32 and same-dtype outputs,
@@ -244,6 +276,7 @@ CPU_CHECKED = {
     "random_views_1": lambda: random_strided_views(1),
     "random_views_2": lambda: random_strided_views(2),
     "broadcast_2d": broadcast_2d,
+    "transposed_2d": transposed_2d,
     "reductions": reductions,
     "int32": int32_ops,
     "config2_reduced": config2_reduced,

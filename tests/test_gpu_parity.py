@@ -64,6 +64,11 @@ def test_row_and_column_broadcast_2d_fast_path():
     print(stats, flush=True)
 
 
+def test_transposed_views_lds_tiled_gather():
+    stats, _ = _run_and_check(C.transposed_2d())
+    print(stats, flush=True)
+
+
 def test_last_dim_reductions():
     stats, _ = _run_and_check(C.reductions())
     print(stats, flush=True)

@@ -88,3 +88,44 @@ def test_task_bytes_counts_each_distinct_element_once():
     got = [_status(hp.tasks, i, c3.impl_for()[i])[1] for i in range(6)]
     assert got == want
     assert sum(want) == 20 * n + 64 * 64 * 2 + 4 * rows * 4      # 20 bytes per score element plus the small vectors
+
+
+def test_task_plan_picks_the_execution_path_the_layout_calls_for():
+    """The host classifies each task by the strides left after merging dims: contiguous ->
+    vector path, row vector / per-row scalar -> 2-D path, a transposed input under a contiguous
+    output -> LDS tiles, anything else -> the generic walk; reductions by row contiguity."""
+    from helpers import Builder
+    b = Builder()
+    f = lambda *shape: b.pool(np.zeros(shape, np.float32))
+    a, c = f(4, 96, 80), f(4, 96, 80)
+    o = f(4, 96, 80)
+    at = f(4, 80, 96).transpose(0, 2, 1)
+    b.add("ADD", o, [a, c])                                              # 0 contiguous: dims merge to 1
+    b.add("ADD", o[0], [a[0], np.broadcast_to(f(80), (96, 80))])         # 1 row vector
+    b.add("SUB_EXP", o[0], [a[0], np.broadcast_to(f(96)[:, None], (96, 80))])   # 2 per-row scalar
+    b.add("MUL", o, [at, c])                                             # 3 transposed input, batched
+    b.add("MUL", o[0], [at[0], at[1]])                                   # 4 rank 2, both transposed
+    b.add("MUL", o[0, :4, :4], [at[0, :4, :4], c[0, :4, :4]])            # 5 output not contiguous
+    b.add("COPY", o.transpose(0, 2, 1), [f(4, 80, 96)])                  # 6 transposed OUTPUT: generic
+    b.add("COPY", o, [at])                                               # 7 same-dtype copy keeps raw bits: generic
+    b.add("RELU", o[:, ::2, :], [a[:, ::2, :]])                          # 8 gapped rows: generic
+    b.add("SUM_LAST", f(4, 96), [a])                                     # 9 contiguous rows
+    b.add("MAX_LAST", f(4, 96), [at])                                    # 10 strided rows
+    b.add("ADD", f(4, 5)[:0], [f(4, 5)[:0], f(4, 5)[:0]])                # 11 empty
+    s = b.stream()
+    hp = HostPools(s)
+    impl = s.impl_for()
+    got = [R.task_plan(hp.tasks, i, impl[i]) for i in range(len(s))]
+    paths = [g[0] for g in got]
+    assert paths == ["CONTIG", "ROW2D", "ROW2D", "TILE2D", "TILE2D", "GENERIC", "GENERIC", "GENERIC", "GENERIC",
+                     "RED_CONTIG", "RED_GENERIC", "NOP"], paths
+    assert got[0][3] == 1                                  # [4, 96, 80] contiguous merges to one dim
+    assert got[3][1] * got[3][2] >= 4 * 3 * 3 and got[3][3] == 3      # 4 batches of 3 x 3 tiles
+    # a large transposed task splits into at most 1024 units that cover every tile
+    big = Builder()
+    src = big.pool(np.zeros((3000, 2100), np.float16)).T
+    big.add("RELU", big.pool(np.zeros((2100, 3000), np.float16)), [src])
+    sb = big.stream()
+    path, chunks, per, nd = R.task_plan(HostPools(sb).tasks, 0, S.IMPL["RELU"])
+    tiles = ((2100 + 31) // 32) * ((3000 + 31) // 32)
+    assert path == "TILE2D" and chunks <= 1024 and (chunks - 1) * per < tiles <= chunks * per
