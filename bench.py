@@ -155,6 +155,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--skip-extras", action="store_true", help="only the headline stream and the roofline leg")
+    ap.add_argument("--report", default="", help="directory for one JSON report per configuration")
     ap.add_argument("--only-roofline", action="store_true",
                     help="run nothing but the bandwidth stream through the persistent kernel (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -320,6 +321,46 @@ def main():
                 per_launch_p99_us=out["per_launch_p99_us"], extras=extras,
                 roofline=roofline, cpu_baseline=cpu_baseline)
     print(json.dumps(line), flush=True)
+    if args.report:
+        write_reports(args.report, R, line)
+
+
+def host_info():
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.startswith("model name"):
+                    model = ln.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return dict(nproc=os.cpu_count(), usable_cpus=len(os.sched_getaffinity(0)), cpu_model=model)
+
+
+def write_reports(directory, R, line):
+    """One JSON per configuration: what was run, on what, with which knobs, and the figures measured
+    by this process.  Parity figures are written by the GPU tests of the full configurations (they
+    own the comparison with the oracle), beside these files."""
+    os.makedirs(directory, exist_ok=True)
+    common = dict(device=R.device_info(0), host=host_info(),
+                  knobs=dict(queue_capacity=4096, workgroups=line["config"]["workgroups"], threads_per_workgroup=256,
+                             workgroups_per_cu=4), hbm_peak_gbps=HBM_PEAK_GBPS)
+    ex = line["extras"]
+    per = {
+        "config2": dict(seed=1, tasks=10000, persistent_tasks_per_s=line["value"],
+                        per_launch_tasks_per_s=line["per_launch_tasks_per_s"], speedup=line["speedup_vs_per_launch"],
+                        p50_us=line["p50_us"], p99_us=line["p99_us"], per_launch_p50_us=line["per_launch_p50_us"],
+                        per_launch_p99_us=line["per_launch_p99_us"], oracle_tasks_per_s=line["cpu_baseline"]["value"],
+                        oracle_sample=line["cpu_baseline"]["sample"], push_mode=ex.get("push_mode")),
+        "config1": dict(seed=0, tasks=1000, pingpong=ex.get("pingpong"), **ex.get("config1", {})),
+        "config3": dict(seed=2, tasks=12000, **ex.get("config3", {})),
+        "config4": dict(seed=3, **ex.get("config4", {})),
+        "config5": dict(seed=4, roofline=line["roofline"], **ex.get("config5", {})),
+    }
+    for name, body in per.items():
+        with open(os.path.join(directory, "perf_%s.json" % name), "w") as f:
+            json.dump(dict(config=name, **common, **body), f, indent=1)
 
 
 if __name__ == "__main__":

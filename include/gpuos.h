@@ -275,6 +275,14 @@ int gpuos_task_bytes(const gpuos_task* task, uint32_t impl_id, uint64_t* out_byt
  * dims left after merging adjacent dims.  For tests and for sizing. */
 int gpuos_task_plan(const gpuos_task* task, uint32_t impl_id, uint32_t out[4]);
 
+/* Properties of `device` as the HIP runtime reports them (for reports; the
+ * figures the roofline is priced against are the published ones, not these):
+ * out[0] compute units, out[1] core clock kHz, out[2] memory clock kHz,
+ * out[3] memory bus width bits, out[4] device memory bytes, out[5] L2 bytes,
+ * out[6] LDS bytes per workgroup, out[7] wavefront size.  name: HOST buffer
+ * of name_len bytes, always NUL-terminated (nullable). */
+int gpuos_device_info(int32_t device, uint64_t out[8], char* name, uint32_t name_len);
+
 const char* gpuos_strerror(int status);
 const char* gpuos_last_hip_error(void);   /* text of the last failed HIP call     */
 

@@ -47,6 +47,8 @@ def lib():
         L.orc_run_stream.restype = ctypes.c_int64
         L.orc_sum_last_f64.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.orc_sum_last_f64.restype = ctypes.c_int
+        L.orc_rowop_f64.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.orc_rowop_f64.restype = ctypes.c_int
         L.orc_f16_to_f32.argtypes = [ctypes.c_uint16]
         L.orc_f16_to_f32.restype = ctypes.c_float
         L.orc_f32_to_f16.argtypes = [ctypes.c_float]
@@ -96,3 +98,16 @@ def sum_last_f64(tasks, i, n_rows):
     if rc != 0:
         raise ValueError("orc_sum_last_f64 rc=%d" % rc)
     return s, l1
+
+
+def rowop_f64(tasks, i, impl):
+    """Unrounded fp64 results of a row operation (softmax family, layer norm) in the task's
+    row-major shape, and the per-element magnitude its fp32 evaluation error scales with."""
+    t = tasks[i]
+    shape = [int(x) for x in t["size"][: int(t["ndim"])]]
+    y = np.zeros(shape, dtype=np.float64)
+    scale = np.zeros(shape, dtype=np.float64)
+    rc = lib().orc_rowop_f64(tasks.ctypes.data + i * tasks.dtype.itemsize, int(impl), y.ctypes.data, scale.ctypes.data)
+    if rc != 0:
+        raise ValueError("orc_rowop_f64 rc=%d" % rc)
+    return y, scale

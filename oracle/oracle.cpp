@@ -25,6 +25,7 @@
 #include <cstddef>
 #include <cstring>
 #include <limits>
+#include <vector>
 
 namespace {
 
@@ -103,10 +104,16 @@ int arity_of(int impl) {
     case ORC_FMA: return 3;
     case ORC_RELU: case ORC_EXP: case ORC_GELU_ERF: case ORC_GELU_TANH: case ORC_SCALE:
     case ORC_COPY: case ORC_SUM_LAST: case ORC_MAX_LAST: case ORC_MIN_LAST: return 1;
+    case ORC_SOFTMAX_LAST: return 1;
+    case ORC_MASKED_SOFTMAX_LAST: return 2;
+    case ORC_LAYERNORM_LAST: return 3;
     default: return -1;
   }
 }
 bool is_reduction(int impl) { return impl == ORC_SUM_LAST || impl == ORC_MAX_LAST || impl == ORC_MIN_LAST; }
+bool is_rowop(int impl) {
+  return impl == ORC_SOFTMAX_LAST || impl == ORC_MASKED_SOFTMAX_LAST || impl == ORC_LAYERNORM_LAST;
+}
 bool int_capable(int impl) {
   return impl == ORC_ADD || impl == ORC_SUB || impl == ORC_MUL || impl == ORC_COPY || is_reduction(impl);
 }
@@ -224,7 +231,7 @@ int validate(const orc_task* t, int impl) {
     all_int = all_int && t->in[k].dtype == ORC_I32;
   }
   if (any_int && !all_int) return ORC_E_INVAL;
-  if (all_int && !int_capable(impl)) return ORC_E_INVAL;
+  if (all_int && !int_capable(impl)) return ORC_E_INVAL;   // row operations are float-only (not int_capable)
   return ORC_OK;
 }
 
@@ -307,6 +314,80 @@ void run_reduction(const orc_task* t, int impl) {
   }
 }
 
+// ---- fused row operations (Section 5.2: softmax, layer normalisation) ---------------
+// Each row of the last dim is one independent problem.  The definition is the textbook one,
+// evaluated in double from the inputs (fp16 / bf16 / fp32 -> double is exact); the result
+// passes through fp32 and is then rounded to the output dtype, like every other result here.
+//   softmax:        y_j = exp(t_j - m) / sum_k exp(t_k - m),  m = max_k t_k,
+//                   t = x  or  t = alpha * x + mask (alpha widened to double, product and
+//                   sum exact enough in double to count as exact);
+//                   a NaN anywhere in t, a row whose maximum is +inf, or a row of all -inf
+//                   gives NaN where the arithmetic above gives NaN (inf - inf);
+//   layer norm:     mean = sum x / n, var = sum (x - mean)^2 / n (biased), eps = alpha,
+//                   y_j = (x_j - mean) / sqrt(var + eps) * gamma_j + beta_j.
+// y (nullable): unrounded doubles, row-major over the task's shape.  scale (nullable): see
+// oracle.h.  store: write the rounded results into the task's output tensor.
+void run_rowop(const orc_task* t, int impl, bool store, double* y_out, double* scale_out) {
+  const int nd = t->ndim, ond = nd - 1;
+  const int64_t n = t->size[nd - 1];
+  int64_t outer = 1;
+  for (int d = 0; d < ond; ++d) outer *= t->size[d];
+  if (outer == 0 || n == 0) return;
+  int64_t s_last[3] = {0, 0, 0};
+  for (int k = 0; k < t->n_inputs; ++k) s_last[k] = eff_stride(t->in[k], nd - 1);
+  const int64_t so_last = t->out.stride[nd - 1];
+  std::vector<double> v((size_t)n), res((size_t)n), scl((size_t)n);
+  for (int64_t o = 0; o < outer; ++o) {
+    int64_t base[3] = {0, 0, 0};
+    for (int k = 0; k < t->n_inputs; ++k) base[k] = offset_of(t->in[k], ond, t->size, o);
+    const int64_t obase = offset_of(t->out, ond, t->size, o);
+    auto in = [&](int k, int64_t j) {
+      return (double)load_as_float(t->in[k].ptr, base[k] + j * s_last[k], t->in[k].dtype);
+    };
+    if (impl == ORC_LAYERNORM_LAST) {
+      double sum = 0.0;
+      for (int64_t j = 0; j < n; ++j) { v[(size_t)j] = in(0, j); sum += v[(size_t)j]; }
+      const double mean = sum / (double)n;
+      double ss = 0.0, maxdev = 0.0;
+      for (int64_t j = 0; j < n; ++j) {
+        const double d = v[(size_t)j] - mean;
+        ss += d * d;
+        if (std::fabs(d) > maxdev) maxdev = std::fabs(d);
+      }
+      const double var = ss / (double)n;
+      const double rstd = 1.0 / std::sqrt(var + (double)t->alpha);
+      for (int64_t j = 0; j < n; ++j) {
+        const double g = in(1, j), b = in(2, j);
+        res[(size_t)j] = (v[(size_t)j] - mean) * rstd * g + b;
+        scl[(size_t)j] = (std::fabs(v[(size_t)j]) + std::fabs(mean) + maxdev) * rstd * std::fabs(g) + std::fabs(b);
+      }
+    } else {
+      bool any_nan = false;
+      double m = -HUGE_VAL;
+      for (int64_t j = 0; j < n; ++j) {
+        double a = in(0, j);
+        if (impl == ORC_MASKED_SOFTMAX_LAST) a = (double)t->alpha * a + in(1, j);
+        v[(size_t)j] = a;
+        if (a != a) any_nan = true;
+        else if (a > m) m = a;
+      }
+      double sum = 0.0;
+      for (int64_t j = 0; j < n; ++j) { res[(size_t)j] = std::exp(v[(size_t)j] - m); sum += res[(size_t)j]; }
+      const double lg = std::log2((double)n);
+      for (int64_t j = 0; j < n; ++j) {
+        res[(size_t)j] = any_nan ? std::nan("") : res[(size_t)j] / sum;
+        const double dist = std::fabs(v[(size_t)j] - m);
+        scl[(size_t)j] = res[(size_t)j] * ((dist == dist && dist < HUGE_VAL ? dist : 0.0) + 8.0 + lg);
+      }
+    }
+    for (int64_t j = 0; j < n; ++j) {
+      if (y_out) y_out[o * n + j] = res[(size_t)j];
+      if (scale_out) scale_out[o * n + j] = scl[(size_t)j];
+      if (store) store_from_float(t->out.ptr, obase + j * so_last, t->out.dtype, (float)res[(size_t)j]);
+    }
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -318,6 +399,7 @@ int orc_run_task(const orc_task* t, int impl, int mode) {
   if (rc != ORC_OK) return rc;
   if (impl == ORC_FAIL) return ORC_E_BADOP;
   if (is_reduction(impl)) run_reduction(t, impl);
+  else if (is_rowop(impl)) run_rowop(t, impl, true, nullptr, nullptr);
   else run_elementwise(t, impl, mode);
   return ORC_OK;
 }
@@ -353,6 +435,14 @@ int orc_sum_last_f64(const orc_task* t, double* sum, double* l1) {
     sum[o] = s;
     l1[o] = a;
   }
+  return ORC_OK;
+}
+
+int orc_rowop_f64(const orc_task* t, int impl, double* y, double* scale) {
+  if (!is_rowop(impl)) return ORC_E_INVAL;
+  const int rc = validate(t, impl);
+  if (rc != ORC_OK) return rc;
+  run_rowop(t, impl, false, y, scale);
   return ORC_OK;
 }
 

@@ -31,7 +31,12 @@ enum {
   ORC_ADD = 1, ORC_SUB = 2, ORC_MUL = 3, ORC_DIV = 4, ORC_RELU = 5, ORC_EXP = 6,
   ORC_GELU_ERF = 7, ORC_GELU_TANH = 8, ORC_SCALE = 9, ORC_FMA = 10,
   ORC_SUB_EXP = 11, ORC_COPY = 12, ORC_SUM_LAST = 13, ORC_MAX_LAST = 14,
-  ORC_MIN_LAST = 15, ORC_FAIL = 16
+  ORC_MIN_LAST = 15, ORC_FAIL = 16,
+  /* fused row operations (Section 5.2 lists softmax and layer normalisation) */
+  ORC_SOFTMAX_LAST = 17,         /* y = softmax over the last dim of x                      */
+  ORC_MASKED_SOFTMAX_LAST = 18,  /* y = softmax over the last dim of alpha * x + mask       */
+  ORC_LAYERNORM_LAST = 19        /* y = (x - mean) / sqrt(var + alpha) * gamma + beta,
+                                    mean and (biased) variance over the last dim            */
 };
 enum { ORC_OK = 0, ORC_E_INVAL = -1, ORC_E_BADOP = -3 };
 enum { ORC_FLAG_FENCE = 1, ORC_FLAG_KEEPDIM = 2 };
@@ -81,6 +86,15 @@ int64_t orc_run_stream(const orc_task* tasks, int64_t n, const int32_t* impl,
  * entry per outer index in row-major order.  Used for the reduction
  * tolerance |g - o| <= 1e-5 * max(|o|, L1/sqrt(n)). */
 int orc_sum_last_f64(const orc_task* t, double* sum, double* l1);
+
+/* For a row operation (softmax, masked softmax, layer norm): the results
+ * BEFORE any rounding, evaluated in double from the inputs (each converted
+ * exactly to double), one value per element in row-major order of the task's
+ * shape; and per element the magnitude the floating-point error of an fp32
+ * evaluation scales with (`scale`, nullable): for the softmax family
+ * y * (|t - max| + 8 + log2 n) with t the softmax argument, for layer norm
+ * (|x| + |mean| + max|x - mean|) * rstd * |gamma| + |beta|. */
+int orc_rowop_f64(const orc_task* t, int impl, double* y, double* scale);
 
 /* scalar conversions, exported so the tests can sweep all 65536 patterns */
 float    orc_f16_to_f32(uint16_t h);

@@ -933,6 +933,25 @@ const char* gpuos_strerror(int status) {
   }
 }
 
+int gpuos_device_info(int32_t device, uint64_t out[8], char* name, uint32_t name_len) {
+  if (!out) return GPUOS_E_INVAL;
+  hipDeviceProp_t p;
+  HIP_TRY(hipGetDeviceProperties(&p, device));
+  out[0] = (uint64_t)p.multiProcessorCount;
+  out[1] = (uint64_t)p.clockRate;
+  out[2] = (uint64_t)p.memoryClockRate;
+  out[3] = (uint64_t)p.memoryBusWidth;
+  out[4] = (uint64_t)p.totalGlobalMem;
+  out[5] = (uint64_t)p.l2CacheSize;
+  out[6] = (uint64_t)p.sharedMemPerBlock;
+  out[7] = (uint64_t)p.warpSize;
+  if (name && name_len) {
+    std::strncpy(name, p.name, name_len - 1);
+    name[name_len - 1] = 0;
+  }
+  return GPUOS_OK;
+}
+
 const char* gpuos_last_hip_error(void) { return g_hip_error.c_str(); }
 
 void gpuos_abi_layout(uint32_t out[8]) {

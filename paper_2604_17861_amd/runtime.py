@@ -91,6 +91,7 @@ def lib():
         "gpuos_launch_per_op": (ctypes.c_int, [i32, vp, u32, vp, i32, vp, P(ctypes.c_double)]),
         "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
         "gpuos_task_plan": (ctypes.c_int, [vp, u32, vp]),
+        "gpuos_device_info": (ctypes.c_int, [i32, vp, vp, u32]),
         "gpuos_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "gpuos_last_hip_error": (ctypes.c_char_p, []),
         "gpuos_abi_layout": (None, [vp]),
@@ -106,7 +107,7 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_strerror",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
 
@@ -122,6 +123,18 @@ def abi_layout():
     out = np.zeros(8, dtype=np.uint32)
     lib().gpuos_abi_layout(out.ctypes.data)
     return out
+
+
+def device_info(device=0):
+    """What the HIP runtime reports for `device` (gpuos_device_info)."""
+    out = (ctypes.c_uint64 * 8)()
+    name = ctypes.create_string_buffer(128)
+    _check(lib().gpuos_device_info(int(device), out, name, 128), "gpuos_device_info")
+    keys = ("compute_units", "core_clock_khz", "memory_clock_khz", "memory_bus_bits", "memory_bytes", "l2_bytes",
+            "lds_bytes_per_workgroup", "wavefront")
+    d = {k: int(v) for k, v in zip(keys, out)}
+    d["name"] = name.value.decode()
+    return d
 
 
 def default_config():

@@ -36,11 +36,13 @@ F32, F16, BF16, I32 = 0, 1, 2, 3
 ELEM_SIZE = {F32: 4, F16: 2, BF16: 2, I32: 4}
 
 IMPL = dict(NONE=0, ADD=1, SUB=2, MUL=3, DIV=4, RELU=5, EXP=6, GELU_ERF=7, GELU_TANH=8, SCALE=9,
-            FMA=10, SUB_EXP=11, COPY=12, SUM_LAST=13, MAX_LAST=14, MIN_LAST=15, FAIL=16)
+            FMA=10, SUB_EXP=11, COPY=12, SUM_LAST=13, MAX_LAST=14, MIN_LAST=15, FAIL=16,
+            SOFTMAX_LAST=17, MASKED_SOFTMAX_LAST=18, LAYERNORM_LAST=19)
 IMPL_NAME = {v: k for k, v in IMPL.items()}
 ARITY = {1: 2, 2: 2, 3: 2, 4: 2, 5: 1, 6: 1, 7: 1, 8: 1, 9: 1, 10: 3, 11: 2, 12: 1, 13: 1, 14: 1,
-         15: 1, 16: 1}
+         15: 1, 16: 1, 17: 1, 18: 2, 19: 3}
 REDUCTIONS = (13, 14, 15)
+ROWOPS = (17, 18, 19)          # fused row operations: the output has the input's full shape
 
 # Logical operator ids the streams use.  They differ from the impl ids on
 # purpose (id = impl + 32) so that a mix-up of the two shows; OP_GELU is the

@@ -1,6 +1,8 @@
 """GPU-side test plumbing: pools in device memory (torch is used for allocation and copies only),
 running a stream through the C ABI binding, and the element-by-element comparison against the
 CPU oracle with the tolerances the build states."""
+import json
+import os
 import math
 
 import numpy as np
@@ -150,3 +152,21 @@ def _ulp_size(v, dt):
     frac = 10 if dt == S.F16 else 7
     a = np.maximum(np.abs(v), 2.0 ** -14 if dt == S.F16 else 2.0 ** -126)
     return 2.0 ** (np.floor(np.log2(a)) - frac)
+
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def parity_report(config, parts, **more):
+    """One JSON per configuration beside bench.py's perf_<config>.json: what was compared with the
+    oracle and the worst deviations found (mismatches = tasks outside the tolerance, which the
+    comparison itself turns into a failed assertion, so a written report always says 0)."""
+    out = dict(config=config, compared_tasks=sum(p["tasks"] for p in parts),
+               compared_elements=sum(p["elements"] for p in parts),
+               max_ulp=max(p["max_ulp"] for p in parts),
+               max_reduction_error_ratio=max(p["max_red_ratio"] for p in parts), mismatches=0, **more)
+    d = os.path.join(ROOT, "gpurun_out")
+    os.makedirs(d, exist_ok=True)
+    with open(os.path.join(d, "parity_%s.json" % config), "w") as f:
+        json.dump(out, f, indent=1)
+    print(out, flush=True)

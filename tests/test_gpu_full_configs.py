@@ -17,7 +17,7 @@ CFG = dict(idle_exit_ms=30000, wait_timeout_ms=30000)
 
 
 def test_config2_full():
-    from gpu_helpers import DevicePools, run_stream, compare_with_oracle
+    from gpu_helpers import DevicePools, run_stream, compare_with_oracle, parity_report
     s = S.config2()
     print("config2 full: 10,000 tasks", flush=True)
     dp = DevicePools(s)
@@ -29,14 +29,14 @@ def test_config2_full():
     imgs = dp.download()
     with ThreadPoolExecutor(8) as ex:                      # harness parallelism over disjoint ticket ranges
         parts = list(ex.map(lambda k: compare_with_oracle(s, imgs, first=k * 1250, count=1250), range(8)))
-    print({k: max(p[k] for p in parts) for k in ("max_ulp", "max_red_ratio")}, flush=True)
+    parity_report("config2", parts, seed=1, tasks=len(s))
     assert max(p["max_ulp"] for p in parts) <= 2
 
 
 def test_config3_full_2000_chains():
     """All 2,000 chains run; the chains that last used each buffer set (24 of them) are compared task
     by task, and every surviving probability tensor is checked for the softmax properties."""
-    from gpu_helpers import DevicePools, run_stream, compare_with_oracle
+    from gpu_helpers import DevicePools, run_stream, compare_with_oracle, parity_report
     s = S.config3()
     print("config3 full: 12,000 tasks", flush=True)
     dp = DevicePools(s)
@@ -53,7 +53,8 @@ def test_config3_full_2000_chains():
     # compare backwards inside a chain: each task's inputs are still what the GPU left there
     with ThreadPoolExecutor(8) as ex:
         parts = list(ex.map(lambda c: compare_with_oracle(s, imgs, first=c * 6, count=6), sorted(last.values())))
-    print({k: max(p[k] for p in parts) for k in ("max_ulp", "max_red_ratio")}, flush=True)
+    parity_report("config3", parts, seed=2, tasks=len(s), note="the 24 chains that last wrote each buffer set, task "
+                   "by task; softmax properties on every surviving probability tensor")
     for (pi, k), c in last.items():
         b, n = s.info["pairs"][pi]
         lay = s.info["layout"][(b, n)][k]
@@ -67,7 +68,7 @@ def test_config4_full_million_tasks_with_hot_swaps():
     """1,000,000 tasks with 99 swaps under load.  Window w is copied back after its last task
     completed and before window w+2 (same memory) is submitted; every 5th window is compared in full
     against the oracle for the recorded versions; the version invariants are checked for all tasks."""
-    from gpu_helpers import DevicePools, compare_with_oracle
+    from gpu_helpers import DevicePools, compare_with_oracle, parity_report
     s = S.config4()
     window = s.info["window"]
     n_win = len(s) // window
@@ -111,13 +112,14 @@ def test_config4_full_million_tasks_with_hot_swaps():
         return compare_with_oracle(s, [in_img, img_out], versions=versions, first=w * window, count=window)
     with ThreadPoolExecutor(8) as ex:
         parts = list(ex.map(check, sorted(kept)))
-    print("windows compared:", sorted(kept), {k: max(p[k] for p in parts) for k in ("max_ulp",)}, flush=True)
+    parity_report("config4", parts, seed=3, tasks=len(s), swaps=len(s.swaps), windows_compared=sorted(kept),
+                   distinct_gelu_versions=int(len(np.unique(v[gelu]))))
 
 
 def test_config5_full_bandwidth_stream():
     """20,000 large tasks; outputs rotate through 64 slots, so the last 64 tasks are compared in full
     (inputs are read-only pools)."""
-    from gpu_helpers import compare_with_oracle
+    from gpu_helpers import compare_with_oracle, parity_report
     from bench import DevicePools as BenchPools, submit_pass
     s = S.config5()
     print("config5 full: 20,000 tasks", flush=True)
@@ -131,4 +133,4 @@ def test_config5_full_bandwidth_stream():
     first = len(s) - s.info["out_slots"]
     with ThreadPoolExecutor(8) as ex:
         parts = list(ex.map(lambda k: compare_with_oracle(s, imgs, first=first + 8 * k, count=8), range(8)))
-    print({k: max(p[k] for p in parts) for k in ("max_ulp", "max_red_ratio")}, flush=True)
+    parity_report("config5", parts, seed=4, tasks=len(s), note="the last 64 tasks (one per output slot) in full")

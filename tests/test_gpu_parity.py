@@ -29,6 +29,8 @@ def test_config1_full_bit_exact():
     print("config1: 1000 x fp32 ADD n=1024", flush=True)
     stats, comps = _run_and_check(S.config1())
     assert stats["max_ulp"] == 0 and stats["elements"] == 1000 * 1024
+    from gpu_helpers import parity_report
+    parity_report("config1", [stats], seed=0, tasks=1000)
     assert np.all(comps["op_version"] == 1)
 
 
