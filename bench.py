@@ -261,6 +261,22 @@ def main():
                                  per_launch_gbps=b3 / pl3 / 1e9, chains=len(s3) // 6)
         log("config3:", extras["config3"])
         del dp3
+        # ---- the same softmax as ONE fused task per chain (row operation, rows in registers) -------
+        s3f = S.config3_fused()
+        dp3f = DevicePools(s3f, torch)
+        b3f = int(R.task_bytes(dp3f.tasks, s3f.impl_for()).sum())
+        r3f = bench_persistent(R, s3f, dp3f, 3, 1)
+        R.launch_per_op(dp3f.tasks, s3f.table, count=200)
+        t0 = time.perf_counter()
+        R.launch_per_op(dp3f.tasks, s3f.table)
+        pl3f = time.perf_counter() - t0
+        extras["config3_fused"] = dict(persistent_softmax_per_s=r3f["tasks_per_s"], per_launch_softmax_per_s=len(s3f) / pl3f,
+                                       chain_softmax_per_s=r3["tasks_per_s"] / 6,
+                                       speedup_vs_chain=r3f["tasks_per_s"] / (r3["tasks_per_s"] / 6),
+                                       persistent_gbps=b3f * r3f["tasks_per_s"] / len(s3f) / 1e9,
+                                       per_launch_gbps=b3f / pl3f / 1e9, tasks=len(s3f))
+        log("config3 fused:", extras["config3_fused"])
+        del dp3f
         # ---- fourth configuration (hot swaps while running) -----------------------------------
         s4 = S.config4(n_tasks=args.cfg4_tasks)
         dp4 = DevicePools(s4, torch)

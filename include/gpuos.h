@@ -72,6 +72,19 @@ enum gpuos_dtype { GPUOS_F32 = 0, GPUOS_F16 = 1, GPUOS_BF16 = 2, GPUOS_I32 = 3 }
  *   floats, two's-complement wrap for I32; max/min propagate NaN)
  *   FAIL: kill-switch stub (paper Section 5.3): completes at once with
  *   status GPUOS_E_BADOP and writes nothing.
+ * Fused row operations (Section 5.2 names softmax and layer normalisation):
+ * every row of the last dim is one problem, the output has the input's shape,
+ * further inputs broadcast like any other operand.  Defined as the exact
+ * function of the inputs; the device evaluates in fp32 (row held in
+ * registers, one read and one write of the row) to within
+ * 2^-22 * (the magnitude its rounding errors scale with) of it, then rounds
+ * to the output dtype.  Float tensors only.
+ *   SOFTMAX_LAST (x): y_j = e^(x_j - m) / sum_k e^(x_k - m), m = max_k x_k
+ *   MASKED_SOFTMAX_LAST (x, mask): the same on t = a * x + mask
+ *     (mask entries of -inf give exactly 0; a row with a NaN, a +inf or
+ *     nothing but -inf is all NaN)
+ *   LAYERNORM_LAST (x, gamma, beta): (x - mean) / sqrt(var + a) * gamma + beta
+ *     with the mean and the biased variance of the row, a = epsilon.
  * I32 tensors are accepted by ADD SUB MUL COPY SUM_LAST MAX_LAST MIN_LAST only,
  * and only when every tensor of the task is I32. */
 enum gpuos_impl {
@@ -82,7 +95,9 @@ enum gpuos_impl {
   GPUOS_IMPL_SUB_EXP = 11, GPUOS_IMPL_COPY = 12,
   GPUOS_IMPL_SUM_LAST = 13, GPUOS_IMPL_MAX_LAST = 14, GPUOS_IMPL_MIN_LAST = 15,
   GPUOS_IMPL_FAIL = 16,
-  GPUOS_IMPL_COUNT = 17
+  GPUOS_IMPL_SOFTMAX_LAST = 17, GPUOS_IMPL_MASKED_SOFTMAX_LAST = 18,
+  GPUOS_IMPL_LAYERNORM_LAST = 19,
+  GPUOS_IMPL_COUNT = 20
 };
 
 /* ---- task flags --------------------------------------------------------- */
@@ -183,8 +198,8 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* cfg
  * version+1 with a store-release.  The worker never stops.  A task keeps the
  * slot and version it claimed; before a slot is overwritten the call waits
  * (bounded by wait_timeout_ms) until no unfinished task can still hold it.
- * The new impl must have the arity and kind (elementwise / reduction) of the
- * old one, or be GPUOS_IMPL_FAIL.  *out_version (nullable) gets the version.
+ * The new impl must have the arity and kind (elementwise / reduction / row
+ * operation) of the old one, or be GPUOS_IMPL_FAIL.  *out_version (nullable) gets the version.
  * Tasks submitted after the call returns observe a version >= *out_version. */
 int gpuos_register_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t impl_id, uint32_t* out_version);
 int gpuos_swap_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t impl_id, uint32_t* out_version);
@@ -269,7 +284,8 @@ int gpuos_task_bytes(const gpuos_task* task, uint32_t impl_id, uint64_t* out_byt
  * execution path (0 nothing to do, 1 contiguous vector, 2 [rows, cols]
  * with row-vector / per-row-scalar operands, 3 generic strided walk,
  * 4 contiguous-row reduction, 5 generic reduction, 6 LDS-tiled transposed
- * gather),
+ * gather, 7 row operation with rows in registers, 8 row operation over any
+ * strides),
  * out[1] = work units (chunks) the task is split into, out[2] = size of one
  * unit in the path's own unit (elements, rows or 32 x 32 tiles), out[3] =
  * dims left after merging adjacent dims.  For tests and for sizing. */

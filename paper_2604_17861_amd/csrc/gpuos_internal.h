@@ -21,8 +21,11 @@ enum Path : uint8_t {
   PATH_GENERIC = 3,      // index decomposition over <= 6 dims, any strides / dtypes
   PATH_RED_CONTIG = 4,   // last-dim reduction of a contiguous [rows, n] input
   PATH_RED_GENERIC = 5,  // last-dim reduction, any strides
-  PATH_TILE2D = 6        // [R, C] contiguous output, >= 1 input stored transposed:
+  PATH_TILE2D = 6,       // [R, C] contiguous output, >= 1 input stored transposed:
                          // gathered through an LDS tile
+  PATH_ROW_FUSED = 7,    // row operation (softmax, layer norm): contiguous rows of whole
+                         // 16-byte vectors, one dtype, a row lives in one wavefront's registers
+  PATH_ROW_GENERIC = 8   // row operation over any strides / dtypes: three passes over memory
 };
 
 enum RecFlag : uint8_t {
@@ -32,7 +35,8 @@ enum RecFlag : uint8_t {
   RF_DEPS_RESOLVED = 8   // set by the dispatcher: published only after the dependencies completed
 };
 
-enum OperandKind : uint8_t { K_FULL = 0, K_ROWVEC = 1, K_ROWSCALAR = 2, K_TRANSPOSED = 3 };
+enum OperandKind : uint8_t { K_FULL = 0, K_ROWVEC = 1, K_ROWSCALAR = 2, K_TRANSPOSED = 3,
+                             K_PERIODIC = 4 };   // PATH_ROW_FUSED: contiguous [period, n] block reused every `period` rows
 
 constexpr uint32_t kMaxChunksPerTask = 1024;   // unit ring holds capacity * this entries
 constexpr uint32_t kChunkElems = 16384;        // minimum elements per chunk
@@ -56,17 +60,19 @@ struct alignas(16) Record {
   uint32_t version;          // table version the task claimed        (dispatcher)
   int32_t  status;           // 0, or the error the task completes with (dispatcher)
   uint32_t nchunks;
-  uint32_t chunk;            // elements (elementwise) or rows (reduction) per chunk
-  uint32_t numel;            // elementwise: output elements; reduction: output rows
-  uint32_t red_n;            // reduction length
+  uint32_t chunk;            // elements (elementwise) or rows (reduction, row operation) per chunk
+  uint32_t numel;            // elementwise: output elements; reduction / row operation: rows
+  uint32_t red_n;            // reduction / row length
   float    alpha;
   uint16_t dep[3];
   uint16_t pad1;
   uint64_t ticket;
   uint64_t ptr[4];           // in0, in1, in2, out (device addresses)
   uint32_t size[6];          // coalesced iteration shape (reductions: outer dims)
-  uint32_t stride[4][6];     // elements; 0 on broadcast dims; reductions: stride[0][5]
-                             // is the input stride along the reduced dim
+  uint32_t stride[4][6];     // elements; 0 on broadcast dims; reductions and row operations:
+                             // stride[k][5] is operand k's stride along the last dim, dims
+                             // 0..ndim-1 are the outer dims; PATH_ROW_FUSED: stride[k][0] is
+                             // the period (rows) of a K_PERIODIC input
   uint32_t pad2[9];
   uint32_t check;            // xor of the 63 words above ^ record_check_seed(ticket): set by the host
 };

@@ -734,6 +734,233 @@ DEV void red_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
 }
 
 // ---------------------------------------------------------------------------
+// fused row operations (operator library, Section 5.2: softmax, layer normalisation).
+// Each row of the last dim is one problem; the output has the input's shape.
+//   PATH_ROW_FUSED: one dtype, contiguous rows of whole aligned 16-byte vectors, at most 256
+//     vectors per row.  A row is read once into the registers of the P lanes that own it
+//     (P = 64 for rows over 64 vectors, else the power of two >= vectors per row, 64 / P rows
+//     per wavefront pass), reduced with xor butterflies over those lanes, and written once.
+//   PATH_ROW_GENERIC: any strides and dtypes; one wavefront per row, three passes over memory.
+// Arithmetic is fp32.  Lanes outside a row feed the identity (-inf to the softmax, 0 to the
+// sums).  The softmax maximum ignores NaN; a NaN still poisons its row through the sum.
+// ---------------------------------------------------------------------------
+DEV float bfly_sum(float v, uint32_t width) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1)
+    if ((uint32_t)off < width) v += __shfl_xor(v, off, 64);
+  return v;
+}
+DEV float bfly_max(float v, uint32_t width) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1)
+    if ((uint32_t)off < width) v = __builtin_fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+template <int ROP> struct RowOp {
+  static constexpr int NIN = ROP == GPUOS_IMPL_SOFTMAX_LAST ? 1 : (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? 2 : 3);
+  static constexpr bool SOFTMAX = ROP != GPUOS_IMPL_LAYERNORM_LAST;
+};
+
+template <int POL, int ROP, int DT, int KW, int UP>
+DEV void rowop_fused(const Record* r, uint32_t row_begin, uint32_t row_end) {
+  using E = Elem<DT>;
+  using M = Mem<POL>;
+  using RO = RowOp<ROP>;
+  constexpr uint32_t V = E::V;
+  const uint32_t n = uni(r->red_n), vpr = n / V;
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  uint32_t P = 64;
+  if (KW == 1) { P = 1; while (P < vpr) P <<= 1; }
+  const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
+  const float alpha = r->alpha;
+  const uint32_t nrows = row_end - row_begin;
+  const uint32_t chunk_bytes = nrows * n * E::ES;
+  const uint64_t chunk_off = (uint64_t)row_begin * n * E::ES;
+  const rsrc_t rx = make_rsrc(uni_ptr(r->ptr[0]) + chunk_off, chunk_bytes);
+  const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + chunk_off, chunk_bytes);
+  // second / third input: laid out like x (K_FULL) or a [period, n] block reused every period rows
+  rsrc_t rs[2];
+  uint32_t period[2] = {0, 0};
+#pragma unroll
+  for (int k = 1; k < RO::NIN; ++k) {
+    if (uni(r->okind[k]) == K_FULL) {
+      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]) + chunk_off, chunk_bytes);
+    } else {
+      period[k - 1] = uni(r->stride[k][0]);
+      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), period[k - 1] * n * E::ES);
+    }
+  }
+  // layer norm: gamma and beta are row vectors (period 1): this lane's pieces are loaded once
+  v4i gq[KW], bq[KW];
+  if (!RO::SOFTMAX) {
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      const uint32_t vec = j + 64u * k;
+      gq[k] = M::ld16(rs[0], vec * 16u);             // past the row: reads zeros (bounds-checked), never used
+      bq[k] = M::ld16(rs[1], vec * 16u);
+    }
+  }
+  for (uint32_t base = row_begin + wave * rpw * UP; base < row_end; base += 4u * rpw * UP) {
+    v4i q[UP][KW], mq[UP][KW];
+    bool act[UP][KW];
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+      const uint32_t row = base + u * rpw + sub, lr = row - row_begin;
+      uint32_t mr = lr;
+      if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST && period[0]) mr = row % period[0];
+#pragma unroll
+      for (int k = 0; k < KW; ++k) {
+        const uint32_t vec = j + 64u * k;
+        act[u][k] = row < row_end && vec < vpr;
+        // rows past the chunk and vectors past the row read zeros or a neighbour's data; masked below
+        q[u][k] = M::ld16(rx, (lr * vpr + vec) * 16u);
+        if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) mq[u][k] = M::ld16(rs[0], (mr * vpr + vec) * 16u);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+      const uint32_t row = base + u * rpw + sub, lr = row - row_begin;
+      float t[KW][V];
+      if (RO::SOFTMAX) {
+        float m = -__builtin_inff();
+#pragma unroll
+        for (int k = 0; k < KW; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) {
+            float x = E::get(q[u][k], e);
+            if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) x = alpha * x + E::get(mq[u][k], e);
+            t[k][e] = act[u][k] ? x : -__builtin_inff();
+            m = __builtin_fmaxf(m, t[k][e]);
+          }
+        m = bfly_max(m, P);
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KW; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) { t[k][e] = __expf(t[k][e] - m); s += t[k][e]; }
+        s = bfly_sum(s, P);
+        const float inv = 1.0f / s;
+#pragma unroll
+        for (int k = 0; k < KW; ++k) {
+          v4i oq;
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * inv);
+          if (act[u][k]) M::st16(ro, (lr * vpr + j + 64u * k) * 16u, oq);
+        }
+      } else {
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KW; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[u][k] ? E::get(q[u][k], e) : 0.0f; s += t[k][e]; }
+        const float mean = bfly_sum(s, P) / (float)n;
+        float ss = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KW; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[u][k] ? t[k][e] - mean : 0.0f; ss += t[k][e] * t[k][e]; }
+        const float var = bfly_sum(ss, P) / (float)n;
+        const float rstd = 1.0f / __builtin_sqrtf(var + alpha);
+#pragma unroll
+        for (int k = 0; k < KW; ++k) {
+          v4i oq;
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * E::get(gq[k], e) + E::get(bq[k], e));
+          if (act[u][k]) M::st16(ro, (lr * vpr + j + 64u * k) * 16u, oq);
+        }
+      }
+    }
+  }
+}
+
+template <int POL, int ROP>
+DEV void rowop_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
+  using RO = RowOp<ROP>;
+  const int nd = (int)uni(r->ndim);                   // outer dims
+  const uint32_t n = uni(r->red_n);
+  const float alpha = r->alpha;
+  const char* p[3];
+  uint32_t dt[3], sl[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int kk = k < RO::NIN ? k : 0;
+    p[k] = uni_ptr(r->ptr[kk]); dt[k] = uni(r->dtype[kk]); sl[k] = uni(r->stride[kk][5]);
+  }
+  char* po = (char*)uni_ptr(r->ptr[3]);
+  const uint32_t odt = uni(r->dtype[3]), slo = uni(r->stride[3][5]);
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  for (uint32_t row = row_begin + wave; row < row_end; row += 4) {
+    uint32_t rem = row, off[3] = {0, 0, 0}, ooff = 0;
+#pragma unroll
+    for (int d = GPUOS_MAX_DIMS - 2; d >= 0; --d) {
+      if (d < nd) {
+        const uint32_t sz = uni(r->size[d]);
+        const uint32_t qd = rem / sz, idx = rem - qd * sz;
+        rem = qd;
+#pragma unroll
+        for (int k = 0; k < RO::NIN; ++k) off[k] += idx * uni(r->stride[k][d]);
+        ooff += idx * uni(r->stride[3][d]);
+      }
+    }
+    if (RO::SOFTMAX) {
+      auto arg = [&](uint32_t jx) {
+        float x = load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]);
+        if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) x = alpha * x + load_rt<POL>(p[1], off[1] + jx * sl[1], dt[1]);
+        return x;
+      };
+      float m = -__builtin_inff();
+      for (uint32_t jx = lane; jx < n; jx += 64) m = __builtin_fmaxf(m, arg(jx));
+      m = bfly_max(m, 64);
+      float s = 0.0f;
+      for (uint32_t jx = lane; jx < n; jx += 64) s += __expf(arg(jx) - m);
+      s = bfly_sum(s, 64);
+      const float inv = 1.0f / s;
+      for (uint32_t jx = lane; jx < n; jx += 64) store_rt<POL>(po, ooff + jx * slo, odt, __expf(arg(jx) - m) * inv);
+    } else {
+      float s = 0.0f;
+      for (uint32_t jx = lane; jx < n; jx += 64) s += load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]);
+      const float mean = bfly_sum(s, 64) / (float)n;
+      float ss = 0.0f;
+      for (uint32_t jx = lane; jx < n; jx += 64) {
+        const float d = load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]) - mean;
+        ss += d * d;
+      }
+      const float var = bfly_sum(ss, 64) / (float)n;
+      const float rstd = 1.0f / __builtin_sqrtf(var + alpha);
+      for (uint32_t jx = lane; jx < n; jx += 64) {
+        const float d = load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]) - mean;
+        store_rt<POL>(po, ooff + jx * slo, odt,
+                      d * rstd * load_rt<POL>(p[1], off[1] + jx * sl[1], dt[1]) + load_rt<POL>(p[2], off[2] + jx * sl[2], dt[2]));
+      }
+    }
+  }
+}
+
+template <int POL, int ROP, int DT>
+DEV void rowop_fused_dt(const Record* r, uint32_t begin, uint32_t end) {
+  const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
+  if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 2>(r, begin, end);
+  else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 1>(r, begin, end);
+  else rowop_fused<POL, ROP, DT, 4, 1>(r, begin, end);
+}
+
+template <int POL, int ROP>
+DEV void run_rowop(const Record* r, uint32_t chunk) {
+  const uint32_t per = uni(r->chunk), rows = uni(r->numel);
+  const uint32_t begin = chunk * per;
+  const uint32_t end = (rows - begin < per) ? rows : begin + per;
+  if (uni(r->path) == PATH_ROW_FUSED) {
+    const uint32_t dt = uni(r->dtype[3]);
+    if (dt == GPUOS_F32) rowop_fused_dt<POL, ROP, GPUOS_F32>(r, begin, end);
+    else if (dt == GPUOS_F16) rowop_fused_dt<POL, ROP, GPUOS_F16>(r, begin, end);
+    else rowop_fused_dt<POL, ROP, GPUOS_BF16>(r, begin, end);
+  } else {
+    rowop_generic<POL, ROP>(r, begin, end);
+  }
+}
+
+// ---------------------------------------------------------------------------
 // chunk executor: operator dispatch by implementation id (the role of the
 // paper's function-pointer table call, Section 4.1; here a switch over
 // precompiled implementations selected by the table entry).
@@ -804,6 +1031,9 @@ DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_
     case GPUOS_IMPL_SUM_LAST: run_reduction<POL, GPUOS_IMPL_SUM_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_MAX_LAST: run_reduction<POL, GPUOS_IMPL_MAX_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_MIN_LAST: run_reduction<POL, GPUOS_IMPL_MIN_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_SOFTMAX_LAST>(r, chunk); break;
+    case GPUOS_IMPL_MASKED_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_MASKED_SOFTMAX_LAST>(r, chunk); break;
+    case GPUOS_IMPL_LAYERNORM_LAST: run_rowop<POL, GPUOS_IMPL_LAYERNORM_LAST>(r, chunk); break;
     case GPUOS_IMPL_FAIL: return GPUOS_E_BADOP;       // kill-switch stub: fail fast, write nothing
     default: return GPUOS_E_BADOP;
   }

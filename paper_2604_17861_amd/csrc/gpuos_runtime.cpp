@@ -51,13 +51,19 @@ int impl_arity(uint32_t impl) {
     case GPUOS_IMPL_FMA: return 3;
     case GPUOS_IMPL_RELU: case GPUOS_IMPL_EXP: case GPUOS_IMPL_GELU_ERF: case GPUOS_IMPL_GELU_TANH:
     case GPUOS_IMPL_SCALE: case GPUOS_IMPL_COPY: case GPUOS_IMPL_SUM_LAST: case GPUOS_IMPL_MAX_LAST:
-    case GPUOS_IMPL_MIN_LAST: return 1;
+    case GPUOS_IMPL_MIN_LAST: case GPUOS_IMPL_SOFTMAX_LAST: return 1;
+    case GPUOS_IMPL_MASKED_SOFTMAX_LAST: return 2;
+    case GPUOS_IMPL_LAYERNORM_LAST: return 3;
     default: return -1;
   }
 }
 bool impl_is_reduction(uint32_t impl) {
   return impl == GPUOS_IMPL_SUM_LAST || impl == GPUOS_IMPL_MAX_LAST || impl == GPUOS_IMPL_MIN_LAST;
 }
+bool impl_is_rowop(uint32_t impl) {
+  return impl == GPUOS_IMPL_SOFTMAX_LAST || impl == GPUOS_IMPL_MASKED_SOFTMAX_LAST || impl == GPUOS_IMPL_LAYERNORM_LAST;
+}
+int impl_kind(uint32_t impl) { return impl_is_reduction(impl) ? 1 : (impl_is_rowop(impl) ? 2 : 0); }
 bool impl_takes_int(uint32_t impl) {
   return impl == GPUOS_IMPL_ADD || impl == GPUOS_IMPL_SUB || impl == GPUOS_IMPL_MUL ||
          impl == GPUOS_IMPL_COPY || impl_is_reduction(impl);
@@ -186,6 +192,84 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
   for (int k = 0; k < ar; ++k) { rec.dtype[k] = (uint8_t)ops[k].dtype; rec.ptr[k] = ops[k].ptr; }
   rec.dtype[3] = (uint8_t)ops[ar].dtype;
   rec.ptr[3] = ops[ar].ptr;
+
+  if (impl_is_rowop(impl)) {
+    // ---- fused row operation: rows of the last dim, every operand has the full rank ----
+    if (numel == 0) { rec.path = PATH_NOP; rec.nchunks = 1; *r = rec; return GPUOS_OK; }
+    const int64_t n = size[t.ndim - 1];
+    const int64_t rows = numel / n;
+    int64_t osz[GPUOS_MAX_DIMS];
+    Operand oo[4];
+    int64_t s_last[4];
+    for (int k = 0; k <= ar; ++k) {
+      oo[k] = ops[k];
+      s_last[k] = n > 1 ? ops[k].stride[t.ndim - 1] : 1;
+      for (int d = t.ndim - 1; d < GPUOS_MAX_DIMS; ++d) oo[k].stride[d] = 0;
+    }
+    for (int d = 0; d < GPUOS_MAX_DIMS; ++d) osz[d] = d < t.ndim - 1 ? size[d] : 1;
+    int nd = 1;
+    if (t.ndim > 1) nd = coalesce(t.ndim - 1, osz, oo, ar + 1);
+    else { osz[0] = 1; for (int k = 0; k <= ar; ++k) oo[k].stride[0] = 0; }
+    if (rows == 1) { nd = 1; osz[0] = 1; for (int k = 0; k <= ar; ++k) oo[k].stride[0] = 0; }
+    rec.ndim = (uint8_t)nd;
+    for (int k = 0; k <= ar; ++k) {
+      const int kk = k < ar ? k : 3;
+      for (int d = 0; d < nd; ++d) rec.stride[kk][d] = (uint32_t)oo[k].stride[d];
+      rec.stride[kk][5] = (uint32_t)s_last[k];
+    }
+    for (int d = 0; d < nd; ++d) rec.size[d] = (uint32_t)osz[d];
+    rec.red_n = (uint32_t)n;
+    rec.numel = (uint32_t)rows;
+    rec.path = PATH_ROW_GENERIC;
+    // rows in registers: one dtype, unit stride along the row, whole aligned vectors, at most
+    // 256 vectors per row; x and the output contiguous; further inputs contiguous [period, n]
+    // blocks that repeat every `period` rows (period = rows: same layout as x; 1: a row vector)
+    const uint32_t es = dtype_size(ops[ar].dtype);
+    const uint32_t V = 16u / es;
+    auto dense_rows = [&](const Operand& o, int from) {      // dims from..nd-1 laid out as [.., n] contiguous
+      int64_t want = n;
+      for (int d = nd - 1; d >= from; --d) {
+        if (osz[d] > 1 && o.stride[d] != want) return false;
+        want *= osz[d];
+      }
+      return true;
+    };
+    bool fast = same_dt && n % V == 0 && n / V <= 256;
+    for (int k = 0; k <= ar && fast; ++k) fast = s_last[k] == 1 && aligned16(ops[k].ptr);
+    fast = fast && (rows == 1 || (dense_rows(oo[0], 0) && dense_rows(oo[ar], 0)));
+    uint32_t period[3] = {0, 0, 0};
+    for (int k = 1; k < ar && fast; ++k) {
+      if (rows == 1 || dense_rows(oo[k], 0)) { rec.okind[k] = K_FULL; continue; }
+      int q = nd;                                            // outer dims 0..q-1 broadcast, q..nd-1 dense
+      while (q > 0 && dense_rows(oo[k], q - 1) && oo[k].stride[q - 1] != 0) --q;
+      // here dims q..nd-1 are dense; dims 0..q-1 must all be broadcast
+      bool ok = true;
+      for (int d = 0; d < q; ++d) ok = ok && (osz[d] == 1 || oo[k].stride[d] == 0);
+      int64_t per = 1;
+      for (int d = q; d < nd; ++d) per *= osz[d];
+      if (!ok || per * n * (int64_t)es >= kMaxExtent) { fast = false; break; }
+      rec.okind[k] = K_PERIODIC;
+      period[k] = (uint32_t)per;
+    }
+    if (impl == GPUOS_IMPL_LAYERNORM_LAST && fast && rows > 1)    // gamma, beta: row vectors, loaded once per lane
+      fast = rec.okind[1] == K_PERIODIC && period[1] == 1 && rec.okind[2] == K_PERIODIC && period[2] == 1;
+    if (fast) {
+      rec.path = PATH_ROW_FUSED;
+      rec.rflags |= RF_VEC;
+      for (int k = 1; k < ar; ++k) rec.stride[k][0] = period[k];
+    }
+    uint64_t row_bytes = 0;
+    for (int k = 0; k <= ar; ++k) row_bytes += (uint64_t)n * dtype_size(ops[k].dtype);
+    uint64_t rpc = (uint64_t)chunk_elems * 12 / row_bytes;
+    if (rpc < 1) rpc = 1;
+    if (rpc >= 16) rpc = (rpc + 15) / 16 * 16;
+    const uint64_t min_rpc = ((uint64_t)rows + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
+    if (rpc < min_rpc) rpc = min_rpc;
+    rec.chunk = (uint32_t)rpc;
+    rec.nchunks = (uint32_t)(((uint64_t)rows + rpc - 1) / rpc);
+    *r = rec;
+    return GPUOS_OK;
+  }
 
   if (!red) {
     if (numel == 0) { rec.path = PATH_NOP; rec.nchunks = 1; *r = rec; return GPUOS_OK; }
@@ -673,7 +757,7 @@ int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_
   if (o.version == 0) return GPUOS_E_BADOP;
   if (!c->worker_running) return GPUOS_E_DEAD;
   if (impl_id != GPUOS_IMPL_FAIL && o.impl != GPUOS_IMPL_FAIL &&
-      (impl_arity(impl_id) != impl_arity(o.impl) || impl_is_reduction(impl_id) != impl_is_reduction(o.impl)))
+      (impl_arity(impl_id) != impl_arity(o.impl) || impl_kind(impl_id) != impl_kind(o.impl)))
     return GPUOS_E_INVAL;
   // The inactive slot still holds version-1's predecessor.  A task can only hold
   // that entry if it was submitted before the previous swap returned: wait for those.

@@ -409,6 +409,53 @@ def config3(n_chains=2000, seed=2, buffer_sets=2, heads=16, Bs=(1, 2, 4, 8), Ss=
                             layout={p: layout[p]["sets"] for p in pairs}))
 
 
+def config3_fused(n_chains=2000, seed=2, buffer_sets=2, heads=16, Bs=(1, 2, 4, 8), Ss=(64, 128, 256),
+                  batch=1) -> Stream:
+    """The third configuration's softmax with each six-task chain replaced by ONE fused task:
+    MASKED_SOFTMAX_LAST(scores, causal mask; alpha = 1/sqrt(64)) -> probabilities.  Same shapes,
+    same seeded order over the (B, S) pairs, same score values and the same reuse of
+    `buffer_sets` output buffers per pair (a task depends on the task that wrote its buffer
+    before)."""
+    rng = np.random.default_rng(seed)
+    pairs = [(b, s) for b in Bs for s in Ss]
+    order = rng.permutation(len(pairs))
+    pools: List[Pool] = []
+    layout = {}
+    for (b, s) in pairs:
+        n = b * heads * s * s
+        mask = np.zeros((s, s), dtype=np.float16)
+        mask[np.triu_indices(s, k=1)] = -np.inf
+        pools.append(Pool(f"mask_{b}_{s}", s * s * 2, mask.view(np.uint8).reshape(-1).copy()))
+        mask_pool = len(pools) - 1
+        sets = []
+        for _ in range(buffer_sets):
+            pools.append(Pool(f"s_{b}_{s}", n * 2, random_values(rng, n, "normal2", F16)))
+            pools.append(Pool(f"p_{b}_{s}", n * 2))
+            sets.append(dict(s=len(pools) - 2, p=len(pools) - 1))
+        layout[(b, s)] = dict(mask=mask_pool, sets=sets, used=0, last_ticket=[None] * buffer_sets)
+    tasks, pool_of = new_tasks(n_chains)
+    chain_pair = np.zeros(n_chains, dtype=np.int32)
+    chain_set = np.zeros(n_chains, dtype=np.int32)
+    for c in range(n_chains):
+        pi = int(order[c % len(pairs)])
+        b, s = pairs[pi]
+        L = layout[(b, s)]
+        k = L["used"] % buffer_sets
+        L["used"] += 1
+        chain_pair[c], chain_set[c] = pi, k
+        shape4 = [b, heads, s, s]
+        st4 = contiguous_strides(shape4)
+        dep = 0 if L["last_ticket"][k] is None else c - L["last_ticket"][k]
+        set_head(tasks, c, OP["MASKED_SOFTMAX_LAST"], shape4, 2, alpha=0.125, dep=(dep, 0, 0))
+        set_tensor(tasks, pool_of, c, 0, L["sets"][k]["s"], 0, st4, F16)
+        set_tensor(tasks, pool_of, c, 1, L["mask"], 0, [0, 0, s, 1], F16, 0b0011)
+        set_tensor(tasks, pool_of, c, 3, L["sets"][k]["p"], 0, st4, F16)
+        L["last_ticket"][k] = c
+    return Stream("config3_fused", tasks, pool_of, pools, batch=batch,
+                  info=dict(seed=seed, pairs=pairs, chain_pair=chain_pair, chain_set=chain_set, heads=heads,
+                            buffer_sets=buffer_sets, layout={p: layout[p]["sets"] for p in pairs}))
+
+
 # ---- configuration 4 ---------------------------------------------------------
 
 def config4(n_tasks=1000000, seed=3, swap_every=10000, window=10000, numel_lo=1024,

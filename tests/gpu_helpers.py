@@ -17,6 +17,8 @@ EXACT = {S.IMPL[n] for n in ("ADD", "SUB", "MUL", "DIV", "RELU", "SCALE", "FMA",
 TRANSCENDENTAL = {S.IMPL[n] for n in ("EXP", "SUB_EXP", "GELU_ERF", "GELU_TANH")}
 ULP_TOL = 2            # elementwise float results: within 2 ulp of the output dtype
 RED_REL = 1e-5         # fp32 reductions: |g - o| <= 1e-5 * max(|o|, L1 / sqrt(n))
+ROW_REL = 2.0 ** -22   # fused row operations: |g - y| <= 2^-22 * scale (scale: oracle.rowop_f64)
+ROW_ABS = 1.5 * 2.0 ** -126   # ... plus results below fp32's normal range, which the device may flush
 
 
 class DevicePools:
@@ -127,6 +129,23 @@ def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, 
             stats["max_red_ratio"] = max(stats["max_red_ratio"], ratio)
             assert ratio <= 1.0, "task %d SUM_LAST: error %.3g x tolerance" % (i, ratio)
             assert np.array_equal(np.isnan(gv[~fin]), np.isnan(s64[~fin]))
+            continue
+        if impl in S.ROWOPS:
+            # fp32 evaluation of the exact row function: error <= ROW_REL * (the magnitude the
+            # rounding errors scale with, from the oracle) + half a step of a 16-bit output
+            # format + the flush of results below fp32's normal range
+            y64, scale = oracle.rowop_f64(tasks, i, impl)
+            gv = _as_f64(gb, dt).reshape(y64.shape)
+            tol = ROW_REL * scale + ROW_ABS
+            if dt != S.F32:
+                tol = tol + _ulp_size(y64, dt)
+            fin = np.isfinite(y64)
+            err = np.abs(gv - y64)
+            ratio = float((err[fin] / tol[fin]).max()) if fin.any() else 0.0
+            stats["max_red_ratio"] = max(stats["max_red_ratio"], ratio)
+            assert np.array_equal(np.isnan(gv), np.isnan(y64)), "task %d (%s): NaN pattern differs" % (i, S.IMPL_NAME[impl])
+            assert ratio <= 1.0, "task %d (%s, dtype %d): error %.3g x tolerance at flat index %d" % (
+                i, S.IMPL_NAME[impl], dt, ratio, int(np.argmax(np.where(fin, err / tol, 0))))
             continue
         d = ulp_distance(gb, ob, dt)
         mx = int(d.max()) if d.size else 0

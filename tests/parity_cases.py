@@ -202,6 +202,79 @@ def transposed_2d():
     return b.stream("transposed_2d")
 
 
+def row_operations():
+    """Softmax, scaled + masked softmax and layer norm over the last dim: rows in registers (row
+    lengths from one vector to 256 vectors, sub-wave and whole-wave ownership, several chunks and
+    ragged last chunks) and the generic path (odd lengths, strided rows, mixed dtypes, long rows);
+    masks laid out like x, repeated every S rows, or one row; special values."""
+    rng = np.random.default_rng(12)
+    b = Builder()
+    for code in (S.F32, S.F16, S.BF16):
+        V = 4 if code == S.F32 else 8
+        dt = np_dtype(code)
+        for rows, n in ((1, V), (7, 8 * V), (300, 24 * V), (1000, 64 * V), (130, 65 * V), (90, 128 * V),
+                        (50, 200 * V), (40, 256 * V), (12, 257 * V), (33, 5), (65, 1001), (3, 20000)):
+            x = b.pool(to_dtype((rng.standard_normal((rows, n)) * 3).astype(np.float32), code))
+            o1, o2, o3 = (b.pool(np.zeros((rows, n), dt)) for _ in range(3))
+            b.add("SOFTMAX_LAST", o1, [x])
+            mrow = b.pool(to_dtype(rng.standard_normal(n).astype(np.float32), code))
+            b.add("MASKED_SOFTMAX_LAST", o2, [x, np.broadcast_to(mrow, (rows, n))], alpha=0.3)
+            g = b.pool(to_dtype((1 + 0.2 * rng.standard_normal(n)).astype(np.float32), code))
+            be = b.pool(to_dtype(rng.standard_normal(n).astype(np.float32), code))
+            b.add("LAYERNORM_LAST", o3, [x, np.broadcast_to(g, (rows, n)), np.broadcast_to(be, (rows, n))], alpha=1e-5)
+        # attention-shaped: [B, H, S, S] scores, causal mask [S, S] repeated every S rows, and a full-size bias
+        for (B_, H_, S_) in ((2, 3, 64), (1, 5, 128), (3, 2, 24)):
+            x = b.pool(to_dtype((rng.standard_normal((B_, H_, S_, S_)) * 2).astype(np.float32), code))
+            causal = np.where(np.tril(np.ones((S_, S_), bool)), 0.0, -np.inf).astype(np.float32)
+            m = b.pool(to_dtype(causal, code))
+            o = b.pool(np.zeros((B_, H_, S_, S_), dt))
+            b.add("MASKED_SOFTMAX_LAST", o, [x, np.broadcast_to(m, (B_, H_, S_, S_))], alpha=0.125)
+            bias = b.pool(to_dtype(rng.standard_normal((B_, H_, S_, S_)).astype(np.float32), code))
+            o = b.pool(np.zeros((B_, H_, S_, S_), dt))
+            b.add("MASKED_SOFTMAX_LAST", o, [x, bias], alpha=1.0)
+            mh = b.pool(to_dtype(rng.standard_normal((H_, 1, S_)).astype(np.float32), code))     # per head, one row
+            o = b.pool(np.zeros((B_, H_, S_, S_), dt))
+            b.add("MASKED_SOFTMAX_LAST", o, [x, np.broadcast_to(mh[None], (B_, H_, S_, S_))], alpha=0.5)
+    # generic path: strided rows, transposed views, mixed dtypes, fp32 output of 16-bit input
+    x16 = b.pool(to_dtype((rng.standard_normal((64, 96)) * 2).astype(np.float32), S.F16))
+    x32 = b.pool((rng.standard_normal((96, 64)) * 2).astype(np.float32))
+    g32 = b.pool((1 + 0.1 * rng.standard_normal(96)).astype(np.float32))
+    be16 = b.pool(to_dtype(rng.standard_normal(96).astype(np.float32), S.BF16))
+    o = b.pool(np.zeros((64, 96), np.float32))
+    b.add("SOFTMAX_LAST", o, [x16])
+    o = b.pool(np.zeros((64, 96), np.float16))
+    b.add("SOFTMAX_LAST", o, [x32.T])
+    o = b.pool(np.zeros((64, 48), np.float32))
+    b.add("MASKED_SOFTMAX_LAST", o, [x16[:, ::2], x32.T[:, 1::2]], alpha=-0.7)
+    o = b.pool(np.zeros((64, 96), np.uint16))
+    b.add("LAYERNORM_LAST", o, [x16, np.broadcast_to(g32, (64, 96)), np.broadcast_to(be16, (64, 96))], alpha=1e-3)
+    o = b.pool(np.zeros((64, 96), np.float32))
+    b.add("LAYERNORM_LAST", o, [x32.T, x32.T, x32.T], alpha=0.25)              # per-element gamma and beta
+    x4 = b.pool(rng.standard_normal((2, 3, 4, 5, 6, 32)).astype(np.float32))     # six dims, outer dims permuted
+    o = b.pool(np.zeros((4, 2, 3, 5, 6, 32), np.float32))
+    b.add("SOFTMAX_LAST", o, [x4.transpose(2, 0, 1, 3, 4, 5)])
+    # special values
+    inf, nan = np.inf, np.nan
+    sp = np.zeros((8, 16), np.float32)
+    sp[0, 3] = nan
+    sp[1, :] = -inf
+    sp[2, 5] = inf
+    sp[3, ::2] = -inf
+    sp[4, :] = 88.0
+    sp[5, :] = np.linspace(-120, 0, 16)                 # results far below fp32's normal range
+    sp[6, :] = 1e30
+    xs = b.pool(sp)
+    o = b.pool(np.zeros((8, 16), np.float32))
+    b.add("SOFTMAX_LAST", o, [xs])
+    o = b.pool(np.zeros((8, 15), np.float32))
+    b.add("SOFTMAX_LAST", o, [xs[:, :15]])               # the same through the generic path
+    const = b.pool(np.full((4, 64), 3.0, np.float32))   # zero variance: eps alone under the root
+    one, zero = b.pool(np.ones(64, np.float32)), b.pool(np.zeros(64, np.float32))
+    o = b.pool(np.zeros((4, 64), np.float32))
+    b.add("LAYERNORM_LAST", o, [const, np.broadcast_to(one, (4, 64)), np.broadcast_to(zero, (4, 64))], alpha=1e-5)
+    return b.stream("row_operations")
+
+
 def reductions():
     """SUM / MAX / MIN over the last dim: row lengths from 1 to 20000 (sub-wave rows, one workgroup
     per row, scalar fallback for odd lengths), all float dtypes, fp32 and same-dtype outputs,
@@ -256,6 +329,10 @@ def config3_reduced():
     return S.config3(n_chains=12, buffer_sets=1)
 
 
+def config3_fused_reduced():
+    return S.config3_fused(n_chains=12, buffer_sets=1)
+
+
 def config4_reduced():
     return S.config4(n_tasks=30000, swap_every=2000, window=15000, in_pool_elems=1 << 20)
 
@@ -278,9 +355,11 @@ CPU_CHECKED = {
     "broadcast_2d": broadcast_2d,
     "transposed_2d": transposed_2d,
     "reductions": reductions,
+    "row_operations": row_operations,
     "int32": int32_ops,
     "config2_reduced": config2_reduced,
     "config3_reduced": config3_reduced,
+    "config3_fused_reduced": config3_fused_reduced,
     "config4_reduced": config4_reduced,
     "config5_reduced": config5_reduced,
 }

@@ -71,6 +71,12 @@ def test_transposed_views_lds_tiled_gather():
     print(stats, flush=True)
 
 
+def test_fused_row_operations():
+    stats, _ = _run_and_check(C.row_operations())
+    print(stats, flush=True)
+    assert stats["max_red_ratio"] <= 1.0
+
+
 def test_last_dim_reductions():
     stats, _ = _run_and_check(C.reductions())
     print(stats, flush=True)
@@ -90,6 +96,38 @@ def test_config2_reduced():
 def test_config3_reduced_all_pairs():
     stats, _ = _run_and_check(C.config3_reduced())
     print(stats, flush=True)
+
+
+def test_config3_fused_softmax_all_pairs():
+    """One fused task per (B, S) pair of the third configuration, against the oracle; and against
+    the six-task chain run on the same scores: the two agree to a few fp16 steps."""
+    from gpu_helpers import DevicePools, run_stream
+    stats, _ = _run_and_check(C.config3_fused_reduced())
+    print(stats, flush=True)
+    assert stats["max_red_ratio"] <= 1.0
+    sf, sc = C.config3_fused_reduced(), C.config3_reduced()
+    outs = []
+    for s in (sf, sc):
+        dp = DevicePools(s)
+        with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
+            rt.register_table(s.table)
+            run_stream(s, rt, dp)
+        imgs = dp.download()
+        res = {}
+        for c in range(12):
+            b, n = s.info["pairs"][int(s.info["chain_pair"][c])]
+            lay = s.info["layout"][(b, n)][0]
+            cnt = b * 16 * n * n
+            if s is sf:
+                res[(b, n)] = imgs[lay["p"]][: cnt * 2].view(np.float16).astype(np.float64)
+            else:
+                res[(b, n)] = imgs[lay["w"]][lay["p"]: lay["p"] + cnt * 2].view(np.float16).astype(np.float64)
+        outs.append(res)
+    for key in outs[0]:
+        f, c = outs[0][key], outs[1][key]
+        assert np.array_equal(f == 0, c == 0)
+        big = c > 2.0 ** -10
+        assert (np.abs(f - c)[big] / c[big]).max() <= 8 * 2.0 ** -11, key
 
 
 def test_config4_reduced_hot_swap():

@@ -44,15 +44,12 @@ def _status(tasks, i, impl):
     return R.lib().gpuos_task_bytes(tasks.ctypes.data + i * tasks.dtype.itemsize, int(impl), ctypes.byref(b)), b.value
 
 
-def test_validation_agrees_with_the_oracle_on_damaged_descriptors():
-    """Differential test of two independently written validators."""
-    rng = np.random.default_rng(77)
-    s = C.config2_reduced()
+def _damage_and_compare(s, rng, trials):
     hp = HostPools(s)
     T = hp.tasks
     impl = s.impl_for()
     n_bad = 0
-    for trial in range(3000):
+    for trial in range(trials):
         i = int(rng.integers(len(T)))
         t = T[i:i + 1].copy()
         kind = int(rng.integers(12))
@@ -72,6 +69,15 @@ def test_validation_agrees_with_the_oracle_on_damaged_descriptors():
         want = oracle.validate(t, 0, use_impl)
         assert got == want, (trial, kind, i, use_impl, got, want)
         n_bad += want != 0
+    return n_bad
+
+
+def test_validation_agrees_with_the_oracle_on_damaged_descriptors():
+    """Differential test of two independently written validators."""
+    rng = np.random.default_rng(77)
+    n_bad = 0
+    for s in (C.config2_reduced(), C.row_operations(), C.reductions()):
+        n_bad += _damage_and_compare(s, rng, 2000)
     assert n_bad > 300
 
 
@@ -129,3 +135,39 @@ def test_task_plan_picks_the_execution_path_the_layout_calls_for():
     path, chunks, per, nd = R.task_plan(HostPools(sb).tasks, 0, S.IMPL["RELU"])
     tiles = ((2100 + 31) // 32) * ((3000 + 31) // 32)
     assert path == "TILE2D" and chunks <= 1024 and (chunks - 1) * per < tiles <= chunks * per
+
+
+def test_task_plan_for_row_operations():
+    """Rows of whole aligned vectors (at most 256 of them), one dtype, contiguous -> rows in
+    registers, with further inputs laid out like x, repeated every `period` rows, or one row;
+    everything else takes the three-pass path."""
+    from helpers import Builder
+    b = Builder()
+    f = lambda *shape: b.pool(np.zeros(shape, np.float32))
+    h = lambda *shape: b.pool(np.zeros(shape, np.float16))
+    x = f(2, 3, 64, 64)
+    b.add("SOFTMAX_LAST", f(2, 3, 64, 64), [x])                                              # 0 fused
+    b.add("MASKED_SOFTMAX_LAST", f(2, 3, 64, 64), [x, np.broadcast_to(f(64, 64), (2, 3, 64, 64))])   # 1 fused, period 64
+    b.add("MASKED_SOFTMAX_LAST", f(2, 3, 64, 64), [x, f(2, 3, 64, 64)])                      # 2 fused, full
+    b.add("MASKED_SOFTMAX_LAST", f(2, 3, 64, 64), [x, np.broadcast_to(f(64), (2, 3, 64, 64))])       # 3 fused, one row
+    b.add("MASKED_SOFTMAX_LAST", f(2, 3, 64, 64), [x, np.broadcast_to(f(2, 1, 64, 64), (2, 3, 64, 64))])  # 4 mask skips a middle dim
+    b.add("LAYERNORM_LAST", f(50, 1024), [f(50, 1024), np.broadcast_to(f(1024), (50, 1024)), np.broadcast_to(f(1024), (50, 1024))])  # 5
+    b.add("LAYERNORM_LAST", f(50, 1024), [f(50, 1024), f(50, 1024), np.broadcast_to(f(1024), (50, 1024))])   # 6 per-element gamma
+    b.add("SOFTMAX_LAST", f(10, 1028), [f(10, 1028)])                                        # 7 257 vectors
+    b.add("SOFTMAX_LAST", f(10, 30), [f(10, 30)])                                            # 8 not whole vectors
+    b.add("SOFTMAX_LAST", f(10, 32), [h(10, 32)])                                            # 9 mixed dtypes
+    b.add("SOFTMAX_LAST", f(10, 32), [f(10, 64)[:, ::2]])                                    # 10 strided
+    b.add("SOFTMAX_LAST", f(10, 32), [f(10, 36)[:, :32]])                                    # 11 row pitch
+    b.add("SOFTMAX_LAST", f(32), [f(32)])                                                    # 12 one row, rank 1
+    b.add("SOFTMAX_LAST", h(4, 2048), [h(4, 2048)])                                          # 13 fp16: 256 vectors
+    s = b.stream()
+    hp = HostPools(s)
+    impl = s.impl_for()
+    got = [R.task_plan(hp.tasks, i, impl[i]) for i in range(len(s))]
+    want = ["ROW_FUSED"] * 4 + ["ROW_GENERIC", "ROW_FUSED", "ROW_GENERIC", "ROW_GENERIC", "ROW_GENERIC", "ROW_GENERIC",
+                                "ROW_GENERIC", "ROW_GENERIC", "ROW_FUSED", "ROW_FUSED"]
+    assert [g[0] for g in got] == want, [g[0] for g in got]
+    rows = 2 * 3 * 64
+    assert (got[0][1] - 1) * got[0][2] < rows <= got[0][1] * got[0][2]
+    # bytes: x and y once, the mask at its true size
+    assert R.task_bytes(hp.tasks[1:2], impl[1:2])[0] == 2 * rows * 64 * 4 + 64 * 64 * 4
