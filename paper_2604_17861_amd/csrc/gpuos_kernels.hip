@@ -940,8 +940,8 @@ DEV void rowop_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
 template <int POL, int ROP, int DT>
 DEV void rowop_fused_dt(const Record* r, uint32_t begin, uint32_t end) {
   const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
-  if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 2>(r, begin, end);
-  else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 1>(r, begin, end);
+  if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 4>(r, begin, end);
+  else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 2>(r, begin, end);
   else rowop_fused<POL, ROP, DT, 4, 1>(r, begin, end);
 }
 
