@@ -31,6 +31,9 @@ namespace gpuos {
 #define SC_SYSTEM __HIP_MEMORY_SCOPE_SYSTEM
 
 #define DEV __device__ __forceinline__
+// The per-path executors are real functions (not inlined into the worker loop): each gets a
+// register allocation of its own, so the streaming loops do not inherit the worker loop's live values.
+#define PATHFN __device__ __attribute__((noinline))
 
 // ---------------------------------------------------------------------------
 // memory access policy
@@ -201,13 +204,25 @@ DEV const char* uni_ptr(uint64_t p) {
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
   return (const char*)(((uint64_t)hi << 32) | lo);
 }
+// Arguments of a PATHFN function arrive in vector registers and pointers arrive generic.  Both
+// facts are restored on entry: values the whole workgroup shares go back to scalar registers
+// (uni / uni_ptr), and a pointer known to address LDS goes back to the LDS address space (so that
+// it is read with LDS instructions, not flat ones).
+template <class T> DEV T* lds_arg(T* p) {
+  typedef __attribute__((address_space(3))) T* lds_t;
+  const uint32_t a = uni((uint32_t)(uintptr_t)(lds_t)p);
+  return (T*)(lds_t)(uintptr_t)a;
+}
 
 // ---------------------------------------------------------------------------
 // PATH_CONTIG: out[i] = f(a[i], b[i], c[i]), all operands the same dtype.
 // 16 bytes per lane per access, four accesses in flight per operand.
 // ---------------------------------------------------------------------------
 template <int POL, int IMPL, int DT>
-DEV void ew_contig(const Record* r, uint32_t begin, uint32_t end) {
+PATHFN void ew_contig(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
+  const Record* r = lds_arg(r_v);
+  uint32_t begin = uni(begin_v);
+  const uint32_t end = uni(end_v);
   using E = Elem<DT>;
   using M = Mem<POL>;
   constexpr int V = E::V, N = Op<IMPL>::N, U = 4;
@@ -269,7 +284,9 @@ DEV void ew_contig(const Record* r, uint32_t begin, uint32_t end) {
 }
 
 template <int POL, int IMPL>
-DEV void ew_contig_int(const Record* r, uint32_t begin, uint32_t end) {
+PATHFN void ew_contig_int(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t begin = uni(begin_v), end = uni(end_v);
   const char* a = uni_ptr(r->ptr[0]);
   const char* b = r->n_inputs > 1 ? uni_ptr(r->ptr[1]) : a;
   char* o = (char*)uni_ptr(r->ptr[3]);
@@ -285,7 +302,10 @@ DEV void ew_contig_int(const Record* r, uint32_t begin, uint32_t end) {
 constexpr uint32_t kScratchFloats = 3200;   // LDS scratch per workgroup (broadcast staging, transpose tiles, reduction partials)
 
 template <int POL, int IMPL, int DT>
-DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end, float* s_scratch) {
+PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t begin = uni(begin_v), end = uni(end_v);
+  float* s_scratch = lds_arg(s_v);
   using E = Elem<DT>;
   using M = Mem<POL>;
   constexpr int V = E::V, N = Op<IMPL>::N;
@@ -362,7 +382,10 @@ DEV void ew_row2d(const Record* r, uint32_t begin, uint32_t end, float* s_scratc
 constexpr uint32_t kTile = 32, kTilePitch = 33;
 
 template <int POL, int IMPL>
-DEV void ew_tile2d(const Record* r, uint32_t tile_begin, uint32_t tile_end, float* s_scratch) {
+PATHFN void ew_tile2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t tile_begin = uni(begin_v), tile_end = uni(end_v);
+  float* s_scratch = lds_arg(s_v);
   constexpr int N = Op<IMPL>::N;
   const uint32_t R = uni(r->size[1]), C = uni(r->size[2]);
   const uint32_t tr = (R + kTile - 1) / kTile, tc = (C + kTile - 1) / kTile;
@@ -419,7 +442,9 @@ DEV void ew_tile2d(const Record* r, uint32_t tile_begin, uint32_t tile_end, floa
 // operand strides (0 on broadcast dims), per operand dtype.
 // ---------------------------------------------------------------------------
 template <int POL, int IMPL, bool INT>
-DEV void ew_generic(const Record* r, uint32_t begin, uint32_t end) {
+PATHFN void ew_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t begin = uni(begin_v), end = uni(end_v);
   using M = Mem<POL>;
   constexpr int N = INT ? 2 : Op<IMPL>::N;
   const int nd = (int)uni(r->ndim);
@@ -511,29 +536,64 @@ template <int RIMPL> DEV int32_t wave_reduce_i(int32_t acc, uint32_t width) {
 //   medium rows: one wavefront per row, RA rows at a time, UN loads per row in flight;
 //   long rows   (>= 1024 vectors): the four wavefronts take a quarter of each row, partial
 //               results meet in LDS once per chunk (one barrier per chunk, not per row).
+// Per-element accumulation.  SUM adds.  MAX / MIN must propagate NaN: the running value ignores
+// NaN (one compare + select) and `nan` remembers whether one was seen (one unordered compare,
+// or-ed into a wavefront-uniform mask register); red_finish folds the two before the lanes are combined.
+template <int RIMPL> DEV float red_step(float acc, float x, bool& nan) {
+  if (RIMPL == GPUOS_IMPL_SUM_LAST) return acc + x;
+  nan = nan || (x != x);
+  if (RIMPL == GPUOS_IMPL_MAX_LAST) return x > acc ? x : acc;
+  return x < acc ? x : acc;
+}
+template <int RIMPL> DEV float red_finish(float acc, bool nan) {
+  if (RIMPL == GPUOS_IMPL_SUM_LAST) return acc;
+  return nan ? __builtin_nanf("") : acc;
+}
+
 template <int RIMPL, int DT>
-DEV float red_vector(const v4i& q, uint32_t f0, uint32_t lo, uint32_t hi, bool edge, float acc) {
+DEV float red_vector(const v4i& q, uint32_t f0, uint32_t lo, uint32_t hi, bool edge, float acc, bool& nan) {
   // q holds elements f0 .. f0+V-1 of the flat run; the row is [lo, hi)
   using E = Elem<DT>;
   if (!edge) {
 #pragma unroll
-    for (int k = 0; k < E::V; ++k) acc = red_combine<RIMPL>(acc, E::get(q, k));
+    for (int k = 0; k < E::V; ++k) acc = red_step<RIMPL>(acc, E::get(q, k), nan);
   } else {
 #pragma unroll
     for (int k = 0; k < E::V; ++k)
-      if (f0 + k >= lo && f0 + k < hi) acc = red_combine<RIMPL>(acc, E::get(q, k));
+      if (f0 + k >= lo && f0 + k < hi) acc = red_step<RIMPL>(acc, E::get(q, k), nan);
   }
   return acc;
 }
 
-struct RedRun {        // the chunk's rows as a flat run of vectors
-  rsrc_t rin;
+constexpr uint32_t kNoLoad = 0x7ffffff0u;   // a buffer offset past every resource: the load returns 0 and moves no data
+
+struct RedArgs {       // what a row-reduction variant is called with (plain values: see lds_arg)
+  const char* base;    // first byte of the run: the tensor base advanced to the chunk's first vector
+  uint32_t bytes;      // length of the run, whole vectors
   uint32_t base_elem;  // first element of the run (multiple of V), relative to the tensor
   uint32_t n;
+  char* po;
+  uint32_t odt, row_begin, row_end, max_span;
+  float* s_part;       // LDS
 };
+struct RedRun {        // the chunk's rows as a flat run of vectors
+  rsrc_t rin;
+  uint32_t base_elem;
+  uint32_t n;
+};
+DEV RedRun red_run(const RedArgs& a) {
+  RedRun run;
+  run.rin = make_rsrc(uni_ptr((uint64_t)a.base), uni(a.bytes));
+  run.base_elem = uni(a.base_elem);
+  run.n = uni(a.n);
+  return run;
+}
 
 template <int POL, int RIMPL, int DT, int RA, int UN>
-DEV void red_rows_wave(const RedRun& run, char* po, uint32_t odt, uint32_t row_begin, uint32_t row_end) {
+PATHFN void red_rows_wave(RedArgs a) {
+  const RedRun run = red_run(a);
+  char* po = (char*)uni_ptr((uint64_t)a.po);
+  const uint32_t odt = uni(a.odt), row_begin = uni(a.row_begin), row_end = uni(a.row_end);
   using E = Elem<DT>;
   using M = Mem<POL>;
   constexpr uint32_t V = E::V;
@@ -542,11 +602,13 @@ DEV void red_rows_wave(const RedRun& run, char* po, uint32_t odt, uint32_t row_b
   // wave w takes rows row_begin + w, + 4, + 8, ... ; RA of them at a time
   for (uint32_t row0 = row_begin + wave; row0 < row_end; row0 += 4 * RA) {
     float acc[RA];
+    bool nan[RA];
     uint32_t lo[RA], hi[RA], j0[RA], j1[RA];
     uint32_t span = 0;
 #pragma unroll
     for (int i = 0; i < RA; ++i) {
       acc[i] = red_identity<RIMPL>();
+      nan[i] = false;
       const uint32_t row = row0 + 4 * i;
       lo[i] = row * n - run.base_elem;
       hi[i] = lo[i] + n;
@@ -561,20 +623,22 @@ DEV void red_rows_wave(const RedRun& run, char* po, uint32_t odt, uint32_t row_b
 #pragma unroll
       for (int i = 0; i < RA; ++i)
 #pragma unroll
-        for (int u = 0; u < UN; ++u)   // loads past the run are clamped by the buffer bounds and masked below
-          q[i][u] = M::ld16(run.rin, (j0[i] + v + u * 64) * 16u);
+        for (int u = 0; u < UN; ++u) {   // vectors past the row are not fetched
+          const uint32_t j = j0[i] + v + u * 64;
+          q[i][u] = M::ld16(run.rin, (j <= j1[i] && hi[i] > lo[i]) ? j * 16u : kNoLoad);
+        }
 #pragma unroll
       for (int i = 0; i < RA; ++i)
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
           const uint32_t j = j0[i] + v + u * 64;
           if (j <= j1[i] && hi[i] > lo[i])
-            acc[i] = red_vector<RIMPL, DT>(q[i][u], j * V, lo[i], hi[i], j == j0[i] || j == j1[i], acc[i]);
+            acc[i] = red_vector<RIMPL, DT>(q[i][u], j * V, lo[i], hi[i], j == j0[i] || j == j1[i], acc[i], nan[i]);
         }
     }
 #pragma unroll
     for (int i = 0; i < RA; ++i) {
-      const float t = wave_reduce<RIMPL>(acc[i], 64);
+      const float t = wave_reduce<RIMPL>(red_finish<RIMPL>(acc[i], nan[i]), 64);
       if (lane == 0 && row0 + 4 * i < row_end) store_rt<POL>(po, row0 + 4 * i, odt, t);
     }
   }
@@ -583,8 +647,11 @@ DEV void red_rows_wave(const RedRun& run, char* po, uint32_t odt, uint32_t row_b
 constexpr uint32_t kRedPartialRows = 64;   // rows of partial results the LDS scratch holds
 
 template <int POL, int RIMPL, int DT>
-DEV void red_rows_quarter(const RedRun& run, char* po, uint32_t odt, uint32_t row_begin, uint32_t row_end,
-                          float* s_part) {
+PATHFN void red_rows_quarter(RedArgs a) {
+  const RedRun run = red_run(a);
+  char* po = (char*)uni_ptr((uint64_t)a.po);
+  const uint32_t odt = uni(a.odt), row_begin = uni(a.row_begin), row_end = uni(a.row_end);
+  float* s_part = lds_arg(a.s_part);
   using E = Elem<DT>;
   using M = Mem<POL>;
   constexpr uint32_t V = E::V;
@@ -598,20 +665,21 @@ DEV void red_rows_quarter(const RedRun& run, char* po, uint32_t odt, uint32_t ro
     const uint32_t q_begin = j0 + wave * sq;
     const uint32_t q_end = (q_begin + sq <= j1 + 1) ? q_begin + sq : j1 + 1;
     float a0 = red_identity<RIMPL>(), a1 = a0;
+    bool nan = false;
     for (uint32_t v = q_begin + lane; v < q_end; v += 64 * UN) {
       v4i q[UN];
 #pragma unroll
-      for (int u = 0; u < UN; ++u) q[u] = M::ld16(run.rin, (v + u * 64) * 16u);
+      for (int u = 0; u < UN; ++u) q[u] = M::ld16(run.rin, (v + u * 64 < q_end) ? (v + u * 64) * 16u : kNoLoad);
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
         const uint32_t j = v + u * 64;
         if (j < q_end) {
-          if ((u & 1) == 0) a0 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a0);
-          else a1 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a1);
+          if ((u & 1) == 0) a0 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a0, nan);
+          else a1 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a1, nan);
         }
       }
     }
-    const float t = wave_reduce<RIMPL>(red_combine<RIMPL>(a0, a1), 64);
+    const float t = wave_reduce<RIMPL>(red_finish<RIMPL>(red_combine<RIMPL>(a0, a1), nan), 64);
     if (lane == 0) s_part[(row - row_begin) * 4 + wave] = t;
   }
   __syncthreads();
@@ -625,8 +693,10 @@ DEV void red_rows_quarter(const RedRun& run, char* po, uint32_t odt, uint32_t ro
 }
 
 template <int POL, int RIMPL, int DT>
-DEV void red_rows_short(const RedRun& run, char* po, uint32_t odt, uint32_t row_begin, uint32_t row_end,
-                        uint32_t max_span) {
+PATHFN void red_rows_short(RedArgs a) {
+  const RedRun run = red_run(a);
+  char* po = (char*)uni_ptr((uint64_t)a.po);
+  const uint32_t odt = uni(a.odt), row_begin = uni(a.row_begin), row_end = uni(a.row_end), max_span = uni(a.max_span);
   using E = Elem<DT>;
   using M = Mem<POL>;
   constexpr uint32_t V = E::V;
@@ -636,6 +706,8 @@ DEV void red_rows_short(const RedRun& run, char* po, uint32_t odt, uint32_t row_
   uint32_t P = 1;                                     // lanes per row: power of two >= the widest span
   while (P < max_span) P <<= 1;
   const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
+  const bool gather = UP * rpw <= 64u;                // the pass's rows fit one lane each
+  // one wavefront pass covers the UP * rpw consecutive rows base .. base + UP * rpw - 1
   for (uint32_t base = row_begin + wave * rpw * UP; base < row_end; base += 4 * rpw * UP) {
     v4i q[UP];
     uint32_t lo[UP], hi[UP], j0[UP], j1[UP];
@@ -646,18 +718,28 @@ DEV void red_rows_short(const RedRun& run, char* po, uint32_t odt, uint32_t row_
       hi[u] = lo[u] + n;
       j0[u] = lo[u] / V;
       j1[u] = (hi[u] - 1) / V;
-      q[u] = M::ld16(run.rin, (j0[u] + j) * 16u);
+      q[u] = M::ld16(run.rin, (row < row_end && j0[u] + j <= j1[u]) ? (j0[u] + j) * 16u : kNoLoad);
     }
+    float mine = 0.0f;                                // lane L ends up with the result of row base + L
 #pragma unroll
     for (int u = 0; u < UP; ++u) {
       const uint32_t row = base + u * rpw + sub;
       const uint32_t jj = j0[u] + j;
       float acc = red_identity<RIMPL>();
+      bool nan = false;
       if (row < row_end && jj <= j1[u])
-        acc = red_vector<RIMPL, DT>(q[u], jj * V, lo[u], hi[u], jj == j0[u] || jj == j1[u], acc);
-      acc = wave_reduce<RIMPL>(acc, P);
-      if (row < row_end && j == 0) store_rt<POL>(po, row, odt, acc);
+        acc = red_vector<RIMPL, DT>(q[u], jj * V, lo[u], hi[u], jj == j0[u] || jj == j1[u], acc, nan);
+      acc = wave_reduce<RIMPL>(red_finish<RIMPL>(acc, nan), P);
+      // every lane of sub-group s now holds the result of row base + u * rpw + s
+      if (gather) {
+        const float got = __shfl(acc, (int)((lane & (rpw - 1u)) * P), 64);
+        if (lane / rpw == (uint32_t)u) mine = got;
+      } else if (row < row_end && j == 0) {
+        store_rt<POL>(po, row, odt, acc);            // rows of one or two vectors: the owners are adjacent lanes already
+      }
     }
+    // UP * rpw consecutive rows, one lane each: a coalesced store instead of one 4-byte store per row
+    if (gather && lane < UP * rpw && base + lane < row_end) store_rt<POL>(po, base + lane, odt, mine);
   }
 }
 
@@ -671,19 +753,20 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
   const uint32_t odt = uni(r->dtype[3]);
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
   if (r->rflags & RF_VEC) {                           // tensor base is 16-byte aligned
-    RedRun run;
-    run.n = n;
-    run.base_elem = (row_begin * n) / V * V;          // chunk start, aligned down to a vector
+    RedArgs a;
+    a.n = n;
+    a.base_elem = (row_begin * n) / V * V;            // chunk start, aligned down to a vector
     // end rounded up to a whole vector (the base is 16-byte aligned, so the padding stays inside
     // the 16-byte block that holds the last element); vector loads further out read zeros; both
     // are masked per element
-    run.rin = make_rsrc(pin + (uint64_t)run.base_elem * E::ES, ((row_end * n - run.base_elem) * E::ES + 15u) & ~15u);
-    const uint32_t max_span = (n % V == 0 && run.base_elem == row_begin * n) ? n / V : (n + V - 2) / V + 1;
-    if (max_span <= 64u) red_rows_short<POL, RIMPL, DT>(run, po, odt, row_begin, row_end, max_span);
-    else if (max_span >= 1024u && row_end - row_begin <= kRedPartialRows)
-      red_rows_quarter<POL, RIMPL, DT>(run, po, odt, row_begin, row_end, s_part);
-    else if (max_span < 256u) red_rows_wave<POL, RIMPL, DT, 4, 2>(run, po, odt, row_begin, row_end);
-    else red_rows_wave<POL, RIMPL, DT, 2, 4>(run, po, odt, row_begin, row_end);
+    a.base = pin + (uint64_t)a.base_elem * E::ES;
+    a.bytes = ((row_end * n - a.base_elem) * E::ES + 15u) & ~15u;
+    a.po = po; a.odt = odt; a.row_begin = row_begin; a.row_end = row_end; a.s_part = s_part;
+    a.max_span = (n % V == 0 && a.base_elem == row_begin * n) ? n / V : (n + V - 2) / V + 1;
+    if (a.max_span <= 64u) red_rows_short<POL, RIMPL, DT>(a);
+    else if (a.max_span >= 1024u && row_end - row_begin <= kRedPartialRows) red_rows_quarter<POL, RIMPL, DT>(a);
+    else if (a.max_span < 256u) red_rows_wave<POL, RIMPL, DT, 4, 2>(a);
+    else red_rows_wave<POL, RIMPL, DT, 2, 4>(a);
     return;
   }
   // tensor base not 16-byte aligned: one wave per row, element loads
@@ -699,7 +782,9 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
 // PATH_RED_GENERIC: one wave per output row; outer index decomposed over the
 // coalesced outer dims; stride[0][5] walks the reduced dim.
 template <int POL, int RIMPL, bool INT>
-DEV void red_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
+PATHFN void red_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t row_begin = uni(begin_v), row_end = uni(end_v);
   using M = Mem<POL>;
   const int nd = (int)uni(r->ndim);                   // outer dims
   const uint32_t n = uni(r->red_n), sl = uni(r->stride[0][5]);
@@ -875,7 +960,9 @@ DEV void rowop_fused(const Record* r, uint32_t row_begin, uint32_t row_end) {
 }
 
 template <int POL, int ROP>
-DEV void rowop_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
+PATHFN void rowop_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t row_begin = uni(begin_v), row_end = uni(end_v);
   using RO = RowOp<ROP>;
   const int nd = (int)uni(r->ndim);                   // outer dims
   const uint32_t n = uni(r->red_n);
@@ -938,7 +1025,9 @@ DEV void rowop_generic(const Record* r, uint32_t row_begin, uint32_t row_end) {
 }
 
 template <int POL, int ROP, int DT>
-DEV void rowop_fused_dt(const Record* r, uint32_t begin, uint32_t end) {
+PATHFN void rowop_fused_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t begin = uni(begin_v), end = uni(end_v);
   const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
   if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 4>(r, begin, end);
   else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 2>(r, begin, end);
