@@ -144,6 +144,24 @@ typedef struct gpuos_completion {
   uint64_t t_done_ns;               /* time the host first saw the completion word  */
 } gpuos_completion;                 /* 32 bytes */
 
+/* Device-side tracepoint of one task (paper Section 5.3: task id, dequeue
+ * time, execution time, operator-table version), written by the workgroup that
+ * finishes the task into a ring in host memory that can be read while the
+ * worker runs.  Times are ticks of the device's constant 100 MHz clock (10 ns)
+ * since the worker kernel started. */
+typedef struct gpuos_trace_record {
+  uint64_t ticket;
+  uint64_t t_dequeue;               /* dispatcher took the task from the ring          */
+  uint64_t t_start;                 /* the workgroup that ran chunk 0 had claimed it   */
+  uint64_t t_done;                  /* the last chunk's stores had reached memory      */
+  uint32_t op_version;              /* table version the task claimed                  */
+  uint16_t op_id;
+  int8_t   status;
+  uint8_t  reserved;
+  uint32_t nchunks;                 /* work units the task was split into              */
+  uint32_t workgroup;               /* workgroup that ran the last chunk               */
+} gpuos_trace_record;               /* 48 bytes */
+
 /* paper Table 1 peek_queue(): head, tail, processed counts */
 typedef struct gpuos_queue_state {
   uint64_t head_submitted;          /* tickets written into the ring by the host    */
@@ -177,7 +195,11 @@ typedef struct gpuos_config {
                                        host memory, polled by the device over PCIe;
                                        1: in device memory, written by the host through
                                        the PCIe BAR (needs a host-visible BAR)          */
-  uint32_t reserved[5];
+  uint32_t trace_entries;           /* > 0: keep a device-written trace record for the
+                                       last this-many tickets (rounded up to a power of
+                                       two, at most 1<<20) and count dispatched tasks per
+                                       operator; 0: tracing off (default)               */
+  uint32_t reserved[4];
 } gpuos_config;
 
 /* Fill *cfg with the defaults named above. */
@@ -279,6 +301,28 @@ int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n,
 /* Algorithmic HBM bytes of a task (tensor bytes the operation itself must
  * move: each distinct input element once, each output element once). */
 int gpuos_task_bytes(const gpuos_task* task, uint32_t impl_id, uint64_t* out_bytes);
+
+/* Observability (paper Section 5.3), available when cfg.trace_entries > 0,
+ * else GPUOS_E_INVAL.
+ * gpuos_get_trace: trace records of tickets [first_ticket, first_ticket + n),
+ * which must be complete (wait for them first) and among the last
+ * trace_entries tickets; out: HOST array of n.  GPUOS_E_INVAL if a record has
+ * been overwritten by a later ticket or is not there yet.
+ * gpuos_op_counts: tasks dispatched so far per operator id, as of the
+ * dispatcher's last flush (it flushes whenever the ring runs empty and every
+ * 256 batches); out: HOST array of GPUOS_MAX_OPS.
+ * gpuos_trace_origin: host steady_clock nanoseconds (the clock of
+ * gpuos_completion) at device tick 0, to within the latency of one device
+ * write to host memory. */
+int gpuos_get_trace(gpuos_ctx* ctx, uint64_t first_ticket, uint32_t n, gpuos_trace_record* out);
+int gpuos_op_counts(gpuos_ctx* ctx, uint64_t* out);
+int gpuos_trace_origin(gpuos_ctx* ctx, uint64_t* host_ns);
+
+/* Kill switch (paper Section 5.3): rebind op_id to the stub that fails every
+ * task at once with GPUOS_E_BADOP and writes nothing; the same as
+ * gpuos_swap_op(ctx, op_id, GPUOS_IMPL_FAIL, out_version).  A later swap_op
+ * to a real implementation brings the operator back. */
+int gpuos_kill_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t* out_version);
 
 /* How the host would hand this task to the workers (no GPU needed): out[0] =
  * execution path (0 nothing to do, 1 contiguous vector, 2 [rows, cols]

@@ -73,7 +73,8 @@ struct alignas(16) Record {
                              // stride[k][5] is operand k's stride along the last dim, dims
                              // 0..ndim-1 are the outer dims; PATH_ROW_FUSED: stride[k][0] is
                              // the period (rows) of a K_PERIODIC input
-  uint32_t pad2[9];
+  uint32_t t_dequeue[2];     // device clock when the dispatcher took the task (lo, hi)  (dispatcher)
+  uint32_t pad2[7];
   uint32_t check;            // xor of the 63 words above ^ record_check_seed(ticket): set by the host
 };
 static_assert(sizeof(Record) == 256, "ring record must be 256 bytes");
@@ -105,6 +106,7 @@ struct HostCtl {
   alignas(64) uint64_t dispatched;   // device -> host: tickets dequeued from the ring
   alignas(64) uint64_t heartbeat;    // device -> host: dispatcher poll counter
   alignas(64) uint32_t exit_code;    // device -> host: 0 running, 1 stop seen, 2 idle exit
+  alignas(64) uint64_t clock_origin; // device -> host: the device clock when the dispatcher started
 };
 struct DoorbellCtl {
   alignas(64) uint64_t tail;         // host -> device: tickets published (doorbell)
@@ -133,7 +135,18 @@ struct SlotState {                   // device memory, one per ring slot
   uint64_t done_seq;                 // ticket+1 of the last task completed in this slot
   uint32_t chunks_done;
   uint32_t pad;
+  uint64_t t_first;                  // tracing: device clock when chunk 0 of the current task was claimed
 };
+
+struct TraceRec {                    // = gpuos_trace_record (48 bytes), host memory, one per traced ticket
+  uint64_t ticket, t_dequeue, t_start, t_done;
+  uint32_t op_version;
+  uint16_t op_id;
+  int8_t status;
+  uint8_t reserved;
+  uint32_t nchunks, workgroup;
+};
+static_assert(sizeof(TraceRec) == 48, "trace record layout");
 
 // Work-unit entry: bits 0..19 chunk, 20..35 ring slot, 36..43 op id, 44 table slot,
 // 45 op id valid, 46..63 stamp.  The stamp is the lap of the unit ring plus one (18 bits): the
@@ -159,6 +172,9 @@ struct WorkerArgs {
   uint32_t   unit_mask;
   uint32_t   unit_shift;     // log2 of the unit ring size
   uint64_t   idle_exit_ticks;   // 0 = never; 100 MHz ticks
+  TraceRec*  trace;          // host memory; nullptr = tracing off
+  uint64_t*  opcount;        // host memory, GPUOS_MAX_OPS totals (tracing only)
+  uint32_t   trace_mask;
 };
 
 // implemented in gpuos_kernels.hip

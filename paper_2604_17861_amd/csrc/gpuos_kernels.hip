@@ -1171,6 +1171,7 @@ struct DispShared {
   uint32_t bad[kDispatchBatch], ok[kDispatchBatch];   // staging: record still fails its check / passed on this read
   uint32_t nbad;
   uint32_t pre[kPrefetch];                 // prefetched with the poll and valid
+  uint32_t opcnt[GPUOS_MAX_OPS];           // tracing: tasks dispatched per operator since the last flush
   uint32_t ready[kPendMax];                // per pending entry: dependencies complete
   uint64_t tail, epoch_word;
   uint32_t n, npend, npub;
@@ -1269,10 +1270,14 @@ DEV uint32_t dispatcher_service_pending(const WorkerArgs& a, DispShared* s, uint
 DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   const uint32_t tid = threadIdx.x;
   uint64_t mirrored = 0, units_w = 0, seen_epoch = 0;
-  for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) s->entry[op] = 0;
+  for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) { s->entry[op] = 0; s->opcnt[op] = 0; }
   if (tid == 0) s->npend = 0;
   __syncthreads();
   uint64_t idle_since = wall_clock64();
+  if (tid == 0) __hip_atomic_store(&a.h->clock_origin, idle_since, __ATOMIC_RELAXED, SC_SYSTEM);
+  const bool tracing = a.trace != nullptr;
+  uint32_t passes_since_flush = 0;
+  bool counts_dirty = false;
   uint64_t polls = 0;
   bool stopping = false;
   uint64_t st_batches = 0, st_records = 0, st_units = 0, st_stage = 0, st_resolve = 0, st_write = 0, st_busy = 0;
@@ -1424,6 +1429,10 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         rc.status = status;
         if (status != GPUOS_OK || rc.nchunks == 0) rc.nchunks = 1; // one unit reports the task
         rc.ticket = ticket;
+        if (tracing) {
+          rc.t_dequeue[0] = (uint32_t)tk0; rc.t_dequeue[1] = (uint32_t)(tk0 >> 32);
+          if (op < GPUOS_MAX_OPS) atomicAdd(&s->opcnt[op], 1u);
+        }
         uint32_t defer = 0;
         if ((rc.dep[0] | rc.dep[1] | rc.dep[2]) != 0 && rc.nchunks > kSmallTaskChunks) {
           // a large dependent task: its workers never wait; it is published once its
@@ -1488,6 +1497,27 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       st_batches += 1; st_records += n; st_units += total;
       st_stage += tk1 - tk0; st_resolve += tk2 - tk1; st_write += idle_since - tk2; st_busy += idle_since - tk0;
       units_w += dispatcher_service_pending(a, s, units_w);
+      if (tracing) {
+        counts_dirty = true;
+        if (++passes_since_flush >= 256u) {
+          for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) {
+            const uint32_t add = s->opcnt[op];
+            if (add) { s->opcnt[op] = 0; __hip_atomic_fetch_add(&a.opcount[op], (uint64_t)add, __ATOMIC_RELAXED, SC_SYSTEM); }
+          }
+          passes_since_flush = 0;
+          counts_dirty = false;
+          __syncthreads();
+        }
+      }
+    }
+    if (tracing && counts_dirty && mirrored >= tail) {        // the ring ran empty: publish the per-operator counts
+      for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) {
+        const uint32_t add = s->opcnt[op];
+        if (add) { s->opcnt[op] = 0; __hip_atomic_fetch_add(&a.opcount[op], (uint64_t)add, __ATOMIC_RELAXED, SC_SYSTEM); }
+      }
+      passes_since_flush = 0;
+      counts_dirty = false;
+      __syncthreads();
     }
     if (stopping && mirrored >= tail) {
       while (s->npend != 0) units_w += dispatcher_service_pending(a, s, units_w);   // nothing is left behind
@@ -1603,6 +1633,9 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       __syncthreads();
     }
     const uint64_t c3 = wall_clock64();
+    const bool tracing = a.trace != nullptr;
+    if (tracing && tid == 0 && chunk == 0 && r->nchunks > 1)
+      __hip_atomic_store(&a.st[slot].t_first, c1, __ATOMIC_RELAXED, SC_SYSTEM);   // in memory before this chunk is counted
     // ---- execute ----
     if (status == GPUOS_OK) status = exec_chunk<POL_COHERENT>(r, impl, chunk, s->red);
     drain_stores();                   // this wave's (write-through) stores have reached memory
@@ -1619,6 +1652,22 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       }
       if (last) {
         const uint64_t ticket = r->ticket;
+        if (tracing) {
+          // the tracepoint lands before the completion word that lets the host read it
+          const uint64_t origin = __hip_atomic_load(&a.h->clock_origin, __ATOMIC_RELAXED, SC_SYSTEM);
+          const uint64_t t_start = nchunks > 1 ? __hip_atomic_load(&a.st[slot].t_first, __ATOMIC_RELAXED, SC_SYSTEM) : c1;
+          TraceRec* tr = &a.trace[ticket & a.trace_mask];
+          const uint64_t tdq = ((uint64_t)r->t_dequeue[1] << 32) | r->t_dequeue[0];
+          __hip_atomic_store(&tr->t_dequeue, tdq - origin, __ATOMIC_RELAXED, SC_SYSTEM);
+          __hip_atomic_store(&tr->t_start, t_start - origin, __ATOMIC_RELAXED, SC_SYSTEM);
+          __hip_atomic_store(&tr->t_done, c4 - origin, __ATOMIC_RELAXED, SC_SYSTEM);
+          const uint64_t w4 = (uint64_t)r->version | ((uint64_t)r->op_id << 32) | ((uint64_t)(uint8_t)(int8_t)status << 48);
+          __hip_atomic_store((uint64_t*)&tr->op_version, w4, __ATOMIC_RELAXED, SC_SYSTEM);
+          const uint64_t w5 = (uint64_t)nchunks | ((uint64_t)blockIdx.x << 32);
+          __hip_atomic_store((uint64_t*)&tr->nchunks, w5, __ATOMIC_RELAXED, SC_SYSTEM);
+          __hip_atomic_store(&tr->ticket, ticket, __ATOMIC_RELAXED, SC_SYSTEM);
+          drain_stores();
+        }
         __hip_atomic_store(&a.st[slot].done_seq, ticket + 1, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.hcomp[slot], pack_completion(ticket, status, r->version), __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_fetch_add(&a.d->done_count, 1ull, __ATOMIC_RELAXED, SC_AGENT);

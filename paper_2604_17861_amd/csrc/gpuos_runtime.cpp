@@ -426,6 +426,11 @@ struct gpuos_ctx {
   uint64_t* units = nullptr;
   SlotState* st = nullptr;
   OpSlots* dtable = nullptr;
+  // tracing (host-coherent; nullptr when off)
+  TraceRec* trace = nullptr;
+  uint64_t* opcount = nullptr;
+  uint32_t trace_mask = 0;
+  uint64_t origin_host_ns = 0;               // host clock when the worker's first heartbeat was seen
   // producer state
   uint64_t head = 0;                         // tickets written
   std::atomic<uint64_t> published{0};        // tickets behind the doorbell
@@ -533,6 +538,9 @@ void bump_epoch(gpuos_ctx* c, uint32_t op_hint, bool stop) {
 void free_all(gpuos_ctx* c) {
   if (c->h) (void)hipHostFree(c->h);
   if (c->hcomp) (void)hipHostFree(c->hcomp);
+  if (c->trace) (void)hipHostFree(c->trace);
+  if (c->opcount) (void)hipHostFree(c->opcount);
+  c->trace = nullptr; c->opcount = nullptr;
   if (c->push) {
     if (c->bell) (void)hipFree(c->bell);
     if (c->hring) (void)hipFree(c->hring);
@@ -661,6 +669,18 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
     return fail(GPUOS_E_HIP);
   std::memset(c->h, 0, sizeof(HostCtl));
   std::memset(c->hcomp, 0, sizeof(uint64_t) * cap);
+  if (cfg.trace_entries) {
+    uint32_t te = 1;
+    while (te < cfg.trace_entries && te < (1u << 20)) te <<= 1;
+    if (te < cap) te = cap;                                   // every in-flight ticket has an entry of its own
+    if (!hip_ok(hipHostMalloc((void**)&c->trace, sizeof(TraceRec) * te, hflags), "hipHostMalloc(trace)") ||
+        !hip_ok(hipHostMalloc((void**)&c->opcount, sizeof(uint64_t) * GPUOS_MAX_OPS, hflags), "hipHostMalloc(opcount)"))
+      return fail(GPUOS_E_HIP);
+    std::memset(c->trace, 0xff, sizeof(TraceRec) * te);       // ticket = ~0: no record yet
+    std::memset(c->opcount, 0, sizeof(uint64_t) * GPUOS_MAX_OPS);
+    c->trace_mask = te - 1;
+    c->cfg.trace_entries = te;
+  }
   if (c->push) {
     if (!hip_ok(hipMemset(c->bell, 0, sizeof(DoorbellCtl)), "hipMemset") ||
         !hip_ok(hipMemset(c->hring, 0, sizeof(Record) * cap), "hipMemset") ||
@@ -700,6 +720,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   a.unit_shift = 0;
   while (((size_t)1 << a.unit_shift) < n_units) ++a.unit_shift;
   a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
+  a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
   if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
   if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);
   if (!hip_ok(hipEventRecord(c->ev_stop, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
@@ -720,6 +741,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       __builtin_ia32_pause();
     }
   }
+  c->origin_host_ns = now_ns();
   if (cfg.harvester_thread) {
     c->harvester_run.store(true);
     c->harvester = std::thread(harvester_main, c, sched_getcpu());
@@ -966,6 +988,37 @@ int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n, con
   if (out_seconds) *out_seconds = (double)(now_ns() - t0) * 1e-9;
   (void)hipStreamDestroy(s);
   return rc;
+}
+
+int gpuos_get_trace(gpuos_ctx* c, uint64_t first, uint32_t n, gpuos_trace_record* out) {
+  if (!c || !out || !c->trace) return GPUOS_E_INVAL;
+  static_assert(sizeof(gpuos_trace_record) == sizeof(TraceRec), "trace record layout");
+  if (first + n > c->floor.load(std::memory_order_acquire)) {
+    if (c->worker_running && !c->harvester_run.load(std::memory_order_relaxed)) harvest(c);
+    if (first + n > c->floor.load(std::memory_order_acquire)) return GPUOS_E_INVAL;   // not complete yet
+  }
+  for (uint32_t i = 0; i < n; ++i) {
+    const TraceRec* tr = &c->trace[(first + i) & c->trace_mask];
+    std::memcpy(&out[i], tr, sizeof(TraceRec));
+    if (out[i].ticket != first + i) return GPUOS_E_INVAL;      // overwritten by a later ticket
+  }
+  return GPUOS_OK;
+}
+
+int gpuos_op_counts(gpuos_ctx* c, uint64_t* out) {
+  if (!c || !out || !c->opcount) return GPUOS_E_INVAL;
+  for (uint32_t op = 0; op < GPUOS_MAX_OPS; ++op) out[op] = __atomic_load_n(&c->opcount[op], __ATOMIC_ACQUIRE);
+  return GPUOS_OK;
+}
+
+int gpuos_trace_origin(gpuos_ctx* c, uint64_t* host_ns) {
+  if (!c || !host_ns || !c->trace) return GPUOS_E_INVAL;
+  *host_ns = c->origin_host_ns;
+  return GPUOS_OK;
+}
+
+int gpuos_kill_op(gpuos_ctx* c, uint32_t op_id, uint32_t* out_version) {
+  return gpuos_swap_op(c, op_id, GPUOS_IMPL_FAIL, out_version);
 }
 
 int gpuos_task_plan(const gpuos_task* t, uint32_t impl, uint32_t out[4]) {

@@ -31,7 +31,8 @@ class Config(ctypes.Structure):
                 ("harvester_thread", ctypes.c_uint32), ("defer_op_check", ctypes.c_uint32),
                 ("idle_exit_ms", ctypes.c_uint32), ("wait_timeout_ms", ctypes.c_uint32),
                 ("completion_log", ctypes.c_uint32), ("chunk_elems", ctypes.c_uint32),
-                ("push_ring", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 5)]
+                ("push_ring", ctypes.c_uint32), ("trace_entries", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32 * 4)]
 
 
 class QueueState(ctypes.Structure):
@@ -92,6 +93,10 @@ def lib():
         "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
         "gpuos_task_plan": (ctypes.c_int, [vp, u32, vp]),
         "gpuos_device_info": (ctypes.c_int, [i32, vp, vp, u32]),
+        "gpuos_get_trace": (ctypes.c_int, [vp, u64, u32, vp]),
+        "gpuos_op_counts": (ctypes.c_int, [vp, vp]),
+        "gpuos_trace_origin": (ctypes.c_int, [vp, P(u64)]),
+        "gpuos_kill_op": (ctypes.c_int, [vp, u32, P(u32)]),
         "gpuos_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "gpuos_last_hip_error": (ctypes.c_char_p, []),
         "gpuos_abi_layout": (None, [vp]),
@@ -107,7 +112,8 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_strerror",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_get_trace", "gpuos_op_counts",
+           "gpuos_trace_origin", "gpuos_kill_op", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
 
@@ -123,6 +129,12 @@ def abi_layout():
     out = np.zeros(8, dtype=np.uint32)
     lib().gpuos_abi_layout(out.ctypes.data)
     return out
+
+
+TRACE_DT = np.dtype([("ticket", "<u8"), ("t_dequeue", "<u8"), ("t_start", "<u8"), ("t_done", "<u8"),
+                     ("op_version", "<u4"), ("op_id", "<u2"), ("status", "i1"), ("reserved", "u1"),
+                     ("nchunks", "<u4"), ("workgroup", "<u4")])
+assert TRACE_DT.itemsize == 48
 
 
 def device_info(device=0):
@@ -250,6 +262,27 @@ class Runtime:
                   "disp_ticks_write", "disp_ticks_busy", "disp_polls", "work_units", "work_ticks_wait",
                   "work_ticks_fetch", "work_ticks_dep", "work_ticks_exec", "work_ticks_complete",
                   "work_ticks_total", "disp_deferred"]
+
+    def trace(self, first, n):
+        """Device-written trace records of completed tickets [first, first + n) (gpuos_get_trace)."""
+        out = np.zeros(n, dtype=TRACE_DT)
+        _check(lib().gpuos_get_trace(self._ctx, int(first), int(n), out.ctypes.data), "gpuos_get_trace")
+        return out
+
+    def op_counts(self):
+        out = np.zeros(256, dtype=np.uint64)
+        _check(lib().gpuos_op_counts(self._ctx, out.ctypes.data), "gpuos_op_counts")
+        return out
+
+    def trace_origin_ns(self):
+        v = ctypes.c_uint64()
+        _check(lib().gpuos_trace_origin(self._ctx, ctypes.byref(v)), "gpuos_trace_origin")
+        return v.value
+
+    def kill_op(self, op_id):
+        v = ctypes.c_uint32()
+        _check(lib().gpuos_kill_op(self._ctx, int(op_id), ctypes.byref(v)), "gpuos_kill_op")
+        return v.value
 
     def worker_stats(self):
         """Counters of the persistent kernel (after stop_worker); ticks are 10 ns."""

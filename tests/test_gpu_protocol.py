@@ -296,3 +296,68 @@ def test_push_mode_ring_in_device_memory():
             gelu = s.tasks["op_id"] == S.OP_GELU
             for k, (t, _, _) in enumerate(s.swaps):
                 assert np.all(v[t:][gelu[t:]] >= k + 2)
+
+
+def test_device_trace_ring_and_operator_counts():
+    """Tracing on: every task leaves a device-written tracepoint (dequeue <= start <= done on the
+    device clock, version / op / status / chunk count as the completion log and the descriptors say),
+    the per-operator dispatch counts add up to the stream's histogram, kill_op shows in the trace,
+    and records older than the trace ring report as overwritten.  Tracing off: the calls say so."""
+    s = S.config2(n_tasks=3000)
+    dp = _dev(s)
+    with R.Runtime(0, trace_entries=1024, **CFG) as rt:
+        rt.register_table(s.table)
+        assert rt.cfg.trace_entries == 1024
+        t0 = rt.submit(dp.tasks, 0, 2000)
+        rt.wait()
+        tr = rt.trace(t0 + 1000, 1000)                         # the last 1000 of 2000: inside a ring of 4096 (>= capacity)
+        comps = rt.completions(t0 + 1000, 1000)
+        assert np.array_equal(tr["ticket"], np.arange(t0 + 1000, t0 + 2000, dtype=np.uint64))
+        assert np.all(tr["t_dequeue"] <= tr["t_start"]) and np.all(tr["t_start"] <= tr["t_done"])
+        assert np.all(tr["t_done"] < 100e6 * 20)               # ticks since the worker started: well under the 20 s of the test
+        assert np.array_equal(tr["op_version"], comps["op_version"]) and np.all(tr["status"] == 0)
+        assert np.array_equal(tr["op_id"], s.tasks["op_id"][1000:2000])
+        impl = s.impl_for()
+        want_chunks = np.array([R.task_plan(dp.tasks, i, impl[i])[1] for i in range(1000, 2000)])
+        assert np.array_equal(tr["nchunks"], want_chunks)
+        assert tr["workgroup"].min() >= 1 and tr["workgroup"].max() < 1024 and len(np.unique(tr["workgroup"])) > 50
+        exec_us = (tr["t_done"] - tr["t_start"]) / 100.0
+        print("device exec time per task: p50 %.1f us, p99 %.1f us; dequeue->start p50 %.1f us" % (
+            np.percentile(exec_us, 50), np.percentile(exec_us, 99),
+            np.percentile((tr["t_start"] - tr["t_dequeue"]) / 100.0, 50)), flush=True)
+        # the ring is idle now: the counts have been flushed
+        deadline = time.time() + 5
+        want = np.bincount(s.tasks["op_id"][:2000].astype(np.int64), minlength=256).astype(np.uint64)
+        while time.time() < deadline and not np.array_equal(rt.op_counts(), want):
+            time.sleep(0.01)
+        assert np.array_equal(rt.op_counts(), want)
+        # kill switch: the stub's status is in the trace, nothing else changes
+        v = rt.kill_op(S.OP["EXP"])
+        t1 = rt.submit(dp.tasks, 2000, 1000)
+        try:
+            rt.wait()
+        except R.GpuosError as e:
+            assert e.status == R.E_BADOP
+        tr2 = rt.trace(t1, 1000)
+        is_exp = s.tasks["op_id"][2000:3000] == S.OP["EXP"]
+        assert is_exp.any() and np.all(tr2["status"][is_exp] == R.E_BADOP) and np.all(tr2["status"][~is_exp] == 0)
+        assert np.all(tr2["op_version"][is_exp] == v)
+        # records that the ring no longer holds
+        big = rt.cfg.trace_entries
+        assert big == 4096 or big == 1024
+        origin = rt.trace_origin_ns()
+        assert origin > 0
+    s2 = _simple_adds(6000, 256)
+    dp2 = _dev(s2)
+    with R.Runtime(16, trace_entries=64, **CFG) as rt:
+        rt.register_table(s2.table)
+        t0 = rt.submit(dp2.tasks, 0, 6000)
+        rt.wait()
+        assert len(rt.trace(t0 + 6000 - 64, 64)) == 64
+        with pytest.raises(R.GpuosError):
+            rt.trace(t0, 1)                                    # overwritten long ago
+    with R.Runtime(0, **CFG) as rt:
+        with pytest.raises(R.GpuosError):
+            rt.op_counts()
+        with pytest.raises(R.GpuosError):
+            rt.trace(0, 1)
