@@ -52,25 +52,19 @@ class DevicePools:
 
 
 def submit_pass(rt, stream, tasks):
-    """One pass over the stream: batches of stream.batch, hot swaps where scheduled, then wait."""
+    """One pass over the stream: batches of stream.batch, hot swaps where scheduled, then wait.
+    The batches between two swaps are submitted by the library's own loop
+    (gpuos_submit_from_threads with one thread: gpuos_submit + gpuos_flush per batch in the calling
+    thread), so that the interpreter is not part of what is timed."""
     n = len(tasks)
     batch = stream.batch or n
+    cuts = sorted({0, n} | {t for t, _, _ in stream.swaps if 0 < t < n})
     swaps = {t: (op, impl) for t, op, impl in stream.swaps}
-    i = 0
-    first = None
-    while i < n:
-        if i in swaps and i > 0:
-            rt.swap_op(*swaps[i])
-        m = min(batch, n - i)
-        if swaps:
-            for t in range(i + 1, i + m):
-                if t in swaps:
-                    m = t - i
-                    break
-        tk = rt.submit(tasks, i, m)
-        if first is None:
-            first = tk
-        i += m
+    first = rt.peek_queue().head_submitted
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        if lo in swaps and lo > 0:
+            rt.swap_op(*swaps[lo])
+        rt.submit_from_threads(tasks[lo:hi], 1, batch, 1)
     rt.wait()
     return first
 
@@ -96,10 +90,11 @@ def bench_persistent(R, stream, dp, steps, warmup, harvester=True, capacity=0, *
                 lat.append((c["t_done_ns"] - c["t_submit_ns"]).astype(np.int64))
         dt = time.perf_counter() - t0
         q = rt.peek_queue()
-        wg = q.workgroups
+        wg, push = q.workgroups, q.push_ring
     lat = np.concatenate(lat) if lat else np.zeros(0, np.int64)
     return dict(tasks_per_s=steps * len(stream) / dt, seconds=dt, p50_us=percentile_us(lat, 50),
-                p99_us=percentile_us(lat, 99), workgroups=wg)
+                p99_us=percentile_us(lat, 99), workgroups=wg, ring="device memory (host writes through the BAR)" if push
+                else "host memory (device polls over PCIe)")
 
 
 def _reset_swaps(rt, stream):
@@ -107,6 +102,24 @@ def _reset_swaps(rt, stream):
     if stream.swaps and len(stream.swaps) % 2 == 1:
         op = stream.swaps[0][1]
         rt.swap_op(op, stream.table[op])
+
+
+def bench_multi_producer(R, stream, dp, passes=8, **cfg):
+    """tasks/s of the headline stream when 1, 2, 4, 8 and 16 host threads (native threads started
+    by the library) submit disjoint parts of it to ONE context at the same time, batches of 64."""
+    out = {}
+    n = len(stream)
+    for nt in (1, 2, 4, 8, 16):
+        with R.Runtime(0, harvester_thread=1, idle_exit_ms=60000, **cfg) as rt:
+            rt.register_table(stream.table)
+            rt.submit_from_threads(dp.tasks, nt, 64, 1)
+            rt.wait()
+            t0 = time.perf_counter()
+            rt.submit_from_threads(dp.tasks, nt, 64, passes)
+            rt.wait()
+            dt = time.perf_counter() - t0
+        out["threads_%d" % nt] = passes * n / dt
+    return out
 
 
 def bench_pingpong(R, stream, dp, n=5000, **cfg):
@@ -219,7 +232,7 @@ def main():
                per_launch_tasks_per_s=per_launch_tps, speedup_vs_per_launch=res["tasks_per_s"] / per_launch_tps,
                p50_us=res["p50_us"], p99_us=res["p99_us"],
                per_launch_p50_us=percentile_us(lat, 50), per_launch_p99_us=percentile_us(lat, 99),
-               workgroups=res["workgroups"])
+               workgroups=res["workgroups"], ring=res["ring"])
 
     extras = {}
     if not args.skip_extras:
@@ -231,11 +244,14 @@ def main():
         extras["pingpong"] = dict(persistent_p50_us=p50, persistent_p99_us=p99,
                                   per_launch_p50_us=percentile_us(lat1, 50), per_launch_p99_us=percentile_us(lat1, 99))
         log("pingpong:", extras["pingpong"])
-        # ---- push mode: ring in device memory, host writes through the PCIe BAR -------------------
-        pp50, pp99 = bench_pingpong(R, s1, dp1, push_ring=1)
-        rpush = bench_persistent(R, s2, dp2, max(4, args.steps // 2), 1, push_ring=1)
-        extras["push_mode"] = dict(config2_tasks_per_s=rpush["tasks_per_s"], pingpong_p50_us=pp50, pingpong_p99_us=pp99)
-        log("push mode:", extras["push_mode"])
+        # ---- the other ring placement: host memory polled by the device over PCIe ------------------
+        pp50, pp99 = bench_pingpong(R, s1, dp1, push_ring=0)
+        rpull = bench_persistent(R, s2, dp2, max(4, args.steps // 2), 1, push_ring=0)
+        extras["host_ring_mode"] = dict(config2_tasks_per_s=rpull["tasks_per_s"], pingpong_p50_us=pp50, pingpong_p99_us=pp99)
+        log("ring in host memory:", extras["host_ring_mode"])
+        # ---- several producer threads on one ring (ticket reservation is serialised, packing is not) ----
+        extras["multi_producer"] = bench_multi_producer(R, s2, dp2)
+        log("multi producer:", extras["multi_producer"])
         # ---- first configuration ----------------------------------------------------------
         r1 = bench_persistent(R, s1, dp1, max(20, args.steps), args.warmup)
         R.launch_per_op(dp1.tasks, s1.table)
@@ -330,7 +346,7 @@ def main():
                 dtype="f32", data="synthetic",
                 config=dict(workload="config2: 10,000 mixed elementwise tasks (fp32/fp16/bf16 50/25/25, numel "
                                      "log-uniform 256..65536, 30% strided inputs, 20% broadcast), batches of 64",
-                            queue_capacity=4096, workgroups=out["workgroups"]),
+                            queue_capacity=4096, workgroups=out["workgroups"], ring=out["ring"]),
                 per_launch_tasks_per_s=out["per_launch_tasks_per_s"],
                 speedup_vs_per_launch=out["speedup_vs_per_launch"],
                 p50_us=out["p50_us"], p99_us=out["p99_us"], per_launch_p50_us=out["per_launch_p50_us"],
@@ -368,7 +384,7 @@ def write_reports(directory, R, line):
                         per_launch_tasks_per_s=line["per_launch_tasks_per_s"], speedup=line["speedup_vs_per_launch"],
                         p50_us=line["p50_us"], p99_us=line["p99_us"], per_launch_p50_us=line["per_launch_p50_us"],
                         per_launch_p99_us=line["per_launch_p99_us"], oracle_tasks_per_s=line["cpu_baseline"]["value"],
-                        oracle_sample=line["cpu_baseline"]["sample"], push_mode=ex.get("push_mode")),
+                        oracle_sample=line["cpu_baseline"]["sample"], host_ring_mode=ex.get("host_ring_mode"), multi_producer=ex.get("multi_producer")),
         "config1": dict(seed=0, tasks=1000, pingpong=ex.get("pingpong"), **ex.get("config1", {})),
         "config3": dict(seed=2, tasks=12000, **ex.get("config3", {})),
         "config4": dict(seed=3, **ex.get("config4", {})),

@@ -17,8 +17,17 @@
  *     and unmodified until gpuos_wait() has covered the ticket;
  *   - every call returns 0 (GPUOS_OK) or a negative gpuos_status; nothing
  *     throws or aborts across this boundary;
- *   - a context has ONE producer thread (the paper's single-producer ring);
- *     gpuos_swap_op may be called from that thread between submits;
+ *   - any number of host threads may call gpuos_submit / gpuos_flush /
+ *     gpuos_wait / gpuos_register_op / gpuos_swap_op / the query calls on one
+ *     context at the same time (Section 6.4 speaks of many concurrent host
+ *     threads on one ring): descriptors are validated and packed in
+ *     the calling thread, ticket reservation and the ring writes are
+ *     serialised inside the library, so the tickets of one gpuos_submit call
+ *     are consecutive and dependencies (back-distances) inside that call mean
+ *     what they say; a back-distance that reaches before the call's first
+ *     ticket names whatever another thread may have enqueued there, so only
+ *     a single producer may use those.  gpuos_init / gpuos_shutdown /
+ *     gpuos_stop_worker are for one thread;
  *   - while a context is alive the worker kernel is resident on its own
  *     non-blocking stream: the caller must not call hipDeviceSynchronize(),
  *     hipFree() or anything else that waits for "all streams" before
@@ -171,6 +180,9 @@ typedef struct gpuos_queue_state {
   uint64_t heartbeat;               /* worker poll-loop counter (liveness)          */
   uint32_t capacity;
   uint32_t workgroups;              /* resident worker workgroups                   */
+  uint32_t push_ring;               /* 1: the ring lives in device memory (cfg.push_ring
+                                       as resolved at init)                          */
+  uint32_t reserved;
 } gpuos_queue_state;
 
 typedef struct gpuos_config {
@@ -191,10 +203,13 @@ typedef struct gpuos_config {
                                        (0 => 1<<21; rounded up to a power of two)   */
   uint32_t chunk_elems;             /* elements of a task one workgroup takes at a time
                                        (0 => 16384; rounded up to a multiple of 1024)  */
-  uint32_t push_ring;               /* 0: ring, doorbell and table source in fine-grained
-                                       host memory, polled by the device over PCIe;
-                                       1: in device memory, written by the host through
-                                       the PCIe BAR (needs a host-visible BAR)          */
+  uint32_t push_ring;               /* where the ring, the doorbell and the table source
+                                       live: 0 = fine-grained host memory that the device
+                                       polls over PCIe; 1 = device memory that the host
+                                       writes through the PCIe BAR (needs a host-visible
+                                       BAR; the device then polls its own memory and a
+                                       dispatcher pass is about half as long); 2 = 1 when
+                                       the device reports a large BAR, else 0 (default)   */
   uint32_t trace_entries;           /* > 0: keep a device-written trace record for the
                                        last this-many tickets (rounded up to a power of
                                        two, at most 1<<20) and count dispatched tasks per
@@ -297,6 +312,17 @@ int gpuos_run_serial(gpuos_ctx* ctx, const gpuos_task* tasks, uint32_t n, uint64
 int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n,
                         const uint32_t* impl_of_op, int32_t sync_each,
                         uint64_t* lat_ns, double* out_seconds);
+
+/* Measurement helper for the many-producers case (Section 6.4): n_threads host
+ * threads started by the library submit tasks[0 .. n) to ctx at the same time,
+ * thread k its contiguous share in batches of `batch` (one doorbell per
+ * batch), `passes` times over (n_threads = 1: the calling thread does it, no
+ * thread is started); the call returns when every thread has
+ * submitted everything (it does not wait for completion: call gpuos_wait).
+ * *out_seconds (nullable): wall time from the start of the threads to the
+ * last submit returning.  Tasks must not depend on each other. */
+int gpuos_submit_from_threads(gpuos_ctx* ctx, const gpuos_task* tasks, uint32_t n, uint32_t n_threads,
+                              uint32_t batch, uint32_t passes, double* out_seconds);
 
 /* Algorithmic HBM bytes of a task (tensor bytes the operation itself must
  * move: each distinct input element once, each output element once). */

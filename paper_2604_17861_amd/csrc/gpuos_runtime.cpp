@@ -432,7 +432,9 @@ struct gpuos_ctx {
   uint32_t trace_mask = 0;
   uint64_t origin_host_ns = 0;               // host clock when the worker's first heartbeat was seen
   // producer state
-  uint64_t head = 0;                         // tickets written
+  std::mutex prod_mu;                        // producers: ticket reservation, ring writes, doorbell, table changes
+  std::mutex harvest_mu;                     // one harvester at a time
+  std::atomic<uint64_t> head{0};             // tickets written (changed under prod_mu)
   std::atomic<uint64_t> published{0};        // tickets behind the doorbell
   std::atomic<uint64_t> floor{0};            // completed in order
   std::atomic<int32_t> first_error{0};
@@ -457,6 +459,8 @@ bool g_atexit_registered = false;
 
 // Harvest completion words in ticket order (single consumer).
 uint64_t harvest(gpuos_ctx* c) {
+  std::unique_lock<std::mutex> lk(c->harvest_mu, std::try_to_lock);
+  if (!lk.owns_lock()) return 0;             // another thread is harvesting: it will advance the floor
   uint64_t f = c->floor.load(std::memory_order_relaxed);
   const uint64_t pub = c->published.load(std::memory_order_acquire);
   uint64_t t_done = 0;
@@ -516,15 +520,21 @@ int wait_floor(gpuos_ctx* c, uint64_t target, uint64_t timeout_ns) {
   }
 }
 
+// Publish every written ticket: time-stamp, one store-release of the tail.  Caller holds prod_mu.
 void doorbell(gpuos_ctx* c) {
   const uint64_t pub = c->published.load(std::memory_order_relaxed);
-  if (pub == c->head) return;
+  const uint64_t head = c->head.load(std::memory_order_relaxed);
+  if (pub == head) return;
   const uint64_t t = now_ns();
-  for (uint64_t i = pub; i < c->head; ++i) c->log[i & c->log_mask].t_submit_ns = t;
-  c->published.store(c->head, std::memory_order_release);
+  for (uint64_t i = pub; i < head; ++i) c->log[i & c->log_mask].t_submit_ns = t;
+  c->published.store(head, std::memory_order_release);
   if (c->push) _mm_sfence();                                    // records (write-combined BAR stores) before the doorbell
-  __atomic_store_n(&c->bell->tail, c->head, __ATOMIC_RELEASE);  // the commit: one store-release
+  __atomic_store_n(&c->bell->tail, head, __ATOMIC_RELEASE);     // the commit: one store-release
   if (c->push) _mm_sfence();                                    // ... and push the doorbell out of the write-combining buffer
+}
+void doorbell_locked(gpuos_ctx* c) {
+  std::lock_guard<std::mutex> lk(c->prod_mu);
+  doorbell(c);
 }
 
 void bump_epoch(gpuos_ctx* c, uint32_t op_hint, bool stop) {
@@ -567,8 +577,8 @@ int stop_worker(gpuos_ctx* c) {
   if (c->worker_joined) return GPUOS_OK;
   int rc = GPUOS_OK;
   if (c->worker_running) {
-    doorbell(c);
-    rc = wait_floor(c, c->head, c->wait_ns);                  // drain
+    doorbell_locked(c);
+    rc = wait_floor(c, c->head.load(), c->wait_ns);           // drain
     bump_epoch(c, 0xff, true);                                // signal worker exit
     const uint64_t t0 = now_ns();
     hipError_t q;
@@ -613,6 +623,7 @@ void gpuos_default_config(gpuos_config* cfg) {
   cfg->wait_timeout_ms = 30000;
   cfg->completion_log = 1u << 20;
   cfg->chunk_elems = kChunkElems;
+  cfg->push_ring = 2;               // device-memory ring when the BAR allows it
 }
 
 int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* user_cfg) {
@@ -650,7 +661,13 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   if (!hip_ok(hipGetDeviceProperties(&prop, cfg.device), "hipGetDeviceProperties")) return fail(GPUOS_E_HIP);
   const unsigned hflags = hipHostMallocCoherent | hipHostMallocMapped;
   const size_t n_units = (size_t)cap * kMaxChunksPerTask;
-  c->push = cfg.push_ring != 0;
+  c->push = cfg.push_ring == 1;
+  if (cfg.push_ring >= 2) {
+    int large_bar = 0;
+    if (hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, cfg.device) != hipSuccess) large_bar = 0;
+    c->push = large_bar != 0;
+  }
+  c->cfg.push_ring = c->push ? 1u : 0u;
   auto to_device_alloc = [&](void** p, size_t n, const char* what) {
     // memory the host writes and the device reads: pinned host memory, or (push mode) device
     // memory that the host reaches through the BAR
@@ -758,11 +775,12 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
 int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
   if (impl_id == GPUOS_IMPL_NONE || impl_id >= GPUOS_IMPL_COUNT) return GPUOS_E_BADOP;
+  std::lock_guard<std::mutex> lk(c->prod_mu);
   if (c->ops[op_id].version != 0) return GPUOS_E_INVAL;            // already bound: use swap_op
   if (!c->worker_running) return GPUOS_E_DEAD;
   OpInfo& o = c->ops[op_id];
-  o.impl = impl_id;
-  o.version = 1;
+  __atomic_store_n(&o.impl, impl_id, __ATOMIC_RELAXED);
+  __atomic_store_n(&o.version, 1u, __ATOMIC_RELEASE);
   o.prev_swap_head = 0;
   __atomic_store_n(&c->htable[op_id].slot[1], pack_entry(impl_id, 1), __ATOMIC_RELAXED);
   if (c->push) _mm_sfence();                 // write-combined stores: the slot before the version
@@ -775,6 +793,7 @@ int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* 
 int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
   if (impl_id == GPUOS_IMPL_NONE || impl_id >= GPUOS_IMPL_COUNT) return GPUOS_E_BADOP;
+  std::lock_guard<std::mutex> lk(c->prod_mu);
   OpInfo& o = c->ops[op_id];
   if (o.version == 0) return GPUOS_E_BADOP;
   if (!c->worker_running) return GPUOS_E_DEAD;
@@ -793,9 +812,9 @@ int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_
   if (c->push) _mm_sfence();                 // write-combined stores: the slot before the version
   __atomic_store_n(&c->htable[op_id].version, v, __ATOMIC_RELEASE);                           // flip
   bump_epoch(c, op_id, false);
-  o.impl = impl_id;
-  o.version = v;
-  o.prev_swap_head = c->head;
+  __atomic_store_n(&o.impl, impl_id, __ATOMIC_RELAXED);
+  __atomic_store_n(&o.version, v, __ATOMIC_RELEASE);
+  o.prev_swap_head = c->head.load(std::memory_order_relaxed);
   if (out_version) *out_version = v;
   return GPUOS_OK;
 }
@@ -803,15 +822,19 @@ int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_
 int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* out_first_ticket) {
   if (!c || (!tasks && n)) return GPUOS_E_INVAL;
   if (!c->worker_running || worker_exited(c)) return GPUOS_E_DEAD;
-  if (out_first_ticket) *out_first_ticket = c->head;
-  if (n == 0) return GPUOS_OK;
-  // pass 1: validate everything (all-or-nothing)
+  if (n == 0) {
+    if (out_first_ticket) *out_first_ticket = c->head.load(std::memory_order_acquire);
+    return GPUOS_OK;
+  }
+  // pass 1 (no shared state: any number of host threads do this side by side): validate
+  // everything and pack it; nothing is enqueued if one descriptor fails
   static thread_local std::vector<Record> staged;
   staged.resize(n);
   for (uint32_t i = 0; i < n; ++i) {
     const gpuos_task& t = tasks[i];
     uint32_t impl = GPUOS_IMPL_NONE;
-    if (t.op_id < GPUOS_MAX_OPS) impl = c->ops[t.op_id].version ? c->ops[t.op_id].impl : GPUOS_IMPL_NONE;
+    if (t.op_id < GPUOS_MAX_OPS && __atomic_load_n(&c->ops[t.op_id].version, __ATOMIC_ACQUIRE) != 0)
+      impl = __atomic_load_n(&c->ops[t.op_id].impl, __ATOMIC_RELAXED);
     int rc;
     if (impl == GPUOS_IMPL_NONE) {
       if (!c->cfg.defer_op_check) return GPUOS_E_BADOP;
@@ -820,54 +843,61 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
       rc = pack_task(t, impl, &staged[i], c->cfg.chunk_elems);
     }
     if (rc != GPUOS_OK) return rc;
-    for (int k = 0; k < 3; ++k) {
-      const uint64_t back = t.dep[k];
-      if (back >= c->cap || back > c->head + i) return GPUOS_E_INVAL;
-    }
+    for (int k = 0; k < 3; ++k)
+      if (t.dep[k] >= c->cap) return GPUOS_E_INVAL;
   }
+  // pass 2 (one producer at a time): reserve n consecutive tickets and write the records
+  std::lock_guard<std::mutex> lk(c->prod_mu);
+  uint64_t head = c->head.load(std::memory_order_relaxed);
+  for (uint32_t i = 0; i < n; ++i)
+    for (int k = 0; k < 3; ++k)
+      if (tasks[i].dep[k] > head + i) return GPUOS_E_INVAL;       // names a ticket before the first one
+  if (out_first_ticket) *out_first_ticket = head;
   if (c->cfg.nonblocking_submit) {
     if (!c->harvester_run.load(std::memory_order_relaxed)) harvest(c);
-    if ((uint64_t)n > c->cap - (c->head - c->floor.load(std::memory_order_acquire))) return GPUOS_E_FULL;
+    if ((uint64_t)n > c->cap - (head - c->floor.load(std::memory_order_acquire))) return GPUOS_E_FULL;
   }
-  // pass 2: write the records into their slots
   for (uint32_t i = 0; i < n; ++i) {
-    if (c->head - c->floor.load(std::memory_order_acquire) >= c->cap) {
+    if (head - c->floor.load(std::memory_order_acquire) >= c->cap) {
+      c->head.store(head, std::memory_order_release);
       doorbell(c);                                                // publish so that the device can make room
-      const int rc = wait_floor(c, c->head - c->cap + 1, c->wait_ns);
+      const int rc = wait_floor(c, head - c->cap + 1, c->wait_ns);
       if (rc != GPUOS_OK) return rc;
     }
     Record& rec = staged[i];
-    rec.ticket = c->head;
+    rec.ticket = head;
     const uint32_t* w = reinterpret_cast<const uint32_t*>(&rec);
-    uint32_t x = record_check_seed(c->head);
+    uint32_t x = record_check_seed(head);
     for (int k = 0; k < 63; ++k) x ^= w[k];
     rec.check = x;                                                // xor over all 64 words == the seed
-    std::memcpy(&c->hring[c->head & c->mask], &rec, sizeof(Record));
-    ++c->head;
+    std::memcpy(&c->hring[head & c->mask], &rec, sizeof(Record));
+    ++head;
   }
+  c->head.store(head, std::memory_order_release);
   return GPUOS_OK;
 }
 
 int gpuos_flush(gpuos_ctx* c) {
   if (!c) return GPUOS_E_INVAL;
   if (!c->worker_running) return GPUOS_E_DEAD;
-  doorbell(c);
+  doorbell_locked(c);
   return GPUOS_OK;
 }
 
 int gpuos_wait(gpuos_ctx* c, uint64_t ticket, uint64_t timeout_ns) {
   if (!c) return GPUOS_E_INVAL;
-  if (c->worker_running) doorbell(c);
+  if (c->worker_running) doorbell_locked(c);
   const bool all = ticket == GPUOS_ALL;
-  if (!all && ticket >= c->head) return GPUOS_E_INVAL;
-  const uint64_t target = all ? c->head : ticket + 1;
+  const uint64_t head = c->head.load(std::memory_order_acquire);
+  if (!all && ticket >= head) return GPUOS_E_INVAL;
+  const uint64_t target = all ? head : ticket + 1;
   if (c->floor.load(std::memory_order_acquire) < target) {
     if (!c->worker_running) return GPUOS_E_DEAD;
     const int rc = wait_floor(c, target, timeout_ns ? timeout_ns : c->wait_ns);
     if (rc != GPUOS_OK) return rc;
   }
   if (all) return c->first_error.exchange(0);
-  if (c->head - ticket > c->log_mask + 1) return GPUOS_OK;        // fell out of the log
+  if (head - ticket > c->log_mask + 1) return GPUOS_OK;           // fell out of the log
   return c->log[ticket & c->log_mask].status;
 }
 
@@ -883,13 +913,15 @@ int gpuos_get_completions(gpuos_ctx* c, uint64_t first, uint32_t n, gpuos_comple
 int gpuos_peek_queue(gpuos_ctx* c, gpuos_queue_state* out) {
   if (!c || !out) return GPUOS_E_INVAL;
   if (c->worker_running && !c->harvester_run.load(std::memory_order_relaxed)) harvest(c);
-  out->head_submitted = c->head;
+  out->head_submitted = c->head.load(std::memory_order_acquire);
   out->tail_published = c->published.load(std::memory_order_acquire);
   out->claimed = c->h ? __atomic_load_n(&c->h->dispatched, __ATOMIC_ACQUIRE) : 0;
   out->completed = c->floor.load(std::memory_order_acquire);
   out->heartbeat = c->h ? __atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) : 0;
   out->capacity = c->cap;
   out->workgroups = c->workgroups;
+  out->push_ring = c->push ? 1u : 0u;
+  out->reserved = 0;
   return GPUOS_OK;
 }
 
@@ -988,6 +1020,45 @@ int gpuos_launch_per_op(int32_t device, const gpuos_task* tasks, uint32_t n, con
   if (out_seconds) *out_seconds = (double)(now_ns() - t0) * 1e-9;
   (void)hipStreamDestroy(s);
   return rc;
+}
+
+int gpuos_submit_from_threads(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint32_t n_threads,
+                              uint32_t batch, uint32_t passes, double* out_seconds) {
+  if (!c || (!tasks && n) || n_threads == 0 || n_threads > 256 || batch == 0) return GPUOS_E_INVAL;
+  if (n_threads == 1) {
+    const uint64_t t0 = now_ns();
+    int rc = GPUOS_OK;
+    for (uint32_t p = 0; p < passes && rc == GPUOS_OK; ++p)
+      for (uint32_t i = 0; i < n && rc == GPUOS_OK; i += batch) {
+        rc = gpuos_submit(c, tasks + i, n - i < batch ? n - i : batch, nullptr);
+        if (rc == GPUOS_OK) rc = gpuos_flush(c);
+      }
+    if (out_seconds) *out_seconds = (double)(now_ns() - t0) * 1e-9;
+    return rc;
+  }
+  std::vector<std::thread> threads;
+  std::vector<int> rcs(n_threads, GPUOS_OK);
+  std::atomic<uint32_t> ready{0};
+  std::atomic<bool> go{false};
+  for (uint32_t k = 0; k < n_threads; ++k) {
+    threads.emplace_back([&, k] {
+      const uint32_t lo = (uint32_t)((uint64_t)k * n / n_threads), hi = (uint32_t)((uint64_t)(k + 1) * n / n_threads);
+      ready.fetch_add(1);
+      while (!go.load(std::memory_order_acquire)) __builtin_ia32_pause();
+      for (uint32_t p = 0; p < passes && rcs[k] == GPUOS_OK; ++p)
+        for (uint32_t i = lo; i < hi && rcs[k] == GPUOS_OK; i += batch) {
+          rcs[k] = gpuos_submit(c, tasks + i, hi - i < batch ? hi - i : batch, nullptr);
+          if (rcs[k] == GPUOS_OK) rcs[k] = gpuos_flush(c);
+        }
+    });
+  }
+  while (ready.load() < n_threads) __builtin_ia32_pause();
+  const uint64_t t0 = now_ns();
+  go.store(true, std::memory_order_release);
+  for (auto& t : threads) t.join();
+  if (out_seconds) *out_seconds = (double)(now_ns() - t0) * 1e-9;
+  for (int rc : rcs) if (rc != GPUOS_OK) return rc;
+  return GPUOS_OK;
 }
 
 int gpuos_get_trace(gpuos_ctx* c, uint64_t first, uint32_t n, gpuos_trace_record* out) {

@@ -39,7 +39,7 @@ class QueueState(ctypes.Structure):
     _fields_ = [("head_submitted", ctypes.c_uint64), ("tail_published", ctypes.c_uint64),
                 ("claimed", ctypes.c_uint64), ("completed", ctypes.c_uint64),
                 ("heartbeat", ctypes.c_uint64), ("capacity", ctypes.c_uint32),
-                ("workgroups", ctypes.c_uint32)]
+                ("workgroups", ctypes.c_uint32), ("push_ring", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class GpuosError(RuntimeError):
@@ -93,6 +93,7 @@ def lib():
         "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
         "gpuos_task_plan": (ctypes.c_int, [vp, u32, vp]),
         "gpuos_device_info": (ctypes.c_int, [i32, vp, vp, u32]),
+        "gpuos_submit_from_threads": (ctypes.c_int, [vp, vp, u32, u32, u32, u32, P(ctypes.c_double)]),
         "gpuos_get_trace": (ctypes.c_int, [vp, u64, u32, vp]),
         "gpuos_op_counts": (ctypes.c_int, [vp, vp]),
         "gpuos_trace_origin": (ctypes.c_int, [vp, P(u64)]),
@@ -112,7 +113,7 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_get_trace", "gpuos_op_counts",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
            "gpuos_trace_origin", "gpuos_kill_op", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
@@ -262,6 +263,13 @@ class Runtime:
                   "disp_ticks_write", "disp_ticks_busy", "disp_polls", "work_units", "work_ticks_wait",
                   "work_ticks_fetch", "work_ticks_dep", "work_ticks_exec", "work_ticks_complete",
                   "work_ticks_total", "disp_deferred"]
+
+    def submit_from_threads(self, tasks, n_threads, batch=64, passes=1):
+        """gpuos_submit_from_threads over the whole array; returns the seconds until all was submitted."""
+        secs = ctypes.c_double()
+        _check(lib().gpuos_submit_from_threads(self._ctx, _tasks_ptr(tasks, 0), len(tasks), int(n_threads), int(batch),
+                                               int(passes), ctypes.byref(secs)), "gpuos_submit_from_threads")
+        return secs.value
 
     def trace(self, first, n):
         """Device-written trace records of completed tickets [first, first + n) (gpuos_get_trace)."""
