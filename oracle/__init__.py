@@ -49,6 +49,10 @@ def lib():
         L.orc_sum_last_f64.restype = ctypes.c_int
         L.orc_rowop_f64.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         L.orc_rowop_f64.restype = ctypes.c_int
+        L.orc_validate_program.argtypes = [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32]
+        L.orc_validate_program.restype = ctypes.c_int
+        L.orc_run_task_program.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int]
+        L.orc_run_task_program.restype = ctypes.c_int
         L.orc_f16_to_f32.argtypes = [ctypes.c_uint16]
         L.orc_f16_to_f32.restype = ctypes.c_float
         L.orc_f32_to_f16.argtypes = [ctypes.c_float]
@@ -80,15 +84,38 @@ def run_task(tasks, i, impl, mode=MODE_F64CORE):
     return lib().orc_run_task(tasks.ctypes.data + i * tasks.dtype.itemsize, int(impl), int(mode))
 
 
-def run_stream(tasks, impls, mode=MODE_F64CORE, first=0, count=None):
-    """Run tasks[first:first+count] in order; returns the per-task status array."""
+def run_stream(tasks, impls, mode=MODE_F64CORE, first=0, count=None, programs=None):
+    """Run tasks[first:first+count] in order; returns the per-task status array.  programs: impl id
+    -> (instruction array, n_inputs) for the tasks whose operator is a program."""
     n = len(tasks) - first if count is None else count
     impls = np.ascontiguousarray(impls, dtype=np.int32)
     assert len(impls) == len(tasks)
     status = np.zeros(n, dtype=np.int32)
-    lib().orc_run_stream(tasks.ctypes.data + first * tasks.dtype.itemsize, n,
-                         impls.ctypes.data + 4 * first, int(mode), status.ctypes.data)
+    if not programs or not np.isin(impls[first: first + n], list(programs)).any():
+        lib().orc_run_stream(tasks.ctypes.data + first * tasks.dtype.itemsize, n,
+                             impls.ctypes.data + 4 * first, int(mode), status.ctypes.data)
+        return status
+    for k in range(n):
+        i = first + k
+        if int(impls[i]) in programs:
+            code, nin = programs[int(impls[i])]
+            status[k] = run_task_program(tasks, i, code, nin, mode)
+        else:
+            status[k] = run_task(tasks, i, impls[i], mode)
     return status
+
+
+def validate_program(code, n_inputs):
+    code = np.ascontiguousarray(code)
+    return lib().orc_validate_program(code.ctypes.data, len(code), int(n_inputs))
+
+
+def run_task_program(tasks, i, code, n_inputs, mode=MODE_F64CORE):
+    """Run task i with the operator given as a program (instruction array of 8-byte records)."""
+    code = np.ascontiguousarray(code)
+    assert code.dtype.itemsize == 8
+    return lib().orc_run_task_program(tasks.ctypes.data + i * tasks.dtype.itemsize, code.ctypes.data, len(code),
+                                      int(n_inputs), int(mode))
 
 
 def sum_last_f64(tasks, i, n_rows):

@@ -196,9 +196,9 @@ int check_tensor(const orc_tensor& t, int ndim, const int64_t* size, bool is_out
   return ORC_OK;
 }
 
-int validate(const orc_task* t, int impl) {
+int validate(const orc_task* t, int impl, int program_arity = 0) {
   if (impl == ORC_FAIL) return ORC_OK;            // executes nothing; reported at run time
-  const int ar = arity_of(impl);
+  const int ar = program_arity > 0 ? program_arity : arity_of(impl);   // a program: elementwise, float-only, this arity
   if (ar < 0) return ORC_E_BADOP;
   if (t->ndim < 1 || t->ndim > ORC_MAX_DIMS) return ORC_E_INVAL;
   if (t->n_inputs != ar) return ORC_E_INVAL;
@@ -311,6 +311,58 @@ void run_reduction(const orc_task* t, int impl) {
       else acc = impl == ORC_MAX_LAST ? max_nan(acc, x) : min_nan(acc, x);
     }
     store_from_float(t->out.ptr, out_off, t->out.dtype, acc);
+  }
+}
+
+// ---- operator programs ---------------------------------------------------------------
+// One fp32 operation per instruction, in program order, on eight fp32 registers.
+int validate_program(const orc_instr* code, uint32_t n, uint32_t n_inputs) {
+  if (!code || n < 1 || n > ORC_PROGRAM_MAX_INSTR || n_inputs < 1 || n_inputs > 3) return ORC_E_INVAL;
+  for (uint32_t i = 0; i < n; ++i)
+    if (code[i].op >= ORC_PC_COUNT || code[i].dst >= ORC_PROGRAM_REGS || code[i].a >= ORC_PROGRAM_REGS ||
+        code[i].b >= ORC_PROGRAM_REGS)
+      return ORC_E_INVAL;
+  return ORC_OK;
+}
+
+float program_value(const orc_instr* code, uint32_t n, float x, float y, float z, float alpha, int mode) {
+  float r[ORC_PROGRAM_REGS] = {x, y, z, alpha, 0.f, 0.f, 0.f, 0.f};
+  for (uint32_t i = 0; i < n; ++i) {
+    const orc_instr& in = code[i];
+    const float a = r[in.a], b = r[in.b];
+    float v = 0.f;
+    switch (in.op) {
+      case ORC_PC_MOV: v = a; break;
+      case ORC_PC_IMM: v = in.imm; break;
+      case ORC_PC_ADD: v = a + b; break;
+      case ORC_PC_SUB: v = a - b; break;
+      case ORC_PC_MUL: v = a * b; break;
+      case ORC_PC_DIV: v = a / b; break;
+      case ORC_PC_FMA: v = std::fma(a, b, r[in.dst]); break;
+      case ORC_PC_MAX: v = (a != a) ? a : ((b != b) ? b : (a > b ? a : b)); break;
+      case ORC_PC_MIN: v = (a != a) ? a : ((b != b) ? b : (a < b ? a : b)); break;
+      case ORC_PC_NEG: v = -a; break;
+      case ORC_PC_ABS: v = std::fabs(a); break;
+      case ORC_PC_RELU: v = (a != a) ? a : (a > 0.0f ? a : 0.0f); break;
+      case ORC_PC_EXP: v = exp_core(a, mode); break;
+      case ORC_PC_SQRT: v = std::sqrt(a); break;
+      default: break;
+    }
+    r[in.dst] = v;
+  }
+  return r[0];
+}
+
+void run_program(const orc_task* t, const orc_instr* code, uint32_t n, int mode) {
+  const int nd = t->ndim;
+  int64_t numel = 1;
+  for (int d = 0; d < nd; ++d) numel *= t->size[d];
+  for (int64_t i = 0; i < numel; ++i) {
+    float v[3] = {0.f, 0.f, 0.f};
+    for (int k = 0; k < t->n_inputs; ++k)
+      v[k] = load_as_float(t->in[k].ptr, offset_of(t->in[k], nd, t->size, i), t->in[k].dtype);
+    store_from_float(t->out.ptr, offset_of(t->out, nd, t->size, i), t->out.dtype,
+                     program_value(code, n, v[0], v[1], v[2], t->alpha, mode));
   }
 }
 
@@ -435,6 +487,20 @@ int orc_sum_last_f64(const orc_task* t, double* sum, double* l1) {
     sum[o] = s;
     l1[o] = a;
   }
+  return ORC_OK;
+}
+
+int orc_validate_program(const orc_instr* code, uint32_t n_instr, uint32_t n_inputs) {
+  return validate_program(code, n_instr, n_inputs);
+}
+
+int orc_run_task_program(const orc_task* t, const orc_instr* code, uint32_t n_instr, uint32_t n_inputs, int mode) {
+  int rc = validate_program(code, n_instr, n_inputs);
+  if (rc != ORC_OK) return rc;
+  rc = validate(t, ORC_COPY, (int)n_inputs);        // the rules of an elementwise operator of this arity ...
+  if (rc != ORC_OK) return rc;
+  if (t->out.dtype == ORC_I32) return ORC_E_INVAL;  // ... but programs are float-only
+  run_program(t, code, n_instr, mode);
   return ORC_OK;
 }
 

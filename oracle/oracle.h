@@ -96,6 +96,34 @@ int orc_sum_last_f64(const orc_task* t, double* sum, double* l1);
  * (|x| + |mean| + max|x - mean|) * rstd * |gamma| + |beta|. */
 int orc_rowop_f64(const orc_task* t, int impl, double* y, double* scale);
 
+/* Operator programs: an elementwise operator given as a short list of
+ * instructions instead of a built-in id (the role of the paper's runtime
+ * operator injection, Sections 1.2 and 4.1).  Eight fp32 registers; on entry
+ * r0, r1, r2 hold the inputs converted to fp32 (0 for inputs the task does not
+ * have), r3 = alpha, r4..r7 = 0.  Each instruction is ONE IEEE binary32
+ * operation (RNE, denormals kept) on registers: dst = op(a, b):
+ *   MOV a | IMM imm | ADD | SUB | MUL | DIV | FMA fma(a, b, dst) (one rounding) |
+ *   MAX, MIN (a NaN operand wins, a first; else a > b ? a : b resp. a < b ? a : b) |
+ *   NEG | ABS | RELU (a > 0 ? a : +0, NaN stays) | EXP (the mathematical
+ *   function, evaluated per `mode` like the EXP operator) | SQRT (correctly rounded).
+ * The result is r0 after the last instruction, rounded to the output dtype. */
+enum {
+  ORC_PC_MOV = 0, ORC_PC_IMM = 1, ORC_PC_ADD = 2, ORC_PC_SUB = 3, ORC_PC_MUL = 4, ORC_PC_DIV = 5,
+  ORC_PC_FMA = 6, ORC_PC_MAX = 7, ORC_PC_MIN = 8, ORC_PC_NEG = 9, ORC_PC_ABS = 10, ORC_PC_RELU = 11,
+  ORC_PC_EXP = 12, ORC_PC_SQRT = 13, ORC_PC_COUNT = 14
+};
+typedef struct orc_instr { uint8_t op, dst, a, b; float imm; } orc_instr;   /* 8 bytes */
+enum { ORC_PROGRAM_MAX_INSTR = 32, ORC_PROGRAM_REGS = 8 };
+
+/* ORC_OK if the program is well-formed (1..32 instructions, 1..3 inputs, known
+ * opcodes, register numbers below 8), else ORC_E_INVAL. */
+int orc_validate_program(const orc_instr* code, uint32_t n_instr, uint32_t n_inputs);
+
+/* Execute one elementwise task whose operator is the program (task.n_inputs
+ * must equal n_inputs; float tensors only; descriptor rules as orc_validate
+ * for an elementwise operator of that arity). */
+int orc_run_task_program(const orc_task* t, const orc_instr* code, uint32_t n_instr, uint32_t n_inputs, int mode);
+
 /* scalar conversions, exported so the tests can sweep all 65536 patterns */
 float    orc_f16_to_f32(uint16_t h);
 uint16_t orc_f32_to_f16(float f);

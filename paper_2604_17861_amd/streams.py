@@ -52,6 +52,29 @@ OP_GELU = 80
 
 FLAG_FENCE, FLAG_KEEPDIM = 1, 2
 
+# Operator programs (elementwise operators defined at run time as instruction lists): impl ids from
+# PROGRAM_BASE name the programs a context (or a test) has defined.  Eight fp32 registers: r0..r2 the
+# inputs, r3 alpha, r4..r7 zero; each instruction dst = op(a, b); the result is r0.
+PROGRAM_BASE = 64
+INSTR_DT = np.dtype([("op", "u1"), ("dst", "u1"), ("a", "u1"), ("b", "u1"), ("imm", "<f4")])
+PC = dict(MOV=0, IMM=1, ADD=2, SUB=3, MUL=4, DIV=5, FMA=6, MAX=7, MIN=8, NEG=9, ABS=10, RELU=11, EXP=12, SQRT=13)
+PC_INEXACT = (PC["EXP"],)
+
+
+def program(*instrs):
+    """Assemble ('ADD', dst, a, b) / ('IMM', dst, value) / ('NEG', dst, a) ... tuples."""
+    code = np.zeros(len(instrs), dtype=INSTR_DT)
+    for i, ins in enumerate(instrs):
+        name = ins[0]
+        code[i]["op"] = PC[name]
+        code[i]["dst"] = ins[1]
+        if name == "IMM":
+            code[i]["imm"] = ins[2]
+        else:
+            code[i]["a"] = ins[2]
+            code[i]["b"] = ins[3] if len(ins) > 3 else 0
+    return code
+
 
 def default_table() -> Dict[int, int]:
     """logical op id -> impl id as registered before any stream starts."""
@@ -86,6 +109,7 @@ class Stream:
     swaps: List[Tuple[int, int, int]] = field(default_factory=list)  # (before task index, op id, impl)
     batch: int = 0                           # submit batch size (0 = one batch)
     info: dict = field(default_factory=dict)
+    programs: Dict[int, Tuple[np.ndarray, int]] = field(default_factory=dict)   # impl id >= PROGRAM_BASE -> (INSTR_DT code, n_inputs)
 
     def __len__(self):
         return len(self.tasks)

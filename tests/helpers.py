@@ -81,6 +81,14 @@ class Builder:
         self.bases = []
         self.rows = []
         self.table = dict(S.default_table()) if table is None else dict(table)
+        self.programs = {}
+
+    def define_program(self, op_id, code, n_inputs):
+        """Bind logical op `op_id` to a program; returns the impl id it will have."""
+        impl = S.PROGRAM_BASE + len(self.programs)
+        self.programs[impl] = (code, n_inputs)
+        self.table[op_id] = impl
+        return impl
 
     def pool(self, arr):
         arr = np.ascontiguousarray(arr)
@@ -124,12 +132,12 @@ class Builder:
             es = v.dtype.itemsize
             S.set_tensor(tasks, pool_of, i, 3, p, off, [s // es for s in v.strides], _NP2CODE[v.dtype])
         pools = [S.Pool("p%d" % k, b.nbytes, b.view(np.uint8).reshape(-1)) for k, b in enumerate(self.bases)]
-        return S.Stream(name, tasks, pool_of, pools, table=self.table, batch=batch)
+        return S.Stream(name, tasks, pool_of, pools, table=self.table, batch=batch, programs=dict(self.programs))
 
 
 def run_oracle(stream, mode=0, versions=None, images=None):
     """Execute the whole stream on the CPU oracle; returns (HostPools, status)."""
     import oracle
     hp = HostPools(stream, images)
-    st = oracle.run_stream(hp.tasks, stream.impl_for(versions), mode)
+    st = oracle.run_stream(hp.tasks, stream.impl_for(versions), mode, programs=stream.programs)
     return hp, st
