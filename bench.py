@@ -122,6 +122,32 @@ def bench_multi_producer(R, stream, dp, passes=8, **cfg):
     return out
 
 
+def bench_program(R, s5, dp5, impl5, n_tasks=1500):
+    """The ADD tasks of the bandwidth stream with ADD bound to the built-in implementation and to a
+    one-instruction program (interpreted by the resident kernel): what the interpreter costs when
+    the operator is bound by memory; and the same for a six-instruction program."""
+    from paper_2604_17861_amd import streams as S
+    idx = np.nonzero(impl5 == S.IMPL["ADD"])[0][:n_tasks]
+    sub = dp5.tasks[idx].copy()
+    sub["dep"] = 0
+    nbytes = int(R.task_bytes(dp5.tasks[idx], impl5[idx]).sum())
+    out = {}
+    progs = {"builtin_add": None, "program_add_1_instr": S.program(("ADD", 0, 0, 1)),
+             "program_6_instr": S.program(("SUB", 4, 0, 1), ("MUL", 4, 4, 3), ("ABS", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5),
+                                          ("DIV", 0, 0, 4))}
+    for label, code in progs.items():
+        with R.Runtime(0, idle_exit_ms=60000) as rt:
+            table = dict(s5.table)
+            if code is not None:
+                table[S.OP["ADD"]] = rt.define_program(code, 2)
+            rt.register_table(table)
+            rt.submit_from_threads(sub, 1, 64, 1)
+            rt.wait()
+            rt.stop_worker()
+            out[label + "_gbps"] = nbytes / rt.worker_elapsed_ms() / 1e6
+    return out
+
+
 def bench_pingpong(R, stream, dp, n=5000, **cfg):
     """Unloaded latency: one task at a time, timed inside the library (gpuos_run_serial), the same
     way the per-launch path times launch + synchronize."""
@@ -322,6 +348,10 @@ def main():
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
                     traffic=measured_traffic(len(s5)), kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"],
                     algorithmic_bytes=rf["bytes"], workload="config5: %d bandwidth tasks" % len(s5))
+    if not args.skip_extras:
+        # ---- an operator defined at run time as a program against the built-in it re-implements -----
+        extras["operator_program"] = bench_program(R, s5, dp5, impl5)
+        log("operator program:", extras["operator_program"])
     del dp5
 
     # ---- CPU oracle on a bounded sample of the headline stream (one core) ------------------------

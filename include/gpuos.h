@@ -109,6 +109,44 @@ enum gpuos_impl {
   GPUOS_IMPL_COUNT = 20
 };
 
+/* ---- operator programs: operators defined while the worker runs ----------
+ * The paper injects new operators into the running kernel by compiling device
+ * code at run time and publishing its address through the dual-slot table
+ * (Sections 1.2, 4.1).  Here a new ELEMENTWISE operator is given as a short
+ * program that the resident kernel interprets (calls into code objects loaded
+ * after the kernel started are not a documented facility of this platform, and
+ * elementwise work is bound by memory, not by the interpreter).  The rest of
+ * the protocol is the paper's: gpuos_define_program stores the program in a
+ * device-visible table and returns an implementation id; gpuos_register_op /
+ * gpuos_swap_op bind a logical operator to it through the inactive slot and
+ * the version flip, without stopping the worker.
+ * Eight fp32 registers.  On entry r0, r1, r2 = the task's inputs converted to
+ * fp32 (0 where the task has fewer), r3 = task.alpha, r4..r7 = 0.  Every
+ * instruction is ONE IEEE binary32 operation (RNE, denormals kept),
+ * dst = op(a, b); the result is r0 after the last instruction, rounded to the
+ * output dtype.  Float tensors only; any shapes, strides, dtypes, broadcast. */
+enum gpuos_opcode {
+  GPUOS_PC_MOV = 0,   /* dst = a                                               */
+  GPUOS_PC_IMM = 1,   /* dst = imm                                             */
+  GPUOS_PC_ADD = 2, GPUOS_PC_SUB = 3, GPUOS_PC_MUL = 4, GPUOS_PC_DIV = 5,
+  GPUOS_PC_FMA = 6,   /* dst = fma(a, b, dst), one rounding                    */
+  GPUOS_PC_MAX = 7, GPUOS_PC_MIN = 8,  /* a NaN operand wins (a first); else a > b ? a : b,
+                                          resp. a < b ? a : b                  */
+  GPUOS_PC_NEG = 9, GPUOS_PC_ABS = 10,
+  GPUOS_PC_RELU = 11, /* a > 0 ? a : +0, NaN stays NaN                         */
+  GPUOS_PC_EXP = 12,  /* e^a, within 2 ulp like GPUOS_IMPL_EXP                 */
+  GPUOS_PC_SQRT = 13, /* correctly rounded                                     */
+  GPUOS_PC_COUNT = 14
+};
+typedef struct gpuos_instr {
+  uint8_t op, dst, a, b;            /* enum gpuos_opcode; register numbers 0..7   */
+  float   imm;                      /* GPUOS_PC_IMM only                          */
+} gpuos_instr;                      /* 8 bytes */
+#define GPUOS_PROGRAM_MAX_INSTR 32
+#define GPUOS_PROGRAM_REGS      8
+#define GPUOS_MAX_PROGRAMS      64
+#define GPUOS_IMPL_PROGRAM_BASE 64  /* implementation ids 64 .. 127 name programs */
+
 /* ---- task flags --------------------------------------------------------- */
 #define GPUOS_FLAG_FENCE   1u  /* start only after EVERY earlier ticket completed  */
 #define GPUOS_FLAG_KEEPDIM 2u  /* reductions: output keeps a trailing dim of size 1
@@ -240,6 +278,18 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* cfg
  * Tasks submitted after the call returns observe a version >= *out_version. */
 int gpuos_register_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t impl_id, uint32_t* out_version);
 int gpuos_swap_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t impl_id, uint32_t* out_version);
+
+/* Define an operator program (see enum gpuos_opcode): code: HOST array of
+ * n_instr (1..32) instructions, copied; n_inputs: 1..3 tensor inputs the
+ * operator takes.  *out_impl_id receives an implementation id that
+ * gpuos_register_op and gpuos_swap_op accept (kind: elementwise, arity:
+ * n_inputs).  A context holds at most GPUOS_MAX_PROGRAMS programs; they live
+ * until shutdown (GPUOS_E_FULL when the table is full, GPUOS_E_INVAL for a
+ * malformed program).  May be called while the worker runs and tasks are in
+ * flight.  gpuos_launch_per_op, gpuos_task_plan and gpuos_task_bytes know
+ * built-in implementations only. */
+int gpuos_define_program(gpuos_ctx* ctx, const gpuos_instr* code, uint32_t n_instr, uint32_t n_inputs,
+                         uint32_t* out_impl_id);
 
 /* Paper Section 4.2: acquire n consecutive tickets, write the packed records
  * into their slots (slot = ticket & (capacity-1)).  tasks: HOST array of n

@@ -138,6 +138,15 @@ struct SlotState {                   // device memory, one per ring slot
   uint64_t t_first;                  // tracing: device clock when chunk 0 of the current task was claimed
 };
 
+// One operator program as the device reads it (device-visible memory written by the host).
+// The header is written after the code: ready == kProgramReady means the code is complete.
+constexpr uint32_t kProgramReady = 0x50524f47u;
+struct ProgramImage {
+  uint32_t n_instr, n_inputs, ready, pad;
+  uint32_t code[2 * GPUOS_PROGRAM_MAX_INSTR];   // per instruction: op | dst << 8 | a << 16 | b << 24, then imm bits
+};
+static_assert(sizeof(ProgramImage) == 272, "program image layout");
+
 struct TraceRec {                    // = gpuos_trace_record (48 bytes), host memory, one per traced ticket
   uint64_t ticket, t_dequeue, t_start, t_done;
   uint32_t op_version;
@@ -172,6 +181,7 @@ struct WorkerArgs {
   uint32_t   unit_mask;
   uint32_t   unit_shift;     // log2 of the unit ring size
   uint64_t   idle_exit_ticks;   // 0 = never; 100 MHz ticks
+  const ProgramImage* progs; // GPUOS_MAX_PROGRAMS images, written by the host
   TraceRec*  trace;          // host memory; nullptr = tracing off
   uint64_t*  opcount;        // host memory, GPUOS_MAX_OPS totals (tracing only)
   uint32_t   trace_mask;

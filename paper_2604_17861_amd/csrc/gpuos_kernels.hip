@@ -191,6 +191,108 @@ template <> struct Op<GPUOS_IMPL_FMA> { static constexpr int N = 3; static DEV f
 template <> struct Op<GPUOS_IMPL_SUB_EXP> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { const float d = x - y; return expf(d); } };
 template <> struct Op<GPUOS_IMPL_COPY> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return x; } };
 
+// ---------------------------------------------------------------------------
+// operator programs: elementwise operators defined at run time, interpreted.  The program of
+// the chunk being executed sits in LDS (exec_program puts it there); every lane runs the same
+// instruction on its own element, so opcode and register numbers are wavefront-uniform and the
+// loop over the instructions is scalar control flow.  One IEEE binary32 operation per instruction.
+// ---------------------------------------------------------------------------
+__shared__ ProgramImage g_prog;
+
+// internal implementation tags: "the program in LDS, taking N inputs"
+enum { kImplProg1 = 201, kImplProg2 = 202, kImplProg3 = 203 };
+
+// The same program over K elements at once: every instruction is decoded once (scalar work) and
+// applied to the K elements a lane holds, so the interpreter's overhead is shared by a whole
+// 16-byte vector instead of being paid per element.
+template <int K>
+DEV void run_program_vec(const float (&x)[K], const float (&y)[K], const float (&z)[K], float alpha, float (&o)[K]) {
+  // The register file is eight separately named arrays selected by a switch on the (uniform)
+  // register number: a dynamically indexed array would be placed in scratch memory.
+  float r0[K], r1[K], r2[K], r3[K], r4[K], r5[K], r6[K], r7[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    r0[k] = x[k]; r1[k] = y[k]; r2[k] = z[k]; r3[k] = alpha;
+    r4[k] = 0.f; r5[k] = 0.f; r6[k] = 0.f; r7[k] = 0.f;
+  }
+#define GPUOS_RF_COPY(dst, src) _Pragma("unroll") for (int k = 0; k < K; ++k) dst[k] = src[k];
+#define GPUOS_RF_READ(dst, idx) switch (idx) { \
+    case 0: GPUOS_RF_COPY(dst, r0) break; case 1: GPUOS_RF_COPY(dst, r1) break; \
+    case 2: GPUOS_RF_COPY(dst, r2) break; case 3: GPUOS_RF_COPY(dst, r3) break; \
+    case 4: GPUOS_RF_COPY(dst, r4) break; case 5: GPUOS_RF_COPY(dst, r5) break; \
+    case 6: GPUOS_RF_COPY(dst, r6) break; default: GPUOS_RF_COPY(dst, r7) break; }
+#define GPUOS_RF_WRITE(idx, src) switch (idx) { \
+    case 0: GPUOS_RF_COPY(r0, src) break; case 1: GPUOS_RF_COPY(r1, src) break; \
+    case 2: GPUOS_RF_COPY(r2, src) break; case 3: GPUOS_RF_COPY(r3, src) break; \
+    case 4: GPUOS_RF_COPY(r4, src) break; case 5: GPUOS_RF_COPY(r5, src) break; \
+    case 6: GPUOS_RF_COPY(r6, src) break; default: GPUOS_RF_COPY(r7, src) break; }
+  const uint32_t n = __builtin_amdgcn_readfirstlane(g_prog.n_instr);
+  for (uint32_t i = 0; i < n; ++i) {
+    const uint32_t w = __builtin_amdgcn_readfirstlane(g_prog.code[2 * i]);
+    const float imm = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(g_prog.code[2 * i + 1]));
+    const uint32_t op = w & 0xffu, d = (w >> 8) & 7u, ia = (w >> 16) & 7u, ib = (w >> 24) & 7u;
+    float a[K], b[K], v[K];
+    GPUOS_RF_READ(a, ia)
+    GPUOS_RF_READ(b, ib)
+    switch (op) {
+#define GPUOS_PC_CASE(code, expr) case code: _Pragma("unroll") for (int k = 0; k < K; ++k) v[k] = (expr); break;
+      GPUOS_PC_CASE(GPUOS_PC_MOV, a[k])
+      GPUOS_PC_CASE(GPUOS_PC_IMM, imm)
+      GPUOS_PC_CASE(GPUOS_PC_ADD, a[k] + b[k])
+      GPUOS_PC_CASE(GPUOS_PC_SUB, a[k] - b[k])
+      GPUOS_PC_CASE(GPUOS_PC_MUL, a[k] * b[k])
+      GPUOS_PC_CASE(GPUOS_PC_DIV, a[k] / b[k])
+      GPUOS_PC_CASE(GPUOS_PC_MAX, (a[k] != a[k]) ? a[k] : ((b[k] != b[k]) ? b[k] : (a[k] > b[k] ? a[k] : b[k])))
+      GPUOS_PC_CASE(GPUOS_PC_MIN, (a[k] != a[k]) ? a[k] : ((b[k] != b[k]) ? b[k] : (a[k] < b[k] ? a[k] : b[k])))
+      GPUOS_PC_CASE(GPUOS_PC_NEG, -a[k])
+      GPUOS_PC_CASE(GPUOS_PC_ABS, __builtin_fabsf(a[k]))
+      GPUOS_PC_CASE(GPUOS_PC_RELU, (a[k] != a[k]) ? a[k] : (a[k] > 0.0f ? a[k] : 0.0f))
+      GPUOS_PC_CASE(GPUOS_PC_EXP, expf(a[k]))
+      GPUOS_PC_CASE(GPUOS_PC_SQRT, __builtin_sqrtf(a[k]))
+#undef GPUOS_PC_CASE
+      case GPUOS_PC_FMA: {
+        float c[K];
+        GPUOS_RF_READ(c, d)
+#pragma unroll
+        for (int k = 0; k < K; ++k) v[k] = __builtin_fmaf(a[k], b[k], c[k]);
+      } break;
+      default:
+#pragma unroll
+        for (int k = 0; k < K; ++k) v[k] = 0.f;
+        break;
+    }
+    GPUOS_RF_WRITE(d, v)
+  }
+#pragma unroll
+  for (int k = 0; k < K; ++k) o[k] = r0[k];
+#undef GPUOS_RF_COPY
+#undef GPUOS_RF_READ
+#undef GPUOS_RF_WRITE
+}
+
+DEV float run_program(float x, float y, float z, float alpha) {      // one element (strided and ragged-tail paths)
+  const float xs[1] = {x}, ys[1] = {y}, zs[1] = {z};
+  float os[1];
+  run_program_vec<1>(xs, ys, zs, alpha, os);
+  return os[0];
+}
+template <> struct Op<kImplProg1> { static constexpr int N = 1; static DEV float f(float x, float, float, float a) { return run_program(x, 0.f, 0.f, a); } };
+template <> struct Op<kImplProg2> { static constexpr int N = 2; static DEV float f(float x, float y, float, float a) { return run_program(x, y, 0.f, a); } };
+template <> struct Op<kImplProg3> { static constexpr int N = 3; static DEV float f(float x, float y, float z, float a) { return run_program(x, y, z, a); } };
+
+// o[k] = f(x[k], y[k], z[k], alpha) for the K elements a lane holds: element by element for the
+// built-in implementations (the compiler unrolls it back into straight code), instruction by
+// instruction for a program.
+template <int IMPL, int K>
+DEV void apply_vec(const float (&x)[K], const float (&y)[K], const float (&z)[K], float alpha, float (&o)[K]) {
+  if (IMPL == kImplProg1 || IMPL == kImplProg2 || IMPL == kImplProg3) {
+    run_program_vec<K>(x, y, z, alpha, o);
+  } else {
+#pragma unroll
+    for (int k = 0; k < K; ++k) o[k] = Op<IMPL>::f(x[k], y[k], z[k], alpha);
+  }
+}
+
 template <int IMPL> DEV uint32_t int_op(uint32_t x, uint32_t y) {
   if (IMPL == GPUOS_IMPL_ADD) return x + y;
   if (IMPL == GPUOS_IMPL_SUB) return x - y;
@@ -253,9 +355,14 @@ PATHFN void ew_contig(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
         v4i q;
         if (IMPL == GPUOS_IMPL_COPY) q = qa[u];
         else {
+          float xa[V], xb[V], xc[V], xo[V];
 #pragma unroll
-          for (int k = 0; k < V; ++k)
-            E::put(q, k, Op<IMPL>::f(E::get(qa[u], k), N > 1 ? E::get(qb[u], k) : 0.f, N > 2 ? E::get(qc[u], k) : 0.f, alpha));
+          for (int k = 0; k < V; ++k) {
+            xa[k] = E::get(qa[u], k); xb[k] = N > 1 ? E::get(qb[u], k) : 0.f; xc[k] = N > 2 ? E::get(qc[u], k) : 0.f;
+          }
+          apply_vec<IMPL, V>(xa, xb, xc, alpha, xo);
+#pragma unroll
+          for (int k = 0; k < V; ++k) E::put(q, k, xo[k]);
         }
         M::st16(ro, (v + u * kThreads) * 16u, q);
       }
@@ -267,9 +374,14 @@ PATHFN void ew_contig(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
       if (N > 2) qc = M::ld16(rc, v * 16u);
       if (IMPL == GPUOS_IMPL_COPY) q = qa;
       else {
+        float xa[V], xb[V], xc[V], xo[V];
 #pragma unroll
-        for (int k = 0; k < V; ++k)
-          E::put(q, k, Op<IMPL>::f(E::get(qa, k), N > 1 ? E::get(qb, k) : 0.f, N > 2 ? E::get(qc, k) : 0.f, alpha));
+        for (int k = 0; k < V; ++k) {
+          xa[k] = E::get(qa, k); xb[k] = N > 1 ? E::get(qb, k) : 0.f; xc[k] = N > 2 ? E::get(qc, k) : 0.f;
+        }
+        apply_vec<IMPL, V>(xa, xb, xc, alpha, xo);
+#pragma unroll
+        for (int k = 0; k < V; ++k) E::put(q, k, xo[k]);
       }
       M::st16(ro, v * 16u, q);
     }
@@ -359,13 +471,14 @@ PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float*
       else s[k] = load_rt<POL>(p[k], row * st0[k], dt[k]);
     }
     v4i res;
+    float xv[3][V], xo[V];
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
-      float x[3] = {0.f, 0.f, 0.f};
+    for (int e = 0; e < V; ++e)
 #pragma unroll
-      for (int k = 0; k < N; ++k) x[k] = (kind[k] == K_ROWSCALAR) ? s[k] : E::get(q[k], e);
-      E::put(res, e, Op<IMPL>::f(x[0], x[1], x[2], alpha));
-    }
+      for (int k = 0; k < 3; ++k) xv[k][e] = k < N ? ((kind[k] == K_ROWSCALAR) ? s[k] : E::get(q[k], e)) : 0.f;
+    apply_vec<IMPL, V>(xv[0], xv[1], xv[2], alpha, xo);
+#pragma unroll
+    for (int e = 0; e < V; ++e) E::put(res, e, xo[e]);
     M::st16(ro, v * 16u, res);
   }
   if (staged) __syncthreads();        // the scratch may be reused by the next chunk
@@ -1100,10 +1213,31 @@ DEV void run_reduction(const Record* r, uint32_t chunk, float* s_red) {
   }
 }
 
+// A task whose operator is a program: fetch the program into LDS (17 lanes x 16 bytes), then run
+// the ordinary elementwise paths with the interpreter as their functor.
+template <int POL>
+DEV int32_t exec_program(const Record* r, uint32_t impl, uint32_t chunk, float* s_red, const ProgramImage* progs) {
+  const uint32_t k = impl - GPUOS_IMPL_PROGRAM_BASE;
+  if (progs == nullptr || k >= GPUOS_MAX_PROGRAMS) return GPUOS_E_BADOP;
+  const rsrc_t rp = make_rsrc(progs + k, (uint32_t)sizeof(ProgramImage));
+  if (threadIdx.x < sizeof(ProgramImage) / 16) ((v4i*)&g_prog)[threadIdx.x] = Mem<POL_COHERENT>::ld16(rp, threadIdx.x * 16u);
+  __syncthreads();
+  int32_t status = GPUOS_OK;
+  const uint32_t n_in = uni(g_prog.n_inputs), n_instr = uni(g_prog.n_instr);
+  if (uni(g_prog.ready) != kProgramReady || n_instr < 1 || n_instr > GPUOS_PROGRAM_MAX_INSTR || n_in != uni(r->n_inputs))
+    status = GPUOS_E_INVAL;                            // never defined (or not what the task was packed for)
+  else if (n_in == 1) run_elementwise<POL, kImplProg1>(r, chunk, s_red);
+  else if (n_in == 2) run_elementwise<POL, kImplProg2>(r, chunk, s_red);
+  else run_elementwise<POL, kImplProg3>(r, chunk, s_red);
+  __syncthreads();                                     // the next chunk may bring another program
+  return status;
+}
+
 // returns the task status contribution of this chunk (0 or an error)
 template <int POL>
-DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_red) {
+DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_red, const ProgramImage* progs) {
   if (uni(r->path) == PATH_NOP) return impl == GPUOS_IMPL_FAIL ? GPUOS_E_BADOP : GPUOS_OK;
+  if (impl >= GPUOS_IMPL_PROGRAM_BASE) return exec_program<POL>(r, impl, chunk, s_red, progs);
   switch (impl) {
     case GPUOS_IMPL_ADD: run_elementwise<POL, GPUOS_IMPL_ADD>(r, chunk, s_red); break;
     case GPUOS_IMPL_SUB: run_elementwise<POL, GPUOS_IMPL_SUB>(r, chunk, s_red); break;
@@ -1637,7 +1771,7 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
     if (tracing && tid == 0 && chunk == 0 && r->nchunks > 1)
       __hip_atomic_store(&a.st[slot].t_first, c1, __ATOMIC_RELAXED, SC_SYSTEM);   // in memory before this chunk is counted
     // ---- execute ----
-    if (status == GPUOS_OK) status = exec_chunk<POL_COHERENT>(r, impl, chunk, s->red);
+    if (status == GPUOS_OK) status = exec_chunk<POL_COHERENT>(r, impl, chunk, s->red, a.progs);
     drain_stores();                   // this wave's (write-through) stores have reached memory
     __syncthreads();                  // ... and so have the other three waves'
     const uint64_t c4 = wall_clock64();
@@ -1696,7 +1830,7 @@ __global__ void __launch_bounds__(kThreads) gpuos_single_task_kernel(Record rec)
   __shared__ float s_red[kScratchFloats];
   if (threadIdx.x == 0) s_rec = rec;
   __syncthreads();
-  exec_chunk<POL_PLAIN>(&s_rec, s_rec.impl, blockIdx.x, s_red);
+  exec_chunk<POL_PLAIN>(&s_rec, s_rec.impl, blockIdx.x, s_red, nullptr);   // built-in implementations only
 }
 
 int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream) {

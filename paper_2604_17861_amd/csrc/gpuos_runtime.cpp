@@ -142,7 +142,7 @@ inline bool aligned16(uint64_t p) { return (p & 15u) == 0; }
 
 // Validate `t` for implementation `impl` and pack it.  Nothing is written to
 // *r unless the result is GPUOS_OK.
-int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elems = kChunkElems) {
+int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elems = kChunkElems, int program_arity = 0) {
   Record rec;
   std::memset(&rec, 0, sizeof(rec));
   rec.op_id = t.op_id;
@@ -157,7 +157,8 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
     *r = rec;
     return GPUOS_OK;
   }
-  const int ar = impl_arity(impl);
+  // an operator program: elementwise, float-only, the arity it was defined with
+  const int ar = impl >= GPUOS_IMPL_PROGRAM_BASE ? (program_arity > 0 ? program_arity : -1) : impl_arity(impl);
   if (ar < 0) return GPUOS_E_BADOP;
   if (t.ndim < 1 || t.ndim > GPUOS_MAX_DIMS || t.n_inputs != ar) return GPUOS_E_INVAL;
   int64_t size[GPUOS_MAX_DIMS];
@@ -426,6 +427,10 @@ struct gpuos_ctx {
   uint64_t* units = nullptr;
   SlotState* st = nullptr;
   OpSlots* dtable = nullptr;
+  // operator programs (device-visible like the ring; written by the host)
+  ProgramImage* progs = nullptr;
+  uint32_t n_progs = 0;                      // changed under prod_mu
+  uint8_t prog_arity[GPUOS_MAX_PROGRAMS] = {};
   // tracing (host-coherent; nullptr when off)
   TraceRec* trace = nullptr;
   uint64_t* opcount = nullptr;
@@ -552,10 +557,12 @@ void free_all(gpuos_ctx* c) {
   if (c->opcount) (void)hipHostFree(c->opcount);
   c->trace = nullptr; c->opcount = nullptr;
   if (c->push) {
+    if (c->progs) (void)hipFree(c->progs);
     if (c->bell) (void)hipFree(c->bell);
     if (c->hring) (void)hipFree(c->hring);
     if (c->htable) (void)hipFree(c->htable);
   } else {
+    if (c->progs) (void)hipHostFree(c->progs);
     if (c->bell) (void)hipHostFree(c->bell);
     if (c->hring) (void)hipHostFree(c->hring);
     if (c->htable) (void)hipHostFree(c->htable);
@@ -568,6 +575,7 @@ void free_all(gpuos_ctx* c) {
   if (c->ev_start) (void)hipEventDestroy(c->ev_start);
   if (c->ev_stop) (void)hipEventDestroy(c->ev_stop);
   if (c->stream) (void)hipStreamDestroy(c->stream);
+  c->progs = nullptr;
   c->h = nullptr; c->bell = nullptr; c->hring = nullptr; c->hcomp = nullptr; c->htable = nullptr;
   c->d = nullptr; c->dring = nullptr; c->units = nullptr; c->st = nullptr; c->dtable = nullptr;
   c->ev_start = nullptr; c->ev_stop = nullptr; c->stream = nullptr;
@@ -678,6 +686,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       !to_device_alloc((void**)&c->hring, sizeof(Record) * cap, "alloc(ring)") ||
       !hip_ok(hipHostMalloc((void**)&c->hcomp, sizeof(uint64_t) * cap, hflags), "hipHostMalloc(comp)") ||
       !to_device_alloc((void**)&c->htable, sizeof(OpSlots) * GPUOS_MAX_OPS, "alloc(table)") ||
+      !to_device_alloc((void**)&c->progs, sizeof(ProgramImage) * GPUOS_MAX_PROGRAMS, "alloc(programs)") ||
       !hip_ok(hipMalloc((void**)&c->d, sizeof(DevCtl)), "hipMalloc(ctl)") ||
       !hip_ok(hipMalloc((void**)&c->dring, sizeof(Record) * cap), "hipMalloc(ring)") ||
       !hip_ok(hipMalloc((void**)&c->units, sizeof(uint64_t) * n_units), "hipMalloc(units)") ||
@@ -701,12 +710,14 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   if (c->push) {
     if (!hip_ok(hipMemset(c->bell, 0, sizeof(DoorbellCtl)), "hipMemset") ||
         !hip_ok(hipMemset(c->hring, 0, sizeof(Record) * cap), "hipMemset") ||
-        !hip_ok(hipMemset(c->htable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS), "hipMemset"))
+        !hip_ok(hipMemset(c->htable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS), "hipMemset") ||
+        !hip_ok(hipMemset(c->progs, 0, sizeof(ProgramImage) * GPUOS_MAX_PROGRAMS), "hipMemset"))
       return fail(GPUOS_E_HIP);
   } else {
     std::memset(c->bell, 0, sizeof(DoorbellCtl));
     std::memset(c->hring, 0, sizeof(Record) * cap);
     std::memset(c->htable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS);
+    std::memset(c->progs, 0, sizeof(ProgramImage) * GPUOS_MAX_PROGRAMS);
   }
   if (!hip_ok(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking), "hipStreamCreateWithFlags") ||
       !hip_ok(hipEventCreate(&c->ev_start), "hipEventCreate") ||
@@ -737,6 +748,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   a.unit_shift = 0;
   while (((size_t)1 << a.unit_shift) < n_units) ++a.unit_shift;
   a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
+  a.progs = c->progs;
   a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
   if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
   if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);
@@ -772,10 +784,52 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   return GPUOS_OK;
 }
 
+namespace {
+// built-in implementation, or a program this context has defined (caller holds prod_mu)
+bool impl_known(const gpuos_ctx* c, uint32_t impl) {
+  if (impl != GPUOS_IMPL_NONE && impl < GPUOS_IMPL_COUNT) return true;
+  return impl >= GPUOS_IMPL_PROGRAM_BASE && impl - GPUOS_IMPL_PROGRAM_BASE < c->n_progs;
+}
+int ctx_impl_arity(const gpuos_ctx* c, uint32_t impl) {
+  return impl >= GPUOS_IMPL_PROGRAM_BASE ? (int)c->prog_arity[impl - GPUOS_IMPL_PROGRAM_BASE] : impl_arity(impl);
+}
+}  // namespace
+
+int gpuos_define_program(gpuos_ctx* c, const gpuos_instr* code, uint32_t n_instr, uint32_t n_inputs, uint32_t* out_impl_id) {
+  if (!c || !code || !out_impl_id) return GPUOS_E_INVAL;
+  if (n_instr < 1 || n_instr > GPUOS_PROGRAM_MAX_INSTR || n_inputs < 1 || n_inputs > GPUOS_MAX_INPUTS) return GPUOS_E_INVAL;
+  ProgramImage img;
+  std::memset(&img, 0, sizeof(img));
+  for (uint32_t i = 0; i < n_instr; ++i) {
+    const gpuos_instr& in = code[i];
+    if (in.op >= GPUOS_PC_COUNT || in.dst >= GPUOS_PROGRAM_REGS || in.a >= GPUOS_PROGRAM_REGS || in.b >= GPUOS_PROGRAM_REGS)
+      return GPUOS_E_INVAL;
+    img.code[2 * i] = (uint32_t)in.op | ((uint32_t)in.dst << 8) | ((uint32_t)in.a << 16) | ((uint32_t)in.b << 24);
+    std::memcpy(&img.code[2 * i + 1], &in.imm, 4);
+  }
+  img.n_instr = n_instr; img.n_inputs = n_inputs; img.ready = kProgramReady;
+  std::lock_guard<std::mutex> lk(c->prod_mu);
+  if (!c->worker_running) return GPUOS_E_DEAD;
+  if (c->n_progs >= GPUOS_MAX_PROGRAMS) return GPUOS_E_FULL;
+  const uint32_t k = c->n_progs;
+  // the code first, the header (with the ready word) after it: the device never runs half a program
+  std::memcpy(c->progs[k].code, img.code, sizeof(img.code));
+  if (c->push) _mm_sfence();
+  std::atomic_thread_fence(std::memory_order_release);
+  std::memcpy(&c->progs[k], &img, 16);
+  if (c->push) _mm_sfence();
+  std::atomic_thread_fence(std::memory_order_release);
+  c->prog_arity[k] = (uint8_t)n_inputs;
+  c->n_progs = k + 1;
+  *out_impl_id = GPUOS_IMPL_PROGRAM_BASE + k;
+  return GPUOS_OK;
+}
+
 int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
-  if (impl_id == GPUOS_IMPL_NONE || impl_id >= GPUOS_IMPL_COUNT) return GPUOS_E_BADOP;
+  if (impl_id == GPUOS_IMPL_NONE || (impl_id >= GPUOS_IMPL_COUNT && impl_id < GPUOS_IMPL_PROGRAM_BASE)) return GPUOS_E_BADOP;
   std::lock_guard<std::mutex> lk(c->prod_mu);
+  if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   if (c->ops[op_id].version != 0) return GPUOS_E_INVAL;            // already bound: use swap_op
   if (!c->worker_running) return GPUOS_E_DEAD;
   OpInfo& o = c->ops[op_id];
@@ -792,13 +846,13 @@ int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* 
 
 int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
-  if (impl_id == GPUOS_IMPL_NONE || impl_id >= GPUOS_IMPL_COUNT) return GPUOS_E_BADOP;
   std::lock_guard<std::mutex> lk(c->prod_mu);
+  if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   OpInfo& o = c->ops[op_id];
   if (o.version == 0) return GPUOS_E_BADOP;
   if (!c->worker_running) return GPUOS_E_DEAD;
   if (impl_id != GPUOS_IMPL_FAIL && o.impl != GPUOS_IMPL_FAIL &&
-      (impl_arity(impl_id) != impl_arity(o.impl) || impl_kind(impl_id) != impl_kind(o.impl)))
+      (ctx_impl_arity(c, impl_id) != ctx_impl_arity(c, o.impl) || impl_kind(impl_id) != impl_kind(o.impl)))
     return GPUOS_E_INVAL;
   // The inactive slot still holds version-1's predecessor.  A task can only hold
   // that entry if it was submitted before the previous swap returned: wait for those.
@@ -840,7 +894,9 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
       if (!c->cfg.defer_op_check) return GPUOS_E_BADOP;
       rc = pack_task(t, GPUOS_IMPL_FAIL, &staged[i], c->cfg.chunk_elems);   // the device reports the bad op id
     } else {
-      rc = pack_task(t, impl, &staged[i], c->cfg.chunk_elems);
+      // a program's arity was stored before its id could be bound to any operator
+      const int pa = impl >= GPUOS_IMPL_PROGRAM_BASE ? (int)c->prog_arity[(impl - GPUOS_IMPL_PROGRAM_BASE) % GPUOS_MAX_PROGRAMS] : 0;
+      rc = pack_task(t, impl, &staged[i], c->cfg.chunk_elems, pa);
     }
     if (rc != GPUOS_OK) return rc;
     for (int k = 0; k < 3; ++k)

@@ -93,6 +93,7 @@ def lib():
         "gpuos_task_bytes": (ctypes.c_int, [vp, u32, P(u64)]),
         "gpuos_task_plan": (ctypes.c_int, [vp, u32, vp]),
         "gpuos_device_info": (ctypes.c_int, [i32, vp, vp, u32]),
+        "gpuos_define_program": (ctypes.c_int, [vp, vp, u32, u32, P(u32)]),
         "gpuos_submit_from_threads": (ctypes.c_int, [vp, vp, u32, u32, u32, u32, P(ctypes.c_double)]),
         "gpuos_get_trace": (ctypes.c_int, [vp, u64, u32, vp]),
         "gpuos_op_counts": (ctypes.c_int, [vp, vp]),
@@ -113,7 +114,7 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_define_program", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
            "gpuos_trace_origin", "gpuos_kill_op", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
@@ -196,7 +197,24 @@ class Runtime:
         _check(lib().gpuos_swap_op(self._ctx, op_id, impl_id, ctypes.byref(v)), "gpuos_swap_op")
         return v.value
 
-    def register_table(self, table):
+    def define_program(self, code, n_inputs):
+        """gpuos_define_program: code is an array of 8-byte instructions {op, dst, a, b, imm}
+        (streams.program assembles one); returns the implementation id to register / swap in."""
+        code = np.ascontiguousarray(code)
+        assert code.dtype.itemsize == 8
+        v = ctypes.c_uint32()
+        _check(lib().gpuos_define_program(self._ctx, code.ctypes.data, len(code), int(n_inputs), ctypes.byref(v)),
+               "gpuos_define_program")
+        return v.value
+
+    def register_table(self, table, programs=None):
+        """Bind every logical op of `table`.  programs: impl id -> (code, n_inputs) for the table's
+        program entries; they are defined first, in id order, and must receive those ids."""
+        for impl in sorted(programs or {}):
+            code, nin = programs[impl]
+            got = self.define_program(code, nin)
+            if got != impl:
+                raise ValueError("program defined as impl %d, the table expects %d" % (got, impl))
         for op, impl in table.items():
             self.register_op(op, impl)
 

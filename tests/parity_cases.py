@@ -275,6 +275,56 @@ def row_operations():
     return b.stream("row_operations")
 
 
+def operator_programs():
+    """Operators defined as programs: an exactly rounded mix (bit-exact), a leaky-relu-like select by
+    max / min, a three-input fma chain, sqrt / abs / neg / div, and two with an exponential inside
+    (sigmoid, softplus-like) whose error bound is derived below.  Layouts: contiguous (several
+    chunks), row vector and per-row scalar operands, transposed inputs, stride-2 slices, mixed
+    dtypes, all float output dtypes."""
+    rng = np.random.default_rng(21)
+    b = Builder()
+    P = S.program
+    progs = {
+        210: (P(("MUL", 4, 0, 1), ("ADD", 4, 4, 3), ("SUB", 0, 4, 0)), 2),                      # x*y + alpha - x
+        211: (P(("IMM", 4, 0.0), ("MAX", 5, 0, 4), ("MIN", 6, 0, 4), ("MUL", 6, 6, 3), ("ADD", 0, 5, 6)), 1),   # leaky relu, slope alpha
+        212: (P(("MOV", 4, 2), ("FMA", 4, 0, 1), ("FMA", 4, 4, 3), ("NEG", 0, 4)), 3),          # -(fma(fma(x,y,z), alpha, ...)) chain
+        213: (P(("ABS", 4, 0), ("SQRT", 4, 4), ("IMM", 5, 1.0), ("ADD", 5, 5, 4), ("DIV", 0, 0, 5), ("RELU", 0, 0)), 1),   # relu(x / (1 + sqrt|x|))
+        214: (P(("NEG", 4, 0), ("EXP", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5), ("DIV", 0, 5, 4)), 1),   # sigmoid
+        215: (P(("SUB", 4, 0, 1), ("MUL", 4, 4, 3), ("EXP", 4, 4), ("MUL", 0, 4, 1)), 2),       # exp(alpha (x - y)) * y
+    }
+    impl_of = {op: b.define_program(op, code, nin) for op, (code, nin) in sorted(progs.items())}
+    codes = (S.F32, S.F16, S.BF16)
+    def T(shape, code, scale=2.0):
+        return b.pool(to_dtype((rng.standard_normal(shape) * scale).astype(np.float32), code))
+    n = 0
+    for code in codes:
+        dt = np_dtype(code)
+        ocode = codes[(code + 1) % 3]
+        for numel in (1000, 16384, 70001):
+            x, y, z = T(numel, code), T(numel, code), T(numel, code)
+            for op in (210, 211, 212, 213, 214, 215):
+                nin = progs[op][1]
+                o = b.pool(np.zeros(numel, np_dtype(ocode if op in (211, 214) else code)))
+                b.add("COPY", o, [x, y, z][:nin], op_id=op, alpha=0.3)
+        R_, C_ = 130, 264
+        m = T((R_, C_), code)
+        row, col = T(C_, code), b.pool(rng.standard_normal(R_).astype(np.float32))
+        mt = T((C_, R_ + 3), code)[:, :R_].T                 # unit stride along R
+        wide = T((R_, 2 * C_), code)
+        for op, ins in ((210, [m, np.broadcast_to(row, (R_, C_))]), (215, [m, np.broadcast_to(col[:, None], (R_, C_))]),
+                        (210, [mt, m]), (212, [mt, np.broadcast_to(row, (R_, C_)), wide[:, ::2]]),
+                        (214, [mt]), (213, [wide[:, 1::2]]), (211, [m[::2]])):
+            shape = ins[0].shape
+            o = b.pool(np.zeros(shape, dt if op != 215 else np.float32))
+            b.add("COPY", o, ins, op_id=op, alpha=-0.7)
+    s = b.stream("operator_programs")
+    # sigmoid: e = exp(-x) within 2 ulp (relative 2^-22); 1 + e inherits at most that (relative to a
+    # value >= 1, half an ulp more for the add); the division adds half an ulp: 3 ulp of fp32, and a
+    # 16-bit output format absorbs all of it but one step.  exp(alpha (x - y)) * y: 2 ulp then half.
+    s.info["program_ulp"] = {impl_of[214]: 4, impl_of[215]: 3}
+    return s
+
+
 def reductions():
     """SUM / MAX / MIN over the last dim: row lengths from 1 to 20000 (sub-wave rows, one workgroup
     per row, scalar fallback for odd lengths), all float dtypes, fp32 and same-dtype outputs,
@@ -355,6 +405,7 @@ CPU_CHECKED = {
     "broadcast_2d": broadcast_2d,
     "transposed_2d": transposed_2d,
     "reductions": reductions,
+    "operator_programs": operator_programs,
     "row_operations": row_operations,
     "int32": int32_ops,
     "config2_reduced": config2_reduced,

@@ -15,7 +15,7 @@ def _run_and_check(stream, capacity=0, **cfg):
     print("case", stream.name, "tasks", len(stream), flush=True)
     dp = DevicePools(stream)
     with R.Runtime(capacity, idle_exit_ms=20000, wait_timeout_ms=20000, **cfg) as rt:
-        rt.register_table(stream.table)
+        rt.register_table(stream.table, stream.programs)
         t0 = run_stream(stream, rt, dp)
         comps = rt.completions(t0, len(stream))
         assert rt.worker_alive()
@@ -75,6 +75,52 @@ def test_fused_row_operations():
     stats, _ = _run_and_check(C.row_operations())
     print(stats, flush=True)
     assert stats["max_red_ratio"] <= 1.0
+
+
+def test_operator_programs():
+    """Elementwise operators defined as programs, on contiguous / row-broadcast / transposed /
+    strided / mixed-dtype operands and several chunks: programs of exactly rounded instructions are
+    bit-exact, the ones with an exponential inside stay within the bound the test derives."""
+    stats, _ = _run_and_check(C.operator_programs())
+    print(stats, flush=True)
+
+
+def test_program_swapped_in_while_the_worker_runs():
+    """The paper's injection flow without stopping the kernel: tasks of a logical operator are in
+    flight under its built-in implementation; a program is defined and swapped in; later tasks
+    record the new version and their results are the program's."""
+    from gpu_helpers import DevicePools, compare_with_oracle
+    s = S.config1(n_tasks=3000, numel=4096, seed=9)
+    dp = DevicePools(s)
+    code = S.program(("ADD", 4, 0, 1), ("MUL", 0, 4, 4), ("IMM", 5, 0.5), ("SUB", 0, 0, 5))     # (x + y)^2 - 0.5
+    with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
+        rt.register_table(s.table)
+        rt.submit(dp.tasks, 0, 1000)
+        impl = rt.define_program(code, 2)                 # while the first thousand are running
+        assert impl == S.PROGRAM_BASE
+        rt.submit(dp.tasks, 1000, 1000)
+        v = rt.swap_op(S.OP["ADD"], impl)
+        assert v == 2
+        rt.submit(dp.tasks, 2000, 1000)
+        rt.wait()
+        comps = rt.completions(0, 3000)
+        with pytest.raises(R.GpuosError):                 # a unary built-in cannot replace a binary operator ...
+            rt.swap_op(S.OP["ADD"], S.IMPL["RELU"])
+        with pytest.raises(R.GpuosError):                 # ... nor can a program that was never defined
+            rt.swap_op(S.OP["ADD"], impl + 1)
+        with pytest.raises(R.GpuosError):
+            rt.define_program(code[:0], 2)
+    assert np.all(comps["status"] == 0)
+    ver = comps["op_version"]
+    assert np.all(ver[:1000] == 1) and np.all(ver[2000:] == 2) and set(np.unique(ver[1000:2000])) <= {1, 2}
+    s.swaps = [(2000, S.OP["ADD"], impl)]
+    s.programs = {impl: (code, 2)}
+    stats = compare_with_oracle(s, dp.download(), versions=ver)
+    assert stats["max_ulp"] == 0
+    out = dp.download()[2].view(np.float32).reshape(3000, 4096)
+    a = dp.download()[0].view(np.float32).reshape(3000, 4096)
+    b = dp.download()[1].view(np.float32).reshape(3000, 4096)
+    assert np.array_equal(out[2500], (a[2500] + b[2500]) ** 2 - np.float32(0.5))
 
 
 def test_last_dim_reductions():

@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
+from paper_2604_17861_amd import streams as S
 import parity_cases as C
 from helpers import HostPools
 
@@ -14,10 +15,14 @@ def test_case_is_in_bounds_and_valid(name):
     assert C.stream_extent_violations(s) == []
     hp = HostPools(s)
     impl = s.impl_for()
-    bad = [i for i in range(len(s)) if oracle.validate(hp.tasks, i, impl[i]) != 0]
+    stand_in = {1: S.IMPL["RELU"], 2: S.IMPL["DIV"], 3: S.IMPL["FMA"]}      # a program validates like a float built-in of its arity
+    def check(i):
+        k = int(impl[i])
+        return oracle.validate(hp.tasks, i, stand_in[s.programs[k][1]] if k in s.programs else k)
+    bad = [i for i in range(len(s)) if check(i) != 0]
     assert bad == []
     if name not in ("config3_reduced", "config3_fused_reduced", "config5_reduced"):      # these take long on the CPU; the GPU suite runs them
-        st = oracle.run_stream(hp.tasks, impl)
+        st = oracle.run_stream(hp.tasks, impl, programs=s.programs)
         assert np.all(st == 0)
 
 
