@@ -1,0 +1,169 @@
+// CPU-only test of the host side of the queue protocol against the device stand-in
+// (device_standin.cpp), meant to be built with -fsanitize=thread.  Prints one line per check and
+// exits non-zero on the first failure.
+#include <atomic>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "../../include/gpuos.h"
+
+extern "C" uint64_t standin_errors();
+extern "C" uint64_t standin_records();
+
+#define CHECK(cond) do { if (!(cond)) { std::printf("FAILED %s:%d: %s\n", __FILE__, __LINE__, #cond); std::exit(1); } } while (0)
+
+static gpuos_task add_task(uint16_t op, uint32_t numel, uint16_t dep = 0) {
+  gpuos_task t;
+  std::memset(&t, 0, sizeof(t));
+  t.op_id = op; t.ndim = 1; t.n_inputs = 2; t.size[0] = numel;
+  for (int k = 0; k < 2; ++k) { t.in[k].ptr = (void*)(uintptr_t)(0x100000 * (k + 1)); t.in[k].stride[0] = 1; t.in[k].dtype = GPUOS_F32; }
+  t.out.ptr = (void*)(uintptr_t)0x900000; t.out.stride[0] = 1; t.out.dtype = GPUOS_F32;
+  t.dep[0] = dep;
+  return t;
+}
+
+static gpuos_ctx* make(uint32_t cap, bool nonblocking = false, bool harvester = false) {
+  gpuos_config cfg;
+  gpuos_default_config(&cfg);
+  cfg.nonblocking_submit = nonblocking;
+  cfg.harvester_thread = harvester;
+  cfg.wait_timeout_ms = 20000;
+  gpuos_ctx* c = nullptr;
+  CHECK(gpuos_init(&c, cap, &cfg) == GPUOS_OK);
+  CHECK(gpuos_register_op(c, 7, GPUOS_IMPL_ADD, nullptr) == GPUOS_OK);
+  CHECK(gpuos_register_op(c, 9, GPUOS_IMPL_MUL, nullptr) == GPUOS_OK);
+  return c;
+}
+
+int main() {
+  // 1. many producers, tiny rings: every ticket exactly once, consecutive inside a call, in-order log
+  for (uint32_t cap : {2u, 8u, 64u}) {
+    for (int harv = 0; harv < 2; ++harv) {
+      gpuos_ctx* c = make(cap, false, harv != 0);
+      const int n_threads = 6, per_thread = 3000;
+      std::vector<std::vector<uint64_t>> firsts(n_threads);
+      std::vector<std::thread> th;
+      std::atomic<int> failures{0};
+      for (int k = 0; k < n_threads; ++k)
+        th.emplace_back([&, k] {
+          unsigned s = 17u * (unsigned)k + 1u;
+          int left = per_thread;
+          while (left > 0) {
+            s = s * 1664525u + 1013904223u;
+            int m = 1 + (int)((s >> 16) % 5u);
+            if (m > left) m = left;
+            gpuos_task batch[5];
+            for (int i = 0; i < m; ++i) batch[i] = add_task(k % 2 ? 7 : 9, 1000 + (uint32_t)i, i > 0 ? 1 : 0);   // chain inside the call
+            uint64_t first = ~0ull;
+            if (gpuos_submit(c, batch, (uint32_t)m, &first) != GPUOS_OK) { failures++; return; }
+            for (int i = 0; i < m; ++i) firsts[k].push_back(first + (uint64_t)i);
+            if ((s >> 8) % 7u == 0 && gpuos_wait(c, first + (uint64_t)m - 1, 0) != GPUOS_OK) { failures++; return; }
+            if ((s >> 8) % 11u == 0) gpuos_flush(c);
+            left -= m;
+          }
+        });
+      for (auto& t : th) t.join();
+      CHECK(failures.load() == 0);
+      CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+      const uint64_t total = (uint64_t)n_threads * per_thread;
+      std::vector<int> seen(total, 0);
+      for (auto& v : firsts) for (uint64_t t : v) { CHECK(t < total); seen[t]++; }
+      for (uint64_t t = 0; t < total; ++t) CHECK(seen[t] == 1);
+      std::vector<gpuos_completion> comp(total);
+      CHECK(gpuos_get_completions(c, 0, (uint32_t)total, comp.data()) == GPUOS_OK);
+      for (uint64_t t = 0; t < total; ++t) {
+        CHECK(comp[t].ticket == t && comp[t].status == 0 && comp[t].op_version == 1);
+        CHECK(comp[t].t_done_ns >= comp[t].t_submit_ns);
+      }
+      gpuos_queue_state q;
+      CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK);
+      CHECK(q.head_submitted == total && q.tail_published == total && q.claimed == total && q.completed == total);
+      CHECK(gpuos_worker_alive(c) == 1);
+      CHECK(gpuos_shutdown(c) == GPUOS_OK);
+      std::printf("ok: %d producers x %d tasks, capacity %u, harvester thread %d\n", n_threads, per_thread, cap, harv);
+    }
+  }
+  // 2. a full ring in non-blocking mode: E_FULL and nothing enqueued; a dependency that reaches
+  //    before the first ticket or beyond the ring is rejected
+  {
+    gpuos_ctx* c = make(4, true);
+    gpuos_task five[5];
+    for (int i = 0; i < 5; ++i) five[i] = add_task(7, 64);
+    uint64_t first = 0;
+    CHECK(gpuos_submit(c, five, 5, &first) == GPUOS_E_FULL);
+    gpuos_queue_state q;
+    CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK && q.head_submitted == 0);
+    gpuos_task bad = add_task(7, 64, 1);
+    CHECK(gpuos_submit(c, &bad, 1, nullptr) == GPUOS_E_INVAL);          // ticket 0 has nothing before it
+    CHECK(gpuos_submit(c, five, 4, &first) == GPUOS_OK && first == 0);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+    bad = add_task(7, 64, 4);
+    CHECK(gpuos_submit(c, &bad, 1, nullptr) == GPUOS_E_INVAL);          // back-distance >= capacity
+    bad = add_task(200, 64);
+    CHECK(gpuos_submit(c, &bad, 1, nullptr) == GPUOS_E_BADOP);          // never registered
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: non-blocking ring, dependency and op-id checks\n");
+  }
+  // 3. swaps while producers run: versions never go back in ticket order, the kill switch shows,
+  //    a swap returns only versions that later tasks observe
+  {
+    gpuos_ctx* c = make(16);
+    std::atomic<bool> stop{false};
+    std::atomic<uint64_t> after_swap_first{0};
+    std::thread prod([&] {
+      gpuos_task t = add_task(7, 128);
+      while (!stop.load()) CHECK(gpuos_submit(c, &t, 1, nullptr) == GPUOS_OK);
+    });
+    uint32_t v = 0;
+    for (int i = 0; i < 40; ++i) {
+      CHECK(gpuos_swap_op(c, 7, i % 2 ? GPUOS_IMPL_ADD : GPUOS_IMPL_SUB, &v) == GPUOS_OK);
+      CHECK(v == (uint32_t)i + 2);
+    }
+    CHECK(gpuos_swap_op(c, 7, GPUOS_IMPL_RELU, &v) == GPUOS_E_INVAL);   // arity differs
+    stop.store(true);
+    prod.join();
+    gpuos_task t = add_task(7, 128);
+    uint64_t tk = 0;
+    CHECK(gpuos_submit(c, &t, 1, &tk) == GPUOS_OK);
+    CHECK(gpuos_wait(c, tk, 0) == GPUOS_OK);
+    std::vector<gpuos_completion> comp(tk + 1);
+    // the log holds at least the last 2^20 tickets
+    const uint64_t lo = tk + 1 > (1u << 20) ? tk + 1 - (1u << 20) : 0;
+    CHECK(gpuos_get_completions(c, lo, (uint32_t)(tk + 1 - lo), comp.data()) == GPUOS_OK);
+    for (uint64_t i = 1; i + lo <= tk; ++i) CHECK(comp[i].op_version >= comp[i - 1].op_version);
+    CHECK(comp[tk - lo].op_version == 41);
+    CHECK(gpuos_kill_op(c, 7, &v) == GPUOS_OK && v == 42);
+    CHECK(gpuos_submit(c, &t, 1, &tk) == GPUOS_OK);
+    CHECK(gpuos_wait(c, tk, 0) == GPUOS_E_BADOP);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_E_BADOP);                // first error, reported once
+    CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: 40 swaps under load, kill switch\n");
+  }
+  // 4. shutdown with tasks in flight drains them; use after stop is refused; programs are table entries
+  {
+    gpuos_ctx* c = make(32);
+    gpuos_instr code[2] = {{GPUOS_PC_ADD, 0, 0, 1, 0.f}, {GPUOS_PC_MUL, 0, 0, 3, 0.f}};
+    uint32_t impl = 0;
+    CHECK(gpuos_define_program(c, code, 2, 2, &impl) == GPUOS_OK && impl == GPUOS_IMPL_PROGRAM_BASE);
+    CHECK(gpuos_register_op(c, 30, impl, nullptr) == GPUOS_OK);
+    CHECK(gpuos_register_op(c, 31, impl + 1, nullptr) == GPUOS_E_BADOP);
+    code[1].a = 9;
+    CHECK(gpuos_define_program(c, code, 2, 2, &impl) == GPUOS_E_INVAL);
+    std::vector<gpuos_task> many(500, add_task(30, 4096));
+    CHECK(gpuos_submit(c, many.data(), 500, nullptr) == GPUOS_OK);
+    CHECK(gpuos_stop_worker(c) == GPUOS_OK);
+    gpuos_queue_state q;
+    CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK && q.completed == 500);
+    CHECK(gpuos_submit(c, many.data(), 1, nullptr) == GPUOS_E_DEAD);
+    CHECK(gpuos_worker_alive(c) == 0);
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: shutdown drains, use after stop refused, program ids\n");
+  }
+  CHECK(standin_errors() == 0);
+  std::printf("all ok: %llu records through the stand-in, 0 protocol errors\n", (unsigned long long)standin_records());
+  return 0;
+}
