@@ -170,6 +170,13 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
     numel *= size[d];
     if (numel > kMaxExtent) return GPUOS_E_INVAL;
   }
+  // Chunk size: chunk_elems (about 192 KiB of traffic) streams best for the largest tensors; tasks
+  // of up to a million elements are split twice as finely, which shortens the critical path of
+  // dependent chains of mid-sized operations (more workgroups per task) at no cost in bandwidth.
+  // The same goes for a link of a chain (a task that waits for one of the few tickets right before
+  // it): its successor waits for its slowest chunk, so the tail of every task is on the critical path.
+  const bool chained = (t.dep[0] >= 1 && t.dep[0] <= 8) || (t.dep[1] >= 1 && t.dep[1] <= 8) || (t.dep[2] >= 1 && t.dep[2] <= 8);
+  if ((numel <= (1 << 20) || chained) && chunk_elems >= 2048) chunk_elems /= 2;
   const bool red = impl_is_reduction(impl);
   const int nd_out = red ? t.ndim - 1 : t.ndim;
   Operand ops[4];                                   // inputs 0..ar-1, then the output
