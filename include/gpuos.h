@@ -31,7 +31,14 @@
  *   - while a context is alive the worker kernel is resident on its own
  *     non-blocking stream: the caller must not call hipDeviceSynchronize(),
  *     hipFree() or anything else that waits for "all streams" before
- *     gpuos_shutdown(), or the process deadlocks.
+ *     gpuos_shutdown(), or the process deadlocks.  The worker also occupies
+ *     one of the process's hardware queues for good: work that the HIP runtime
+ *     places on that queue waits until the worker exits.  Seen on MI355X with
+ *     4 hardware queues: device<->host copies of 16 KiB or less (done by a copy
+ *     kernel; larger ones go to the DMA engines and run alongside), on the
+ *     default stream and on a freshly created one.  Move small results with a
+ *     GPUOS_IMPL_COPY task into pinned, device-mapped host memory instead, or
+ *     read them after gpuos_stop_worker().
  */
 #ifndef GPUOS_H_
 #define GPUOS_H_
