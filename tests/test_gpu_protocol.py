@@ -409,3 +409,31 @@ def test_many_producer_threads_on_one_context():
         for img in dp.tensors[-1:]:
             img.zero_()                           # outputs start from zero again for the next capacity
         torch.cuda.synchronize()                  # no context is alive here: waiting for every stream is safe
+
+
+def test_small_results_reach_the_host_through_a_copy_task_into_pinned_memory():
+    """While the worker is resident a small device-to-host copy may queue behind it; the way to
+    read a small result is a COPY task whose output is pinned (device-mapped) host memory: it is
+    complete, and visible to the host, when gpuos_wait returns."""
+    n = 1000
+    src = torch.arange(n, dtype=torch.float32, device="cuda:0") * 0.5
+    torch.cuda.current_stream().synchronize()
+    dst = torch.zeros(n, dtype=torch.float32).pin_memory()
+    tasks, pool_of = S.new_tasks(2)
+    S.set_head(tasks, 0, S.OP["COPY"], [n], 1)
+    S.set_tensor(tasks, pool_of, 0, 0, 0, src.data_ptr(), [1], S.F32)
+    S.set_tensor(tasks, pool_of, 0, 3, 0, dst.data_ptr(), [1], S.F32)
+    S.set_head(tasks, 1, S.OP["SCALE"], [n // 2], 1, alpha=-2.0, dep=(1, 0, 0))          # host memory as an INPUT as well
+    S.set_tensor(tasks, pool_of, 1, 0, 0, dst.data_ptr(), [2], S.F32)
+    S.set_tensor(tasks, pool_of, 1, 3, 0, dst.data_ptr() + 4, [2], S.F32)
+    with R.Runtime(0, **CFG) as rt:
+        rt.register_table(S.default_table())
+        t = rt.submit(tasks, 0, 1)
+        rt.wait(t)
+        assert rt.worker_alive()
+        assert np.array_equal(dst.numpy(), np.arange(n, dtype=np.float32) * 0.5)      # read while the worker runs
+        t = rt.submit(tasks, 1, 1)
+        rt.wait(t)
+        want = np.arange(n, dtype=np.float32) * 0.5
+        want[1::2] = want[0::2] * np.float32(-2.0)
+        assert np.array_equal(dst.numpy(), want)
