@@ -1137,6 +1137,178 @@ PATHFN void rowop_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
   }
 }
 
+// Rows longer than one wavefront's registers: the whole workgroup owns a row.  KW = 1..4: the row
+// (up to 1024 vectors) lives in registers, 256 lanes x KW vectors, read once and written once.
+// KW = 0: any length, three streaming passes of 16-byte vector loads over the row (the second and
+// third pass re-read what the first brought into the caches).  Cross-wavefront reductions go
+// through four rotating LDS slots: one barrier per reduction.
+template <int POL, int ROP, int DT, int KW>
+DEV void rowop_wg(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_red) {
+  using E = Elem<DT>;
+  using M = Mem<POL>;
+  using RO = RowOp<ROP>;
+  constexpr uint32_t V = E::V;
+  constexpr int KR = KW > 0 ? KW : 1;
+  const uint32_t n = uni(r->red_n), vpr = n / V;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const float alpha = r->alpha;
+  const uint32_t nrows = row_end - row_begin;
+  const uint32_t chunk_bytes = nrows * n * E::ES;
+  const uint64_t chunk_off = (uint64_t)row_begin * n * E::ES;
+  const rsrc_t rx = make_rsrc(uni_ptr(r->ptr[0]) + chunk_off, chunk_bytes);
+  const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + chunk_off, chunk_bytes);
+  rsrc_t rs[2];
+  uint32_t period[2] = {0, 0};
+#pragma unroll
+  for (int k = 1; k < RO::NIN; ++k) {
+    if (uni(r->okind[k]) == K_FULL) {
+      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]) + chunk_off, chunk_bytes);
+    } else {
+      period[k - 1] = uni(r->stride[k][0]);
+      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), period[k - 1] * n * E::ES);
+    }
+  }
+  uint32_t turn = 0;                                   // which of the four LDS slots the next reduction uses
+  auto wg_sum = [&](float v) {
+    v = bfly_sum(v, 64);
+    float* slot = s_red + (turn & 3u) * 4u;
+    ++turn;
+    if (lane == 0) slot[wave] = v;
+    __syncthreads();
+    return (slot[0] + slot[1]) + (slot[2] + slot[3]);
+  };
+  auto wg_max = [&](float v) {
+    v = bfly_max(v, 64);
+    float* slot = s_red + (turn & 3u) * 4u;
+    ++turn;
+    if (lane == 0) slot[wave] = v;
+    __syncthreads();
+    return __builtin_fmaxf(__builtin_fmaxf(slot[0], slot[1]), __builtin_fmaxf(slot[2], slot[3]));
+  };
+  // the argument of element e of vector `vec` of local row lr (softmax family) / the element itself
+  auto arg = [&](const v4i& q, const v4i& mq, int e) {
+    float x = E::get(q, e);
+    if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) x = alpha * x + E::get(mq, e);
+    return x;
+  };
+  v4i gq[KR], bq[KR];                                  // layer norm, KW > 0: this lane's gamma / beta pieces
+  if (!RO::SOFTMAX && KW > 0) {
+#pragma unroll
+    for (int k = 0; k < KR; ++k) {
+      gq[k] = M::ld16(rs[0], (tid + kThreads * k) * 16u);
+      bq[k] = M::ld16(rs[1], (tid + kThreads * k) * 16u);
+    }
+  }
+  for (uint32_t row = row_begin; row < row_end; ++row) {
+    const uint32_t lr = row - row_begin;
+    uint32_t mr = lr;
+    if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST && period[0]) mr = row % period[0];
+    if (KW > 0) {
+      v4i q[KR], mq[KR];
+      bool act[KR];
+#pragma unroll
+      for (int k = 0; k < KR; ++k) {
+        const uint32_t vec = tid + kThreads * k;
+        act[k] = vec < vpr;
+        q[k] = M::ld16(rx, act[k] ? (lr * vpr + vec) * 16u : kNoLoad);
+        if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) mq[k] = M::ld16(rs[0], act[k] ? (mr * vpr + vec) * 16u : kNoLoad);
+      }
+      float t[KR][V];
+      if (RO::SOFTMAX) {
+        float m = -__builtin_inff();
+#pragma unroll
+        for (int k = 0; k < KR; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[k] ? arg(q[k], mq[k], e) : -__builtin_inff(); m = __builtin_fmaxf(m, t[k][e]); }
+        m = wg_max(m);
+        float sum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KR; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) { t[k][e] = __expf(t[k][e] - m); sum += t[k][e]; }
+        const float inv = 1.0f / wg_sum(sum);
+#pragma unroll
+        for (int k = 0; k < KR; ++k) {
+          v4i oq;
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * inv);
+          if (act[k]) M::st16(ro, (lr * vpr + tid + kThreads * k) * 16u, oq);
+        }
+      } else {
+        float sum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KR; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[k] ? E::get(q[k], e) : 0.0f; sum += t[k][e]; }
+        const float mean = wg_sum(sum) / (float)n;
+        float ss = 0.0f;
+#pragma unroll
+        for (int k = 0; k < KR; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[k] ? t[k][e] - mean : 0.0f; ss += t[k][e] * t[k][e]; }
+        const float rstd = 1.0f / __builtin_sqrtf(wg_sum(ss) / (float)n + alpha);
+#pragma unroll
+        for (int k = 0; k < KR; ++k) {
+          v4i oq;
+#pragma unroll
+          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * E::get(gq[k], e) + E::get(bq[k], e));
+          if (act[k]) M::st16(ro, (lr * vpr + tid + kThreads * k) * 16u, oq);
+        }
+      }
+    } else if (RO::SOFTMAX) {
+      const v4i zero = {0, 0, 0, 0};
+      float m = -__builtin_inff();
+      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
+        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
+        const v4i mq = ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? M::ld16(rs[0], (mr * vpr + vec) * 16u) : zero;
+#pragma unroll
+        for (int e = 0; e < (int)V; ++e) m = __builtin_fmaxf(m, arg(q, mq, e));
+      }
+      m = wg_max(m);
+      float sum = 0.0f;
+      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
+        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
+        const v4i mq = ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? M::ld16(rs[0], (mr * vpr + vec) * 16u) : zero;
+#pragma unroll
+        for (int e = 0; e < (int)V; ++e) sum += __expf(arg(q, mq, e) - m);
+      }
+      const float inv = 1.0f / wg_sum(sum);
+      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
+        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
+        const v4i mq = ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? M::ld16(rs[0], (mr * vpr + vec) * 16u) : zero;
+        v4i oq;
+#pragma unroll
+        for (int e = 0; e < (int)V; ++e) E::put(oq, e, __expf(arg(q, mq, e) - m) * inv);
+        M::st16(ro, (lr * vpr + vec) * 16u, oq);
+      }
+    } else {
+      float sum = 0.0f;
+      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
+        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
+#pragma unroll
+        for (int e = 0; e < (int)V; ++e) sum += E::get(q, e);
+      }
+      const float mean = wg_sum(sum) / (float)n;
+      float ss = 0.0f;
+      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
+        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
+#pragma unroll
+        for (int e = 0; e < (int)V; ++e) { const float d = E::get(q, e) - mean; ss += d * d; }
+      }
+      const float rstd = 1.0f / __builtin_sqrtf(wg_sum(ss) / (float)n + alpha);
+      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
+        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
+        const v4i g = M::ld16(rs[0], vec * 16u), b = M::ld16(rs[1], vec * 16u);
+        v4i oq;
+#pragma unroll
+        for (int e = 0; e < (int)V; ++e) E::put(oq, e, (E::get(q, e) - mean) * rstd * E::get(g, e) + E::get(b, e));
+        M::st16(ro, (lr * vpr + vec) * 16u, oq);
+      }
+    }
+  }
+  __syncthreads();                                     // the LDS slots belong to the next chunk after this
+}
+
 template <int POL, int ROP, int DT>
 PATHFN void rowop_fused_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
   const Record* r = lds_arg(r_v);
@@ -1147,16 +1319,34 @@ PATHFN void rowop_fused_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v) 
   else rowop_fused<POL, ROP, DT, 4, 1>(r, begin, end);
 }
 
+template <int POL, int ROP, int DT>
+PATHFN void rowop_wg_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
+  const Record* r = lds_arg(r_v);
+  float* s_red = lds_arg(s_v);
+  const uint32_t begin = uni(begin_v), end = uni(end_v);
+  const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
+  if (vpr <= 512u) rowop_wg<POL, ROP, DT, 2>(r, begin, end, s_red);
+  else if (vpr <= 1024u) rowop_wg<POL, ROP, DT, 4>(r, begin, end, s_red);
+  else rowop_wg<POL, ROP, DT, 0>(r, begin, end, s_red);
+}
+
 template <int POL, int ROP>
-DEV void run_rowop(const Record* r, uint32_t chunk) {
+DEV void run_rowop(const Record* r, uint32_t chunk, float* s_red) {
   const uint32_t per = uni(r->chunk), rows = uni(r->numel);
   const uint32_t begin = chunk * per;
   const uint32_t end = (rows - begin < per) ? rows : begin + per;
   if (uni(r->path) == PATH_ROW_FUSED) {
     const uint32_t dt = uni(r->dtype[3]);
-    if (dt == GPUOS_F32) rowop_fused_dt<POL, ROP, GPUOS_F32>(r, begin, end);
-    else if (dt == GPUOS_F16) rowop_fused_dt<POL, ROP, GPUOS_F16>(r, begin, end);
-    else rowop_fused_dt<POL, ROP, GPUOS_BF16>(r, begin, end);
+    const bool wide = uni(r->red_n) * (dt == GPUOS_F32 ? 4u : 2u) > 256u * 16u;     // more than 256 vectors per row
+    if (!wide) {
+      if (dt == GPUOS_F32) rowop_fused_dt<POL, ROP, GPUOS_F32>(r, begin, end);
+      else if (dt == GPUOS_F16) rowop_fused_dt<POL, ROP, GPUOS_F16>(r, begin, end);
+      else rowop_fused_dt<POL, ROP, GPUOS_BF16>(r, begin, end);
+    } else {
+      if (dt == GPUOS_F32) rowop_wg_dt<POL, ROP, GPUOS_F32>(r, begin, end, s_red);
+      else if (dt == GPUOS_F16) rowop_wg_dt<POL, ROP, GPUOS_F16>(r, begin, end, s_red);
+      else rowop_wg_dt<POL, ROP, GPUOS_BF16>(r, begin, end, s_red);
+    }
   } else {
     rowop_generic<POL, ROP>(r, begin, end);
   }
@@ -1254,9 +1444,9 @@ DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_
     case GPUOS_IMPL_SUM_LAST: run_reduction<POL, GPUOS_IMPL_SUM_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_MAX_LAST: run_reduction<POL, GPUOS_IMPL_MAX_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_MIN_LAST: run_reduction<POL, GPUOS_IMPL_MIN_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_SOFTMAX_LAST>(r, chunk); break;
-    case GPUOS_IMPL_MASKED_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_MASKED_SOFTMAX_LAST>(r, chunk); break;
-    case GPUOS_IMPL_LAYERNORM_LAST: run_rowop<POL, GPUOS_IMPL_LAYERNORM_LAST>(r, chunk); break;
+    case GPUOS_IMPL_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_SOFTMAX_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_MASKED_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_MASKED_SOFTMAX_LAST>(r, chunk, s_red); break;
+    case GPUOS_IMPL_LAYERNORM_LAST: run_rowop<POL, GPUOS_IMPL_LAYERNORM_LAST>(r, chunk, s_red); break;
     case GPUOS_IMPL_FAIL: return GPUOS_E_BADOP;       // kill-switch stub: fail fast, write nothing
     default: return GPUOS_E_BADOP;
   }

@@ -229,8 +229,8 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
     rec.red_n = (uint32_t)n;
     rec.numel = (uint32_t)rows;
     rec.path = PATH_ROW_GENERIC;
-    // rows in registers: one dtype, unit stride along the row, whole aligned vectors, at most
-    // 256 vectors per row; x and the output contiguous; further inputs contiguous [period, n]
+    // vector path (rows in registers up to 1024 vectors, streamed beyond): one dtype, unit stride
+    // along the row, whole aligned vectors; x and the output contiguous; further inputs contiguous [period, n]
     // blocks that repeat every `period` rows (period = rows: same layout as x; 1: a row vector)
     const uint32_t es = dtype_size(ops[ar].dtype);
     const uint32_t V = 16u / es;
@@ -242,7 +242,7 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
       }
       return true;
     };
-    bool fast = same_dt && n % V == 0 && n / V <= 256;
+    bool fast = same_dt && n % V == 0 && n * (int64_t)es < kMaxExtent;
     for (int k = 0; k <= ar && fast; ++k) fast = s_last[k] == 1 && aligned16(ops[k].ptr);
     fast = fast && (rows == 1 || (dense_rows(oo[0], 0) && dense_rows(oo[ar], 0)));
     uint32_t period[3] = {0, 0, 0};

@@ -204,8 +204,9 @@ def transposed_2d():
 
 def row_operations():
     """Softmax, scaled + masked softmax and layer norm over the last dim: rows in registers (row
-    lengths from one vector to 256 vectors, sub-wave and whole-wave ownership, several chunks and
-    ragged last chunks) and the generic path (odd lengths, strided rows, mixed dtypes, long rows);
+    lengths from one vector to 1024 vectors: sub-wave, whole-wave and whole-workgroup ownership,
+    several chunks and ragged last chunks), streamed rows beyond that, and the generic path (odd
+    lengths, strided rows, mixed dtypes);
     masks laid out like x, repeated every S rows, or one row; special values."""
     rng = np.random.default_rng(12)
     b = Builder()
@@ -213,7 +214,8 @@ def row_operations():
         V = 4 if code == S.F32 else 8
         dt = np_dtype(code)
         for rows, n in ((1, V), (7, 8 * V), (300, 24 * V), (1000, 64 * V), (130, 65 * V), (90, 128 * V),
-                        (50, 200 * V), (40, 256 * V), (12, 257 * V), (33, 5), (65, 1001), (3, 20000)):
+                        (50, 200 * V), (40, 256 * V), (12, 257 * V), (9, 512 * V), (7, 1000 * V), (5, 1024 * V),
+                        (3, 1500 * V), (2, 4096 * V), (33, 5), (65, 1001), (3, 20000)):
             x = b.pool(to_dtype((rng.standard_normal((rows, n)) * 3).astype(np.float32), code))
             o1, o2, o3 = (b.pool(np.zeros((rows, n), dt)) for _ in range(3))
             b.add("SOFTMAX_LAST", o1, [x])

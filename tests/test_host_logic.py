@@ -153,7 +153,7 @@ def test_task_plan_for_row_operations():
     b.add("MASKED_SOFTMAX_LAST", f(2, 3, 64, 64), [x, np.broadcast_to(f(2, 1, 64, 64), (2, 3, 64, 64))])  # 4 mask skips a middle dim
     b.add("LAYERNORM_LAST", f(50, 1024), [f(50, 1024), np.broadcast_to(f(1024), (50, 1024)), np.broadcast_to(f(1024), (50, 1024))])  # 5
     b.add("LAYERNORM_LAST", f(50, 1024), [f(50, 1024), f(50, 1024), np.broadcast_to(f(1024), (50, 1024))])   # 6 per-element gamma
-    b.add("SOFTMAX_LAST", f(10, 1028), [f(10, 1028)])                                        # 7 257 vectors
+    b.add("SOFTMAX_LAST", f(10, 1028), [f(10, 1028)])                                        # 7 257 vectors: a workgroup per row
     b.add("SOFTMAX_LAST", f(10, 30), [f(10, 30)])                                            # 8 not whole vectors
     b.add("SOFTMAX_LAST", f(10, 32), [h(10, 32)])                                            # 9 mixed dtypes
     b.add("SOFTMAX_LAST", f(10, 32), [f(10, 64)[:, ::2]])                                    # 10 strided
@@ -164,7 +164,7 @@ def test_task_plan_for_row_operations():
     hp = HostPools(s)
     impl = s.impl_for()
     got = [R.task_plan(hp.tasks, i, impl[i]) for i in range(len(s))]
-    want = ["ROW_FUSED"] * 4 + ["ROW_GENERIC", "ROW_FUSED", "ROW_GENERIC", "ROW_GENERIC", "ROW_GENERIC", "ROW_GENERIC",
+    want = ["ROW_FUSED"] * 4 + ["ROW_GENERIC", "ROW_FUSED", "ROW_GENERIC", "ROW_FUSED", "ROW_GENERIC", "ROW_GENERIC",
                                 "ROW_GENERIC", "ROW_GENERIC", "ROW_FUSED", "ROW_FUSED"]
     assert [g[0] for g in got] == want, [g[0] for g in got]
     rows = 2 * 3 * 64
