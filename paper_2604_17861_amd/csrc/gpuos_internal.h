@@ -75,12 +75,31 @@ struct alignas(16) Record {
                              // the period (rows) of a K_PERIODIC input
   uint32_t t_dequeue[2];     // device clock when the dispatcher took the task (lo, hi)  (dispatcher)
   uint32_t pad2[7];
-  uint32_t check;            // xor of the 63 words above ^ record_check_seed(ticket): set by the host
+  uint32_t check;            // makes record_check_sum() of the record equal record_check_seed(ticket);
+                             // set by the host, with the ticket field zero
 };
 static_assert(sizeof(Record) == 256, "ring record must be 256 bytes");
 
-// The value the xor of all 64 words of an intact record of `ticket` gives (check included).
-GPUOS_HD inline uint32_t record_check_seed(uint64_t ticket) { return 0x9E3779B9u ^ (uint32_t)ticket ^ (uint32_t)(ticket >> 32); }
+// Check word of a ring record.  With write-combined stores from several producer threads the
+// pieces of a record reach device memory in any order, so the dispatcher may read any mixture
+// of the record a slot held on the previous lap and the one being written.  The check is a
+// weighted sum of the 64 words (word k times an odd constant of its own; the check word itself
+// times 1) that must equal a seed derived from the ticket alone.  Position-dependent weights:
+// two stale pointers that moved by the same amount do not cancel (they do under a plain xor).
+// The ticket enters ONLY through the seed: the record's own ticket field is zero in the ring (the
+// dispatcher fills it in); were it among the summed words, the previous lap's contents and check
+// word would still verify under the new ticket word.
+GPUOS_HD inline uint32_t record_check_weight(uint32_t k) { return k == 63u ? 1u : (2u * k + 1u) * 0x9E3779B1u; }
+GPUOS_HD inline uint32_t record_check_seed(uint64_t ticket) {
+  const uint64_t m = (ticket + 0x9E3779B97F4A7C15ull) * 0xD6E8FEB86659FD93ull;
+  return (uint32_t)(m >> 32) ^ (uint32_t)m ^ 0x9E3779B9u;
+}
+// sum over words [0, n) of word * weight (n = 64: the value an intact record gives == its seed)
+GPUOS_HD inline uint32_t record_check_sum(const uint32_t* words, uint32_t n) {
+  uint32_t x = 0;
+  for (uint32_t k = 0; k < n; ++k) x += words[k] * record_check_weight(k);
+  return x;
+}
 
 // Completion word (8 bytes, one atomic store to host memory):
 //   bits 0..31  low half of ticket+1, bits 32..39 status (int8), bits 40..63 version

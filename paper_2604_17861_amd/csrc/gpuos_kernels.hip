@@ -960,7 +960,21 @@ template <int ROP> struct RowOp {
   static constexpr bool SOFTMAX = ROP != GPUOS_IMPL_LAYERNORM_LAST;
 };
 
-template <int POL, int ROP, int DT, int KW, int UP>
+// gamma / beta of a layer norm for the V elements of one vector position: of x's dtype (one
+// 16-byte vector), or fp32 under 16-bit x (P32: two vectors), as frameworks keep them.
+template <int POL, int DT, bool P32> struct RowParam {
+  v4i q[P32 ? 2 : 1];
+  DEV void load(rsrc_t rs, uint32_t vec) {
+    if (P32) { q[0] = Mem<POL>::ld16(rs, vec * 32u); q[P32 ? 1 : 0] = Mem<POL>::ld16(rs, vec * 32u + 16u); }
+    else q[0] = Mem<POL>::ld16(rs, vec * 16u);
+  }
+  DEV float get(int e) const {
+    if (P32) return Elem<GPUOS_F32>::get(q[(e >> 2) & (P32 ? 1 : 0)], e & 3);
+    return Elem<DT>::get(q[0], e);
+  }
+};
+
+template <int POL, int ROP, int DT, int KW, int UP, bool P32 = false>
 DEV void rowop_fused(const Record* r, uint32_t row_begin, uint32_t row_end) {
   using E = Elem<DT>;
   using M = Mem<POL>;
@@ -977,26 +991,29 @@ DEV void rowop_fused(const Record* r, uint32_t row_begin, uint32_t row_end) {
   const uint64_t chunk_off = (uint64_t)row_begin * n * E::ES;
   const rsrc_t rx = make_rsrc(uni_ptr(r->ptr[0]) + chunk_off, chunk_bytes);
   const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + chunk_off, chunk_bytes);
-  // second / third input: laid out like x (K_FULL) or a [period, n] block reused every period rows
+  // second / third input: laid out like x (K_FULL) or a [period, n] block reused every period rows;
+  // layer norm: gamma and beta are always one row
   rsrc_t rs[2];
   uint32_t period[2] = {0, 0};
 #pragma unroll
   for (int k = 1; k < RO::NIN; ++k) {
-    if (uni(r->okind[k]) == K_FULL) {
+    if (!RO::SOFTMAX) {
+      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), n * (P32 ? 4u : (uint32_t)E::ES));
+    } else if (uni(r->okind[k]) == K_FULL) {
       rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]) + chunk_off, chunk_bytes);
     } else {
       period[k - 1] = uni(r->stride[k][0]);
       rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), period[k - 1] * n * E::ES);
     }
   }
-  // layer norm: gamma and beta are row vectors (period 1): this lane's pieces are loaded once
-  v4i gq[KW], bq[KW];
+  // layer norm: this lane's pieces of gamma and beta are loaded once
+  RowParam<POL, DT, P32> gq[KW], bq[KW];
   if (!RO::SOFTMAX) {
 #pragma unroll
     for (int k = 0; k < KW; ++k) {
       const uint32_t vec = j + 64u * k;
-      gq[k] = M::ld16(rs[0], vec * 16u);             // past the row: reads zeros (bounds-checked), never used
-      bq[k] = M::ld16(rs[1], vec * 16u);
+      gq[k].load(rs[0], vec);                        // past the row: reads zeros (bounds-checked), never used
+      bq[k].load(rs[1], vec);
     }
   }
   for (uint32_t base = row_begin + wave * rpw * UP; base < row_end; base += 4u * rpw * UP) {
@@ -1064,7 +1081,7 @@ DEV void rowop_fused(const Record* r, uint32_t row_begin, uint32_t row_end) {
         for (int k = 0; k < KW; ++k) {
           v4i oq;
 #pragma unroll
-          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * E::get(gq[k], e) + E::get(bq[k], e));
+          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * gq[k].get(e) + bq[k].get(e));
           if (act[u][k]) M::st16(ro, (lr * vpr + j + 64u * k) * 16u, oq);
         }
       }
@@ -1142,7 +1159,7 @@ PATHFN void rowop_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
 // KW = 0: any length, three streaming passes of 16-byte vector loads over the row (the second and
 // third pass re-read what the first brought into the caches).  Cross-wavefront reductions go
 // through four rotating LDS slots: one barrier per reduction.
-template <int POL, int ROP, int DT, int KW>
+template <int POL, int ROP, int DT, int KW, bool P32 = false>
 DEV void rowop_wg(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_red) {
   using E = Elem<DT>;
   using M = Mem<POL>;
@@ -1161,7 +1178,9 @@ DEV void rowop_wg(const Record* r, uint32_t row_begin, uint32_t row_end, float* 
   uint32_t period[2] = {0, 0};
 #pragma unroll
   for (int k = 1; k < RO::NIN; ++k) {
-    if (uni(r->okind[k]) == K_FULL) {
+    if (!RO::SOFTMAX) {
+      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), n * (P32 ? 4u : (uint32_t)E::ES));      // gamma, beta: one row
+    } else if (uni(r->okind[k]) == K_FULL) {
       rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]) + chunk_off, chunk_bytes);
     } else {
       period[k - 1] = uni(r->stride[k][0]);
@@ -1191,12 +1210,12 @@ DEV void rowop_wg(const Record* r, uint32_t row_begin, uint32_t row_end, float* 
     if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) x = alpha * x + E::get(mq, e);
     return x;
   };
-  v4i gq[KR], bq[KR];                                  // layer norm, KW > 0: this lane's gamma / beta pieces
+  RowParam<POL, DT, P32> gq[KR], bq[KR];               // layer norm, KW > 0: this lane's gamma / beta pieces
   if (!RO::SOFTMAX && KW > 0) {
 #pragma unroll
     for (int k = 0; k < KR; ++k) {
-      gq[k] = M::ld16(rs[0], (tid + kThreads * k) * 16u);
-      bq[k] = M::ld16(rs[1], (tid + kThreads * k) * 16u);
+      gq[k].load(rs[0], tid + kThreads * k);
+      bq[k].load(rs[1], tid + kThreads * k);
     }
   }
   for (uint32_t row = row_begin; row < row_end; ++row) {
@@ -1251,7 +1270,7 @@ DEV void rowop_wg(const Record* r, uint32_t row_begin, uint32_t row_end, float* 
         for (int k = 0; k < KR; ++k) {
           v4i oq;
 #pragma unroll
-          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * E::get(gq[k], e) + E::get(bq[k], e));
+          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * gq[k].get(e) + bq[k].get(e));
           if (act[k]) M::st16(ro, (lr * vpr + tid + kThreads * k) * 16u, oq);
         }
       }
@@ -1298,10 +1317,12 @@ DEV void rowop_wg(const Record* r, uint32_t row_begin, uint32_t row_end, float* 
       const float rstd = 1.0f / __builtin_sqrtf(wg_sum(ss) / (float)n + alpha);
       for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
         const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
-        const v4i g = M::ld16(rs[0], vec * 16u), b = M::ld16(rs[1], vec * 16u);
+        RowParam<POL, DT, P32> g, b;
+        g.load(rs[0], vec);
+        b.load(rs[1], vec);
         v4i oq;
 #pragma unroll
-        for (int e = 0; e < (int)V; ++e) E::put(oq, e, (E::get(q, e) - mean) * rstd * E::get(g, e) + E::get(b, e));
+        for (int e = 0; e < (int)V; ++e) E::put(oq, e, (E::get(q, e) - mean) * rstd * g.get(e) + b.get(e));
         M::st16(ro, (lr * vpr + vec) * 16u, oq);
       }
     }
@@ -1314,6 +1335,13 @@ PATHFN void rowop_fused_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v) 
   const Record* r = lds_arg(r_v);
   const uint32_t begin = uni(begin_v), end = uni(end_v);
   const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
+  if (ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32 && uni(r->dtype[1]) == GPUOS_F32) {   // fp32 gamma / beta under 16-bit x
+    constexpr bool P = ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32;
+    if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 4, P>(r, begin, end);
+    else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 2, P>(r, begin, end);
+    else rowop_fused<POL, ROP, DT, 4, 1, P>(r, begin, end);
+    return;
+  }
   if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 4>(r, begin, end);
   else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 2>(r, begin, end);
   else rowop_fused<POL, ROP, DT, 4, 1>(r, begin, end);
@@ -1325,6 +1353,13 @@ PATHFN void rowop_wg_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v, flo
   float* s_red = lds_arg(s_v);
   const uint32_t begin = uni(begin_v), end = uni(end_v);
   const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
+  if (ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32 && uni(r->dtype[1]) == GPUOS_F32) {
+    constexpr bool P = ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32;
+    if (vpr <= 512u) rowop_wg<POL, ROP, DT, 2, P>(r, begin, end, s_red);
+    else if (vpr <= 1024u) rowop_wg<POL, ROP, DT, 4, P>(r, begin, end, s_red);
+    else rowop_wg<POL, ROP, DT, 0, P>(r, begin, end, s_red);
+    return;
+  }
   if (vpr <= 512u) rowop_wg<POL, ROP, DT, 2>(r, begin, end, s_red);
   else if (vpr <= 1024u) rowop_wg<POL, ROP, DT, 4>(r, begin, end, s_red);
   else rowop_wg<POL, ROP, DT, 0>(r, begin, end, s_red);
@@ -1501,6 +1536,16 @@ struct DispShared {
   uint32_t n, npend, npub;
 };
 
+// The 16 lanes that hold a record's 16-byte pieces: the weighted check sum of the whole record
+// (see record_check_weight), in every one of them.
+DEV uint32_t record_piece_sum(const v4i& q, uint32_t part) {
+  uint32_t x = 0;
+#pragma unroll
+  for (uint32_t j = 0; j < 4; ++j) x += (uint32_t)q[j] * record_check_weight(4u * part + j);
+  x += __shfl_xor(x, 8, 16); x += __shfl_xor(x, 4, 16); x += __shfl_xor(x, 2, 16); x += __shfl_xor(x, 1, 16);
+  return x;
+}
+
 DEV void dispatcher_refresh_table(const WorkerArgs& a, DispShared* s, uint32_t only_op) {
   // copy entries host table -> device table with the dual-slot protocol: the
   // inactive slot is written first, then the version is published.
@@ -1635,8 +1680,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       order_loads();
       // keep the prefetched records whose check word holds and that the doorbell value read in the
       // same round covers
-      uint32_t x = (uint32_t)(q[0] ^ q[1] ^ q[2] ^ q[3]);
-      x ^= __shfl_xor(x, 8, 16); x ^= __shfl_xor(x, 4, 16); x ^= __shfl_xor(x, 2, 16); x ^= __shfl_xor(x, 1, 16);
+      const uint32_t x = record_piece_sum(q, part);
       const bool good = mirrored + g < t && x == record_check_seed(mirrored + g);
       if (good) ((v4i*)&s->rec[g])[part] = q;
       if (part == 0) s->pre[g] = good ? 1u : 0u;
@@ -1707,8 +1751,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
             const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
             const v4i q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
             ((v4i*)&s->rec[rix])[part] = q;
-            uint32_t x = (uint32_t)(q[0] ^ q[1] ^ q[2] ^ q[3]);
-            x ^= __shfl_xor(x, 8, 16); x ^= __shfl_xor(x, 4, 16); x ^= __shfl_xor(x, 2, 16); x ^= __shfl_xor(x, 1, 16);
+            const uint32_t x = record_piece_sum(q, part);
             if (part == 0) s->ok[rix] = (x == record_check_seed(mirrored + rix)) ? 1u : 0u;
           }
         }

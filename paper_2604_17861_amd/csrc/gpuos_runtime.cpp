@@ -242,7 +242,10 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
       }
       return true;
     };
-    bool fast = same_dt && n % V == 0 && n * (int64_t)es < kMaxExtent;
+    // one dtype for every tensor; layer norm also with fp32 gamma and beta under 16-bit x and y
+    const bool ln_p32 = impl == GPUOS_IMPL_LAYERNORM_LAST && ops[0].dtype == ops[ar].dtype && ops[0].dtype != GPUOS_F32 &&
+                        ops[1].dtype == GPUOS_F32 && ops[2].dtype == GPUOS_F32;
+    bool fast = (same_dt || ln_p32) && n % V == 0 && n * (int64_t)es < kMaxExtent && n * 4 < kMaxExtent;
     for (int k = 0; k <= ar && fast; ++k) fast = s_last[k] == 1 && aligned16(ops[k].ptr);
     fast = fast && (rows == 1 || (dense_rows(oo[0], 0) && dense_rows(oo[ar], 0)));
     uint32_t period[3] = {0, 0, 0};
@@ -396,7 +399,7 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
     rec.path = PATH_RED_GENERIC;
   }
   // same traffic per chunk as an elementwise chunk: chunk_elems * 12 bytes of input rows
-  uint64_t rpc = (uint64_t)chunk_elems * 12 / ((uint64_t)n * dtype_size(ops[0].dtype));
+  uint64_t rpc = (uint64_t)chunk_elems * 24 / ((uint64_t)n * dtype_size(ops[0].dtype));
   if (rpc < 1) rpc = 1;
   if (rpc >= 16) rpc = (rpc + 15) / 16 * 16;          // whole passes of the row-per-wave kernels
   const uint64_t min_rpc = ((uint64_t)rows + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
@@ -928,14 +931,14 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
       if (rc != GPUOS_OK) return rc;
     }
     Record& rec = staged[i];
-    rec.ticket = head;
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(&rec);
-    uint32_t x = record_check_seed(head);
-    for (int k = 0; k < 63; ++k) x ^= w[k];
-    rec.check = x;                                                // xor over all 64 words == the seed
+    rec.ticket = 0;                                               // enters the check through the seed only
+    rec.check = record_check_seed(head) - record_check_sum(reinterpret_cast<const uint32_t*>(&rec), 63);
     std::memcpy(&c->hring[head & c->mask], &rec, sizeof(Record));
     ++head;
   }
+  // Device-memory ring: the records sit in THIS core's write-combining buffers; push them out
+  // before another producer thread can ring the doorbell over them.
+  if (c->push) _mm_sfence();
   c->head.store(head, std::memory_order_release);
   return GPUOS_OK;
 }

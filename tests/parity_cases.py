@@ -237,6 +237,14 @@ def row_operations():
             mh = b.pool(to_dtype(rng.standard_normal((H_, 1, S_)).astype(np.float32), code))     # per head, one row
             o = b.pool(np.zeros((B_, H_, S_, S_), dt))
             b.add("MASKED_SOFTMAX_LAST", o, [x, np.broadcast_to(mh[None], (B_, H_, S_, S_))], alpha=0.5)
+    # layer norm with fp32 gamma / beta under 16-bit x and y (how frameworks keep the parameters): vector paths
+    for code in (S.F16, S.BF16):
+        for rows, n in ((9, 64), (40, 768), (33, 1024), (17, 2048), (6, 4096), (5, 8192), (3, 12288)):
+            x = b.pool(to_dtype((rng.standard_normal((rows, n)) * 2 + 0.5).astype(np.float32), code))
+            g = b.pool((1 + 0.2 * rng.standard_normal(n)).astype(np.float32))
+            be = b.pool(rng.standard_normal(n).astype(np.float32))
+            o = b.pool(np.zeros((rows, n), np_dtype(code)))
+            b.add("LAYERNORM_LAST", o, [x, np.broadcast_to(g, (rows, n)), np.broadcast_to(be, (rows, n))], alpha=1e-5)
     # generic path: strided rows, transposed views, mixed dtypes, fp32 output of 16-bit input
     x16 = b.pool(to_dtype((rng.standard_normal((64, 96)) * 2).astype(np.float32), S.F16))
     x32 = b.pool((rng.standard_normal((96, 64)) * 2).astype(np.float32))

@@ -67,15 +67,12 @@ void consumer(gpuos::WorkerArgs a, Worker* w) {
         bool good = false;
         for (int attempt = 0; attempt < 1000 && !good; ++attempt) {
           std::memcpy(&rec, &a.hring[ticket & a.cap_mask], sizeof(Record));
-          uint32_t x = 0;
-          const uint32_t* words = reinterpret_cast<const uint32_t*>(&rec);
-          for (int k = 0; k < 64; ++k) x ^= words[k];
-          good = x == record_check_seed(ticket);
+          good = record_check_sum(reinterpret_cast<const uint32_t*>(&rec), 64) == record_check_seed(ticket);
           if (!good) g_retries.fetch_add(1);
         }
         int32_t status = GPUOS_OK;
         uint32_t version = 0;
-        if (!good || rec.ticket != ticket) { g_errors.fetch_add(1); status = GPUOS_E_INVAL; }
+        if (!good || rec.ticket != 0) { g_errors.fetch_add(1); status = GPUOS_E_INVAL; }   // the ticket lives in the check word's seed
         else if (rec.op_id >= GPUOS_MAX_OPS || table[rec.op_id].version == 0) status = GPUOS_E_BADOP;
         else {
           version = table[rec.op_id].version;

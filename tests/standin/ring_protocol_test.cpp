@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "../../include/gpuos.h"
+#include "../../paper_2604_17861_amd/csrc/gpuos_internal.h"
 
 extern "C" uint64_t standin_errors();
 extern "C" uint64_t standin_records();
@@ -38,7 +39,47 @@ static gpuos_ctx* make(uint32_t cap, bool nonblocking = false, bool harvester = 
   return c;
 }
 
+// The ring record's check word must reject every mixture of the record a slot held on the previous
+// lap and the record being written into it (write-combined stores land piecewise, in any order):
+// all 8-byte pieces in which two same-shaped tasks differ, in every old / new combination.
+static void check_word_rejects_mixtures() {
+  using gpuos::Record;
+  auto seal = [](Record& r, uint64_t ticket) {          // what gpuos_submit does to a packed record
+    r.ticket = 0;
+    r.check = gpuos::record_check_seed(ticket) - gpuos::record_check_sum(reinterpret_cast<const uint32_t*>(&r), 63);
+  };
+  auto verifies = [](const Record& r, uint64_t ticket) { // what the dispatcher does
+    return gpuos::record_check_sum(reinterpret_cast<const uint32_t*>(&r), 64) == gpuos::record_check_seed(ticket);
+  };
+  for (uint64_t cap : {2ull, 64ull, 4096ull, 65536ull})
+    for (uint64_t t : {0ull, 1ull, 63ull, 4095ull, 123456789ull, (1ull << 32) - 1, (1ull << 40) + 17}) {
+      Record oldr, newr;
+      std::memset(&oldr, 0, sizeof(oldr));
+      oldr.op_id = 7; oldr.path = 1; oldr.ndim = 1; oldr.n_inputs = 2; oldr.nchunks = 1; oldr.chunk = 8192; oldr.numel = 2048;
+      oldr.size[0] = 2048;
+      newr = oldr;
+      for (int k = 0; k < 4; ++k) { oldr.ptr[k] = 0x7f0000000000ull + 0x10000000ull * k + 8192ull * 77; newr.ptr[k] = 0x7f0000000000ull + 0x10000000ull * k + 8192ull * 1234; }
+      seal(oldr, t);
+      seal(newr, t + cap);
+      CHECK(verifies(newr, t + cap) && verifies(oldr, t));
+      CHECK(!verifies(oldr, t + cap) && !verifies(newr, t));
+      const uint64_t* po = reinterpret_cast<const uint64_t*>(&oldr);
+      const uint64_t* pn = reinterpret_cast<const uint64_t*>(&newr);
+      int diff[32], nd = 0;
+      for (int k = 0; k < 32; ++k) if (po[k] != pn[k]) diff[nd++] = k;
+      CHECK(nd >= 2 && nd <= 8);
+      for (unsigned mask = 0; mask + 1 < (1u << nd); ++mask) {     // every mixture except "all new"
+        Record mix = newr;
+        uint64_t* pm = reinterpret_cast<uint64_t*>(&mix);
+        for (int j = 0; j < nd; ++j) if (!((mask >> j) & 1u)) pm[diff[j]] = po[diff[j]];   // bit clear: the old piece is still there
+        CHECK(!verifies(mix, t + cap));
+      }
+    }
+  std::printf("ok: check word rejects every old/new mixture of a slot's records\n");
+}
+
 int main() {
+  check_word_rejects_mixtures();
   // 1. many producers, tiny rings: every ticket exactly once, consecutive inside a call, in-order log
   for (uint32_t cap : {2u, 8u, 64u}) {
     for (int harv = 0; harv < 2; ++harv) {

@@ -160,12 +160,14 @@ def test_task_plan_for_row_operations():
     b.add("SOFTMAX_LAST", f(10, 32), [f(10, 36)[:, :32]])                                    # 11 row pitch
     b.add("SOFTMAX_LAST", f(32), [f(32)])                                                    # 12 one row, rank 1
     b.add("SOFTMAX_LAST", h(4, 2048), [h(4, 2048)])                                          # 13 fp16: 256 vectors
+    b.add("LAYERNORM_LAST", h(50, 1024), [h(50, 1024), np.broadcast_to(f(1024), (50, 1024)), np.broadcast_to(f(1024), (50, 1024))])  # 14 fp32 parameters under fp16 x
+    b.add("LAYERNORM_LAST", h(50, 1024), [h(50, 1024), np.broadcast_to(f(1024), (50, 1024)), np.broadcast_to(h(1024), (50, 1024))])  # 15 gamma fp32, beta fp16
     s = b.stream()
     hp = HostPools(s)
     impl = s.impl_for()
     got = [R.task_plan(hp.tasks, i, impl[i]) for i in range(len(s))]
     want = ["ROW_FUSED"] * 4 + ["ROW_GENERIC", "ROW_FUSED", "ROW_GENERIC", "ROW_FUSED", "ROW_GENERIC", "ROW_GENERIC",
-                                "ROW_GENERIC", "ROW_GENERIC", "ROW_FUSED", "ROW_FUSED"]
+                                "ROW_GENERIC", "ROW_GENERIC", "ROW_FUSED", "ROW_FUSED", "ROW_FUSED", "ROW_GENERIC"]
     assert [g[0] for g in got] == want, [g[0] for g in got]
     rows = 2 * 3 * 64
     assert (got[0][1] - 1) * got[0][2] < rows <= got[0][1] * got[0][2]
