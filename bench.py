@@ -25,6 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+KNOBS = {}                  # gpuos_config fields every context of this run is created with (--workgroups-per-cu)
 
 
 def log(*a):
@@ -74,7 +75,7 @@ def percentile_us(ns, q):
 
 
 def bench_persistent(R, stream, dp, steps, warmup, harvester=True, capacity=0, **cfg):
-    with R.Runtime(capacity, harvester_thread=1 if harvester else 0, idle_exit_ms=60000, **cfg,
+    with R.Runtime(capacity, harvester_thread=1 if harvester else 0, idle_exit_ms=60000, **KNOBS, **cfg,
                    completion_log=max(1 << 20, 1 << int(np.ceil(np.log2(len(stream) + 1))))) as rt:
         rt.register_table(stream.table)
         for _ in range(warmup):
@@ -110,7 +111,7 @@ def bench_multi_producer(R, stream, dp, passes=8, **cfg):
     out = {}
     n = len(stream)
     for nt in (1, 2, 4, 8, 16):
-        with R.Runtime(0, harvester_thread=1, idle_exit_ms=60000, **cfg) as rt:
+        with R.Runtime(0, harvester_thread=1, idle_exit_ms=60000, **KNOBS, **cfg) as rt:
             rt.register_table(stream.table)
             rt.submit_from_threads(dp.tasks, nt, 64, 1)
             rt.wait()
@@ -136,7 +137,7 @@ def bench_program(R, s5, dp5, impl5, n_tasks=1500):
              "program_6_instr": S.program(("SUB", 4, 0, 1), ("MUL", 4, 4, 3), ("ABS", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5),
                                           ("DIV", 0, 0, 4))}
     for label, code in progs.items():
-        with R.Runtime(0, idle_exit_ms=60000) as rt:
+        with R.Runtime(0, idle_exit_ms=60000, **KNOBS) as rt:
             table = dict(s5.table)
             if code is not None:
                 table[S.OP["ADD"]] = rt.define_program(code, 2)
@@ -151,7 +152,7 @@ def bench_program(R, s5, dp5, impl5, n_tasks=1500):
 def bench_pingpong(R, stream, dp, n=5000, **cfg):
     """Unloaded latency: one task at a time, timed inside the library (gpuos_run_serial), the same
     way the per-launch path times launch + synchronize."""
-    with R.Runtime(0, idle_exit_ms=60000, **cfg) as rt:
+    with R.Runtime(0, idle_exit_ms=60000, **KNOBS, **cfg) as rt:
         rt.register_table(stream.table)
         rt.run_serial(dp.tasks, 0, min(200, len(stream)))
         lat = np.concatenate([rt.run_serial(dp.tasks, 0, min(len(stream), n - k)) for k in range(0, n, len(stream))])
@@ -162,7 +163,7 @@ def bench_roofline(R, stream, dp, impls):
     """The persistent kernel alone over the bandwidth stream: one worker lifetime that holds
     nothing but this stream, timed by HIP events on the worker's own stream."""
     nbytes = int(R.task_bytes(dp.tasks, impls).sum())
-    with R.Runtime(0, idle_exit_ms=60000) as rt:
+    with R.Runtime(0, idle_exit_ms=60000, **KNOBS) as rt:
         rt.register_table(stream.table)
         t0 = time.perf_counter()
         submit_pass(rt, stream, dp.tasks)
@@ -201,8 +202,11 @@ def main():
                     help="run one ordinary COPY kernel over 1 GiB (counter calibration for profiler runs) and exit")
     ap.add_argument("--cfg5-tasks", type=int, default=20000)
     ap.add_argument("--cfg4-tasks", type=int, default=1000000)
+    ap.add_argument("--workgroups-per-cu", type=int, default=0, help="0: the library's default")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time given to the oracle baseline")
     args = ap.parse_args()
+    if args.workgroups_per_cu:
+        KNOBS["workgroups_per_cu"] = args.workgroups_per_cu
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one ring, one persistent kernel and one operator table "
                  "per GPU; there is no multi-GPU path to measure). Use --gpus 1.")
@@ -403,6 +407,10 @@ def host_info():
     return dict(nproc=os.cpu_count(), usable_cpus=len(os.sched_getaffinity(0)), cpu_model=model)
 
 
+def common_cus(R):
+    return int(R.device_info(0)["compute_units"])
+
+
 def write_reports(directory, R, line):
     """One JSON per configuration: what was run, on what, with which knobs, and the figures measured
     by this process.  Parity figures are written by the GPU tests of the full configurations (they
@@ -410,7 +418,7 @@ def write_reports(directory, R, line):
     os.makedirs(directory, exist_ok=True)
     common = dict(device=R.device_info(0), host=host_info(),
                   knobs=dict(queue_capacity=4096, workgroups=line["config"]["workgroups"], threads_per_workgroup=256,
-                             workgroups_per_cu=4), hbm_peak_gbps=HBM_PEAK_GBPS)
+                             workgroups_per_cu=line["config"]["workgroups"] // common_cus(R)), hbm_peak_gbps=HBM_PEAK_GBPS)
     ex = line["extras"]
     per = {
         "config2": dict(seed=1, tasks=10000, persistent_tasks_per_s=line["value"],

@@ -31,13 +31,16 @@
  *   - while a context is alive the worker kernel is resident on its own
  *     non-blocking stream: the caller must not call hipDeviceSynchronize(),
  *     hipFree() or anything else that waits for "all streams" before
- *     gpuos_shutdown(), or the process deadlocks.  The worker also occupies
- *     one of the process's hardware queues for good: work that the HIP runtime
- *     places on that queue waits until the worker exits.  Seen on MI355X with
- *     4 hardware queues: device<->host copies of 16 KiB or less (done by a copy
- *     kernel; larger ones go to the DMA engines and run alongside), on the
- *     default stream and on a freshly created one.  Move small results with a
- *     GPUOS_IMPL_COPY task into pinned, device-mapped host memory instead, or
+ *     gpuos_shutdown(), or the process deadlocks.  Other kernels share the
+ *     compute units with the worker: it is built for 128 vector registers per
+ *     lane and the default of 3 workgroups per compute unit leaves a quarter of
+ *     every register file, and more than half of the local memory and wave
+ *     slots, to them.  With workgroups_per_cu = 4 the worker fills every
+ *     register file and NO other kernel can start until it exits -- that
+ *     includes the copy kernel the HIP runtime uses for device<->host copies of
+ *     16 KiB or less (larger ones go to the DMA engines): use 4 only for a
+ *     process that runs nothing else on the GPU, and then move small results
+ *     with a GPUOS_IMPL_COPY task into pinned, device-mapped host memory or
  *     read them after gpuos_stop_worker().
  */
 #ifndef GPUOS_H_
@@ -234,7 +237,7 @@ typedef struct gpuos_config {
   int32_t  device;                  /* HIP device ordinal                           */
   uint32_t threads_per_workgroup;   /* paper's threads_per_block; 0 => 256 (only 256
                                        is supported by the built kernel)            */
-  uint32_t workgroups_per_cu;       /* 0 => 4; clamped to what is co-resident       */
+  uint32_t workgroups_per_cu;       /* 0 => 3; 1..4, clamped to what is co-resident; 4 leaves no room for other kernels (see above) */
   uint32_t nonblocking_submit;      /* 1: a full ring returns GPUOS_E_FULL          */
   uint32_t harvester_thread;        /* 1: a pinned host thread harvests completions
                                        and time-stamps them (latency measurement)   */
@@ -351,6 +354,17 @@ int gpuos_worker_stats(gpuos_ctx* ctx, uint64_t out[16]);
  * the context so that timing and logs can still be read; gpuos_shutdown frees. */
 int gpuos_stop_worker(gpuos_ctx* ctx);
 int gpuos_worker_elapsed_ms(gpuos_ctx* ctx, float* out_ms);
+
+/* Launch the worker again on a context whose worker has left: after
+ * gpuos_stop_worker, or after it exited by itself (cfg.idle_exit_ms).  Tickets,
+ * the completion log, the operator table (swaps made while it was stopped
+ * included), programs and counters continue; gpuos_worker_elapsed_ms then covers
+ * the latest run only.  This is how a caller hands the whole GPU to a kernel that
+ * cannot start beside the worker (see the conventions at the top) and takes it
+ * back: stop, run that kernel, start.  GPUOS_OK also when the worker is running;
+ * GPUOS_E_DEAD if the earlier run lost work or could not be joined.  Like
+ * init / stop / shutdown: one thread, and no other thread inside a call. */
+int gpuos_start_worker(gpuos_ctx* ctx);
 
 /* Submit tasks[0..n) one at a time, waiting for each before the next is submitted, and
  * store each task's submit -> completion-seen host nanoseconds into lat_ns (HOST array of n,

@@ -204,10 +204,15 @@ struct WorkerArgs {
   TraceRec*  trace;          // host memory; nullptr = tracing off
   uint64_t*  opcount;        // host memory, GPUOS_MAX_OPS totals (tracing only)
   uint32_t   trace_mask;
+  uint32_t   resume;         // 1: the context has run before; its counters continue where they stopped
+  uint64_t   resume_tickets; // tickets dequeued (and completed) by the earlier runs
 };
 
 // implemented in gpuos_kernels.hip
 int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream);
+// Before a worker is launched again on a context that has run before (same stream, ahead of it):
+// the workgroups of the last run left with claims they never served.
+int launch_resume_fixup(DevCtl* d, void* stream);
 int worker_max_blocks_per_cu(int* out);
 int launch_single(const Record& r, void* stream);   // one ordinary kernel launch for one task
 

@@ -1638,12 +1638,16 @@ DEV uint32_t dispatcher_service_pending(const WorkerArgs& a, DispShared* s, uint
 
 DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   const uint32_t tid = threadIdx.x;
-  uint64_t mirrored = 0, units_w = 0, seen_epoch = 0;
+  // A context whose worker was stopped and started again continues its ticket and work-unit
+  // counts (both are zero on a fresh context); the operator table is read again from the host's
+  // copy because the epoch seen starts at zero.
+  uint64_t mirrored = a.resume_tickets, seen_epoch = 0;
+  uint64_t units_w = __hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM);
   for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) { s->entry[op] = 0; s->opcnt[op] = 0; }
   if (tid == 0) s->npend = 0;
   __syncthreads();
   uint64_t idle_since = wall_clock64();
-  if (tid == 0) __hip_atomic_store(&a.h->clock_origin, idle_since, __ATOMIC_RELAXED, SC_SYSTEM);
+  if (tid == 0 && !a.resume) __hip_atomic_store(&a.h->clock_origin, idle_since, __ATOMIC_RELAXED, SC_SYSTEM);
   const bool tracing = a.trace != nullptr;
   uint32_t passes_since_flush = 0;
   bool counts_dirty = false;
@@ -1651,7 +1655,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   bool stopping = false;
   uint64_t st_batches = 0, st_records = 0, st_units = 0, st_stage = 0, st_resolve = 0, st_write = 0, st_busy = 0;
   uint64_t st_deferred = 0;
-  uint64_t claimed = 0;                    // last value read from the claim counter (thread 0)
+  uint64_t claimed = units_w;              // last value read from the claim counter (thread 0)
   const rsrc_t rh = make_rsrc(a.hring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   while (true) {
@@ -1892,9 +1896,10 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       __syncthreads();                                 // ... before the stop flag can be seen
       if (tid == 0) {
         uint64_t* st = a.d->stat;
-        st[ST_DISP_BATCHES] = st_batches; st[ST_DISP_RECORDS] = st_records; st[ST_DISP_UNITS] = st_units;
-        st[ST_DISP_TICKS_STAGE] = st_stage; st[ST_DISP_TICKS_RESOLVE] = st_resolve; st[ST_DISP_TICKS_WRITE] = st_write;
-        st[ST_DISP_TICKS_TOTAL_BUSY] = st_busy; st[ST_DISP_POLLS] = polls; st[ST_DISP_DEFERRED] = st_deferred;
+        // totals over every run of the context's worker
+        st[ST_DISP_BATCHES] += st_batches; st[ST_DISP_RECORDS] += st_records; st[ST_DISP_UNITS] += st_units;
+        st[ST_DISP_TICKS_STAGE] += st_stage; st[ST_DISP_TICKS_RESOLVE] += st_resolve; st[ST_DISP_TICKS_WRITE] += st_write;
+        st[ST_DISP_TICKS_TOTAL_BUSY] += st_busy; st[ST_DISP_POLLS] += polls; st[ST_DISP_DEFERRED] += st_deferred;
         __hip_atomic_store(&a.d->tail_units, units_w, __ATOMIC_RELAXED, SC_SYSTEM);
         drain_stores();
         __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELAXED, SC_SYSTEM);
@@ -2064,6 +2069,21 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
   if (threadIdx.x == 0) s_rec = rec;
   __syncthreads();
   exec_chunk<POL_PLAIN>(&s_rec, s_rec.impl, blockIdx.x, s_red, nullptr);   // built-in implementations only
+}
+
+// The workgroups of a stopped worker left holding work-unit numbers beyond the last published one
+// (each claims a number, sees the stop flag and exits): hand those numbers out again, and lower
+// the stop flag, before the next worker starts.
+__global__ void gpuos_resume_fixup_kernel(DevCtl* d) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    d->claim = d->tail_units;
+    d->stop_dev = 0;
+  }
+}
+
+int launch_resume_fixup(DevCtl* d, void* stream) {
+  hipLaunchKernelGGL(gpuos_resume_fixup_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, d);
+  return (int)hipGetLastError();
 }
 
 int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream) {

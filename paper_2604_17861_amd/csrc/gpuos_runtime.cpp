@@ -462,6 +462,7 @@ struct gpuos_ctx {
   std::thread harvester;
   std::atomic<bool> harvester_run{false};
   bool worker_running = false;
+  WorkerArgs wargs{};                     // what the worker was launched with (gpuos_start_worker launches it again)
   bool worker_joined = false;
   uint64_t wait_ns = 0;
 };
@@ -637,7 +638,7 @@ void gpuos_default_config(gpuos_config* cfg) {
   (void)hipGetDevice(&dev);
   cfg->device = dev;
   cfg->threads_per_workgroup = kThreads;
-  cfg->workgroups_per_cu = 4;
+  cfg->workgroups_per_cu = 3;
   cfg->wait_timeout_ms = 30000;
   cfg->completion_log = 1u << 20;
   cfg->chunk_elems = kChunkElems;
@@ -651,7 +652,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   if (user_cfg) cfg = *user_cfg; else gpuos_default_config(&cfg);
   if (cfg.threads_per_workgroup == 0) cfg.threads_per_workgroup = kThreads;
   if (cfg.threads_per_workgroup != kThreads) return GPUOS_E_INVAL;
-  if (cfg.workgroups_per_cu == 0) cfg.workgroups_per_cu = 4;
+  if (cfg.workgroups_per_cu == 0) cfg.workgroups_per_cu = 3;
   if (cfg.wait_timeout_ms == 0) cfg.wait_timeout_ms = 30000;
   if (cfg.completion_log == 0) cfg.completion_log = 1u << 20;
   if (cfg.chunk_elems == 0) cfg.chunk_elems = kChunkElems;
@@ -760,6 +761,8 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
   a.progs = c->progs;
   a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
+  a.resume = 0; a.resume_tickets = 0;
+  c->wargs = a;
   if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
   if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);
   if (!hip_ok(hipEventRecord(c->ev_stop, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
@@ -770,7 +773,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
     const uint64_t t0 = now_ns();
     while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
       if (now_ns() - t0 > c->wait_ns) {
-        // The kernel never started (its hardware queue is busy).  Ask it to exit as soon as it
+        // The kernel never started (the device is busy with other work).  Ask it to exit as soon as it
         // does; if it still has not finished, keep its memory alive: freeing under a queued
         // kernel would fault when it finally runs.
         if (stop_worker(c) == GPUOS_E_TIMEOUT) return GPUOS_E_TIMEOUT;
@@ -819,7 +822,7 @@ int gpuos_define_program(gpuos_ctx* c, const gpuos_instr* code, uint32_t n_instr
   }
   img.n_instr = n_instr; img.n_inputs = n_inputs; img.ready = kProgramReady;
   std::lock_guard<std::mutex> lk(c->prod_mu);
-  if (!c->worker_running) return GPUOS_E_DEAD;
+  if (!c->worker_running && !c->worker_joined) return GPUOS_E_DEAD;
   if (c->n_progs >= GPUOS_MAX_PROGRAMS) return GPUOS_E_FULL;
   const uint32_t k = c->n_progs;
   // the code first, the header (with the ready word) after it: the device never runs half a program
@@ -841,7 +844,7 @@ int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* 
   std::lock_guard<std::mutex> lk(c->prod_mu);
   if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   if (c->ops[op_id].version != 0) return GPUOS_E_INVAL;            // already bound: use swap_op
-  if (!c->worker_running) return GPUOS_E_DEAD;
+  if (!c->worker_running && !c->worker_joined) return GPUOS_E_DEAD;   // a stopped worker reads the table when it is started again
   OpInfo& o = c->ops[op_id];
   __atomic_store_n(&o.impl, impl_id, __ATOMIC_RELAXED);
   __atomic_store_n(&o.version, 1u, __ATOMIC_RELEASE);
@@ -860,7 +863,7 @@ int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_
   if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   OpInfo& o = c->ops[op_id];
   if (o.version == 0) return GPUOS_E_BADOP;
-  if (!c->worker_running) return GPUOS_E_DEAD;
+  if (!c->worker_running && !c->worker_joined) return GPUOS_E_DEAD;
   if (impl_id != GPUOS_IMPL_FAIL && o.impl != GPUOS_IMPL_FAIL &&
       (ctx_impl_arity(c, impl_id) != ctx_impl_arity(c, o.impl) || impl_kind(impl_id) != impl_kind(o.impl)))
     return GPUOS_E_INVAL;
@@ -1016,6 +1019,48 @@ int gpuos_set_yield_every(gpuos_ctx* c, uint32_t every) {
 int gpuos_stop_worker(gpuos_ctx* c) {
   if (!c) return GPUOS_E_INVAL;
   return stop_worker(c);
+}
+
+int gpuos_start_worker(gpuos_ctx* c) {
+  if (!c || !c->h) return GPUOS_E_INVAL;
+  if (c->worker_running && !worker_exited(c)) return GPUOS_OK;          // it is running
+  if (c->worker_running) {                                              // it left by itself (idle exit): join it
+    const int rc = stop_worker(c);
+    if (rc != GPUOS_OK) return rc;
+  }
+  if (!c->worker_joined) return GPUOS_E_DEAD;                           // an earlier stop timed out: the kernel may still be there
+  const uint64_t head = c->head.load(std::memory_order_acquire);
+  if (c->floor.load(std::memory_order_acquire) != head) return GPUOS_E_DEAD;   // work was lost: not a state to continue from
+  HIP_TRY(hipSetDevice(c->device));
+  __atomic_store_n(&c->h->exit_code, 0u, __ATOMIC_RELEASE);
+  __atomic_store_n(&c->h->heartbeat, (uint64_t)0, __ATOMIC_RELEASE);
+  {
+    std::lock_guard<std::mutex> lk(c->prod_mu);
+    bump_epoch(c, 0xff, false);                                         // lowers the stop bit; the new worker reads the whole table
+  }
+  WorkerArgs a = c->wargs;
+  a.resume = 1;
+  a.resume_tickets = head;
+  HIP_TRY((hipError_t)launch_resume_fixup(c->d, c->stream));
+  HIP_TRY(hipEventRecord(c->ev_start, c->stream));
+  HIP_TRY((hipError_t)launch_worker(a, c->workgroups, c->stream));
+  HIP_TRY(hipEventRecord(c->ev_stop, c->stream));
+  c->worker_running = true;
+  c->worker_joined = false;
+  const uint64_t t0 = now_ns();
+  while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
+    if (now_ns() - t0 > c->wait_ns) {
+      (void)stop_worker(c);                                             // leaves as soon as it starts
+      return GPUOS_E_TIMEOUT;
+    }
+    if (hipStreamQuery(c->stream) != hipErrorNotReady) { c->worker_running = false; c->worker_joined = true; return GPUOS_E_DEAD; }
+    __builtin_ia32_pause();
+  }
+  if (c->cfg.harvester_thread) {
+    c->harvester_run.store(true);
+    c->harvester = std::thread(harvester_main, c, sched_getcpu());
+  }
+  return GPUOS_OK;
 }
 
 int gpuos_worker_elapsed_ms(gpuos_ctx* c, float* out_ms) {

@@ -86,6 +86,7 @@ def lib():
         "gpuos_set_yield_every": (ctypes.c_int, [vp, u32]),
         "gpuos_shutdown": (ctypes.c_int, [vp]),
         "gpuos_stop_worker": (ctypes.c_int, [vp]),
+        "gpuos_start_worker": (ctypes.c_int, [vp]),
         "gpuos_worker_elapsed_ms": (ctypes.c_int, [vp, P(ctypes.c_float)]),
         "gpuos_worker_stats": (ctypes.c_int, [vp, vp]),
         "gpuos_run_serial": (ctypes.c_int, [vp, vp, u32, vp]),
@@ -113,7 +114,7 @@ def lib():
 
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
-           "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker",
+           "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker", "gpuos_start_worker",
            "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_define_program", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
            "gpuos_trace_origin", "gpuos_kill_op", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
@@ -270,6 +271,13 @@ class Runtime:
         rc = lib().gpuos_stop_worker(self._ctx)
         if check:
             _check(rc, "gpuos_stop_worker")
+        return rc
+
+    def start_worker(self, check=True):
+        """gpuos_start_worker: launch the worker again after stop_worker() or an idle exit."""
+        rc = lib().gpuos_start_worker(self._ctx)
+        if check:
+            _check(rc, "gpuos_start_worker")
         return rc
 
     def worker_elapsed_ms(self):

@@ -34,10 +34,10 @@ std::atomic<uint64_t> g_errors{0}, g_records{0}, g_retries{0};
 void consumer(gpuos::WorkerArgs a, Worker* w) {
   using namespace gpuos;
   struct Entry { uint32_t impl = 0, version = 0; } table[GPUOS_MAX_OPS];
-  uint64_t mirrored = 0, seen_epoch = 0, polls = 0;
+  uint64_t mirrored = a.resume_tickets, seen_epoch = 0, polls = 0;      // a worker started again continues the count
   std::mt19937 rng(12345);
   const uint32_t cap = a.cap_mask + 1;
-  __atomic_store_n(&a.h->clock_origin, 1ull, __ATOMIC_RELEASE);
+  if (!a.resume) __atomic_store_n(&a.h->clock_origin, 1ull, __ATOMIC_RELEASE);
   while (true) {
     ++polls;
     __atomic_store_n(&a.h->heartbeat, polls, __ATOMIC_RELEASE);
@@ -112,13 +112,18 @@ uint64_t standin_retries() { return g_retries.load(); }
 namespace gpuos {
 int launch_worker(const WorkerArgs& a, uint32_t, void* stream) {
   Worker* w = new Worker();
+  Worker* old = nullptr;
   {
     std::lock_guard<std::mutex> lk(g_mu);
+    auto it = g_workers.find(stream);
+    if (it != g_workers.end()) old = it->second;                  // a worker that ran on this stream before and has left
     g_workers[stream] = w;
   }
+  if (old) { if (old->th.joinable()) old->th.join(); delete old; }
   w->th = std::thread(consumer, a, w);
   return 0;
 }
+int launch_resume_fixup(DevCtl* d, void*) { d->claim = d->tail_units; d->stop_dev = 0; return 0; }
 int worker_max_blocks_per_cu(int* out) { *out = 4; return 0; }
 int launch_single(const Record&, void*) { return 0; }
 }  // namespace gpuos

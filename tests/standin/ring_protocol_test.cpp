@@ -204,6 +204,36 @@ int main() {
     CHECK(gpuos_shutdown(c) == GPUOS_OK);
     std::printf("ok: shutdown drains, use after stop refused, program ids\n");
   }
+  // 5. the worker stopped and started again several times: tickets, the completion log, the
+  //    operator table (a swap made while stopped) and the ring position all continue
+  for (int harv = 0; harv < 2; ++harv) {
+    gpuos_ctx* c = make(8, false, harv != 0);
+    uint64_t expect = 0;
+    uint32_t v = 0;
+    for (int round = 0; round < 5; ++round) {
+      std::vector<gpuos_task> some(13 + 7 * round, add_task(7, 256));
+      uint64_t first = ~0ull;
+      CHECK(gpuos_submit(c, some.data(), (uint32_t)some.size(), &first) == GPUOS_OK && first == expect);
+      expect += some.size();
+      CHECK(gpuos_start_worker(c) == GPUOS_OK);                          // running: nothing to do
+      CHECK(gpuos_stop_worker(c) == GPUOS_OK);                           // drains
+      gpuos_queue_state q;
+      CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK && q.completed == expect && q.claimed == expect);
+      CHECK(gpuos_worker_alive(c) == 0);
+      CHECK(gpuos_submit(c, some.data(), 1, nullptr) == GPUOS_E_DEAD);
+      CHECK(gpuos_swap_op(c, 7, round % 2 ? GPUOS_IMPL_ADD : GPUOS_IMPL_SUB, &v) == GPUOS_OK && v == (uint32_t)round + 2);
+      CHECK(gpuos_start_worker(c) == GPUOS_OK);
+      CHECK(gpuos_worker_alive(c) == 1);
+      uint64_t tk = 0;
+      CHECK(gpuos_submit(c, some.data(), 1, &tk) == GPUOS_OK && tk == expect);
+      expect += 1;
+      CHECK(gpuos_wait(c, tk, 0) == GPUOS_OK);
+      gpuos_completion comp;
+      CHECK(gpuos_get_completions(c, tk, 1, &comp) == GPUOS_OK && comp.ticket == tk && comp.op_version == (uint32_t)round + 2);
+    }
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: worker stopped and started 5 times, harvester thread %d\n", harv);
+  }
   CHECK(standin_errors() == 0);
   std::printf("all ok: %llu records through the stand-in, 0 protocol errors\n", (unsigned long long)standin_records());
   return 0;

@@ -1,0 +1,289 @@
+"""The PyTorch dispatch filter (paper Section 5.1) on the CPU: the mode's host logic -- eligibility,
+descriptor marshalling, declared dependencies, host waits, keeping tensors alive, the load and
+context filters -- against plain eager PyTorch.  The runtime is replaced by a stand-in that executes
+the submitted descriptors with the CPU oracle, LAZILY (only when the mode waits, or at the end) and
+in a random order that honours nothing but the declared dependencies: a missing dependency, a
+missing wait or a dropped tensor shows as a wrong result."""
+import random
+from types import SimpleNamespace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_17861_amd import streams as S
+from paper_2604_17861_amd.dispatch import GpuosMode
+
+
+class LazyOracleRuntime:
+    def __init__(self, capacity=4096, seed=0):
+        self.capacity, self.rng = capacity, random.Random(seed)
+        self.table, self.queue, self.head, self.done = {}, [], 0, 0
+        self.executed_order = []
+        self.running = True
+
+    def peek_queue(self):
+        return SimpleNamespace(capacity=self.capacity, completed=self.done)
+
+    def register_op(self, op, impl):
+        self.table[op] = impl
+        return 1
+
+    def submit(self, tasks, first=0, count=None):
+        n = len(tasks) - first if count is None else count
+        assert self.running, "submit to a stopped worker"
+        assert self.head + n - self.done <= self.capacity, "ring overrun"
+        t0 = self.head
+        for k in range(n):
+            self.queue.append((self.head, np.array(tasks[first + k: first + k + 1])))
+            self.head += 1
+        return t0
+
+    def wait(self, ticket=None):
+        upto = self.head - 1 if ticket is None else ticket
+        pending = [q for q in self.queue if q[0] <= upto]
+        self.queue = [q for q in self.queue if q[0] > upto]
+        left = {t for t, _ in pending}
+        while pending:
+            ready = [q for q in pending if all(d == 0 or (q[0] - d) not in left for d in q[1]["dep"][0])]
+            assert ready, "dependency cycle"
+            q = self.rng.choice(ready)
+            pending.remove(q)
+            left.discard(q[0])
+            impl = np.array([self.table[int(q[1]["op_id"][0])]], np.int32)
+            st = oracle.run_stream(q[1], impl)
+            assert st[0] == 0, "oracle rejected ticket %d: %r" % (q[0], q[1])
+            self.executed_order.append(q[0])
+        self.done = max(self.done, upto + 1)
+        return 0
+
+    def stop_worker(self):
+        self.wait()
+        self.running = False
+
+    def start_worker(self):
+        self.running = True
+
+    def shutdown(self):
+        pass
+
+
+def mode(seed=0, capacity=4096, **kw):
+    kw.setdefault("resume_after", 1)             # back to the worker at the first eligible operation after a hand-over
+    return GpuosMode(rt=LazyOracleRuntime(capacity, seed), device="cpu", **kw)
+
+
+def same(a, b, exact=True, tol=2e-3):
+    assert a.shape == b.shape and a.dtype == b.dtype, (a.shape, b.shape, a.dtype, b.dtype)
+    if exact:
+        assert torch.equal(a, b) or torch.equal(torch.nan_to_num(a.float()), torch.nan_to_num(b.float())), (a, b)
+    else:
+        torch.testing.assert_close(a.float(), b.float(), rtol=tol, atol=tol)
+
+
+def model(a, b, row, c16):
+    """Small eager program: exact elementwise steps, broadcasting, views, a matmul PyTorch keeps."""
+    y = torch.relu(a + b) * 0.5                    # ADD, RELU, SCALE
+    z = (y - row) * b.t().t()                      # row broadcast, views
+    w = z.t() / (a.t().abs() + 1.0)                # abs, add-scalar: PyTorch's path; DIV redirected
+    m = w @ w.t()                                  # PyTorch's path
+    u = (c16 + c16) * c16                          # fp16
+    v = u + a[:, : u.shape[1]]                     # fp16 + fp32 -> fp32
+    return y, z, w, m, u, v
+
+
+def inputs(seed=0):
+    g = torch.Generator().manual_seed(seed)
+    a = torch.randn(24, 24, generator=g)
+    b = torch.randn(24, 24, generator=g)
+    row = torch.randn(24, generator=g)
+    c16 = torch.randn(24, 8, generator=g).half()
+    return a, b, row, c16
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_exact_operations_equal_eager_under_lazy_random_order_execution(seed):
+    want = model(*inputs(seed))
+    m = mode(seed, batch=5)
+    with m:
+        got = model(*inputs(seed))
+    for g, w in zip(got, want):
+        same(g, w)
+    st = m.stats
+    assert st["redirected"] >= 9 and st["fallback_type"] >= 3 and st["views"] >= 4, st
+    assert st["by_op"]["ADD"] >= 3 and st["by_op"]["SCALE"] == 1 and st["by_op"]["DIV"] == 1
+
+
+def test_transcendentals_reductions_and_softmax_within_tolerance():
+    g = torch.Generator().manual_seed(3)
+    x = torch.randn(6, 10, 33, generator=g)
+    h = torch.randn(40, 17, generator=g).bfloat16()
+
+    def f():
+        return (torch.exp(x), torch.nn.functional.gelu(x), torch.nn.functional.gelu(x, approximate="tanh"),
+                x.sum(-1), x.sum(dim=2, keepdim=True), x.amax(-1), x.amin(dim=-1, keepdim=True),
+                torch.softmax(x, -1), torch.softmax(h, dim=1), h.float().sum(-1), x[0, 0].sum(-1), x.transpose(1, 2).amax(-1))
+    want = f()
+    m = mode()
+    with m:
+        got = f()
+    for k, (a, b) in enumerate(zip(got, want)):
+        same(a, b, exact=k in (5, 6, 11), tol=2e-5 if a.dtype is torch.float32 else 1e-2)
+    assert m.stats["by_op"] == {"EXP": 1, "GELU_ERF": 1, "GELU_TANH": 1, "SUM_LAST": 4, "MAX_LAST": 2, "MIN_LAST": 1,
+                                "SOFTMAX_LAST": 2}, m.stats
+
+
+def test_what_the_filter_leaves_to_pytorch():
+    a, b, _, c16 = inputs(4)
+    big = torch.randn(300, 300)
+    d = a.double()
+    i = torch.arange(24, dtype=torch.int32)
+
+    def f():
+        return (torch.add(a, b, alpha=2.0), a + 1.5, a / 3.0, big + big, d + d, a.sum(0), a.sum(), torch.softmax(a, 0),
+                i * i, i + i, i // 2, a + i, c16 + torch.tensor(0.1), torch.exp(i), a.sum(-1, dtype=torch.float64))
+    want = f()
+    m = mode(max_numel=1 << 12)
+    with m:
+        got = f()
+    for g, w in zip(got, want):
+        same(g, w)
+    assert m.stats["by_op"] == {"MUL": 1, "ADD": 1}, m.stats          # the two int32 operations
+    assert m.stats["fallback_size"] == 1 and m.stats["fallback_type"] >= 12, m.stats
+
+
+def test_pytorch_kernel_that_overwrites_an_input_waits_for_the_pending_reader():
+    a, b, _, _ = inputs(5)
+    a0 = a.clone()
+    m = mode()
+    with m:
+        y = a + b                      # pending, reads a
+        a.add_(1.0)                    # PyTorch's own in-place kernel: must not run before y is computed
+        z = a * b                      # reads the updated a
+    same(y, a0 + b)
+    same(z, (a0 + 1.0) * b)
+    assert m.stats["host_waits"] >= 1
+
+
+def test_results_read_by_pytorch_and_by_the_host_are_complete():
+    a, b, _, _ = inputs(6)
+    m = mode(batch=64)
+    with m:
+        y = a * b
+        s = float((y @ torch.ones(24)).sum())          # matmul + sum-all: PyTorch's path reading a pending result
+        waits = m.stats["host_waits"]
+        e = (a - b)[3, 4].item()                        # the host reads one element of a pending result
+    assert abs(s - float(((a * b) @ torch.ones(24)).sum())) < 1e-4
+    assert waits >= 1 and m.stats["host_waits"] > waits
+    assert e == (a - b)[3, 4].item()
+
+
+def test_temporaries_dropped_by_the_caller_stay_alive_until_their_tasks_ran():
+    a, b, _, _ = inputs(7)
+
+    def f(steps):
+        t = a
+        for _ in range(steps):
+            t = torch.relu(t * 0.99 + b)            # three tasks per step; the previous t is dropped at once
+        return t
+    want = f(40)
+    m = mode(batch=16)
+    with m:
+        got = f(40)
+    same(got, want)
+    assert m.stats["redirected"] == 120 and m.stats["host_waits"] <= 2, m.stats
+    assert not m._inflight and not m._touch and not m._writer
+
+
+def test_load_filter_takes_the_normal_path_when_the_ring_is_nearly_full():
+    a, b, _, _ = inputs(8)
+
+    def f():
+        out = []
+        t = a
+        for k in range(60):
+            t = t + b
+            out.append(t)
+        return out
+    want = f()
+    m = mode(capacity=16, batch=4)
+    with m:
+        got = f()
+    for g, w in zip(got, want):
+        same(g, w)
+    assert m.stats["fallback_load"] > 0 and m.stats["redirected"] > 0, m.stats
+
+
+def test_context_filter_redirects_from_the_nth_sighting():
+    a, b, _, _ = inputs(9)
+    m = mode(min_calls=3)
+    with m:
+        r = [a + b for _ in range(5)] + [a[:4] + b[:4]]
+    for x in r[:5]:
+        same(x, a + b)
+    assert m.stats["fallback_context"] == 3 and m.stats["redirected"] == 3, m.stats
+
+
+def test_declared_dependencies_are_exactly_the_pending_writers_of_the_inputs():
+    a, b, _, _ = inputs(10)
+    rt = LazyOracleRuntime()
+    m = GpuosMode(rt=rt, device="cpu", batch=64)
+    with m:
+        y = a + b            # ticket 0
+        z = a * b            # 1
+        w = y - z            # 2: deps 2, 1
+        v = w.t() + y        # 3: deps 1 (w through a view), 3
+        u = torch.relu(a)    # 4: none
+        m._submit()
+        deps = [sorted(int(d) for d in q[1]["dep"][0] if d) for q in rt.queue]
+    assert deps == [[], [], [1, 2], [1, 3], []], deps
+    same(v, ((a + b) - a * b).t() + (a + b))
+    del u
+
+
+def test_zero_dim_and_broadcast_shapes():
+    g = torch.Generator().manual_seed(11)
+    s = torch.randn((), generator=g)
+    col = torch.randn(7, 1, generator=g)
+    x = torch.randn(3, 7, 5, generator=g)
+    x6 = torch.randn(2, 3, 4, 4, 3, 2, generator=g)
+
+    def f():
+        return s * s, x * s, x + col, col + x, x6.permute(5, 4, 3, 2, 1, 0) - x6, torch.relu(s), x[:, :6:2, 1::2] * x[:, 1::2, ::2][:, :, :2]
+    want = f()
+    m = mode()
+    with m:
+        got = f()
+    for a, b in zip(got, want):
+        same(a, b)
+    assert m.stats["redirected"] == 7, m.stats
+
+
+def test_gpu_is_handed_over_for_matrix_products_and_taken_back_after_enough_small_operations():
+    a, b, _, _ = inputs(12)
+
+    def f():
+        y = a + b                      # redirected
+        m = y @ b                      # hand-over: the worker is stopped (and y is complete by then)
+        out = [m]
+        for _ in range(12):
+            out.append(out[-1] * 0.5)  # eligible; the first four stay on PyTorch's path
+        return out
+    want = f()
+    md = mode(resume_after=5)
+    with md:
+        got = f()
+        assert md.rt.running
+    for g, w in zip(got, want):
+        same(g, w)
+    st = md.stats
+    assert st["pauses"] == 1 and st["resumes"] == 1 and st["fallback_paused"] == 4 and st["redirected"] == 1 + 8, st
+    # a program that alternates small operations and matrix products stays with PyTorch after the first one
+    md = mode(resume_after=5)
+    with md:
+        t = a
+        for _ in range(6):
+            t = torch.relu(t @ b) * 0.1
+        assert not md.rt.running
+    assert md.stats["pauses"] == 1 and md.stats["redirected"] == 0 and md.stats["fallback_paused"] == 12, md.stats

@@ -1,0 +1,192 @@
+"""The PyTorch dispatch filter (paper Section 5.1) on the GPU: eager PyTorch programs under GpuosMode
+against the same programs on PyTorch's own kernels.  Redirected operations are executed by the
+persistent worker kernel (checked through its per-operator counters); PyTorch's kernels run beside
+the resident worker on the same compute units."""
+import time
+
+import pytest
+import torch
+
+from paper_2604_17861_amd import runtime as R
+from paper_2604_17861_amd import streams as S
+from paper_2604_17861_amd.dispatch import GpuosMode
+
+pytestmark = pytest.mark.gpu
+CFG = dict(idle_exit_ms=20000, wait_timeout_ms=20000)
+DEV = "cuda:0"
+
+
+def gen(seed, *shape, dtype=torch.float32):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn(*shape, generator=g).to(dtype).to(DEV)
+
+
+def same(a, b, exact=True, tol=2e-5):
+    assert a.shape == b.shape and a.dtype == b.dtype, (a.shape, b.shape, a.dtype, b.dtype)
+    a, b = a.cpu(), b.cpu()
+    if exact:
+        assert torch.equal(a, b), (a - b).abs().max()
+    else:
+        torch.testing.assert_close(a.float(), b.float(), rtol=tol, atol=tol)
+
+
+def test_ordinary_kernels_and_small_copies_run_beside_the_resident_worker():
+    """The default launch leaves room on every compute unit: a PyTorch kernel and a 4 KiB
+    device-to-host copy finish at once while the worker is resident and idle (with the register
+    files full they would only start when the worker exits: idle_exit_ms, 20 s here)."""
+    x = torch.ones(1024, device=DEV)
+    torch.cuda.current_stream().synchronize()
+    with R.Runtime(0, **CFG) as rt:
+        assert rt.peek_queue().workgroups == 3 * int(R.device_info(0)["compute_units"])
+        t0 = time.perf_counter()
+        y = x + 1
+        torch.cuda.current_stream().synchronize()
+        h = y.cpu()
+        dt = time.perf_counter() - t0
+        assert rt.worker_alive()
+    assert dt < 2.0, dt
+    assert torch.equal(h, torch.full((1024,), 2.0))
+
+
+def program(a, b, row, h):
+    y = torch.relu(a + b) * 0.5
+    z = (y - row) * b.t()
+    w = z.t() / (a.abs() + 1.0)                     # abs, add-scalar: PyTorch's kernels between redirected ones
+    m = w @ w.t()                                   # PyTorch's matmul reads a redirected result
+    r = torch.relu(m[:64, :64]) - a[:64, :64]       # redirected operations read PyTorch's result (through views)
+    u = (h + h) * h
+    v = u + a[: h.shape[0], : h.shape[1]]
+    return y, z, w, m, r, u, v
+
+
+def test_exact_program_is_bit_identical_to_eager_and_runs_on_the_worker():
+    args = gen(0, 96, 96), gen(1, 96, 96), gen(2, 96), gen(3, 40, 24, dtype=torch.bfloat16)
+    want = program(*args)
+    torch.cuda.current_stream().synchronize()
+    mode = GpuosMode(trace_entries=1024, resume_after=1, **CFG)      # the matmul stops the worker, the next small operation starts it
+    try:
+        with mode:
+            got = program(*args)
+        for k, (g, w) in enumerate(zip(got, want)):
+            same(g, w, exact=k not in (3, 4), tol=1e-4)      # exact but for what passes through the matmul (its kernel choice may differ run to run)
+        st = mode.stats
+        assert st["redirected"] == 11 and st["by_op"] == {"ADD": 3, "RELU": 2, "SCALE": 1, "SUB": 2, "MUL": 2, "DIV": 1}, st
+        assert st["stream_syncs"] >= 2 and st["host_waits"] >= 1 and st["pauses"] == 1 and st["resumes"] == 1, st
+        t0 = time.perf_counter()
+        counts = mode.rt.op_counts()                          # flushed by the dispatcher when the ring runs empty
+        while int(counts.sum()) != st["redirected"] and time.perf_counter() - t0 < 2.0:
+            time.sleep(0.01)
+            counts = mode.rt.op_counts()
+        assert int(counts.sum()) == st["redirected"]
+        assert int(counts[S.OP["ADD"]]) == 3 and int(counts[S.OP["DIV"]]) == 1
+    finally:
+        mode.close()
+
+
+def test_transcendentals_reductions_and_softmax_within_tolerance():
+    x = gen(4, 6, 10, 130)
+    h = gen(5, 64, 48, dtype=torch.float16)
+
+    def f():
+        return (torch.exp(x), torch.nn.functional.gelu(x), torch.nn.functional.gelu(x, approximate="tanh"),
+                x.sum(-1), x.sum(dim=2, keepdim=True), x.amax(-1), x.amin(dim=-1, keepdim=True),
+                torch.softmax(x, -1), torch.softmax(h, dim=1), x.transpose(1, 2).amax(-1), torch.exp(h))
+    want = f()
+    torch.cuda.current_stream().synchronize()
+    mode = GpuosMode(**CFG)
+    try:
+        with mode:
+            got = f()
+        for k, (a, b) in enumerate(zip(got, want)):
+            same(a, b, exact=k in (5, 6, 9), tol=3e-5 if a.dtype is torch.float32 else 2e-3)
+        assert mode.stats["redirected"] == 11 and mode.stats["fallback_type"] == 0, mode.stats
+    finally:
+        mode.close()
+
+
+def test_in_place_pytorch_kernel_waits_for_the_pending_reader_and_long_chains_keep_their_temporaries():
+    a, b = gen(6, 128, 64), gen(7, 128, 64)
+    a0 = a.clone()
+
+    def chain(t, steps):
+        for _ in range(steps):
+            t = torch.relu(t * 0.99 + b)             # the previous t is dropped at once
+        return t
+    want = chain(a0 + 1.0, 400)
+    torch.cuda.current_stream().synchronize()
+    mode = GpuosMode(batch=16, **CFG)
+    try:
+        with mode:
+            y = a + b                    # pending reader of a
+            a.add_(1.0)                  # PyTorch's in-place kernel
+            got = chain(a, 400)
+        same(y, a0 + b)
+        same(got, want)
+        assert mode.stats["redirected"] == 1201, mode.stats
+        assert mode.stats["host_waits"] <= 3, mode.stats          # the chain itself needs no host wait
+    finally:
+        mode.close()
+
+
+def test_load_filter_with_a_tiny_ring():
+    a, b = gen(8, 64, 64), gen(9, 64, 64)
+
+    def f():
+        out, t = [], a
+        for _ in range(300):
+            t = t * 0.5 + b
+            out.append(t)
+        return out
+    want = f()
+    torch.cuda.current_stream().synchronize()
+    with R.Runtime(16, **CFG) as rt:
+        mode = GpuosMode(rt=rt, batch=4)
+        with mode:
+            got = f()
+        for g, w in zip(got, want):
+            same(g, w)
+        assert mode.stats["redirected"] > 0, mode.stats
+        assert mode.stats["redirected"] + mode.stats["fallback_load"] == 600, mode.stats
+        mode.close()
+        assert rt.worker_alive()           # a context handed in stays the caller's
+
+
+def test_large_matrix_products_get_the_whole_gpu_and_an_unknown_large_kernel_is_not_stuck_for_long():
+    big = gen(10, 2048, 2048)
+    a, b = gen(11, 64, 64), gen(12, 64, 64)
+    want_mm = big @ big
+    torch.cuda.current_stream().synchronize()
+    # (i) known: the worker is stopped first
+    mode = GpuosMode(wait_timeout_ms=20000)
+    try:
+        with mode:
+            y = a + b
+            t0 = time.perf_counter()
+            m = big @ big
+            torch.cuda.current_stream().synchronize()
+            dt = time.perf_counter() - t0
+            z = [y * 0.5 for _ in range(70)][-1]              # 64 eligible operations later the worker is back
+        assert dt < 0.15, dt
+        same(m, want_mm, exact=False, tol=1e-3)
+        same(z, (a + b) * 0.5)
+        assert mode.stats["pauses"] == 1 and mode.stats["resumes"] == 1 and mode.stats["redirected"] == 1 + 7, mode.stats
+    finally:
+        mode.close()
+    # (ii) not on the list, and a worker that leaves no room for it: the kernel starts when the
+    # worker's idle exit fires (200 ms), and the next redirected operation starts the worker again
+    mode = GpuosMode(yield_ops=(), workgroups_per_cu=3, wait_timeout_ms=20000)
+    try:
+        with mode:
+            y = a + b
+            t0 = time.perf_counter()
+            m = big @ big
+            torch.cuda.current_stream().synchronize()
+            dt = time.perf_counter() - t0
+            z = y * 0.5
+        assert dt < 2.0, dt
+        same(m, want_mm, exact=False, tol=1e-3)
+        same(z, (a + b) * 0.5)
+        assert mode.stats["pauses"] == 0 and mode.stats["redirected"] == 2, mode.stats
+        assert mode.stats["restarts"] == (1 if dt > 0.1 else 0), (mode.stats, dt)
+    finally:
+        mode.close()

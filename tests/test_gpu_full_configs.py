@@ -1,5 +1,5 @@
 """The five configurations at their full sizes, in the launch configuration bench.py times (default
-capacity 4096, 4 workgroups per CU, the stream's own batch size), against the oracle: everything
+capacity 4096, the default 3 workgroups per CU, the stream's own batch size), against the oracle: everything
 that survives in memory is compared element by element; where buffers are reused by design, the
 last writers are compared and properties that hold at any size are checked for the rest."""
 from concurrent.futures import ThreadPoolExecutor

@@ -437,3 +437,43 @@ def test_small_results_reach_the_host_through_a_copy_task_into_pinned_memory():
         want = np.arange(n, dtype=np.float32) * 0.5
         want[1::2] = want[0::2] * np.float32(-2.0)
         assert np.array_equal(dst.numpy(), want)
+
+
+def test_worker_stopped_and_started_again_continues_where_it_was():
+    """gpuos_stop_worker / gpuos_start_worker (and the idle exit): tickets, results, the operator
+    table and the trace continue across runs of the worker kernel."""
+    from gpu_helpers import DevicePools, run_stream, compare_with_oracle
+    import parity_cases as P
+    s = P.config2_reduced()
+    dp = DevicePools(s)
+    n = len(s)
+    cuts = [0, n // 5, n // 2, n - 7, n]
+    with R.Runtime(64, idle_exit_ms=300, wait_timeout_ms=20000, trace_entries=4096) as rt:
+        rt.register_table(s.table)
+        for k in range(4):
+            first = run_stream(s, rt, dp, cuts[k], cuts[k + 1] - cuts[k])
+            assert first == cuts[k]
+            if k == 0:
+                rt.stop_worker()
+                assert not rt.worker_alive()
+                assert rt.submit(dp.tasks, 0, 1, check=False)[0] == R.E_DEAD
+                assert rt.start_worker(check=False) == R.OK
+            elif k == 1:
+                time.sleep(0.6)                                   # idle exit: the worker leaves by itself
+                assert not rt.worker_alive()
+                assert rt.start_worker(check=False) == R.OK
+            elif k == 2:
+                rt.stop_worker()
+                rt.start_worker()
+                rt.start_worker()                                 # running: nothing to do
+            assert rt.worker_alive()
+        q = rt.peek_queue()
+        assert q.completed == n and q.claimed == n and q.head_submitted == n
+        comp = rt.completions(0, n)
+        assert (comp["status"] == 0).all() and (comp["ticket"] == np.arange(n)).all()
+        tr = rt.trace(n - 50, 50)
+        assert (tr["t_done"] >= tr["t_start"]).all() and (tr["t_start"] >= tr["t_dequeue"]).all()
+        assert int(rt.op_counts().sum()) == n
+        rt.stop_worker()
+        gpu = dp.download()
+    compare_with_oracle(s, gpu)
