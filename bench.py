@@ -149,6 +149,44 @@ def bench_program(R, s5, dp5, impl5, n_tasks=1500):
     return out
 
 
+def bench_dispatch(steps=2000):
+    """Eager PyTorch code (a chain of relu(t * c + b) on 1,024-element tensors: 3 small operations
+    per step) on PyTorch's own launch path and under the dispatch filter, which turns every one of
+    them into a task.  The filter's hook is Python: this leg shows what the integration layer costs,
+    not what the queue can do."""
+    import torch
+    from paper_2604_17861_amd.dispatch import GpuosMode
+    g = torch.Generator().manual_seed(0)
+    a = torch.randn(32, 32, generator=g).to("cuda:0")
+    b = torch.randn(32, 32, generator=g).to("cuda:0")
+
+    def chain(n):
+        t = a
+        for _ in range(n):
+            t = torch.relu(t * 0.99 + b)
+        return t
+    stream = torch.cuda.current_stream()
+    chain(200)
+    stream.synchronize()
+    t0 = time.perf_counter()
+    want = chain(steps)
+    stream.synchronize()
+    eager = 3 * steps / (time.perf_counter() - t0)
+    mode = GpuosMode(idle_exit_ms=60000)
+    try:
+        with mode:
+            chain(200)
+        t0 = time.perf_counter()
+        with mode:
+            got = chain(steps)                       # leaving the block waits for the last task
+        routed = 3 * steps / (time.perf_counter() - t0)
+        same = bool(torch.equal(got.cpu(), want.cpu()))
+        st = {k: v for k, v in mode.stats.items() if k != "by_op"}
+    finally:
+        mode.close()
+    return dict(eager_ops_per_s=eager, filtered_ops_per_s=routed, bit_identical=same, stats=st)
+
+
 def bench_pingpong(R, stream, dp, n=5000, **cfg):
     """Unloaded latency: one task at a time, timed inside the library (gpuos_run_serial), the same
     way the per-launch path times launch + synchronize."""
@@ -357,6 +395,8 @@ def main():
         # ---- an operator defined at run time as a program against the built-in it re-implements -----
         extras["operator_program"] = bench_program(R, s5, dp5, impl5)
         log("operator program:", extras["operator_program"])
+        extras["torch_dispatch"] = bench_dispatch()
+        log("torch dispatch filter:", extras["torch_dispatch"])
     del dp5
 
     # ---- CPU oracle on a bounded sample of the headline stream (one core) ------------------------
