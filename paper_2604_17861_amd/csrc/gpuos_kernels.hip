@@ -1647,7 +1647,12 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   if (tid == 0) s->npend = 0;
   __syncthreads();
   uint64_t idle_since = wall_clock64();
-  if (tid == 0 && !a.resume) __hip_atomic_store(&a.h->clock_origin, idle_since, __ATOMIC_RELAXED, SC_SYSTEM);
+  if (tid == 0) {
+    if (!a.resume) __hip_atomic_store(&a.h->clock_origin, idle_since, __ATOMIC_RELAXED, SC_SYSTEM);
+    // the first heartbeat leaves together with the clock origin: the host pairs the moment it sees
+    // it with device tick `clock_origin` (later heartbeats are poll counts, all above 1)
+    __hip_atomic_store(&a.h->heartbeat, 1ull, __ATOMIC_RELAXED, SC_SYSTEM);
+  }
   const bool tracing = a.trace != nullptr;
   uint32_t passes_since_flush = 0;
   bool counts_dirty = false;

@@ -61,6 +61,7 @@ _INT_OK = ("ADD", "SUB", "MUL")
 _TASK = struct.Struct("<HBBI6q" + "Q6qBB6x" * 4 + "f3H6x")
 assert _TASK.size == S.TASK_DT.itemsize
 _NO_TENSOR = (0, 0, 0, 0, 0, 0, 0, 0, 0)
+_ZEROS = (0,) * S.MAX_DIMS
 aten = torch.ops.aten
 
 
@@ -160,7 +161,7 @@ class GpuosMode(TorchDispatchMode):
                 return _Plan("SCALE", [a], tuple(a.shape), tuple(a.shape), a.dtype, alpha=float(o))
             if not self._tensor_ok(o):
                 return None
-            dt = torch.result_type(a, o)
+            dt = a.dtype if a.dtype is o.dtype else torch.result_type(a, o)
             if dt not in _DT or (dt is torch.int32) != (a.dtype is torch.int32) or (a.dtype is torch.int32) != (o.dtype is torch.int32):
                 return None
             # PyTorch converts an operand to the result dtype before computing; the kernel computes on
@@ -170,10 +171,12 @@ class GpuosMode(TorchDispatchMode):
                 return None
             if dt is torch.int32 and name not in _INT_OK:
                 return None
-            try:
-                shape = tuple(torch.broadcast_shapes(a.shape, o.shape))
-            except RuntimeError:
-                return None
+            shape = tuple(a.shape)
+            if shape != tuple(o.shape):
+                try:
+                    shape = tuple(torch.broadcast_shapes(a.shape, o.shape))
+                except RuntimeError:
+                    return None
             return _Plan(name, [a, o], shape, shape, dt)
         return plan
 
@@ -277,9 +280,11 @@ class GpuosMode(TorchDispatchMode):
         """{ptr, stride[6], dtype, bcast_mask} of `t` broadcast to the iteration shape `size`
         (dims aligned at the right, as PyTorch broadcasts)."""
         nd, td = len(size), t.dim()
+        shape, stride = tuple(t.shape), t.stride()
+        if shape == size:                                   # nothing to broadcast
+            return (t.data_ptr(), *stride, *_ZEROS[nd:], _DT[t.dtype], 0)
         st = [0] * S.MAX_DIMS
         mask = 0
-        shape, stride = t.shape, t.stride()
         for d in range(nd):
             k = d - (nd - td)
             if k >= 0 and shape[k] != 1:
@@ -297,12 +302,12 @@ class GpuosMode(TorchDispatchMode):
         deps = []
         keys = []
         for t in p.inputs:
-            k = t.untyped_storage().data_ptr()
+            k = t.data_ptr() - t.storage_offset() * t.element_size()       # the storage's address
             keys.append(k)
             w = self._writer.get(k)
             if w is not None and 0 < me - w < self.capacity and (me - w) not in deps:
                 deps.append(me - w)                         # an older writer has completed: the ring wrapped past it
-        ko = out.untyped_storage().data_ptr()
+        ko = out.data_ptr()                                 # freshly allocated: offset 0
         keys.append(ko)
         ops = [self._operand(t, size) for t in p.inputs]
         if p.reduce:
@@ -377,7 +382,7 @@ class GpuosMode(TorchDispatchMode):
             newest = -1
             for t in _tensors(args, kwargs):
                 if t.device == self.device:
-                    k = self._touch.get(t.untyped_storage().data_ptr())
+                    k = self._touch.get(t.data_ptr() - t.storage_offset() * t.element_size())
                     if k is not None and k > newest:
                         newest = k
             if newest >= 0:

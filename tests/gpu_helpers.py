@@ -76,7 +76,7 @@ def _strided(buf, dt_code, byte_off, shape, strides_elems):
     es = np.dtype(dt).itemsize
     arr = buf[byte_off:].view(np.uint8)
     need = (1 + sum((s - 1) * st for s, st in zip(shape, strides_elems))) * es if all(s > 0 for s in shape) else 0
-    base = np.frombuffer(arr[:need].tobytes(), dtype=dt) if False else arr[:need].view(dt)
+    base = arr[:need].view(dt)
     return np.lib.stride_tricks.as_strided(base, shape=shape, strides=[st * es for st in strides_elems],
                                            writeable=False)
 
