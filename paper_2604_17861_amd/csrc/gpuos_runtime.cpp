@@ -771,15 +771,18 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   // wait for the first heartbeat so that init returns with a live worker
   {
     const uint64_t t0 = now_ns();
+    uint32_t spins = 0;
     while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
-      if (now_ns() - t0 > c->wait_ns) {
+      if ((spins & 255u) == 0 && now_ns() - t0 > c->wait_ns) {
         // The kernel never started (the device is busy with other work).  Ask it to exit as soon as it
         // does; if it still has not finished, keep its memory alive: freeing under a queued
         // kernel would fault when it finally runs.
         if (stop_worker(c) == GPUOS_E_TIMEOUT) return GPUOS_E_TIMEOUT;
         return fail(GPUOS_E_TIMEOUT);
       }
-      if (hipStreamQuery(c->stream) != hipErrorNotReady) { return fail(GPUOS_E_DEAD); }
+      // look at the stream only now and then: the moment the heartbeat is seen ties the device
+      // clock to the host clock, and a stream query takes microseconds
+      if ((++spins & 4095u) == 0 && hipStreamQuery(c->stream) != hipErrorNotReady) { return fail(GPUOS_E_DEAD); }
       __builtin_ia32_pause();
     }
   }
@@ -1048,12 +1051,16 @@ int gpuos_start_worker(gpuos_ctx* c) {
   c->worker_running = true;
   c->worker_joined = false;
   const uint64_t t0 = now_ns();
+  uint32_t spins = 0;
   while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
-    if (now_ns() - t0 > c->wait_ns) {
+    if ((spins & 255u) == 0 && now_ns() - t0 > c->wait_ns) {
       (void)stop_worker(c);                                             // leaves as soon as it starts
       return GPUOS_E_TIMEOUT;
     }
-    if (hipStreamQuery(c->stream) != hipErrorNotReady) { c->worker_running = false; c->worker_joined = true; return GPUOS_E_DEAD; }
+    if ((++spins & 4095u) == 0 && hipStreamQuery(c->stream) != hipErrorNotReady) {
+      c->worker_running = false; c->worker_joined = true;
+      return GPUOS_E_DEAD;
+    }
     __builtin_ia32_pause();
   }
   if (c->cfg.harvester_thread) {

@@ -360,6 +360,14 @@ def test_device_trace_ring_and_operator_counts():
         assert len(rt.trace(t0 + 6000 - 64, 64)) == 64
         with pytest.raises(R.GpuosError):
             rt.trace(t0, 1)                                    # overwritten long ago
+        # the device clock lines up with the host clock: a lone task is dequeued after the host rang
+        # the doorbell and done before the host saw its completion word (slack: the PCIe write of the first heartbeat and the host's polling step)
+        lat = rt.run_serial(dp2.tasks, 0, 50)
+        first = t0 + 6000
+        tr3, c3 = rt.trace(first, 50), rt.completions(first, 50)
+        deq = tr3["t_dequeue"].astype(np.int64) * 10 + rt.trace_origin_ns() - c3["t_submit_ns"].astype(np.int64)
+        fin = c3["t_done_ns"].astype(np.int64) - (tr3["t_done"].astype(np.int64) * 10 + rt.trace_origin_ns())
+        assert -6000 < np.median(deq) < 20000 and -6000 < np.median(fin) < 20000, (np.median(deq), np.median(fin), np.median(lat))
     with R.Runtime(0, **CFG) as rt:
         with pytest.raises(R.GpuosError):
             rt.op_counts()
