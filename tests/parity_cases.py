@@ -364,6 +364,51 @@ def reductions():
     return b.stream("reductions")
 
 
+def degenerate():
+    """The degenerate cases: empty tensors (nothing may be touched), one-element tensors, six dims of
+    size 1, six real dims, rows of one element, in-place updates, an input used twice, an all-broadcast
+    operand, NaN payloads and -0 through COPY, outputs that are interior slices of their buffers
+    (the bytes around them must survive).  Only exactly rounded operations: the test compares whole
+    buffers byte by byte."""
+    rng = np.random.default_rng(21)
+    b = Builder()
+    f = lambda *sh: b.pool(rng.integers(-8, 9, sh).astype(np.float32))
+    x, y, o = f(40), f(40), f(40)
+    b.add("ADD", o[:0], [x[:0], y[:0]])                                   # empty 1-D
+    e3 = f(4, 6, 5)
+    b.add("MUL", e3[:, :0, :], [e3[:, :0, :], e3[:, :0, :]])              # empty in the middle dim
+    z = f(3, 8); zo = f(3)
+    b.add("SUM_LAST", zo[:0], [z[:0]])                                    # no rows
+    b.add("SOFTMAX_LAST", z[:0], [z[:0]])                                 # no rows (a row operation)
+    b.add("ADD", o[5:6], [x[7:8], y[9:10]])                               # one element, interior output
+    s6 = f(1, 1, 1, 1, 1, 1); t6 = f(1, 1, 1, 1, 1, 1); o6 = f(1, 1, 1, 1, 1, 1)
+    b.add("SUB", o6, [s6, t6])
+    r6 = f(2, 3, 2, 3, 2, 3); q6 = f(3, 2, 3, 2, 3, 2); w6 = f(2, 3, 2, 3, 2, 3)
+    b.add("ADD", w6, [r6, q6.transpose(5, 4, 3, 2, 1, 0)])                # six real dims, one operand reversed
+    one = f(1, 1); oo = f(1)
+    b.add("MAX_LAST", oo, [one])                                          # a row of one element
+    col = f(9, 1); co = f(9)
+    b.add("SUM_LAST", co, [col])                                          # nine rows of one element
+    ip, iq = f(5, 33), f(5, 33)
+    b.add("ADD", ip, [ip, iq])                                            # in place
+    ir = b.pool(rng.standard_normal((7, 19)).astype(np.float32))
+    b.add("RELU", ir[1:6, 2:17], [ir[1:6, 2:17]])                         # in place on an interior block
+    tw = f(64); to = f(64)
+    b.add("MUL", to, [tw, tw])                                            # the same tensor twice
+    sc = f(1, 1); bb = f(3, 4); bo = f(3, 4)
+    b.add("ADD", bo, [np.broadcast_to(sc, (3, 4)), bb])                   # an operand broadcast along every dim
+    pay = np.array([0x7fc00001, 0xffc12345, 0x80000000, 0x00000001, 0x7f800000, 0xff800000, 0x7f812345, 0], np.uint32)
+    cp = b.pool(pay.view(np.float32).copy()); cq = b.pool(np.zeros(10, np.float32))
+    b.add("COPY", cq[1:9], [cp])                                          # NaN payloads, -0, a subnormal, infinities
+    h = b.pool(np.array([0x7e01, 0xfe02, 0x8000, 0x0001, 0x7c00], np.uint16).view(np.float16).copy()); ho = b.pool(np.zeros(7, np.float16))
+    b.add("COPY", ho[1:6], [h])
+    mid = f(6, 1, 7); mo = f(6, 1, 7)
+    b.add("SUB", mo, [mid, np.broadcast_to(mid[:, :, 3:4], (6, 1, 7))])   # a size-1 dim and a broadcast column
+    i32 = b.pool(np.array([2147483647, -2147483648, -1, 0, 5], np.int32)); io = b.pool(np.zeros(7, np.int32))
+    b.add("ADD", io[1:6], [i32, i32])                                     # int32 wrap-around, interior output
+    return b.stream("degenerate")
+
+
 def int32_ops():
     rng = np.random.default_rng(10)
     b = Builder()
@@ -418,6 +463,7 @@ CPU_CHECKED = {
     "operator_programs": operator_programs,
     "row_operations": row_operations,
     "int32": int32_ops,
+    "degenerate": degenerate,
     "config2_reduced": config2_reduced,
     "config3_reduced": config3_reduced,
     "config3_fused_reduced": config3_fused_reduced,

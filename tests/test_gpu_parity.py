@@ -71,6 +71,27 @@ def test_transposed_views_lds_tiled_gather():
     print(stats, flush=True)
 
 
+def test_degenerate_shapes_leave_everything_else_untouched():
+    """Empty, one-element, six-dimensional, in-place, aliased and all-broadcast tasks (exactly rounded
+    operations only): every buffer as a whole equals the oracle's byte for byte, so the results are
+    right, nothing was written outside the outputs and empty tasks touched nothing."""
+    from gpu_helpers import DevicePools, run_stream
+    from helpers import run_oracle
+    s = C.degenerate()
+    dp = DevicePools(s)
+    with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
+        rt.register_table(s.table)
+        t0 = run_stream(s, rt, dp)
+        comps = rt.completions(t0, len(s))
+    assert np.all(comps["status"] == 0), comps["status"]
+    gpu = dp.download()
+    hp, st = run_oracle(s)                       # the whole stream in order from the same initial buffers (it has in-place tasks)
+    assert np.all(st == 0)
+    for k, (g, o) in enumerate(zip(gpu, hp.arrays)):
+        g8, o8 = np.asarray(g).view(np.uint8).reshape(-1), np.asarray(o).view(np.uint8).reshape(-1)
+        assert np.array_equal(g8, o8), "buffer %d differs at bytes %s" % (k, np.nonzero(g8 != o8)[0][:16])
+
+
 def test_fused_row_operations():
     stats, _ = _run_and_check(C.row_operations())
     print(stats, flush=True)
