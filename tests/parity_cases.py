@@ -409,6 +409,59 @@ def degenerate():
     return b.stream("degenerate")
 
 
+def dependency_dag(seed, n_tasks=2500, n_buffers=10, max_dist=48):
+    """A random stream of exactly rounded operations over a FEW buffers, so that almost every task
+    reads or overwrites what an earlier, possibly still running, task wrote or reads: read-after-write,
+    write-after-write and write-after-read hazards, each declared the way a caller must (back-distances
+    to the tickets involved; FENCE when there are more than three).  Task sizes from 256 elements to
+    256K (many chunks) make completions overtake each other.  The result of the whole stream is
+    unique: the test compares every buffer with sequential execution byte for byte."""
+    rng = np.random.default_rng(100 + seed)
+    b = Builder()
+    side = 512
+    bufs = [b.pool(rng.integers(-4, 5, (side, side)).astype(np.float32)) for _ in range(n_buffers)]
+    last_writer = [None] * n_buffers                 # ticket of the newest task that wrote the buffer
+    readers = [[] for _ in range(n_buffers)]         # tickets that read it since
+    for t in range(n_tasks):
+        rows = int(rng.choice([1, 4, 32, 128, 512]))
+        cols = int(rng.choice([256, 512])) if rows > 1 else 256
+        r0 = int(rng.integers(0, side - rows + 1))
+        c0 = int(rng.integers(0, side - cols + 1))
+        view = lambda k: bufs[k][r0: r0 + rows, c0: c0 + cols]
+        o = int(rng.integers(2, n_buffers))            # buffers 0 and 1 are never written: the second operands of ADD / SUB,
+        name = str(rng.choice(["ADD", "SUB", "RELU", "COPY", "SCALE", "MAX_ROWS"]))   # so magnitudes grow by at most 4 per task
+        if name == "MAX_ROWS":                        # a reduction: [rows, cols] -> column r0.. of the output buffer
+            i0 = int(rng.integers(n_buffers))
+            while i0 == o:
+                i0 = int(rng.integers(n_buffers))
+            ins, out, impl = [view(i0)], bufs[o][r0: r0 + rows, c0], "MAX_LAST"
+        else:
+            nin = 2 if name in ("ADD", "SUB") else 1
+            ids = [int(rng.integers(n_buffers))] + ([int(rng.integers(2))] if nin == 2 else [])
+            ins, out, impl = [view(k) for k in ids], view(o), name       # an input from the output buffer is the same view: in place
+        used = [i0] if name == "MAX_ROWS" else ids
+        need = set()
+        for k in used:
+            if last_writer[k] is not None:
+                need.add(last_writer[k])             # read after write
+        if last_writer[o] is not None:
+            need.add(last_writer[o])                 # write after write
+        need.update(readers[o])                      # write after read
+        need.discard(t)
+        dist = sorted(t - w for w in need)
+        if len(dist) <= 3 and (not dist or dist[-1] <= max_dist):   # a back-distance must stay inside the ring
+            dep, flags = tuple(dist + [0] * (3 - len(dist))), 0
+        else:
+            dep, flags = (0, 0, 0), S.FLAG_FENCE
+        b.add(impl, out, ins, alpha=-1.0 if name == "SCALE" else 0.0, dep=dep, flags=flags)
+        for k in used:
+            if k != o:
+                readers[k].append(t)
+        last_writer[o] = t
+        readers[o] = []
+    return b.stream("dependency_dag_%d" % seed, batch=64)
+
+
 def int32_ops():
     rng = np.random.default_rng(10)
     b = Builder()
@@ -464,6 +517,7 @@ CPU_CHECKED = {
     "row_operations": row_operations,
     "int32": int32_ops,
     "degenerate": degenerate,
+    "dependency_dag": lambda: dependency_dag(0, n_tasks=300),
     "config2_reduced": config2_reduced,
     "config3_reduced": config3_reduced,
     "config3_fused_reduced": config3_fused_reduced,

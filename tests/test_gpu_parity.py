@@ -92,6 +92,32 @@ def test_degenerate_shapes_leave_everything_else_untouched():
         assert np.array_equal(g8, o8), "buffer %d differs at bytes %s" % (k, np.nonzero(g8 != o8)[0][:16])
 
 
+@pytest.mark.parametrize("seed,capacity", [(0, 0), (1, 64), (2, 0)])
+def test_random_dependency_dags_equal_sequential_execution(seed, capacity):
+    """2,500 exactly rounded tasks over ten buffers with every kind of hazard between them, declared
+    as dependencies: the buffers at the end equal sequential execution byte for byte, with the
+    default ring and with one of 64 slots (dependencies then reach across laps of the ring)."""
+    from gpu_helpers import DevicePools, run_stream
+    from helpers import run_oracle
+    s = C.dependency_dag(seed)
+    fences = int((s.tasks["flags"] & S.FLAG_FENCE != 0).sum())
+    with_deps = int((s.tasks["dep"] != 0).any(axis=1).sum())
+    print("dag", seed, "tasks", len(s), "with dependencies", with_deps, "fences", fences, flush=True)
+    assert with_deps > 2000 and fences > 20
+    dp = DevicePools(s)
+    with R.Runtime(capacity, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
+        rt.register_table(s.table)
+        t0 = run_stream(s, rt, dp)
+        comps = rt.completions(t0, len(s))
+    assert np.all(comps["status"] == 0)
+    gpu = dp.download()
+    hp, st = run_oracle(s)
+    assert np.all(st == 0)
+    for k, (g, o) in enumerate(zip(gpu, hp.arrays)):
+        g8, o8 = np.asarray(g).view(np.uint8).reshape(-1), np.asarray(o).view(np.uint8).reshape(-1)
+        assert np.array_equal(g8, o8), "buffer %d differs at bytes %s" % (k, np.nonzero(g8 != o8)[0][:16])
+
+
 def test_fused_row_operations():
     stats, _ = _run_and_check(C.row_operations())
     print(stats, flush=True)
