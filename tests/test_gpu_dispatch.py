@@ -157,7 +157,7 @@ def test_large_matrix_products_get_the_whole_gpu_and_an_unknown_large_kernel_is_
     want_mm = big @ big
     torch.cuda.current_stream().synchronize()
     # (i) known: the worker is stopped first
-    mode = GpuosMode(wait_timeout_ms=20000)
+    mode = GpuosMode(wait_timeout_ms=20000, idle_exit_ms=10000)     # were the worker not stopped, the product would wait 10 s
     try:
         with mode:
             y = a + b
@@ -166,7 +166,7 @@ def test_large_matrix_products_get_the_whole_gpu_and_an_unknown_large_kernel_is_
             torch.cuda.current_stream().synchronize()
             dt = time.perf_counter() - t0
             z = [y * 0.5 for _ in range(70)][-1]              # 64 eligible operations later the worker is back
-        assert dt < 0.15, dt
+        assert dt < 3.0, dt
         same(m, want_mm, exact=False, tol=1e-3)
         same(z, (a + b) * 0.5)
         assert mode.stats["pauses"] == 1 and mode.stats["resumes"] == 1 and mode.stats["redirected"] == 1 + 7, mode.stats
