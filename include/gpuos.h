@@ -421,6 +421,30 @@ int gpuos_trace_origin(gpuos_ctx* ctx, uint64_t* host_ns);
  * to a real implementation brings the operator back. */
 int gpuos_kill_op(gpuos_ctx* ctx, uint32_t op_id, uint32_t* out_version);
 
+/* Audit log of the operator table (paper Section 4.4: every injection is
+ * recorded for later review): one record per successful gpuos_register_op,
+ * gpuos_swap_op, gpuos_kill_op and gpuos_define_program, in the order they took
+ * effect.  head_ticket = tickets submitted before the change: every task from
+ * that ticket on observes it (earlier ones may).  A program is recorded with
+ * its length, arity and the FNV-1a hash (64 bit) of its instruction bytes.
+ * The context keeps the latest 65,536 records.  out: HOST array of n records
+ * starting at record number `first` (counted from the context's first change);
+ * *out_total (may be NULL): records written so far.  GPUOS_E_INVAL if the range
+ * is not (any longer) there. */
+enum gpuos_audit_kind { GPUOS_AUDIT_REGISTER = 1, GPUOS_AUDIT_SWAP = 2, GPUOS_AUDIT_KILL = 3, GPUOS_AUDIT_DEFINE_PROGRAM = 4 };
+typedef struct gpuos_audit_record {
+  uint64_t t_ns;          /* host steady_clock nanoseconds (the clock of gpuos_completion) */
+  uint64_t head_ticket;
+  uint32_t kind;          /* enum gpuos_audit_kind                          */
+  uint32_t op_id;         /* logical operator; 0 for DEFINE_PROGRAM         */
+  uint32_t impl_id;       /* implementation bound, or the id the program got */
+  uint32_t version;       /* the operator's version after the change; 0 for DEFINE_PROGRAM */
+  uint32_t n_instr;       /* DEFINE_PROGRAM, and changes that bind a program */
+  uint32_t n_inputs;
+  uint64_t code_hash;
+} gpuos_audit_record;     /* 48 bytes */
+int gpuos_audit_log(gpuos_ctx* ctx, uint64_t first, uint32_t n, gpuos_audit_record* out, uint64_t* out_total);
+
 /* How the host would hand this task to the workers (no GPU needed): out[0] =
  * execution path (0 nothing to do, 1 contiguous vector, 2 [rows, cols]
  * with row-vector / per-row-scalar operands, 3 generic strided walk,

@@ -12,6 +12,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <deque>
 #include <mutex>
 #include <new>
 #include <string>
@@ -462,6 +463,10 @@ struct gpuos_ctx {
   std::thread harvester;
   std::atomic<bool> harvester_run{false};
   bool worker_running = false;
+  std::deque<gpuos_audit_record> audit;   // latest kAuditKeep changes of the operator table (under prod_mu)
+  uint64_t audit_total = 0;
+  uint64_t prog_hash[GPUOS_MAX_PROGRAMS] = {};
+  uint32_t prog_len[GPUOS_MAX_PROGRAMS] = {};
   WorkerArgs wargs{};                     // what the worker was launched with (gpuos_start_worker launches it again)
   bool worker_joined = false;
   uint64_t wait_ns = 0;
@@ -801,6 +806,21 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
 }
 
 namespace {
+constexpr size_t kAuditKeep = 65536;
+// caller holds prod_mu
+void audit(gpuos_ctx* c, uint32_t kind, uint32_t op_id, uint32_t impl_id, uint32_t version) {
+  gpuos_audit_record r{};
+  r.t_ns = now_ns();
+  r.head_ticket = c->head.load(std::memory_order_relaxed);
+  r.kind = kind; r.op_id = op_id; r.impl_id = impl_id; r.version = version;
+  if (impl_id >= GPUOS_IMPL_PROGRAM_BASE && impl_id - GPUOS_IMPL_PROGRAM_BASE < GPUOS_MAX_PROGRAMS) {
+    const uint32_t k = impl_id - GPUOS_IMPL_PROGRAM_BASE;
+    r.n_instr = c->prog_len[k]; r.n_inputs = c->prog_arity[k]; r.code_hash = c->prog_hash[k];
+  }
+  if (c->audit.size() == kAuditKeep) c->audit.pop_front();
+  c->audit.push_back(r);
+  ++c->audit_total;
+}
 // built-in implementation, or a program this context has defined (caller holds prod_mu)
 bool impl_known(const gpuos_ctx* c, uint32_t impl) {
   if (impl != GPUOS_IMPL_NONE && impl < GPUOS_IMPL_COUNT) return true;
@@ -836,8 +856,14 @@ int gpuos_define_program(gpuos_ctx* c, const gpuos_instr* code, uint32_t n_instr
   if (c->push) _mm_sfence();
   std::atomic_thread_fence(std::memory_order_release);
   c->prog_arity[k] = (uint8_t)n_inputs;
+  c->prog_len[k] = n_instr;
+  uint64_t hsh = 0xcbf29ce484222325ull;                            // FNV-1a over the caller's instruction bytes
+  for (size_t b = 0; b < (size_t)n_instr * sizeof(gpuos_instr); ++b)
+    hsh = (hsh ^ reinterpret_cast<const unsigned char*>(code)[b]) * 0x100000001b3ull;
+  c->prog_hash[k] = hsh;
   c->n_progs = k + 1;
   *out_impl_id = GPUOS_IMPL_PROGRAM_BASE + k;
+  audit(c, GPUOS_AUDIT_DEFINE_PROGRAM, 0, GPUOS_IMPL_PROGRAM_BASE + k, 0);
   return GPUOS_OK;
 }
 
@@ -856,6 +882,7 @@ int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* 
   if (c->push) _mm_sfence();                 // write-combined stores: the slot before the version
   __atomic_store_n(&c->htable[op_id].version, 1u, __ATOMIC_RELEASE);
   bump_epoch(c, op_id, false);
+  audit(c, GPUOS_AUDIT_REGISTER, op_id, impl_id, 1);
   if (out_version) *out_version = 1;
   return GPUOS_OK;
 }
@@ -885,6 +912,7 @@ int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_
   __atomic_store_n(&o.impl, impl_id, __ATOMIC_RELAXED);
   __atomic_store_n(&o.version, v, __ATOMIC_RELEASE);
   o.prev_swap_head = c->head.load(std::memory_order_relaxed);
+  audit(c, impl_id == GPUOS_IMPL_FAIL ? GPUOS_AUDIT_KILL : GPUOS_AUDIT_SWAP, op_id, impl_id, v);
   if (out_version) *out_version = v;
   return GPUOS_OK;
 }
@@ -1208,6 +1236,16 @@ int gpuos_trace_origin(gpuos_ctx* c, uint64_t* host_ns) {
 
 int gpuos_kill_op(gpuos_ctx* c, uint32_t op_id, uint32_t* out_version) {
   return gpuos_swap_op(c, op_id, GPUOS_IMPL_FAIL, out_version);
+}
+
+int gpuos_audit_log(gpuos_ctx* c, uint64_t first, uint32_t n, gpuos_audit_record* out, uint64_t* out_total) {
+  if (!c || (!out && n)) return GPUOS_E_INVAL;
+  std::lock_guard<std::mutex> lk(c->prod_mu);
+  if (out_total) *out_total = c->audit_total;
+  const uint64_t oldest = c->audit_total - c->audit.size();
+  if (first < oldest || first + n > c->audit_total) return GPUOS_E_INVAL;
+  for (uint32_t i = 0; i < n; ++i) out[i] = c->audit[(size_t)(first - oldest) + i];
+  return GPUOS_OK;
 }
 
 int gpuos_task_plan(const gpuos_task* t, uint32_t impl, uint32_t out[4]) {

@@ -100,6 +100,7 @@ def lib():
         "gpuos_op_counts": (ctypes.c_int, [vp, vp]),
         "gpuos_trace_origin": (ctypes.c_int, [vp, P(u64)]),
         "gpuos_kill_op": (ctypes.c_int, [vp, u32, P(u32)]),
+        "gpuos_audit_log": (ctypes.c_int, [vp, u64, u32, vp, P(u64)]),
         "gpuos_strerror": (ctypes.c_char_p, [ctypes.c_int]),
         "gpuos_last_hip_error": (ctypes.c_char_p, []),
         "gpuos_abi_layout": (None, [vp]),
@@ -116,7 +117,7 @@ EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swa
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker", "gpuos_start_worker",
            "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_define_program", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
-           "gpuos_trace_origin", "gpuos_kill_op", "gpuos_strerror",
+           "gpuos_trace_origin", "gpuos_kill_op", "gpuos_audit_log", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
 
@@ -138,6 +139,10 @@ TRACE_DT = np.dtype([("ticket", "<u8"), ("t_dequeue", "<u8"), ("t_start", "<u8")
                      ("op_version", "<u4"), ("op_id", "<u2"), ("status", "i1"), ("reserved", "u1"),
                      ("nchunks", "<u4"), ("workgroup", "<u4")])
 assert TRACE_DT.itemsize == 48
+AUDIT_DT = np.dtype([("t_ns", "<u8"), ("head_ticket", "<u8"), ("kind", "<u4"), ("op_id", "<u4"), ("impl_id", "<u4"),
+                     ("version", "<u4"), ("n_instr", "<u4"), ("n_inputs", "<u4"), ("code_hash", "<u8")])
+assert AUDIT_DT.itemsize == 48
+AUDIT_REGISTER, AUDIT_SWAP, AUDIT_KILL, AUDIT_DEFINE_PROGRAM = 1, 2, 3, 4
 
 
 def device_info(device=0):
@@ -306,6 +311,15 @@ class Runtime:
     def op_counts(self):
         out = np.zeros(256, dtype=np.uint64)
         _check(lib().gpuos_op_counts(self._ctx, out.ctypes.data), "gpuos_op_counts")
+        return out
+
+    def audit_log(self):
+        """Every change of the operator table so far (gpuos_audit_log), oldest first."""
+        total = ctypes.c_uint64()
+        _check(lib().gpuos_audit_log(self._ctx, 0, 0, None, ctypes.byref(total)), "gpuos_audit_log")
+        first = max(0, total.value - 65536)
+        out = np.zeros(total.value - first, dtype=AUDIT_DT)
+        _check(lib().gpuos_audit_log(self._ctx, first, len(out), out.ctypes.data, None), "gpuos_audit_log")
         return out
 
     def trace_origin_ns(self):

@@ -181,8 +181,26 @@ int main() {
     CHECK(gpuos_wait(c, tk, 0) == GPUOS_E_BADOP);
     CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_E_BADOP);                // first error, reported once
     CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+    // the audit log has every change, in order: one register (make()), 40 swaps, the kill
+    uint64_t total = 0;
+    CHECK(gpuos_audit_log(c, 0, 0, nullptr, &total) == GPUOS_OK);
+    std::vector<gpuos_audit_record> log(total);
+    CHECK(gpuos_audit_log(c, 0, (uint32_t)total, log.data(), nullptr) == GPUOS_OK);
+    CHECK(gpuos_audit_log(c, 1, (uint32_t)total, log.data(), nullptr) == GPUOS_E_INVAL);
+    size_t swaps = 0, kills = 0, regs = 0;
+    uint32_t last_v = 0;
+    for (size_t i = 0; i < log.size(); ++i) {
+      if (i) CHECK(log[i].t_ns >= log[i - 1].t_ns && log[i].head_ticket >= log[i - 1].head_ticket);
+      if (log[i].op_id != 7) { regs += log[i].kind == GPUOS_AUDIT_REGISTER; continue; }
+      CHECK(log[i].version == last_v + 1);
+      last_v = log[i].version;
+      if (log[i].kind == GPUOS_AUDIT_REGISTER) { regs++; CHECK(log[i].version == 1 && log[i].head_ticket == 0); }
+      else if (log[i].kind == GPUOS_AUDIT_SWAP) { swaps++; CHECK(log[i].impl_id == (log[i].version % 2 ? GPUOS_IMPL_ADD : GPUOS_IMPL_SUB)); }
+      else if (log[i].kind == GPUOS_AUDIT_KILL) { kills++; CHECK(log[i].impl_id == GPUOS_IMPL_FAIL && log[i].version == 42 && log[i].head_ticket == tk); }
+    }
+    CHECK(swaps == 40 && kills == 1 && regs >= 1 && last_v == 42);
     CHECK(gpuos_shutdown(c) == GPUOS_OK);
-    std::printf("ok: 40 swaps under load, kill switch\n");
+    std::printf("ok: 40 swaps under load, kill switch, audit log\n");
   }
   // 4. shutdown with tasks in flight drains them; use after stop is refused; programs are table entries
   {
@@ -192,6 +210,16 @@ int main() {
     CHECK(gpuos_define_program(c, code, 2, 2, &impl) == GPUOS_OK && impl == GPUOS_IMPL_PROGRAM_BASE);
     CHECK(gpuos_register_op(c, 30, impl, nullptr) == GPUOS_OK);
     CHECK(gpuos_register_op(c, 31, impl + 1, nullptr) == GPUOS_E_BADOP);
+    {
+      uint64_t total = 0;
+      CHECK(gpuos_audit_log(c, 0, 0, nullptr, &total) == GPUOS_OK && total >= 2);
+      gpuos_audit_record two[2];
+      CHECK(gpuos_audit_log(c, total - 2, 2, two, nullptr) == GPUOS_OK);
+      uint64_t h = 0xcbf29ce484222325ull;
+      for (size_t b = 0; b < sizeof(code); ++b) h = (h ^ reinterpret_cast<const unsigned char*>(code)[b]) * 0x100000001b3ull;
+      CHECK(two[0].kind == GPUOS_AUDIT_DEFINE_PROGRAM && two[0].impl_id == impl && two[0].n_instr == 2 && two[0].n_inputs == 2 && two[0].code_hash == h);
+      CHECK(two[1].kind == GPUOS_AUDIT_REGISTER && two[1].op_id == 30 && two[1].impl_id == impl && two[1].code_hash == h && two[1].version == 1);
+    }
     code[1].a = 9;
     CHECK(gpuos_define_program(c, code, 2, 2, &impl) == GPUOS_E_INVAL);
     std::vector<gpuos_task> many(500, add_task(30, 4096));

@@ -157,7 +157,12 @@ def test_program_swapped_in_while_the_worker_runs():
             rt.swap_op(S.OP["ADD"], impl + 1)
         with pytest.raises(R.GpuosError):
             rt.define_program(code[:0], 2)
+        log = rt.audit_log()                              # the injection is on record: what, when, from which ticket on
     assert np.all(comps["status"] == 0)
+    assert list(log["kind"]) == [R.AUDIT_REGISTER] * len(s.table) + [R.AUDIT_DEFINE_PROGRAM, R.AUDIT_SWAP]
+    assert log["impl_id"][-2] == impl and log["n_instr"][-2] == 4 and log["head_ticket"][-2] == 1000
+    assert log["op_id"][-1] == S.OP["ADD"] and log["version"][-1] == 2 and log["head_ticket"][-1] == 2000
+    assert log["code_hash"][-1] == log["code_hash"][-2] != 0 and np.all(np.diff(log["t_ns"].astype(np.int64)) >= 0)
     ver = comps["op_version"]
     assert np.all(ver[:1000] == 1) and np.all(ver[2000:] == 2) and set(np.unique(ver[1000:2000])) <= {1, 2}
     s.swaps = [(2000, S.OP["ADD"], impl)]
