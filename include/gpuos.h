@@ -262,7 +262,14 @@ typedef struct gpuos_config {
                                        last this-many tickets (rounded up to a power of
                                        two, at most 1<<20) and count dispatched tasks per
                                        operator; 0: tracing off (default)               */
-  uint32_t reserved[4];
+  uint32_t markers;                 /* 1: annotate the host calls for a profiler's marker
+                                       trace (rocprofv3 --marker-trace): ranges around
+                                       gpuos_submit and gpuos_wait, marks at init, table
+                                       changes, stop and start.  The roctx library is
+                                       looked up at run time (the environment variable
+                                       GPUOS_ROCTX_LIBRARY names another one); without it
+                                       the option does nothing.  0: off (default)          */
+  uint32_t reserved[3];
 } gpuos_config;
 
 /* Fill *cfg with the defaults named above. */

@@ -20,6 +20,7 @@
 #include <vector>
 
 #include <immintrin.h>
+#include <dlfcn.h>
 #include <pthread.h>
 #include <sched.h>
 
@@ -38,6 +39,49 @@ bool hip_ok(hipError_t e, const char* what) {
   return false;
 }
 #define HIP_TRY(call) do { if (!hip_ok((call), #call)) return GPUOS_E_HIP; } while (0)
+
+// Profiler markers (paper Section 5.3: markers a timeline tool shows next to the kernels).  The
+// roctx entry points are looked up once, at the first use, in the profiler SDK's library or the
+// older one; a process that is not being profiled pays a null check.
+struct Roctx {
+  int (*push)(const char*) = nullptr;
+  int (*pop)() = nullptr;
+  void (*mark)(const char*) = nullptr;
+};
+const Roctx& roctx() {
+  static const Roctx r = [] {
+    Roctx x;
+    const char* names[3] = {std::getenv("GPUOS_ROCTX_LIBRARY"), "librocprofiler-sdk-roctx.so.1", "libroctx64.so.4"};
+    for (const char* n : names) {
+      if (!n || !*n) continue;
+      void* h = dlopen(n, RTLD_NOW | RTLD_GLOBAL);
+      if (!h) continue;
+      x.push = reinterpret_cast<int (*)(const char*)>(dlsym(h, "roctxRangePushA"));
+      x.pop = reinterpret_cast<int (*)()>(dlsym(h, "roctxRangePop"));
+      x.mark = reinterpret_cast<void (*)(const char*)>(dlsym(h, "roctxMarkA"));
+      if (x.push && x.pop && x.mark) break;
+      x = Roctx();
+    }
+    return x;
+  }();
+  return r;
+}
+struct MarkerRange {                    // a range on the calling thread for the lifetime of the object
+  bool on;
+  MarkerRange(bool enabled, const char* fmt, unsigned long long a = 0, unsigned long long b = 0) : on(enabled && roctx().push) {
+    if (!on) return;
+    char buf[96];
+    std::snprintf(buf, sizeof(buf), fmt, a, b);
+    roctx().push(buf);
+  }
+  ~MarkerRange() { if (on) roctx().pop(); }
+};
+void marker(bool enabled, const char* fmt, unsigned long long a = 0, unsigned long long b = 0, unsigned long long c3 = 0) {
+  if (!enabled || !roctx().mark) return;
+  char buf[96];
+  std::snprintf(buf, sizeof(buf), fmt, a, b, c3);
+  roctx().mark(buf);
+}
 
 inline uint64_t now_ns() {
   return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
@@ -801,6 +845,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
     g_live.push_back(c);
     if (!g_atexit_registered) { std::atexit(shutdown_all_at_exit); g_atexit_registered = true; }
   }
+  marker(cfg.markers != 0, "gpuos: worker launched, %llu workgroups, ring of %llu slots", c->workgroups, c->cap);
   *out = c;
   return GPUOS_OK;
 }
@@ -816,6 +861,13 @@ void audit(gpuos_ctx* c, uint32_t kind, uint32_t op_id, uint32_t impl_id, uint32
   if (impl_id >= GPUOS_IMPL_PROGRAM_BASE && impl_id - GPUOS_IMPL_PROGRAM_BASE < GPUOS_MAX_PROGRAMS) {
     const uint32_t k = impl_id - GPUOS_IMPL_PROGRAM_BASE;
     r.n_instr = c->prog_len[k]; r.n_inputs = c->prog_arity[k]; r.code_hash = c->prog_hash[k];
+  }
+  static const char* const what[5] = {"", "register", "swap", "kill", "define program"};
+  if (c->cfg.markers) {
+    char buf[96];
+    std::snprintf(buf, sizeof(buf), "gpuos %s: op %u impl %u version %u from ticket %llu", what[kind], op_id, impl_id, version,
+                  (unsigned long long)r.head_ticket);
+    if (roctx().mark) roctx().mark(buf);
   }
   if (c->audit.size() == kAuditKeep) c->audit.pop_front();
   c->audit.push_back(r);
@@ -920,6 +972,7 @@ int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_
 int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* out_first_ticket) {
   if (!c || (!tasks && n)) return GPUOS_E_INVAL;
   if (!c->worker_running || worker_exited(c)) return GPUOS_E_DEAD;
+  MarkerRange mr(c->cfg.markers != 0, "gpuos_submit %llu tasks", n);
   if (n == 0) {
     if (out_first_ticket) *out_first_ticket = c->head.load(std::memory_order_acquire);
     return GPUOS_OK;
@@ -986,6 +1039,7 @@ int gpuos_flush(gpuos_ctx* c) {
 
 int gpuos_wait(gpuos_ctx* c, uint64_t ticket, uint64_t timeout_ns) {
   if (!c) return GPUOS_E_INVAL;
+  MarkerRange mr(c->cfg.markers != 0, ticket == GPUOS_ALL ? "gpuos_wait all" : "gpuos_wait ticket %llu", ticket);
   if (c->worker_running) doorbell_locked(c);
   const bool all = ticket == GPUOS_ALL;
   const uint64_t head = c->head.load(std::memory_order_acquire);
@@ -1049,6 +1103,7 @@ int gpuos_set_yield_every(gpuos_ctx* c, uint32_t every) {
 
 int gpuos_stop_worker(gpuos_ctx* c) {
   if (!c) return GPUOS_E_INVAL;
+  MarkerRange mr(c->cfg.markers != 0, "gpuos_stop_worker");
   return stop_worker(c);
 }
 
@@ -1095,6 +1150,7 @@ int gpuos_start_worker(gpuos_ctx* c) {
     c->harvester_run.store(true);
     c->harvester = std::thread(harvester_main, c, sched_getcpu());
   }
+  marker(c->cfg.markers != 0, "gpuos: worker launched again at ticket %llu", head);
   return GPUOS_OK;
 }
 

@@ -262,6 +262,29 @@ int main() {
     CHECK(gpuos_shutdown(c) == GPUOS_OK);
     std::printf("ok: worker stopped and started 5 times, harvester thread %d\n", harv);
   }
+  // 6. profiler markers: with cfg.markers the calls are annotated through the marker library the
+  //    environment names (the test driver points it at a recorder); off by default
+  if (std::getenv("GPUOS_ROCTX_LIBRARY")) {
+    gpuos_config cfg;
+    gpuos_default_config(&cfg);
+    CHECK(cfg.markers == 0);
+    cfg.markers = 1;
+    cfg.wait_timeout_ms = 20000;
+    gpuos_ctx* c = nullptr;
+    CHECK(gpuos_init(&c, 16, &cfg) == GPUOS_OK);
+    uint32_t v = 0;
+    CHECK(gpuos_register_op(c, 7, GPUOS_IMPL_ADD, &v) == GPUOS_OK);
+    std::vector<gpuos_task> some(5, add_task(7, 256));
+    uint64_t tk = 0;
+    CHECK(gpuos_submit(c, some.data(), 5, &tk) == GPUOS_OK);
+    CHECK(gpuos_wait(c, tk + 4, 0) == GPUOS_OK);
+    CHECK(gpuos_swap_op(c, 7, GPUOS_IMPL_SUB, &v) == GPUOS_OK);
+    CHECK(gpuos_stop_worker(c) == GPUOS_OK);
+    CHECK(gpuos_start_worker(c) == GPUOS_OK);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: markers\n");
+  }
   CHECK(standin_errors() == 0);
   std::printf("all ok: %llu records through the stand-in, 0 protocol errors\n", (unsigned long long)standin_records());
   return 0;

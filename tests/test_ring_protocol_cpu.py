@@ -20,9 +20,21 @@ def test_host_protocol_against_a_device_stand_in(sanitizer, tmp_path):
     flags = ["-std=c++17", "-O1", "-g", "-pthread", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include"]
     if sanitizer == "thread":
         flags += ["-fsanitize=thread"]
-    subprocess.run(["g++"] + flags + SRC + ["-o", exe], check=True, cwd=ROOT)
-    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=1 exitcode=66 second_deadlock_stack=1")
+    subprocess.run(["g++"] + flags + SRC + ["-ldl", "-o", exe], check=True, cwd=ROOT)
+    recorder, record = str(tmp_path / "libroctx_recorder.so"), str(tmp_path / "markers.txt")
+    subprocess.run(["gcc", "-shared", "-fPIC", "-O1", os.path.join(HERE, "standin", "roctx_recorder.c"), "-o", recorder], check=True)
+    env = dict(os.environ, TSAN_OPTIONS="halt_on_error=1 exitcode=66 second_deadlock_stack=1",
+               GPUOS_ROCTX_LIBRARY=recorder, ROCTX_RECORD=record)
     r = subprocess.run([exe], capture_output=True, text=True, timeout=600, env=env)
     print(r.stdout[-3000:], r.stderr[-6000:])
     assert r.returncode == 0, "exit %d" % r.returncode
     assert "all ok" in r.stdout and "ThreadSanitizer" not in r.stderr
+    # only the context created with cfg.markers = 1 wrote markers: ranges are balanced and name the calls
+    lines = open(record).read().splitlines()
+    print("\n".join(lines))
+    assert sum(l.startswith("push") for l in lines) == sum(l.startswith("pop") for l in lines) == 4
+    want = ["mark gpuos: worker launched, 12 workgroups, ring of 16 slots", "mark gpuos register: op 7 impl 1 version 1 from ticket 0",
+            "push gpuos_submit 5 tasks", "push gpuos_wait ticket 4", "mark gpuos swap: op 7 impl 2 version 2 from ticket 5",
+            "push gpuos_stop_worker", "mark gpuos: worker launched again at ticket 5", "push gpuos_wait all"]
+    it = iter(lines)
+    assert all(any(l == w for l in it) for w in want), lines
