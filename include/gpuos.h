@@ -269,7 +269,11 @@ typedef struct gpuos_config {
                                        looked up at run time (the environment variable
                                        GPUOS_ROCTX_LIBRARY names another one); without it
                                        the option does nothing.  0: off (default)          */
-  uint32_t reserved[3];
+  uint32_t phase_timers;            /* 1: the dispatcher and the workers time every phase of
+                                       their work for gpuos_worker_stats (about a dozen reads
+                                       of the device clock per task: measurable on small
+                                       tasks); 0: only the counts are kept (default)        */
+  uint32_t reserved[2];
 } gpuos_config;
 
 /* Fill *cfg with the defaults named above. */
@@ -347,7 +351,8 @@ int gpuos_set_yield_every(gpuos_ctx* ctx, uint32_t every);
 int gpuos_shutdown(gpuos_ctx* ctx);
 
 /* Performance counters of the persistent kernel (paper Section 5.3), valid after
- * gpuos_stop_worker.  out[0..15] (HOST array): dispatcher batches, records, work
+ * gpuos_stop_worker.  The counts are always kept; the times are zero unless
+ * cfg.phase_timers was set.  out[0..15] (HOST array): dispatcher batches, records, work
  * units, then dispatcher time staging / resolving / writing / busy in 10 ns ticks,
  * dispatcher polls; then summed over all worker workgroups: work units executed
  * and 10 ns ticks spent waiting for work, fetching descriptors, waiting for

@@ -205,6 +205,7 @@ struct WorkerArgs {
   uint64_t*  opcount;        // host memory, GPUOS_MAX_OPS totals (tracing only)
   uint32_t   trace_mask;
   uint32_t   resume;         // 1: the context has run before; its counters continue where they stopped
+  uint32_t   timing;         // 1: time every phase (performance counters); 0: read the clock only where tracing or the idle exit need it
   uint64_t   resume_tickets; // tickets dequeued (and completed) by the earlier runs
 };
 

@@ -1538,11 +1538,20 @@ struct DispShared {
 
 // The 16 lanes that hold a record's 16-byte pieces: the weighted check sum of the whole record
 // (see record_check_weight), in every one of them.
+// Reading the clock is a memory-like operation: a dozen reads per task are measurable, so the phase
+// timers are an option and the clock is read only where something needs the value.
+DEV uint64_t clock_if(bool on) { return on ? wall_clock64() : 0ull; }
+
 DEV uint32_t record_piece_sum(const v4i& q, uint32_t part) {
   uint32_t x = 0;
 #pragma unroll
   for (uint32_t j = 0; j < 4; ++j) x += (uint32_t)q[j] * record_check_weight(4u * part + j);
-  x += __shfl_xor(x, 8, 16); x += __shfl_xor(x, 4, 16); x += __shfl_xor(x, 2, 16); x += __shfl_xor(x, 1, 16);
+  // sum over the 16 lanes of the row with DPP rotations (row_ror 8, 4, 2, 1): every lane ends with
+  // the whole sum, and unlike a shuffle nothing goes through the LDS crossbar
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x124, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x122, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x121, 0xf, 0xf, false);
   return x;
 }
 
@@ -1654,6 +1663,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
     __hip_atomic_store(&a.h->heartbeat, 1ull, __ATOMIC_RELAXED, SC_SYSTEM);
   }
   const bool tracing = a.trace != nullptr;
+  const bool timing = a.timing != 0;
   uint32_t passes_since_flush = 0;
   bool counts_dirty = false;
   uint64_t polls = 0;
@@ -1661,6 +1671,10 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   uint64_t st_batches = 0, st_records = 0, st_units = 0, st_stage = 0, st_resolve = 0, st_write = 0, st_busy = 0;
   uint64_t st_deferred = 0;
   uint64_t claimed = units_w;              // last value read from the claim counter (thread 0)
+  constexpr uint32_t kStagePieces = kDispatchBatch * 16u / kThreads;      // 16-byte pieces of a batch per thread
+  static_assert(kStagePieces * kThreads == kDispatchBatch * 16u, "a batch is staged in whole rounds of the workgroup");
+  uint64_t pre_base = ~0ull;               // first ticket of the records requested ahead (they wait in s->rec)
+  uint32_t pre_n = 0;                      // how many
   const rsrc_t rh = make_rsrc(a.hring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   while (true) {
@@ -1743,7 +1757,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         if (s->npend == 0) __builtin_amdgcn_s_sleep(8);
         break;                                                     // back to the poll loop (stop, table, heartbeat)
       }
-      const uint64_t tk0 = wall_clock64();
+      const uint64_t tk0 = clock_if(timing || tracing);
       // stage: 16 pieces of 16 bytes per record.  System-scope loads: an ordinary load of host
       // memory may hit a line the CU's vector cache kept from the previous lap of the ring.
       // Every record carries a check word (xor of its other 63 words, its ticket and a constant):
@@ -1754,14 +1768,23 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       first_batch = false;
       __syncthreads();
       for (uint32_t attempt = 0; attempt < kStageRetries; ++attempt) {
-        for (uint32_t p = tid; p < n * 16u; p += kThreads) {
-          const uint32_t rix = p >> 4, part = p & 15u;
-          if (s->bad[rix]) {                                       // uniform over the 16 lanes of a record
-            const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
-            const v4i q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
-            ((v4i*)&s->rec[rix])[part] = q;
-            const uint32_t x = record_piece_sum(q, part);
-            if (part == 0) s->ok[rix] = (x == record_check_seed(mirrored + rix)) ? 1u : 0u;
+        // With a backlog, the pieces of this batch were requested while the previous batch was
+        // being written out and already lie in s->rec (below): the first attempt only checks them.
+        const bool preloaded = attempt == 0 && pre_base == mirrored;
+#pragma unroll
+        for (uint32_t j = 0; j < kStagePieces; ++j) {
+          const uint32_t p = tid + j * kThreads;
+          if (p < n * 16u) {
+            const uint32_t rix = p >> 4, part = p & 15u;
+            if (s->bad[rix]) {                                     // uniform over the 16 lanes of a record
+              const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
+              const bool have = preloaded && p < pre_n * 16u;
+              const v4i q = have ? ((const v4i*)&s->rec[rix])[part]
+                                 : Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
+              if (!have) ((v4i*)&s->rec[rix])[part] = q;
+              const uint32_t x = record_piece_sum(q, part);
+              if (part == 0) s->ok[rix] = (x == record_check_seed(mirrored + rix)) ? 1u : 0u;
+            }
           }
         }
         __syncthreads();
@@ -1775,7 +1798,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         if (s->nbad == 0) break;
         __builtin_amdgcn_s_sleep(16);
       }
-      const uint64_t tk1 = wall_clock64();
+      const uint64_t tk1 = clock_if(timing);
       // a FENCE task starts a batch of its own: cut the batch in front of the first one after slot 0
       if (tid < 64) {
         const bool f = tid >= 1 && tid < n && (s->rec[tid].rflags & RF_FENCE);
@@ -1858,7 +1881,22 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         }
       }
       __syncthreads();
-      const uint64_t tk2 = wall_clock64();
+      const uint64_t tk2 = clock_if(timing);
+      // Request the next batch now, if the doorbell value already covers it: the loads travel while
+      // this batch is written to the mirror and published.  A piece that turns out incomplete fails
+      // its record's check word at staging time and is read again there.
+      pre_base = mirrored + n;
+      pre_n = tail > pre_base ? (uint32_t)((tail - pre_base) < kDispatchBatch ? (tail - pre_base) : kDispatchBatch) : 0u;
+      v4i pre_q[kStagePieces];
+#pragma unroll
+      for (uint32_t j = 0; j < kStagePieces; ++j) {
+        const uint32_t p = tid + j * kThreads;
+        pre_q[j] = v4i{0, 0, 0, 0};
+        if (p < pre_n * 16u) {
+          const uint32_t slot = (uint32_t)((pre_base + (p >> 4)) & a.cap_mask);
+          pre_q[j] = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + (p & 15u) * 16u);
+        }
+      }
       // write the records into the device mirror (write-through stores), held-back ones included
       for (uint32_t p = tid; p < n * 16u; p += kThreads) {
         const uint32_t rix = p >> 4, part = p & 15u;
@@ -1866,12 +1904,19 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, ((const v4i*)&s->rec[rix])[part]);
       }
       const uint32_t total = dispatcher_publish(a, s, s->npub, units_w);   // drains the stores above as well
+      // nothing reads this batch's staging any more (the mirror has it, held-back tasks were copied
+      // to the pending list): it takes the records requested ahead
+#pragma unroll
+      for (uint32_t j = 0; j < kStagePieces; ++j) {
+        const uint32_t p = tid + j * kThreads;
+        if (p < pre_n * 16u) ((v4i*)&s->rec[p >> 4])[p & 15u] = pre_q[j];
+      }
       units_w += total;
       mirrored += n;
       if (tid == 0) __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
-      idle_since = wall_clock64();
+      if (timing || a.idle_exit_ticks != 0) idle_since = wall_clock64();
       st_batches += 1; st_records += n; st_units += total;
-      st_stage += tk1 - tk0; st_resolve += tk2 - tk1; st_write += idle_since - tk2; st_busy += idle_since - tk0;
+      if (timing) { st_stage += tk1 - tk0; st_resolve += tk2 - tk1; st_write += idle_since - tk2; st_busy += idle_since - tk0; }
       units_w += dispatcher_service_pending(a, s, units_w);
       if (tracing) {
         counts_dirty = true;
@@ -1929,9 +1974,10 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
   const uint32_t tid = threadIdx.x;
   const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   uint64_t w_units = 0, w_wait = 0, w_fetch = 0, w_dep = 0, w_exec = 0, w_done = 0;
-  const uint64_t w_start = wall_clock64();
+  const bool timing = a.timing != 0, tracing = a.trace != nullptr;
+  const uint64_t w_start = clock_if(timing);
   while (true) {
-    const uint64_t c0 = wall_clock64();
+    const uint64_t c0 = clock_if(timing);
     // ---- claim one work unit (elected lane, atomic fetch-add) ----
     if (tid == 0) {
       const uint64_t g = __hip_atomic_fetch_add(&a.d->claim, 1ull, __ATOMIC_RELAXED, SC_AGENT);
@@ -1977,7 +2023,7 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       }
       return;
     }
-    const uint64_t c1 = wall_clock64();
+    const uint64_t c1 = clock_if(timing || tracing);
     // the unit is the same for the whole workgroup: keep its fields in scalar registers
     const uint32_t unit_lo = uni((uint32_t)s->unit), unit_hi = uni((uint32_t)(s->unit >> 32));
     const uint64_t unit = ((uint64_t)unit_hi << 32) | unit_lo;
@@ -1993,7 +2039,7 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
     int32_t status = r->status;
     const uint32_t impl = uni(r->impl);
     if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
-    const uint64_t c2 = wall_clock64();
+    const uint64_t c2 = clock_if(timing);
     // ---- dependencies: earlier tickets named by back-distance ----
     if ((r->dep[0] | r->dep[1] | r->dep[2]) != 0 && !(r->rflags & RF_DEPS_RESOLVED)) {
       if (tid == 0) {
@@ -2009,15 +2055,14 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       }
       __syncthreads();
     }
-    const uint64_t c3 = wall_clock64();
-    const bool tracing = a.trace != nullptr;
+    const uint64_t c3 = clock_if(timing);
     if (tracing && tid == 0 && chunk == 0 && r->nchunks > 1)
       __hip_atomic_store(&a.st[slot].t_first, c1, __ATOMIC_RELAXED, SC_SYSTEM);   // in memory before this chunk is counted
     // ---- execute ----
     if (status == GPUOS_OK) status = exec_chunk<POL_COHERENT>(r, impl, chunk, s->red, a.progs);
     drain_stores();                   // this wave's (write-through) stores have reached memory
     __syncthreads();                  // ... and so have the other three waves'
-    const uint64_t c4 = wall_clock64();
+    const uint64_t c4 = clock_if(timing || tracing);
     // ---- complete ----
     if (tid == 0) {
       const uint32_t nchunks = r->nchunks;
@@ -2051,8 +2096,9 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
       }
     }
     __syncthreads();                  // the descriptor in LDS may be overwritten after this
-    const uint64_t c5 = wall_clock64();
-    w_units += 1; w_wait += c1 - c0; w_fetch += c2 - c1; w_dep += c3 - c2; w_exec += c4 - c3; w_done += c5 - c4;
+    const uint64_t c5 = clock_if(timing);
+    w_units += 1;
+    if (timing) { w_wait += c1 - c0; w_fetch += c2 - c1; w_dep += c3 - c2; w_exec += c4 - c3; w_done += c5 - c4; }
   }
 }
 

@@ -811,6 +811,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   a.progs = c->progs;
   a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
   a.resume = 0; a.resume_tickets = 0;
+  a.timing = cfg.phase_timers ? 1u : 0u;
   c->wargs = a;
   if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
   if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);

@@ -193,7 +193,7 @@ def test_fence_and_in_place_updates():
 def test_introspection_yield_policy_and_stats():
     s = _simple_adds(200, 8192)
     dp = _dev(s)
-    with R.Runtime(0, **CFG) as rt:
+    with R.Runtime(0, phase_timers=1, **CFG) as rt:
         assert rt.worker_alive()
         q = rt.peek_queue()
         assert q.capacity == 4096 and q.workgroups >= 256 and q.head_submitted == 0 and q.heartbeat > 0
