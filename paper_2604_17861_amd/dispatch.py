@@ -10,9 +10,13 @@ on PyTorch's normal kernel-launch path.
     print(rt_mode.stats)
 
 The filter looks at the four things the paper names:
-  operation type     the aten overloads in `GpuosMode.handlers` (elementwise arithmetic, relu, exp,
-                     gelu, last-dim sum / max / min, last-dim softmax), float16 / bfloat16 / float32
-                     (int32 for add / sub / mul), ordinary strided tensors of at most 6 dims;
+  operation type     the aten overloads in `GpuosMode.handlers` (elementwise arithmetic with tensors
+                     and Python numbers, relu, exp, gelu, neg, abs, sqrt, sigmoid, silu, maximum,
+                     minimum, clamp_min / clamp_max, last-dim sum / max / min, last-dim softmax),
+                     float16 / bfloat16 / float32 (int32 for add / sub / mul of tensors), ordinary
+                     strided tensors of at most 6 dims.  Operators the built-in library lacks are
+                     defined on the live context as programs (`PROGRAMS`), the paper's run-time
+                     operator injection put to use;
   tensor size        1 <= numel(output) <= max_numel (reductions: the input's numel);
   execution context  an (operation, shape, dtype) signature is redirected from its `min_calls`-th
                      sighting on, so one-off operations stay on the normal path;
@@ -102,6 +106,12 @@ class GpuosMode(TorchDispatchMode):
         for name, impl in S.IMPL.items():                       # logical id = impl id + 32, as in streams.OP
             if name not in ("NONE",):
                 self.rt.register_op(S.OP[name], impl)
+        # operators the built-in library lacks are added the way the paper adds operators at run time:
+        # as programs defined on the live context and bound to logical ids of their own
+        self.op_id = {name: S.OP[name] for name in S.IMPL if name != "NONE"}
+        for k, (name, (code, n_in)) in enumerate(sorted(PROGRAMS.items())):
+            self.rt.register_op(_PROGRAM_OP_BASE + k, self.rt.define_program(code, n_in))
+            self.op_id[name] = _PROGRAM_OP_BASE + k
         self.max_numel, self.min_calls, self.batch = int(max_numel), int(min_calls), max(1, int(batch))
         self._buf = bytearray(self.batch * _TASK.size)
         self._tasks = np.frombuffer(self._buf, dtype=S.TASK_DT)
@@ -116,10 +126,14 @@ class GpuosMode(TorchDispatchMode):
         self.stats = dict(redirected=0, fallback_type=0, fallback_size=0, fallback_context=0, fallback_load=0,
                           fallback_paused=0, views=0, stream_syncs=0, host_waits=0, submits=0, pauses=0, resumes=0,
                           restarts=0, by_op={})
-        u, b, r = self._unary, self._binary, self._reduce
+        u, b, r, sc = self._unary, self._binary, self._reduce, self._scalar
         self.handlers = {
-            aten.add.Tensor: b("ADD"), aten.sub.Tensor: b("SUB"), aten.mul.Tensor: b("MUL"), aten.div.Tensor: b("DIV"),
+            aten.add.Tensor: b("ADD", "ADD_SCALAR"), aten.sub.Tensor: b("SUB", "SUB_SCALAR"), aten.mul.Tensor: b("MUL", "SCALE"),
+            aten.div.Tensor: b("DIV"), aten.maximum.default: b("MAXIMUM"), aten.minimum.default: b("MINIMUM"),
+            aten.rsub.Scalar: sc("RSUB_SCALAR"), aten.clamp_min.default: sc("CLAMP_MIN"), aten.clamp_max.default: sc("CLAMP_MAX"),
             aten.relu.default: u("RELU"), aten.exp.default: u("EXP"), aten.gelu.default: self._gelu,
+            aten.neg.default: u("NEG"), aten.abs.default: u("ABS"), aten.sqrt.default: u("SQRT"),
+            aten.sigmoid.default: u("SIGMOID"), aten.silu.default: u("SILU"),
             aten.sum.dim_IntList: r("SUM_LAST"), aten.amax.default: r("MAX_LAST"), aten.amin.default: r("MIN_LAST"),
             aten._softmax.default: self._softmax,
         }
@@ -144,7 +158,18 @@ class GpuosMode(TorchDispatchMode):
         x = args[0]
         return _Plan("GELU_TANH" if approx == "tanh" else "GELU_ERF", [x], tuple(x.shape), tuple(x.shape), x.dtype)
 
-    def _binary(self, name):
+    def _scalar(self, name):
+        """tensor (op) python number: the number travels in the descriptor's alpha."""
+        def plan(args, kwargs):
+            if len(args) != 2 or kwargs or not self._tensor_ok(args[0]) or args[0].dtype is torch.int32:
+                return None
+            x, c = args
+            if isinstance(c, (bool, complex)) or not isinstance(c, (int, float)):
+                return None
+            return _Plan(name, [x], tuple(x.shape), tuple(x.shape), x.dtype, alpha=float(c))
+        return plan
+
+    def _binary(self, name, with_number=None):
         def plan(args, kwargs):
             if len(args) != 2 or not isinstance(args[0], torch.Tensor):
                 return None
@@ -155,10 +180,11 @@ class GpuosMode(TorchDispatchMode):
             if not self._tensor_ok(a):
                 return None
             if not isinstance(o, torch.Tensor):
-                # tensor * python scalar is the scale operator; other scalar forms stay with PyTorch
-                if name != "MUL" or isinstance(o, (bool, complex)) or not isinstance(o, (int, float)) or a.dtype is torch.int32:
+                # tensor (op) python number: scale, or the one-instruction programs; a division stays with
+                # PyTorch (it multiplies by the reciprocal, which rounds differently)
+                if with_number is None or isinstance(o, (bool, complex)) or not isinstance(o, (int, float)) or a.dtype is torch.int32:
                     return None
-                return _Plan("SCALE", [a], tuple(a.shape), tuple(a.shape), a.dtype, alpha=float(o))
+                return _Plan(with_number, [a], tuple(a.shape), tuple(a.shape), a.dtype, alpha=float(o))
             if not self._tensor_ok(o):
                 return None
             dt = a.dtype if a.dtype is o.dtype else torch.result_type(a, o)
@@ -169,7 +195,7 @@ class GpuosMode(TorchDispatchMode):
             # 16-bit operand under a float32 result); a float32 0-dim operand under a 16-bit result is not.
             if any(t.dtype is not dt and dt is not torch.float32 for t in (a, o)):
                 return None
-            if dt is torch.int32 and name not in _INT_OK:
+            if dt is torch.int32 and name not in _INT_OK:         # (the programs are float operators)
                 return None
             shape = tuple(a.shape)
             if shape != tuple(o.shape):
@@ -324,7 +350,7 @@ class GpuosMode(TorchDispatchMode):
             ops.append(_NO_TENSOR)
         deps += [0] * (3 - len(deps))
         sz = list(size) + [1] * (S.MAX_DIMS - nd)
-        _TASK.pack_into(self._buf, self._staged * _TASK.size, S.OP[p.impl], nd, len(p.inputs), p.flags, *sz,
+        _TASK.pack_into(self._buf, self._staged * _TASK.size, self.op_id[p.impl], nd, len(p.inputs), p.flags, *sz,
                         *ops[0], *ops[1], *ops[2], *o, p.alpha, *deps)
         for k in keys:
             self._touch[k] = me
@@ -424,6 +450,19 @@ class GpuosMode(TorchDispatchMode):
         if self._own and self.rt is not None:
             self.rt.shutdown()
         self.rt = None
+
+
+P_ = S.program
+_PROGRAM_OP_BASE = 160
+# name -> (instructions, inputs).  r0..r2 are the inputs, r3 the descriptor's alpha, r4..r7 start at zero.
+PROGRAMS = {
+    "ADD_SCALAR": (P_(("ADD", 0, 0, 3)), 1), "SUB_SCALAR": (P_(("SUB", 0, 0, 3)), 1), "RSUB_SCALAR": (P_(("SUB", 0, 3, 0)), 1),
+    "CLAMP_MIN": (P_(("MAX", 0, 0, 3)), 1), "CLAMP_MAX": (P_(("MIN", 0, 0, 3)), 1),
+    "NEG": (P_(("NEG", 0, 0)), 1), "ABS": (P_(("ABS", 0, 0)), 1), "SQRT": (P_(("SQRT", 0, 0)), 1),
+    "MAXIMUM": (P_(("MAX", 0, 0, 1)), 2), "MINIMUM": (P_(("MIN", 0, 0, 1)), 2),
+    "SIGMOID": (P_(("NEG", 4, 0), ("EXP", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5), ("DIV", 0, 5, 4)), 1),
+    "SILU": (P_(("NEG", 4, 0), ("EXP", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5), ("DIV", 0, 0, 4)), 1),
+}
 
 
 def _overloads(*names):

@@ -51,8 +51,9 @@ def test_ordinary_kernels_and_small_copies_run_beside_the_resident_worker():
 def program(a, b, row, h):
     y = torch.relu(a + b) * 0.5
     z = (y - row) * b.t()
-    w = z.t() / (a.abs() + 1.0)                     # abs, add-scalar: PyTorch's kernels between redirected ones
-    m = w @ w.t()                                   # PyTorch's matmul reads a redirected result
+    w = z.t() / (a.abs() + 1.0)                     # abs and add-a-number: programs the mode defined on its context
+    c = torch.cumsum(w, 0)                          # PyTorch's kernel between redirected ones, reading a pending result
+    m = (w + c * 0.0) @ w.t()                       # PyTorch's matmul reads a redirected result
     r = torch.relu(m[:64, :64]) - a[:64, :64]       # redirected operations read PyTorch's result (through views)
     u = (h + h) * h
     v = u + a[: h.shape[0], : h.shape[1]]
@@ -70,7 +71,8 @@ def test_exact_program_is_bit_identical_to_eager_and_runs_on_the_worker():
         for k, (g, w) in enumerate(zip(got, want)):
             same(g, w, exact=k not in (3, 4), tol=1e-4)      # exact but for what passes through the matmul (its kernel choice may differ run to run)
         st = mode.stats
-        assert st["redirected"] == 11 and st["by_op"] == {"ADD": 3, "RELU": 2, "SCALE": 1, "SUB": 2, "MUL": 2, "DIV": 1}, st
+        assert st["redirected"] == 15 and st["by_op"] == {"ADD": 4, "RELU": 2, "SCALE": 2, "SUB": 2, "MUL": 2, "DIV": 1, "ABS": 1,
+                                                          "ADD_SCALAR": 1}, st
         assert st["stream_syncs"] >= 2 and st["host_waits"] >= 1 and st["pauses"] == 1 and st["resumes"] == 1, st
         t0 = time.perf_counter()
         counts = mode.rt.op_counts()                          # flushed by the dispatcher when the ring runs empty
@@ -78,7 +80,7 @@ def test_exact_program_is_bit_identical_to_eager_and_runs_on_the_worker():
             time.sleep(0.01)
             counts = mode.rt.op_counts()
         assert int(counts.sum()) == st["redirected"]
-        assert int(counts[S.OP["ADD"]]) == 3 and int(counts[S.OP["DIV"]]) == 1
+        assert int(counts[S.OP["ADD"]]) == 4 and int(counts[S.OP["DIV"]]) == 1 and int(counts[mode.op_id["ABS"]]) == 1
     finally:
         mode.close()
 
@@ -188,5 +190,27 @@ def test_large_matrix_products_get_the_whole_gpu_and_an_unknown_large_kernel_is_
         same(z, (a + b) * 0.5)
         assert mode.stats["pauses"] == 0 and mode.stats["redirected"] == 2, mode.stats
         assert mode.stats["restarts"] == (1 if dt > 0.1 else 0), (mode.stats, dt)
+    finally:
+        mode.close()
+
+
+def test_operators_defined_as_programs_on_the_live_context():
+    x, y = gen(13, 9, 400) * 3, gen(14, 9, 400)
+    h = x.half()
+
+    def f():
+        return (x + 1.5, x - 0.25, 2.0 - x, h + 3, -x, x.abs(), torch.maximum(x, y), torch.minimum(x, y[0]),
+                x.clamp_min(0.5), x.clamp_max(-0.5), x * 3, x.abs().sqrt(), torch.sigmoid(x), torch.nn.functional.silu(x), torch.sigmoid(h))
+    want = f()
+    torch.cuda.current_stream().synchronize()
+    mode = GpuosMode(**CFG)
+    try:
+        with mode:
+            got = f()
+        for k, (a, b) in enumerate(zip(got, want)):
+            same(a, b, exact=k < 11, tol=1e-6 if a.dtype is torch.float32 else 2e-3)
+        assert mode.stats["fallback_type"] == 0 and mode.stats["redirected"] == 16, mode.stats
+        log = mode.rt.audit_log()                   # the programs are on record like every other table change
+        assert int((log["kind"] == R.AUDIT_DEFINE_PROGRAM).sum()) == 12
     finally:
         mode.close()
