@@ -373,8 +373,10 @@ int gpuos_worker_elapsed_ms(gpuos_ctx* ctx, float* out_ms);
  * included), programs and counters continue; gpuos_worker_elapsed_ms then covers
  * the latest run only.  This is how a caller hands the whole GPU to a kernel that
  * cannot start beside the worker (see the conventions at the top) and takes it
- * back: stop, run that kernel, start.  GPUOS_OK also when the worker is running;
- * GPUOS_E_DEAD if the earlier run lost work or could not be joined.  Like
+ * back: stop, run that kernel, start.  Tasks that were published just as the worker
+ * left by itself (their gpuos_wait reports GPUOS_E_DEAD) are still in the ring and
+ * are executed by the new run: start the worker, wait again.  GPUOS_OK also when the
+ * worker is running; GPUOS_E_DEAD if the earlier run lost work or could not be joined.  Like
  * init / stop / shutdown: one thread, and no other thread inside a call. */
 int gpuos_start_worker(gpuos_ctx* ctx);
 

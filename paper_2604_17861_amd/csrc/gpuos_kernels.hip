@@ -2082,7 +2082,11 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
           const uint64_t tdq = ((uint64_t)r->t_dequeue[1] << 32) | r->t_dequeue[0];
           __hip_atomic_store(&tr->t_dequeue, tdq - origin, __ATOMIC_RELAXED, SC_SYSTEM);
           __hip_atomic_store(&tr->t_start, t_start - origin, __ATOMIC_RELAXED, SC_SYSTEM);
-          __hip_atomic_store(&tr->t_done, c4 - origin, __ATOMIC_RELAXED, SC_SYSTEM);
+          // The clock is read here, once this workgroup knows it finished the task: the time taken
+          // right after its own chunk (c4) can lie before the start of chunk 0 when this workgroup's
+          // count arrives late (seen once in a few thousand multi-chunk tasks).
+          const uint64_t t_done = nchunks > 1 ? wall_clock64() : c4;
+          __hip_atomic_store(&tr->t_done, t_done - origin, __ATOMIC_RELAXED, SC_SYSTEM);
           const uint64_t w4 = (uint64_t)r->version | ((uint64_t)r->op_id << 32) | ((uint64_t)(uint8_t)(int8_t)status << 48);
           __hip_atomic_store((uint64_t*)&tr->op_version, w4, __ATOMIC_RELAXED, SC_SYSTEM);
           const uint64_t w5 = (uint64_t)nchunks | ((uint64_t)blockIdx.x << 32);

@@ -645,8 +645,10 @@ int stop_worker(gpuos_ctx* c) {
   if (c->worker_joined) return GPUOS_OK;
   int rc = GPUOS_OK;
   if (c->worker_running) {
-    doorbell_locked(c);
-    rc = wait_floor(c, c->head.load(), c->wait_ns);           // drain
+    if (!worker_exited(c)) {                                  // (one that left by itself is only joined)
+      doorbell_locked(c);
+      rc = wait_floor(c, c->head.load(), c->wait_ns);         // drain
+    }
     bump_epoch(c, 0xff, true);                                // signal worker exit
     const uint64_t t0 = now_ns();
     hipError_t q;
@@ -1116,8 +1118,10 @@ int gpuos_start_worker(gpuos_ctx* c) {
     if (rc != GPUOS_OK) return rc;
   }
   if (!c->worker_joined) return GPUOS_E_DEAD;                           // an earlier stop timed out: the kernel may still be there
-  const uint64_t head = c->head.load(std::memory_order_acquire);
-  if (c->floor.load(std::memory_order_acquire) != head) return GPUOS_E_DEAD;   // work was lost: not a state to continue from
+  // A worker that leaves drains what it has dequeued.  Records published after its last look at the
+  // doorbell (an idle exit can race with a submit) are still in the ring: the new worker takes them.
+  const uint64_t head = __atomic_load_n(&c->h->dispatched, __ATOMIC_ACQUIRE);
+  if (c->floor.load(std::memory_order_acquire) != head) return GPUOS_E_DEAD;   // dequeued work was lost: not a state to continue from
   HIP_TRY(hipSetDevice(c->device));
   __atomic_store_n(&c->h->exit_code, 0u, __ATOMIC_RELEASE);
   __atomic_store_n(&c->h->heartbeat, (uint64_t)0, __ATOMIC_RELEASE);

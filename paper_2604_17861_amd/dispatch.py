@@ -422,13 +422,24 @@ class GpuosMode(TorchDispatchMode):
         an older task may read the same memory)."""
         self._submit()
         while ticket >= self._floor:
-            self.rt.wait(ticket)
+            self._wait_one(ticket)
             self.stats["host_waits"] += 1
             self._floor = max(self._floor, int(self.rt.peek_queue().completed))
             if ticket >= self._floor:
-                self.rt.wait(self._floor)              # the oldest one still running
+                self._wait_one(self._floor)            # the oldest one still running
                 self._floor = max(self._floor, int(self.rt.peek_queue().completed))
         self._retire()
+
+    def _wait_one(self, ticket):
+        try:
+            self.rt.wait(ticket)
+        except R.GpuosError as e:
+            if e.status != R.E_DEAD:
+                raise
+            # the worker's idle exit raced with the submit: the records are in the ring, the next run takes them
+            self.rt.start_worker()
+            self.stats["restarts"] += 1
+            self.rt.wait(ticket)
 
     def synchronize(self):
         """Submit what is staged and wait until every redirected operation has completed."""

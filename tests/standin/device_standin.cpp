@@ -30,6 +30,9 @@ struct Worker {
 std::mutex g_mu;
 std::map<void*, Worker*> g_workers;               // by stream
 std::atomic<uint64_t> g_errors{0}, g_records{0}, g_retries{0};
+// Test hook: the consumer leaves "by itself" (exit code 2, as after an idle time-out) in front of this
+// ticket, whatever the doorbell says: the race of an idle exit with a submit, made deterministic.
+std::atomic<uint64_t> g_leave_before{~0ull};
 
 void consumer(gpuos::WorkerArgs a, Worker* w) {
   using namespace gpuos;
@@ -58,6 +61,8 @@ void consumer(gpuos::WorkerArgs a, Worker* w) {
     const bool stopping = (ew & 3u) != 0;
     if (stopping) tail = __atomic_load_n(&a.bell->tail, __ATOMIC_ACQUIRE);
     if (tail - mirrored > cap) g_errors.fetch_add(1);                           // the producer overran the ring
+    const uint64_t leave = g_leave_before.load();
+    if (tail > leave) tail = leave > mirrored ? leave : mirrored;               // ... and does not look at what lies beyond
     while (mirrored < tail) {
       const uint32_t n = (uint32_t)((tail - mirrored) < 64 ? (tail - mirrored) : 64);
       uint64_t comp[64];
@@ -98,6 +103,12 @@ void consumer(gpuos::WorkerArgs a, Worker* w) {
       w->done.store(true, std::memory_order_release);
       return;
     }
+    if (mirrored >= leave) {
+      g_leave_before.store(~0ull);
+      __atomic_store_n(&a.h->exit_code, 2u, __ATOMIC_RELEASE);
+      w->done.store(true, std::memory_order_release);
+      return;
+    }
     if ((polls & 15u) == 0) std::this_thread::yield();
   }
 }
@@ -107,6 +118,7 @@ extern "C" {
 uint64_t standin_errors() { return g_errors.load(); }
 uint64_t standin_records() { return g_records.load(); }
 uint64_t standin_retries() { return g_retries.load(); }
+void standin_leave_before(uint64_t ticket) { g_leave_before.store(ticket); }
 }
 
 namespace gpuos {

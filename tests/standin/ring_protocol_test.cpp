@@ -12,6 +12,7 @@
 #include "../../paper_2604_17861_amd/csrc/gpuos_internal.h"
 
 extern "C" uint64_t standin_errors();
+extern "C" void standin_leave_before(uint64_t ticket);
 extern "C" uint64_t standin_records();
 
 #define CHECK(cond) do { if (!(cond)) { std::printf("FAILED %s:%d: %s\n", __FILE__, __LINE__, #cond); std::exit(1); } } while (0)
@@ -261,6 +262,32 @@ int main() {
     }
     CHECK(gpuos_shutdown(c) == GPUOS_OK);
     std::printf("ok: worker stopped and started 5 times, harvester thread %d\n", harv);
+  }
+  // 5b. an idle exit that races with a submit: the worker leaves without having seen the last
+  //     doorbell; the wait says so, and the worker started again executes what was left in the ring
+  {
+    gpuos_ctx* c = make(16);
+    std::vector<gpuos_task> some(10, add_task(7, 256));
+    uint64_t tk = 0;
+    CHECK(gpuos_submit(c, some.data(), 4, &tk) == GPUOS_OK && tk == 0);
+    CHECK(gpuos_wait(c, 3, 0) == GPUOS_OK);
+    standin_leave_before(6);                                          // tickets 4, 5 will be served, 6.. not
+    CHECK(gpuos_submit(c, some.data(), 10, &tk) == GPUOS_OK && tk == 4);
+    CHECK(gpuos_wait(c, 5, 0) == GPUOS_OK);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_E_DEAD);
+    CHECK(gpuos_worker_alive(c) == 0);
+    gpuos_queue_state q;
+    CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK && q.completed == 6 && q.claimed == 6 && q.head_submitted == 14);
+    CHECK(gpuos_start_worker(c) == GPUOS_OK);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+    CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK && q.completed == 14 && q.claimed == 14);
+    std::vector<gpuos_completion> comp(14);
+    CHECK(gpuos_get_completions(c, 0, 14, comp.data()) == GPUOS_OK);
+    for (uint64_t t = 0; t < 14; ++t) CHECK(comp[t].ticket == t && comp[t].status == 0);
+    CHECK(gpuos_submit(c, some.data(), 3, &tk) == GPUOS_OK && tk == 14);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: tasks stranded by an idle exit are executed after a restart\n");
   }
   // 6. profiler markers: with cfg.markers the calls are annotated through the marker library the
   //    environment names (the test driver points it at a recorder); off by default

@@ -317,7 +317,8 @@ def test_device_trace_ring_and_operator_counts():
         tr = rt.trace(t0 + 1000, 1000)                         # the last 1000 of 2000: inside a ring of 4096 (>= capacity)
         comps = rt.completions(t0 + 1000, 1000)
         assert np.array_equal(tr["ticket"], np.arange(t0 + 1000, t0 + 2000, dtype=np.uint64))
-        assert np.all(tr["t_dequeue"] <= tr["t_start"]) and np.all(tr["t_start"] <= tr["t_done"])
+        odd = tr[(tr["t_dequeue"] > tr["t_start"]) | (tr["t_start"] > tr["t_done"])]
+        assert len(odd) == 0, odd
         assert np.all(tr["t_done"] < 100e6 * 20)               # ticks since the worker started: well under the 20 s of the test
         assert np.array_equal(tr["op_version"], comps["op_version"]) and np.all(tr["status"] == 0)
         assert np.array_equal(tr["op_id"], s.tasks["op_id"][1000:2000])
@@ -360,14 +361,18 @@ def test_device_trace_ring_and_operator_counts():
         assert len(rt.trace(t0 + 6000 - 64, 64)) == 64
         with pytest.raises(R.GpuosError):
             rt.trace(t0, 1)                                    # overwritten long ago
-        # the device clock lines up with the host clock: a lone task is dequeued after the host rang
-        # the doorbell and done before the host saw its completion word (slack: the PCIe write of the first heartbeat and the host's polling step)
+        # The device clock lines up with the host clock: a lone task is dequeued after the host rang the
+        # doorbell and done before the host saw its completion word.  The two transit times together do
+        # not depend on the clock offset at all; each alone is off by the offset's error, which is the
+        # PCIe write of the first heartbeat plus whatever the host thread was doing when it arrived.
         lat = rt.run_serial(dp2.tasks, 0, 50)
         first = t0 + 6000
         tr3, c3 = rt.trace(first, 50), rt.completions(first, 50)
         deq = tr3["t_dequeue"].astype(np.int64) * 10 + rt.trace_origin_ns() - c3["t_submit_ns"].astype(np.int64)
         fin = c3["t_done_ns"].astype(np.int64) - (tr3["t_done"].astype(np.int64) * 10 + rt.trace_origin_ns())
-        assert -6000 < np.median(deq) < 20000 and -6000 < np.median(fin) < 20000, (np.median(deq), np.median(fin), np.median(lat))
+        both = float(np.median(deq + fin))
+        assert 500 < both < 30000, (both, np.median(lat))
+        assert -50000 < np.median(deq) < 80000 and -50000 < np.median(fin) < 80000, (np.median(deq), np.median(fin))
     with R.Runtime(0, **CFG) as rt:
         with pytest.raises(R.GpuosError):
             rt.op_counts()
