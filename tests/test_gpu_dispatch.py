@@ -214,3 +214,25 @@ def test_operators_defined_as_programs_on_the_live_context():
         assert int((log["kind"] == R.AUDIT_DEFINE_PROGRAM).sum()) == 12
     finally:
         mode.close()
+
+
+def test_device_wide_synchronisation_under_the_mode_returns_after_the_idle_exit():
+    """torch.cuda.synchronize() waits for every stream, the worker's included: under the mode it
+    returns when the worker's idle exit fires (200 ms by default) instead of never, and the next
+    redirected operation starts the worker again."""
+    a, b = gen(15, 64, 64), gen(16, 64, 64)
+    torch.cuda.current_stream().synchronize()
+    mode = GpuosMode(wait_timeout_ms=20000)
+    try:
+        with mode:
+            z = (a + b) * 2.0
+            mode.synchronize()
+            t0 = time.perf_counter()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            w = z - a
+        assert dt < 3.0, dt
+        same(w, (a + b) * 2.0 - a)
+        assert mode.stats["restarts"] == 1 and mode.stats["redirected"] == 3, mode.stats
+    finally:
+        mode.close()
