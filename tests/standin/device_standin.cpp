@@ -11,6 +11,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <atomic>
+#include <chrono>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -33,6 +34,8 @@ std::atomic<uint64_t> g_errors{0}, g_records{0}, g_retries{0};
 // Test hook: the consumer leaves "by itself" (exit code 2, as after an idle time-out) in front of this
 // ticket, whatever the doorbell says: the race of an idle exit with a submit, made deterministic.
 std::atomic<uint64_t> g_leave_before{~0ull};
+// Test hook: the consumer sleeps this long before it serves the next batch (a device that is busy).
+std::atomic<uint32_t> g_stall_ms{0};
 
 void consumer(gpuos::WorkerArgs a, Worker* w) {
   using namespace gpuos;
@@ -64,6 +67,7 @@ void consumer(gpuos::WorkerArgs a, Worker* w) {
     const uint64_t leave = g_leave_before.load();
     if (tail > leave) tail = leave > mirrored ? leave : mirrored;               // ... and does not look at what lies beyond
     while (mirrored < tail) {
+      if (const uint32_t ms = g_stall_ms.exchange(0)) std::this_thread::sleep_for(std::chrono::milliseconds(ms));
       const uint32_t n = (uint32_t)((tail - mirrored) < 64 ? (tail - mirrored) : 64);
       uint64_t comp[64];
       for (uint32_t i = 0; i < n; ++i) {
@@ -119,6 +123,7 @@ uint64_t standin_errors() { return g_errors.load(); }
 uint64_t standin_records() { return g_records.load(); }
 uint64_t standin_retries() { return g_retries.load(); }
 void standin_leave_before(uint64_t ticket) { g_leave_before.store(ticket); }
+void standin_stall_ms(uint32_t ms) { g_stall_ms.store(ms); }
 }
 
 namespace gpuos {

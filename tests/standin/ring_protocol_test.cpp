@@ -2,6 +2,7 @@
 // (device_standin.cpp), meant to be built with -fsanitize=thread.  Prints one line per check and
 // exits non-zero on the first failure.
 #include <atomic>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -13,6 +14,7 @@
 
 extern "C" uint64_t standin_errors();
 extern "C" void standin_leave_before(uint64_t ticket);
+extern "C" void standin_stall_ms(uint32_t ms);
 extern "C" uint64_t standin_records();
 
 #define CHECK(cond) do { if (!(cond)) { std::printf("FAILED %s:%d: %s\n", __FILE__, __LINE__, #cond); std::exit(1); } } while (0)
@@ -288,6 +290,25 @@ int main() {
     CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
     CHECK(gpuos_shutdown(c) == GPUOS_OK);
     std::printf("ok: tasks stranded by an idle exit are executed after a restart\n");
+  }
+  // 5c. a wait with a time limit on a device that is busy: GPUOS_E_TIMEOUT, nothing lost, the same
+  //     wait without a limit succeeds; a ticket that was never issued is refused
+  {
+    gpuos_ctx* c = make(16);
+    gpuos_task t = add_task(7, 256);
+    uint64_t tk = 0;
+    standin_stall_ms(400);
+    CHECK(gpuos_submit(c, &t, 1, &tk) == GPUOS_OK);
+    const auto t0 = std::chrono::steady_clock::now();
+    CHECK(gpuos_wait(c, tk, 30ull * 1000 * 1000) == GPUOS_E_TIMEOUT);
+    const double waited = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    CHECK(waited > 0.025 && waited < 0.3);
+    CHECK(gpuos_worker_alive(c) == 1);
+    CHECK(gpuos_wait(c, tk + 1, 0) == GPUOS_E_INVAL);
+    CHECK(gpuos_wait(c, tk, 0) == GPUOS_OK);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 1) == GPUOS_OK);                     // complete already: no time is needed
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: wait with a time limit\n");
   }
   // 6. profiler markers: with cfg.markers the calls are annotated through the marker library the
   //    environment names (the test driver points it at a recorder); off by default
