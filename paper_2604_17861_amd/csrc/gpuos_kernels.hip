@@ -663,13 +663,31 @@ template <int RIMPL> DEV float red_finish(float acc, bool nan) {
   return nan ? __builtin_nanf("") : acc;
 }
 
+// Two elements per step for max / min: one three-operand max (min) and ONE unordered compare of
+// the two new elements with each other, which is true exactly when either is a NaN.  The hardware
+// max / min skip quiet NaNs, which is fine: the flag decides the result (red_finish).  Three
+// operations per element (compare, compare, select) become one; the 16-bit reductions were
+// bound by them.
+template <int RIMPL> DEV float red_step2(float acc, float x0, float x1, bool& nan) {
+  nan = nan || __builtin_isunordered(x0, x1);
+  float r;
+  if (RIMPL == GPUOS_IMPL_MAX_LAST) asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(acc), "v"(x0), "v"(x1));
+  else asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(acc), "v"(x0), "v"(x1));
+  return r;
+}
+
 template <int RIMPL, int DT>
 DEV float red_vector(const v4i& q, uint32_t f0, uint32_t lo, uint32_t hi, bool edge, float acc, bool& nan) {
   // q holds elements f0 .. f0+V-1 of the flat run; the row is [lo, hi)
   using E = Elem<DT>;
   if (!edge) {
+    if (RIMPL == GPUOS_IMPL_SUM_LAST) {
 #pragma unroll
-    for (int k = 0; k < E::V; ++k) acc = red_step<RIMPL>(acc, E::get(q, k), nan);
+      for (int k = 0; k < E::V; ++k) acc = red_step<RIMPL>(acc, E::get(q, k), nan);
+    } else {
+#pragma unroll
+      for (int k = 0; k < E::V; k += 2) acc = red_step2<RIMPL>(acc, E::get(q, k), E::get(q, k + 1), nan);
+    }
   } else {
 #pragma unroll
     for (int k = 0; k < E::V; ++k)
