@@ -2,8 +2,9 @@
  * gpuos.h -- C ABI of the MI355X-native GPUOS hot path.
  *
  * One long-lived ("persistent") HIP worker kernel drains a host-fed ring of
- * task descriptors and executes small tensor operations (elementwise ops and
- * last-dim reductions over <=6-D strided / broadcast tensors) through a
+ * task descriptors and executes small tensor operations (elementwise ops,
+ * last-dim reductions and fused row operations over <=6-D strided / broadcast
+ * tensors, and operators defined at run time as short programs) through a
  * versioned dual-slot operator table.  The design follows the paper's
  * Section 4.1 (ring buffer channel, persistent kernel executor, dynamic
  * operator table), Section 4.2 (task submission protocol: acquire slot,
@@ -27,7 +28,7 @@
  *     what they say; a back-distance that reaches before the call's first
  *     ticket names whatever another thread may have enqueued there, so only
  *     a single producer may use those.  gpuos_init / gpuos_shutdown /
- *     gpuos_stop_worker are for one thread;
+ *     gpuos_stop_worker / gpuos_start_worker are for one thread;
  *   - while a context is alive the worker kernel is resident on its own
  *     non-blocking stream: the caller must not call hipDeviceSynchronize(),
  *     hipFree() or anything else that waits for "all streams" before
@@ -41,7 +42,11 @@
  *     16 KiB or less (larger ones go to the DMA engines): use 4 only for a
  *     process that runs nothing else on the GPU, and then move small results
  *     with a GPUOS_IMPL_COPY task into pinned, device-mapped host memory or
- *     read them after gpuos_stop_worker().
+ *     read them after gpuos_stop_worker().  Kernels that need more registers
+ *     or local memory than the worker leaves (large matrix products do, even at
+ *     3 and 2 workgroups per compute unit) wait until it has left: hand them
+ *     the GPU with gpuos_stop_worker() ... gpuos_start_worker(), or let
+ *     cfg.idle_exit_ms do so.
  */
 #ifndef GPUOS_H_
 #define GPUOS_H_
