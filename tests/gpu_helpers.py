@@ -9,7 +9,6 @@ import numpy as np
 import torch
 
 import oracle
-from paper_2604_17861_amd import runtime as R
 from paper_2604_17861_amd import streams as S
 from helpers import ulp_distance, np_dtype, bf16_bits_to_f32
 

@@ -8,7 +8,6 @@ import numpy as np
 import pytest
 import torch
 
-import oracle
 from paper_2604_17861_amd import runtime as R
 from paper_2604_17861_amd import streams as S
 

@@ -2,7 +2,6 @@
 element by element on the same seeded inputs."""
 import numpy as np
 import pytest
-import torch
 
 from paper_2604_17861_amd import runtime as R
 from paper_2604_17861_amd import streams as S

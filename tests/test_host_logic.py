@@ -6,7 +6,6 @@ import os
 import re
 
 import numpy as np
-import pytest
 
 import oracle
 from paper_2604_17861_amd import runtime as R

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 from paper_2604_17861_amd import streams as S
-from helpers import HostPools, run_oracle
+from helpers import HostPools
 
 
 def test_config1_shape_and_determinism():
