@@ -141,7 +141,8 @@ class GpuosMode(TorchDispatchMode):
     # ---- eligibility: operation type ------------------------------------------------------------
     def _tensor_ok(self, t):
         return (type(t) is torch.Tensor and t.device == self.device and t.dtype in _DT and t.layout is torch.strided
-                and t.dim() <= S.MAX_DIMS and not t.is_conj() and not t.is_neg())
+                and t.dim() <= S.MAX_DIMS and not t.is_conj() and not t.is_neg()
+                and (t.dim() == 0 or max(t.stride()) < (1 << 24)))      # the ring record holds 32-bit extents
 
     def _unary(self, name):
         def plan(args, kwargs):

@@ -317,3 +317,12 @@ def test_operators_defined_as_programs_on_the_live_context():
     assert m.stats["fallback_type"] == 0 and m.stats["redirected"] == 16, m.stats
     assert m.stats["by_op"]["ADD_SCALAR"] == 2 and m.stats["by_op"]["SIGMOID"] == 2 and m.stats["by_op"]["SCALE"] == 1
     assert len(m.rt.programs) == 12 and min(m.op_id[n] for n in m.rt.programs and ("SILU", "NEG")) >= 160
+
+
+def test_views_with_huge_strides_stay_with_pytorch():
+    big = torch.zeros(1 << 25)
+    v = big[:: 1 << 24]                                   # two elements, 16M apart
+    m = mode()
+    with m:
+        r = v + v
+    assert m.stats["redirected"] == 0 and m.stats["fallback_type"] >= 1 and r.shape == (2,)
