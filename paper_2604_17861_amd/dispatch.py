@@ -66,6 +66,7 @@ _TASK = struct.Struct("<HBBI6q" + "Q6qBB6x" * 4 + "f3H6x")
 assert _TASK.size == S.TASK_DT.itemsize
 _NO_TENSOR = (0, 0, 0, 0, 0, 0, 0, 0, 0)
 _ZEROS = (0,) * S.MAX_DIMS
+_MAX_EXTENT = (1 << 31) - 4096          # elements a tensor view may span (gpuos_submit rejects more)
 aten = torch.ops.aten
 
 
@@ -142,7 +143,8 @@ class GpuosMode(TorchDispatchMode):
     def _tensor_ok(self, t):
         return (type(t) is torch.Tensor and t.device == self.device and t.dtype in _DT and t.layout is torch.strided
                 and t.dim() <= S.MAX_DIMS and not t.is_conj() and not t.is_neg()
-                and (t.dim() == 0 or max(t.stride()) < (1 << 24)))      # the ring record holds 32-bit extents
+                and (t.dim() == 0 or max(t.stride()) * t.numel() < _MAX_EXTENT       # quick bound, then the extent itself:
+                     or sum((n - 1) * st for n, st in zip(t.shape, t.stride())) < _MAX_EXTENT))   # the ring record holds 32-bit offsets
 
     def _unary(self, name):
         def plan(args, kwargs):

@@ -319,10 +319,15 @@ def test_operators_defined_as_programs_on_the_live_context():
     assert len(m.rt.programs) == 12 and min(m.op_id[n] for n in m.rt.programs and ("SILU", "NEG")) >= 160
 
 
-def test_views_with_huge_strides_stay_with_pytorch():
-    big = torch.zeros(1 << 25)
-    v = big[:: 1 << 24]                                   # two elements, 16M apart
+def test_views_that_span_more_than_the_record_can_address_stay_with_pytorch():
+    big = torch.empty((1 << 31) + 8, dtype=torch.float16)         # 4 GiB of address space; only four elements are touched
+    far = big[:: 1 << 31]                                         # two elements, 2^31 apart: beyond a record's 32-bit offsets
+    near = big[:: 1 << 24][:2]                                    # two elements, 16M apart: fine
+    far.fill_(1.0); near.fill_(2.0)
     m = mode()
     with m:
-        r = v + v
-    assert m.stats["redirected"] == 0 and m.stats["fallback_type"] >= 1 and r.shape == (2,)
+        r = far + far
+        q = near + near
+    assert m.stats["redirected"] == 1 and m.stats["by_op"] == {"ADD": 1}, m.stats
+    assert r.tolist() == [4.0, 2.0]                               # far[0] is near[0], filled last with 2
+    assert q.tolist() == [4.0, 4.0]
