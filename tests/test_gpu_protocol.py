@@ -507,3 +507,58 @@ def test_wait_with_a_time_limit():
         assert rt.wait(t0 + 63, check=False) == R.OK
         assert rt.wait(timeout_ns=1, check=False) == R.OK        # everything is complete: no time needed
     assert compare_with_oracle(s, dp.download())["max_ulp"] == 0
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5])
+def test_randomized_call_sequences(seed):
+    """A seeded random walk over the host calls -- submits of 1..40 tasks with and without a
+    doorbell, waits for earlier tickets, queue peeks, yield-policy changes, the worker stopped and
+    started, read-outs of the completion log -- on a random ring size and placement.  Whatever the
+    interleaving, every ticket completes once, in the log in order, and the results are the oracle's."""
+    from gpu_helpers import compare_with_oracle
+    import parity_cases as P
+    rng = np.random.default_rng(1000 + seed)
+    s = P.config2_reduced()
+    dp = _dev(s)
+    n = len(s)
+    cap = int(rng.choice([4, 64, 4096]))
+    cfg = dict(CFG, push_ring=int(rng.integers(0, 2)), harvester_thread=int(rng.integers(0, 2)),
+               trace_entries=int(rng.choice([0, 256])))
+    print("seed", seed, "capacity", cap, cfg, flush=True)
+    done = 0
+    with R.Runtime(cap, **cfg) as rt:
+        rt.register_table(s.table)
+        steps = 0
+        while done < n:
+            steps += 1
+            a = rng.random()
+            if a < 0.55:
+                k = int(min(n - done, rng.integers(1, 41)))
+                first = rt.submit(dp.tasks, done, k, flush=bool(rng.random() < 0.7))
+                assert first == done
+                done += k
+            elif a < 0.70 and done:
+                rt.wait(int(rng.integers(0, done)))
+            elif a < 0.78:
+                q = rt.peek_queue()
+                assert q.head_submitted == done and q.completed <= q.claimed <= q.tail_published <= done
+            elif a < 0.84:
+                rt.set_yield_every(int(rng.choice([0, 0, 3, 50])))
+            elif a < 0.90 and done:
+                lo = int(rng.integers(0, done))
+                rt.wait(lo)
+                c = rt.completions(lo, 1)
+                assert c["ticket"][0] == lo and c["status"][0] == 0
+            elif a < 0.95:
+                rt.stop_worker()                                  # drains what was submitted (a doorbell is rung)
+                assert rt.peek_queue().completed == done
+                rt.start_worker()
+            else:
+                rt.flush()
+        rt.wait()
+        comps = rt.completions(0, n)
+        assert rt.worker_alive()
+    print("steps", steps, flush=True)
+    assert np.array_equal(comps["ticket"], np.arange(n, dtype=np.uint64)) and np.all(comps["status"] == 0)
+    assert np.all(comps["t_done_ns"] >= comps["t_submit_ns"])
+    compare_with_oracle(s, dp.download(), versions=comps["op_version"])
