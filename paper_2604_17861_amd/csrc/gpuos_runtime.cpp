@@ -653,8 +653,11 @@ int stop_worker(gpuos_ctx* c) {
     const uint64_t t0 = now_ns();
     hipError_t q;
     while ((q = hipStreamQuery(c->stream)) == hipErrorNotReady) {
-      if (now_ns() - t0 > c->wait_ns) break;
-      std::this_thread::sleep_for(std::chrono::microseconds(50));
+      const uint64_t waited = now_ns() - t0;
+      if (waited > c->wait_ns) break;
+      // the kernel leaves within tens of microseconds of the flag: poll tightly at first (a caller
+      // that hands the GPU to another kernel waits for exactly this), back off afterwards
+      if (waited > 300000ull) std::this_thread::sleep_for(std::chrono::microseconds(50));
     }
     if (q == hipErrorNotReady) rc = GPUOS_E_TIMEOUT;
     else if (q != hipSuccess) { hip_ok(q, "worker kernel"); rc = GPUOS_E_HIP; }
