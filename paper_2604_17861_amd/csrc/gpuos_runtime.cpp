@@ -83,6 +83,26 @@ void marker(bool enabled, const char* fmt, unsigned long long a = 0, unsigned lo
   roctx().mark(buf);
 }
 
+// The producers' lock.  It is held for a few microseconds at a time (the ring writes of one batch),
+// and a waiter is usually the next producer with its batch already packed: spin on the flag first
+// (test-and-test-and-set with pause), and only give the time slice away when that takes long (the
+// holder lost its core, or waits for room in a full ring).  A futex-based mutex puts waiters to
+// sleep after a few hundred nanoseconds and pays a wake-up on every hand-over.
+class SpinMutex {
+ public:
+  void lock() {
+    for (uint32_t spins = 0;; ++spins) {
+      if (!flag_.load(std::memory_order_relaxed) && !flag_.exchange(true, std::memory_order_acquire)) return;
+      if (spins < 4096) __builtin_ia32_pause();
+      else sched_yield();
+    }
+  }
+  bool try_lock() { return !flag_.load(std::memory_order_relaxed) && !flag_.exchange(true, std::memory_order_acquire); }
+  void unlock() { flag_.store(false, std::memory_order_release); }
+ private:
+  std::atomic<bool> flag_{false};
+};
+
 inline uint64_t now_ns() {
   return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
              std::chrono::steady_clock::now().time_since_epoch()).count();
@@ -492,7 +512,7 @@ struct gpuos_ctx {
   uint32_t trace_mask = 0;
   uint64_t origin_host_ns = 0;               // host clock when the worker's first heartbeat was seen
   // producer state
-  std::mutex prod_mu;                        // producers: ticket reservation, ring writes, doorbell, table changes
+  SpinMutex prod_mu;                         // producers: ticket reservation, ring writes, doorbell, table changes
   std::mutex harvest_mu;                     // one harvester at a time
   std::atomic<uint64_t> head{0};             // tickets written (changed under prod_mu)
   std::atomic<uint64_t> published{0};        // tickets behind the doorbell
@@ -598,7 +618,7 @@ void doorbell(gpuos_ctx* c) {
   if (c->push) _mm_sfence();                                    // ... and push the doorbell out of the write-combining buffer
 }
 void doorbell_locked(gpuos_ctx* c) {
-  std::lock_guard<std::mutex> lk(c->prod_mu);
+  std::lock_guard<SpinMutex> lk(c->prod_mu);
   doorbell(c);
 }
 
@@ -902,7 +922,7 @@ int gpuos_define_program(gpuos_ctx* c, const gpuos_instr* code, uint32_t n_instr
     std::memcpy(&img.code[2 * i + 1], &in.imm, 4);
   }
   img.n_instr = n_instr; img.n_inputs = n_inputs; img.ready = kProgramReady;
-  std::lock_guard<std::mutex> lk(c->prod_mu);
+  std::lock_guard<SpinMutex> lk(c->prod_mu);
   if (!c->worker_running && !c->worker_joined) return GPUOS_E_DEAD;
   if (c->n_progs >= GPUOS_MAX_PROGRAMS) return GPUOS_E_FULL;
   const uint32_t k = c->n_progs;
@@ -928,7 +948,7 @@ int gpuos_define_program(gpuos_ctx* c, const gpuos_instr* code, uint32_t n_instr
 int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
   if (impl_id == GPUOS_IMPL_NONE || (impl_id >= GPUOS_IMPL_COUNT && impl_id < GPUOS_IMPL_PROGRAM_BASE)) return GPUOS_E_BADOP;
-  std::lock_guard<std::mutex> lk(c->prod_mu);
+  std::lock_guard<SpinMutex> lk(c->prod_mu);
   if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   if (c->ops[op_id].version != 0) return GPUOS_E_INVAL;            // already bound: use swap_op
   if (!c->worker_running && !c->worker_joined) return GPUOS_E_DEAD;   // a stopped worker reads the table when it is started again
@@ -947,7 +967,7 @@ int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* 
 
 int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
-  std::lock_guard<std::mutex> lk(c->prod_mu);
+  std::lock_guard<SpinMutex> lk(c->prod_mu);
   if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   OpInfo& o = c->ops[op_id];
   if (o.version == 0) return GPUOS_E_BADOP;
@@ -1004,9 +1024,13 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
     if (rc != GPUOS_OK) return rc;
     for (int k = 0; k < 3; ++k)
       if (t.dep[k] >= c->cap) return GPUOS_E_INVAL;
+    // The part of the check word that does not depend on the ticket: the weighted sum of the
+    // other 63 words, with the record's ticket field zero (the ticket enters through the seed only).
+    staged[i].ticket = 0;
+    staged[i].check = record_check_sum(reinterpret_cast<const uint32_t*>(&staged[i]), 63);
   }
   // pass 2 (one producer at a time): reserve n consecutive tickets and write the records
-  std::lock_guard<std::mutex> lk(c->prod_mu);
+  std::lock_guard<SpinMutex> lk(c->prod_mu);
   uint64_t head = c->head.load(std::memory_order_relaxed);
   for (uint32_t i = 0; i < n; ++i)
     for (int k = 0; k < 3; ++k)
@@ -1024,8 +1048,7 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
       if (rc != GPUOS_OK) return rc;
     }
     Record& rec = staged[i];
-    rec.ticket = 0;                                               // enters the check through the seed only
-    rec.check = record_check_seed(head) - record_check_sum(reinterpret_cast<const uint32_t*>(&rec), 63);
+    rec.check = record_check_seed(head) - rec.check;              // pass 1 left the sum of the other 63 words here
     std::memcpy(&c->hring[head & c->mask], &rec, sizeof(Record));
     ++head;
   }
@@ -1129,7 +1152,7 @@ int gpuos_start_worker(gpuos_ctx* c) {
   __atomic_store_n(&c->h->exit_code, 0u, __ATOMIC_RELEASE);
   __atomic_store_n(&c->h->heartbeat, (uint64_t)0, __ATOMIC_RELEASE);
   {
-    std::lock_guard<std::mutex> lk(c->prod_mu);
+    std::lock_guard<SpinMutex> lk(c->prod_mu);
     bump_epoch(c, 0xff, false);                                         // lowers the stop bit; the new worker reads the whole table
   }
   WorkerArgs a = c->wargs;
@@ -1304,7 +1327,7 @@ int gpuos_kill_op(gpuos_ctx* c, uint32_t op_id, uint32_t* out_version) {
 
 int gpuos_audit_log(gpuos_ctx* c, uint64_t first, uint32_t n, gpuos_audit_record* out, uint64_t* out_total) {
   if (!c || (!out && n)) return GPUOS_E_INVAL;
-  std::lock_guard<std::mutex> lk(c->prod_mu);
+  std::lock_guard<SpinMutex> lk(c->prod_mu);
   if (out_total) *out_total = c->audit_total;
   const uint64_t oldest = c->audit_total - c->audit.size();
   if (first < oldest || first + n > c->audit_total) return GPUOS_E_INVAL;
