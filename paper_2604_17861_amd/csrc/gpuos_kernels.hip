@@ -1538,8 +1538,16 @@ struct PendEntry {
   uint16_t pad;
 };
 
+// A staged record with a pitch of 68 words instead of 64: when the 64 lanes of a wavefront read the
+// same field of 64 different records (the resolve and split steps do little else), a pitch of 64
+// words puts all of them on one LDS bank; with 68 they spread over 16.
+struct alignas(16) StagedRecord : Record {
+  uint32_t pitch_pad[4];
+};
+static_assert(sizeof(StagedRecord) == 272, "staging pitch");
+
 struct DispShared {
-  Record rec[kDispatchBatch];              // 16 KB staging of the batch being mirrored
+  StagedRecord rec[kDispatchBatch];        // 17 KB staging of the batch being mirrored
   uint64_t entry[GPUOS_MAX_OPS];           // shadow of the device table: current {impl, version}
   PubEntry pub[kDispatchBatch];            // tasks whose units are published in this pass (<= 64)
   uint32_t ubeg[kDispatchBatch + 1];       // exclusive prefix of their nchunks
