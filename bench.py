@@ -6,7 +6,8 @@ dispatch, execution, completion harvesting) over the second configuration's stre
 elementwise tasks submitted in batches of 64.  `value` is persistent-queue tasks/s on that stream
 with all tensors resident in HBM.  The same JSON line carries
   * the same stream issued as one ordinary kernel launch per task (throughput and latency mode),
-  * p50 / p99 submit->done latency of the persistent path (loaded, and unloaded ping-pong),
+  * p50 / p99 submit->done latency, one task of the stream at a time on both paths (p50_us against
+    per_launch_p50_us), and of every task when the stream is submitted flat out (loaded_p50_us),
   * the other small-op streams (first and fourth configuration) against per-op launches,
   * "roofline": the persistent kernel over the fifth configuration (bandwidth stream): algorithmic
     bytes / kernel duration from HIP events on the worker's stream, against 8 TB/s,
@@ -299,9 +300,13 @@ def main():
     per_launch_tps = max(1, args.steps // 4) * len(s2) / (time.perf_counter() - t0)
     _, lat = R.launch_per_op(dp2.tasks, s2.table, sync_each=True, count=3000)
     log("config2 per-launch: %.0f tasks/s, p50 %.1f us" % (per_launch_tps, percentile_us(lat, 50)))
+    # the like-for-like of the per-launch latency (launch + synchronize, one task at a time): the same
+    # tasks through the persistent kernel one at a time (submit + wait)
+    u50, u99 = bench_pingpong(R, s2, dp2, n=3000)
+    log("config2 one task at a time: persistent p50 %.1f us, p99 %.1f us" % (u50, u99))
     out.update(value=res["tasks_per_s"], ms_per_step=1e3 * res["seconds"] / args.steps,
                per_launch_tasks_per_s=per_launch_tps, speedup_vs_per_launch=res["tasks_per_s"] / per_launch_tps,
-               p50_us=res["p50_us"], p99_us=res["p99_us"],
+               p50_us=u50, p99_us=u99, loaded_p50_us=res["p50_us"], loaded_p99_us=res["p99_us"],
                per_launch_p50_us=percentile_us(lat, 50), per_launch_p99_us=percentile_us(lat, 99),
                workgroups=res["workgroups"], ring=res["ring"])
 
@@ -429,7 +434,12 @@ def main():
                 per_launch_tasks_per_s=out["per_launch_tasks_per_s"],
                 speedup_vs_per_launch=out["speedup_vs_per_launch"],
                 p50_us=out["p50_us"], p99_us=out["p99_us"], per_launch_p50_us=out["per_launch_p50_us"],
-                per_launch_p99_us=out["per_launch_p99_us"], extras=extras,
+                per_launch_p99_us=out["per_launch_p99_us"],
+                loaded_p50_us=out["loaded_p50_us"], loaded_p99_us=out["loaded_p99_us"],
+                latency_note="p50_us / p99_us and per_launch_*: submit -> completion seen by the host, one task of the "
+                             "stream at a time, on both paths; loaded_*: every task of the timed steps, submitted flat "
+                             "out in batches of 64, queueing in a ring of 4096 included",
+                extras=extras,
                 roofline=roofline, cpu_baseline=cpu_baseline)
     print(json.dumps(line), flush=True)
     if args.report:
@@ -466,7 +476,9 @@ def write_reports(directory, R, line):
         "config2": dict(seed=1, tasks=10000, persistent_tasks_per_s=line["value"],
                         per_launch_tasks_per_s=line["per_launch_tasks_per_s"], speedup=line["speedup_vs_per_launch"],
                         p50_us=line["p50_us"], p99_us=line["p99_us"], per_launch_p50_us=line["per_launch_p50_us"],
-                        per_launch_p99_us=line["per_launch_p99_us"], oracle_tasks_per_s=line["cpu_baseline"]["value"],
+                        per_launch_p99_us=line["per_launch_p99_us"], loaded_p50_us=line["loaded_p50_us"],
+                        loaded_p99_us=line["loaded_p99_us"], latency_note=line["latency_note"],
+                        oracle_tasks_per_s=line["cpu_baseline"]["value"],
                         oracle_sample=line["cpu_baseline"]["sample"], host_ring_mode=ex.get("host_ring_mode"), multi_producer=ex.get("multi_producer")),
         "config1": dict(seed=0, tasks=1000, pingpong=ex.get("pingpong"), **ex.get("config1", {})),
         "config3": dict(seed=2, tasks=12000, **ex.get("config3", {})),
