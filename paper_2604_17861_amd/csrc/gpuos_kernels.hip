@@ -1653,22 +1653,37 @@ DEV uint32_t dispatcher_service_pending(const WorkerArgs& a, DispShared* s, uint
   const uint32_t tid = threadIdx.x;
   const uint32_t np = s->npend;
   if (np == 0) return 0;
-  if (tid < np) s->ready[tid] = deps_complete(a, s->pend[tid].ticket, s->pend[tid].dep) ? 1u : 0u;
-  __syncthreads();
-  if (tid == 0) {                                  // split into ready (at most 64 per call) / still pending
-    uint32_t k = 0, j = 0;
-    for (uint32_t i = 0; i < np; ++i) {
-      if (s->ready[i] && k < kDispatchBatch) s->pub[k++] = s->pend[i].pub;   // the rest waits for the next call
-      else { if (j != i) s->pend[j] = s->pend[i]; ++j; }
-    }
-    s->npub = k;
-    s->npend = j;
+  static_assert(kPendMax <= 128 && kPendMax <= kThreads, "one pending entry per thread of the first two wavefronts");
+  // One entry per thread: is it ready, and where does it go?  The first kDispatchBatch ready entries
+  // move to the publish list, everything else closes ranks in the pending list; both keep their order
+  // (ticket order).  Positions come from a ballot inside each of the two wavefronts plus the count
+  // of the first one.
+  const uint32_t lane = tid & 63u, wave = tid >> 6;
+  PendEntry e;
+  bool ready = false;
+  if (tid < np) {
+    e = s->pend[tid];
+    ready = deps_complete(a, e.ticket, e.dep);
   }
-  __syncthreads();
-  const uint32_t npub = s->npub;
-  if (npub == 0) return 0;
+  uint64_t m_ready = 0;
+  if (tid < 128u) {
+    m_ready = __ballot(ready);
+    if (lane == 0) s->ready[wave] = (uint32_t)__popcll(m_ready);
+  }
+  __syncthreads();                                 // the counts; and every entry is in its thread's registers
+  const uint32_t ready0 = s->ready[0], ready_all = ready0 + s->ready[1];
+  if (tid < np) {
+    const uint32_t ready_before = (uint32_t)__popcll(m_ready & ((1ull << lane) - 1ull)) + (wave ? ready0 : 0u);
+    const uint32_t taken_before = ready_before < kDispatchBatch ? ready_before : kDispatchBatch;
+    if (ready && ready_before < kDispatchBatch) s->pub[ready_before] = e.pub;      // the rest waits for the next call
+    else s->pend[tid - taken_before] = e;
+  }
+  const uint32_t npub = ready_all < kDispatchBatch ? ready_all : kDispatchBatch;
+  __syncthreads();                                 // the lists are complete (and s->ready may be reused)
+  if (tid == 0) s->npend = np - npub;
+  if (npub == 0) { __syncthreads(); return 0; }
   order_loads();
-  return dispatcher_publish(a, s, npub, units_w);
+  return dispatcher_publish(a, s, npub, units_w);  // its barriers also cover the new pending count
 }
 
 DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
