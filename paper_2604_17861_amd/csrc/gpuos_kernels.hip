@@ -164,6 +164,8 @@ template <int POL> DEV void store_rt(void* p, uint32_t i, uint32_t dt, float f) 
 // and rounded once: an fp32 evaluation cannot hold 2 ulp for x < 0, where
 // 1 + tanh(u) and 1 + erf(u) cancel.
 // ---------------------------------------------------------------------------
+constexpr uint32_t kNoLoad = 0x7ffffff0u;   // a buffer offset past every resource: the load returns 0 and moves no data
+
 template <int IMPL> struct Op;
 template <> struct Op<GPUOS_IMPL_ADD> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x + y; } };
 template <> struct Op<GPUOS_IMPL_SUB> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x - y; } };
@@ -457,29 +459,43 @@ PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float*
       }
     __syncthreads();
   }
-  for (uint32_t v = threadIdx.x; v < nvec; v += kThreads) {
-    const uint32_t i = begin + v * V;
-    const uint32_t row = i / C, col = i - row * C;
-    v4i q[3];
-    float s[3];
-    uint32_t region = 0;
+  // UN vectors per thread and round: all their loads are issued before the first result is needed
+  // (one vector per round left a single request in flight per operand)
+  constexpr int UN = 4;
+  for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * UN) {
+    v4i q[UN][3];
+    float s[UN][3];
 #pragma unroll
-    for (int k = 0; k < N; ++k) {
-      if (kind[k] == K_FULL) q[k] = M::ld16(rs[k], v * 16u);
-      else if (kind[k] == K_ROWVEC) q[k] = M::ld16(rs[k], col * E::ES);
-      else if (staged) { s[k] = s_scratch[region + row - row_first]; region += row_cnt; }
-      else s[k] = load_rt<POL>(p[k], row * st0[k], dt[k]);
+    for (int u = 0; u < UN; ++u) {
+      const uint32_t v = v0 + (uint32_t)u * kThreads;
+      const bool act = v < nvec;
+      const uint32_t i = begin + (act ? v : 0u) * V;
+      const uint32_t row = i / C, col = i - row * C;
+      uint32_t region = 0;
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        if (kind[k] == K_FULL) q[u][k] = M::ld16(rs[k], act ? v * 16u : kNoLoad);
+        else if (kind[k] == K_ROWVEC) q[u][k] = M::ld16(rs[k], act ? col * E::ES : kNoLoad);
+        else if (staged) { s[u][k] = s_scratch[region + row - row_first]; region += row_cnt; }
+        else s[u][k] = load_rt<POL>(p[k], row * st0[k], dt[k]);
+      }
     }
-    v4i res;
-    float xv[3][V], xo[V];
 #pragma unroll
-    for (int e = 0; e < V; ++e)
+    for (int u = 0; u < UN; ++u) {
+      const uint32_t v = v0 + (uint32_t)u * kThreads;
+      if (v < nvec) {
+        v4i res;
+        float xv[3][V], xo[V];
 #pragma unroll
-      for (int k = 0; k < 3; ++k) xv[k][e] = k < N ? ((kind[k] == K_ROWSCALAR) ? s[k] : E::get(q[k], e)) : 0.f;
-    apply_vec<IMPL, V>(xv[0], xv[1], xv[2], alpha, xo);
+        for (int e = 0; e < V; ++e)
 #pragma unroll
-    for (int e = 0; e < V; ++e) E::put(res, e, xo[e]);
-    M::st16(ro, v * 16u, res);
+          for (int k = 0; k < 3; ++k) xv[k][e] = k < N ? ((kind[k] == K_ROWSCALAR) ? s[u][k] : E::get(q[u][k], e)) : 0.f;
+        apply_vec<IMPL, V>(xv[0], xv[1], xv[2], alpha, xo);
+#pragma unroll
+        for (int e = 0; e < V; ++e) E::put(res, e, xo[e]);
+        M::st16(ro, v * 16u, res);
+      }
+    }
   }
   if (staged) __syncthreads();        // the scratch may be reused by the next chunk
 }
@@ -696,7 +712,6 @@ DEV float red_vector(const v4i& q, uint32_t f0, uint32_t lo, uint32_t hi, bool e
   return acc;
 }
 
-constexpr uint32_t kNoLoad = 0x7ffffff0u;   // a buffer offset past every resource: the load returns 0 and moves no data
 
 struct RedArgs {       // what a row-reduction variant is called with (plain values: see lds_arg)
   const char* base;    // first byte of the run: the tensor base advanced to the chunk's first vector
