@@ -369,6 +369,20 @@ def main():
                                        per_launch_gbps=b3f / pl3f / 1e9, tasks=len(s3f))
         log("config3 fused:", extras["config3_fused"])
         del dp3f
+        # ---- the paper's micro-benchmark shape: sequences of 100 dependent small operations ----------
+        seq = {}
+        for il in (1, 16, 256):
+            sq = S.sequences(n_seq=1000, length=100, interleave=il)
+            dpq = DevicePools(sq, torch)
+            rq = bench_persistent(R, sq, dpq, 1, 0)
+            seq["persistent_interleave_%d_tasks_per_s" % il] = rq["tasks_per_s"]
+            if il == 1:
+                t0 = time.perf_counter()
+                R.launch_per_op(dpq.tasks, sq.table)
+                seq["per_launch_tasks_per_s"] = len(sq) / (time.perf_counter() - t0)
+            del dpq
+        extras["sequences_100x1000"] = seq
+        log("sequences of 100 dependent operations x 1000:", seq)
         # ---- fourth configuration (hot swaps while running) -----------------------------------
         s4 = S.config4(n_tasks=args.cfg4_tasks)
         dp4 = DevicePools(s4, torch)

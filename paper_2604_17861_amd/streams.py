@@ -246,6 +246,44 @@ def config1(n_tasks=1000, numel=1024, seed=0) -> Stream:
                   info=dict(seed=seed, numel=numel))
 
 
+def sequences(n_seq=1000, length=100, interleave=1, seed=5) -> Stream:
+    """The shape of the paper's elementwise micro-benchmark (Section 6.1): n_seq sequences of `length`
+    dependent elementwise operations on an fp32 tensor of 1K-16K elements (numel log-uniform per
+    sequence).  Step t of a sequence reads what step t-1 wrote (two buffers per sequence, used in
+    turn) and names it as its dependency.  Sequences are independent; `interleave` of them are
+    issued round-robin (1: one sequence after the other, the order an eager framework produces;
+    more: what a caller with several requests in flight produces).  Operations cycle through
+    x + c, x * c, relu(x), 0.99 x, x - c with a per-sequence operand c in [-1, 1]: all exactly
+    rounded, values stay bounded."""
+    rng = np.random.default_rng(seed)
+    n = n_seq * length
+    tasks, pool_of = new_tasks(n)
+    numel = np.round(np.exp(rng.uniform(np.log(1024), np.log(16384), n_seq))).astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(numel)])[:-1] * 4                 # byte offset of sequence s in every pool
+    total = int(numel.sum())
+    x0 = Pool("x0", total * 4, random_values(rng, total, "uniform1", F32))
+    c = Pool("c", total * 4, random_values(rng, total, "uniform1", F32))
+    bufs = [Pool("ping", total * 4), Pool("pong", total * 4)]
+    ops = [("ADD", 2), ("MUL", 2), ("RELU", 1), ("SCALE", 1), ("SUB", 2)]
+    i = 0
+    for s0 in range(0, n_seq, interleave):
+        group = range(s0, min(n_seq, s0 + interleave))
+        for t in range(length):
+            for sq in group:
+                name, nin = ops[t % len(ops)]
+                # the previous step of this sequence was issued len(group) tasks ago
+                set_head(tasks, i, OP[name], [int(numel[sq])], nin, alpha=0.99 if name == "SCALE" else 0.0,
+                         dep=(len(group) if t else 0, 0, 0))
+                src = 0 if t == 0 else 2 + (t - 1) % 2                     # pool of the input: x0, then ping / pong in turn
+                set_tensor(tasks, pool_of, i, 0, src, int(off[sq]), [1], F32)
+                if nin == 2:
+                    set_tensor(tasks, pool_of, i, 1, 1, int(off[sq]), [1], F32)
+                set_tensor(tasks, pool_of, i, 3, 2 + t % 2, int(off[sq]), [1], F32)
+                i += 1
+    return Stream("sequences_%d" % interleave, tasks, pool_of, [x0, c] + bufs, batch=64,
+                  info=dict(seed=seed, n_seq=n_seq, length=length, interleave=interleave))
+
+
 # ---- configuration 2 ---------------------------------------------------------
 
 def _draw_shape(rng, numel, rank):

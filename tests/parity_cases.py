@@ -517,6 +517,7 @@ CPU_CHECKED = {
     "row_operations": row_operations,
     "int32": int32_ops,
     "degenerate": degenerate,
+    "sequences": lambda: S.sequences(n_seq=40, length=12, interleave=4),
     "dependency_dag": lambda: dependency_dag(0, n_tasks=300),
     "config2_reduced": config2_reduced,
     "config3_reduced": config3_reduced,

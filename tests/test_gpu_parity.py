@@ -117,6 +117,27 @@ def test_random_dependency_dags_equal_sequential_execution(seed, capacity):
         assert np.array_equal(g8, o8), "buffer %d differs at bytes %s" % (k, np.nonzero(g8 != o8)[0][:16])
 
 
+@pytest.mark.parametrize("interleave", [1, 8, 64])
+def test_sequences_of_dependent_small_operations(interleave):
+    """The shape of the paper's elementwise micro-benchmark: sequences of dependent small operations,
+    issued one after the other or several round-robin.  The buffers at the end equal sequential
+    execution byte for byte whatever the interleaving."""
+    from gpu_helpers import DevicePools, run_stream
+    from helpers import run_oracle
+    s = S.sequences(n_seq=128, length=25, interleave=interleave)
+    dp = DevicePools(s)
+    with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
+        rt.register_table(s.table)
+        t0 = run_stream(s, rt, dp)
+        comps = rt.completions(t0, len(s))
+    assert np.all(comps["status"] == 0)
+    gpu = dp.download()
+    hp, st = run_oracle(s)
+    assert np.all(st == 0)
+    for k, (g, o) in enumerate(zip(gpu, hp.arrays)):
+        assert np.array_equal(np.asarray(g).view(np.uint8).reshape(-1), np.asarray(o).view(np.uint8).reshape(-1)), "buffer %d differs" % k
+
+
 def test_fused_row_operations():
     stats, _ = _run_and_check(C.row_operations())
     print(stats, flush=True)
