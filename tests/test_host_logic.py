@@ -172,3 +172,12 @@ def test_task_plan_for_row_operations():
     assert (got[0][1] - 1) * got[0][2] < rows <= got[0][1] * got[0][2]
     # bytes: x and y once, the mask at its true size
     assert R.task_bytes(hp.tasks[1:2], impl[1:2])[0] == 2 * rows * 64 * 4 + 64 * 64 * 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build measures one GPU's share; bench.py says so instead of running with --gpus N > 1."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
