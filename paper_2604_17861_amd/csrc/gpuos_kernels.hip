@@ -642,17 +642,39 @@ template <int RIMPL> DEV int32_t red_combine_i(int32_t a, int32_t b) {
   return a < b ? a : b;
 }
 
-// xor-butterfly over the `width` lanes (power of two <= 64) a lane belongs to
+// The partner of a lane in step OFF of an all-reduce butterfly over aligned groups of 2 * OFF
+// lanes.  Steps 1 and 2 swap inside a quad and steps 4 and 8 mirror a half row / a row of 16 lanes
+// (lane i with i ^ 7, i ^ 15): DPP operand modifiers, no trip through the LDS crossbar that a
+// shuffle takes.  The masks 1, 2, 7, 15, 16, 32 are independent, so the steps still reach every
+// lane of the group.  Steps 16 and 32 cross rows and stay shuffles.  All lanes must be active.
+template <int OFF> DEV int butterfly_partner(int v) {
+  if (OFF == 1) return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false);      // quad_perm [1,0,3,2]
+  if (OFF == 2) return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false);      // quad_perm [2,3,0,1]
+  if (OFF == 4) return __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false);     // row_half_mirror
+  if (OFF == 8) return __builtin_amdgcn_update_dpp(v, v, 0x140, 0xf, 0xf, false);     // row_mirror
+  return __shfl_xor(v, OFF, 64);
+}
+template <int OFF> DEV float butterfly_partner(float v) {
+  return __builtin_bit_cast(float, butterfly_partner<OFF>(__builtin_bit_cast(int, v)));
+}
+
+// all-reduce over the `width` lanes (power of two <= 64, aligned) a lane belongs to
 template <int RIMPL> DEV float wave_reduce(float acc, uint32_t width) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1)
-    if ((uint32_t)off < width) acc = red_combine<RIMPL>(acc, __shfl_xor(acc, off, 64));
+  if (width > 32) acc = red_combine<RIMPL>(acc, butterfly_partner<32>(acc));
+  if (width > 16) acc = red_combine<RIMPL>(acc, butterfly_partner<16>(acc));
+  if (width > 8) acc = red_combine<RIMPL>(acc, butterfly_partner<8>(acc));
+  if (width > 4) acc = red_combine<RIMPL>(acc, butterfly_partner<4>(acc));
+  if (width > 2) acc = red_combine<RIMPL>(acc, butterfly_partner<2>(acc));
+  if (width > 1) acc = red_combine<RIMPL>(acc, butterfly_partner<1>(acc));
   return acc;
 }
 template <int RIMPL> DEV int32_t wave_reduce_i(int32_t acc, uint32_t width) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1)
-    if ((uint32_t)off < width) acc = red_combine_i<RIMPL>(acc, __shfl_xor(acc, off, 64));
+  if (width > 32) acc = red_combine_i<RIMPL>(acc, butterfly_partner<32>(acc));
+  if (width > 16) acc = red_combine_i<RIMPL>(acc, butterfly_partner<16>(acc));
+  if (width > 8) acc = red_combine_i<RIMPL>(acc, butterfly_partner<8>(acc));
+  if (width > 4) acc = red_combine_i<RIMPL>(acc, butterfly_partner<4>(acc));
+  if (width > 2) acc = red_combine_i<RIMPL>(acc, butterfly_partner<2>(acc));
+  if (width > 1) acc = red_combine_i<RIMPL>(acc, butterfly_partner<1>(acc));
   return acc;
 }
 
@@ -976,15 +998,21 @@ PATHFN void red_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
 // sums).  The softmax maximum ignores NaN; a NaN still poisons its row through the sum.
 // ---------------------------------------------------------------------------
 DEV float bfly_sum(float v, uint32_t width) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1)
-    if ((uint32_t)off < width) v += __shfl_xor(v, off, 64);
+  if (width > 32) v += butterfly_partner<32>(v);
+  if (width > 16) v += butterfly_partner<16>(v);
+  if (width > 8) v += butterfly_partner<8>(v);
+  if (width > 4) v += butterfly_partner<4>(v);
+  if (width > 2) v += butterfly_partner<2>(v);
+  if (width > 1) v += butterfly_partner<1>(v);
   return v;
 }
 DEV float bfly_max(float v, uint32_t width) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1)
-    if ((uint32_t)off < width) v = __builtin_fmaxf(v, __shfl_xor(v, off, 64));
+  if (width > 32) v = __builtin_fmaxf(v, butterfly_partner<32>(v));
+  if (width > 16) v = __builtin_fmaxf(v, butterfly_partner<16>(v));
+  if (width > 8) v = __builtin_fmaxf(v, butterfly_partner<8>(v));
+  if (width > 4) v = __builtin_fmaxf(v, butterfly_partner<4>(v));
+  if (width > 2) v = __builtin_fmaxf(v, butterfly_partner<2>(v));
+  if (width > 1) v = __builtin_fmaxf(v, butterfly_partner<1>(v));
   return v;
 }
 
