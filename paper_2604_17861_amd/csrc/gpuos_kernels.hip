@@ -868,7 +868,7 @@ PATHFN void red_rows_short(RedArgs a) {
   using E = Elem<DT>;
   using M = Mem<POL>;
   constexpr uint32_t V = E::V;
-  constexpr int UP = 4;
+  constexpr int UP = 8;
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
   const uint32_t n = run.n;
   uint32_t P = 1;                                     // lanes per row: power of two >= the widest span
