@@ -1660,13 +1660,17 @@ DEV bool deps_complete(const WorkerArgs& a, uint64_t ticket, const uint16_t* dep
 DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npub, uint64_t units_w) {
   const uint32_t tid = threadIdx.x;
   if (tid < 64) {                                  // wave 0: inclusive scan of nchunks
-    uint32_t v = tid < npub ? s->pub[tid].nchunks : 0u;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t t = __shfl_up(v, off, 64);
-      if ((int)tid >= off) v += t;
-    }
-    if (tid < npub) s->ubeg[tid + 1] = v;
+    // inclusive scan over the wavefront with DPP: shifts by 1, 2, 4, 8 inside each row of 16 lanes
+    // (lanes the shift runs out of the row for add 0), then lane 15 of a row to the whole next row
+    // (rows 1 and 3), then lane 31 to rows 2 and 3.  Six shuffles through the LDS crossbar before.
+    int v = (int)(tid < npub ? s->pub[tid].nchunks : 0u);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
+    if (tid < npub) s->ubeg[tid + 1] = (uint32_t)v;
     if (tid == 0) s->ubeg[0] = 0;
   }
   __syncthreads();
