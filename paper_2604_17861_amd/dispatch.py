@@ -51,6 +51,7 @@ HIP worker kernel through the C ABI (Runtime.submit).  Ordering rules that keep 
 """
 import struct
 from collections import deque
+from math import prod
 
 import numpy as np
 import torch
@@ -60,12 +61,14 @@ from . import runtime as R
 from . import streams as S
 
 _DT = {torch.float32: S.F32, torch.float16: S.F16, torch.bfloat16: S.BF16, torch.int32: S.I32}
+_ITEMSIZE = {torch.float32: 4, torch.float16: 2, torch.bfloat16: 2, torch.int32: 4}
 _INT_OK = ("ADD", "SUB", "MUL")
 # struct gpuos_task: header, size[6], in[3] + out as {ptr, stride[6], dtype, bcast_mask, pad}, alpha, dep[3], pad
 _TASK = struct.Struct("<HBBI6q" + "Q6qBB6x" * 4 + "f3H6x")
 assert _TASK.size == S.TASK_DT.itemsize
 _NO_TENSOR = (0, 0, 0, 0, 0, 0, 0, 0, 0)
 _ZEROS = (0,) * S.MAX_DIMS
+_ONES = (1,) * S.MAX_DIMS
 _MAX_EXTENT = (1 << 31) - 4096          # elements a tensor view may span (gpuos_submit rejects more)
 aten = torch.ops.aten
 
@@ -141,17 +144,28 @@ class GpuosMode(TorchDispatchMode):
 
     # ---- eligibility: operation type ------------------------------------------------------------
     def _tensor_ok(self, t):
-        return (type(t) is torch.Tensor and t.device == self.device and t.dtype in _DT and t.layout is torch.strided
-                and t.dim() <= S.MAX_DIMS and not t.is_conj() and not t.is_neg()
-                and (t.dim() == 0 or max(t.stride()) * t.numel() < _MAX_EXTENT       # quick bound, then the extent itself:
-                     or sum((n - 1) * st for n, st in zip(t.shape, t.stride())) < _MAX_EXTENT))   # the ring record holds 32-bit offsets
+        if (type(t) is not torch.Tensor or t.dtype not in _DT or t.device != self.device or t.layout is not torch.strided
+                or t.is_conj() or t.is_neg()):
+            return False
+        nd = t.dim()
+        if nd == 0:
+            return True
+        if nd > S.MAX_DIMS:
+            return False
+        n = t.numel()
+        if n < _MAX_EXTENT and t.is_contiguous():
+            return True
+        # the ring record holds 32-bit element offsets: a quick bound, then the extent of the view itself
+        return (max(t.stride()) * n < _MAX_EXTENT
+                or sum((k - 1) * st for k, st in zip(t.shape, t.stride())) < _MAX_EXTENT)
 
     def _unary(self, name):
         def plan(args, kwargs):
             if len(args) != 1 or kwargs or not self._tensor_ok(args[0]) or args[0].dtype is torch.int32:
                 return None
             x = args[0]
-            return _Plan(name, [x], tuple(x.shape), tuple(x.shape), x.dtype)
+            shape = tuple(x.shape)
+            return _Plan(name, (x,), shape, shape, x.dtype)
         return plan
 
     def _gelu(self, args, kwargs):
@@ -159,7 +173,8 @@ class GpuosMode(TorchDispatchMode):
         if not args or not self._tensor_ok(args[0]) or args[0].dtype is torch.int32 or approx not in ("none", "tanh"):
             return None
         x = args[0]
-        return _Plan("GELU_TANH" if approx == "tanh" else "GELU_ERF", [x], tuple(x.shape), tuple(x.shape), x.dtype)
+        shape = tuple(x.shape)
+        return _Plan("GELU_TANH" if approx == "tanh" else "GELU_ERF", (x,), shape, shape, x.dtype)
 
     def _scalar(self, name):
         """tensor (op) python number: the number travels in the descriptor's alpha."""
@@ -169,7 +184,8 @@ class GpuosMode(TorchDispatchMode):
             x, c = args
             if isinstance(c, (bool, complex)) or not isinstance(c, (int, float)):
                 return None
-            return _Plan(name, [x], tuple(x.shape), tuple(x.shape), x.dtype, alpha=float(c))
+            shape = tuple(x.shape)
+            return _Plan(name, (x,), shape, shape, x.dtype, alpha=float(c))
         return plan
 
     def _binary(self, name, with_number=None):
@@ -177,8 +193,8 @@ class GpuosMode(TorchDispatchMode):
             if len(args) != 2 or not isinstance(args[0], torch.Tensor):
                 return None
             a, o = args
-            if kwargs.get("alpha", 1) != 1 or kwargs.get("rounding_mode") is not None or any(
-                    k not in ("alpha", "rounding_mode") for k in kwargs):
+            if kwargs and (kwargs.get("alpha", 1) != 1 or kwargs.get("rounding_mode") is not None or any(
+                    k not in ("alpha", "rounding_mode") for k in kwargs)):
                 return None
             if not self._tensor_ok(a):
                 return None
@@ -187,17 +203,20 @@ class GpuosMode(TorchDispatchMode):
                 # PyTorch (it multiplies by the reciprocal, which rounds differently)
                 if with_number is None or isinstance(o, (bool, complex)) or not isinstance(o, (int, float)) or a.dtype is torch.int32:
                     return None
-                return _Plan(with_number, [a], tuple(a.shape), tuple(a.shape), a.dtype, alpha=float(o))
+                shape = tuple(a.shape)
+                return _Plan(with_number, (a,), shape, shape, a.dtype, alpha=float(o))
             if not self._tensor_ok(o):
                 return None
-            dt = a.dtype if a.dtype is o.dtype else torch.result_type(a, o)
-            if dt not in _DT or (dt is torch.int32) != (a.dtype is torch.int32) or (a.dtype is torch.int32) != (o.dtype is torch.int32):
-                return None
-            # PyTorch converts an operand to the result dtype before computing; the kernel computes on
-            # the operand as stored.  The two agree when that conversion is exact (same dtype, or a
-            # 16-bit operand under a float32 result); a float32 0-dim operand under a 16-bit result is not.
-            if any(t.dtype is not dt and dt is not torch.float32 for t in (a, o)):
-                return None
+            dt = a.dtype
+            if dt is not o.dtype:
+                dt = torch.result_type(a, o)
+                if dt not in _DT or (dt is torch.int32) != (a.dtype is torch.int32) or (a.dtype is torch.int32) != (o.dtype is torch.int32):
+                    return None
+                # PyTorch converts an operand to the result dtype before computing; the kernel computes on
+                # the operand as stored.  The two agree when that conversion is exact (same dtype, or a
+                # 16-bit operand under a float32 result); a float32 0-dim operand under a 16-bit result is not.
+                if dt is not torch.float32:
+                    return None
             if dt is torch.int32 and name not in _INT_OK:         # (the programs are float operators)
                 return None
             shape = tuple(a.shape)
@@ -206,7 +225,7 @@ class GpuosMode(TorchDispatchMode):
                     shape = tuple(torch.broadcast_shapes(a.shape, o.shape))
                 except RuntimeError:
                     return None
-            return _Plan(name, [a, o], shape, shape, dt)
+            return _Plan(name, (a, o), shape, shape, dt)
         return plan
 
     def _reduce(self, name):
@@ -222,7 +241,7 @@ class GpuosMode(TorchDispatchMode):
             if want not in (None, x.dtype) or (x.dtype is torch.int32 and name == "SUM_LAST"):
                 return None                              # torch sums int32 into int64
             outer = tuple(x.shape[:-1])
-            return _Plan(name, [x], tuple(x.shape), outer + ((1,) if keep else ()), x.dtype,
+            return _Plan(name, (x,), tuple(x.shape), outer + ((1,) if keep else ()), x.dtype,
                          flags=S.FLAG_KEEPDIM if keep else 0, reduce=True)
         return plan
 
@@ -232,7 +251,8 @@ class GpuosMode(TorchDispatchMode):
         x, dim, half_to_float = args
         if x.dim() < 1 or dim % x.dim() != x.dim() - 1 or half_to_float or x.dtype is torch.int32:
             return None
-        return _Plan("SOFTMAX_LAST", [x], tuple(x.shape), tuple(x.shape), x.dtype)
+        shape = tuple(x.shape)
+        return _Plan("SOFTMAX_LAST", (x,), shape, shape, x.dtype)
 
     # ---- the dispatch hook ------------------------------------------------------------------------
     def __torch_dispatch__(self, func, types, args=(), kwargs=None):
@@ -259,9 +279,7 @@ class GpuosMode(TorchDispatchMode):
         return self._normal_path(func, args, kwargs)
 
     def _redirect(self, func, p):
-        n = 1
-        for s in p.size:
-            n *= s
+        n = prod(p.size)
         if n < 1 or n > self.max_numel or len(p.size) > S.MAX_DIMS:       # tensor size
             self.stats["fallback_size"] += 1
             return None
@@ -305,13 +323,13 @@ class GpuosMode(TorchDispatchMode):
 
     # ---- descriptor marshalling -----------------------------------------------------------------
     @staticmethod
-    def _operand(t, size):
+    def _operand(t, ptr, size, nd):
         """{ptr, stride[6], dtype, bcast_mask} of `t` broadcast to the iteration shape `size`
         (dims aligned at the right, as PyTorch broadcasts)."""
-        nd, td = len(size), t.dim()
-        shape, stride = tuple(t.shape), t.stride()
+        shape, stride = t.shape, t.stride()
         if shape == size:                                   # nothing to broadcast
-            return (t.data_ptr(), *stride, *_ZEROS[nd:], _DT[t.dtype], 0)
+            return (ptr, *stride, *_ZEROS[nd:], _DT[t.dtype], 0)
+        td = len(shape)
         st = [0] * S.MAX_DIMS
         mask = 0
         for d in range(nd):
@@ -320,7 +338,7 @@ class GpuosMode(TorchDispatchMode):
                 st[d] = stride[k]
             elif size[d] != 1:
                 mask |= 1 << d
-        return (t.data_ptr(), *st, _DT[t.dtype], mask)
+        return (ptr, *st, _DT[t.dtype], mask)
 
     def _stage(self, p, out):
         size = p.size if p.size else (1,)                  # a 0-dim tensor iterates as [1]
@@ -328,17 +346,20 @@ class GpuosMode(TorchDispatchMode):
         if p.reduce and nd == 1:
             size, nd = (1,) + size, 2                      # a vector reduces as one row
         me = (self._next if self._next is not None else 0) + self._staged
-        deps = []
-        keys = []
+        writer, touch, cap = self._writer, self._touch, self.capacity
+        deps, ops, keys = [], [], []
         for t in p.inputs:
-            k = t.data_ptr() - t.storage_offset() * t.element_size()       # the storage's address
+            ptr = t.data_ptr()
+            k = ptr - t.storage_offset() * _ITEMSIZE[t.dtype]                # the storage's address
+            w = writer.get(k)
+            if w is not None:
+                d = me - w
+                if 0 < d < cap and d not in deps:           # further back: the ring wrapped past it, it has completed
+                    deps.append(d)
+            touch[k] = me
             keys.append(k)
-            w = self._writer.get(k)
-            if w is not None and 0 < me - w < self.capacity and (me - w) not in deps:
-                deps.append(me - w)                         # an older writer has completed: the ring wrapped past it
+            ops.append(self._operand(t, ptr, size, nd))
         ko = out.data_ptr()                                 # freshly allocated: offset 0
-        keys.append(ko)
-        ops = [self._operand(t, size) for t in p.inputs]
         if p.reduce:
             # the output walks the outer dims (size[:-1]); it is freshly allocated and contiguous
             ost = [0] * S.MAX_DIMS
@@ -346,19 +367,19 @@ class GpuosMode(TorchDispatchMode):
             for d in range(nd - 2, -1, -1):
                 ost[d] = acc
                 acc *= size[d]
-            o = (out.data_ptr(), *ost, _DT[out.dtype], 0)
+            o = (ko, *ost, _DT[out.dtype], 0)
         else:
-            o = self._operand(out, size)
+            o = self._operand(out, ko, size, nd)
         while len(ops) < 3:
             ops.append(_NO_TENSOR)
-        deps += [0] * (3 - len(deps))
-        sz = list(size) + [1] * (S.MAX_DIMS - nd)
-        _TASK.pack_into(self._buf, self._staged * _TASK.size, self.op_id[p.impl], nd, len(p.inputs), p.flags, *sz,
-                        *ops[0], *ops[1], *ops[2], *o, p.alpha, *deps)
-        for k in keys:
-            self._touch[k] = me
-        self._writer[ko] = me
-        self._inflight.append((me, (out, *p.inputs), keys, ko))
+        while len(deps) < 3:
+            deps.append(0)
+        _TASK.pack_into(self._buf, self._staged * _TASK.size, self.op_id[p.impl], nd, len(p.inputs), p.flags,
+                        *size, *_ONES[nd:], *ops[0], *ops[1], *ops[2], *o, p.alpha, *deps)
+        touch[ko] = me
+        writer[ko] = me
+        keys.append(ko)
+        self._inflight.append((me, (out, p.inputs), keys, ko))
         self._staged += 1
         if self._staged == self.batch:
             self._submit()
