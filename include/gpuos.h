@@ -324,7 +324,10 @@ int gpuos_define_program(gpuos_ctx* ctx, const gpuos_instr* code, uint32_t n_ins
  * The records become visible to the device at the next gpuos_flush (the
  * paper's fuse(): one aggregated submission).  When the ring is full the call
  * publishes what it has written and blocks until slots free up (or returns
- * GPUOS_E_FULL with nothing enqueued in non-blocking mode).
+ * GPUOS_E_FULL with nothing enqueued in non-blocking mode).  If that wait
+ * ends in GPUOS_E_TIMEOUT or GPUOS_E_DEAD, the tasks written before it stay
+ * enqueued and keep their tickets (gpuos_peek_queue's head_submitted minus
+ * *out_first_ticket says how many); the rest were not submitted.
  * *out_first_ticket (nullable) receives the ticket of tasks[0]. */
 int gpuos_submit(gpuos_ctx* ctx, const gpuos_task* tasks, uint32_t n, uint64_t* out_first_ticket);
 

@@ -310,6 +310,34 @@ int main() {
     CHECK(gpuos_shutdown(c) == GPUOS_OK);
     std::printf("ok: wait with a time limit\n");
   }
+  // 5d. back-pressure that runs into the time limit in the middle of a submit: the records written
+  //     before the stall keep their tickets and are executed, the rest were never submitted, and
+  //     the next submit continues right after them
+  {
+    gpuos_config cfg;
+    gpuos_default_config(&cfg);
+    cfg.wait_timeout_ms = 150;
+    gpuos_ctx* c = nullptr;
+    CHECK(gpuos_init(&c, 16, &cfg) == GPUOS_OK);
+    CHECK(gpuos_register_op(c, 7, GPUOS_IMPL_ADD, nullptr) == GPUOS_OK);
+    std::vector<gpuos_task> many(40, add_task(7, 256));
+    uint64_t tk = ~0ull;
+    standin_stall_ms(700);
+    CHECK(gpuos_submit(c, many.data(), 40, &tk) == GPUOS_E_TIMEOUT);
+    CHECK(tk == 0);
+    gpuos_queue_state q;
+    CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK);
+    const uint64_t taken = q.head_submitted - tk;
+    CHECK(taken == 16);                                                 // one ring's worth went in before the ring was full
+    CHECK(gpuos_wait(c, GPUOS_ALL, 5000ull * 1000 * 1000) == GPUOS_OK);
+    std::vector<gpuos_completion> comp(taken);
+    CHECK(gpuos_get_completions(c, 0, (uint32_t)taken, comp.data()) == GPUOS_OK);
+    for (uint64_t t = 0; t < taken; ++t) CHECK(comp[t].ticket == t && comp[t].status == 0);
+    CHECK(gpuos_submit(c, many.data(), 3, &tk) == GPUOS_OK && tk == taken);
+    CHECK(gpuos_wait(c, GPUOS_ALL, 5000ull * 1000 * 1000) == GPUOS_OK);
+    CHECK(gpuos_shutdown(c) == GPUOS_OK);
+    std::printf("ok: a submit that times out under back-pressure keeps what it had written\n");
+  }
   // 6. profiler markers: with cfg.markers the calls are annotated through the marker library the
   //    environment names (the test driver points it at a recorder); off by default
   if (std::getenv("GPUOS_ROCTX_LIBRARY")) {
