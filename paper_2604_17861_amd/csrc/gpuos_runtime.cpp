@@ -745,7 +745,12 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   c->wait_ns = (uint64_t)cfg.wait_timeout_ms * 1000000ull;
   uint64_t logcap = 1;
   while (logcap < cfg.completion_log || logcap < cap) logcap <<= 1;
-  c->log.assign(logcap, gpuos_completion{});
+  try {
+    c->log.assign(logcap, gpuos_completion{});
+  } catch (const std::bad_alloc&) {                             // no exception may cross the C boundary
+    delete c;
+    return GPUOS_E_NOMEM;
+  }
   c->log_mask = logcap - 1;
 
   auto fail = [&](int rc) { free_all(c); delete c; return rc; };
@@ -1006,7 +1011,11 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
   // pass 1 (no shared state: any number of host threads do this side by side): validate
   // everything and pack it; nothing is enqueued if one descriptor fails
   static thread_local std::vector<Record> staged;
-  staged.resize(n);
+  try {
+    staged.resize(n);
+  } catch (const std::bad_alloc&) {                             // no exception may cross the C boundary
+    return GPUOS_E_NOMEM;
+  }
   for (uint32_t i = 0; i < n; ++i) {
     const gpuos_task& t = tasks[i];
     uint32_t impl = GPUOS_IMPL_NONE;
