@@ -669,7 +669,10 @@ int stop_worker(gpuos_ctx* c) {
       doorbell_locked(c);
       rc = wait_floor(c, c->head.load(), c->wait_ns);         // drain
     }
-    bump_epoch(c, 0xff, true);                                // signal worker exit
+    {
+      std::lock_guard<SpinMutex> lk(c->prod_mu);              // the epoch is the producers' (a swap may be running)
+      bump_epoch(c, 0xff, true);                              // signal worker exit
+    }
     const uint64_t t0 = now_ns();
     hipError_t q;
     while ((q = hipStreamQuery(c->stream)) == hipErrorNotReady) {
@@ -682,7 +685,11 @@ int stop_worker(gpuos_ctx* c) {
     if (q == hipErrorNotReady) rc = GPUOS_E_TIMEOUT;
     else if (q != hipSuccess) { hip_ok(q, "worker kernel"); rc = GPUOS_E_HIP; }
     c->worker_running = false;
-    if (rc != GPUOS_E_TIMEOUT) c->worker_joined = true;
+    c->worker_joined = q != hipErrorNotReady;                 // the kernel has left the GPU (whatever the drain said)
+  } else if (c->stream) {
+    // an earlier stop ran into its time limit with the kernel still resident: look again
+    if (hipStreamQuery(c->stream) == hipErrorNotReady) rc = GPUOS_E_TIMEOUT;
+    else c->worker_joined = true;
   }
   if (c->harvester_run.load()) {
     c->harvester_run.store(false, std::memory_order_release);
@@ -857,7 +864,8 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
         // The kernel never started (the device is busy with other work).  Ask it to exit as soon as it
         // does; if it still has not finished, keep its memory alive: freeing under a queued
         // kernel would fault when it finally runs.
-        if (stop_worker(c) == GPUOS_E_TIMEOUT) return GPUOS_E_TIMEOUT;
+        (void)stop_worker(c);
+        if (!c->worker_joined) return GPUOS_E_TIMEOUT;
         return fail(GPUOS_E_TIMEOUT);
       }
       // look at the stream only now and then: the moment the heartbeat is seen ties the device
@@ -1217,7 +1225,7 @@ int gpuos_shutdown(gpuos_ctx* c) {
     for (size_t i = 0; i < g_live.size(); ++i)
       if (g_live[i] == c) { g_live.erase(g_live.begin() + (long)i); break; }
   }
-  if (rc == GPUOS_E_TIMEOUT) return rc;     // the kernel may still be running: leak rather than free under it
+  if (!c->worker_joined) return rc;         // the kernel may still be running: leak rather than free under it
   (void)hipSetDevice(c->device);
   free_all(c);
   delete c;
