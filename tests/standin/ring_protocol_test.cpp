@@ -316,13 +316,13 @@ int main() {
   {
     gpuos_config cfg;
     gpuos_default_config(&cfg);
-    cfg.wait_timeout_ms = 150;
+    cfg.wait_timeout_ms = 400;
     gpuos_ctx* c = nullptr;
     CHECK(gpuos_init(&c, 16, &cfg) == GPUOS_OK);
     CHECK(gpuos_register_op(c, 7, GPUOS_IMPL_ADD, nullptr) == GPUOS_OK);
     std::vector<gpuos_task> many(40, add_task(7, 256));
     uint64_t tk = ~0ull;
-    standin_stall_ms(700);
+    standin_stall_ms(1600);
     CHECK(gpuos_submit(c, many.data(), 40, &tk) == GPUOS_E_TIMEOUT);
     CHECK(tk == 0);
     gpuos_queue_state q;
