@@ -189,7 +189,9 @@ def test_large_matrix_products_get_the_whole_gpu_and_an_unknown_large_kernel_is_
         same(m, want_mm, exact=False, tol=1e-3)
         same(z, (a + b) * 0.5)
         assert mode.stats["pauses"] == 0 and mode.stats["redirected"] == 2, mode.stats
-        assert mode.stats["restarts"] == (1 if dt > 0.1 else 0), (mode.stats, dt)
+        # either the product found room beside the worker (no restart, and it did not sit out the idle
+        # exit), or the worker left for it and the next redirected operation started it again
+        assert mode.stats["restarts"] == 1 or (mode.stats["restarts"] == 0 and dt < 0.19), (mode.stats, dt)
     finally:
         mode.close()
 
