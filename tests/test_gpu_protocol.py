@@ -496,15 +496,17 @@ def test_wait_with_a_time_limit():
     """gpuos_wait with a limit far below the work outstanding reports GPUOS_E_TIMEOUT and loses
     nothing: the same wait without a limit succeeds and the results are right."""
     from gpu_helpers import compare_with_oracle
-    s = _simple_adds(64, 1 << 22, seed=5)                 # 64 adds of 4M elements: about 0.5 ms of memory traffic
+    s = _simple_adds(64, 1 << 22, seed=5)                 # 64 adds of 4M elements: about 0.5 ms of memory traffic a pass
     dp = _dev(s)
     with R.Runtime(0, **CFG) as rt:
         rt.register_table(s.table)
         t0 = rt.submit(dp.tasks, 0, 64)
-        assert rt.wait(t0 + 63, timeout_ns=1000, check=False) == R.E_TIMEOUT
+        for _ in range(3):                                       # the same adds again (they only rewrite their results):
+            rt.submit(dp.tasks, 0, 64)                           # about 2 ms outstanding, far above a host hiccup
+        assert rt.wait(t0 + 255, timeout_ns=1000, check=False) == R.E_TIMEOUT
         assert rt.worker_alive()
-        assert rt.wait(t0 + 64, check=False) == R.E_INVAL        # never issued
-        assert rt.wait(t0 + 63, check=False) == R.OK
+        assert rt.wait(t0 + 256, check=False) == R.E_INVAL       # never issued
+        assert rt.wait(t0 + 255, check=False) == R.OK
         assert rt.wait(timeout_ns=1, check=False) == R.OK        # everything is complete: no time needed
     assert compare_with_oracle(s, dp.download())["max_ulp"] == 0
 
