@@ -515,7 +515,8 @@ def test_wait_with_a_time_limit():
 def test_randomized_call_sequences(seed):
     """A seeded random walk over the host calls -- submits of 1..40 tasks with and without a
     doorbell, waits for earlier tickets, queue peeks, yield-policy changes, the worker stopped and
-    started, read-outs of the completion log -- on a random ring size and placement.  Whatever the
+    started, read-outs of the completion log -- on a random ring size, placement, grid size and
+    chunk size.  Whatever the
     interleaving, every ticket completes once, in the log in order, and the results are the oracle's."""
     from gpu_helpers import compare_with_oracle
     import parity_cases as P
@@ -526,6 +527,8 @@ def test_randomized_call_sequences(seed):
     cap = int(rng.choice([4, 64, 4096]))
     cfg = dict(CFG, push_ring=int(rng.integers(0, 2)), harvester_thread=int(rng.integers(0, 2)),
                trace_entries=int(rng.choice([0, 256])))
+    shape = np.random.default_rng(2000 + seed)                    # (its own generator: the walks above stay as they were)
+    cfg.update(workgroups_per_cu=int(shape.integers(1, 5)), chunk_elems=int(shape.choice([0, 1024, 4096, 32768])))
     print("seed", seed, "capacity", cap, cfg, flush=True)
     done = 0
     with R.Runtime(cap, **cfg) as rt:
