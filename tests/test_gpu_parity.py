@@ -267,3 +267,13 @@ def test_config4_reduced_hot_swap():
 def test_config5_reduced():
     stats, _ = _run_and_check(C.config5_reduced())
     print(stats, flush=True)
+
+
+@pytest.mark.parametrize("per_cu,chunk_elems", [(1, 1024), (2, 32768), (4, 2048)])
+def test_other_grid_and_chunk_sizes(per_cu, chunk_elems):
+    """The number of workgroups and the cut of a task into chunks are scheduling, not arithmetic:
+    the chained and the streaming configuration meet the same bars on a quarter-size grid with
+    the finest chunks, on a half-size grid with coarse ones, and on the fullest grid."""
+    for stream in (C.config3_reduced(), C.config5_reduced()):
+        stats, _ = _run_and_check(stream, workgroups_per_cu=per_cu, chunk_elems=chunk_elems)
+        print(per_cu, chunk_elems, stats, flush=True)
