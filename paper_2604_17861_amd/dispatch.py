@@ -97,6 +97,8 @@ class GpuosMode(TorchDispatchMode):
                  **runtime_kw):
         super().__init__()
         self.device = torch.device(device if device is not None else "cuda:0")
+        if self.device.type == "cuda" and self.device.index is None:
+            self.device = torch.device("cuda", 0)          # tensors report their device with its index
         self._own = rt is None
         if rt is None:
             runtime_kw.setdefault("workgroups_per_cu", 1)
