@@ -63,6 +63,7 @@ from . import streams as S
 _DT = {torch.float32: S.F32, torch.float16: S.F16, torch.bfloat16: S.BF16, torch.int32: S.I32}
 _ITEMSIZE = {torch.float32: 4, torch.float16: 2, torch.bfloat16: 2, torch.int32: 4}
 _INT_OK = ("ADD", "SUB", "MUL")
+_PLAIN_TENSORS = (torch.Tensor, torch.nn.Parameter)     # no other subclass: those carry semantics of their own
 # struct gpuos_task: header, size[6], in[3] + out as {ptr, stride[6], dtype, bcast_mask, pad}, alpha, dep[3], pad
 _TASK = struct.Struct("<HBBI6q" + "Q6qBB6x" * 4 + "f3H6x")
 assert _TASK.size == S.TASK_DT.itemsize
@@ -146,7 +147,7 @@ class GpuosMode(TorchDispatchMode):
 
     # ---- eligibility: operation type ------------------------------------------------------------
     def _tensor_ok(self, t):
-        if (type(t) is not torch.Tensor or t.dtype not in _DT or t.device != self.device or t.layout is not torch.strided
+        if (type(t) not in _PLAIN_TENSORS or t.dtype not in _DT or t.device != self.device or t.layout is not torch.strided
                 or t.is_conj() or t.is_neg()):
             return False
         nd = t.dim()

@@ -331,3 +331,32 @@ def test_views_that_span_more_than_the_record_can_address_stay_with_pytorch():
     assert m.stats["redirected"] == 1 and m.stats["by_op"] == {"ADD": 1}, m.stats
     assert r.tolist() == [4.0, 2.0]                               # far[0] is near[0], filled last with 2
     assert q.tolist() == [4.0, 4.0]
+
+
+def test_parameters_are_plain_tensors_and_autograd_still_works():
+    """A module's parameters are redirected like any tensor (bias adds, scales), other tensor
+    subclasses are not; autograd records above the dispatch level, so gradients are unchanged."""
+    g = torch.Generator().manual_seed(11)
+    x = torch.randn(8, 16, generator=g)
+    bias = torch.nn.Parameter(torch.randn(16, generator=g))
+
+    def f():
+        y = torch.relu(x + bias) * 2.0
+        y.sum().backward()
+        grad, bias.grad = bias.grad.clone(), None
+        return y.detach(), grad
+    want = f()
+    m = mode(4)
+    with m:
+        got = f()
+    same(got[0], want[0])
+    same(got[1], want[1], exact=False, tol=1e-5)            # (the sums of the backward pass may be ordered differently)
+    assert m.stats["by_op"]["ADD"] >= 1 and m.stats["by_op"]["RELU"] == 1 and m.stats["by_op"]["SCALE"] >= 1, m.stats
+
+    class Tagged(torch.Tensor):
+        pass
+    t = torch.randn(4, 4, generator=g).as_subclass(Tagged)
+    m = mode(5)
+    with m:
+        z = t + t
+    assert m.stats["redirected"] == 0 and torch.equal(torch.Tensor(z), torch.Tensor(t) * 2)
