@@ -414,10 +414,14 @@ def main():
                     algorithmic_bytes=rf["bytes"], workload="config5: %d bandwidth tasks" % len(s5))
     if not args.skip_extras:
         # ---- an operator defined at run time as a program against the built-in it re-implements -----
-        extras["operator_program"] = bench_program(R, s5, dp5, impl5)
-        log("operator program:", extras["operator_program"])
-        extras["torch_dispatch"] = bench_dispatch()
-        log("torch dispatch filter:", extras["torch_dispatch"])
+        # (side legs after the figures of record: a failure in one is reported in its place and does
+        # not cost the line)
+        for name, leg in (("operator_program", lambda: bench_program(R, s5, dp5, impl5)), ("torch_dispatch", bench_dispatch)):
+            try:
+                extras[name] = leg()
+            except Exception as e:                                  # noqa: BLE001
+                extras[name] = dict(error=repr(e))
+            log(name + ":", extras[name])
     del dp5
 
     # ---- CPU oracle on a bounded sample of the headline stream (one core) ------------------------
