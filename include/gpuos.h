@@ -278,7 +278,13 @@ typedef struct gpuos_config {
                                        their work for gpuos_worker_stats (about a dozen reads
                                        of the device clock per task: measurable on small
                                        tasks); 0: only the counts are kept (default)        */
-  uint32_t reserved[2];
+  uint32_t dep_wait_us;             /* bound, in microseconds, on the time a worker workgroup waits
+                                       for a dependency of the task it holds (what it waits for was
+                                       published before its own unit, so the wait ends by itself; the
+                                       bound is a safety net).  A task that runs into it completes
+                                       with GPUOS_E_TIMEOUT and writes nothing; its dependants run.
+                                       0 => wait_timeout_ms                                    */
+  uint32_t reserved[1];
 } gpuos_config;
 
 /* Fill *cfg with the defaults named above. */

@@ -207,6 +207,7 @@ struct WorkerArgs {
   uint32_t   resume;         // 1: the context has run before; its counters continue where they stopped
   uint32_t   timing;         // 1: time every phase (performance counters); 0: read the clock only where tracing or the idle exit need it
   uint64_t   resume_tickets; // tickets dequeued (and completed) by the earlier runs
+  uint64_t   dep_wait_ticks; // bound on a worker's wait for a dependency; 100 MHz ticks
 };
 
 // implemented in gpuos_kernels.hip

@@ -1552,15 +1552,22 @@ DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_
 // ---------------------------------------------------------------------------
 // dispatcher (workgroup 0)
 //
-// Besides mirroring the host ring it is the scheduler of dependent work: units
-// are claimed in publication order and a worker that claimed a unit whose
-// dependency is not complete can only wait, so a large dependent task published
-// too early would park hundreds of workgroups while ready work of other chains
-// sits behind it.  A task with more than kSmallTaskChunks chunks whose
-// dependencies are not complete when it is dequeued is therefore held on a
-// pending list and its units are published when the done words say so; small
-// dependent tasks are published at once (their few workgroups wait on the done
-// word, which is the shortest hand-off for sequential chains of small ops).
+// Besides mirroring the host ring it is the scheduler of dependent work.  Units are claimed in
+// publication order, and a worker that holds a unit whose dependency is incomplete can only wait.
+// Two rules keep that from hurting:
+//  * A task with more than kSmallTaskChunks chunks whose dependencies are incomplete when it is
+//    dequeued is HELD on a pending list and published when the done words say so (otherwise hundreds
+//    of workgroups would park on it while ready work of other chains sits behind it).  Small dependent
+//    tasks are published at once and their few workgroups wait on the done word, the shortest hand-off
+//    for sequential chains of small operations.
+//  * Publication order respects dependency order: a task that names a task which is itself not yet
+//    published (it is on the pending list, or held earlier in the same pass) is held too, whatever its
+//    size.  So whatever a waiting worker waits for lies BEFORE its own unit in the unit ring, its units
+//    were claimed earlier by resident workgroups, and by induction over the ring position the wait
+//    ends.  (Without this rule a held large task followed by more small dependants than there are
+//    workgroups parks every workgroup behind units that come after theirs.)
+// Held tasks are flagged RF_DEPS_RESOLVED: they are published only after their dependencies
+// completed, so their workers never wait.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kPendMax = 128;         // tasks held back at a time
 constexpr uint64_t kLookaheadUnits = 8192; // work units kept published ahead of the claim counter
@@ -1653,6 +1660,30 @@ DEV bool deps_complete(const WorkerArgs& a, uint64_t ticket, const uint16_t* dep
     }
   }
   return ok;
+}
+
+// Does the task name a ticket that sits on the pending list (published later than everything the
+// dispatcher has published so far)?  The list is in ticket order: two compares reject most
+// candidates, a binary search decides the rest.
+DEV bool names_pending(const DispShared* s, uint64_t ticket, const uint16_t* dep) {
+  const uint32_t np = s->npend;
+  if (np == 0) return false;
+  const uint64_t first = s->pend[0].ticket, last = s->pend[np - 1].ticket;
+  bool hit = false;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const uint32_t back = dep[k];
+    if (back == 0 || back > ticket) continue;
+    const uint64_t d = ticket - back;
+    if (d < first || d > last) continue;
+    uint32_t lo = 0, hi = np;
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (s->pend[mid].ticket < d) lo = mid + 1; else hi = mid;
+    }
+    hit = hit || (lo < np && s->pend[lo].ticket == d);
+  }
+  return hit;
 }
 
 // Write the work units of s->pub[0 .. npub) and make them claimable.  Called by the whole
@@ -1921,11 +1952,18 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
           if (op < GPUOS_MAX_OPS) atomicAdd(&s->opcnt[op], 1u);
         }
         uint32_t defer = 0;
-        if ((rc.dep[0] | rc.dep[1] | rc.dep[2]) != 0 && rc.nchunks > kSmallTaskChunks) {
-          // a large dependent task: its workers never wait; it is published once its
-          // dependencies are complete (now, or later from the pending list)
-          rc.rflags |= RF_DEPS_RESOLVED;
-          defer = deps_complete(a, ticket, rc.dep) ? 0u : 1u;
+        if ((rc.dep[0] | rc.dep[1] | rc.dep[2]) != 0) {
+          if (rc.nchunks > kSmallTaskChunks) {
+            // a large dependent task: its workers never wait; it is published once its
+            // dependencies are complete (now, or later from the pending list)
+            rc.rflags |= RF_DEPS_RESOLVED;
+            defer = deps_complete(a, ticket, rc.dep) ? 0u : 1u;
+          } else {
+            // a small one is published at once and its workers wait, unless it names a task that is
+            // itself held back: then it joins the pending list behind that task (tasks held in this
+            // very pass are found below, in the split)
+            defer = names_pending(s, ticket, rc.dep) ? 1u : 0u;
+          }
         }
         s->defer[tid] = defer;
       }
@@ -1943,9 +1981,28 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       if (tid < 64) {                                              // wave 0 holds all n <= 64 records: split by ballot
         const uint32_t npend0 = s->npend;
         const bool mine = tid < n;
-        const bool held = mine && s->defer[tid] != 0;
-        const uint64_t m_pub = __ballot(mine && !held), m_def = __ballot(held);
+        bool held = mine && s->defer[tid] != 0;
+        // A task that names a task held in this pass is held too (a large one already is: such a
+        // dependency cannot be complete).  Dependencies point backwards, so a few rounds of
+        // "held if one of my in-pass dependencies is held" reach the fixed point.
+        uint64_t dep_mask = 0;                                     // records of this pass the task names
+        if (mine && !held) {
+#pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            const uint32_t back = s->rec[tid].dep[k];
+            if (back != 0 && back <= tid) dep_mask |= 1ull << (tid - back);
+          }
+        }
+        uint64_t m_def = __ballot(held);
+        while (true) {
+          held = held || (dep_mask & m_def) != 0;
+          const uint64_t m2 = __ballot(held);
+          if (m2 == m_def) break;
+          m_def = m2;
+        }
+        const uint64_t m_pub = __ballot(mine && !held);
         const uint64_t below = (1ull << tid) - 1ull;
+        if (held) s->rec[tid].rflags |= RF_DEPS_RESOLVED;          // published only after its dependencies completed
         if (mine) {
           const Record& rc = s->rec[tid];
           PubEntry pe;
@@ -2051,10 +2108,13 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
 // ---------------------------------------------------------------------------
 // worker (every workgroup but 0)
 // ---------------------------------------------------------------------------
+constexpr uint64_t kStopGraceTicks = 10000000ull;   // 100 ms (100 MHz clock): how long a worker still waits for a dependency once the stop flag is up
+
 struct WorkShared {
   Record rec;
   uint64_t unit, entry;
   int32_t exit_flag;
+  int32_t dep_status;              // 0, or the status a task whose dependency wait ran out completes with
   float red[kScratchFloats];
 };
 
@@ -2129,19 +2189,37 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
     if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
     const uint64_t c2 = clock_if(timing);
     // ---- dependencies: earlier tickets named by back-distance ----
+    // What is awaited was published before this unit (the dispatcher sees to that), so the wait ends
+    // when resident workgroups finish work they already hold.  It is bounded all the same (the
+    // context's wait limit; a short grace once the stop flag is up): a task that runs into the bound
+    // completes with GPUOS_E_TIMEOUT without executing, and the kernel always leaves.
     if ((r->dep[0] | r->dep[1] | r->dep[2]) != 0 && !(r->rflags & RF_DEPS_RESOLVED)) {
       if (tid == 0) {
         const uint64_t ticket = r->ticket;
-        for (int k = 0; k < 3; ++k) {
+        int32_t gave_up = 0;
+        uint64_t t_begin = 0;
+        uint32_t spins = 0;
+        for (int k = 0; k < 3 && !gave_up; ++k) {
           const uint32_t back = r->dep[k];
           if (back == 0 || back > ticket) continue;
           const uint64_t want = ticket - back + 1;
           const uint64_t* w = &a.st[(ticket - back) & a.cap_mask].done_seq;
-          while (__hip_atomic_load(w, __ATOMIC_RELAXED, SC_SYSTEM) < want) __builtin_amdgcn_s_sleep(1);
+          while (__hip_atomic_load(w, __ATOMIC_RELAXED, SC_SYSTEM) < want) {
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 31u) == 0) {
+              const uint64_t now = wall_clock64();
+              if (t_begin == 0) t_begin = now;
+              uint64_t limit = a.dep_wait_ticks;
+              if (limit > kStopGraceTicks && __hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) limit = kStopGraceTicks;
+              if (now - t_begin > limit) { gave_up = GPUOS_E_TIMEOUT; break; }
+            }
+          }
         }
         order_loads();
+        s->dep_status = gave_up;
       }
       __syncthreads();
+      if (status == GPUOS_OK && s->dep_status != 0) status = s->dep_status;
     }
     const uint64_t c3 = clock_if(timing);
     if (tracing && tid == 0 && chunk == 0 && r->nchunks > 1)

@@ -849,6 +849,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
   a.resume = 0; a.resume_tickets = 0;
   a.timing = cfg.phase_timers ? 1u : 0u;
+  a.dep_wait_ticks = cfg.dep_wait_us ? (uint64_t)cfg.dep_wait_us * 100ull : (uint64_t)cfg.wait_timeout_ms * 100000ull;
   c->wargs = a;
   if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
   if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);
@@ -1017,7 +1018,8 @@ int gpuos_submit(gpuos_ctx* c, const gpuos_task* tasks, uint32_t n, uint64_t* ou
     return GPUOS_OK;
   }
   // pass 1 (no shared state: any number of host threads do this side by side): validate
-  // everything and pack it; nothing is enqueued if one descriptor fails
+  // everything and pack it; nothing is enqueued if one descriptor fails validation (a blocking
+  // submit that runs out of time waiting for room keeps what it has enqueued: see the header)
   static thread_local std::vector<Record> staged;
   try {
     staged.resize(n);
@@ -1142,6 +1144,7 @@ int gpuos_worker_alive(gpuos_ctx* c) {
 int gpuos_set_yield_every(gpuos_ctx* c, uint32_t every) {
   if (!c) return GPUOS_E_INVAL;
   if (!c->worker_running) return GPUOS_E_DEAD;
+  std::lock_guard<SpinMutex> lk(c->prod_mu);                      // the epoch is the producers' (a swap may be running)
   __atomic_store_n(&c->bell->yield_every, every, __ATOMIC_RELEASE);
   bump_epoch(c, 0xff, false);
   return GPUOS_OK;

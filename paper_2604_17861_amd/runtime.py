@@ -32,7 +32,8 @@ class Config(ctypes.Structure):
                 ("idle_exit_ms", ctypes.c_uint32), ("wait_timeout_ms", ctypes.c_uint32),
                 ("completion_log", ctypes.c_uint32), ("chunk_elems", ctypes.c_uint32),
                 ("push_ring", ctypes.c_uint32), ("trace_entries", ctypes.c_uint32),
-                ("markers", ctypes.c_uint32), ("phase_timers", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 2)]
+                ("markers", ctypes.c_uint32), ("phase_timers", ctypes.c_uint32), ("dep_wait_us", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32 * 1)]
 
 
 class QueueState(ctypes.Structure):

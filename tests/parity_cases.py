@@ -462,6 +462,30 @@ def dependency_dag(seed, n_tasks=2500, n_buffers=10, max_dist=48):
     return b.stream("dependency_dag_%d" % seed, batch=64)
 
 
+def producer_with_dependants(n_consumers=1200, n_links=300):
+    """The stream shape that needs publication in dependency order: a large task, a large task that
+    depends on it (held back by the dispatcher while the first one runs), then more small tasks than
+    there are workgroups that each read one row of the held task's output, and a chain of four-chunk
+    links whose first link reads it too.  Exactly rounded operations on small integers: the buffers at
+    the end equal sequential execution byte for byte."""
+    rng = np.random.default_rng(77)
+    rows, cols = 2048, 1024
+    assert n_consumers <= rows
+    f = lambda *shape: b.pool(rng.integers(-3, 4, shape).astype(np.float32))
+    b = Builder()
+    A, B, Cc, D = f(rows, cols), f(rows, cols), f(rows, cols), f(rows, cols)
+    X, Y, Z = b.pool(np.zeros((rows, cols), np.float32)), b.pool(np.zeros((rows, cols), np.float32)), b.pool(np.zeros((rows, cols), np.float32))
+    b.add("ADD", X, [A, B])                                    # 2M elements: 128 chunks
+    b.add("MUL", Y, [X, Cc], dep=(1, 0, 0))                    # large and dependent: held until the ADD is done
+    for k in range(n_consumers):                               # one row each, all naming the held task
+        b.add("SUB", Z[k], [Y[k], D[k]], dep=(k + 1, 0, 0))
+    W, E = b.pool(np.zeros(4 * 8192, np.float32)), f(4 * 8192)
+    b.add("ADD", W, [Y.reshape(-1)[: 4 * 8192], E], dep=(n_consumers + 1, 0, 0))     # four chunks, reads the held task's output
+    for _ in range(n_links - 1):
+        b.add("ADD", W, [W, E], dep=(1, 0, 0))                 # in place, each link after the previous one
+    return b.stream("producer_with_dependants", batch=64)
+
+
 def int32_ops():
     rng = np.random.default_rng(10)
     b = Builder()
@@ -519,6 +543,7 @@ CPU_CHECKED = {
     "degenerate": degenerate,
     "sequences": lambda: S.sequences(n_seq=40, length=12, interleave=4),
     "dependency_dag": lambda: dependency_dag(0, n_tasks=300),
+    "producer_with_dependants": producer_with_dependants,
     "config2_reduced": config2_reduced,
     "config3_reduced": config3_reduced,
     "config3_fused_reduced": config3_fused_reduced,

@@ -117,6 +117,70 @@ def test_random_dependency_dags_equal_sequential_execution(seed, capacity):
         assert np.array_equal(g8, o8), "buffer %d differs at bytes %s" % (k, np.nonzero(g8 != o8)[0][:16])
 
 
+def test_held_producer_with_more_small_dependants_than_workgroups():
+    """A large task held back by the dispatcher, 1,200 one-row tasks and a chain of 300 four-chunk
+    links that all name it: the dispatcher publishes in dependency order (the small dependants join
+    the pending list behind the held task), so no workgroup ever waits for work published after its
+    own.  The buffers at the end equal sequential execution byte for byte; through the default ring
+    and through one of 2,048 slots (the dependants then reach back across most of the ring)."""
+    from gpu_helpers import DevicePools, run_stream
+    from helpers import run_oracle
+    s = C.producer_with_dependants()
+    hp, st = run_oracle(s)
+    assert np.all(st == 0)
+    for capacity in (0, 2048):
+        print("producer_with_dependants, ring", capacity, flush=True)
+        dp = DevicePools(s)
+        with R.Runtime(capacity, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
+            rt.register_table(s.table)
+            t0 = run_stream(s, rt, dp)
+            comps = rt.completions(t0, len(s))
+            rt.stop_worker()
+            held = rt.worker_stats()["disp_deferred"]
+        assert np.all(comps["status"] == 0)
+        assert held >= 2                      # the large dependent task and at least some of its small dependants
+        gpu = dp.download()
+        for k, (g, o) in enumerate(zip(gpu, hp.arrays)):
+            g8, o8 = np.asarray(g).view(np.uint8).reshape(-1), np.asarray(o).view(np.uint8).reshape(-1)
+            assert np.array_equal(g8, o8), "buffer %d differs at bytes %s" % (k, np.nonzero(g8 != o8)[0][:16])
+
+
+def test_dependency_wait_is_bounded():
+    """cfg.dep_wait_us: a workgroup that holds a small task whose dependency is still running gives
+    up after the bound; the task completes with GPUOS_E_TIMEOUT and writes nothing, everything else
+    runs, and the worker stays alive.  With a bound of one microsecond behind a 16M-element task
+    the wait usually runs out (either outcome is legal: the bound is a safety net, not a schedule)."""
+    from gpu_helpers import DevicePools, run_stream
+    rng = np.random.default_rng(5)
+    b = C.Builder()
+    n = 1 << 24
+    x = b.pool(rng.uniform(-3, 3, n).astype(np.float32))
+    y = b.pool(np.zeros(n, np.float32))
+    z = b.pool(np.full(1024, 7.0, np.float32))
+    w = b.pool(np.zeros(1024, np.float32))
+    b.add("GELU_ERF", y, [x])                                  # long: 1,024 chunks evaluated in fp64
+    b.add("COPY", z, [y[:1024]], dep=(1, 0, 0))                # small and dependent: its workgroup waits
+    b.add("RELU", w, [x[:1024]])                               # independent
+    s = b.stream("bounded_wait")
+    dp = DevicePools(s)
+    with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000, dep_wait_us=1) as rt:
+        rt.register_table(s.table)
+        t0 = run_stream(s, rt, dp, wait=False)
+        rc = rt.wait(check=False)
+        comps = rt.completions(t0, 3)
+        assert rt.worker_alive()
+    print("bounded wait: statuses", comps["status"], flush=True)
+    assert comps["status"][0] == 0 and comps["status"][2] == 0
+    assert comps["status"][1] in (0, R.E_TIMEOUT) and rc == comps["status"][1]
+    imgs = dp.download()
+    zz, yy = imgs[2].view(np.float32), imgs[1].view(np.float32)
+    if comps["status"][1] == R.E_TIMEOUT:
+        assert np.all(zz == 7.0)                               # it wrote nothing
+    else:
+        assert np.array_equal(zz, yy[:1024])
+    assert np.array_equal(imgs[3].view(np.float32), np.maximum(imgs[0].view(np.float32)[:1024], 0))
+
+
 @pytest.mark.parametrize("interleave", [1, 8, 64])
 def test_sequences_of_dependent_small_operations(interleave):
     """The shape of the paper's elementwise micro-benchmark: sequences of dependent small operations,

@@ -52,3 +52,26 @@ def test_random_dags_do_park_under_the_large_only_rule():
         tasks = M.random_dag(np.random.default_rng(seed), 700)
         hits += M.simulate(tasks, 5, "large_only").deadlock
     assert hits >= 1
+
+
+def test_the_gpu_regression_stream_is_one_the_large_only_rule_parks_on():
+    """tests/parity_cases.producer_with_dependants, with the chunk counts the host really packs
+    (gpuos_task_plan): under the first rule every one of 767 workers ends up parked; under the rule
+    the kernel implements the stream drains."""
+    import parity_cases as C
+    from helpers import HostPools
+    from paper_2604_17861_amd import runtime as R
+    s = C.producer_with_dependants()
+    hp = HostPools(s)
+    impl = s.impl_for()
+    tasks = []
+    for i in range(len(s)):
+        path, nchunks, _, _ = R.task_plan(hp.tasks, i, int(impl[i]))
+        tasks.append(M.Task(nchunks, tuple(int(d) for d in s.tasks["dep"][i]), False))
+    assert tasks[0].nchunks > 4 and tasks[1].nchunks > 4 and all(t.nchunks == 1 for t in tasks[2:1202]) and tasks[1202].nchunks == 4
+    # the dispatcher is fast against a 2M-element task: give it enough passes per chunk-time to publish the consumers
+    r = M.simulate(tasks, 767, "large_only", disp_passes=32)
+    assert r.deadlock and r.parked == 767
+    r = M.simulate(tasks, 767, "published_deps", disp_passes=32)
+    assert not r.deadlock and r.completed == len(tasks)
+    assert r.held == 128          # the pending list fills behind the held task; dequeuing pauses until it is published
