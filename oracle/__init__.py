@@ -47,7 +47,7 @@ def lib():
         L.orc_run_stream.restype = ctypes.c_int64
         L.orc_sum_last_f64.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.orc_sum_last_f64.restype = ctypes.c_int
-        L.orc_rowop_f64.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.orc_rowop_f64.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
         L.orc_rowop_f64.restype = ctypes.c_int
         L.orc_validate_program.argtypes = [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32]
         L.orc_validate_program.restype = ctypes.c_int
@@ -129,12 +129,11 @@ def sum_last_f64(tasks, i, n_rows):
 
 def rowop_f64(tasks, i, impl):
     """Unrounded fp64 results of a row operation (softmax family, layer norm) in the task's
-    row-major shape, and the per-element magnitude its fp32 evaluation error scales with."""
+    row-major shape."""
     t = tasks[i]
     shape = [int(x) for x in t["size"][: int(t["ndim"])]]
     y = np.zeros(shape, dtype=np.float64)
-    scale = np.zeros(shape, dtype=np.float64)
-    rc = lib().orc_rowop_f64(tasks.ctypes.data + i * tasks.dtype.itemsize, int(impl), y.ctypes.data, scale.ctypes.data)
+    rc = lib().orc_rowop_f64(tasks.ctypes.data + i * tasks.dtype.itemsize, int(impl), y.ctypes.data)
     if rc != 0:
         raise ValueError("orc_rowop_f64 rc=%d" % rc)
-    return y, scale
+    return y

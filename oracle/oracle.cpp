@@ -377,9 +377,9 @@ void run_program(const orc_task* t, const orc_instr* code, uint32_t n, int mode)
 //                   gives NaN where the arithmetic above gives NaN (inf - inf);
 //   layer norm:     mean = sum x / n, var = sum (x - mean)^2 / n (biased), eps = alpha,
 //                   y_j = (x_j - mean) / sqrt(var + eps) * gamma_j + beta_j.
-// y (nullable): unrounded doubles, row-major over the task's shape.  scale (nullable): see
-// oracle.h.  store: write the rounded results into the task's output tensor.
-void run_rowop(const orc_task* t, int impl, bool store, double* y_out, double* scale_out) {
+// y (nullable): unrounded doubles, row-major over the task's shape.
+// store: write the rounded results into the task's output tensor.
+void run_rowop(const orc_task* t, int impl, bool store, double* y_out) {
   const int nd = t->ndim, ond = nd - 1;
   const int64_t n = t->size[nd - 1];
   int64_t outer = 1;
@@ -388,7 +388,7 @@ void run_rowop(const orc_task* t, int impl, bool store, double* y_out, double* s
   int64_t s_last[3] = {0, 0, 0};
   for (int k = 0; k < t->n_inputs; ++k) s_last[k] = eff_stride(t->in[k], nd - 1);
   const int64_t so_last = t->out.stride[nd - 1];
-  std::vector<double> v((size_t)n), res((size_t)n), scl((size_t)n);
+  std::vector<double> v((size_t)n), res((size_t)n);
   for (int64_t o = 0; o < outer; ++o) {
     int64_t base[3] = {0, 0, 0};
     for (int k = 0; k < t->n_inputs; ++k) base[k] = offset_of(t->in[k], ond, t->size, o);
@@ -400,18 +400,16 @@ void run_rowop(const orc_task* t, int impl, bool store, double* y_out, double* s
       double sum = 0.0;
       for (int64_t j = 0; j < n; ++j) { v[(size_t)j] = in(0, j); sum += v[(size_t)j]; }
       const double mean = sum / (double)n;
-      double ss = 0.0, maxdev = 0.0;
+      double ss = 0.0;
       for (int64_t j = 0; j < n; ++j) {
         const double d = v[(size_t)j] - mean;
         ss += d * d;
-        if (std::fabs(d) > maxdev) maxdev = std::fabs(d);
       }
       const double var = ss / (double)n;
       const double rstd = 1.0 / std::sqrt(var + (double)t->alpha);
       for (int64_t j = 0; j < n; ++j) {
         const double g = in(1, j), b = in(2, j);
         res[(size_t)j] = (v[(size_t)j] - mean) * rstd * g + b;
-        scl[(size_t)j] = (std::fabs(v[(size_t)j]) + std::fabs(mean) + maxdev) * rstd * std::fabs(g) + std::fabs(b);
       }
     } else {
       bool any_nan = false;
@@ -425,16 +423,10 @@ void run_rowop(const orc_task* t, int impl, bool store, double* y_out, double* s
       }
       double sum = 0.0;
       for (int64_t j = 0; j < n; ++j) { res[(size_t)j] = std::exp(v[(size_t)j] - m); sum += res[(size_t)j]; }
-      const double lg = std::log2((double)n);
-      for (int64_t j = 0; j < n; ++j) {
-        res[(size_t)j] = any_nan ? std::nan("") : res[(size_t)j] / sum;
-        const double dist = std::fabs(v[(size_t)j] - m);
-        scl[(size_t)j] = res[(size_t)j] * ((dist == dist && dist < HUGE_VAL ? dist : 0.0) + 8.0 + lg);
-      }
+      for (int64_t j = 0; j < n; ++j) res[(size_t)j] = any_nan ? std::nan("") : res[(size_t)j] / sum;
     }
     for (int64_t j = 0; j < n; ++j) {
       if (y_out) y_out[o * n + j] = res[(size_t)j];
-      if (scale_out) scale_out[o * n + j] = scl[(size_t)j];
       if (store) store_from_float(t->out.ptr, obase + j * so_last, t->out.dtype, (float)res[(size_t)j]);
     }
   }
@@ -451,7 +443,7 @@ int orc_run_task(const orc_task* t, int impl, int mode) {
   if (rc != ORC_OK) return rc;
   if (impl == ORC_FAIL) return ORC_E_BADOP;
   if (is_reduction(impl)) run_reduction(t, impl);
-  else if (is_rowop(impl)) run_rowop(t, impl, true, nullptr, nullptr);
+  else if (is_rowop(impl)) run_rowop(t, impl, true, nullptr);
   else run_elementwise(t, impl, mode);
   return ORC_OK;
 }
@@ -504,11 +496,11 @@ int orc_run_task_program(const orc_task* t, const orc_instr* code, uint32_t n_in
   return ORC_OK;
 }
 
-int orc_rowop_f64(const orc_task* t, int impl, double* y, double* scale) {
+int orc_rowop_f64(const orc_task* t, int impl, double* y) {
   if (!is_rowop(impl)) return ORC_E_INVAL;
   const int rc = validate(t, impl);
   if (rc != ORC_OK) return rc;
-  run_rowop(t, impl, false, y, scale);
+  run_rowop(t, impl, false, y);
   return ORC_OK;
 }
 

@@ -16,7 +16,7 @@ EXACT = {S.IMPL[n] for n in ("ADD", "SUB", "MUL", "DIV", "RELU", "SCALE", "FMA",
 TRANSCENDENTAL = {S.IMPL[n] for n in ("EXP", "SUB_EXP", "GELU_ERF", "GELU_TANH")}
 ULP_TOL = 2            # elementwise float results: within 2 ulp of the output dtype
 RED_REL = 1e-5         # fp32 reductions: |g - o| <= 1e-5 * max(|o|, L1 / sqrt(n))
-ROW_REL = 2.0 ** -22   # fused row operations: |g - y| <= 2^-22 * scale (scale: oracle.rowop_f64)
+ROW_REL = 2.0 ** -22   # fused row operations: |g - y| <= 2^-22 * scale (scale: rowop_error_scale below)
 ROW_ABS = 1.5 * 2.0 ** -126   # ... plus results below fp32's normal range, which the device may flush
 
 
@@ -70,28 +70,38 @@ def run_stream(stream, rt, dp, first=0, count=None, wait=True):
     return t0
 
 
-def _strided(buf, dt_code, byte_off, shape, strides_elems):
+def _view_at(addr, dt_code, shape, strides_elems):
+    """A numpy view of the strided tensor whose element 0 lives at host address `addr`."""
+    import ctypes
     dt = np_dtype(dt_code)
     es = np.dtype(dt).itemsize
-    arr = buf[byte_off:].view(np.uint8)
     need = (1 + sum((s - 1) * st for s, st in zip(shape, strides_elems))) * es if all(s > 0 for s in shape) else 0
-    base = arr[:need].view(dt)
+    base = np.frombuffer((ctypes.c_uint8 * need).from_address(addr), dtype=dt)
     return np.lib.stride_tricks.as_strided(base, shape=shape, strides=[st * es for st in strides_elems],
                                            writeable=False)
 
 
-def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, mode=oracle.MODE_F64CORE):
-    """Per task: run the oracle on the inputs the GPU saw (gpu_images) into a scratch copy of the
-    pools and compare the task's output elements.  Returns a stats dict; raises AssertionError on
-    any violation."""
+def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, mode=oracle.MODE_F64CORE, task_arrays=None):
+    """Per task: run the oracle on the inputs the GPU saw into scratch memory and compare the task's
+    output elements with what the GPU wrote.  By default the GPU's memory is given as pool images
+    (gpu_images) and the oracle writes into a copy of them.  task_arrays=(tg, to, t0) gives two task
+    arrays with HOST pointers instead (gpu_images is then unused) whose rows are the stream's tasks
+    t0, t0+1, ...: identical inputs (what the GPU saw), tg's outputs are the GPU's results, to's
+    outputs are scratch the oracle writes.  Returns a stats dict; raises AssertionError on any
+    violation."""
     n = len(stream) - first if count is None else count
     impls = stream.impl_for(versions)
-    gpu = [np.ascontiguousarray(a) for a in gpu_images]
-    orc = [a.copy() for a in gpu]
-    in_bases = [a.ctypes.data for a in gpu]
-    out_bases = [a.ctypes.data for a in orc]
-    tasks = stream.materialize(in_bases, out_bases)
-    st = oracle.run_stream(tasks, impls, mode, first, n, programs=stream.programs)
+    if task_arrays is None:
+        gpu = [np.ascontiguousarray(a) for a in gpu_images]
+        orc = [a.copy() for a in gpu]
+        in_bases = [a.ctypes.data for a in gpu]
+        tg = stream.materialize(in_bases)
+        tasks = stream.materialize(in_bases, [a.ctypes.data for a in orc])
+        t0 = 0
+    else:
+        tg, tasks, t0 = task_arrays
+        assert t0 <= first and first + n <= t0 + len(tasks)
+    st = oracle.run_stream(tasks, impls[t0: t0 + len(tasks)], mode, first - t0, n, programs=stream.programs)
     assert np.all(st == 0), "oracle rejected tasks: %s" % np.nonzero(st)[0][:10]
     stats = dict(max_ulp=0, max_red_ratio=0.0, tasks=n, elements=0)
     T = stream.tasks
@@ -106,9 +116,9 @@ def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, 
             oshape, ostr = [1], [1]
         if any(s == 0 for s in oshape):
             continue
-        pool, off, dt = int(stream.pool_of[i, 3]), int(T["out"]["ptr"][i]), int(T["out"]["dtype"][i])
-        g = _strided(gpu[pool], dt, off, oshape, ostr)
-        o = _strided(orc[pool], dt, off, oshape, ostr)
+        dt = int(T["out"]["dtype"][i])
+        g = _view_at(int(tg["out"]["ptr"][i - t0]), dt, oshape, ostr)
+        o = _view_at(int(tasks["out"]["ptr"][i - t0]), dt, oshape, ostr)
         stats["elements"] += g.size
         if dt == S.I32:
             assert np.array_equal(g, o), "task %d (%s): integer mismatch" % (i, S.IMPL_NAME[impl])
@@ -117,7 +127,7 @@ def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, 
         gb, ob = np.ascontiguousarray(g).view(bits), np.ascontiguousarray(o).view(bits)
         if impl == S.IMPL["SUM_LAST"]:
             nrows = int(np.prod(oshape))
-            s64, l1 = oracle.sum_last_f64(tasks, i, nrows)
+            s64, l1 = oracle.sum_last_f64(tasks, i - t0, nrows)
             gv = _as_f64(gb, dt).reshape(-1)
             tol = RED_REL * np.maximum(np.abs(s64), l1 / math.sqrt(size[-1]))
             if dt != S.F32:
@@ -132,9 +142,10 @@ def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, 
             continue
         if impl in S.ROWOPS:
             # fp32 evaluation of the exact row function: error <= ROW_REL * (the magnitude the
-            # rounding errors scale with, from the oracle) + half a step of a 16-bit output
+            # rounding errors scale with) + half a step of a 16-bit output
             # format + the flush of results below fp32's normal range
-            y64, scale = oracle.rowop_f64(tasks, i, impl)
+            y64 = oracle.rowop_f64(tasks, i - t0, impl)
+            scale = rowop_error_scale(tasks, i - t0, impl, y64)
             gv = _as_f64(gb, dt).reshape(y64.shape)
             tol = ROW_REL * scale + ROW_ABS
             if dt != S.F32:
@@ -146,6 +157,8 @@ def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, 
             assert np.array_equal(np.isnan(gv), np.isnan(y64)), "task %d (%s): NaN pattern differs" % (i, S.IMPL_NAME[impl])
             assert ratio <= 1.0, "task %d (%s, dtype %d): error %.3g x tolerance at flat index %d" % (
                 i, S.IMPL_NAME[impl], dt, ratio, int(np.argmax(np.where(fin, err / tol, 0))))
+            continue
+        if np.array_equal(gb, ob):                             # identical bit patterns: 0 ulp, nothing more to measure
             continue
         d = ulp_distance(gb, ob, dt)
         mx = int(d.max()) if d.size else 0
@@ -161,6 +174,38 @@ def compare_with_oracle(stream, gpu_images, versions=None, first=0, count=None, 
             raise AssertionError("task %d (%s, dtype %d): %d ulp at flat index %d: gpu %r oracle %r" % (
                 i, S.IMPL_NAME.get(impl, "program %d" % impl), dt, mx, k, gb.reshape(-1)[k], ob.reshape(-1)[k]))
     return stats
+
+
+def _input_f64(tasks, i, k, shape):
+    """Input k of task i (host pointers) as float64 in the task's shape, broadcast dims expanded."""
+    rec = tasks["inp"][i, k]
+    dt = int(rec["dtype"])
+    strides = [0 if (int(rec["bcast_mask"]) >> d) & 1 else int(rec["stride"][d]) for d in range(len(shape))]
+    v = _view_at(int(rec["ptr"]), dt, list(shape), strides)
+    if dt == S.BF16:
+        return bf16_bits_to_f32(np.ascontiguousarray(v)).astype(np.float64).reshape(shape)
+    return np.asarray(v, dtype=np.float64)
+
+
+def rowop_error_scale(tasks, i, impl, y64):
+    """Per element, the magnitude the rounding errors of a float32 evaluation of a row operation
+    scale with (the gate is 2^-22 times this; derivation in the design notes).  Test logic, computed
+    from the oracle's unrounded results y64 and the task's inputs:
+    softmax family: y * (|t - max t| + 8 + log2 n), where t is the softmax argument; the distance to
+      the row maximum is read off the result itself, |t_j - max t| = ln(max_k y_k / y_j);
+    layer norm: (|x| + |mean| + max_k |x_k - mean|) * rstd * |gamma| + |beta|."""
+    n = y64.shape[-1]
+    if impl != S.IMPL["LAYERNORM_LAST"]:
+        with np.errstate(divide="ignore", invalid="ignore"):
+            dist = np.log(y64.max(axis=-1, keepdims=True)) - np.log(y64)
+        dist = np.where(np.isfinite(dist), dist, 0.0)            # entries that are exactly 0 (a -inf argument): scale 0
+        return y64 * (dist + 8.0 + math.log2(n))
+    alpha = float(tasks["alpha"][i])
+    x, g, b = (_input_f64(tasks, i, k, y64.shape) for k in range(3))
+    mean = x.mean(axis=-1, keepdims=True)
+    dev = x - mean
+    rstd = 1.0 / np.sqrt((dev * dev).mean(axis=-1, keepdims=True) + alpha)
+    return (np.abs(x) + np.abs(mean) + np.abs(dev).max(axis=-1, keepdims=True)) * rstd * np.abs(g) + np.abs(b)
 
 
 def _as_f64(bits, dt):

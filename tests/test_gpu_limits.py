@@ -11,6 +11,7 @@ import oracle
 from paper_2604_17861_amd import runtime as R
 from paper_2604_17861_amd import streams as S
 from helpers import Builder, run_oracle
+from gpu_helpers import rowop_error_scale
 
 pytestmark = pytest.mark.gpu
 CFG = dict(idle_exit_ms=30000, wait_timeout_ms=30000)
@@ -99,7 +100,8 @@ def test_tensors_just_under_two_to_the_31_elements():
     for r in (0, 524287, rows - 1):
         got = outs[3][r * n: (r + 1) * n].cpu().numpy()
         _, s, hp = _oracle("SOFTMAX_LAST", got[None, :], [x[r * n: (r + 1) * n].cpu().numpy()[None, :]])
-        y64, scale = oracle.rowop_f64(hp.tasks, 0, S.IMPL["SOFTMAX_LAST"])
+        y64 = oracle.rowop_f64(hp.tasks, 0, S.IMPL["SOFTMAX_LAST"])
+        scale = rowop_error_scale(hp.tasks, 0, S.IMPL["SOFTMAX_LAST"], y64)
         tol = 2.0 ** -22 * scale + 2.0 ** (np.floor(np.log2(np.maximum(y64, 2.0 ** -14))) - 10)
         assert np.all(np.abs(got.astype(np.float64)[None, :] - y64) <= tol), r
     assert abs(float(outs[3][(rows - 1) * n: rows * n].float().sum()) - 1.0) < 1e-2

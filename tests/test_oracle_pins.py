@@ -212,6 +212,12 @@ def test_reductions_hand_values():
     run1("MIN_LAST", o, [a]); assert o.tolist() == [1, 4]
     run1("MAX_LAST", o, [np.array([[1, np.nan, 3], [-np.inf, -5, -7]], np.float32)])
     assert np.isnan(o[0]) and o[1] == -5
+    # MIN propagates NaN wherever it stands in the row, and -inf / +inf are ordinary values
+    o4 = np.zeros(4, np.float32)
+    run1("MIN_LAST", o4, [np.array([[np.nan, 1, 3], [2, 7, np.nan], [np.inf, -5, -np.inf], [np.inf, np.inf, np.inf]], np.float32)])
+    assert np.isnan(o4[0]) and np.isnan(o4[1]) and o4[2] == -np.inf and o4[3] == np.inf
+    run1("MAX_LAST", o4, [np.array([[3, 1, np.nan], [np.nan, 7, 2], [-np.inf, -5, np.inf], [-np.inf, -np.inf, -np.inf]], np.float32)])
+    assert np.isnan(o4[0]) and np.isnan(o4[1]) and o4[2] == np.inf and o4[3] == -np.inf
     # reduce a transposed view: column sums of a
     o3 = np.zeros(3, np.float32)
     run1("SUM_LAST", o3, [a.T]); assert o3.tolist() == [5, 7, 9]

@@ -43,7 +43,7 @@ def test_softmax_two_elements_is_the_logistic_function():
         b.add("SOFTMAX_LAST", o, [x])
         return [o]
     s, hp, (y,) = _run(build)
-    y64, _ = _f64(s, hp)
+    y64 = _f64(s, hp)
     for k, (a, c) in enumerate(rows.astype(np.float64)):
         want0 = 1.0 / (1.0 + math.exp(c - a))
         assert abs(y64[k, 0] - want0) <= 4e-16 and abs(y64[k, 1] - (1.0 - want0)) <= 4e-16
@@ -90,10 +90,9 @@ def test_softmax_matches_scipy_on_strided_views(code):
         return [o]
     s, hp, (y,) = _run(build)
     want = scipy.special.softmax(as64.transpose(0, 2, 1)[:, ::2, 1:], axis=-1)
-    y64, scale = _f64(s, hp)
+    y64 = _f64(s, hp)
     assert np.abs(y64 - want).max() <= 1e-15
     assert np.array_equal(y, want.astype(np.float32))
-    assert np.all(scale >= 8 * y64) and np.all(scale <= (8 + 40 + 6) * y64 + 1e-300)
 
 
 def test_masked_softmax_scales_then_masks_and_broadcasts_the_mask():
@@ -112,7 +111,7 @@ def test_masked_softmax_scales_then_masks_and_broadcasts_the_mask():
     s, hp, (y,) = _run(build)
     t = alpha * xs.astype(np.float64) + mask.astype(np.float64)
     want = scipy.special.softmax(t, axis=-1)
-    y64, _ = _f64(s, hp)
+    y64 = _f64(s, hp)
     assert np.abs(y64 - want).max() <= 1e-15
     iu = np.triu_indices(n, 1)
     assert not y[:, :, iu[0], iu[1]].any()              # exp(-inf) is exactly 0
@@ -226,10 +225,9 @@ def test_layernorm_matches_torch_float64_on_strided_views(code):
     want = torch.nn.functional.layer_norm(torch.from_numpy(x64[:, ::2].copy()), (n,), torch.from_numpy(g64),
                                           torch.from_numpy(braw.astype(np.float64)),
                                           eps=float(np.float32(eps))).numpy()
-    y64, scale = _f64(s, hp)
+    y64 = _f64(s, hp)
     assert np.abs(y64 - want).max() <= 1e-13
     assert np.abs(y.astype(np.float64) - want).max() <= 2.0 ** -23 * np.abs(want).max()
-    assert np.all(scale >= np.abs(y64))
 
 
 def test_layernorm_output_statistics_closed_form():
@@ -244,7 +242,7 @@ def test_layernorm_output_statistics_closed_form():
         b.add("LAYERNORM_LAST", o, [x, np.broadcast_to(one, xs.shape), np.broadcast_to(zero, xs.shape)], alpha=eps)
         return [o]
     s, hp, _ = _run(build)
-    y64, _ = _f64(s, hp)
+    y64 = _f64(s, hp)
     var = xs.astype(np.float64).var(-1)
     assert np.abs(y64.mean(-1)).max() < 1e-14
     assert np.abs(y64.var(-1) - var / (var + eps)).max() < 1e-13
@@ -262,7 +260,7 @@ def test_rowop_outputs_round_through_fp32_to_the_output_dtype():
         b.add("SOFTMAX_LAST", ob, [x])
         return [oh, ob]
     s, hp, (yh, yb) = _run(build)
-    y64, _ = _f64(s, hp)
+    y64 = _f64(s, hp)
     f32 = y64.astype(np.float32)
     assert np.array_equal(yh, f32.astype(np.float16))
     assert np.array_equal(yb, torch.from_numpy(f32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
