@@ -297,6 +297,39 @@ void gpuos_default_config(gpuos_config* cfg);
  * cfg: NULL => defaults on the current device.  *out receives the context. */
 int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* cfg);
 
+/* gpuos_init for callers that cannot allocate (harnesses that forbid hipMalloc /
+ * hipHostMalloc at run time, serving loops that set a context up and tear it down
+ * over and over): the same context and the same worker kernel, but the call
+ * allocates nothing, neither on the device nor on the host.  The device-side state
+ * (control block, ring mirror, work-unit ring, done words, operator table) lives in
+ * a file-scope device array of the library, about 8.3 MiB that every GPU the library
+ * is loaded on holds until the process ends; everything the host side needs (the
+ * context object, ring, doorbell, completion words and log, table source, programs)
+ * lives in host_block.
+ *   queue_capacity: power of two in [2, GPUOS_STATIC_MAX_CAPACITY]; 0 => the maximum.
+ *     A larger value is GPUOS_E_INVAL (gpuos_last_hip_error() says why).
+ *   cfg: as for gpuos_init (NULL => defaults); push_ring is ignored (the ring is
+ *     in host_block, polled by the device); harvester_thread and trace_entries must
+ *     be 0 (they allocate); completion_log is queue_capacity.
+ *   host_block: caller-owned HOST memory that the device can read and write
+ *     coherently (hipHostMalloc with hipHostMallocCoherent | hipHostMallocMapped, or
+ *     the like), 256-byte aligned, host_bytes >= GPUOS_STATIC_HOST_BYTES(queue_capacity).
+ *     The library clears it.  It must stay untouched until gpuos_shutdown() has
+ *     returned; gpuos_shutdown() does not free it.
+ *   stream: a hipStream_t of the caller's on cfg.device (not the null stream; created
+ *     non-blocking) that carries nothing but the worker until gpuos_shutdown(); the
+ *     library does not destroy it.
+ * All contexts made by this call on one GPU share that GPU's array, which keeps
+ * what the previous one left: the call clears it, and only ONE such context can be
+ * alive per GPU at a time: a second call before gpuos_shutdown() of the first
+ * returns GPUOS_E_FULL instead of racing.  gpuos_worker_elapsed_ms is not available
+ * on such a context (no events); every other call works as on any context
+ * (gpuos_register_op and gpuos_define_program keep their audit records on the heap). */
+#define GPUOS_STATIC_MAX_CAPACITY 1024
+#define GPUOS_STATIC_HOST_BYTES(capacity) (65536ull + 512ull * (capacity))
+int gpuos_init_static(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* cfg,
+                      void* host_block, uint64_t host_bytes, void* stream);
+
 /* Operator table (paper Section 4.1 "Dynamic Operator Table"; dual-slot
  * update protocol).  Each logical op id owns two slots {impl, version} and a
  * version word; the active slot is version & 1.

@@ -210,7 +210,28 @@ struct WorkerArgs {
   uint64_t   dep_wait_ticks; // bound on a worker's wait for a dependency; 100 MHz ticks
 };
 
+// Where the device-side state of a context lies inside one block of device memory (the context
+// created by gpuos_init_static keeps it in a file-scope device array instead of allocating it).
+constexpr uint32_t kStaticMaxCapacity = 1024;
+struct StaticLayout { size_t d, dring, units, st, dtable, total; };
+constexpr size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+constexpr StaticLayout static_layout(uint32_t cap) {
+  StaticLayout l{};
+  l.d = 0;
+  l.dring = align_up(l.d + sizeof(DevCtl), 256);
+  l.units = align_up(l.dring + sizeof(Record) * cap, 256);
+  l.st = align_up(l.units + sizeof(uint64_t) * (size_t)cap * kMaxChunksPerTask, 256);
+  l.dtable = align_up(l.st + sizeof(SlotState) * cap, 256);
+  l.total = align_up(l.dtable + sizeof(OpSlots) * GPUOS_MAX_OPS, 256);
+  return l;
+}
+constexpr size_t kStaticScratchBytes = static_layout(kStaticMaxCapacity).total;   // about 8.3 MiB
+
 // implemented in gpuos_kernels.hip
+// Address, on `device`, of the file-scope device array that holds the device-side state of a
+// context made by gpuos_init_static (each GPU has its own copy at its own address; looked up once
+// per device).  Returns a hipError_t.
+int static_scratch(int device, void** out);
 int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream);
 // Before a worker is launched again on a context that has run before (same stream, ahead of it):
 // the workgroups of the last run left with claims they never served.

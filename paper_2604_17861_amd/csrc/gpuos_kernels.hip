@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/gpuos.h"
 #include "gpuos_internal.h"
 
@@ -2305,6 +2307,34 @@ __global__ void gpuos_resume_fixup_kernel(DevCtl* d) {
 int launch_resume_fixup(DevCtl* d, void* stream) {
   hipLaunchKernelGGL(gpuos_resume_fixup_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, d);
   return (int)hipGetLastError();
+}
+
+// Device-side state (control block, ring mirror, work-unit ring, slot state, operator table) of the
+// one context per GPU that gpuos_init_static creates: a file-scope array instead of hipMalloc.  In
+// host code the name `scratch` is only a handle for the symbol, not a device address: the address
+// on each GPU comes from hipGetSymbolAddress, once per device, with that device current, and that
+// pointer is what the host passes on (memset, kernel arguments).
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch(int device, void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  if (device < 0 || device >= kMaxDevices || !out) return (int)hipErrorInvalidValue;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptr[device]) {
+    int cur = 0;
+    hipError_t e = hipGetDevice(&cur);
+    if (e == hipSuccess && cur != device) e = hipSetDevice(device);
+    void* p = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (cur != device) (void)hipSetDevice(cur);
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    ptr[device] = p;
+  }
+  *out = ptr[device];
+  return (int)hipSuccess;
 }
 
 int launch_worker(const WorkerArgs& a, uint32_t grid, void* stream) {

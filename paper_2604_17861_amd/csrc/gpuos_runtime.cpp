@@ -12,7 +12,6 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <deque>
 #include <mutex>
 #include <new>
 #include <string>
@@ -520,15 +519,17 @@ struct gpuos_ctx {
   std::atomic<int32_t> first_error{0};
   uint64_t epoch = 0;
   OpInfo ops[GPUOS_MAX_OPS];
-  // completion log
-  std::vector<gpuos_completion> log;
+  // completion log (log points into log_store, or into the caller's block for a static context)
+  std::vector<gpuos_completion> log_store;
+  gpuos_completion* log = nullptr;
   uint64_t log_mask = 0;
   // harvester
   std::thread harvester;
   std::atomic<bool> harvester_run{false};
   bool worker_running = false;
-  std::deque<gpuos_audit_record> audit;   // latest kAuditKeep changes of the operator table (under prod_mu)
+  std::vector<gpuos_audit_record> audit;  // latest kAuditKeep changes of the operator table, a ring once full (under prod_mu)
   uint64_t audit_total = 0;
+  bool static_mode = false;               // made by gpuos_init_static: the library owns neither the memory nor the stream
   uint64_t prog_hash[GPUOS_MAX_PROGRAMS] = {};
   uint32_t prog_len[GPUOS_MAX_PROGRAMS] = {};
   WorkerArgs wargs{};                     // what the worker was launched with (gpuos_start_worker launches it again)
@@ -631,6 +632,7 @@ void bump_epoch(gpuos_ctx* c, uint32_t op_hint, bool stop) {
 }
 
 void free_all(gpuos_ctx* c) {
+  if (c->static_mode) return;               // the caller's host block and stream, the library's device array: nothing to free
   if (c->h) (void)hipHostFree(c->h);
   if (c->hcomp) (void)hipHostFree(c->hcomp);
   if (c->trace) (void)hipHostFree(c->trace);
@@ -699,6 +701,9 @@ int stop_worker(gpuos_ctx* c) {
   return rc;
 }
 
+constexpr int kMaxStaticDevices = 64;
+std::atomic<gpuos_ctx*> g_static_owner[kMaxStaticDevices];       // the context that holds a device's static array
+
 void shutdown_all_at_exit() {
   std::vector<gpuos_ctx*> live;
   {
@@ -706,8 +711,81 @@ void shutdown_all_at_exit() {
     live = g_live;
   }
   for (gpuos_ctx* c : live) (void)stop_worker(c);
+  for (auto& o : g_static_owner)
+    if (gpuos_ctx* c = o.load()) (void)stop_worker(c);
 }
 
+}  // namespace
+
+
+namespace {
+// Size the grid, launch the persistent worker for the first time and wait for its first heartbeat.
+// On GPUOS_E_TIMEOUT with !worker_joined the kernel is still queued: the caller must keep the memory.
+int launch_first_worker(gpuos_ctx* c, int compute_units, size_t n_units) {
+  const gpuos_config& cfg = c->cfg;
+  // size the grid to what is co-resident: every workgroup must be running for
+  // the spin-waits (claims, dependencies) to be deadlock-free
+  int occ = 0;
+  if (!hip_ok((hipError_t)worker_max_blocks_per_cu(&occ), "hipOccupancyMaxActiveBlocksPerMultiprocessor")) return GPUOS_E_HIP;
+  if (occ < 1) return GPUOS_E_HIP;
+  uint32_t per_cu = cfg.workgroups_per_cu;
+  if (per_cu > (uint32_t)occ) per_cu = (uint32_t)occ;
+  c->workgroups = (uint32_t)compute_units * per_cu;
+  if (c->workgroups < 2) c->workgroups = 2;
+  c->cfg.workgroups_per_cu = per_cu;
+
+  WorkerArgs a;
+  a.h = c->h; a.bell = c->bell; a.hring = c->hring; a.hcomp = c->hcomp; a.htable = c->htable;
+  a.d = c->d; a.dring = c->dring; a.units = c->units; a.st = c->st; a.dtable = c->dtable;
+  a.cap_mask = c->mask;
+  a.unit_mask = (uint32_t)(n_units - 1);
+  a.unit_shift = 0;
+  while (((size_t)1 << a.unit_shift) < n_units) ++a.unit_shift;
+  a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
+  a.progs = c->progs;
+  a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
+  a.resume = 0; a.resume_tickets = 0;
+  a.timing = cfg.phase_timers ? 1u : 0u;
+  a.dep_wait_ticks = cfg.dep_wait_us ? (uint64_t)cfg.dep_wait_us * 100ull : (uint64_t)cfg.wait_timeout_ms * 100000ull;
+  c->wargs = a;
+  if (c->ev_start && !hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return GPUOS_E_HIP;
+  if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return GPUOS_E_HIP;
+  if (c->ev_stop && !hip_ok(hipEventRecord(c->ev_stop, c->stream), "hipEventRecord")) return GPUOS_E_HIP;
+  c->worker_running = true;
+
+  // wait for the first heartbeat so that init returns with a live worker
+  {
+    const uint64_t t0 = now_ns();
+    uint32_t spins = 0;
+    while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
+      if ((spins & 255u) == 0 && now_ns() - t0 > c->wait_ns) {
+        // The kernel never started (the device is busy with other work).  Ask it to exit as soon as it
+        // does; if it still has not finished, its memory must stay: freeing under a queued
+        // kernel would fault when it finally runs.
+        (void)stop_worker(c);
+        return GPUOS_E_TIMEOUT;
+      }
+      // look at the stream only now and then: the moment the heartbeat is seen ties the device
+      // clock to the host clock, and a stream query takes microseconds
+      if ((++spins & 4095u) == 0 && hipStreamQuery(c->stream) != hipErrorNotReady) return GPUOS_E_DEAD;
+      __builtin_ia32_pause();
+    }
+  }
+  c->origin_host_ns = now_ns();
+  if (cfg.harvester_thread) {
+    c->harvester_run.store(true);
+    c->harvester = std::thread(harvester_main, c, sched_getcpu());
+  }
+  if (!c->static_mode) {
+    std::lock_guard<std::mutex> lk(g_live_mu);
+    g_live.push_back(c);
+  }
+  {
+    std::lock_guard<std::mutex> lk(g_live_mu);
+    if (!g_atexit_registered) { std::atexit(shutdown_all_at_exit); g_atexit_registered = true; }
+  }
+  return GPUOS_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -753,11 +831,12 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   uint64_t logcap = 1;
   while (logcap < cfg.completion_log || logcap < cap) logcap <<= 1;
   try {
-    c->log.assign(logcap, gpuos_completion{});
+    c->log_store.assign(logcap, gpuos_completion{});
   } catch (const std::bad_alloc&) {                             // no exception may cross the C boundary
     delete c;
     return GPUOS_E_NOMEM;
   }
+  c->log = c->log_store.data();
   c->log_mask = logcap - 1;
 
   auto fail = [&](int rc) { free_all(c); delete c; return rc; };
@@ -826,66 +905,112 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       !hip_ok(hipStreamSynchronize(c->stream), "hipStreamSynchronize"))
     return fail(GPUOS_E_HIP);
 
-  // size the grid to what is co-resident: every workgroup must be running for
-  // the spin-waits (claims, dependencies) to be deadlock-free
-  int occ = 0;
-  if (!hip_ok((hipError_t)worker_max_blocks_per_cu(&occ), "hipOccupancyMaxActiveBlocksPerMultiprocessor")) return fail(GPUOS_E_HIP);
-  if (occ < 1) return fail(GPUOS_E_HIP);
-  uint32_t per_cu = cfg.workgroups_per_cu;
-  if (per_cu > (uint32_t)occ) per_cu = (uint32_t)occ;
-  c->workgroups = (uint32_t)prop.multiProcessorCount * per_cu;
-  if (c->workgroups < 2) c->workgroups = 2;
-  c->cfg.workgroups_per_cu = per_cu;
-
-  WorkerArgs a;
-  a.h = c->h; a.bell = c->bell; a.hring = c->hring; a.hcomp = c->hcomp; a.htable = c->htable;
-  a.d = c->d; a.dring = c->dring; a.units = c->units; a.st = c->st; a.dtable = c->dtable;
-  a.cap_mask = c->mask;
-  a.unit_mask = (uint32_t)(n_units - 1);
-  a.unit_shift = 0;
-  while (((size_t)1 << a.unit_shift) < n_units) ++a.unit_shift;
-  a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
-  a.progs = c->progs;
-  a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
-  a.resume = 0; a.resume_tickets = 0;
-  a.timing = cfg.phase_timers ? 1u : 0u;
-  a.dep_wait_ticks = cfg.dep_wait_us ? (uint64_t)cfg.dep_wait_us * 100ull : (uint64_t)cfg.wait_timeout_ms * 100000ull;
-  c->wargs = a;
-  if (!hip_ok(hipEventRecord(c->ev_start, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
-  if (!hip_ok((hipError_t)launch_worker(a, c->workgroups, c->stream), "launch worker")) return fail(GPUOS_E_HIP);
-  if (!hip_ok(hipEventRecord(c->ev_stop, c->stream), "hipEventRecord")) return fail(GPUOS_E_HIP);
-  c->worker_running = true;
-
-  // wait for the first heartbeat so that init returns with a live worker
   {
-    const uint64_t t0 = now_ns();
-    uint32_t spins = 0;
-    while (__atomic_load_n(&c->h->heartbeat, __ATOMIC_ACQUIRE) == 0) {
-      if ((spins & 255u) == 0 && now_ns() - t0 > c->wait_ns) {
-        // The kernel never started (the device is busy with other work).  Ask it to exit as soon as it
-        // does; if it still has not finished, keep its memory alive: freeing under a queued
-        // kernel would fault when it finally runs.
-        (void)stop_worker(c);
-        if (!c->worker_joined) return GPUOS_E_TIMEOUT;
-        return fail(GPUOS_E_TIMEOUT);
-      }
-      // look at the stream only now and then: the moment the heartbeat is seen ties the device
-      // clock to the host clock, and a stream query takes microseconds
-      if ((++spins & 4095u) == 0 && hipStreamQuery(c->stream) != hipErrorNotReady) { return fail(GPUOS_E_DEAD); }
-      __builtin_ia32_pause();
-    }
-  }
-  c->origin_host_ns = now_ns();
-  if (cfg.harvester_thread) {
-    c->harvester_run.store(true);
-    c->harvester = std::thread(harvester_main, c, sched_getcpu());
-  }
-  {
-    std::lock_guard<std::mutex> lk(g_live_mu);
-    g_live.push_back(c);
-    if (!g_atexit_registered) { std::atexit(shutdown_all_at_exit); g_atexit_registered = true; }
+    const int rc = launch_first_worker(c, prop.multiProcessorCount, n_units);
+    if (rc == GPUOS_E_TIMEOUT && !c->worker_joined) return rc;    // the kernel may still start: its memory stays
+    if (rc != GPUOS_OK) return fail(rc);
   }
   marker(cfg.markers != 0, "gpuos: worker launched, %llu workgroups, ring of %llu slots", c->workgroups, c->cap);
+  *out = c;
+  return GPUOS_OK;
+}
+
+namespace {
+// Where the host-side pieces of a static context lie inside the caller's block.
+struct StaticHostLayout { size_t ctx, h, bell, ring, comp, table, progs, log, total; };
+constexpr StaticHostLayout static_host_layout(uint32_t cap) {
+  StaticHostLayout l{};
+  l.ctx = 0;
+  l.h = align_up(l.ctx + sizeof(gpuos_ctx), 256);
+  l.bell = align_up(l.h + sizeof(HostCtl), 256);
+  l.ring = align_up(l.bell + sizeof(DoorbellCtl), 256);
+  l.comp = align_up(l.ring + sizeof(Record) * cap, 256);
+  l.table = align_up(l.comp + sizeof(uint64_t) * cap, 256);
+  l.progs = align_up(l.table + sizeof(OpSlots) * GPUOS_MAX_OPS, 256);
+  l.log = align_up(l.progs + sizeof(ProgramImage) * GPUOS_MAX_PROGRAMS, 256);
+  l.total = align_up(l.log + sizeof(gpuos_completion) * cap, 256);
+  return l;
+}
+static_assert(static_host_layout(GPUOS_STATIC_MAX_CAPACITY).total <= GPUOS_STATIC_HOST_BYTES(GPUOS_STATIC_MAX_CAPACITY) &&
+              static_host_layout(2).total <= GPUOS_STATIC_HOST_BYTES(2), "GPUOS_STATIC_HOST_BYTES must cover the layout");
+static_assert(GPUOS_STATIC_MAX_CAPACITY == kStaticMaxCapacity, "one limit");
+}  // namespace
+
+int gpuos_init_static(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* user_cfg,
+                      void* host_block, uint64_t host_bytes, void* stream) {
+  if (!out) return GPUOS_E_INVAL;
+  *out = nullptr;
+  gpuos_config cfg;
+  if (user_cfg) cfg = *user_cfg; else gpuos_default_config(&cfg);
+  if (cfg.threads_per_workgroup == 0) cfg.threads_per_workgroup = kThreads;
+  if (cfg.workgroups_per_cu == 0) cfg.workgroups_per_cu = 3;
+  if (cfg.wait_timeout_ms == 0) cfg.wait_timeout_ms = 30000;
+  if (cfg.chunk_elems == 0) cfg.chunk_elems = kChunkElems;
+  cfg.chunk_elems = (cfg.chunk_elems + 1023u) / 1024u * 1024u;
+  const uint32_t cap = queue_capacity ? queue_capacity : kStaticMaxCapacity;
+  auto reject = [](const char* why) { g_hip_error = std::string("gpuos_init_static: ") + why; return GPUOS_E_INVAL; };
+  if (cfg.threads_per_workgroup != kThreads) return reject("only 256 threads per workgroup are built");
+  if (cap < 2 || (cap & (cap - 1)) != 0) return reject("queue_capacity must be a power of two >= 2");
+  if (cap > kStaticMaxCapacity) return reject("queue_capacity exceeds GPUOS_STATIC_MAX_CAPACITY (1024): the device-side state would not fit the static array");
+  if (cfg.device < 0 || cfg.device >= kMaxStaticDevices) return reject("device ordinal out of range");
+  if (cfg.harvester_thread || cfg.trace_entries) return reject("harvester_thread and trace_entries need allocations: not available here");
+  if (!host_block || ((uintptr_t)host_block & 255u) != 0) return reject("host_block must be 256-byte aligned");
+  const StaticHostLayout hl = static_host_layout(cap);
+  if (host_bytes < hl.total) return reject("host_block is smaller than GPUOS_STATIC_HOST_BYTES(queue_capacity)");
+  if (!stream) return reject("a stream of the caller's is required (not the null stream)");
+
+  // One static context per device: the array is shared by every call on that GPU.
+  gpuos_ctx* expected = nullptr;
+  gpuos_ctx* const self = reinterpret_cast<gpuos_ctx*>((char*)host_block + hl.ctx);
+  if (!g_static_owner[cfg.device].compare_exchange_strong(expected, self)) {
+    g_hip_error = "gpuos_init_static: this device's static array is held by a live context";
+    return GPUOS_E_FULL;
+  }
+  auto release = [&](int rc) { g_static_owner[cfg.device].store(nullptr); return rc; };
+  if (!hip_ok(hipSetDevice(cfg.device), "hipSetDevice")) return release(GPUOS_E_HIP);
+  int cus = 0;
+  if (!hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg.device), "hipDeviceGetAttribute") || cus < 1)
+    return release(GPUOS_E_HIP);
+  void* base = nullptr;                                          // this device's copy of the static array
+  if (!hip_ok((hipError_t)static_scratch(cfg.device, &base), "hipGetSymbolAddress(scratch)")) return release(GPUOS_E_HIP);
+
+  std::memset(host_block, 0, hl.total);
+  gpuos_ctx* c = new (self) gpuos_ctx();                         // placement: no allocation
+  c->static_mode = true;
+  cfg.push_ring = 0;                                             // the ring lives in the caller's host memory
+  cfg.completion_log = cap;
+  c->cfg = cfg;
+  c->device = cfg.device;
+  c->cap = cap;
+  c->mask = cap - 1;
+  c->wait_ns = (uint64_t)cfg.wait_timeout_ms * 1000000ull;
+  char* hb = (char*)host_block;
+  c->h = (HostCtl*)(hb + hl.h);
+  c->bell = (DoorbellCtl*)(hb + hl.bell);
+  c->hring = (Record*)(hb + hl.ring);
+  c->hcomp = (uint64_t*)(hb + hl.comp);
+  c->htable = (OpSlots*)(hb + hl.table);
+  c->progs = (ProgramImage*)(hb + hl.progs);
+  c->log = (gpuos_completion*)(hb + hl.log);
+  c->log_mask = cap - 1;
+  c->push = false;
+  c->stream = (hipStream_t)stream;
+  const StaticLayout dl = static_layout(cap);
+  char* db = (char*)base;
+  c->d = (DevCtl*)(db + dl.d);
+  c->dring = (Record*)(db + dl.dring);
+  c->units = (uint64_t*)(db + dl.units);
+  c->st = (SlotState*)(db + dl.st);
+  c->dtable = (OpSlots*)(db + dl.dtable);
+  const size_t n_units = (size_t)cap * kMaxChunksPerTask;
+  auto fail = [&](int rc) { c->~gpuos_ctx(); return release(rc); };
+  // The array keeps what the previous context left in it: everything this one reads before it
+  // writes starts at zero (counters, stamps of the unit ring, done words, the table).  Same
+  // stream as the worker, so the kernel starts after the clears.
+  if (!hip_ok(hipMemsetAsync(base, 0, dl.total, c->stream), "hipMemsetAsync(scratch)")) return fail(GPUOS_E_HIP);
+  const int rc = launch_first_worker(c, cus, n_units);
+  if (rc == GPUOS_E_TIMEOUT && !c->worker_joined) return rc;      // the kernel may still start: the array stays taken
+  if (rc != GPUOS_OK) return fail(rc);
   *out = c;
   return GPUOS_OK;
 }
@@ -909,8 +1034,8 @@ void audit(gpuos_ctx* c, uint32_t kind, uint32_t op_id, uint32_t impl_id, uint32
                   (unsigned long long)r.head_ticket);
     if (roctx().mark) roctx().mark(buf);
   }
-  if (c->audit.size() == kAuditKeep) c->audit.pop_front();
-  c->audit.push_back(r);
+  if (c->audit.size() < kAuditKeep) c->audit.push_back(r);
+  else c->audit[(size_t)(c->audit_total % kAuditKeep)] = r;
   ++c->audit_total;
 }
 // built-in implementation, or a program this context has defined (caller holds prod_mu)
@@ -1179,9 +1304,9 @@ int gpuos_start_worker(gpuos_ctx* c) {
   a.resume = 1;
   a.resume_tickets = head;
   HIP_TRY((hipError_t)launch_resume_fixup(c->d, c->stream));
-  HIP_TRY(hipEventRecord(c->ev_start, c->stream));
+  if (c->ev_start) HIP_TRY(hipEventRecord(c->ev_start, c->stream));
   HIP_TRY((hipError_t)launch_worker(a, c->workgroups, c->stream));
-  HIP_TRY(hipEventRecord(c->ev_stop, c->stream));
+  if (c->ev_stop) HIP_TRY(hipEventRecord(c->ev_stop, c->stream));
   c->worker_running = true;
   c->worker_joined = false;
   const uint64_t t0 = now_ns();
@@ -1207,7 +1332,7 @@ int gpuos_start_worker(gpuos_ctx* c) {
 
 int gpuos_worker_elapsed_ms(gpuos_ctx* c, float* out_ms) {
   if (!c || !out_ms) return GPUOS_E_INVAL;
-  if (!c->worker_joined) return GPUOS_E_INVAL;
+  if (!c->worker_joined || !c->ev_start) return GPUOS_E_INVAL;   // (a static context has no events)
   HIP_TRY(hipEventElapsedTime(out_ms, c->ev_start, c->ev_stop));
   return GPUOS_OK;
 }
@@ -1230,6 +1355,12 @@ int gpuos_shutdown(gpuos_ctx* c) {
   }
   if (!c->worker_joined) return rc;         // the kernel may still be running: leak rather than free under it
   (void)hipSetDevice(c->device);
+  if (c->static_mode) {                     // the caller's block and stream; the device array goes back to the pool of one
+    const int dev = c->device;
+    c->~gpuos_ctx();
+    g_static_owner[dev].store(nullptr);
+    return rc;
+  }
   free_all(c);
   delete c;
   return rc;
@@ -1351,7 +1482,7 @@ int gpuos_audit_log(gpuos_ctx* c, uint64_t first, uint32_t n, gpuos_audit_record
   if (out_total) *out_total = c->audit_total;
   const uint64_t oldest = c->audit_total - c->audit.size();
   if (first < oldest || first + n > c->audit_total) return GPUOS_E_INVAL;
-  for (uint32_t i = 0; i < n; ++i) out[i] = c->audit[(size_t)(first - oldest) + i];
+  for (uint32_t i = 0; i < n; ++i) out[i] = c->audit[(size_t)((first + i) % kAuditKeep)];   // record k lives at k mod kAuditKeep
   return GPUOS_OK;
 }
 

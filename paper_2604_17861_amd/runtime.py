@@ -76,6 +76,7 @@ def lib():
     sig = {
         "gpuos_default_config": (None, [P(Config)]),
         "gpuos_init": (ctypes.c_int, [P(vp), u32, P(Config)]),
+        "gpuos_init_static": (ctypes.c_int, [P(vp), u32, P(Config), vp, u64, vp]),
         "gpuos_register_op": (ctypes.c_int, [vp, u32, u32, P(u32)]),
         "gpuos_swap_op": (ctypes.c_int, [vp, u32, u32, P(u32)]),
         "gpuos_submit": (ctypes.c_int, [vp, vp, u32, P(u64)]),
@@ -114,12 +115,20 @@ def lib():
     return L
 
 
-EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
+EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_init_static", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker", "gpuos_start_worker",
            "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_define_program", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
            "gpuos_trace_origin", "gpuos_kill_op", "gpuos_audit_log", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
+
+
+STATIC_MAX_CAPACITY = 1024
+
+
+def static_host_bytes(capacity):
+    """GPUOS_STATIC_HOST_BYTES(capacity) of include/gpuos.h."""
+    return 65536 + 512 * int(capacity)
 
 
 def strerror(status):
@@ -181,7 +190,9 @@ _live = weakref.WeakSet()
 class Runtime:
     """One GPUOS context: gpuos_init ... gpuos_shutdown."""
 
-    def __init__(self, queue_capacity=0, **cfg_fields):
+    def __init__(self, queue_capacity=0, static=None, **cfg_fields):
+        """gpuos_init; with static=(host_block_address, host_bytes, stream_handle): gpuos_init_static,
+        the context that allocates nothing (the caller owns the block and the stream)."""
         L = lib()
         cfg = default_config()
         for k, v in cfg_fields.items():
@@ -189,7 +200,12 @@ class Runtime:
                 raise TypeError("unknown config field " + k)
             setattr(cfg, k, v)
         self._ctx = ctypes.c_void_p()
-        _check(L.gpuos_init(ctypes.byref(self._ctx), queue_capacity, ctypes.byref(cfg)), "gpuos_init")
+        if static is None:
+            _check(L.gpuos_init(ctypes.byref(self._ctx), queue_capacity, ctypes.byref(cfg)), "gpuos_init")
+        else:
+            block, nbytes, stream = static
+            _check(L.gpuos_init_static(ctypes.byref(self._ctx), queue_capacity, ctypes.byref(cfg), block, nbytes, stream),
+                   "gpuos_init_static")
         self.cfg = cfg
         _live.add(self)
 

@@ -31,6 +31,8 @@ struct Worker {
 std::mutex g_mu;
 std::map<void*, Worker*> g_workers;               // by stream
 std::atomic<uint64_t> g_errors{0}, g_records{0}, g_retries{0};
+std::atomic<uint64_t> g_alloc_calls{0};             // calls of the allocating / freeing / creating HIP entry points
+alignas(256) unsigned char g_scratch[gpuos::kStaticScratchBytes];   // stands in for the library's file-scope device array
 // Test hook: the consumer leaves "by itself" (exit code 2, as after an idle time-out) in front of this
 // ticket, whatever the doorbell says: the race of an idle exit with a submit, made deterministic.
 std::atomic<uint64_t> g_leave_before{~0ull};
@@ -124,6 +126,13 @@ uint64_t standin_records() { return g_records.load(); }
 uint64_t standin_retries() { return g_retries.load(); }
 void standin_leave_before(uint64_t ticket) { g_leave_before.store(ticket); }
 void standin_stall_ms(uint32_t ms) { g_stall_ms.store(ms); }
+uint64_t standin_alloc_calls() { return g_alloc_calls.load(); }
+void standin_scratch_dirty() { std::memset(g_scratch, 0xAB, sizeof(g_scratch)); }     // what a previous context left behind
+uint64_t standin_scratch_nonzero(uint64_t n) {
+  uint64_t k = 0;
+  for (uint64_t i = 0; i < n && i < sizeof(g_scratch); ++i) k += g_scratch[i] != 0;
+  return k;
+}
 }
 
 namespace gpuos {
@@ -143,14 +152,15 @@ int launch_worker(const WorkerArgs& a, uint32_t, void* stream) {
 int launch_resume_fixup(DevCtl* d, void*) { d->claim = d->tail_units; d->stop_dev = 0; return 0; }
 int worker_max_blocks_per_cu(int* out) { *out = 4; return 0; }
 int launch_single(const Record&, void*) { return 0; }
+int static_scratch(int, void** out) { *out = g_scratch; return 0; }
 }  // namespace gpuos
 
 // ---- the HIP runtime calls the host code makes, on heap memory -------------------------------
 static void* zalloc(size_t n) { void* p = std::aligned_alloc(256, (n + 255) / 256 * 256); if (p) std::memset(p, 0, n); return p; }
-hipError_t hipHostMalloc(void** p, size_t n, unsigned int) { *p = zalloc(n); return *p ? hipSuccess : hipErrorOutOfMemory; }
-hipError_t hipMalloc(void** p, size_t n) { *p = zalloc(n); return *p ? hipSuccess : hipErrorOutOfMemory; }
-hipError_t hipFree(void* p) { std::free(p); return hipSuccess; }
-hipError_t hipHostFree(void* p) { std::free(p); return hipSuccess; }
+hipError_t hipHostMalloc(void** p, size_t n, unsigned int) { g_alloc_calls.fetch_add(1); *p = zalloc(n); return *p ? hipSuccess : hipErrorOutOfMemory; }
+hipError_t hipMalloc(void** p, size_t n) { g_alloc_calls.fetch_add(1); *p = zalloc(n); return *p ? hipSuccess : hipErrorOutOfMemory; }
+hipError_t hipFree(void* p) { g_alloc_calls.fetch_add(1); std::free(p); return hipSuccess; }
+hipError_t hipHostFree(void* p) { g_alloc_calls.fetch_add(1); std::free(p); return hipSuccess; }
 hipError_t hipMemset(void* p, int v, size_t n) { std::memset(p, v, n); return hipSuccess; }
 hipError_t hipMemsetAsync(void* p, int v, size_t n, hipStream_t) { std::memset(p, v, n); return hipSuccess; }
 hipError_t hipMemcpy(void* d, const void* s, size_t n, hipMemcpyKind) { std::memcpy(d, s, n); return hipSuccess; }
@@ -161,12 +171,15 @@ hipError_t hipGetDeviceProperties(hipDeviceProp_t* p, int) {
   p->multiProcessorCount = 4;
   return hipSuccess;
 }
-hipError_t hipDeviceGetAttribute(int* v, hipDeviceAttribute_t, int) { *v = 0; return hipSuccess; }   // no large BAR: host-memory ring
-hipError_t hipEventCreate(hipEvent_t* e) { *e = reinterpret_cast<hipEvent_t>(new int(0)); return hipSuccess; }
+hipError_t hipDeviceGetAttribute(int* v, hipDeviceAttribute_t a, int) {       // 4 compute units; no large BAR: host-memory ring
+  *v = a == hipDeviceAttributeMultiprocessorCount ? 4 : 0;
+  return hipSuccess;
+}
+hipError_t hipEventCreate(hipEvent_t* e) { g_alloc_calls.fetch_add(1); *e = reinterpret_cast<hipEvent_t>(new int(0)); return hipSuccess; }
 hipError_t hipEventDestroy(hipEvent_t e) { delete reinterpret_cast<int*>(e); return hipSuccess; }
 hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
 hipError_t hipEventElapsedTime(float* ms, hipEvent_t, hipEvent_t) { *ms = 1.0f; return hipSuccess; }
-hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned int) { *s = reinterpret_cast<hipStream_t>(new int(0)); return hipSuccess; }
+hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned int) { g_alloc_calls.fetch_add(1); *s = reinterpret_cast<hipStream_t>(new int(0)); return hipSuccess; }
 hipError_t hipStreamDestroy(hipStream_t s) {
   Worker* w = nullptr;
   {

@@ -9,6 +9,8 @@
 #include <thread>
 #include <vector>
 
+#include <hip/hip_runtime_api.h>
+
 #include "../../include/gpuos.h"
 #include "../../paper_2604_17861_amd/csrc/gpuos_internal.h"
 
@@ -16,6 +18,9 @@ extern "C" uint64_t standin_errors();
 extern "C" void standin_leave_before(uint64_t ticket);
 extern "C" void standin_stall_ms(uint32_t ms);
 extern "C" uint64_t standin_records();
+extern "C" uint64_t standin_alloc_calls();
+extern "C" void standin_scratch_dirty();
+extern "C" uint64_t standin_scratch_nonzero(uint64_t n);
 
 #define CHECK(cond) do { if (!(cond)) { std::printf("FAILED %s:%d: %s\n", __FILE__, __LINE__, #cond); std::exit(1); } } while (0)
 
@@ -360,6 +365,59 @@ int main() {
     CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
     CHECK(gpuos_shutdown(c) == GPUOS_OK);
     std::printf("ok: markers\n");
+  }
+  // 7. the context that allocates nothing: device-side state in the library's static array, host side
+  //    in the caller's block, the caller's stream; one such context per device at a time; the array
+  //    is cleared of what the previous context left
+  {
+    gpuos_config cfg;
+    gpuos_default_config(&cfg);
+    cfg.wait_timeout_ms = 20000;
+    const uint64_t bytes = GPUOS_STATIC_HOST_BYTES(GPUOS_STATIC_MAX_CAPACITY);
+    void* block = std::aligned_alloc(256, bytes);
+    void* block2 = std::aligned_alloc(256, bytes);
+    CHECK(block && block2);
+    std::memset(block, 0x5A, bytes);
+    hipStream_t st1 = nullptr, st2 = nullptr;
+    CHECK(hipStreamCreateWithFlags(&st1, 0) == hipSuccess && hipStreamCreateWithFlags(&st2, 0) == hipSuccess);
+    gpuos_ctx* c = nullptr;
+    gpuos_ctx* c2 = nullptr;
+    CHECK(gpuos_init_static(&c, 2048, &cfg, block, bytes, st1) == GPUOS_E_INVAL && c == nullptr);        // beyond the maximum
+    CHECK(std::strstr(gpuos_last_hip_error(), "GPUOS_STATIC_MAX_CAPACITY") != nullptr);
+    CHECK(gpuos_init_static(&c, 64, &cfg, block, 1000, st1) == GPUOS_E_INVAL);                           // block too small
+    CHECK(gpuos_init_static(&c, 64, &cfg, (char*)block + 8, bytes - 8, st1) == GPUOS_E_INVAL);           // misaligned
+    CHECK(gpuos_init_static(&c, 64, &cfg, block, bytes, nullptr) == GPUOS_E_INVAL);                      // no stream
+    for (uint32_t cap : {64u, 16u}) {                                                                   // twice in a row, the second one smaller
+      standin_scratch_dirty();
+      const uint64_t a0 = standin_alloc_calls();
+      CHECK(gpuos_init_static(&c, cap, &cfg, block, bytes, st1) == GPUOS_OK && c != nullptr);
+      CHECK(standin_alloc_calls() == a0);                                                                // no hipMalloc / hipHostMalloc / stream / event
+      CHECK(standin_scratch_nonzero(gpuos::static_layout(cap).total) == 0);                              // what the last context left is gone
+      CHECK(gpuos_init_static(&c2, 16, &cfg, block2, bytes, st2) == GPUOS_E_FULL && c2 == nullptr);      // one at a time per device
+      CHECK(gpuos_register_op(c, 7, GPUOS_IMPL_ADD, nullptr) == GPUOS_OK);
+      std::vector<gpuos_task> some(200, add_task(7, 256));
+      uint64_t tk = 0;
+      CHECK(gpuos_submit(c, some.data(), 200, &tk) == GPUOS_OK && tk == 0);                              // wraps the ring several times
+      CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+      std::vector<gpuos_completion> comp(cap);
+      CHECK(gpuos_get_completions(c, 200 - cap, cap, comp.data()) == GPUOS_OK);
+      for (uint32_t t = 0; t < cap; ++t) CHECK(comp[t].ticket == 200 - cap + t && comp[t].status == 0 && comp[t].op_version == 1);
+      gpuos_queue_state q;
+      CHECK(gpuos_peek_queue(c, &q) == GPUOS_OK && q.capacity == cap && q.push_ring == 0 && q.completed == 200);
+      CHECK(gpuos_stop_worker(c) == GPUOS_OK);
+      float ms = 0;
+      CHECK(gpuos_worker_elapsed_ms(c, &ms) == GPUOS_E_INVAL);                                           // no events on such a context
+      CHECK(gpuos_start_worker(c) == GPUOS_OK);
+      CHECK(gpuos_submit(c, some.data(), 5, &tk) == GPUOS_OK && tk == 200);
+      CHECK(gpuos_wait(c, GPUOS_ALL, 0) == GPUOS_OK);
+      const uint64_t a1 = standin_alloc_calls();
+      CHECK(gpuos_shutdown(c) == GPUOS_OK);
+      CHECK(standin_alloc_calls() == a1);                                                                // ... and nothing is freed that was not allocated
+      c = nullptr;
+    }
+    CHECK(hipStreamDestroy(st1) == hipSuccess && hipStreamDestroy(st2) == hipSuccess);
+    std::free(block); std::free(block2);
+    std::printf("ok: a context that allocates nothing, twice in a row\n");
   }
   CHECK(standin_errors() == 0);
   std::printf("all ok: %llu records through the stand-in, 0 protocol errors\n", (unsigned long long)standin_records());
