@@ -51,7 +51,9 @@
 #ifndef GPUOS_H_
 #define GPUOS_H_
 
+#if !defined(__HIPCC_RTC__)
 #include <stdint.h>
+#endif
 
 #ifdef __cplusplus
 extern "C" {
@@ -161,6 +163,26 @@ typedef struct gpuos_instr {
 #define GPUOS_PROGRAM_REGS      8
 #define GPUOS_MAX_PROGRAMS      64
 #define GPUOS_IMPL_PROGRAM_BASE 64  /* implementation ids 64 .. 127 name programs */
+
+/* Native code for programs.  Interpreting costs time per element (a six-instruction program runs
+ * at well under half the speed of a built-in), so unless cfg.jit_mode says otherwise every
+ * gpuos_define_program also compiles, with the HIP run-time compiler, a SECOND resident worker
+ * kernel that holds all programs defined so far as straight-line native functors inside the
+ * library's own elementwise execution paths (same arithmetic, instruction by instruction, as the
+ * interpreter).  The dispatcher then routes the tasks of those programs to that kernel's work-unit
+ * ring; table, versions, dependencies and completions are shared with the worker, which never
+ * stops.  The kernel is built when an operator is first bound (gpuos_register_op / gpuos_swap_op)
+ * to a program that is not native yet, for all programs defined by then (cfg.jit_mode = 1: at
+ * every gpuos_define_program): that call compiles in the calling thread (one to two seconds; code
+ * objects are cached per process by the hash of the generated source), lets the previous
+ * generation of the kernel drain and leave, launches the new one, and only then binds.  Until
+ * then, and whenever this path is unavailable or fails, programs are interpreted.
+ * gpuos_native_info: out[0] 1 when programs are being served as native code, out[1] generation of
+ * the run-time kernel, out[2] programs it holds, out[3] kernels compiled by this context, out[4]
+ * taken from the cache, out[5] work units it has executed (valid after gpuos_stop_worker, else
+ * 0), out[6] microseconds the last compilation took, out[7] its workgroups; why (nullable, HOST
+ * buffer of why_len bytes): the reason when the native path is off or was given up. */
+int gpuos_native_info(gpuos_ctx* ctx, uint64_t out[8], char* why, uint32_t why_len);
 
 /* ---- task flags --------------------------------------------------------- */
 #define GPUOS_FLAG_FENCE   1u  /* start only after EVERY earlier ticket completed  */
@@ -284,6 +306,16 @@ typedef struct gpuos_config {
                                        bound is a safety net).  A task that runs into it completes
                                        with GPUOS_E_TIMEOUT and writes nothing; its dependants run.
                                        0 => wait_timeout_ms                                    */
+  uint32_t jit_mode;                /* operators defined as programs (gpuos_define_program): 0 => they
+                                       are also compiled to native code at run time and served by a
+                                       second resident worker kernel, built when an operator is first
+                                       bound to a program that is not native yet (needs the HIP
+                                       run-time compiler library; without it, or when anything in that
+                                       path fails, they stay interpreted); 1 => the same, built at
+                                       every gpuos_define_program; 2 => interpreted only            */
+  uint32_t jit_workgroups_per_cu;   /* workgroups per compute unit of that second kernel (0 => 1;
+                                       clamped so that both kernels stay co-resident: with the default
+                                       3 + 1 every register file is full while programs are defined) */
   uint32_t reserved[1];
 } gpuos_config;
 

@@ -6,14 +6,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgpuos.so")
-SOURCES = ["gpuos_kernels.hip", "gpuos_runtime.cpp"]
-HEADERS = ["gpuos_internal.h", os.path.join("..", "..", "include", "gpuos.h")]
+SOURCES = ["gpuos_kernels.hip", "gpuos_runtime.cpp", "gpuos_jit.cpp"]
+HEADERS = ["gpuos_internal.h", "gpuos_device.h", os.path.join("..", "..", "include", "gpuos.h")]
 
 # -ffp-contract=off: only the FMA operator fuses.  The -packed-fp32-ops target feature switch
 # keeps the compiler from forming packed fp32 instructions.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-variable",
-         "-Wno-unused-but-set-variable", "-pthread"]
+         "-Wno-unused-but-set-variable", "-pthread", "-DGPUOS_CSRC_DIR=" + CSRC, "-ldl"]
 
 
 def needs_build():

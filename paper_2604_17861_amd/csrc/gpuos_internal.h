@@ -2,7 +2,9 @@
 // the library: the packed 256-byte ring record, the control blocks and the
 // operator-table entries.  Not part of the public ABI.
 #pragma once
+#if !defined(__HIPCC_RTC__)
 #include <stdint.h>
+#endif
 
 #if defined(__HIP__)
 #define GPUOS_HD __host__ __device__
@@ -126,12 +128,14 @@ struct HostCtl {
   alignas(64) uint64_t heartbeat;    // device -> host: dispatcher poll counter
   alignas(64) uint32_t exit_code;    // device -> host: 0 running, 1 stop seen, 2 idle exit
   alignas(64) uint64_t clock_origin; // device -> host: the device clock when the dispatcher started
+  alignas(64) uint32_t jit_alive;    // device -> host: generation of the run-time kernel whose workers are running
 };
 struct DoorbellCtl {
   alignas(64) uint64_t tail;         // host -> device: tickets published (doorbell)
   alignas(64) uint64_t epoch_word;   // host -> device: epoch << 12 | op << 4 | stop bit;
                                      // op = 0xff: refresh every entry
   alignas(64) uint32_t yield_every;  // host -> device
+  uint32_t jit_gen;                  // host -> device: generation of run-time kernel that is wanted (earlier ones leave)
 };
 
 struct DevCtl {                      // device memory
@@ -140,6 +144,10 @@ struct DevCtl {                      // device memory
   alignas(128) uint64_t done_count;  // tasks completed
   alignas(128) uint32_t stop_dev;    // dispatcher -> workers
   uint32_t yield_every;
+  uint32_t jit_gen;                  // dispatcher -> workers of run-time kernels: the generation that is wanted (relayed from the doorbell block)
+  alignas(128) uint64_t claim_j;     // second unit ring (tasks of natively compiled programs): next unit to hand out
+  alignas(128) uint64_t tail_units_j;// ... units published on it (kept by the dispatcher, stored when it leaves)
+  alignas(128) uint64_t jit_units;   // ... units executed from it so far
   // performance counters (paper Section 5.3), 100 MHz ticks; workers add theirs when they exit
   alignas(128) uint64_t stat[16];
 };
@@ -161,7 +169,8 @@ struct SlotState {                   // device memory, one per ring slot
 // The header is written after the code: ready == kProgramReady means the code is complete.
 constexpr uint32_t kProgramReady = 0x50524f47u;
 struct ProgramImage {
-  uint32_t n_instr, n_inputs, ready, pad;
+  uint32_t n_instr, n_inputs, ready;
+  uint32_t native;            // 1: a run-time kernel that holds this program as native code is serving the second ring
   uint32_t code[2 * GPUOS_PROGRAM_MAX_INSTR];   // per instruction: op | dst << 8 | a << 16 | b << 24, then imm bits
 };
 static_assert(sizeof(ProgramImage) == 272, "program image layout");
@@ -194,6 +203,7 @@ struct WorkerArgs {
   DevCtl*    d;
   Record*    dring;          // device mirror of the ring
   uint64_t*  units;          // work-unit ring
+  uint64_t*  units_j;        // second work-unit ring, same size (nullptr: no run-time kernels on this context)
   SlotState* st;
   OpSlots*   dtable;         // device-resident operator table
   uint32_t   cap_mask;

@@ -26,1530 +26,9 @@
 
 #include "../../include/gpuos.h"
 #include "gpuos_internal.h"
+#include "gpuos_device.h"
 
 namespace gpuos {
-
-#define SC_AGENT __HIP_MEMORY_SCOPE_AGENT
-#define SC_SYSTEM __HIP_MEMORY_SCOPE_SYSTEM
-
-#define DEV __device__ __forceinline__
-// The per-path executors are real functions (not inlined into the worker loop): each gets a
-// register allocation of its own, so the streaming loops do not inherit the worker loop's live values.
-#define PATHFN __device__ __attribute__((noinline))
-
-// ---------------------------------------------------------------------------
-// memory access policy
-//
-// The persistent kernel never reaches a kernel boundary, and the 8 XCDs have
-// one L2 each that are not coherent with each other for ordinary accesses.
-// Agent-scope acquire / release fences would make a task's data visible, but
-// they write back / invalidate a whole L2 on every chunk, which costs more than
-// half of the HBM bandwidth when a thousand workgroups do it.  Instead every
-// access to task data, descriptors and work units made by the persistent
-// kernel carries the system-scope cache policy (sc0 sc1: stores write through
-// to memory, loads do not hit stale lines), plus nt on the 16-byte streaming
-// accesses.  With that, "release" is: wait until this wave's stores are
-// acknowledged (s_waitcnt), then publish with a relaxed atomic store; "acquire"
-// is: observe the flag with a relaxed atomic load, then read with the same
-// policy.  No L2-wide maintenance happens in the steady state.
-//
-// 16-byte accesses go through buffer instructions whose resource is rebased to
-// the chunk being processed: the hardware bounds-checks them (out-of-range
-// loads return 0, stores are dropped).  The ordinary one-launch-per-task kernel
-// uses POL_PLAIN (non-temporal, kernel-boundary coherence as for any kernel).
-// ---------------------------------------------------------------------------
-enum { POL_PLAIN = 0, POL_COHERENT = 1 };
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-
-DEV rsrc_t make_rsrc(const void* base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
-}
-
-template <int POL> struct Mem {
-  static constexpr int AUX = POL == POL_COHERENT ? 19 : 2;     // sc0|sc1|nt  or  nt
-  static DEV v4i ld16(rsrc_t r, uint32_t off) { return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, AUX); }
-  static DEV void st16(rsrc_t r, uint32_t off, v4i q) { __builtin_amdgcn_raw_buffer_store_b128(q, r, (int)off, 0, AUX); }
-  static DEV uint32_t ld4(const void* p, uint32_t i) {
-    if (POL == POL_COHERENT) return __hip_atomic_load((const uint32_t*)p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    return ((const uint32_t*)p)[i];
-  }
-  static DEV uint32_t ld2(const void* p, uint32_t i) {
-    if (POL == POL_COHERENT) return __hip_atomic_load((const uint16_t*)p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    return ((const uint16_t*)p)[i];
-  }
-  static DEV void st4(void* p, uint32_t i, uint32_t v) {
-    if (POL == POL_COHERENT) __hip_atomic_store((uint32_t*)p + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    else ((uint32_t*)p)[i] = v;
-  }
-  static DEV void st2(void* p, uint32_t i, uint32_t v) {
-    if (POL == POL_COHERENT) __hip_atomic_store((uint16_t*)p + i, (uint16_t)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    else ((uint16_t*)p)[i] = (uint16_t)v;
-  }
-};
-
-// This wave's stores (all write-through) have been acknowledged when this returns.
-DEV void drain_stores() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // keeps the compiler from moving stores below
-  __builtin_amdgcn_s_waitcnt(0);                           // vmcnt = expcnt = lgkmcnt = 0
-}
-DEV void order_loads() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
-
-// ---------------------------------------------------------------------------
-// element conversions (fp16 / bf16 <-> fp32; RNE, denormals kept)
-// ---------------------------------------------------------------------------
-DEV float h2f(uint32_t b) { return (float)__builtin_bit_cast(_Float16, (uint16_t)b); }
-DEV uint32_t f2h(float f) {
-  // The empty asm keeps the fp32 value opaque: without it the compiler folds the producing
-  // multiply / fma and this conversion into one mixed-precision instruction that rounds the
-  // exact result straight to fp16 (one rounding), while the defined result is fp32 first.
-  asm("" : "+v"(f));
-  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
-}
-DEV float b2f(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
-DEV uint32_t f2b(float f) {
-  // round-to-nearest-even, NaN stays a (quiet) NaN: gfx950 has the conversion in hardware
-  // (v_cvt_pk_bf16_f32), which the compiler selects for this cast; done by hand it is six
-  // integer operations per element, and the 16-bit paths are the ones short of ALU time
-  return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
-}
-
-template <int DT> struct Elem;
-template <> struct Elem<GPUOS_F32> {
-  static constexpr int V = 4, ES = 4;
-  static DEV float get(const v4i& q, int k) {
-    const int w = q[k];      // read the lane into a scalar first: bit-casting the element lvalue directly reads lane 0
-    return __builtin_bit_cast(float, w);
-  }
-  static DEV void put(v4i& q, int k, float f) { q[k] = __builtin_bit_cast(int, f); }
-  template <int POL> static DEV float load1(const void* p, uint32_t i) { return __builtin_bit_cast(float, Mem<POL>::ld4(p, i)); }
-  template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st4(p, i, __builtin_bit_cast(uint32_t, f)); }
-  template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st4(o, i, Mem<POL>::ld4(a, i)); }
-};
-template <> struct Elem<GPUOS_F16> {
-  static constexpr int V = 8, ES = 2;
-  static DEV float get(const v4i& q, int k) { return h2f(((uint32_t)q[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
-  static DEV void put(v4i& q, int k, float f) {
-    const uint32_t w = (uint32_t)q[k >> 1];
-    q[k >> 1] = (int)((k & 1) ? ((w & 0xffffu) | (f2h(f) << 16)) : ((w & 0xffff0000u) | f2h(f)));
-  }
-  template <int POL> static DEV float load1(const void* p, uint32_t i) { return h2f(Mem<POL>::ld2(p, i)); }
-  template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st2(p, i, f2h(f)); }
-  template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st2(o, i, Mem<POL>::ld2(a, i)); }
-};
-template <> struct Elem<GPUOS_BF16> {
-  static constexpr int V = 8, ES = 2;
-  static DEV float get(const v4i& q, int k) { return b2f(((uint32_t)q[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
-  static DEV void put(v4i& q, int k, float f) {
-    const uint32_t w = (uint32_t)q[k >> 1];
-    q[k >> 1] = (int)((k & 1) ? ((w & 0xffffu) | (f2b(f) << 16)) : ((w & 0xffff0000u) | f2b(f)));
-  }
-  template <int POL> static DEV float load1(const void* p, uint32_t i) { return b2f(Mem<POL>::ld2(p, i)); }
-  template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st2(p, i, f2b(f)); }
-  template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st2(o, i, Mem<POL>::ld2(a, i)); }
-};
-
-template <int POL> DEV float load_rt(const void* p, uint32_t i, uint32_t dt) {   // runtime dtype
-  if (dt == GPUOS_F32) return __builtin_bit_cast(float, Mem<POL>::ld4(p, i));
-  if (dt == GPUOS_F16) return h2f(Mem<POL>::ld2(p, i));
-  return b2f(Mem<POL>::ld2(p, i));
-}
-template <int POL> DEV void store_rt(void* p, uint32_t i, uint32_t dt, float f) {
-  if (dt == GPUOS_F32) Mem<POL>::st4(p, i, __builtin_bit_cast(uint32_t, f));
-  else if (dt == GPUOS_F16) Mem<POL>::st2(p, i, f2h(f));
-  else Mem<POL>::st2(p, i, f2b(f));
-}
-
-// ---------------------------------------------------------------------------
-// operator library (paper Section 5.2).  fp32 in, fp32 out; the caller rounds
-// to the output dtype.  GELU is evaluated in fp64 in a cancellation-free form
-// and rounded once: an fp32 evaluation cannot hold 2 ulp for x < 0, where
-// 1 + tanh(u) and 1 + erf(u) cancel.
-// ---------------------------------------------------------------------------
-constexpr uint32_t kNoLoad = 0x7ffffff0u;   // a buffer offset past every resource: the load returns 0 and moves no data
-
-template <int IMPL> struct Op;
-template <> struct Op<GPUOS_IMPL_ADD> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x + y; } };
-template <> struct Op<GPUOS_IMPL_SUB> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x - y; } };
-template <> struct Op<GPUOS_IMPL_MUL> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x * y; } };
-template <> struct Op<GPUOS_IMPL_DIV> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { return x / y; } };
-template <> struct Op<GPUOS_IMPL_RELU> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return (x != x) ? x : (x > 0.0f ? x : 0.0f); } };
-template <> struct Op<GPUOS_IMPL_EXP> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return expf(x); } };
-template <> struct Op<GPUOS_IMPL_GELU_ERF> {
-  static constexpr int N = 1;
-  static DEV float f(float x, float, float, float) {
-    const double xd = (double)x;
-    return (float)(0.5 * xd * erfc(-xd * 0.70710678118654752440));
-  }
-};
-template <> struct Op<GPUOS_IMPL_GELU_TANH> {
-  static constexpr int N = 1;
-  static DEV float f(float x, float, float, float) {
-    const double xd = (double)x;
-    const double u = 0.79788456080286535588 * (xd + 0.044715 * xd * xd * xd);
-    return (float)(xd / (1.0 + exp(-2.0 * u)));
-  }
-};
-template <> struct Op<GPUOS_IMPL_SCALE> { static constexpr int N = 1; static DEV float f(float x, float, float, float a) { return x * a; } };
-template <> struct Op<GPUOS_IMPL_FMA> { static constexpr int N = 3; static DEV float f(float x, float y, float z, float) { return __builtin_fmaf(x, y, z); } };
-template <> struct Op<GPUOS_IMPL_SUB_EXP> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { const float d = x - y; return expf(d); } };
-template <> struct Op<GPUOS_IMPL_COPY> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return x; } };
-
-// ---------------------------------------------------------------------------
-// operator programs: elementwise operators defined at run time, interpreted.  The program of
-// the chunk being executed sits in LDS (exec_program puts it there); every lane runs the same
-// instruction on its own element, so opcode and register numbers are wavefront-uniform and the
-// loop over the instructions is scalar control flow.  One IEEE binary32 operation per instruction.
-// ---------------------------------------------------------------------------
-__shared__ ProgramImage g_prog;
-
-// internal implementation tags: "the program in LDS, taking N inputs"
-enum { kImplProg1 = 201, kImplProg2 = 202, kImplProg3 = 203 };
-
-// The same program over K elements at once: every instruction is decoded once (scalar work) and
-// applied to the K elements a lane holds, so the interpreter's overhead is shared by a whole
-// 16-byte vector instead of being paid per element.
-template <int K>
-DEV void run_program_vec(const float (&x)[K], const float (&y)[K], const float (&z)[K], float alpha, float (&o)[K]) {
-  // The register file is eight separately named arrays selected by a switch on the (uniform)
-  // register number: a dynamically indexed array would be placed in scratch memory.
-  float r0[K], r1[K], r2[K], r3[K], r4[K], r5[K], r6[K], r7[K];
-#pragma unroll
-  for (int k = 0; k < K; ++k) {
-    r0[k] = x[k]; r1[k] = y[k]; r2[k] = z[k]; r3[k] = alpha;
-    r4[k] = 0.f; r5[k] = 0.f; r6[k] = 0.f; r7[k] = 0.f;
-  }
-#define GPUOS_RF_COPY(dst, src) _Pragma("unroll") for (int k = 0; k < K; ++k) dst[k] = src[k];
-#define GPUOS_RF_READ(dst, idx) switch (idx) { \
-    case 0: GPUOS_RF_COPY(dst, r0) break; case 1: GPUOS_RF_COPY(dst, r1) break; \
-    case 2: GPUOS_RF_COPY(dst, r2) break; case 3: GPUOS_RF_COPY(dst, r3) break; \
-    case 4: GPUOS_RF_COPY(dst, r4) break; case 5: GPUOS_RF_COPY(dst, r5) break; \
-    case 6: GPUOS_RF_COPY(dst, r6) break; default: GPUOS_RF_COPY(dst, r7) break; }
-#define GPUOS_RF_WRITE(idx, src) switch (idx) { \
-    case 0: GPUOS_RF_COPY(r0, src) break; case 1: GPUOS_RF_COPY(r1, src) break; \
-    case 2: GPUOS_RF_COPY(r2, src) break; case 3: GPUOS_RF_COPY(r3, src) break; \
-    case 4: GPUOS_RF_COPY(r4, src) break; case 5: GPUOS_RF_COPY(r5, src) break; \
-    case 6: GPUOS_RF_COPY(r6, src) break; default: GPUOS_RF_COPY(r7, src) break; }
-  const uint32_t n = __builtin_amdgcn_readfirstlane(g_prog.n_instr);
-  for (uint32_t i = 0; i < n; ++i) {
-    const uint32_t w = __builtin_amdgcn_readfirstlane(g_prog.code[2 * i]);
-    const float imm = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(g_prog.code[2 * i + 1]));
-    const uint32_t op = w & 0xffu, d = (w >> 8) & 7u, ia = (w >> 16) & 7u, ib = (w >> 24) & 7u;
-    float a[K], b[K], v[K];
-    GPUOS_RF_READ(a, ia)
-    GPUOS_RF_READ(b, ib)
-    switch (op) {
-#define GPUOS_PC_CASE(code, expr) case code: _Pragma("unroll") for (int k = 0; k < K; ++k) v[k] = (expr); break;
-      GPUOS_PC_CASE(GPUOS_PC_MOV, a[k])
-      GPUOS_PC_CASE(GPUOS_PC_IMM, imm)
-      GPUOS_PC_CASE(GPUOS_PC_ADD, a[k] + b[k])
-      GPUOS_PC_CASE(GPUOS_PC_SUB, a[k] - b[k])
-      GPUOS_PC_CASE(GPUOS_PC_MUL, a[k] * b[k])
-      GPUOS_PC_CASE(GPUOS_PC_DIV, a[k] / b[k])
-      GPUOS_PC_CASE(GPUOS_PC_MAX, (a[k] != a[k]) ? a[k] : ((b[k] != b[k]) ? b[k] : (a[k] > b[k] ? a[k] : b[k])))
-      GPUOS_PC_CASE(GPUOS_PC_MIN, (a[k] != a[k]) ? a[k] : ((b[k] != b[k]) ? b[k] : (a[k] < b[k] ? a[k] : b[k])))
-      GPUOS_PC_CASE(GPUOS_PC_NEG, -a[k])
-      GPUOS_PC_CASE(GPUOS_PC_ABS, __builtin_fabsf(a[k]))
-      GPUOS_PC_CASE(GPUOS_PC_RELU, (a[k] != a[k]) ? a[k] : (a[k] > 0.0f ? a[k] : 0.0f))
-      GPUOS_PC_CASE(GPUOS_PC_EXP, expf(a[k]))
-      GPUOS_PC_CASE(GPUOS_PC_SQRT, __builtin_sqrtf(a[k]))
-#undef GPUOS_PC_CASE
-      case GPUOS_PC_FMA: {
-        float c[K];
-        GPUOS_RF_READ(c, d)
-#pragma unroll
-        for (int k = 0; k < K; ++k) v[k] = __builtin_fmaf(a[k], b[k], c[k]);
-      } break;
-      default:
-#pragma unroll
-        for (int k = 0; k < K; ++k) v[k] = 0.f;
-        break;
-    }
-    GPUOS_RF_WRITE(d, v)
-  }
-#pragma unroll
-  for (int k = 0; k < K; ++k) o[k] = r0[k];
-#undef GPUOS_RF_COPY
-#undef GPUOS_RF_READ
-#undef GPUOS_RF_WRITE
-}
-
-DEV float run_program(float x, float y, float z, float alpha) {      // one element (strided and ragged-tail paths)
-  const float xs[1] = {x}, ys[1] = {y}, zs[1] = {z};
-  float os[1];
-  run_program_vec<1>(xs, ys, zs, alpha, os);
-  return os[0];
-}
-template <> struct Op<kImplProg1> { static constexpr int N = 1; static DEV float f(float x, float, float, float a) { return run_program(x, 0.f, 0.f, a); } };
-template <> struct Op<kImplProg2> { static constexpr int N = 2; static DEV float f(float x, float y, float, float a) { return run_program(x, y, 0.f, a); } };
-template <> struct Op<kImplProg3> { static constexpr int N = 3; static DEV float f(float x, float y, float z, float a) { return run_program(x, y, z, a); } };
-
-// o[k] = f(x[k], y[k], z[k], alpha) for the K elements a lane holds: element by element for the
-// built-in implementations (the compiler unrolls it back into straight code), instruction by
-// instruction for a program.
-template <int IMPL, int K>
-DEV void apply_vec(const float (&x)[K], const float (&y)[K], const float (&z)[K], float alpha, float (&o)[K]) {
-  if (IMPL == kImplProg1 || IMPL == kImplProg2 || IMPL == kImplProg3) {
-    run_program_vec<K>(x, y, z, alpha, o);
-  } else {
-#pragma unroll
-    for (int k = 0; k < K; ++k) o[k] = Op<IMPL>::f(x[k], y[k], z[k], alpha);
-  }
-}
-
-template <int IMPL> DEV uint32_t int_op(uint32_t x, uint32_t y) {
-  if (IMPL == GPUOS_IMPL_ADD) return x + y;
-  if (IMPL == GPUOS_IMPL_SUB) return x - y;
-  if (IMPL == GPUOS_IMPL_MUL) return x * y;
-  return x;
-}
-
-DEV uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
-DEV const char* uni_ptr(uint64_t p) {
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)p);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(p >> 32));
-  return (const char*)(((uint64_t)hi << 32) | lo);
-}
-// Arguments of a PATHFN function arrive in vector registers and pointers arrive generic.  Both
-// facts are restored on entry: values the whole workgroup shares go back to scalar registers
-// (uni / uni_ptr), and a pointer known to address LDS goes back to the LDS address space (so that
-// it is read with LDS instructions, not flat ones).
-template <class T> DEV T* lds_arg(T* p) {
-  typedef __attribute__((address_space(3))) T* lds_t;
-  const uint32_t a = uni((uint32_t)(uintptr_t)(lds_t)p);
-  return (T*)(lds_t)(uintptr_t)a;
-}
-
-// ---------------------------------------------------------------------------
-// PATH_CONTIG: out[i] = f(a[i], b[i], c[i]), all operands the same dtype.
-// 16 bytes per lane per access, four accesses in flight per operand.
-// ---------------------------------------------------------------------------
-template <int POL, int IMPL, int DT>
-PATHFN void ew_contig(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
-  const Record* r = lds_arg(r_v);
-  uint32_t begin = uni(begin_v);
-  const uint32_t end = uni(end_v);
-  using E = Elem<DT>;
-  using M = Mem<POL>;
-  constexpr int V = E::V, N = Op<IMPL>::N, U = 4;
-  const char* pa = uni_ptr(r->ptr[0]);
-  const char* pb = N > 1 ? uni_ptr(r->ptr[1]) : pa;
-  const char* pc = N > 2 ? uni_ptr(r->ptr[2]) : pa;
-  char* po = (char*)uni_ptr(r->ptr[3]);
-  const float alpha = r->alpha;
-  const uint32_t tid = threadIdx.x;
-  if (r->rflags & RF_VEC) {
-    // buffer resources rebased to this chunk; begin is a multiple of V
-    const uint32_t nvec = (end - begin) / V;
-    const uint32_t bytes = nvec * 16u;
-    const uint64_t boff = (uint64_t)begin * E::ES;
-    const rsrc_t ra = make_rsrc(pa + boff, bytes), rb = make_rsrc(pb + boff, bytes), rc = make_rsrc(pc + boff, bytes);
-    const rsrc_t ro = make_rsrc(po + boff, bytes);
-    uint32_t v = tid;
-    for (; v + (U - 1) * kThreads < nvec; v += U * kThreads) {
-      v4i qa[U], qb[U], qc[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        qa[u] = M::ld16(ra, (v + u * kThreads) * 16u);
-        if (N > 1) qb[u] = M::ld16(rb, (v + u * kThreads) * 16u);
-        if (N > 2) qc[u] = M::ld16(rc, (v + u * kThreads) * 16u);
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        v4i q;
-        if (IMPL == GPUOS_IMPL_COPY) q = qa[u];
-        else {
-          float xa[V], xb[V], xc[V], xo[V];
-#pragma unroll
-          for (int k = 0; k < V; ++k) {
-            xa[k] = E::get(qa[u], k); xb[k] = N > 1 ? E::get(qb[u], k) : 0.f; xc[k] = N > 2 ? E::get(qc[u], k) : 0.f;
-          }
-          apply_vec<IMPL, V>(xa, xb, xc, alpha, xo);
-#pragma unroll
-          for (int k = 0; k < V; ++k) E::put(q, k, xo[k]);
-        }
-        M::st16(ro, (v + u * kThreads) * 16u, q);
-      }
-    }
-    for (; v < nvec; v += kThreads) {
-      const v4i qa = M::ld16(ra, v * 16u);
-      v4i qb, qc, q;
-      if (N > 1) qb = M::ld16(rb, v * 16u);
-      if (N > 2) qc = M::ld16(rc, v * 16u);
-      if (IMPL == GPUOS_IMPL_COPY) q = qa;
-      else {
-        float xa[V], xb[V], xc[V], xo[V];
-#pragma unroll
-        for (int k = 0; k < V; ++k) {
-          xa[k] = E::get(qa, k); xb[k] = N > 1 ? E::get(qb, k) : 0.f; xc[k] = N > 2 ? E::get(qc, k) : 0.f;
-        }
-        apply_vec<IMPL, V>(xa, xb, xc, alpha, xo);
-#pragma unroll
-        for (int k = 0; k < V; ++k) E::put(q, k, xo[k]);
-      }
-      M::st16(ro, v * 16u, q);
-    }
-    begin += nvec * V;                                // ragged tail below
-  }
-  for (uint32_t i = begin + tid; i < end; i += kThreads) {
-    if (IMPL == GPUOS_IMPL_COPY) E::template copy1<POL>(po, pa, i);
-    else
-      E::template store1<POL>(po, i, Op<IMPL>::f(E::template load1<POL>(pa, i), N > 1 ? E::template load1<POL>(pb, i) : 0.f,
-                                                 N > 2 ? E::template load1<POL>(pc, i) : 0.f, alpha));
-  }
-}
-
-template <int POL, int IMPL>
-PATHFN void ew_contig_int(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
-  const Record* r = lds_arg(r_v);
-  const uint32_t begin = uni(begin_v), end = uni(end_v);
-  const char* a = uni_ptr(r->ptr[0]);
-  const char* b = r->n_inputs > 1 ? uni_ptr(r->ptr[1]) : a;
-  char* o = (char*)uni_ptr(r->ptr[3]);
-  for (uint32_t i = begin + threadIdx.x; i < end; i += kThreads)
-    Mem<POL>::st4(o, i, int_op<IMPL>(Mem<POL>::ld4(a, i), Mem<POL>::ld4(b, i)));
-}
-
-// ---------------------------------------------------------------------------
-// PATH_ROW2D: contiguous [R, C] output of dtype DT, C a multiple of the vector
-// width; each input is a full [R, C] tensor (dtype DT), a row vector [C]
-// broadcast over rows (dtype DT), or one scalar per row (any float dtype).
-// ---------------------------------------------------------------------------
-constexpr uint32_t kScratchFloats = 3200;   // LDS scratch per workgroup (broadcast staging, transpose tiles, reduction partials)
-
-template <int POL, int IMPL, int DT>
-PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
-  const Record* r = lds_arg(r_v);
-  const uint32_t begin = uni(begin_v), end = uni(end_v);
-  float* s_scratch = lds_arg(s_v);
-  using E = Elem<DT>;
-  using M = Mem<POL>;
-  constexpr int V = E::V, N = Op<IMPL>::N;
-  const uint32_t C = uni(r->size[1]);
-  const char* p[3];
-  uint32_t kind[3], dt[3], st0[3];
-  rsrc_t rs[3];
-  const uint32_t nvec = (end - begin) / V;
-  const uint64_t boff = (uint64_t)begin * E::ES;
-  uint32_t n_scalar = 0;
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    const int kk = k < N ? k : 0;
-    p[k] = uni_ptr(r->ptr[kk]);
-    kind[k] = uni(r->okind[kk]);
-    dt[k] = uni(r->dtype[kk]);
-    st0[k] = uni(r->stride[kk][0]);
-    // full operands: rebased to the chunk; row vectors: the whole vector
-    rs[k] = kind[k] == K_FULL ? make_rsrc(p[k] + boff, nvec * 16u) : make_rsrc(p[k], C * E::ES);
-    if (k < N && kind[k] == K_ROWSCALAR) ++n_scalar;
-  }
-  const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + boff, nvec * 16u);
-  const float alpha = r->alpha;
-  // Per-row scalars (x - rowmax, e / rowsum): the rows of this chunk are gathered once into LDS
-  // with coalesced loads and broadcast from there; without the staging every 16-byte vector would
-  // cost one more uncached 4-byte memory request.
-  const uint32_t row_first = begin / C, row_cnt = (end - 1) / C - row_first + 1;
-  const bool staged = n_scalar != 0 && row_cnt * n_scalar <= kScratchFloats;
-  if (staged) {
-    uint32_t region = 0;
-#pragma unroll
-    for (int k = 0; k < N; ++k)
-      if (kind[k] == K_ROWSCALAR) {
-        for (uint32_t t = threadIdx.x; t < row_cnt; t += kThreads)
-          s_scratch[region + t] = load_rt<POL>(p[k], (row_first + t) * st0[k], dt[k]);
-        region += row_cnt;
-      }
-    __syncthreads();
-  }
-  // UN vectors per thread and round: all their loads are issued before the first result is needed
-  // (one vector per round left a single request in flight per operand)
-  constexpr int UN = 4;
-  for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * UN) {
-    v4i q[UN][3];
-    float s[UN][3];
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const uint32_t v = v0 + (uint32_t)u * kThreads;
-      const bool act = v < nvec;
-      const uint32_t i = begin + (act ? v : 0u) * V;
-      const uint32_t row = i / C, col = i - row * C;
-      uint32_t region = 0;
-#pragma unroll
-      for (int k = 0; k < N; ++k) {
-        if (kind[k] == K_FULL) q[u][k] = M::ld16(rs[k], act ? v * 16u : kNoLoad);
-        else if (kind[k] == K_ROWVEC) q[u][k] = M::ld16(rs[k], act ? col * E::ES : kNoLoad);
-        else if (staged) { s[u][k] = s_scratch[region + row - row_first]; region += row_cnt; }
-        else s[u][k] = load_rt<POL>(p[k], row * st0[k], dt[k]);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const uint32_t v = v0 + (uint32_t)u * kThreads;
-      if (v < nvec) {
-        v4i res;
-        float xv[3][V], xo[V];
-#pragma unroll
-        for (int e = 0; e < V; ++e)
-#pragma unroll
-          for (int k = 0; k < 3; ++k) xv[k][e] = k < N ? ((kind[k] == K_ROWSCALAR) ? s[u][k] : E::get(q[u][k], e)) : 0.f;
-        apply_vec<IMPL, V>(xv[0], xv[1], xv[2], alpha, xo);
-#pragma unroll
-        for (int e = 0; e < V; ++e) E::put(res, e, xo[e]);
-        M::st16(ro, v * 16u, res);
-      }
-    }
-  }
-  if (staged) __syncthreads();        // the scratch may be reused by the next chunk
-}
-
-// ---------------------------------------------------------------------------
-// PATH_TILE2D: contiguous [B, R, C] output where at least one input is stored with R as its
-// unit-stride dim (a transposed view).  Such an input is gathered through a 32 x 32 LDS tile:
-// it is read along ITS contiguous dim (coalesced), written to LDS, and read back transposed
-// (pitch 33: no bank conflicts), so neither side of the transpose touches memory with a stride.
-// Row-major inputs (unit stride along C, any row pitch, including 0 for a broadcast row) are
-// read directly.  Any float dtype per operand.
-// ---------------------------------------------------------------------------
-constexpr uint32_t kTile = 32, kTilePitch = 33;
-
-template <int POL, int IMPL>
-PATHFN void ew_tile2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
-  const Record* r = lds_arg(r_v);
-  const uint32_t tile_begin = uni(begin_v), tile_end = uni(end_v);
-  float* s_scratch = lds_arg(s_v);
-  constexpr int N = Op<IMPL>::N;
-  const uint32_t R = uni(r->size[1]), C = uni(r->size[2]);
-  const uint32_t tr = (R + kTile - 1) / kTile, tc = (C + kTile - 1) / kTile;
-  const char* p[3];
-  uint32_t kind[3], dt[3], sb[3], sr[3], sc[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    const int kk = k < N ? k : 0;
-    p[k] = uni_ptr(r->ptr[kk]);
-    kind[k] = uni(r->okind[kk]);
-    dt[k] = uni(r->dtype[kk]);
-    sb[k] = uni(r->stride[kk][0]); sr[k] = uni(r->stride[kk][1]); sc[k] = uni(r->stride[kk][2]);
-  }
-  char* po = (char*)uni_ptr(r->ptr[3]);
-  const uint32_t odt = uni(r->dtype[3]);
-  const float alpha = r->alpha;
-  const uint32_t tid = threadIdx.x;
-  for (uint32_t t = tile_begin; t < tile_end; ++t) {
-    const uint32_t b = t / (tr * tc), rem = t - b * tr * tc;
-    const uint32_t ti = rem / tc, tj = rem - ti * tc;
-    const uint32_t r0 = ti * kTile, c0 = tj * kTile;
-    // stage the transposed operands: lanes run along r (their contiguous dim)
-#pragma unroll
-    for (int k = 0; k < N; ++k)
-      if (kind[k] == K_TRANSPOSED) {
-        float* tile = s_scratch + k * (kTile * kTilePitch);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const uint32_t idx = tid + i * kThreads, rr = idx & (kTile - 1), cc = idx / kTile;
-          if (r0 + rr < R && c0 + cc < C)
-            tile[cc * kTilePitch + rr] = load_rt<POL>(p[k], b * sb[k] + (r0 + rr) + (c0 + cc) * sc[k], dt[k]);
-        }
-      }
-    __syncthreads();
-    // compute: lanes run along c (the output's contiguous dim)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t idx = tid + i * kThreads, cc = idx & (kTile - 1), rr = idx / kTile;
-      if (r0 + rr < R && c0 + cc < C) {
-        float x[3] = {0.f, 0.f, 0.f};
-#pragma unroll
-        for (int k = 0; k < N; ++k)
-          x[k] = kind[k] == K_TRANSPOSED ? s_scratch[k * (kTile * kTilePitch) + cc * kTilePitch + rr]
-                                         : load_rt<POL>(p[k], b * sb[k] + (r0 + rr) * sr[k] + (c0 + cc), dt[k]);
-        store_rt<POL>(po, (b * R + r0 + rr) * C + c0 + cc, odt, Op<IMPL>::f(x[0], x[1], x[2], alpha));
-      }
-    }
-    __syncthreads();                  // the tiles are rewritten by the next iteration
-  }
-}
-
-// ---------------------------------------------------------------------------
-// PATH_GENERIC: row-major index decomposition over <= 6 coalesced dims, per
-// operand strides (0 on broadcast dims), per operand dtype.
-// ---------------------------------------------------------------------------
-template <int POL, int IMPL, bool INT>
-PATHFN void ew_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
-  const Record* r = lds_arg(r_v);
-  const uint32_t begin = uni(begin_v), end = uni(end_v);
-  using M = Mem<POL>;
-  constexpr int N = INT ? 2 : Op<IMPL>::N;
-  const int nd = (int)uni(r->ndim);
-  const int nin = (int)uni(r->n_inputs);
-  uint32_t size[GPUOS_MAX_DIMS], st[4][GPUOS_MAX_DIMS];
-#pragma unroll
-  for (int d = 0; d < GPUOS_MAX_DIMS; ++d) {
-    size[d] = uni(r->size[d]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) st[k][d] = uni(r->stride[k][d]);
-  }
-  const char* p[3];
-  uint32_t dt[4];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) { p[k] = uni_ptr(r->ptr[k]); dt[k] = uni(r->dtype[k]); }
-  dt[3] = uni(r->dtype[3]);
-  char* po = (char*)uni_ptr(r->ptr[3]);
-  const float alpha = r->alpha;
-  for (uint32_t i = begin + threadIdx.x; i < end; i += kThreads) {
-    uint32_t rem = i, off[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int d = GPUOS_MAX_DIMS - 1; d >= 0; --d) {
-      if (d < nd) {
-        const uint32_t q = rem / size[d];
-        const uint32_t idx = rem - q * size[d];
-        rem = q;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) off[k] += idx * st[k][d];
-      }
-    }
-    if (INT) {
-      const uint32_t x = M::ld4(p[0], off[0]);
-      const uint32_t y = nin > 1 ? M::ld4(p[1], off[1]) : 0u;
-      M::st4(po, off[3], int_op<IMPL>(x, y));
-    } else if (IMPL == GPUOS_IMPL_COPY && dt[0] == dt[3]) {
-      if (dt[0] == GPUOS_F32) M::st4(po, off[3], M::ld4(p[0], off[0]));
-      else M::st2(po, off[3], M::ld2(p[0], off[0]));
-    } else {
-      const float x = load_rt<POL>(p[0], off[0], dt[0]);
-      const float y = N > 1 ? load_rt<POL>(p[1], off[1], dt[1]) : 0.f;
-      const float z = N > 2 ? load_rt<POL>(p[2], off[2], dt[2]) : 0.f;
-      store_rt<POL>(po, off[3], dt[3], Op<IMPL>::f(x, y, z, alpha));
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------
-// reductions over the last dim
-// ---------------------------------------------------------------------------
-template <int RIMPL> DEV float red_identity() {
-  return RIMPL == GPUOS_IMPL_SUM_LAST ? 0.0f : (RIMPL == GPUOS_IMPL_MAX_LAST ? -__builtin_inff() : __builtin_inff());
-}
-template <int RIMPL> DEV float red_combine(float a, float b) {
-  if (RIMPL == GPUOS_IMPL_SUM_LAST) return a + b;
-  if (a != a) return a;                               // max / min propagate NaN
-  if (b != b) return b;
-  if (RIMPL == GPUOS_IMPL_MAX_LAST) return a > b ? a : b;
-  return a < b ? a : b;
-}
-template <int RIMPL> DEV int32_t red_identity_i() {
-  return RIMPL == GPUOS_IMPL_SUM_LAST ? 0 : (RIMPL == GPUOS_IMPL_MAX_LAST ? (int32_t)0x80000000 : 0x7fffffff);
-}
-template <int RIMPL> DEV int32_t red_combine_i(int32_t a, int32_t b) {
-  if (RIMPL == GPUOS_IMPL_SUM_LAST) return (int32_t)((uint32_t)a + (uint32_t)b);
-  if (RIMPL == GPUOS_IMPL_MAX_LAST) return a > b ? a : b;
-  return a < b ? a : b;
-}
-
-// The partner of a lane in step OFF of an all-reduce butterfly over aligned groups of 2 * OFF
-// lanes.  Steps 1 and 2 swap inside a quad and steps 4 and 8 mirror a half row / a row of 16 lanes
-// (lane i with i ^ 7, i ^ 15): DPP operand modifiers, no trip through the LDS crossbar that a
-// shuffle takes.  The masks 1, 2, 7, 15, 16, 32 are independent, so the steps still reach every
-// lane of the group.  Steps 16 and 32 cross rows and stay shuffles.  All lanes must be active.
-template <int OFF> DEV int butterfly_partner(int v) {
-  if (OFF == 1) return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xf, 0xf, false);      // quad_perm [1,0,3,2]
-  if (OFF == 2) return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xf, 0xf, false);      // quad_perm [2,3,0,1]
-  if (OFF == 4) return __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false);     // row_half_mirror
-  if (OFF == 8) return __builtin_amdgcn_update_dpp(v, v, 0x140, 0xf, 0xf, false);     // row_mirror
-  return __shfl_xor(v, OFF, 64);
-}
-template <int OFF> DEV float butterfly_partner(float v) {
-  return __builtin_bit_cast(float, butterfly_partner<OFF>(__builtin_bit_cast(int, v)));
-}
-
-// all-reduce over the `width` lanes (power of two <= 64, aligned) a lane belongs to
-template <int RIMPL> DEV float wave_reduce(float acc, uint32_t width) {
-  if (width > 32) acc = red_combine<RIMPL>(acc, butterfly_partner<32>(acc));
-  if (width > 16) acc = red_combine<RIMPL>(acc, butterfly_partner<16>(acc));
-  if (width > 8) acc = red_combine<RIMPL>(acc, butterfly_partner<8>(acc));
-  if (width > 4) acc = red_combine<RIMPL>(acc, butterfly_partner<4>(acc));
-  if (width > 2) acc = red_combine<RIMPL>(acc, butterfly_partner<2>(acc));
-  if (width > 1) acc = red_combine<RIMPL>(acc, butterfly_partner<1>(acc));
-  return acc;
-}
-template <int RIMPL> DEV int32_t wave_reduce_i(int32_t acc, uint32_t width) {
-  if (width > 32) acc = red_combine_i<RIMPL>(acc, butterfly_partner<32>(acc));
-  if (width > 16) acc = red_combine_i<RIMPL>(acc, butterfly_partner<16>(acc));
-  if (width > 8) acc = red_combine_i<RIMPL>(acc, butterfly_partner<8>(acc));
-  if (width > 4) acc = red_combine_i<RIMPL>(acc, butterfly_partner<4>(acc));
-  if (width > 2) acc = red_combine_i<RIMPL>(acc, butterfly_partner<2>(acc));
-  if (width > 1) acc = red_combine_i<RIMPL>(acc, butterfly_partner<1>(acc));
-  return acc;
-}
-
-// PATH_RED_CONTIG: input is a contiguous [rows, n] matrix of dtype DT, output a
-// contiguous vector [rows] of any float dtype.  The rows of a chunk are read as one flat
-// run of 16-byte vectors aligned to the tensor base, whatever n is: a vector that straddles
-// a row boundary is loaded by both rows and masked per element.  Three shapes of work:
-//   short rows  (span <= 64 vectors): P lanes per row, 64 / P rows per wavefront pass,
-//               four passes in flight;
-//   medium rows: one wavefront per row, RA rows at a time, UN loads per row in flight;
-//   long rows   (>= 1024 vectors): the four wavefronts take a quarter of each row, partial
-//               results meet in LDS once per chunk (one barrier per chunk, not per row).
-// Per-element accumulation.  SUM adds.  MAX / MIN must propagate NaN: the running value ignores
-// NaN (one compare + select) and `nan` remembers whether one was seen (one unordered compare,
-// or-ed into a wavefront-uniform mask register); red_finish folds the two before the lanes are combined.
-template <int RIMPL> DEV float red_step(float acc, float x, bool& nan) {
-  if (RIMPL == GPUOS_IMPL_SUM_LAST) return acc + x;
-  nan = nan || (x != x);
-  if (RIMPL == GPUOS_IMPL_MAX_LAST) return x > acc ? x : acc;
-  return x < acc ? x : acc;
-}
-template <int RIMPL> DEV float red_finish(float acc, bool nan) {
-  if (RIMPL == GPUOS_IMPL_SUM_LAST) return acc;
-  return nan ? __builtin_nanf("") : acc;
-}
-
-// Two elements per step for max / min: one three-operand max (min) and ONE unordered compare of
-// the two new elements with each other, which is true exactly when either is a NaN.  The hardware
-// max / min skip quiet NaNs, which is fine: the flag decides the result (red_finish).  Three
-// operations per element (compare, compare, select) become one; the 16-bit reductions were
-// bound by them.
-template <int RIMPL> DEV float red_step2(float acc, float x0, float x1, bool& nan) {
-  nan = nan || __builtin_isunordered(x0, x1);
-  float r;
-  if (RIMPL == GPUOS_IMPL_MAX_LAST) asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(acc), "v"(x0), "v"(x1));
-  else asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(acc), "v"(x0), "v"(x1));
-  return r;
-}
-
-template <int RIMPL, int DT>
-DEV float red_vector(const v4i& q, uint32_t f0, uint32_t lo, uint32_t hi, bool edge, float acc, bool& nan) {
-  // q holds elements f0 .. f0+V-1 of the flat run; the row is [lo, hi)
-  using E = Elem<DT>;
-  if (!edge) {
-    if (RIMPL == GPUOS_IMPL_SUM_LAST) {
-#pragma unroll
-      for (int k = 0; k < E::V; ++k) acc = red_step<RIMPL>(acc, E::get(q, k), nan);
-    } else {
-#pragma unroll
-      for (int k = 0; k < E::V; k += 2) acc = red_step2<RIMPL>(acc, E::get(q, k), E::get(q, k + 1), nan);
-    }
-  } else {
-#pragma unroll
-    for (int k = 0; k < E::V; ++k)
-      if (f0 + k >= lo && f0 + k < hi) acc = red_step<RIMPL>(acc, E::get(q, k), nan);
-  }
-  return acc;
-}
-
-
-struct RedArgs {       // what a row-reduction variant is called with (plain values: see lds_arg)
-  const char* base;    // first byte of the run: the tensor base advanced to the chunk's first vector
-  uint32_t bytes;      // length of the run, whole vectors
-  uint32_t base_elem;  // first element of the run (multiple of V), relative to the tensor
-  uint32_t n;
-  char* po;
-  uint32_t odt, row_begin, row_end, max_span;
-  float* s_part;       // LDS
-};
-struct RedRun {        // the chunk's rows as a flat run of vectors
-  rsrc_t rin;
-  uint32_t base_elem;
-  uint32_t n;
-};
-DEV RedRun red_run(const RedArgs& a) {
-  RedRun run;
-  run.rin = make_rsrc(uni_ptr((uint64_t)a.base), uni(a.bytes));
-  run.base_elem = uni(a.base_elem);
-  run.n = uni(a.n);
-  return run;
-}
-
-template <int POL, int RIMPL, int DT, int RA, int UN>
-PATHFN void red_rows_wave(RedArgs a) {
-  const RedRun run = red_run(a);
-  char* po = (char*)uni_ptr((uint64_t)a.po);
-  const uint32_t odt = uni(a.odt), row_begin = uni(a.row_begin), row_end = uni(a.row_end);
-  using E = Elem<DT>;
-  using M = Mem<POL>;
-  constexpr uint32_t V = E::V;
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  const uint32_t n = run.n;
-  // wave w takes rows row_begin + w, + 4, + 8, ... ; RA of them at a time
-  for (uint32_t row0 = row_begin + wave; row0 < row_end; row0 += 4 * RA) {
-    float acc[RA];
-    bool nan[RA];
-    uint32_t lo[RA], hi[RA], j0[RA], j1[RA];
-    uint32_t span = 0;
-#pragma unroll
-    for (int i = 0; i < RA; ++i) {
-      acc[i] = red_identity<RIMPL>();
-      nan[i] = false;
-      const uint32_t row = row0 + 4 * i;
-      lo[i] = row * n - run.base_elem;
-      hi[i] = lo[i] + n;
-      j0[i] = lo[i] / V;
-      j1[i] = (hi[i] - 1) / V;
-      if (row >= row_end) { hi[i] = lo[i]; j1[i] = j0[i]; }
-      const uint32_t sp = j1[i] - j0[i] + 1;
-      span = sp > span ? sp : span;
-    }
-    for (uint32_t v = lane; v < span; v += 64 * UN) {
-      v4i q[RA][UN];
-#pragma unroll
-      for (int i = 0; i < RA; ++i)
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {   // vectors past the row are not fetched
-          const uint32_t j = j0[i] + v + u * 64;
-          q[i][u] = M::ld16(run.rin, (j <= j1[i] && hi[i] > lo[i]) ? j * 16u : kNoLoad);
-        }
-#pragma unroll
-      for (int i = 0; i < RA; ++i)
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-          const uint32_t j = j0[i] + v + u * 64;
-          if (j <= j1[i] && hi[i] > lo[i])
-            acc[i] = red_vector<RIMPL, DT>(q[i][u], j * V, lo[i], hi[i], j == j0[i] || j == j1[i], acc[i], nan[i]);
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < RA; ++i) {
-      const float t = wave_reduce<RIMPL>(red_finish<RIMPL>(acc[i], nan[i]), 64);
-      if (lane == 0 && row0 + 4 * i < row_end) store_rt<POL>(po, row0 + 4 * i, odt, t);
-    }
-  }
-}
-
-constexpr uint32_t kRedPartialRows = 64;   // rows of partial results the LDS scratch holds
-
-template <int POL, int RIMPL, int DT>
-PATHFN void red_rows_quarter(RedArgs a) {
-  const RedRun run = red_run(a);
-  char* po = (char*)uni_ptr((uint64_t)a.po);
-  const uint32_t odt = uni(a.odt), row_begin = uni(a.row_begin), row_end = uni(a.row_end);
-  float* s_part = lds_arg(a.s_part);
-  using E = Elem<DT>;
-  using M = Mem<POL>;
-  constexpr uint32_t V = E::V;
-  constexpr int UN = 8;
-  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-  const uint32_t n = run.n;
-  for (uint32_t row = row_begin; row < row_end; ++row) {
-    const uint32_t lo = row * n - run.base_elem, hi = lo + n;
-    const uint32_t j0 = lo / V, j1 = (hi - 1) / V;
-    const uint32_t span = j1 - j0 + 1, sq = (span + 3u) / 4u;          // vectors per quarter
-    const uint32_t q_begin = j0 + wave * sq;
-    const uint32_t q_end = (q_begin + sq <= j1 + 1) ? q_begin + sq : j1 + 1;
-    float a0 = red_identity<RIMPL>(), a1 = a0;
-    bool nan = false;
-    for (uint32_t v = q_begin + lane; v < q_end; v += 64 * UN) {
-      v4i q[UN];
-#pragma unroll
-      for (int u = 0; u < UN; ++u) q[u] = M::ld16(run.rin, (v + u * 64 < q_end) ? (v + u * 64) * 16u : kNoLoad);
-#pragma unroll
-      for (int u = 0; u < UN; ++u) {
-        const uint32_t j = v + u * 64;
-        if (j < q_end) {
-          if ((u & 1) == 0) a0 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a0, nan);
-          else a1 = red_vector<RIMPL, DT>(q[u], j * V, lo, hi, j == j0 || j == j1, a1, nan);
-        }
-      }
-    }
-    const float t = wave_reduce<RIMPL>(red_finish<RIMPL>(red_combine<RIMPL>(a0, a1), nan), 64);
-    if (lane == 0) s_part[(row - row_begin) * 4 + wave] = t;
-  }
-  __syncthreads();
-  const uint32_t nrows = row_end - row_begin;
-  if (tid < nrows) {
-    const float* p = s_part + tid * 4;
-    const float t = red_combine<RIMPL>(red_combine<RIMPL>(p[0], p[1]), red_combine<RIMPL>(p[2], p[3]));
-    store_rt<POL>(po, row_begin + tid, odt, t);
-  }
-  __syncthreads();
-}
-
-template <int POL, int RIMPL, int DT>
-PATHFN void red_rows_short(RedArgs a) {
-  const RedRun run = red_run(a);
-  char* po = (char*)uni_ptr((uint64_t)a.po);
-  const uint32_t odt = uni(a.odt), row_begin = uni(a.row_begin), row_end = uni(a.row_end), max_span = uni(a.max_span);
-  using E = Elem<DT>;
-  using M = Mem<POL>;
-  constexpr uint32_t V = E::V;
-  constexpr int UP = 8;
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  const uint32_t n = run.n;
-  uint32_t P = 1;                                     // lanes per row: power of two >= the widest span
-  while (P < max_span) P <<= 1;
-  const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
-  const bool gather = UP * rpw <= 64u;                // the pass's rows fit one lane each
-  // one wavefront pass covers the UP * rpw consecutive rows base .. base + UP * rpw - 1
-  for (uint32_t base = row_begin + wave * rpw * UP; base < row_end; base += 4 * rpw * UP) {
-    v4i q[UP];
-    uint32_t lo[UP], hi[UP], j0[UP], j1[UP];
-#pragma unroll
-    for (int u = 0; u < UP; ++u) {
-      const uint32_t row = base + u * rpw + sub;
-      lo[u] = row * n - run.base_elem;
-      hi[u] = lo[u] + n;
-      j0[u] = lo[u] / V;
-      j1[u] = (hi[u] - 1) / V;
-      q[u] = M::ld16(run.rin, (row < row_end && j0[u] + j <= j1[u]) ? (j0[u] + j) * 16u : kNoLoad);
-    }
-    float mine = 0.0f;                                // lane L ends up with the result of row base + L
-#pragma unroll
-    for (int u = 0; u < UP; ++u) {
-      const uint32_t row = base + u * rpw + sub;
-      const uint32_t jj = j0[u] + j;
-      float acc = red_identity<RIMPL>();
-      bool nan = false;
-      if (row < row_end && jj <= j1[u])
-        acc = red_vector<RIMPL, DT>(q[u], jj * V, lo[u], hi[u], jj == j0[u] || jj == j1[u], acc, nan);
-      acc = wave_reduce<RIMPL>(red_finish<RIMPL>(acc, nan), P);
-      // every lane of sub-group s now holds the result of row base + u * rpw + s
-      if (gather) {
-        const float got = __shfl(acc, (int)((lane & (rpw - 1u)) * P), 64);
-        if (lane / rpw == (uint32_t)u) mine = got;
-      } else if (row < row_end && j == 0) {
-        store_rt<POL>(po, row, odt, acc);            // rows of one or two vectors: the owners are adjacent lanes already
-      }
-    }
-    // UP * rpw consecutive rows, one lane each: a coalesced store instead of one 4-byte store per row
-    if (gather && lane < UP * rpw && base + lane < row_end) store_rt<POL>(po, base + lane, odt, mine);
-  }
-}
-
-template <int POL, int RIMPL, int DT>
-DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_part) {
-  using E = Elem<DT>;
-  constexpr uint32_t V = E::V;
-  const uint32_t n = uni(r->red_n);
-  const char* pin = uni_ptr(r->ptr[0]);
-  char* po = (char*)uni_ptr(r->ptr[3]);
-  const uint32_t odt = uni(r->dtype[3]);
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  if (r->rflags & RF_VEC) {                           // tensor base is 16-byte aligned
-    RedArgs a;
-    a.n = n;
-    a.base_elem = (row_begin * n) / V * V;            // chunk start, aligned down to a vector
-    // end rounded up to a whole vector (the base is 16-byte aligned, so the padding stays inside
-    // the 16-byte block that holds the last element); vector loads further out read zeros; both
-    // are masked per element
-    a.base = pin + (uint64_t)a.base_elem * E::ES;
-    a.bytes = ((row_end * n - a.base_elem) * E::ES + 15u) & ~15u;
-    a.po = po; a.odt = odt; a.row_begin = row_begin; a.row_end = row_end; a.s_part = s_part;
-    a.max_span = (n % V == 0 && a.base_elem == row_begin * n) ? n / V : (n + V - 2) / V + 1;
-    if (a.max_span <= 64u) red_rows_short<POL, RIMPL, DT>(a);
-    else if (a.max_span >= 1024u && row_end - row_begin <= kRedPartialRows) red_rows_quarter<POL, RIMPL, DT>(a);
-    else if (a.max_span < 256u) red_rows_wave<POL, RIMPL, DT, 4, 2>(a);
-    else red_rows_wave<POL, RIMPL, DT, 2, 4>(a);
-    return;
-  }
-  // tensor base not 16-byte aligned: one wave per row, element loads
-  for (uint32_t row = row_begin + wave; row < row_end; row += 4) {
-    const char* prow = pin + (uint64_t)row * n * E::ES;
-    float acc = red_identity<RIMPL>();
-    for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine<RIMPL>(acc, E::template load1<POL>(prow, jx));
-    acc = wave_reduce<RIMPL>(acc, 64);
-    if (lane == 0) store_rt<POL>(po, row, odt, acc);
-  }
-}
-
-// PATH_RED_GENERIC: one wave per output row; outer index decomposed over the
-// coalesced outer dims; stride[0][5] walks the reduced dim.
-template <int POL, int RIMPL, bool INT>
-PATHFN void red_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
-  const Record* r = lds_arg(r_v);
-  const uint32_t row_begin = uni(begin_v), row_end = uni(end_v);
-  using M = Mem<POL>;
-  const int nd = (int)uni(r->ndim);                   // outer dims
-  const uint32_t n = uni(r->red_n), sl = uni(r->stride[0][5]);
-  const char* pin = uni_ptr(r->ptr[0]);
-  char* po = (char*)uni_ptr(r->ptr[3]);
-  const uint32_t idt = uni(r->dtype[0]), odt = uni(r->dtype[3]);
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  for (uint32_t row = row_begin + wave; row < row_end; row += 4) {
-    uint32_t rem = row, ioff = 0, ooff = 0;
-#pragma unroll
-    for (int d = GPUOS_MAX_DIMS - 2; d >= 0; --d) {
-      if (d < nd) {
-        const uint32_t sz = uni(r->size[d]);
-        const uint32_t q = rem / sz, idx = rem - q * sz;
-        rem = q;
-        ioff += idx * uni(r->stride[0][d]);
-        ooff += idx * uni(r->stride[3][d]);
-      }
-    }
-    if (INT) {
-      int32_t acc = red_identity_i<RIMPL>();
-      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine_i<RIMPL>(acc, (int32_t)M::ld4(pin, ioff + jx * sl));
-      acc = wave_reduce_i<RIMPL>(acc, 64);
-      if (lane == 0) M::st4(po, ooff, (uint32_t)acc);
-    } else {
-      float acc = red_identity<RIMPL>();
-      for (uint32_t jx = lane; jx < n; jx += 64) acc = red_combine<RIMPL>(acc, load_rt<POL>(pin, ioff + jx * sl, idt));
-      acc = wave_reduce<RIMPL>(acc, 64);
-      if (lane == 0) store_rt<POL>(po, ooff, odt, acc);
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------
-// fused row operations (operator library, Section 5.2: softmax, layer normalisation).
-// Each row of the last dim is one problem; the output has the input's shape.
-//   PATH_ROW_FUSED: one dtype, contiguous rows of whole aligned 16-byte vectors, at most 256
-//     vectors per row.  A row is read once into the registers of the P lanes that own it
-//     (P = 64 for rows over 64 vectors, else the power of two >= vectors per row, 64 / P rows
-//     per wavefront pass), reduced with xor butterflies over those lanes, and written once.
-//   PATH_ROW_GENERIC: any strides and dtypes; one wavefront per row, three passes over memory.
-// Arithmetic is fp32.  Lanes outside a row feed the identity (-inf to the softmax, 0 to the
-// sums).  The softmax maximum ignores NaN; a NaN still poisons its row through the sum.
-// ---------------------------------------------------------------------------
-DEV float bfly_sum(float v, uint32_t width) {
-  if (width > 32) v += butterfly_partner<32>(v);
-  if (width > 16) v += butterfly_partner<16>(v);
-  if (width > 8) v += butterfly_partner<8>(v);
-  if (width > 4) v += butterfly_partner<4>(v);
-  if (width > 2) v += butterfly_partner<2>(v);
-  if (width > 1) v += butterfly_partner<1>(v);
-  return v;
-}
-DEV float bfly_max(float v, uint32_t width) {
-  if (width > 32) v = __builtin_fmaxf(v, butterfly_partner<32>(v));
-  if (width > 16) v = __builtin_fmaxf(v, butterfly_partner<16>(v));
-  if (width > 8) v = __builtin_fmaxf(v, butterfly_partner<8>(v));
-  if (width > 4) v = __builtin_fmaxf(v, butterfly_partner<4>(v));
-  if (width > 2) v = __builtin_fmaxf(v, butterfly_partner<2>(v));
-  if (width > 1) v = __builtin_fmaxf(v, butterfly_partner<1>(v));
-  return v;
-}
-
-template <int ROP> struct RowOp {
-  static constexpr int NIN = ROP == GPUOS_IMPL_SOFTMAX_LAST ? 1 : (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? 2 : 3);
-  static constexpr bool SOFTMAX = ROP != GPUOS_IMPL_LAYERNORM_LAST;
-};
-
-// gamma / beta of a layer norm for the V elements of one vector position: of x's dtype (one
-// 16-byte vector), or fp32 under 16-bit x (P32: two vectors), as frameworks keep them.
-template <int POL, int DT, bool P32> struct RowParam {
-  v4i q[P32 ? 2 : 1];
-  DEV void load(rsrc_t rs, uint32_t vec) {
-    if (P32) { q[0] = Mem<POL>::ld16(rs, vec * 32u); q[P32 ? 1 : 0] = Mem<POL>::ld16(rs, vec * 32u + 16u); }
-    else q[0] = Mem<POL>::ld16(rs, vec * 16u);
-  }
-  DEV float get(int e) const {
-    if (P32) return Elem<GPUOS_F32>::get(q[(e >> 2) & (P32 ? 1 : 0)], e & 3);
-    return Elem<DT>::get(q[0], e);
-  }
-};
-
-template <int POL, int ROP, int DT, int KW, int UP, bool P32 = false>
-DEV void rowop_fused(const Record* r, uint32_t row_begin, uint32_t row_end) {
-  using E = Elem<DT>;
-  using M = Mem<POL>;
-  using RO = RowOp<ROP>;
-  constexpr uint32_t V = E::V;
-  const uint32_t n = uni(r->red_n), vpr = n / V;
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  uint32_t P = 64;
-  if (KW == 1) { P = 1; while (P < vpr) P <<= 1; }
-  const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
-  const float alpha = r->alpha;
-  const uint32_t nrows = row_end - row_begin;
-  const uint32_t chunk_bytes = nrows * n * E::ES;
-  const uint64_t chunk_off = (uint64_t)row_begin * n * E::ES;
-  const rsrc_t rx = make_rsrc(uni_ptr(r->ptr[0]) + chunk_off, chunk_bytes);
-  const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + chunk_off, chunk_bytes);
-  // second / third input: laid out like x (K_FULL) or a [period, n] block reused every period rows;
-  // layer norm: gamma and beta are always one row
-  rsrc_t rs[2];
-  uint32_t period[2] = {0, 0};
-#pragma unroll
-  for (int k = 1; k < RO::NIN; ++k) {
-    if (!RO::SOFTMAX) {
-      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), n * (P32 ? 4u : (uint32_t)E::ES));
-    } else if (uni(r->okind[k]) == K_FULL) {
-      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]) + chunk_off, chunk_bytes);
-    } else {
-      period[k - 1] = uni(r->stride[k][0]);
-      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), period[k - 1] * n * E::ES);
-    }
-  }
-  // layer norm: this lane's pieces of gamma and beta are loaded once
-  RowParam<POL, DT, P32> gq[KW], bq[KW];
-  if (!RO::SOFTMAX) {
-#pragma unroll
-    for (int k = 0; k < KW; ++k) {
-      const uint32_t vec = j + 64u * k;
-      gq[k].load(rs[0], vec);                        // past the row: reads zeros (bounds-checked), never used
-      bq[k].load(rs[1], vec);
-    }
-  }
-  for (uint32_t base = row_begin + wave * rpw * UP; base < row_end; base += 4u * rpw * UP) {
-    v4i q[UP][KW], mq[UP][KW];
-    bool act[UP][KW];
-#pragma unroll
-    for (int u = 0; u < UP; ++u) {
-      const uint32_t row = base + u * rpw + sub, lr = row - row_begin;
-      uint32_t mr = lr;
-      if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST && period[0]) mr = row % period[0];
-#pragma unroll
-      for (int k = 0; k < KW; ++k) {
-        const uint32_t vec = j + 64u * k;
-        act[u][k] = row < row_end && vec < vpr;
-        // rows past the chunk and vectors past the row read zeros or a neighbour's data; masked below
-        q[u][k] = M::ld16(rx, (lr * vpr + vec) * 16u);
-        if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) mq[u][k] = M::ld16(rs[0], (mr * vpr + vec) * 16u);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < UP; ++u) {
-      const uint32_t row = base + u * rpw + sub, lr = row - row_begin;
-      float t[KW][V];
-      if (RO::SOFTMAX) {
-        float m = -__builtin_inff();
-#pragma unroll
-        for (int k = 0; k < KW; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) {
-            float x = E::get(q[u][k], e);
-            if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) x = alpha * x + E::get(mq[u][k], e);
-            t[k][e] = act[u][k] ? x : -__builtin_inff();
-            m = __builtin_fmaxf(m, t[k][e]);
-          }
-        m = bfly_max(m, P);
-        float s = 0.0f;
-#pragma unroll
-        for (int k = 0; k < KW; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) { t[k][e] = __expf(t[k][e] - m); s += t[k][e]; }
-        s = bfly_sum(s, P);
-        const float inv = 1.0f / s;
-#pragma unroll
-        for (int k = 0; k < KW; ++k) {
-          v4i oq;
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * inv);
-          if (act[u][k]) M::st16(ro, (lr * vpr + j + 64u * k) * 16u, oq);
-        }
-      } else {
-        float s = 0.0f;
-#pragma unroll
-        for (int k = 0; k < KW; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[u][k] ? E::get(q[u][k], e) : 0.0f; s += t[k][e]; }
-        const float mean = bfly_sum(s, P) / (float)n;
-        float ss = 0.0f;
-#pragma unroll
-        for (int k = 0; k < KW; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[u][k] ? t[k][e] - mean : 0.0f; ss += t[k][e] * t[k][e]; }
-        const float var = bfly_sum(ss, P) / (float)n;
-        const float rstd = 1.0f / __builtin_sqrtf(var + alpha);
-#pragma unroll
-        for (int k = 0; k < KW; ++k) {
-          v4i oq;
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * gq[k].get(e) + bq[k].get(e));
-          if (act[u][k]) M::st16(ro, (lr * vpr + j + 64u * k) * 16u, oq);
-        }
-      }
-    }
-  }
-}
-
-template <int POL, int ROP>
-PATHFN void rowop_generic(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
-  const Record* r = lds_arg(r_v);
-  const uint32_t row_begin = uni(begin_v), row_end = uni(end_v);
-  using RO = RowOp<ROP>;
-  const int nd = (int)uni(r->ndim);                   // outer dims
-  const uint32_t n = uni(r->red_n);
-  const float alpha = r->alpha;
-  const char* p[3];
-  uint32_t dt[3], sl[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    const int kk = k < RO::NIN ? k : 0;
-    p[k] = uni_ptr(r->ptr[kk]); dt[k] = uni(r->dtype[kk]); sl[k] = uni(r->stride[kk][5]);
-  }
-  char* po = (char*)uni_ptr(r->ptr[3]);
-  const uint32_t odt = uni(r->dtype[3]), slo = uni(r->stride[3][5]);
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  for (uint32_t row = row_begin + wave; row < row_end; row += 4) {
-    uint32_t rem = row, off[3] = {0, 0, 0}, ooff = 0;
-#pragma unroll
-    for (int d = GPUOS_MAX_DIMS - 2; d >= 0; --d) {
-      if (d < nd) {
-        const uint32_t sz = uni(r->size[d]);
-        const uint32_t qd = rem / sz, idx = rem - qd * sz;
-        rem = qd;
-#pragma unroll
-        for (int k = 0; k < RO::NIN; ++k) off[k] += idx * uni(r->stride[k][d]);
-        ooff += idx * uni(r->stride[3][d]);
-      }
-    }
-    if (RO::SOFTMAX) {
-      auto arg = [&](uint32_t jx) {
-        float x = load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]);
-        if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) x = alpha * x + load_rt<POL>(p[1], off[1] + jx * sl[1], dt[1]);
-        return x;
-      };
-      float m = -__builtin_inff();
-      for (uint32_t jx = lane; jx < n; jx += 64) m = __builtin_fmaxf(m, arg(jx));
-      m = bfly_max(m, 64);
-      float s = 0.0f;
-      for (uint32_t jx = lane; jx < n; jx += 64) s += __expf(arg(jx) - m);
-      s = bfly_sum(s, 64);
-      const float inv = 1.0f / s;
-      for (uint32_t jx = lane; jx < n; jx += 64) store_rt<POL>(po, ooff + jx * slo, odt, __expf(arg(jx) - m) * inv);
-    } else {
-      float s = 0.0f;
-      for (uint32_t jx = lane; jx < n; jx += 64) s += load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]);
-      const float mean = bfly_sum(s, 64) / (float)n;
-      float ss = 0.0f;
-      for (uint32_t jx = lane; jx < n; jx += 64) {
-        const float d = load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]) - mean;
-        ss += d * d;
-      }
-      const float var = bfly_sum(ss, 64) / (float)n;
-      const float rstd = 1.0f / __builtin_sqrtf(var + alpha);
-      for (uint32_t jx = lane; jx < n; jx += 64) {
-        const float d = load_rt<POL>(p[0], off[0] + jx * sl[0], dt[0]) - mean;
-        store_rt<POL>(po, ooff + jx * slo, odt,
-                      d * rstd * load_rt<POL>(p[1], off[1] + jx * sl[1], dt[1]) + load_rt<POL>(p[2], off[2] + jx * sl[2], dt[2]));
-      }
-    }
-  }
-}
-
-// Rows longer than one wavefront's registers: the whole workgroup owns a row.  KW = 1..4: the row
-// (up to 1024 vectors) lives in registers, 256 lanes x KW vectors, read once and written once.
-// KW = 0: any length, three streaming passes of 16-byte vector loads over the row (the second and
-// third pass re-read what the first brought into the caches).  Cross-wavefront reductions go
-// through four rotating LDS slots: one barrier per reduction.
-template <int POL, int ROP, int DT, int KW, bool P32 = false>
-DEV void rowop_wg(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_red) {
-  using E = Elem<DT>;
-  using M = Mem<POL>;
-  using RO = RowOp<ROP>;
-  constexpr uint32_t V = E::V;
-  constexpr int KR = KW > 0 ? KW : 1;
-  const uint32_t n = uni(r->red_n), vpr = n / V;
-  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-  const float alpha = r->alpha;
-  const uint32_t nrows = row_end - row_begin;
-  const uint32_t chunk_bytes = nrows * n * E::ES;
-  const uint64_t chunk_off = (uint64_t)row_begin * n * E::ES;
-  const rsrc_t rx = make_rsrc(uni_ptr(r->ptr[0]) + chunk_off, chunk_bytes);
-  const rsrc_t ro = make_rsrc(uni_ptr(r->ptr[3]) + chunk_off, chunk_bytes);
-  rsrc_t rs[2];
-  uint32_t period[2] = {0, 0};
-#pragma unroll
-  for (int k = 1; k < RO::NIN; ++k) {
-    if (!RO::SOFTMAX) {
-      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), n * (P32 ? 4u : (uint32_t)E::ES));      // gamma, beta: one row
-    } else if (uni(r->okind[k]) == K_FULL) {
-      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]) + chunk_off, chunk_bytes);
-    } else {
-      period[k - 1] = uni(r->stride[k][0]);
-      rs[k - 1] = make_rsrc(uni_ptr(r->ptr[k]), period[k - 1] * n * E::ES);
-    }
-  }
-  uint32_t turn = 0;                                   // which of the four LDS slots the next reduction uses
-  auto wg_sum = [&](float v) {
-    v = bfly_sum(v, 64);
-    float* slot = s_red + (turn & 3u) * 4u;
-    ++turn;
-    if (lane == 0) slot[wave] = v;
-    __syncthreads();
-    return (slot[0] + slot[1]) + (slot[2] + slot[3]);
-  };
-  auto wg_max = [&](float v) {
-    v = bfly_max(v, 64);
-    float* slot = s_red + (turn & 3u) * 4u;
-    ++turn;
-    if (lane == 0) slot[wave] = v;
-    __syncthreads();
-    return __builtin_fmaxf(__builtin_fmaxf(slot[0], slot[1]), __builtin_fmaxf(slot[2], slot[3]));
-  };
-  // the argument of element e of vector `vec` of local row lr (softmax family) / the element itself
-  auto arg = [&](const v4i& q, const v4i& mq, int e) {
-    float x = E::get(q, e);
-    if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) x = alpha * x + E::get(mq, e);
-    return x;
-  };
-  RowParam<POL, DT, P32> gq[KR], bq[KR];               // layer norm, KW > 0: this lane's gamma / beta pieces
-  if (!RO::SOFTMAX && KW > 0) {
-#pragma unroll
-    for (int k = 0; k < KR; ++k) {
-      gq[k].load(rs[0], tid + kThreads * k);
-      bq[k].load(rs[1], tid + kThreads * k);
-    }
-  }
-  for (uint32_t row = row_begin; row < row_end; ++row) {
-    const uint32_t lr = row - row_begin;
-    uint32_t mr = lr;
-    if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST && period[0]) mr = row % period[0];
-    if (KW > 0) {
-      v4i q[KR], mq[KR];
-      bool act[KR];
-#pragma unroll
-      for (int k = 0; k < KR; ++k) {
-        const uint32_t vec = tid + kThreads * k;
-        act[k] = vec < vpr;
-        q[k] = M::ld16(rx, act[k] ? (lr * vpr + vec) * 16u : kNoLoad);
-        if (ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST) mq[k] = M::ld16(rs[0], act[k] ? (mr * vpr + vec) * 16u : kNoLoad);
-      }
-      float t[KR][V];
-      if (RO::SOFTMAX) {
-        float m = -__builtin_inff();
-#pragma unroll
-        for (int k = 0; k < KR; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[k] ? arg(q[k], mq[k], e) : -__builtin_inff(); m = __builtin_fmaxf(m, t[k][e]); }
-        m = wg_max(m);
-        float sum = 0.0f;
-#pragma unroll
-        for (int k = 0; k < KR; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) { t[k][e] = __expf(t[k][e] - m); sum += t[k][e]; }
-        const float inv = 1.0f / wg_sum(sum);
-#pragma unroll
-        for (int k = 0; k < KR; ++k) {
-          v4i oq;
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * inv);
-          if (act[k]) M::st16(ro, (lr * vpr + tid + kThreads * k) * 16u, oq);
-        }
-      } else {
-        float sum = 0.0f;
-#pragma unroll
-        for (int k = 0; k < KR; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[k] ? E::get(q[k], e) : 0.0f; sum += t[k][e]; }
-        const float mean = wg_sum(sum) / (float)n;
-        float ss = 0.0f;
-#pragma unroll
-        for (int k = 0; k < KR; ++k)
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) { t[k][e] = act[k] ? t[k][e] - mean : 0.0f; ss += t[k][e] * t[k][e]; }
-        const float rstd = 1.0f / __builtin_sqrtf(wg_sum(ss) / (float)n + alpha);
-#pragma unroll
-        for (int k = 0; k < KR; ++k) {
-          v4i oq;
-#pragma unroll
-          for (int e = 0; e < (int)V; ++e) E::put(oq, e, t[k][e] * rstd * gq[k].get(e) + bq[k].get(e));
-          if (act[k]) M::st16(ro, (lr * vpr + tid + kThreads * k) * 16u, oq);
-        }
-      }
-    } else if (RO::SOFTMAX) {
-      const v4i zero = {0, 0, 0, 0};
-      float m = -__builtin_inff();
-      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
-        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
-        const v4i mq = ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? M::ld16(rs[0], (mr * vpr + vec) * 16u) : zero;
-#pragma unroll
-        for (int e = 0; e < (int)V; ++e) m = __builtin_fmaxf(m, arg(q, mq, e));
-      }
-      m = wg_max(m);
-      float sum = 0.0f;
-      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
-        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
-        const v4i mq = ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? M::ld16(rs[0], (mr * vpr + vec) * 16u) : zero;
-#pragma unroll
-        for (int e = 0; e < (int)V; ++e) sum += __expf(arg(q, mq, e) - m);
-      }
-      const float inv = 1.0f / wg_sum(sum);
-      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
-        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
-        const v4i mq = ROP == GPUOS_IMPL_MASKED_SOFTMAX_LAST ? M::ld16(rs[0], (mr * vpr + vec) * 16u) : zero;
-        v4i oq;
-#pragma unroll
-        for (int e = 0; e < (int)V; ++e) E::put(oq, e, __expf(arg(q, mq, e) - m) * inv);
-        M::st16(ro, (lr * vpr + vec) * 16u, oq);
-      }
-    } else {
-      float sum = 0.0f;
-      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
-        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
-#pragma unroll
-        for (int e = 0; e < (int)V; ++e) sum += E::get(q, e);
-      }
-      const float mean = wg_sum(sum) / (float)n;
-      float ss = 0.0f;
-      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
-        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
-#pragma unroll
-        for (int e = 0; e < (int)V; ++e) { const float d = E::get(q, e) - mean; ss += d * d; }
-      }
-      const float rstd = 1.0f / __builtin_sqrtf(wg_sum(ss) / (float)n + alpha);
-      for (uint32_t vec = tid; vec < vpr; vec += kThreads) {
-        const v4i q = M::ld16(rx, (lr * vpr + vec) * 16u);
-        RowParam<POL, DT, P32> g, b;
-        g.load(rs[0], vec);
-        b.load(rs[1], vec);
-        v4i oq;
-#pragma unroll
-        for (int e = 0; e < (int)V; ++e) E::put(oq, e, (E::get(q, e) - mean) * rstd * g.get(e) + b.get(e));
-        M::st16(ro, (lr * vpr + vec) * 16u, oq);
-      }
-    }
-  }
-  __syncthreads();                                     // the LDS slots belong to the next chunk after this
-}
-
-template <int POL, int ROP, int DT>
-PATHFN void rowop_fused_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
-  const Record* r = lds_arg(r_v);
-  const uint32_t begin = uni(begin_v), end = uni(end_v);
-  const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
-  if (ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32 && uni(r->dtype[1]) == GPUOS_F32) {   // fp32 gamma / beta under 16-bit x
-    constexpr bool P = ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32;
-    if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 4, P>(r, begin, end);
-    else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 2, P>(r, begin, end);
-    else rowop_fused<POL, ROP, DT, 4, 1, P>(r, begin, end);
-    return;
-  }
-  if (vpr <= 64u) rowop_fused<POL, ROP, DT, 1, 4>(r, begin, end);
-  else if (vpr <= 128u) rowop_fused<POL, ROP, DT, 2, 2>(r, begin, end);
-  else rowop_fused<POL, ROP, DT, 4, 1>(r, begin, end);
-}
-
-template <int POL, int ROP, int DT>
-PATHFN void rowop_wg_dt(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
-  const Record* r = lds_arg(r_v);
-  float* s_red = lds_arg(s_v);
-  const uint32_t begin = uni(begin_v), end = uni(end_v);
-  const uint32_t vpr = uni(r->red_n) / Elem<DT>::V;
-  if (ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32 && uni(r->dtype[1]) == GPUOS_F32) {
-    constexpr bool P = ROP == GPUOS_IMPL_LAYERNORM_LAST && DT != GPUOS_F32;
-    if (vpr <= 512u) rowop_wg<POL, ROP, DT, 2, P>(r, begin, end, s_red);
-    else if (vpr <= 1024u) rowop_wg<POL, ROP, DT, 4, P>(r, begin, end, s_red);
-    else rowop_wg<POL, ROP, DT, 0, P>(r, begin, end, s_red);
-    return;
-  }
-  if (vpr <= 512u) rowop_wg<POL, ROP, DT, 2>(r, begin, end, s_red);
-  else if (vpr <= 1024u) rowop_wg<POL, ROP, DT, 4>(r, begin, end, s_red);
-  else rowop_wg<POL, ROP, DT, 0>(r, begin, end, s_red);
-}
-
-template <int POL, int ROP>
-DEV void run_rowop(const Record* r, uint32_t chunk, float* s_red) {
-  const uint32_t per = uni(r->chunk), rows = uni(r->numel);
-  const uint32_t begin = chunk * per;
-  const uint32_t end = (rows - begin < per) ? rows : begin + per;
-  if (uni(r->path) == PATH_ROW_FUSED) {
-    const uint32_t dt = uni(r->dtype[3]);
-    const bool wide = uni(r->red_n) * (dt == GPUOS_F32 ? 4u : 2u) > 256u * 16u;     // more than 256 vectors per row
-    if (!wide) {
-      if (dt == GPUOS_F32) rowop_fused_dt<POL, ROP, GPUOS_F32>(r, begin, end);
-      else if (dt == GPUOS_F16) rowop_fused_dt<POL, ROP, GPUOS_F16>(r, begin, end);
-      else rowop_fused_dt<POL, ROP, GPUOS_BF16>(r, begin, end);
-    } else {
-      if (dt == GPUOS_F32) rowop_wg_dt<POL, ROP, GPUOS_F32>(r, begin, end, s_red);
-      else if (dt == GPUOS_F16) rowop_wg_dt<POL, ROP, GPUOS_F16>(r, begin, end, s_red);
-      else rowop_wg_dt<POL, ROP, GPUOS_BF16>(r, begin, end, s_red);
-    }
-  } else {
-    rowop_generic<POL, ROP>(r, begin, end);
-  }
-}
-
-// ---------------------------------------------------------------------------
-// chunk executor: operator dispatch by implementation id (the role of the
-// paper's function-pointer table call, Section 4.1; here a switch over
-// precompiled implementations selected by the table entry).
-// ---------------------------------------------------------------------------
-template <int POL, int IMPL>
-DEV void run_elementwise(const Record* r, uint32_t chunk, float* s_scratch) {
-  const uint32_t per = uni(r->chunk), numel = uni(r->numel);
-  const uint32_t begin = chunk * per;
-  const uint32_t end = (numel - begin < per) ? numel : begin + per;
-  const uint32_t path = uni(r->path), dt = uni(r->dtype[3]);
-  constexpr bool int_ok = IMPL == GPUOS_IMPL_ADD || IMPL == GPUOS_IMPL_SUB || IMPL == GPUOS_IMPL_MUL || IMPL == GPUOS_IMPL_COPY;
-  if (r->rflags & RF_INT) {
-    if (int_ok) {
-      if (path == PATH_CONTIG) ew_contig_int<POL, IMPL>(r, begin, end);
-      else ew_generic<POL, int_ok ? IMPL : GPUOS_IMPL_COPY, true>(r, begin, end);
-    }
-    return;
-  }
-  if (path == PATH_CONTIG) {
-    if (dt == GPUOS_F32) ew_contig<POL, IMPL, GPUOS_F32>(r, begin, end);
-    else if (dt == GPUOS_F16) ew_contig<POL, IMPL, GPUOS_F16>(r, begin, end);
-    else ew_contig<POL, IMPL, GPUOS_BF16>(r, begin, end);
-  } else if (path == PATH_ROW2D && Op<IMPL>::N >= 2) {
-    constexpr int I2 = Op<IMPL>::N >= 2 ? IMPL : GPUOS_IMPL_ADD;
-    if (dt == GPUOS_F32) ew_row2d<POL, I2, GPUOS_F32>(r, begin, end, s_scratch);
-    else if (dt == GPUOS_F16) ew_row2d<POL, I2, GPUOS_F16>(r, begin, end, s_scratch);
-    else ew_row2d<POL, I2, GPUOS_BF16>(r, begin, end, s_scratch);
-  } else if (path == PATH_TILE2D) {
-    ew_tile2d<POL, IMPL>(r, begin, end, s_scratch);      // begin / end count tiles here
-  } else {
-    ew_generic<POL, IMPL, false>(r, begin, end);
-  }
-}
-
-template <int POL, int RIMPL>
-DEV void run_reduction(const Record* r, uint32_t chunk, float* s_red) {
-  const uint32_t per = uni(r->chunk), rows = uni(r->numel);
-  const uint32_t begin = chunk * per;
-  const uint32_t end = (rows - begin < per) ? rows : begin + per;
-  const uint32_t path = uni(r->path), dt = uni(r->dtype[0]);
-  if (r->rflags & RF_INT) { red_generic<POL, RIMPL, true>(r, begin, end); return; }
-  if (path == PATH_RED_CONTIG) {
-    if (dt == GPUOS_F32) red_contig<POL, RIMPL, GPUOS_F32>(r, begin, end, s_red);
-    else if (dt == GPUOS_F16) red_contig<POL, RIMPL, GPUOS_F16>(r, begin, end, s_red);
-    else red_contig<POL, RIMPL, GPUOS_BF16>(r, begin, end, s_red);
-  } else {
-    red_generic<POL, RIMPL, false>(r, begin, end);
-  }
-}
-
-// A task whose operator is a program: fetch the program into LDS (17 lanes x 16 bytes), then run
-// the ordinary elementwise paths with the interpreter as their functor.
-template <int POL>
-DEV int32_t exec_program(const Record* r, uint32_t impl, uint32_t chunk, float* s_red, const ProgramImage* progs) {
-  const uint32_t k = impl - GPUOS_IMPL_PROGRAM_BASE;
-  if (progs == nullptr || k >= GPUOS_MAX_PROGRAMS) return GPUOS_E_BADOP;
-  const rsrc_t rp = make_rsrc(progs + k, (uint32_t)sizeof(ProgramImage));
-  if (threadIdx.x < sizeof(ProgramImage) / 16) ((v4i*)&g_prog)[threadIdx.x] = Mem<POL_COHERENT>::ld16(rp, threadIdx.x * 16u);
-  __syncthreads();
-  int32_t status = GPUOS_OK;
-  const uint32_t n_in = uni(g_prog.n_inputs), n_instr = uni(g_prog.n_instr);
-  if (uni(g_prog.ready) != kProgramReady || n_instr < 1 || n_instr > GPUOS_PROGRAM_MAX_INSTR || n_in != uni(r->n_inputs))
-    status = GPUOS_E_INVAL;                            // never defined (or not what the task was packed for)
-  else if (n_in == 1) run_elementwise<POL, kImplProg1>(r, chunk, s_red);
-  else if (n_in == 2) run_elementwise<POL, kImplProg2>(r, chunk, s_red);
-  else run_elementwise<POL, kImplProg3>(r, chunk, s_red);
-  __syncthreads();                                     // the next chunk may bring another program
-  return status;
-}
-
-// returns the task status contribution of this chunk (0 or an error)
-template <int POL>
-DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_red, const ProgramImage* progs) {
-  if (uni(r->path) == PATH_NOP) return impl == GPUOS_IMPL_FAIL ? GPUOS_E_BADOP : GPUOS_OK;
-  if (impl >= GPUOS_IMPL_PROGRAM_BASE) return exec_program<POL>(r, impl, chunk, s_red, progs);
-  switch (impl) {
-    case GPUOS_IMPL_ADD: run_elementwise<POL, GPUOS_IMPL_ADD>(r, chunk, s_red); break;
-    case GPUOS_IMPL_SUB: run_elementwise<POL, GPUOS_IMPL_SUB>(r, chunk, s_red); break;
-    case GPUOS_IMPL_MUL: run_elementwise<POL, GPUOS_IMPL_MUL>(r, chunk, s_red); break;
-    case GPUOS_IMPL_DIV: run_elementwise<POL, GPUOS_IMPL_DIV>(r, chunk, s_red); break;
-    case GPUOS_IMPL_RELU: run_elementwise<POL, GPUOS_IMPL_RELU>(r, chunk, s_red); break;
-    case GPUOS_IMPL_EXP: run_elementwise<POL, GPUOS_IMPL_EXP>(r, chunk, s_red); break;
-    case GPUOS_IMPL_GELU_ERF: run_elementwise<POL, GPUOS_IMPL_GELU_ERF>(r, chunk, s_red); break;
-    case GPUOS_IMPL_GELU_TANH: run_elementwise<POL, GPUOS_IMPL_GELU_TANH>(r, chunk, s_red); break;
-    case GPUOS_IMPL_SCALE: run_elementwise<POL, GPUOS_IMPL_SCALE>(r, chunk, s_red); break;
-    case GPUOS_IMPL_FMA: run_elementwise<POL, GPUOS_IMPL_FMA>(r, chunk, s_red); break;
-    case GPUOS_IMPL_SUB_EXP: run_elementwise<POL, GPUOS_IMPL_SUB_EXP>(r, chunk, s_red); break;
-    case GPUOS_IMPL_COPY: run_elementwise<POL, GPUOS_IMPL_COPY>(r, chunk, s_red); break;
-    case GPUOS_IMPL_SUM_LAST: run_reduction<POL, GPUOS_IMPL_SUM_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_MAX_LAST: run_reduction<POL, GPUOS_IMPL_MAX_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_MIN_LAST: run_reduction<POL, GPUOS_IMPL_MIN_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_SOFTMAX_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_MASKED_SOFTMAX_LAST: run_rowop<POL, GPUOS_IMPL_MASKED_SOFTMAX_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_LAYERNORM_LAST: run_rowop<POL, GPUOS_IMPL_LAYERNORM_LAST>(r, chunk, s_red); break;
-    case GPUOS_IMPL_FAIL: return GPUOS_E_BADOP;       // kill-switch stub: fail fast, write nothing
-    default: return GPUOS_E_BADOP;
-  }
-  return GPUOS_OK;
-}
 
 // ---------------------------------------------------------------------------
 // dispatcher (workgroup 0)
@@ -1581,7 +60,7 @@ struct PubEntry {                          // what it takes to publish a task's 
   uint32_t slot;
   uint32_t nchunks;
   uint32_t opinfo;                         // op id | table slot << 8 | valid << 9
-  uint32_t pad;
+  uint32_t route;                          // 0: main unit ring; 1: the second ring, served by the run-time kernel
 };
 struct PendEntry {
   uint64_t ticket;
@@ -1610,15 +89,13 @@ struct DispShared {
   uint32_t pre[kPrefetch];                 // prefetched with the poll and valid
   uint32_t opcnt[GPUOS_MAX_OPS];           // tracing: tasks dispatched per operator since the last flush
   uint32_t ready[kPendMax];                // per pending entry: dependencies complete
+  uint32_t native[GPUOS_MAX_PROGRAMS];     // per operator program: 1 = its tasks go to the second ring (native code is being served there)
   uint64_t tail, epoch_word;
-  uint32_t n, npend, npub;
+  uint32_t n, npend, npub, npub_second;
 };
 
 // The 16 lanes that hold a record's 16-byte pieces: the weighted check sum of the whole record
 // (see record_check_weight), in every one of them.
-// Reading the clock is a memory-like operation: a dozen reads per task are measurable, so the phase
-// timers are an option and the clock is read only where something needs the value.
-DEV uint64_t clock_if(bool on) { return on ? wall_clock64() : 0ull; }
 
 DEV uint32_t record_piece_sum(const v4i& q, uint32_t part) {
   uint32_t x = 0;
@@ -1631,6 +108,19 @@ DEV uint32_t record_piece_sum(const v4i& q, uint32_t part) {
   x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x122, 0xf, 0xf, false);
   x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x121, 0xf, 0xf, false);
   return x;
+}
+
+DEV void dispatcher_refresh_native(const WorkerArgs& a, DispShared* s) {
+  // which programs a run-time kernel serves natively, and which generation of it is wanted
+  // (the host changes both only between two epoch bumps, and waits in between)
+  const uint32_t tid = threadIdx.x;
+  if (tid < GPUOS_MAX_PROGRAMS)
+    s->native[tid] = (a.units_j != nullptr && a.progs != nullptr)
+                         ? __hip_atomic_load(&a.progs[tid].native, __ATOMIC_RELAXED, SC_SYSTEM) : 0u;
+  if (tid == GPUOS_MAX_PROGRAMS) {
+    const uint32_t g = __hip_atomic_load(&a.bell->jit_gen, __ATOMIC_RELAXED, SC_SYSTEM);
+    __hip_atomic_store(&a.d->jit_gen, g, __ATOMIC_RELAXED, SC_SYSTEM);
+  }
 }
 
 DEV void dispatcher_refresh_table(const WorkerArgs& a, DispShared* s, uint32_t only_op) {
@@ -1690,13 +180,16 @@ DEV bool names_pending(const DispShared* s, uint64_t ticket, const uint16_t* dep
 
 // Write the work units of s->pub[0 .. npub) and make them claimable.  Called by the whole
 // workgroup; returns the number of units published.
-DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npub, uint64_t units_w) {
+// Ring `route` only: entries of the other ring count as zero units (they keep their place in the
+// list, so both rings see their tasks in list order).
+DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npub, uint64_t units_w, uint32_t route = 0) {
   const uint32_t tid = threadIdx.x;
+  uint64_t* const ring = route == 0 ? a.units : a.units_j;
   if (tid < 64) {                                  // wave 0: inclusive scan of nchunks
     // inclusive scan over the wavefront with DPP: shifts by 1, 2, 4, 8 inside each row of 16 lanes
     // (lanes the shift runs out of the row for add 0), then lane 15 of a row to the whole next row
     // (rows 1 and 3), then lane 31 to rows 2 and 3.  Six shuffles through the LDS crossbar before.
-    int v = (int)(tid < npub ? s->pub[tid].nchunks : 0u);
+    int v = (int)((tid < npub && s->pub[tid].route == route) ? s->pub[tid].nchunks : 0u);
     v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
     v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
     v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
@@ -1719,7 +212,7 @@ DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npu
     const PubEntry pe = s->pub[lo];
     const uint64_t g = units_w + u;
     // one 8-byte store publishes the unit: the stamp makes it claimable
-    __hip_atomic_store(&a.units[g & a.unit_mask],
+    __hip_atomic_store(&ring[g & a.unit_mask],
                        pack_unit(u - s->ubeg[lo], pe.slot, pe.opinfo & 0xffu, (pe.opinfo >> 8) & 1u, (pe.opinfo >> 9) & 1u,
                                  unit_stamp(g, a.unit_shift)),
                        __ATOMIC_RELAXED, SC_SYSTEM);
@@ -1728,11 +221,19 @@ DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npu
   return total;
 }
 
-// Publish the pending tasks whose dependencies have completed.  Returns the units published.
-DEV uint32_t dispatcher_service_pending(const WorkerArgs& a, DispShared* s, uint64_t units_w) {
+struct UnitCursors { uint64_t w[2]; };      // units published so far on the main ring and on the second ring
+
+// Publish s->pub[0 .. npub) on the ring(s) its entries name.  Called by the whole workgroup.
+DEV void dispatcher_publish_all(const WorkerArgs& a, DispShared* s, uint32_t npub, UnitCursors& uc, bool any_second) {
+  uc.w[0] += dispatcher_publish(a, s, npub, uc.w[0], 0);
+  if (any_second) uc.w[1] += dispatcher_publish(a, s, npub, uc.w[1], 1);
+}
+
+// Publish the pending tasks whose dependencies have completed.
+DEV void dispatcher_service_pending(const WorkerArgs& a, DispShared* s, UnitCursors& uc) {
   const uint32_t tid = threadIdx.x;
   const uint32_t np = s->npend;
-  if (np == 0) return 0;
+  if (np == 0) return;
   static_assert(kPendMax <= 128 && kPendMax <= kThreads, "one pending entry per thread of the first two wavefronts");
   // One entry per thread: is it ready, and where does it go?  The first kDispatchBatch ready entries
   // move to the publish list, everything else closes ranks in the pending list; both keep their order
@@ -1748,10 +249,12 @@ DEV uint32_t dispatcher_service_pending(const WorkerArgs& a, DispShared* s, uint
   uint64_t m_ready = 0;
   if (tid < 128u) {
     m_ready = __ballot(ready);
-    if (lane == 0) s->ready[wave] = (uint32_t)__popcll(m_ready);
+    const uint64_t m_second = __ballot(ready && e.pub.route != 0);
+    if (lane == 0) { s->ready[wave] = (uint32_t)__popcll(m_ready); s->ready[2 + wave] = m_second != 0 ? 1u : 0u; }
   }
   __syncthreads();                                 // the counts; and every entry is in its thread's registers
   const uint32_t ready0 = s->ready[0], ready_all = ready0 + s->ready[1];
+  const bool any_second = (s->ready[2] | s->ready[3]) != 0;
   if (tid < np) {
     const uint32_t ready_before = (uint32_t)__popcll(m_ready & ((1ull << lane) - 1ull)) + (wave ? ready0 : 0u);
     const uint32_t taken_before = ready_before < kDispatchBatch ? ready_before : kDispatchBatch;
@@ -1761,9 +264,9 @@ DEV uint32_t dispatcher_service_pending(const WorkerArgs& a, DispShared* s, uint
   const uint32_t npub = ready_all < kDispatchBatch ? ready_all : kDispatchBatch;
   __syncthreads();                                 // the lists are complete (and s->ready may be reused)
   if (tid == 0) s->npend = np - npub;
-  if (npub == 0) { __syncthreads(); return 0; }
+  if (npub == 0) { __syncthreads(); return; }
   order_loads();
-  return dispatcher_publish(a, s, npub, units_w);  // its barriers also cover the new pending count
+  dispatcher_publish_all(a, s, npub, uc, any_second);   // its barriers also cover the new pending count
 }
 
 DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
@@ -1772,7 +275,9 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   // counts (both are zero on a fresh context); the operator table is read again from the host's
   // copy because the epoch seen starts at zero.
   uint64_t mirrored = a.resume_tickets, seen_epoch = 0;
-  uint64_t units_w = __hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM);
+  UnitCursors uc;
+  uc.w[0] = __hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM);
+  uc.w[1] = __hip_atomic_load(&a.d->tail_units_j, __ATOMIC_RELAXED, SC_SYSTEM);
   for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) { s->entry[op] = 0; s->opcnt[op] = 0; }
   if (tid == 0) s->npend = 0;
   __syncthreads();
@@ -1791,7 +296,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   bool stopping = false;
   uint64_t st_batches = 0, st_records = 0, st_units = 0, st_stage = 0, st_resolve = 0, st_write = 0, st_busy = 0;
   uint64_t st_deferred = 0;
-  uint64_t claimed = units_w;              // last value read from the claim counter (thread 0)
+  uint64_t claimed = uc.w[0];              // last value read from the claim counter (thread 0)
   constexpr uint32_t kStagePieces = kDispatchBatch * 16u / kThreads;      // 16-byte pieces of a batch per thread
   static_assert(kStagePieces * kThreads == kDispatchBatch * 16u, "a batch is staged in whole rounds of the workgroup");
   uint64_t pre_base = ~0ull;               // first ticket of the records requested ahead (they wait in s->rec)
@@ -1844,6 +349,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       const uint32_t hinted = (uint32_t)((ew >> 4) & 0xffu);
       const bool one = ((ew >> 12) - (seen_epoch >> 12)) == 1 && hinted != 0xffu;
       dispatcher_refresh_table(a, s, one ? hinted : 0xffu);
+      dispatcher_refresh_native(a, s);
       if (tid == 0) {
         const uint32_t y = __hip_atomic_load(&a.bell->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.d->yield_every, y, __ATOMIC_RELAXED, SC_SYSTEM);
@@ -1853,7 +359,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
     seen_epoch = ew & ~3ull;
     if (ew & 3u) stopping = true;
 
-    units_w += dispatcher_service_pending(a, s, units_w);
+    dispatcher_service_pending(a, s, uc);
 
     // ---- mirror new records, batch by batch ----
     bool first_batch = true;                       // the prefetched records belong to the first batch after a poll
@@ -1862,19 +368,19 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       // time is then close to what the workers will see, and the pending list stays short.
       if (tid == 0) {
         // the claim counter only grows: re-read it only when the cached value says "too far ahead"
-        if (units_w > claimed && units_w - claimed >= kLookaheadUnits)
+        if (uc.w[0] > claimed && uc.w[0] - claimed >= kLookaheadUnits)
           claimed = __hip_atomic_load(&a.d->claim, __ATOMIC_RELAXED, SC_SYSTEM);
         const uint32_t room = kPendMax - s->npend;
         uint32_t take = (uint32_t)((tail - mirrored) < kDispatchBatch ? (tail - mirrored) : kDispatchBatch);
         if (take > room) take = room;
-        if (units_w > claimed && units_w - claimed >= kLookaheadUnits) take = 0;
+        if (uc.w[0] > claimed && uc.w[0] - claimed >= kLookaheadUnits) take = 0;
         s->n = take;
       }
       __syncthreads();
       uint32_t n = s->n;
       __syncthreads();
       if (n == 0) {                                                // throttled: let the workers catch up
-        units_w += dispatcher_service_pending(a, s, units_w);
+        dispatcher_service_pending(a, s, uc);
         if (s->npend == 0) __builtin_amdgcn_s_sleep(8);
         break;                                                     // back to the poll loop (stop, table, heartbeat)
       }
@@ -1972,7 +478,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       __syncthreads();
       // a leading FENCE: everything earlier must be published and complete first
       if (s->rec[0].rflags & RF_FENCE) {
-        while (s->npend != 0) units_w += dispatcher_service_pending(a, s, units_w);
+        while (s->npend != 0) dispatcher_service_pending(a, s, uc);
         if (tid == 0) {
           while (__hip_atomic_load(&a.d->done_count, __ATOMIC_RELAXED, SC_SYSTEM) < mirrored)
             __builtin_amdgcn_s_sleep(4);
@@ -2004,6 +510,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         }
         const uint64_t m_pub = __ballot(mine && !held);
         const uint64_t below = (1ull << tid) - 1ull;
+        bool second = false;                                       // published now, on the second ring
         if (held) s->rec[tid].rflags |= RF_DEPS_RESOLVED;          // published only after its dependencies completed
         if (mine) {
           const Record& rc = s->rec[tid];
@@ -2011,7 +518,10 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
           pe.slot = (uint32_t)((mirrored + tid) & a.cap_mask);
           pe.nchunks = rc.nchunks;
           pe.opinfo = (rc.op_id & 0xffu) | ((uint32_t)rc.sel << 8) | ((rc.status == GPUOS_OK ? 1u : 0u) << 9);
-          pe.pad = 0;
+          // tasks of a program that a run-time kernel holds as native code go to that kernel's ring
+          const uint32_t prog = rc.impl - GPUOS_IMPL_PROGRAM_BASE;
+          pe.route = (rc.status == GPUOS_OK && rc.impl >= GPUOS_IMPL_PROGRAM_BASE && prog < GPUOS_MAX_PROGRAMS && s->native[prog] != 0) ? 1u : 0u;
+          second = pe.route != 0 && !held;
           if (held) {
             PendEntry& pd = s->pend[npend0 + (uint32_t)__popcll(m_def & below)];
             pd.ticket = mirrored + tid;
@@ -2021,10 +531,12 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
             s->pub[(uint32_t)__popcll(m_pub & below)] = pe;
           }
         }
+        const uint64_t m_second = __ballot(second);
         if (tid == 0) {
           st_deferred += (uint32_t)__popcll(m_def);
           s->npend = npend0 + (uint32_t)__popcll(m_def);
           s->npub = (uint32_t)__popcll(m_pub);
+          s->npub_second = m_second != 0 ? 1u : 0u;
         }
       }
       __syncthreads();
@@ -2050,7 +562,9 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
         Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, ((const v4i*)&s->rec[rix])[part]);
       }
-      const uint32_t total = dispatcher_publish(a, s, s->npub, units_w);   // drains the stores above as well
+      const uint64_t before = uc.w[0] + uc.w[1];
+      dispatcher_publish_all(a, s, s->npub, uc, s->npub_second != 0);       // drains the stores above as well
+      const uint32_t total = (uint32_t)(uc.w[0] + uc.w[1] - before);
       // nothing reads this batch's staging any more (the mirror has it, held-back tasks were copied
       // to the pending list): it takes the records requested ahead
 #pragma unroll
@@ -2058,13 +572,12 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         const uint32_t p = tid + j * kThreads;
         if (p < pre_n * 16u) ((v4i*)&s->rec[p >> 4])[p & 15u] = pre_q[j];
       }
-      units_w += total;
       mirrored += n;
       if (tid == 0) __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
       if (timing || a.idle_exit_ticks != 0) idle_since = wall_clock64();
       st_batches += 1; st_records += n; st_units += total;
       if (timing) { st_stage += tk1 - tk0; st_resolve += tk2 - tk1; st_write += idle_since - tk2; st_busy += idle_since - tk0; }
-      units_w += dispatcher_service_pending(a, s, units_w);
+      dispatcher_service_pending(a, s, uc);
       if (tracing) {
         counts_dirty = true;
         if (++passes_since_flush >= 256u) {
@@ -2088,7 +601,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       __syncthreads();
     }
     if (stopping && mirrored >= tail) {
-      while (s->npend != 0) units_w += dispatcher_service_pending(a, s, units_w);   // nothing is left behind
+      while (s->npend != 0) dispatcher_service_pending(a, s, uc);   // nothing is left behind
       drain_stores();                                  // every unit store of every wave has landed ...
       __syncthreads();                                 // ... before the stop flag can be seen
       if (tid == 0) {
@@ -2097,180 +610,14 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         st[ST_DISP_BATCHES] += st_batches; st[ST_DISP_RECORDS] += st_records; st[ST_DISP_UNITS] += st_units;
         st[ST_DISP_TICKS_STAGE] += st_stage; st[ST_DISP_TICKS_RESOLVE] += st_resolve; st[ST_DISP_TICKS_WRITE] += st_write;
         st[ST_DISP_TICKS_TOTAL_BUSY] += st_busy; st[ST_DISP_POLLS] += polls; st[ST_DISP_DEFERRED] += st_deferred;
-        __hip_atomic_store(&a.d->tail_units, units_w, __ATOMIC_RELAXED, SC_SYSTEM);
+        __hip_atomic_store(&a.d->tail_units, uc.w[0], __ATOMIC_RELAXED, SC_SYSTEM);
+        __hip_atomic_store(&a.d->tail_units_j, uc.w[1], __ATOMIC_RELAXED, SC_SYSTEM);
         drain_stores();
         __hip_atomic_store(&a.d->stop_dev, 1u, __ATOMIC_RELAXED, SC_SYSTEM);
         __hip_atomic_store(&a.h->exit_code, (ew & 2u) ? 2u : 1u, __ATOMIC_RELAXED, SC_SYSTEM);
       }
       return;
     }
-  }
-}
-
-// ---------------------------------------------------------------------------
-// worker (every workgroup but 0)
-// ---------------------------------------------------------------------------
-constexpr uint64_t kStopGraceTicks = 10000000ull;   // 100 ms (100 MHz clock): how long a worker still waits for a dependency once the stop flag is up
-
-struct WorkShared {
-  Record rec;
-  uint64_t unit, entry;
-  int32_t exit_flag;
-  int32_t dep_status;              // 0, or the status a task whose dependency wait ran out completes with
-  float red[kScratchFloats];
-};
-
-DEV void run_worker(const WorkerArgs& a, WorkShared* s) {
-  const uint32_t tid = threadIdx.x;
-  const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
-  uint64_t w_units = 0, w_wait = 0, w_fetch = 0, w_dep = 0, w_exec = 0, w_done = 0;
-  const bool timing = a.timing != 0, tracing = a.trace != nullptr;
-  const uint64_t w_start = clock_if(timing);
-  while (true) {
-    const uint64_t c0 = clock_if(timing);
-    // ---- claim one work unit (elected lane, atomic fetch-add) ----
-    if (tid == 0) {
-      const uint64_t g = __hip_atomic_fetch_add(&a.d->claim, 1ull, __ATOMIC_RELAXED, SC_AGENT);
-      const uint64_t* up = &a.units[g & a.unit_mask];
-      const uint64_t want = unit_stamp(g, a.unit_shift);
-      int32_t ex = 0;
-      uint32_t polls = 0, yield_every = 0;
-      uint64_t u;
-      // Poll the claimed entry itself (its stamp is the ready flag): one load per poll, and every
-      // waiting workgroup polls a different address.
-      while (((u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM)) >> 46) != want) {
-        ++polls;
-        if ((polls & 31u) == 0) {
-          if (__hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) {
-            order_loads();                             // every unit was stored before the stop flag
-            u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM);
-            if ((u >> 46) != want) ex = 1;
-            break;
-          }
-          yield_every = __hip_atomic_load(&a.d->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
-        }
-        // polling policy (paper Section 4.1): short back-off while spinning, longer
-        // pauses every yield_every-th empty poll when the host asked for them
-        if (yield_every != 0 && (polls % yield_every) == 0) { for (int k = 0; k < 16; ++k) __builtin_amdgcn_s_sleep(127); }
-        else if (polls < 64) __builtin_amdgcn_s_sleep(1);
-        else __builtin_amdgcn_s_sleep(8);
-      }
-      order_loads();
-      s->exit_flag = ex;
-      s->unit = u;
-    }
-    __syncthreads();
-    if (s->exit_flag) {
-      if (tid == 0) {
-        uint64_t* st = a.d->stat;
-        __hip_atomic_fetch_add(&st[ST_WORK_UNITS], w_units, __ATOMIC_RELAXED, SC_AGENT);
-        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_WAIT], w_wait, __ATOMIC_RELAXED, SC_AGENT);
-        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_FETCH], w_fetch, __ATOMIC_RELAXED, SC_AGENT);
-        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_DEP], w_dep, __ATOMIC_RELAXED, SC_AGENT);
-        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_EXEC], w_exec, __ATOMIC_RELAXED, SC_AGENT);
-        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_COMPLETE], w_done, __ATOMIC_RELAXED, SC_AGENT);
-        __hip_atomic_fetch_add(&st[ST_WORK_TICKS_TOTAL], c0 - w_start, __ATOMIC_RELAXED, SC_AGENT);
-      }
-      return;
-    }
-    const uint64_t c1 = clock_if(timing || tracing);
-    // the unit is the same for the whole workgroup: keep its fields in scalar registers
-    const uint32_t unit_lo = uni((uint32_t)s->unit), unit_hi = uni((uint32_t)(s->unit >> 32));
-    const uint64_t unit = ((uint64_t)unit_hi << 32) | unit_lo;
-    const uint32_t chunk = (uint32_t)(unit & 0xfffffu);
-    const uint32_t slot = (uint32_t)((unit >> 20) & 0xffffu);
-    const uint32_t op = (uint32_t)((unit >> 36) & 0xffu), sel = (uint32_t)((unit >> 44) & 1u);
-    const bool op_valid = ((unit >> 45) & 1u) != 0;
-    // ---- fetch the descriptor (16 lanes x 16 bytes) and the claimed table slot ----
-    if (tid < 16) ((v4i*)&s->rec)[tid] = Mem<POL_COHERENT>::ld16(rd, slot * (uint32_t)sizeof(Record) + tid * 16u);
-    if (tid == 16) s->entry = op_valid ? __hip_atomic_load(&a.dtable[op].slot[sel], __ATOMIC_RELAXED, SC_SYSTEM) : 0ull;
-    __syncthreads();
-    const Record* r = &s->rec;
-    int32_t status = r->status;
-    const uint32_t impl = uni(r->impl);
-    if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
-    const uint64_t c2 = clock_if(timing);
-    // ---- dependencies: earlier tickets named by back-distance ----
-    // What is awaited was published before this unit (the dispatcher sees to that), so the wait ends
-    // when resident workgroups finish work they already hold.  It is bounded all the same (the
-    // context's wait limit; a short grace once the stop flag is up): a task that runs into the bound
-    // completes with GPUOS_E_TIMEOUT without executing, and the kernel always leaves.
-    if ((r->dep[0] | r->dep[1] | r->dep[2]) != 0 && !(r->rflags & RF_DEPS_RESOLVED)) {
-      if (tid == 0) {
-        const uint64_t ticket = r->ticket;
-        int32_t gave_up = 0;
-        uint64_t t_begin = 0;
-        uint32_t spins = 0;
-        for (int k = 0; k < 3 && !gave_up; ++k) {
-          const uint32_t back = r->dep[k];
-          if (back == 0 || back > ticket) continue;
-          const uint64_t want = ticket - back + 1;
-          const uint64_t* w = &a.st[(ticket - back) & a.cap_mask].done_seq;
-          while (__hip_atomic_load(w, __ATOMIC_RELAXED, SC_SYSTEM) < want) {
-            __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 31u) == 0) {
-              const uint64_t now = wall_clock64();
-              if (t_begin == 0) t_begin = now;
-              uint64_t limit = a.dep_wait_ticks;
-              if (limit > kStopGraceTicks && __hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) limit = kStopGraceTicks;
-              if (now - t_begin > limit) { gave_up = GPUOS_E_TIMEOUT; break; }
-            }
-          }
-        }
-        order_loads();
-        s->dep_status = gave_up;
-      }
-      __syncthreads();
-      if (status == GPUOS_OK && s->dep_status != 0) status = s->dep_status;
-    }
-    const uint64_t c3 = clock_if(timing);
-    if (tracing && tid == 0 && chunk == 0 && r->nchunks > 1)
-      __hip_atomic_store(&a.st[slot].t_first, c1, __ATOMIC_RELAXED, SC_SYSTEM);   // in memory before this chunk is counted
-    // ---- execute ----
-    if (status == GPUOS_OK) status = exec_chunk<POL_COHERENT>(r, impl, chunk, s->red, a.progs);
-    drain_stores();                   // this wave's (write-through) stores have reached memory
-    __syncthreads();                  // ... and so have the other three waves'
-    const uint64_t c4 = clock_if(timing || tracing);
-    // ---- complete ----
-    if (tid == 0) {
-      const uint32_t nchunks = r->nchunks;
-      bool last = true;
-      if (nchunks > 1) {
-        const uint32_t prev = __hip_atomic_fetch_add(&a.st[slot].chunks_done, 1u, __ATOMIC_RELAXED, SC_AGENT);
-        last = (prev + 1 == nchunks);
-        if (last) __hip_atomic_store(&a.st[slot].chunks_done, 0u, __ATOMIC_RELAXED, SC_SYSTEM);
-      }
-      if (last) {
-        const uint64_t ticket = r->ticket;
-        if (tracing) {
-          // the tracepoint lands before the completion word that lets the host read it
-          const uint64_t origin = __hip_atomic_load(&a.h->clock_origin, __ATOMIC_RELAXED, SC_SYSTEM);
-          const uint64_t t_start = nchunks > 1 ? __hip_atomic_load(&a.st[slot].t_first, __ATOMIC_RELAXED, SC_SYSTEM) : c1;
-          TraceRec* tr = &a.trace[ticket & a.trace_mask];
-          const uint64_t tdq = ((uint64_t)r->t_dequeue[1] << 32) | r->t_dequeue[0];
-          __hip_atomic_store(&tr->t_dequeue, tdq - origin, __ATOMIC_RELAXED, SC_SYSTEM);
-          __hip_atomic_store(&tr->t_start, t_start - origin, __ATOMIC_RELAXED, SC_SYSTEM);
-          // The clock is read here, once this workgroup knows it finished the task: the time taken
-          // right after its own chunk (c4) can lie before the start of chunk 0 when this workgroup's
-          // count arrives late (seen once in a few thousand multi-chunk tasks).
-          const uint64_t t_done = nchunks > 1 ? wall_clock64() : c4;
-          __hip_atomic_store(&tr->t_done, t_done - origin, __ATOMIC_RELAXED, SC_SYSTEM);
-          const uint64_t w4 = (uint64_t)r->version | ((uint64_t)r->op_id << 32) | ((uint64_t)(uint8_t)(int8_t)status << 48);
-          __hip_atomic_store((uint64_t*)&tr->op_version, w4, __ATOMIC_RELAXED, SC_SYSTEM);
-          const uint64_t w5 = (uint64_t)nchunks | ((uint64_t)blockIdx.x << 32);
-          __hip_atomic_store((uint64_t*)&tr->nchunks, w5, __ATOMIC_RELAXED, SC_SYSTEM);
-          __hip_atomic_store(&tr->ticket, ticket, __ATOMIC_RELAXED, SC_SYSTEM);
-          drain_stores();
-        }
-        __hip_atomic_store(&a.st[slot].done_seq, ticket + 1, __ATOMIC_RELAXED, SC_SYSTEM);
-        __hip_atomic_store(&a.hcomp[slot], pack_completion(ticket, status, r->version), __ATOMIC_RELAXED, SC_SYSTEM);
-        __hip_atomic_fetch_add(&a.d->done_count, 1ull, __ATOMIC_RELAXED, SC_AGENT);
-      }
-    }
-    __syncthreads();                  // the descriptor in LDS may be overwritten after this
-    const uint64_t c5 = clock_if(timing);
-    w_units += 1;
-    if (timing) { w_wait += c1 - c0; w_fetch += c2 - c1; w_dep += c3 - c2; w_exec += c4 - c3; w_done += c5 - c4; }
   }
 }
 
@@ -2282,7 +629,7 @@ union KernelShared {
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) gpuos_worker_kernel(WorkerArgs a) {
   __shared__ KernelShared sh;
   if (blockIdx.x == 0) run_dispatcher(a, &sh.disp);
-  else run_worker(a, &sh.work);
+  else run_worker<0, BuiltinExec>(a, &sh.work);
 }
 
 // one ordinary launch per task: block b executes chunk b

@@ -28,6 +28,12 @@
 
 using namespace gpuos;
 
+namespace gpuos {        // csrc/gpuos_jit.cpp: operator programs -> code object of the run-time worker kernel
+bool jit_compiler_available();
+int jit_build(const ProgramImage* imgs, uint32_t n, std::vector<char>* code, std::string* err, double* compile_ms, bool* cache_hit);
+void jit_cache_counts(uint64_t* compiles, uint64_t* hits);
+}
+
 namespace {
 
 thread_local std::string g_hip_error;
@@ -530,6 +536,22 @@ struct gpuos_ctx {
   std::vector<gpuos_audit_record> audit;  // latest kAuditKeep changes of the operator table, a ring once full (under prod_mu)
   uint64_t audit_total = 0;
   bool static_mode = false;               // made by gpuos_init_static: the library owns neither the memory nor the stream
+  // operator programs as native code: a second resident worker kernel compiled at run time
+  ProgramImage prog_img[GPUOS_MAX_PROGRAMS] = {};   // host copy of what the device-visible table holds
+  bool jit_enabled = false;               // this context may use the run-time compiler
+  bool jit_failed = false;                // ... and has not given up on it
+  std::mutex jit_mu;                      // one change of generation at a time (taken before prod_mu, never after)
+  uint64_t* units_j = nullptr;            // the second work-unit ring
+  hipStream_t jit_stream = nullptr;
+  hipModule_t jit_mod = nullptr;
+  hipFunction_t jit_fn = nullptr;
+  uint32_t jit_gen = 0;                   // generation of the loaded module (0: none)
+  uint32_t jit_n = 0;                     // programs it holds as native code
+  uint32_t jit_grid = 0;
+  bool jit_running = false;               // its kernel is resident
+  uint64_t jit_builds = 0, jit_cache_hits = 0;
+  double jit_last_ms = 0.0;
+  std::string jit_error;                  // why the native path was given up (jit_failed)
   uint64_t prog_hash[GPUOS_MAX_PROGRAMS] = {};
   uint32_t prog_len[GPUOS_MAX_PROGRAMS] = {};
   WorkerArgs wargs{};                     // what the worker was launched with (gpuos_start_worker launches it again)
@@ -633,6 +655,10 @@ void bump_epoch(gpuos_ctx* c, uint32_t op_hint, bool stop) {
 
 void free_all(gpuos_ctx* c) {
   if (c->static_mode) return;               // the caller's host block and stream, the library's device array: nothing to free
+  if (c->jit_mod) (void)hipModuleUnload(c->jit_mod);
+  if (c->units_j) (void)hipFree(c->units_j);
+  if (c->jit_stream) (void)hipStreamDestroy(c->jit_stream);
+  c->jit_mod = nullptr; c->jit_fn = nullptr; c->units_j = nullptr; c->jit_stream = nullptr;
   if (c->h) (void)hipHostFree(c->h);
   if (c->hcomp) (void)hipHostFree(c->hcomp);
   if (c->trace) (void)hipHostFree(c->trace);
@@ -663,6 +689,19 @@ void free_all(gpuos_ctx* c) {
   c->ev_start = nullptr; c->ev_stop = nullptr; c->stream = nullptr;
 }
 
+// Mark programs [0, jit_n) as served natively (v = 1) or interpreted (v = 0) in the device-visible
+// table; with `announce` the dispatcher is told to read the flags again.  Caller holds jit_mu or is the
+// only thread (stop / start).
+void jit_set_native(gpuos_ctx* c, uint32_t v, bool announce) {
+  std::lock_guard<SpinMutex> lk(c->prod_mu);
+  for (uint32_t k = 0; k < c->jit_n && k < GPUOS_MAX_PROGRAMS; ++k) {
+    c->prog_img[k].native = v;
+    __atomic_store_n(&c->progs[k].native, v, __ATOMIC_RELAXED);
+  }
+  if (c->push) _mm_sfence();
+  if (announce) bump_epoch(c, 0xff, false);
+}
+
 int stop_worker(gpuos_ctx* c) {
   if (c->worker_joined) return GPUOS_OK;
   int rc = GPUOS_OK;
@@ -686,12 +725,26 @@ int stop_worker(gpuos_ctx* c) {
     }
     if (q == hipErrorNotReady) rc = GPUOS_E_TIMEOUT;
     else if (q != hipSuccess) { hip_ok(q, "worker kernel"); rc = GPUOS_E_HIP; }
+    bool jit_left = true;
+    if (c->jit_running) {                                     // the run-time kernel's workers obey the same stop flag
+      hipError_t qj;
+      while ((qj = hipStreamQuery(c->jit_stream)) == hipErrorNotReady && now_ns() - t0 <= c->wait_ns)
+        std::this_thread::sleep_for(std::chrono::microseconds(20));
+      jit_left = qj != hipErrorNotReady;
+      if (!jit_left) rc = GPUOS_E_TIMEOUT;
+      else if (qj != hipSuccess && rc == GPUOS_OK) { hip_ok(qj, "run-time worker kernel"); rc = GPUOS_E_HIP; }
+      if (jit_left) {
+        c->jit_running = false;
+        jit_set_native(c, 0, false);                          // a restarted worker interprets until the run-time kernel is back
+      }
+    }
     c->worker_running = false;
-    c->worker_joined = q != hipErrorNotReady;                 // the kernel has left the GPU (whatever the drain said)
+    c->worker_joined = q != hipErrorNotReady && jit_left;     // the kernels have left the GPU (whatever the drain said)
   } else if (c->stream) {
-    // an earlier stop ran into its time limit with the kernel still resident: look again
-    if (hipStreamQuery(c->stream) == hipErrorNotReady) rc = GPUOS_E_TIMEOUT;
-    else c->worker_joined = true;
+    // an earlier stop ran into its time limit with a kernel still resident: look again
+    if (hipStreamQuery(c->stream) == hipErrorNotReady || (c->jit_running && hipStreamQuery(c->jit_stream) == hipErrorNotReady))
+      rc = GPUOS_E_TIMEOUT;
+    else { c->worker_joined = true; c->jit_running = false; }
   }
   if (c->harvester_run.load()) {
     c->harvester_run.store(false, std::memory_order_release);
@@ -733,10 +786,20 @@ int launch_first_worker(gpuos_ctx* c, int compute_units, size_t n_units) {
   c->workgroups = (uint32_t)compute_units * per_cu;
   if (c->workgroups < 2) c->workgroups = 2;
   c->cfg.workgroups_per_cu = per_cu;
+  if (c->jit_enabled) {
+    // the run-time kernel is built like the worker (same registers per lane, less local memory):
+    // its workgroups take the places per compute unit that the worker leaves free
+    uint32_t jw = cfg.jit_workgroups_per_cu ? cfg.jit_workgroups_per_cu : 1u;
+    if (per_cu + jw > (uint32_t)occ) jw = (uint32_t)occ > per_cu ? (uint32_t)occ - per_cu : 0u;
+    c->cfg.jit_workgroups_per_cu = jw;
+    c->jit_grid = (uint32_t)compute_units * jw;
+    if (jw == 0) { c->jit_enabled = false; c->jit_error = "no room beside the worker's workgroups"; }
+  }
 
-  WorkerArgs a;
+  WorkerArgs a{};
   a.h = c->h; a.bell = c->bell; a.hring = c->hring; a.hcomp = c->hcomp; a.htable = c->htable;
   a.d = c->d; a.dring = c->dring; a.units = c->units; a.st = c->st; a.dtable = c->dtable;
+  a.units_j = c->jit_enabled ? c->units_j : nullptr;
   a.cap_mask = c->mask;
   a.unit_mask = (uint32_t)(n_units - 1);
   a.unit_shift = 0;
@@ -802,6 +865,7 @@ void gpuos_default_config(gpuos_config* cfg) {
   cfg->completion_log = 1u << 20;
   cfg->chunk_elems = kChunkElems;
   cfg->push_ring = 2;               // device-memory ring when the BAR allows it
+  cfg->jit_workgroups_per_cu = 1;
 }
 
 int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* user_cfg) {
@@ -818,6 +882,8 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
   cfg.chunk_elems = (cfg.chunk_elems + 1023u) / 1024u * 1024u;
   uint32_t cap = queue_capacity ? queue_capacity : 4096u;
   if (cap < 2 || cap > 65536 || (cap & (cap - 1)) != 0) return GPUOS_E_INVAL;
+  const char* env_jit = std::getenv("GPUOS_JIT");                 // GPUOS_JIT=0: operator programs stay interpreted
+  if (env_jit && env_jit[0] == '0') cfg.jit_mode = 2;
   const char* env_idle = std::getenv("GPUOS_IDLE_EXIT_MS");
   if (env_idle && cfg.idle_exit_ms == 0) cfg.idle_exit_ms = (uint32_t)std::strtoul(env_idle, nullptr, 10);
 
@@ -869,6 +935,13 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       !hip_ok(hipMalloc((void**)&c->st, sizeof(SlotState) * cap), "hipMalloc(slots)") ||
       !hip_ok(hipMalloc((void**)&c->dtable, sizeof(OpSlots) * GPUOS_MAX_OPS), "hipMalloc(table)"))
     return fail(GPUOS_E_HIP);
+  // operator programs as native code: on unless switched off or the run-time compiler is not there
+  c->jit_enabled = cfg.jit_mode != 2 && jit_compiler_available();
+  if (!c->jit_enabled) c->jit_error = cfg.jit_mode == 2 ? "switched off (cfg.jit_mode)" : "the HIP run-time compiler library was not found";
+  if (c->jit_enabled &&
+      (!hip_ok(hipMalloc((void**)&c->units_j, sizeof(uint64_t) * n_units), "hipMalloc(second unit ring)") ||
+       !hip_ok(hipStreamCreateWithFlags(&c->jit_stream, hipStreamNonBlocking), "hipStreamCreateWithFlags")))
+    return fail(GPUOS_E_HIP);
   std::memset(c->h, 0, sizeof(HostCtl));
   std::memset(c->hcomp, 0, sizeof(uint64_t) * cap);
   if (cfg.trace_entries) {
@@ -902,6 +975,7 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       !hip_ok(hipMemsetAsync(c->st, 0, sizeof(SlotState) * cap, c->stream), "hipMemsetAsync") ||
       !hip_ok(hipMemsetAsync(c->units, 0, sizeof(uint64_t) * n_units, c->stream), "hipMemsetAsync") ||
       !hip_ok(hipMemsetAsync(c->dtable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS, c->stream), "hipMemsetAsync") ||
+      (c->units_j && !hip_ok(hipMemsetAsync(c->units_j, 0, sizeof(uint64_t) * n_units, c->stream), "hipMemsetAsync")) ||
       !hip_ok(hipStreamSynchronize(c->stream), "hipStreamSynchronize"))
     return fail(GPUOS_E_HIP);
 
@@ -1048,6 +1122,130 @@ int ctx_impl_arity(const gpuos_ctx* c, uint32_t impl) {
 }
 }  // namespace
 
+namespace {
+
+void jit_give_up(gpuos_ctx* c, const std::string& why) {
+  c->jit_failed = true;
+  c->jit_error = why;
+  jit_set_native(c, 0, c->worker_running && !worker_exited(c));      // everything is interpreted from here on
+}
+
+// Launch the loaded module's kernel (generation c->jit_gen) and wait until its first workgroup runs.
+int jit_launch(gpuos_ctx* c) {
+  WorkerArgs a = c->wargs;
+  uint32_t gen = c->jit_gen;
+  void* params[2] = {&a, &gen};
+  __atomic_store_n(&c->h->jit_alive, 0u, __ATOMIC_RELEASE);
+  // after whatever the worker's stream did before the worker started (the fix-up of a restart)
+  if (c->ev_start) HIP_TRY(hipStreamWaitEvent(c->jit_stream, c->ev_start, 0));
+  HIP_TRY(hipModuleLaunchKernel(c->jit_fn, c->jit_grid, 1, 1, kThreads, 1, 1, 0, c->jit_stream, params, nullptr));
+  c->jit_running = true;
+  const uint64_t t0 = now_ns();
+  const uint64_t limit = c->wait_ns < 5000000000ull ? c->wait_ns : 5000000000ull;
+  while (__atomic_load_n(&c->h->jit_alive, __ATOMIC_ACQUIRE) != gen) {
+    if (now_ns() - t0 > limit) return GPUOS_E_TIMEOUT;               // no compute unit had room for it
+    if (hipStreamQuery(c->jit_stream) != hipErrorNotReady) { c->jit_running = false; return GPUOS_E_DEAD; }
+    __builtin_ia32_pause();
+  }
+  return GPUOS_OK;
+}
+
+// Make the running kernel of generation c->jit_gen leave while the worker runs on: take its programs
+// off the second ring, wait until everything that may have been routed there has completed, ask for
+// the next generation, join.  Caller holds jit_mu.
+int jit_retire(gpuos_ctx* c) {
+  uint64_t head0;
+  {
+    jit_set_native(c, 0, true);
+    std::lock_guard<SpinMutex> lk(c->prod_mu);
+    head0 = c->head.load(std::memory_order_relaxed);
+    doorbell(c);
+  }
+  // tickets from head0 on were published after the flags went down and are interpreted; earlier ones
+  // may sit on the second ring
+  const int rc = wait_floor(c, head0, c->wait_ns);
+  if (rc != GPUOS_OK) return rc;
+  {
+    std::lock_guard<SpinMutex> lk(c->prod_mu);
+    __atomic_store_n(&c->bell->jit_gen, c->jit_gen + 1, __ATOMIC_RELEASE);
+    bump_epoch(c, 0xff, false);
+  }
+  const uint64_t t0 = now_ns();
+  hipError_t q;
+  while ((q = hipStreamQuery(c->jit_stream)) == hipErrorNotReady) {
+    if (now_ns() - t0 > c->wait_ns) return GPUOS_E_TIMEOUT;
+    std::this_thread::sleep_for(std::chrono::microseconds(20));
+  }
+  c->jit_running = false;
+  if (q != hipSuccess) { hip_ok(q, "run-time worker kernel"); return GPUOS_E_HIP; }
+  return GPUOS_OK;
+}
+
+// Bring the native code up to date with the programs defined so far: compile (or take from the
+// cache) a worker kernel that holds all of them, retire the one that is running, launch the new one,
+// route the programs' tasks to it.  Failures are not errors of the caller's: the programs stay
+// interpreted.
+void jit_install(gpuos_ctx* c) {
+  std::lock_guard<std::mutex> jl(c->jit_mu);
+  if (!c->jit_enabled || c->jit_failed) return;
+  uint32_t n;
+  std::vector<ProgramImage> imgs;
+  {
+    std::lock_guard<SpinMutex> lk(c->prod_mu);
+    n = c->n_progs;
+    imgs.assign(c->prog_img, c->prog_img + n);
+  }
+  if (n == 0 || (c->jit_mod && n == c->jit_n)) return;
+  std::vector<char> code;
+  std::string err;
+  bool hit = false;
+  double ms = 0.0;
+  if (jit_build(imgs.data(), n, &code, &err, &ms, &hit) != 0) { jit_give_up(c, err); return; }
+  if (hit) ++c->jit_cache_hits; else { ++c->jit_builds; c->jit_last_ms = ms; }
+  if (hipSetDevice(c->device) != hipSuccess) { jit_give_up(c, "hipSetDevice"); return; }
+  const bool live = c->worker_running && !worker_exited(c);
+  if (c->jit_running) {
+    if (!live) { jit_give_up(c, "the worker left while its run-time kernel was resident"); return; }
+    const int rc = jit_retire(c);
+    if (rc != GPUOS_OK) { jit_give_up(c, std::string("retiring the previous run-time kernel: ") + gpuos_strerror(rc)); return; }
+  }
+  if (c->jit_mod) { (void)hipModuleUnload(c->jit_mod); c->jit_mod = nullptr; c->jit_fn = nullptr; }
+  hipModule_t mod = nullptr;
+  hipFunction_t fn = nullptr;
+  if (hipModuleLoadData(&mod, code.data()) != hipSuccess || hipModuleGetFunction(&fn, mod, "gpuos_native_worker") != hipSuccess) {
+    if (mod) (void)hipModuleUnload(mod);
+    jit_give_up(c, "loading the compiled worker kernel failed");
+    return;
+  }
+  c->jit_mod = mod;
+  c->jit_fn = fn;
+  c->jit_gen += 1;
+  c->jit_n = 0;                                          // (nothing is native until the kernel runs)
+  {
+    std::lock_guard<SpinMutex> lk(c->prod_mu);
+    __atomic_store_n(&c->bell->jit_gen, c->jit_gen, __ATOMIC_RELEASE);
+    if (c->push) _mm_sfence();
+  }
+  if (live) {
+    const int rc = jit_launch(c);
+    if (rc != GPUOS_OK) {
+      // should it start after all it must leave at once: ask for a generation it is not
+      std::lock_guard<SpinMutex> lk(c->prod_mu);
+      __atomic_store_n(&c->bell->jit_gen, c->jit_gen + 1, __ATOMIC_RELEASE);
+      bump_epoch(c, 0xff, false);
+      c->jit_failed = true;
+      c->jit_error = std::string("the run-time worker kernel did not start: ") + gpuos_strerror(rc);
+      return;
+    }
+    c->jit_n = n;
+    jit_set_native(c, 1, true);
+  } else {
+    c->jit_n = n;                                        // gpuos_start_worker launches it and raises the flags
+  }
+}
+
+}  // namespace
+
 int gpuos_define_program(gpuos_ctx* c, const gpuos_instr* code, uint32_t n_instr, uint32_t n_inputs, uint32_t* out_impl_id) {
   if (!c || !code || !out_impl_id) return GPUOS_E_INVAL;
   if (n_instr < 1 || n_instr > GPUOS_PROGRAM_MAX_INSTR || n_inputs < 1 || n_inputs > GPUOS_MAX_INPUTS) return GPUOS_E_INVAL;
@@ -1061,32 +1259,56 @@ int gpuos_define_program(gpuos_ctx* c, const gpuos_instr* code, uint32_t n_instr
     std::memcpy(&img.code[2 * i + 1], &in.imm, 4);
   }
   img.n_instr = n_instr; img.n_inputs = n_inputs; img.ready = kProgramReady;
-  std::lock_guard<SpinMutex> lk(c->prod_mu);
-  if (!c->worker_running && !c->worker_joined) return GPUOS_E_DEAD;
-  if (c->n_progs >= GPUOS_MAX_PROGRAMS) return GPUOS_E_FULL;
-  const uint32_t k = c->n_progs;
-  // the code first, the header (with the ready word) after it: the device never runs half a program
-  std::memcpy(c->progs[k].code, img.code, sizeof(img.code));
-  if (c->push) _mm_sfence();
-  std::atomic_thread_fence(std::memory_order_release);
-  std::memcpy(&c->progs[k], &img, 16);
-  if (c->push) _mm_sfence();
-  std::atomic_thread_fence(std::memory_order_release);
-  c->prog_arity[k] = (uint8_t)n_inputs;
-  c->prog_len[k] = n_instr;
-  uint64_t hsh = 0xcbf29ce484222325ull;                            // FNV-1a over the caller's instruction bytes
-  for (size_t b = 0; b < (size_t)n_instr * sizeof(gpuos_instr); ++b)
-    hsh = (hsh ^ reinterpret_cast<const unsigned char*>(code)[b]) * 0x100000001b3ull;
-  c->prog_hash[k] = hsh;
-  c->n_progs = k + 1;
-  *out_impl_id = GPUOS_IMPL_PROGRAM_BASE + k;
-  audit(c, GPUOS_AUDIT_DEFINE_PROGRAM, 0, GPUOS_IMPL_PROGRAM_BASE + k, 0);
+  {
+    std::lock_guard<SpinMutex> lk(c->prod_mu);
+    if (!c->worker_running && !c->worker_joined) return GPUOS_E_DEAD;
+    if (c->n_progs >= GPUOS_MAX_PROGRAMS) return GPUOS_E_FULL;
+    const uint32_t k = c->n_progs;
+    // the code first, the header (with the ready word) after it: the device never runs half a program
+    std::memcpy(c->progs[k].code, img.code, sizeof(img.code));
+    if (c->push) _mm_sfence();
+    std::atomic_thread_fence(std::memory_order_release);
+    std::memcpy(&c->progs[k], &img, 16);
+    if (c->push) _mm_sfence();
+    std::atomic_thread_fence(std::memory_order_release);
+    c->prog_img[k] = img;
+    c->prog_arity[k] = (uint8_t)n_inputs;
+    c->prog_len[k] = n_instr;
+    uint64_t hsh = 0xcbf29ce484222325ull;                            // FNV-1a over the caller's instruction bytes
+    for (size_t b = 0; b < (size_t)n_instr * sizeof(gpuos_instr); ++b)
+      hsh = (hsh ^ reinterpret_cast<const unsigned char*>(code)[b]) * 0x100000001b3ull;
+    c->prog_hash[k] = hsh;
+    c->n_progs = k + 1;
+    *out_impl_id = GPUOS_IMPL_PROGRAM_BASE + k;
+    audit(c, GPUOS_AUDIT_DEFINE_PROGRAM, 0, GPUOS_IMPL_PROGRAM_BASE + k, 0);
+  }
+  // The program is usable (interpreted) from here.  Its native code is built when an operator is
+  // first bound to it (gpuos_register_op / gpuos_swap_op), one kernel for all programs defined by
+  // then; with cfg.jit_mode = 1, here.
+  if (c->cfg.jit_mode == 1) jit_install(c);
   return GPUOS_OK;
 }
+
+namespace {
+// Binding an operator to a program whose native code is not live yet: compile, in the calling thread
+// and outside the producers' lock, a worker kernel for all programs defined so far, and bring it up
+// (the program is interpreted until then, and for good if this fails).
+void jit_before_bind(gpuos_ctx* c, uint32_t impl_id) {
+  if (impl_id < GPUOS_IMPL_PROGRAM_BASE || !c->jit_enabled || c->jit_failed) return;
+  bool need;
+  {
+    std::lock_guard<SpinMutex> lk(c->prod_mu);
+    const uint32_t k = impl_id - GPUOS_IMPL_PROGRAM_BASE;
+    need = k < c->n_progs && (k >= c->jit_n || !c->jit_mod);
+  }
+  if (need) jit_install(c);
+}
+}  // namespace
 
 int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
   if (impl_id == GPUOS_IMPL_NONE || (impl_id >= GPUOS_IMPL_COUNT && impl_id < GPUOS_IMPL_PROGRAM_BASE)) return GPUOS_E_BADOP;
+  jit_before_bind(c, impl_id);
   std::lock_guard<SpinMutex> lk(c->prod_mu);
   if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   if (c->ops[op_id].version != 0) return GPUOS_E_INVAL;            // already bound: use swap_op
@@ -1106,6 +1328,7 @@ int gpuos_register_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* 
 
 int gpuos_swap_op(gpuos_ctx* c, uint32_t op_id, uint32_t impl_id, uint32_t* out_version) {
   if (!c || op_id >= GPUOS_MAX_OPS) return GPUOS_E_INVAL;
+  jit_before_bind(c, impl_id);
   std::lock_guard<SpinMutex> lk(c->prod_mu);
   if (!impl_known(c, impl_id)) return GPUOS_E_BADOP;
   OpInfo& o = c->ops[op_id];
@@ -1326,6 +1549,18 @@ int gpuos_start_worker(gpuos_ctx* c) {
     c->harvester_run.store(true);
     c->harvester = std::thread(harvester_main, c, sched_getcpu());
   }
+  if (c->jit_enabled && !c->jit_failed && c->jit_mod && c->jit_n) {   // the native code of the programs comes back too
+    std::lock_guard<std::mutex> jl(c->jit_mu);
+    const int rc = jit_launch(c);
+    if (rc == GPUOS_OK) jit_set_native(c, 1, true);
+    else {
+      std::lock_guard<SpinMutex> lk(c->prod_mu);
+      __atomic_store_n(&c->bell->jit_gen, c->jit_gen + 1, __ATOMIC_RELEASE);     // should it start after all, it leaves at once
+      bump_epoch(c, 0xff, false);
+      c->jit_failed = true;
+      c->jit_error = std::string("the run-time worker kernel did not start again: ") + gpuos_strerror(rc);
+    }
+  }
   marker(c->cfg.markers != 0, "gpuos: worker launched again at ticket %llu", head);
   return GPUOS_OK;
 }
@@ -1342,6 +1577,30 @@ int gpuos_worker_stats(gpuos_ctx* c, uint64_t out[16]) {
   if (!c->worker_joined) return GPUOS_E_INVAL;
   HIP_TRY(hipSetDevice(c->device));
   HIP_TRY(hipMemcpy(out, c->d->stat, sizeof(uint64_t) * 16, hipMemcpyDeviceToHost));
+  return GPUOS_OK;
+}
+
+int gpuos_native_info(gpuos_ctx* c, uint64_t out[8], char* why, uint32_t why_len) {
+  if (!c || !out) return GPUOS_E_INVAL;
+  std::lock_guard<std::mutex> jl(c->jit_mu);
+  out[0] = (c->jit_enabled && !c->jit_failed && c->jit_running) ? 1u : 0u;
+  out[1] = c->jit_gen;
+  out[2] = out[0] ? c->jit_n : 0u;
+  out[3] = c->jit_builds;
+  out[4] = c->jit_cache_hits;
+  out[5] = 0;
+  out[6] = (uint64_t)(c->jit_last_ms * 1000.0);
+  out[7] = c->jit_grid;
+  if (c->worker_joined && c->d && !c->static_mode) {                    // device counters are read once the kernels have left
+    HIP_TRY(hipSetDevice(c->device));
+    HIP_TRY(hipMemcpy(&out[5], &c->d->jit_units, sizeof(uint64_t), hipMemcpyDeviceToHost));
+    out[0] = (c->jit_enabled && !c->jit_failed && c->jit_mod) ? 1u : 0u;
+    out[2] = out[0] ? c->jit_n : 0u;
+  }
+  if (why && why_len) {
+    std::strncpy(why, c->jit_error.c_str(), why_len - 1);
+    why[why_len - 1] = 0;
+  }
   return GPUOS_OK;
 }
 

@@ -33,7 +33,7 @@ class Config(ctypes.Structure):
                 ("completion_log", ctypes.c_uint32), ("chunk_elems", ctypes.c_uint32),
                 ("push_ring", ctypes.c_uint32), ("trace_entries", ctypes.c_uint32),
                 ("markers", ctypes.c_uint32), ("phase_timers", ctypes.c_uint32), ("dep_wait_us", ctypes.c_uint32),
-                ("reserved", ctypes.c_uint32 * 1)]
+                ("jit_mode", ctypes.c_uint32), ("jit_workgroups_per_cu", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 1)]
 
 
 class QueueState(ctypes.Structure):
@@ -97,6 +97,7 @@ def lib():
         "gpuos_task_plan": (ctypes.c_int, [vp, u32, vp]),
         "gpuos_device_info": (ctypes.c_int, [i32, vp, vp, u32]),
         "gpuos_define_program": (ctypes.c_int, [vp, vp, u32, u32, P(u32)]),
+        "gpuos_native_info": (ctypes.c_int, [vp, vp, vp, u32]),
         "gpuos_submit_from_threads": (ctypes.c_int, [vp, vp, u32, u32, u32, u32, P(ctypes.c_double)]),
         "gpuos_get_trace": (ctypes.c_int, [vp, u64, u32, vp]),
         "gpuos_op_counts": (ctypes.c_int, [vp, vp]),
@@ -118,7 +119,7 @@ def lib():
 EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_init_static", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker", "gpuos_start_worker",
-           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_define_program", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
+           "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_define_program", "gpuos_native_info", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
            "gpuos_trace_origin", "gpuos_kill_op", "gpuos_audit_log", "gpuos_strerror",
            "gpuos_last_hip_error", "gpuos_abi_layout"]
 
@@ -229,6 +230,16 @@ class Runtime:
         _check(lib().gpuos_define_program(self._ctx, code.ctypes.data, len(code), int(n_inputs), ctypes.byref(v)),
                "gpuos_define_program")
         return v.value
+
+    def native_info(self):
+        """gpuos_native_info: whether operator programs are served as native code, and by what."""
+        out = (ctypes.c_uint64 * 8)()
+        why = ctypes.create_string_buffer(512)
+        _check(lib().gpuos_native_info(self._ctx, out, why, 512), "gpuos_native_info")
+        keys = ("native", "generation", "programs", "compiled", "cache_hits", "units", "compile_us", "workgroups")
+        d = {k: int(v) for k, v in zip(keys, out)}
+        d["why"] = why.value.decode()
+        return d
 
     def register_table(self, table, programs=None):
         """Bind every logical op of `table`.  programs: impl id -> (code, n_inputs) for the table's

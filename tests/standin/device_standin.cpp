@@ -208,3 +208,10 @@ hipError_t hipStreamSynchronize(hipStream_t s) {
   return hipSuccess;
 }
 const char* hipGetErrorString(hipError_t) { return "stand-in"; }
+// no code objects here: the host code must fall back to interpreted programs
+hipError_t hipModuleLoadData(hipModule_t*, const void*) { return hipErrorNotSupported; }
+hipError_t hipModuleGetFunction(hipFunction_t*, hipModule_t, const char*) { return hipErrorNotSupported; }
+hipError_t hipModuleUnload(hipModule_t) { return hipSuccess; }
+hipError_t hipModuleLaunchKernel(hipFunction_t, unsigned int, unsigned int, unsigned int, unsigned int, unsigned int, unsigned int,
+                                 unsigned int, hipStream_t, void**, void**) { return hipErrorNotSupported; }
+hipError_t hipStreamWaitEvent(hipStream_t, hipEvent_t, unsigned int) { return hipSuccess; }
