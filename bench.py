@@ -127,28 +127,40 @@ def bench_multi_producer(R, stream, dp, passes=8, **cfg):
 
 
 def bench_program(R, s5, dp5, impl5, n_tasks=1500):
-    """The ADD tasks of the bandwidth stream with ADD bound to the built-in implementation and to a
-    one-instruction program (interpreted by the resident kernel): what the interpreter costs when
-    the operator is bound by memory; and the same for a six-instruction program."""
+    """The ADD tasks of the bandwidth stream with ADD bound to the built-in implementation, to a
+    one-instruction program and to a six-instruction program, each program served as native code
+    (compiled at run time into the second resident worker kernel) and interpreted by the resident
+    kernel: what an operator added at run time costs when it is bound by memory.  GB/s by the wall
+    time of submit + wait (the kernels' lifetimes also hold the run-time compilation).  The native legs
+    run with the default split (3 + 1 workgroups per compute unit) and with 2 + 2."""
     from paper_2604_17861_amd import streams as S
     idx = np.nonzero(impl5 == S.IMPL["ADD"])[0][:n_tasks]
     sub = dp5.tasks[idx].copy()
     sub["dep"] = 0
     nbytes = int(R.task_bytes(dp5.tasks[idx], impl5[idx]).sum())
     out = {}
-    progs = {"builtin_add": None, "program_add_1_instr": S.program(("ADD", 0, 0, 1)),
-             "program_6_instr": S.program(("SUB", 4, 0, 1), ("MUL", 4, 4, 3), ("ABS", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5),
-                                          ("DIV", 0, 0, 4))}
-    for label, code in progs.items():
-        with R.Runtime(0, idle_exit_ms=60000, **KNOBS) as rt:
+    one = S.program(("ADD", 0, 0, 1))
+    six = S.program(("SUB", 4, 0, 1), ("MUL", 4, 4, 3), ("ABS", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5), ("DIV", 0, 0, 4))
+    legs = [("builtin_add_gbps", None, {}), ("program_add_1_instr_gbps", one, {}), ("program_6_instr_gbps", six, {}),
+            ("builtin_add_2wg_gbps", None, dict(workgroups_per_cu=2)),
+            ("program_6_instr_2plus2wg_gbps", six, dict(workgroups_per_cu=2, jit_workgroups_per_cu=2)),
+            ("program_add_1_instr_interpreted_gbps", one, dict(jit_mode=2)), ("program_6_instr_interpreted_gbps", six, dict(jit_mode=2))]
+    for label, code, cfg in legs:
+        with R.Runtime(0, idle_exit_ms=60000, **{**KNOBS, **cfg}) as rt:
             table = dict(s5.table)
             if code is not None:
                 table[S.OP["ADD"]] = rt.define_program(code, 2)
             rt.register_table(table)
+            native = rt.native_info()
+            if code is not None and not cfg.get("jit_mode"):
+                out["native_path"] = dict(live=native["native"], workgroups=native["workgroups"], why=native["why"],
+                                          last_compile_ms=native["compile_us"] / 1e3)
+            rt.submit_from_threads(sub[:128], 1, 64, 1)        # warm-up: both kernels have run once
+            rt.wait()
+            t0 = time.perf_counter()
             rt.submit_from_threads(sub, 1, 64, 1)
             rt.wait()
-            rt.stop_worker()
-            out[label + "_gbps"] = nbytes / rt.worker_elapsed_ms() / 1e6
+            out[label] = nbytes / (time.perf_counter() - t0) / 1e9
     return out
 
 

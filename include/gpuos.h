@@ -130,10 +130,11 @@ enum gpuos_impl {
  * The paper injects new operators into the running kernel by compiling device
  * code at run time and publishing its address through the dual-slot table
  * (Sections 1.2, 4.1).  Here a new ELEMENTWISE operator is given as a short
- * program that the resident kernel interprets (calls into code objects loaded
- * after the kernel started are not a documented facility of this platform, and
- * elementwise work is bound by memory, not by the interpreter).  The rest of
- * the protocol is the paper's: gpuos_define_program stores the program in a
+ * program.  The resident kernel can interpret it, and the library compiles it
+ * at run time into native code that a second resident kernel executes (see
+ * gpuos_native_info below); a kernel that is already running cannot call into
+ * a code object loaded later, hence the second kernel.  The rest of the
+ * protocol is the paper's: gpuos_define_program stores the program in a
  * device-visible table and returns an implementation id; gpuos_register_op /
  * gpuos_swap_op bind a logical operator to it through the inactive slot and
  * the version flip, without stopping the worker.
