@@ -29,7 +29,7 @@ def test_abi_layout_agrees_between_library_generator_and_oracle():
     lay = R.abi_layout()
     assert np.array_equal(lay, oracle.abi_layout())
     assert lay[0] == S.TASK_DT.itemsize and lay[7] == S.COMPLETION_DT.itemsize
-    assert ctypes.sizeof(R.Config) == 64 and ctypes.sizeof(R.QueueState) == 56
+    assert ctypes.sizeof(R.Config) == 72 and ctypes.sizeof(R.QueueState) == 56
 
 
 def test_strerror_and_statuses():
