@@ -544,7 +544,8 @@ int gpuos_audit_log(gpuos_ctx* ctx, uint64_t first, uint32_t n, gpuos_audit_reco
  * with row-vector / per-row-scalar operands, 3 generic strided walk,
  * 4 contiguous-row reduction, 5 generic reduction, 6 LDS-tiled transposed
  * gather, 7 row operation with rows in registers, 8 row operation over any
- * strides),
+ * strides, 9 contiguous output with strided / broadcast / mixed-dtype inputs
+ * gathered through LDS),
  * out[1] = work units (chunks) the task is split into, out[2] = size of one
  * unit in the path's own unit (elements, rows or 32 x 32 tiles), out[3] =
  * dims left after merging adjacent dims.  For tests and for sizing. */

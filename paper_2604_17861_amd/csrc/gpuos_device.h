@@ -55,6 +55,11 @@ template <int POL> struct Mem {
   static constexpr int AUX = POL == POL_COHERENT ? 19 : 2;     // sc0|sc1|nt  or  nt
   static DEV v4i ld16(rsrc_t r, uint32_t off) { return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, AUX); }
   static DEV void st16(rsrc_t r, uint32_t off, v4i q) { __builtin_amdgcn_raw_buffer_store_b128(q, r, (int)off, 0, AUX); }
+  static DEV void st8(rsrc_t r, uint32_t off, uint32_t w0, uint32_t w1) {
+    typedef int v2i __attribute__((ext_vector_type(2)));
+    const v2i q = {(int)w0, (int)w1};
+    __builtin_amdgcn_raw_buffer_store_b64(q, r, (int)off, 0, AUX);
+  }
   static DEV uint32_t ld4(const void* p, uint32_t i) {
     if (POL == POL_COHERENT) return __hip_atomic_load((const uint32_t*)p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     return ((const uint32_t*)p)[i];
@@ -400,7 +405,8 @@ PATHFN void ew_contig_int(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
 // width; each input is a full [R, C] tensor (dtype DT), a row vector [C]
 // broadcast over rows (dtype DT), or one scalar per row (any float dtype).
 // ---------------------------------------------------------------------------
-constexpr uint32_t kScratchFloats = 3200;   // LDS scratch per workgroup (broadcast staging, transpose tiles, reduction partials)
+constexpr uint32_t kScratchFloats = 7168;   // LDS scratch per workgroup (gather staging, transpose tiles, reduction partials): 28 KB,
+                                            // still below what the dispatcher's workgroup needs, so the kernel's allocation does not grow
 
 template <int POL, int IMPL, int DT>
 PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
@@ -550,6 +556,122 @@ PATHFN void ew_tile2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float
       }
     }
     __syncthreads();                  // the tiles are rewritten by the next iteration
+  }
+}
+
+// ---------------------------------------------------------------------------
+// PATH_STAGED: contiguous [B, R, C] output (leading sizes may be 1: a matrix, a flat tensor), every
+// input addressed by three strides of its own (any values, 0 on broadcast dims), any float dtype
+// per operand, any alignment of the inputs: stride-2 slices, row and column vectors whatever C is,
+// small transposes, operands of another dtype.  A round is 1024 consecutive output elements, four
+// per lane.  For each input the workgroup first brings the contiguous span of memory that the
+// round touches into LDS with coalesced 16-byte loads (every line is fetched once, whatever the
+// stride), then each lane gathers its elements from LDS; the results leave as whole vectors.  An
+// input whose span does not fit what is left of the LDS is read element by element for that
+// round instead.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kStageRound = 4u * kThreads;
+
+template <int POL, int IMPL>
+PATHFN void ew_staged(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
+  const Record* r = lds_arg(r_v);
+  const uint32_t begin = uni(begin_v), end = uni(end_v);
+  char* lds = (char*)lds_arg(s_v);
+  using M = Mem<POL>;
+  constexpr int N = Op<IMPL>::N;
+  const uint32_t R = uni(r->size[1]), C = uni(r->size[2]), RC = R * C;
+  const char* p[3];
+  uint32_t dt[3], es[3], sb[3], sr[3], sc[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int kk = k < N ? k : 0;
+    p[k] = uni_ptr(r->ptr[kk]);
+    dt[k] = uni(r->dtype[kk]);
+    es[k] = dt[k] == GPUOS_F32 ? 4u : 2u;
+    sb[k] = uni(r->stride[kk][0]); sr[k] = uni(r->stride[kk][1]); sc[k] = uni(r->stride[kk][2]);
+  }
+  const uint32_t odt = uni(r->dtype[3]), oes = odt == GPUOS_F32 ? 4u : 2u;
+  char* po = (char*)uni_ptr(r->ptr[3]);
+  const rsrc_t ro = make_rsrc(po + (uint64_t)begin * oes, (end - begin) * oes);    // rebased to the chunk: stores past it are dropped
+  const float alpha = r->alpha;
+  const uint32_t tid = threadIdx.x;
+  constexpr uint32_t kLdsBytes = kScratchFloats * 4u;
+  for (uint32_t i0 = begin; i0 < end; i0 += kStageRound) {
+    const uint32_t i1 = (end - i0 < kStageRound) ? end : i0 + kStageRound;
+    // indices of the first and the last element of the round (uniform)
+    const uint32_t ba = i0 / RC, ja = i0 - ba * RC, ra = ja / C, ca = ja - ra * C;
+    const uint32_t bb = (i1 - 1) / RC, jb = (i1 - 1) - bb * RC, rb = jb / C, cb = jb - rb * C;
+    uint32_t lo[3], region[3];
+    bool staged[3];
+    uint32_t used = 0;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      // bounds on the element offsets the round can touch (strides are non-negative): exact up to
+      // the outermost index in which its first and last element differ, everything inside that
+      uint32_t first, last;
+      if (ba != bb) { first = ba * sb[k]; last = bb * sb[k] + (R - 1u) * sr[k] + (C - 1u) * sc[k]; }
+      else if (ra != rb) { first = ba * sb[k] + ra * sr[k]; last = ba * sb[k] + rb * sr[k] + (C - 1u) * sc[k]; }
+      else { first = ba * sb[k] + ra * sr[k] + ca * sc[k]; last = ba * sb[k] + ra * sr[k] + cb * sc[k]; }
+      // the span in whole 16-byte vectors of the address space (the base need not be aligned)
+      const uint64_t a_first = (uint64_t)(__UINTPTR_TYPE__)p[k] + (uint64_t)first * es[k];
+      const uint64_t a_last = (uint64_t)(__UINTPTR_TYPE__)p[k] + (uint64_t)last * es[k] + es[k];
+      const uint64_t v_first = a_first & ~15ull;
+      const uint64_t bytes = ((a_last + 15ull) & ~15ull) - v_first;
+      staged[k] = bytes <= (uint64_t)(kLdsBytes - used);
+      lo[k] = first;
+      region[k] = used;
+      if (staged[k]) {
+        const uint32_t nb = (uint32_t)bytes;
+        const rsrc_t rs = make_rsrc((const void*)(__UINTPTR_TYPE__)v_first, nb);
+        for (uint32_t v = tid; v < nb / 16u; v += kThreads)
+          *(v4i*)(lds + used + v * 16u) = M::ld16(rs, v * 16u);
+        region[k] = used + (uint32_t)(a_first - v_first);          // where element `first` lies inside the staged bytes
+        used += nb;
+      }
+    }
+    __syncthreads();
+    const uint32_t i = i0 + 4u * tid;
+    if (i < i1) {
+      uint32_t b = i / RC;
+      const uint32_t j = i - b * RC;
+      uint32_t row = j / C, col = j - row * C;
+      float x[3][4], o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          x[k][e] = 0.0f;
+          if (k < N && i + e < i1) {
+            const uint32_t off = b * sb[k] + row * sr[k] + col * sc[k];
+            if (staged[k]) {
+              const char* q = lds + region[k] + (off - lo[k]) * es[k];
+              x[k][e] = dt[k] == GPUOS_F32 ? *(const float*)q : (dt[k] == GPUOS_F16 ? h2f(*(const uint16_t*)q) : b2f(*(const uint16_t*)q));
+            } else {
+              x[k][e] = load_rt<POL>(p[k], off, dt[k]);
+            }
+          }
+        }
+        if (++col == C) { col = 0; if (++row == R) { row = 0; ++b; } }
+      }
+      apply_vec<IMPL, 4>(x[0], x[1], x[2], alpha, o);
+      const uint32_t rel = (i - begin) * oes;
+      if (i + 4u <= i1) {
+        if (odt == GPUOS_F32) {
+          v4i q;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) q[e] = __builtin_bit_cast(int, o[e]);
+          M::st16(ro, rel, q);
+        } else {
+          uint32_t w0, w1;
+          if (odt == GPUOS_F16) { w0 = f2h(o[0]) | (f2h(o[1]) << 16); w1 = f2h(o[2]) | (f2h(o[3]) << 16); }
+          else { w0 = f2b(o[0]) | (f2b(o[1]) << 16); w1 = f2b(o[2]) | (f2b(o[3]) << 16); }
+          M::st8(ro, rel, w0, w1);
+        }
+      } else {
+        for (uint32_t e = 0; i + e < i1; ++e) store_rt<POL>(po, i + e, odt, o[e]);      // the chunk's ragged end
+      }
+    }
+    __syncthreads();                  // the staged spans are overwritten by the next round
   }
 }
 
@@ -1465,6 +1587,8 @@ DEV void run_elementwise(const Record* r, uint32_t chunk, float* s_scratch) {
     else ew_row2d<POL, I2, GPUOS_BF16>(r, begin, end, s_scratch);
   } else if (path == PATH_TILE2D) {
     ew_tile2d<POL, IMPL>(r, begin, end, s_scratch);      // begin / end count tiles here
+  } else if (path == PATH_STAGED) {
+    ew_staged<POL, IMPL>(r, begin, end, s_scratch);
   } else {
     ew_generic<POL, IMPL, false>(r, begin, end);
   }
@@ -1557,7 +1681,7 @@ struct WorkShared {
   uint64_t unit, entry;
   int32_t exit_flag;
   int32_t dep_status;              // 0, or the status a task whose dependency wait ran out completes with
-  float red[kScratchFloats];
+  alignas(16) float red[kScratchFloats];   // (16-byte LDS vectors are written into it)
 };
 
 // RING 0: the library's own workers, on the main unit ring, executing through EXEC = the built-in

@@ -27,7 +27,9 @@ enum Path : uint8_t {
                          // gathered through an LDS tile
   PATH_ROW_FUSED = 7,    // row operation (softmax, layer norm): contiguous rows of whole
                          // 16-byte vectors, one dtype, a row lives in one wavefront's registers
-  PATH_ROW_GENERIC = 8   // row operation over any strides / dtypes: three passes over memory
+  PATH_ROW_GENERIC = 8,  // row operation over any strides / dtypes: three passes over memory
+  PATH_STAGED = 9        // contiguous [R, C] output, inputs with any row / column strides (stride-2
+                         // slices, row and column vectors, mixed dtypes): gathered through LDS
 };
 
 enum RecFlag : uint8_t {

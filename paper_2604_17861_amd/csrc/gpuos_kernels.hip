@@ -635,7 +635,7 @@ __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4
 // one ordinary launch per task: block b executes chunk b
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) gpuos_single_task_kernel(Record rec) {
   __shared__ Record s_rec;
-  __shared__ float s_red[kScratchFloats];
+  __shared__ alignas(16) float s_red[kScratchFloats];
   if (threadIdx.x == 0) s_rec = rec;
   __syncthreads();
   exec_chunk<POL_PLAIN>(&s_rec, s_rec.impl, blockIdx.x, s_red, nullptr);   // built-in implementations only

@@ -425,6 +425,29 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
         return GPUOS_OK;
       }
     }
+    // Contiguous output of at most three merged dims whose inputs are strided, broadcast or of another
+    // dtype (stride-2 slices, row and column vectors whatever the row length, small transposes,
+    // mixed precision): gathered through LDS.  COPY between equal dtypes stays on the generic path
+    // (raw bits).
+    if (rec.path == PATH_GENERIC && !all_int && nd <= 3 && aligned16(ops[ar].ptr) && !(impl == GPUOS_IMPL_COPY && same_dt)) {
+      const Operand& out = ops[ar];
+      bool out_contig = true;
+      int64_t want = 1;
+      for (int d = nd - 1; d >= 0; --d) {
+        if (size[d] > 1 && out.stride[d] != want) out_contig = false;
+        want *= size[d];
+      }
+      if (out_contig) {
+        rec.path = PATH_STAGED;
+        rec.ndim = 3;
+        const int lead = 3 - nd;                                   // leading dims of size 1
+        for (int d = 0; d < 3; ++d) {
+          rec.size[d] = d < lead ? 1u : (uint32_t)size[d - lead];
+          for (int k = 0; k < ar; ++k) rec.stride[k][d] = d < lead ? 0u : (uint32_t)ops[k].stride[d - lead];
+          rec.stride[3][d] = d < lead ? 0u : (uint32_t)out.stride[d - lead];
+        }
+      }
+    }
     uint64_t traffic = dtype_size(ops[ar].dtype);
     for (int k = 0; k < ar; ++k) traffic += dtype_size(ops[k].dtype);
     uint64_t base_per = ((uint64_t)chunk_elems * 12 / traffic + 1023) / 1024 * 1024;

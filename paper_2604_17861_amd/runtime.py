@@ -415,7 +415,7 @@ def task_bytes(tasks, impls):
     return out
 
 
-PATHS = ("NOP", "CONTIG", "ROW2D", "GENERIC", "RED_CONTIG", "RED_GENERIC", "TILE2D", "ROW_FUSED", "ROW_GENERIC")
+PATHS = ("NOP", "CONTIG", "ROW2D", "GENERIC", "RED_CONTIG", "RED_GENERIC", "TILE2D", "ROW_FUSED", "ROW_GENERIC", "STAGED")
 
 
 def task_plan(tasks, i, impl):

@@ -486,6 +486,57 @@ def producer_with_dependants(n_consumers=1200, n_links=300):
     return b.stream("producer_with_dependants", batch=64)
 
 
+def staged_gathers():
+    """Contiguous outputs whose inputs are stride-2 / 3 / 4 / 9 slices at every phase of a 16-byte
+    vector, row vectors of odd lengths, column vectors over few rows, batches of small transposes,
+    operands of other dtypes, three gathered operands at once, spans too large for the staging
+    memory (read element by element instead), several chunks with a ragged end, special values: the
+    layouts the LDS-staged gather path takes, all float dtypes in and out."""
+    rng = np.random.default_rng(31)
+    b = Builder()
+    codes = (S.F32, S.F16, S.BF16)
+    def T(shape, code, scale=2.0):
+        v = (rng.standard_normal(shape) * scale).astype(np.float32)
+        flat = v.reshape(-1)
+        if flat.size > 40:
+            flat[: len(special_values())] = special_values()
+        return b.pool(to_dtype(v, code))
+    for code in codes:
+        ocode = codes[(code + 1) % 3]
+        for numel in (5, 1000, 4096, 70001):
+            for stride in (2, 3, 4, 9):
+                src = T(numel * stride + 8, code)
+                for phase in (0, 1, 3, 7):
+                    x = src[phase: phase + numel * stride: stride]
+                    o = b.pool(np.zeros(numel, np_dtype(code if phase != 3 else ocode)))
+                    b.add("RELU" if phase % 2 else "SCALE", o, [x], alpha=-1.5)
+            y2, y3 = T(2 * numel + 3, code), T(3 * numel + 3, ocode)
+            o = b.pool(np.zeros(numel, np_dtype(code)))
+            b.add("FMA", o, [y2[1::2][:numel], y3[2::3][:numel], T(numel, code)])       # two gathered operands and a contiguous one
+            o = b.pool(np.zeros(numel, np_dtype(ocode)))
+            b.add("SUB", o, [T(numel, S.F32), np.broadcast_to(T(1, code), (numel,))])   # a scalar operand, mixed dtypes
+        for R_, C_ in ((1, 77), (33, 77), (5, 1), (700, 3), (64, 333), (3, 5000), (2, 40000)):
+            m = T((R_, C_), code)
+            row, col = T(C_, code), T(R_, code)
+            o = b.pool(np.zeros((R_, C_), np_dtype(code)))
+            b.add("ADD", o, [m, np.broadcast_to(row, (R_, C_))])
+            o = b.pool(np.zeros((R_, C_), np_dtype(ocode)))
+            b.add("DIV", o, [np.broadcast_to(col[:, None], (R_, C_)), m])
+            o = b.pool(np.zeros((R_, C_), np_dtype(code)))
+            b.add("MUL", o, [np.broadcast_to(row, (R_, C_)), np.broadcast_to(col[:, None], (R_, C_))])   # outer product: no full operand
+        for B_, R_, C_ in ((9, 13, 3), (40, 5, 7), (3, 300, 2), (2, 7, 99)):
+            t = T((B_, C_, R_), code).transpose(0, 2, 1)                 # batches of small transposes
+            m = T((B_, R_, C_), ocode)
+            o = b.pool(np.zeros((B_, R_, C_), np_dtype(code)))
+            b.add("SUB", o, [t, m])
+            o = b.pool(np.zeros((B_, R_, C_), np_dtype(code)))
+            b.add("GELU_TANH", o, [t])
+        wide = T((130, 2 * 264), code)
+        o = b.pool(np.zeros((130, 264), np_dtype(code)))
+        b.add("SUB_EXP", o, [wide[:, ::2], wide[:, 1::2]])               # two column-strided matrices (rows do not merge)
+    return b.stream("staged_gathers")
+
+
 def int32_ops():
     rng = np.random.default_rng(10)
     b = Builder()
@@ -535,6 +586,7 @@ CPU_CHECKED = {
     "random_views_1": lambda: random_strided_views(1),
     "random_views_2": lambda: random_strided_views(2),
     "broadcast_2d": broadcast_2d,
+    "staged_gathers": staged_gathers,
     "transposed_2d": transposed_2d,
     "reductions": reductions,
     "operator_programs": operator_programs,

@@ -65,6 +65,12 @@ def test_row_and_column_broadcast_2d_fast_path():
     print(stats, flush=True)
 
 
+def test_strided_and_broadcast_inputs_gathered_through_lds():
+    stats, _ = _run_and_check(C.staged_gathers())
+    print(stats, flush=True)
+    assert stats["max_ulp"] <= 2
+
+
 def test_transposed_views_lds_tiled_gather():
     stats, _ = _run_and_check(C.transposed_2d())
     print(stats, flush=True)

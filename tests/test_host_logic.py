@@ -126,6 +126,25 @@ def test_task_plan_picks_the_execution_path_the_layout_calls_for():
                      "RED_CONTIG", "RED_GENERIC", "NOP"], paths
     assert got[0][3] == 1                                  # [4, 96, 80] contiguous merges to one dim
     assert got[3][1] * got[3][2] >= 4 * 3 * 3 and got[3][3] == 3      # 4 batches of 3 x 3 tiles
+    # contiguous output, inputs strided / broadcast / of another dtype: gathered through LDS
+    g = Builder()
+    f = lambda *shape: g.pool(np.zeros(shape, np.float32))
+    h = lambda *shape: g.pool(np.zeros(shape, np.float16))
+    x2 = f(2 * 5000 + 1)
+    g.add("RELU", f(5000), [x2[1::2]])                                   # 0 a stride-2 slice that starts at element 1
+    g.add("ADD", f(33, 77), [f(33, 77), np.broadcast_to(f(77), (33, 77))])          # 1 row vector, 77 is no multiple of the vector width
+    g.add("MUL", f(33, 77), [f(33, 77), np.broadcast_to(f(33)[:, None], (33, 77))]) # 2 column vector: read along the rows through LDS tiles
+    g.add("ADD", f(6, 9, 5), [f(6, 5, 9).transpose(0, 2, 1), f(6, 9, 5)])           # 3 small transposes (5 columns: no LDS tiles)
+    g.add("SUB", h(400), [f(400), h(400)])                               # 4 mixed dtypes
+    g.add("COPY", f(5000), [x2[::2]])                                    # 5 same-dtype copy keeps raw bits: generic
+    g.add("RELU", f(5001)[1:], [x2[: 10000: 2]])                         # 6 output not 16-byte aligned: generic
+    i32 = g.pool(np.zeros(200, np.int32))
+    g.add("ADD", g.pool(np.zeros(100, np.int32)), [i32[::2], i32[1::2]]) # 7 integers: generic
+    g.add("ADD", f(3, 4, 5, 6), [f(3, 4, 5, 6), np.broadcast_to(f(4, 1, 6)[None], (3, 4, 5, 6))])   # 8 four dims that do not merge: generic
+    sg = g.stream()
+    hg = HostPools(sg)
+    got = [R.task_plan(hg.tasks, i, sg.impl_for()[i])[0] for i in range(len(sg))]
+    assert got == ["STAGED", "STAGED", "TILE2D", "STAGED", "STAGED"] + ["GENERIC"] * 4, got
     # a large transposed task splits into at most 1024 units that cover every tile
     big = Builder()
     src = big.pool(np.zeros((3000, 2100), np.float16)).T
