@@ -116,12 +116,30 @@ template <> struct Elem<GPUOS_F32> {
   template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st4(p, i, __builtin_bit_cast(uint32_t, f)); }
   template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st4(o, i, Mem<POL>::ld4(a, i)); }
 };
+// 16-bit elements are taken out of and put into a 32-bit word as the halves of a two-element vector:
+// the compiler then reads a half with the conversion instruction's own operand selector and writes
+// two converted values with one pack (fp16) or one packed conversion (bf16), where shifts and
+// masks on integers cost three to four operations per element.
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bfloat2_t __attribute__((ext_vector_type(2)));
+DEV float opaque_f32(float f) {
+  // keeps the fp32 value a value of its own: without it the compiler folds the producing multiply /
+  // fma and the conversion into one mixed-precision instruction that rounds the exact result
+  // straight to 16 bits (one rounding), while the defined result is fp32 first
+  asm("" : "+v"(f));
+  return f;
+}
 template <> struct Elem<GPUOS_F16> {
   static constexpr int V = 8, ES = 2;
-  static DEV float get(const v4i& q, int k) { return h2f(((uint32_t)q[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
+  static DEV float get(const v4i& q, int k) {
+    const int w = q[k >> 1];
+    return (float)__builtin_bit_cast(half2_t, w)[k & 1];
+  }
   static DEV void put(v4i& q, int k, float f) {
-    const uint32_t w = (uint32_t)q[k >> 1];
-    q[k >> 1] = (int)((k & 1) ? ((w & 0xffffu) | (f2h(f) << 16)) : ((w & 0xffff0000u) | f2h(f)));
+    const int w = q[k >> 1];
+    half2_t h = __builtin_bit_cast(half2_t, w);
+    h[k & 1] = (_Float16)opaque_f32(f);
+    q[k >> 1] = __builtin_bit_cast(int, h);
   }
   template <int POL> static DEV float load1(const void* p, uint32_t i) { return h2f(Mem<POL>::ld2(p, i)); }
   template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st2(p, i, f2h(f)); }
@@ -129,10 +147,15 @@ template <> struct Elem<GPUOS_F16> {
 };
 template <> struct Elem<GPUOS_BF16> {
   static constexpr int V = 8, ES = 2;
-  static DEV float get(const v4i& q, int k) { return b2f(((uint32_t)q[k >> 1] >> ((k & 1) * 16)) & 0xffffu); }
-  static DEV void put(v4i& q, int k, float f) {
+  static DEV float get(const v4i& q, int k) {
     const uint32_t w = (uint32_t)q[k >> 1];
-    q[k >> 1] = (int)((k & 1) ? ((w & 0xffffu) | (f2b(f) << 16)) : ((w & 0xffff0000u) | f2b(f)));
+    return __builtin_bit_cast(float, (k & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+  static DEV void put(v4i& q, int k, float f) {
+    const int w = q[k >> 1];
+    bfloat2_t h = __builtin_bit_cast(bfloat2_t, w);
+    h[k & 1] = (__bf16)f;
+    q[k >> 1] = __builtin_bit_cast(int, h);
   }
   template <int POL> static DEV float load1(const void* p, uint32_t i) { return b2f(Mem<POL>::ld2(p, i)); }
   template <int POL> static DEV void store1(void* p, uint32_t i, float f) { Mem<POL>::st2(p, i, f2b(f)); }
@@ -274,16 +297,38 @@ template <> struct Op<kImplProg1> { static constexpr int N = 1; static DEV float
 template <> struct Op<kImplProg2> { static constexpr int N = 2; static DEV float f(float x, float y, float, float a) { return run_program(x, y, 0.f, a); } };
 template <> struct Op<kImplProg3> { static constexpr int N = 3; static DEV float f(float x, float y, float z, float a) { return run_program(x, y, z, a); } };
 
+// The exponential when the result is going to be rounded to a 16-bit format: the hardware base-2
+// exponential of x * log2(e).  Its relative error (2^-17 at the ends of the range: the product's
+// rounding, times ln 2; one step of the hardware exponential on top) is far below half a step of
+// either 16-bit format (2^-9, 2^-12), so the rounded result is the correctly rounded one or its
+// neighbour, inside the 2 units allowed; the full-precision routine it replaces costs about twenty
+// operations where this costs two (fp16) or seven (bf16).  The hardware exponential flushes results
+// below fp32's normal range.  fp16 does not care (everything below 2^-25 rounds to zero there);
+// bf16 shares fp32's range, so there the argument is raised by 64 and the result scaled back with an
+// exact multiplication, which rounds into the subnormal range correctly.
+template <int DT> DEV float exp_for_16bit(float x) {
+  const float t = x * 1.44269504088896340736f;
+  if (DT == GPUOS_F16) return __builtin_amdgcn_exp2f(t);
+  const bool low = t < -120.0f;
+  return __builtin_amdgcn_exp2f(low ? t + 64.0f : t) * (low ? 0x1.0p-64f : 1.0f);
+}
+// Op<IMPL> as it is evaluated when the output dtype is DT
+template <int IMPL, int DT> struct OpOut : Op<IMPL> {};
+template <> struct OpOut<GPUOS_IMPL_EXP, GPUOS_F16> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return exp_for_16bit<GPUOS_F16>(x); } };
+template <> struct OpOut<GPUOS_IMPL_EXP, GPUOS_BF16> { static constexpr int N = 1; static DEV float f(float x, float, float, float) { return exp_for_16bit<GPUOS_BF16>(x); } };
+template <> struct OpOut<GPUOS_IMPL_SUB_EXP, GPUOS_F16> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { const float d = x - y; return exp_for_16bit<GPUOS_F16>(d); } };
+template <> struct OpOut<GPUOS_IMPL_SUB_EXP, GPUOS_BF16> { static constexpr int N = 2; static DEV float f(float x, float y, float, float) { const float d = x - y; return exp_for_16bit<GPUOS_BF16>(d); } };
+
 // o[k] = f(x[k], y[k], z[k], alpha) for the K elements a lane holds: element by element for the
 // built-in implementations (the compiler unrolls it back into straight code), instruction by
 // instruction for a program.
-template <int IMPL, int K>
+template <int IMPL, int K, int DT = GPUOS_F32>
 DEV void apply_vec(const float (&x)[K], const float (&y)[K], const float (&z)[K], float alpha, float (&o)[K]) {
   if (IMPL == kImplProg1 || IMPL == kImplProg2 || IMPL == kImplProg3) {
     run_program_vec<K>(x, y, z, alpha, o);
   } else {
 #pragma unroll
-    for (int k = 0; k < K; ++k) o[k] = Op<IMPL>::f(x[k], y[k], z[k], alpha);
+    for (int k = 0; k < K; ++k) o[k] = OpOut<IMPL, DT>::f(x[k], y[k], z[k], alpha);
   }
 }
 
@@ -354,7 +399,7 @@ PATHFN void ew_contig(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
           for (int k = 0; k < V; ++k) {
             xa[k] = E::get(qa[u], k); xb[k] = N > 1 ? E::get(qb[u], k) : 0.f; xc[k] = N > 2 ? E::get(qc[u], k) : 0.f;
           }
-          apply_vec<IMPL, V>(xa, xb, xc, alpha, xo);
+          apply_vec<IMPL, V, DT>(xa, xb, xc, alpha, xo);
 #pragma unroll
           for (int k = 0; k < V; ++k) E::put(q, k, xo[k]);
         }
@@ -373,7 +418,7 @@ PATHFN void ew_contig(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
         for (int k = 0; k < V; ++k) {
           xa[k] = E::get(qa, k); xb[k] = N > 1 ? E::get(qb, k) : 0.f; xc[k] = N > 2 ? E::get(qc, k) : 0.f;
         }
-        apply_vec<IMPL, V>(xa, xb, xc, alpha, xo);
+        apply_vec<IMPL, V, DT>(xa, xb, xc, alpha, xo);
 #pragma unroll
         for (int k = 0; k < V; ++k) E::put(q, k, xo[k]);
       }
@@ -384,7 +429,7 @@ PATHFN void ew_contig(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
   for (uint32_t i = begin + tid; i < end; i += kThreads) {
     if (IMPL == GPUOS_IMPL_COPY) E::template copy1<POL>(po, pa, i);
     else
-      E::template store1<POL>(po, i, Op<IMPL>::f(E::template load1<POL>(pa, i), N > 1 ? E::template load1<POL>(pb, i) : 0.f,
+      E::template store1<POL>(po, i, OpOut<IMPL, DT>::f(E::template load1<POL>(pa, i), N > 1 ? E::template load1<POL>(pb, i) : 0.f,
                                                  N > 2 ? E::template load1<POL>(pc, i) : 0.f, alpha));
   }
 }
@@ -408,7 +453,11 @@ PATHFN void ew_contig_int(const Record* r_v, uint32_t begin_v, uint32_t end_v) {
 constexpr uint32_t kScratchFloats = 7168;   // LDS scratch per workgroup (gather staging, transpose tiles, reduction partials): 28 KB,
                                             // still below what the dispatcher's workgroup needs, so the kernel's allocation does not grow
 
-template <int POL, int IMPL, int DT>
+// KIND1 >= 0: a binary operation whose first operand is a full tensor and whose second is of that
+// kind (the attention chain's layouts: full + row vector, full + per-row scalar); the kinds are then
+// compile-time facts and the selects and branches on them disappear.  KIND1 < 0: kinds read from
+// the descriptor.
+template <int POL, int IMPL, int DT, int KIND1>
 PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
   const Record* r = lds_arg(r_v);
   const uint32_t begin = uni(begin_v), end = uni(end_v);
@@ -427,7 +476,7 @@ PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float*
   for (int k = 0; k < 3; ++k) {
     const int kk = k < N ? k : 0;
     p[k] = uni_ptr(r->ptr[kk]);
-    kind[k] = uni(r->okind[kk]);
+    kind[k] = KIND1 < 0 ? uni(r->okind[kk]) : (kk == 0 ? (uint32_t)K_FULL : (uint32_t)KIND1);
     dt[k] = uni(r->dtype[kk]);
     st0[k] = uni(r->stride[kk][0]);
     // full operands: rebased to the chunk; row vectors: the whole vector
@@ -441,6 +490,65 @@ PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float*
   // cost one more uncached 4-byte memory request.
   const uint32_t row_first = begin / C, row_cnt = (end - 1) / C - row_first + 1;
   const bool staged = n_scalar != 0 && row_cnt * n_scalar <= kScratchFloats;
+  // UN vectors per thread and round, all their loads issued before the first result is needed.
+  // A chunk is one or two rounds, so the round is made long (a chunk of 12K 16-bit elements is
+  // exactly one) and the first round's loads leave BEFORE the row scalars are staged: the chunk
+  // then pays one memory latency, not three in a row.
+  constexpr int UN = (N == 2 && KIND1 != (int)K_ROWVEC) ? 6 : 4;
+  // (row, column) of a thread's vectors: one division per chunk, then steps with a carry
+  const uint32_t step = kThreads * V;
+  const uint32_t step_rows = step / C, step_cols = step - step_rows * C;
+  uint32_t row, col;
+  {
+    const uint32_t i = begin + threadIdx.x * V;
+    row = i / C;
+    col = i - row * C;
+  }
+  v4i q[UN][3];
+  uint32_t rowu[UN];
+  auto load_round = [&](uint32_t v0) {
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const uint32_t v = v0 + (uint32_t)u * kThreads;
+      const bool act = v < nvec;
+      rowu[u] = row;
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        if (kind[k] == K_FULL) q[u][k] = M::ld16(rs[k], act ? v * 16u : kNoLoad);
+        else if (kind[k] == K_ROWVEC) q[u][k] = M::ld16(rs[k], act ? col * E::ES : kNoLoad);
+      }
+      row += step_rows;
+      col += step_cols;
+      if (col >= C) { col -= C; ++row; }
+    }
+  };
+  auto compute_round = [&](uint32_t v0) {
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const uint32_t v = v0 + (uint32_t)u * kThreads;
+      if (v < nvec) {
+        float sc[3] = {0.f, 0.f, 0.f};
+        uint32_t region = 0;
+#pragma unroll
+        for (int k = 0; k < N; ++k)
+          if (kind[k] == K_ROWSCALAR) {
+            if (staged) { sc[k] = s_scratch[region + rowu[u] - row_first]; region += row_cnt; }
+            else sc[k] = load_rt<POL>(p[k], rowu[u] * st0[k], dt[k]);
+          }
+        v4i res;
+        float xv[3][V], xo[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+#pragma unroll
+          for (int k = 0; k < 3; ++k) xv[k][e] = k < N ? ((kind[k] == K_ROWSCALAR) ? sc[k] : E::get(q[u][k], e)) : 0.f;
+        apply_vec<IMPL, V, DT>(xv[0], xv[1], xv[2], alpha, xo);
+#pragma unroll
+        for (int e = 0; e < V; ++e) E::put(res, e, xo[e]);
+        M::st16(ro, v * 16u, res);
+      }
+    }
+  };
+  load_round(threadIdx.x);                           // (every thread, whatever nvec: the barrier below is for all)
   if (staged) {
     uint32_t region = 0;
 #pragma unroll
@@ -452,43 +560,10 @@ PATHFN void ew_row2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float*
       }
     __syncthreads();
   }
-  // UN vectors per thread and round: all their loads are issued before the first result is needed
-  // (one vector per round left a single request in flight per operand)
-  constexpr int UN = 4;
-  for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += kThreads * UN) {
-    v4i q[UN][3];
-    float s[UN][3];
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const uint32_t v = v0 + (uint32_t)u * kThreads;
-      const bool act = v < nvec;
-      const uint32_t i = begin + (act ? v : 0u) * V;
-      const uint32_t row = i / C, col = i - row * C;
-      uint32_t region = 0;
-#pragma unroll
-      for (int k = 0; k < N; ++k) {
-        if (kind[k] == K_FULL) q[u][k] = M::ld16(rs[k], act ? v * 16u : kNoLoad);
-        else if (kind[k] == K_ROWVEC) q[u][k] = M::ld16(rs[k], act ? col * E::ES : kNoLoad);
-        else if (staged) { s[u][k] = s_scratch[region + row - row_first]; region += row_cnt; }
-        else s[u][k] = load_rt<POL>(p[k], row * st0[k], dt[k]);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const uint32_t v = v0 + (uint32_t)u * kThreads;
-      if (v < nvec) {
-        v4i res;
-        float xv[3][V], xo[V];
-#pragma unroll
-        for (int e = 0; e < V; ++e)
-#pragma unroll
-          for (int k = 0; k < 3; ++k) xv[k][e] = k < N ? ((kind[k] == K_ROWSCALAR) ? s[u][k] : E::get(q[u][k], e)) : 0.f;
-        apply_vec<IMPL, V>(xv[0], xv[1], xv[2], alpha, xo);
-#pragma unroll
-        for (int e = 0; e < V; ++e) E::put(res, e, xo[e]);
-        M::st16(ro, v * 16u, res);
-      }
-    }
+  compute_round(threadIdx.x);
+  for (uint32_t v0 = threadIdx.x + kThreads * UN; v0 < nvec; v0 += kThreads * UN) {
+    load_round(v0);
+    compute_round(v0);
   }
   if (staged) __syncthreads();        // the scratch may be reused by the next chunk
 }
@@ -1020,6 +1095,48 @@ PATHFN void red_rows_short(RedArgs a) {
   }
 }
 
+// The same when every row is a whole number of vectors and starts on one (the attention shapes: rows
+// of 64 / 128 / 256 16-bit elements): no edges to mask and nothing to remember per pass but the
+// loaded vector, so eight passes stay in registers.
+template <int POL, int RIMPL, int DT>
+PATHFN void red_rows_short_aligned(RedArgs a) {
+  const RedRun run = red_run(a);
+  char* po = (char*)uni_ptr((uint64_t)a.po);
+  const uint32_t odt = uni(a.odt), row_begin = uni(a.row_begin), row_end = uni(a.row_end), vpr = uni(a.max_span);
+  using M = Mem<POL>;
+  constexpr int UP = 8;
+  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  uint32_t P = 1;                                     // lanes per row: power of two >= vectors per row
+  while (P < vpr) P <<= 1;
+  const uint32_t rpw = 64u / P, sub = lane / P, j = lane & (P - 1u);
+  const bool gather = UP * rpw <= 64u;                // the pass's rows fit one lane each
+  const bool mine = j < vpr;
+  for (uint32_t base = row_begin + wave * rpw * UP; base < row_end; base += 4 * rpw * UP) {
+    v4i q[UP];
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+      const uint32_t row = base + u * rpw + sub;
+      q[u] = M::ld16(run.rin, (row < row_end && mine) ? ((row - row_begin) * vpr + j) * 16u : kNoLoad);
+    }
+    float res = 0.0f;                                 // lane L ends up with the result of row base + L
+#pragma unroll
+    for (int u = 0; u < UP; ++u) {
+      const uint32_t row = base + u * rpw + sub;
+      float acc = red_identity<RIMPL>();
+      bool nan = false;
+      if (row < row_end && mine) acc = red_vector<RIMPL, DT>(q[u], 0, 0, 0, false, acc, nan);
+      acc = wave_reduce<RIMPL>(red_finish<RIMPL>(acc, nan), P);
+      if (gather) {
+        const float got = __shfl(acc, (int)((lane & (rpw - 1u)) * P), 64);
+        if (lane / rpw == (uint32_t)u) res = got;
+      } else if (row < row_end && j == 0) {
+        store_rt<POL>(po, row, odt, acc);
+      }
+    }
+    if (gather && lane < UP * rpw && base + lane < row_end) store_rt<POL>(po, base + lane, odt, res);
+  }
+}
+
 template <int POL, int RIMPL, int DT>
 DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float* s_part) {
   using E = Elem<DT>;
@@ -1040,7 +1157,8 @@ DEV void red_contig(const Record* r, uint32_t row_begin, uint32_t row_end, float
     a.bytes = ((row_end * n - a.base_elem) * E::ES + 15u) & ~15u;
     a.po = po; a.odt = odt; a.row_begin = row_begin; a.row_end = row_end; a.s_part = s_part;
     a.max_span = (n % V == 0 && a.base_elem == row_begin * n) ? n / V : (n + V - 2) / V + 1;
-    if (a.max_span <= 64u) red_rows_short<POL, RIMPL, DT>(a);
+    if (a.max_span <= 64u && n % V == 0 && a.base_elem == row_begin * n) red_rows_short_aligned<POL, RIMPL, DT>(a);
+    else if (a.max_span <= 64u) red_rows_short<POL, RIMPL, DT>(a);
     else if (a.max_span >= 1024u && row_end - row_begin <= kRedPartialRows) red_rows_quarter<POL, RIMPL, DT>(a);
     else if (a.max_span < 256u) red_rows_wave<POL, RIMPL, DT, 4, 2>(a);
     else red_rows_wave<POL, RIMPL, DT, 2, 4>(a);
@@ -1582,9 +1700,21 @@ DEV void run_elementwise(const Record* r, uint32_t chunk, float* s_scratch) {
     else ew_contig<POL, IMPL, GPUOS_BF16>(r, begin, end);
   } else if (path == PATH_ROW2D && Op<IMPL>::N >= 2) {
     constexpr int I2 = Op<IMPL>::N >= 2 ? IMPL : GPUOS_IMPL_ADD;
-    if (dt == GPUOS_F32) ew_row2d<POL, I2, GPUOS_F32>(r, begin, end, s_scratch);
-    else if (dt == GPUOS_F16) ew_row2d<POL, I2, GPUOS_F16>(r, begin, end, s_scratch);
-    else ew_row2d<POL, I2, GPUOS_BF16>(r, begin, end, s_scratch);
+    const uint32_t k0 = uni(r->okind[0]), k1 = uni(r->okind[1]);
+    const int spec = (Op<I2>::N == 2 && k0 == K_FULL) ? (k1 == K_ROWSCALAR ? 1 : (k1 == K_ROWVEC ? 2 : 0)) : 0;
+    if (dt == GPUOS_F32) {
+      if (spec == 1) ew_row2d<POL, I2, GPUOS_F32, K_ROWSCALAR>(r, begin, end, s_scratch);
+      else if (spec == 2) ew_row2d<POL, I2, GPUOS_F32, K_ROWVEC>(r, begin, end, s_scratch);
+      else ew_row2d<POL, I2, GPUOS_F32, -1>(r, begin, end, s_scratch);
+    } else if (dt == GPUOS_F16) {
+      if (spec == 1) ew_row2d<POL, I2, GPUOS_F16, K_ROWSCALAR>(r, begin, end, s_scratch);
+      else if (spec == 2) ew_row2d<POL, I2, GPUOS_F16, K_ROWVEC>(r, begin, end, s_scratch);
+      else ew_row2d<POL, I2, GPUOS_F16, -1>(r, begin, end, s_scratch);
+    } else {
+      if (spec == 1) ew_row2d<POL, I2, GPUOS_BF16, K_ROWSCALAR>(r, begin, end, s_scratch);
+      else if (spec == 2) ew_row2d<POL, I2, GPUOS_BF16, K_ROWVEC>(r, begin, end, s_scratch);
+      else ew_row2d<POL, I2, GPUOS_BF16, -1>(r, begin, end, s_scratch);
+    }
   } else if (path == PATH_TILE2D) {
     ew_tile2d<POL, IMPL>(r, begin, end, s_scratch);      // begin / end count tiles here
   } else if (path == PATH_STAGED) {

@@ -87,6 +87,27 @@ def all_16bit_patterns(code):
     return b.stream("all_16bit_%d" % code)
 
 
+def sub_exp_16bit_patterns(code):
+    """exp(x - y) with a 16-bit output for every 16-bit pattern x against sixteen subtrahends y, as a
+    per-row scalar (the attention chain's x - rowmax) and as a full operand: the exponential that is
+    evaluated for 16-bit outputs must stay within 2 units of the output format of the defined result
+    over the whole range (overflow, results below the normal range, NaN, infinities)."""
+    bits = np.arange(65536, dtype=np.uint16)
+    src = bits.view(np.float16) if code == S.F16 else bits
+    ys = np.array([0.0, 1.5, -3.25, 11.0, -11.0, 88.0, -88.0, 0.001, 5.5, -0.75, 20.0, -20.0, 60.0, -60.0, 100.0, -100.0], np.float32)
+    b = Builder()
+    X = b.pool(np.tile(src, 16).reshape(16, 65536))
+    ycol = b.pool(ys)
+    o = b.pool(np.zeros((16, 65536), src.dtype))
+    b.add("SUB_EXP", o, [X, np.broadcast_to(ycol[:, None], (16, 65536))])            # per-row scalar, fp32
+    yfull = b.pool(to_dtype(np.repeat(ys, 65536).reshape(16, 65536), code))
+    o = b.pool(np.zeros((16, 65536), src.dtype))
+    b.add("SUB_EXP", o, [X, yfull])                                                  # contiguous, same dtype
+    o = b.pool(np.zeros(16 * 65536, src.dtype))
+    b.add("EXP", o, [X.reshape(-1)])
+    return b.stream("sub_exp_16bit_%d" % code)
+
+
 def fp32_transcendental_sweep():
     rng = np.random.default_rng(5)
     grids = [np.linspace(-6, 6, 200001), np.linspace(-104, 89, 200001), rng.uniform(-3, 3, 200000),
@@ -582,6 +603,8 @@ CPU_CHECKED = {
     "all_16bit_f16": lambda: all_16bit_patterns(S.F16),
     "all_16bit_bf16": lambda: all_16bit_patterns(S.BF16),
     "fp32_transcendental": fp32_transcendental_sweep,
+    "sub_exp_16bit_f16": lambda: sub_exp_16bit_patterns(S.F16),
+    "sub_exp_16bit_bf16": lambda: sub_exp_16bit_patterns(S.BF16),
     "random_views_0": lambda: random_strided_views(0),
     "random_views_1": lambda: random_strided_views(1),
     "random_views_2": lambda: random_strided_views(2),

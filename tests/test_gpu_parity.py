@@ -48,6 +48,13 @@ def test_all_16bit_patterns_through_unary_ops(code):
     print(stats, flush=True)
 
 
+@pytest.mark.parametrize("code", [S.F16, S.BF16])
+def test_exponential_for_16bit_outputs_over_all_patterns(code):
+    stats, _ = _run_and_check(C.sub_exp_16bit_patterns(code))
+    print(stats, flush=True)
+    assert stats["max_ulp"] <= 2
+
+
 def test_fp32_transcendental_dense_sweep():
     stats, _ = _run_and_check(C.fp32_transcendental_sweep())
     print(stats, flush=True)
