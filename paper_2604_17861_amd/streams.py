@@ -518,6 +518,43 @@ def config3_fused(n_chains=2000, seed=2, buffer_sets=2, heads=16, Bs=(1, 2, 4, 8
                             buffer_sets=buffer_sets, layout={p: layout[p]["sets"] for p in pairs}))
 
 
+def handoff_chains(n_chains=256, length=4096, numel=1024, n_operands=64, seed=6) -> Stream:
+    """Producer -> consumer hand-offs: n_chains independent chains of `length` int32 additions on
+    vectors of `numel` elements, issued round-robin.  Link t of a chain reads what link t-1 wrote
+    (two buffers per chain, used in turn), adds one of n_operands seeded operand vectors, and names
+    link t-1 as its dependency.  Integer arithmetic: the end of a chain is x0 + the sum of its
+    operands exactly (wrap-around), so one stale or torn read anywhere in a chain shows at its end."""
+    rng = np.random.default_rng(seed)
+    n = n_chains * length
+    tasks, pool_of = new_tasks(n)
+    row = numel * 4
+    x0 = rng.integers(-2 ** 31, 2 ** 31 - 1, (n_chains, numel), dtype=np.int64).astype(np.int32)
+    ops = rng.integers(-2 ** 31, 2 ** 31 - 1, (n_operands, numel), dtype=np.int64).astype(np.int32)
+    i = np.arange(n)
+    chain, link = i % n_chains, i // n_chains
+    which = (link * 7 + chain * 13) % n_operands
+    tasks["op_id"] = OP["ADD"]
+    tasks["ndim"] = 1
+    tasks["n_inputs"] = 2
+    tasks["size"][:, 0] = numel
+    # pool 0: buffer A of every chain (starts as x0), pool 1: buffer B, pool 2: the operand table
+    src_pool = (link % 2).astype(np.int16)                       # link 0 reads A and writes B, link 1 reads B and writes A, ...
+    for slot, (pool, off) in enumerate(((src_pool, chain * row), (np.full(n, 2, np.int16), which * row))):
+        tasks["inp"]["ptr"][:, slot] = off
+        tasks["inp"]["stride"][:, slot, 0] = 1
+        tasks["inp"]["dtype"][:, slot] = I32
+        pool_of[:, slot] = pool
+    tasks["out"]["ptr"] = chain * row
+    tasks["out"]["stride"][:, 0] = 1
+    tasks["out"]["dtype"] = I32
+    pool_of[:, 3] = 1 - src_pool
+    tasks["dep"][:, 0] = np.where(link > 0, n_chains, 0)
+    pools = [Pool("a", n_chains * row, x0.view(np.uint8).reshape(-1).copy()), Pool("b", n_chains * row),
+             Pool("operands", n_operands * row, ops.view(np.uint8).reshape(-1).copy())]
+    return Stream("handoff_chains", tasks, pool_of, pools, batch=64,
+                  info=dict(seed=seed, n_chains=n_chains, length=length, numel=numel, which=which.reshape(length, n_chains)))
+
+
 # ---- configuration 4 ---------------------------------------------------------
 
 def config4(n_tasks=1000000, seed=3, swap_every=10000, window=10000, numel_lo=1024,
