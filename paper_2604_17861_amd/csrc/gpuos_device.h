@@ -84,6 +84,12 @@ DEV void drain_stores() {
   __builtin_amdgcn_s_waitcnt(0);                           // vmcnt = expcnt = lgkmcnt = 0
 }
 DEV void order_loads() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
+// Between lanes of ONE wavefront that hand data to each other through LDS: its LDS operations execute
+// in order, so this only keeps the compiler from moving them across (and waits for the counter).
+DEV void lds_wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
 
 // ---------------------------------------------------------------------------
 // element conversions (fp16 / bf16 <-> fp32; RNE, denormals kept)
@@ -1795,6 +1801,22 @@ DEV int32_t exec_chunk(const Record* r, uint32_t impl, uint32_t chunk, float* s_
 // timers are an option and the clock is read only where something needs the value.
 DEV uint64_t clock_if(bool on) { return on ? wall_clock64() : 0ull; }
 
+// The 16 lanes that hold a record's 16-byte pieces: the weighted check sum of the whole record
+// (see record_check_weight), in every one of them.
+
+DEV uint32_t record_piece_sum(const v4i& q, uint32_t part) {
+  uint32_t x = 0;
+#pragma unroll
+  for (uint32_t j = 0; j < 4; ++j) x += (uint32_t)q[j] * record_check_weight(4u * part + j);
+  // sum over the 16 lanes of the row with DPP rotations (row_ror 8, 4, 2, 1): every lane ends with
+  // the whole sum, and unlike a shuffle nothing goes through the LDS crossbar
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x124, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x122, 0xf, 0xf, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x121, 0xf, 0xf, false);
+  return x;
+}
+
 struct BuiltinExec {                // what the library's own workers execute a chunk with
   static DEV int32_t run(const Record* r, uint32_t impl, uint32_t chunk, float* s_red, const ProgramImage* progs) {
     return exec_chunk<POL_COHERENT>(r, impl, chunk, s_red, progs);
@@ -1804,6 +1826,7 @@ struct BuiltinExec {                // what the library's own workers execute a 
 // ---------------------------------------------------------------------------
 // worker (every workgroup but 0)
 // ---------------------------------------------------------------------------
+constexpr uint32_t kMirrorRetries = 1u << 22;       // fetches of a mirror record that does not (yet) verify: seconds
 constexpr uint64_t kStopGraceTicks = 10000000ull;   // 100 ms (100 MHz clock): how long a worker still waits for a dependency once the stop flag is up
 
 struct WorkShared {
@@ -1811,6 +1834,7 @@ struct WorkShared {
   uint64_t unit, entry;
   int32_t exit_flag;
   int32_t dep_status;              // 0, or the status a task whose dependency wait ran out completes with
+  uint32_t rec_sum;                // weighted check sum of the record as fetched
   alignas(16) float red[kScratchFloats];   // (16-byte LDS vectors are written into it)
 };
 
@@ -1886,16 +1910,38 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s, uint32_t gen = 0) {
     // the unit is the same for the whole workgroup: keep its fields in scalar registers
     const uint32_t unit_lo = uni((uint32_t)s->unit), unit_hi = uni((uint32_t)(s->unit >> 32));
     const uint64_t unit = ((uint64_t)unit_hi << 32) | unit_lo;
-    const uint32_t chunk = (uint32_t)(unit & 0xfffffu);
+    const uint32_t chunk = (uint32_t)(unit & 0x3ffu), lap10 = (uint32_t)((unit >> 10) & 0x3ffu);
     const uint32_t slot = (uint32_t)((unit >> 20) & 0xffffu);
     const uint32_t op = (uint32_t)((unit >> 36) & 0xffu), sel = (uint32_t)((unit >> 44) & 1u);
     const bool op_valid = ((unit >> 45) & 1u) != 0;
     // ---- fetch the descriptor (16 lanes x 16 bytes) and the claimed table slot ----
-    if (tid < 16) ((v4i*)&s->rec)[tid] = Mem<POL_COHERENT>::ld16(rd, slot * (uint32_t)sizeof(Record) + tid * 16u);
+    // The dispatcher does not wait for its mirror stores before it publishes a unit: the record is
+    // taken only once its check word holds for the ticket the unit names (else its pieces are still
+    // landing, or belong to the slot's previous lap) and fetched again otherwise.  The stores are on
+    // their way, so this ends; it is bounded like every wait here (a workgroup that runs out leaves
+    // the task to the host's time limit).
     if (tid == 16) s->entry = op_valid ? __hip_atomic_load(&a.dtable[op].slot[sel], __ATOMIC_RELAXED, SC_SYSTEM) : 0ull;
-    __syncthreads();
+    for (uint32_t attempt = 0;; ++attempt) {
+      if (tid < 64) {
+        v4i q = {0, 0, 0, 0};
+        if (tid < 16) q = Mem<POL_COHERENT>::ld16(rd, slot * (uint32_t)sizeof(Record) + tid * 16u);
+        const uint32_t x = record_piece_sum(q, tid & 15u);
+        if (tid < 16) ((v4i*)&s->rec)[tid] = q;
+        if (tid == 0) s->rec_sum = x;
+      }
+      __syncthreads();
+      if (mirror_record_valid(s->rec_sum, s->rec.ticket, slot, lap10, a.cap_mask, a.cap_shift) || attempt >= kMirrorRetries) break;
+      __syncthreads();                                  // everyone has looked at this attempt's copy
+      __builtin_amdgcn_s_sleep(2);
+    }
     const Record* r = &s->rec;
     int32_t status = r->status;
+    if (!mirror_record_valid(s->rec_sum, r->ticket, slot, lap10, a.cap_mask, a.cap_shift)) {
+      // never seen whole: nothing in it can be trusted, not even the ticket it would complete.  The
+      // unit is dropped; the host's wait for the ticket runs into its time limit.
+      __syncthreads();
+      continue;
+    }
     const uint32_t impl = uni(r->impl);
     if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
     const uint64_t c2 = clock_if(timing);

@@ -187,13 +187,28 @@ struct TraceRec {                    // = gpuos_trace_record (48 bytes), host me
 };
 static_assert(sizeof(TraceRec) == 48, "trace record layout");
 
-// Work-unit entry: bits 0..19 chunk, 20..35 ring slot, 36..43 op id, 44 table slot,
-// 45 op id valid, 46..63 stamp.  The stamp is the lap of the unit ring plus one (18 bits): the
-// entry doubles as its own ready flag, so a worker that claimed unit g polls just that entry.
+// Work-unit entry: bits 0..9 chunk, 10..19 lap of the task's ticket around the ring (low 10 bits),
+// 20..35 ring slot, 36..43 op id, 44 table slot, 45 op id valid, 46..63 stamp.  The stamp is the
+// lap of the unit ring plus one (18 bits): the entry doubles as its own ready flag, so a worker that
+// claimed unit g polls just that entry.  The ticket lap lets the worker tell the mirror record it is
+// after from what the slot held a lap earlier (see mirror_record_valid).
 GPUOS_HD inline uint64_t unit_stamp(uint64_t g, uint32_t unit_shift) { return ((g >> unit_shift) + 1) & 0x3ffffull; }
-GPUOS_HD inline uint64_t pack_unit(uint32_t chunk, uint32_t slot, uint32_t op, uint32_t sel, uint32_t valid, uint64_t stamp) {
-  return (uint64_t)chunk | ((uint64_t)slot << 20) | ((uint64_t)(op & 0xff) << 36) |
+GPUOS_HD inline uint64_t pack_unit(uint32_t chunk, uint32_t lap, uint32_t slot, uint32_t op, uint32_t sel, uint32_t valid, uint64_t stamp) {
+  return (uint64_t)(chunk & 0x3ffu) | ((uint64_t)(lap & 0x3ffu) << 10) | ((uint64_t)slot << 20) | ((uint64_t)(op & 0xff) << 36) |
          ((uint64_t)(sel & 1) << 44) | ((uint64_t)(valid & 1) << 45) | (stamp << 46);
+}
+static_assert(kMaxChunksPerTask <= 1024, "a chunk index has 10 bits in a work unit");
+
+// The mirror of the ring is written by the dispatcher with sixteen 16-byte stores per record that
+// land in any order, and the work units that name a record are published WITHOUT waiting for those
+// stores (that wait was a memory round trip in every dispatcher pass and in every lone task's
+// latency).  Instead the record proves itself: the dispatcher recomputes the check word over the
+// record as it leaves (resolved fields and ticket included), and a worker accepts what it fetched
+// only if the weighted sum equals the seed of the record's own ticket AND that ticket is the one the
+// unit names (same slot, same lap); anything else (pieces of the record the slot held a lap ago) is
+// fetched again.
+GPUOS_HD inline bool mirror_record_valid(uint32_t sum, uint64_t ticket, uint32_t slot, uint32_t lap10, uint32_t cap_mask, uint32_t cap_shift) {
+  return sum == record_check_seed(ticket) && (uint32_t)(ticket & cap_mask) == slot && (uint32_t)((ticket >> cap_shift) & 0x3ffu) == lap10;
 }
 
 struct WorkerArgs {
@@ -211,6 +226,7 @@ struct WorkerArgs {
   uint32_t   cap_mask;
   uint32_t   unit_mask;
   uint32_t   unit_shift;     // log2 of the unit ring size
+  uint32_t   cap_shift;      // log2 of the ring capacity
   uint64_t   idle_exit_ticks;   // 0 = never; 100 MHz ticks
   const ProgramImage* progs; // GPUOS_MAX_PROGRAMS images, written by the host
   TraceRec*  trace;          // host memory; nullptr = tracing off

@@ -59,7 +59,7 @@ constexpr uint32_t kStageRetries = 4096;   // re-reads of a record that fails it
 struct PubEntry {                          // what it takes to publish a task's work units
   uint32_t slot;
   uint32_t nchunks;
-  uint32_t opinfo;                         // op id | table slot << 8 | valid << 9
+  uint32_t opinfo;                         // op id | table slot << 8 | valid << 9 | lap of the ticket (10 bits) << 16
   uint32_t route;                          // 0: main unit ring; 1: the second ring, served by the run-time kernel
 };
 struct PendEntry {
@@ -92,23 +92,10 @@ struct DispShared {
   uint32_t native[GPUOS_MAX_PROGRAMS];     // per operator program: 1 = its tasks go to the second ring (native code is being served there)
   uint64_t tail, epoch_word;
   uint32_t n, npend, npub, npub_second;
+  uint64_t lane_tickets, lane_units;       // what the first wavefront's short cut for lone tasks has dispatched / published
+  uint32_t lane_counted;                   // ... and whether it counted an operator (tracing)
 };
 
-// The 16 lanes that hold a record's 16-byte pieces: the weighted check sum of the whole record
-// (see record_check_weight), in every one of them.
-
-DEV uint32_t record_piece_sum(const v4i& q, uint32_t part) {
-  uint32_t x = 0;
-#pragma unroll
-  for (uint32_t j = 0; j < 4; ++j) x += (uint32_t)q[j] * record_check_weight(4u * part + j);
-  // sum over the 16 lanes of the row with DPP rotations (row_ror 8, 4, 2, 1): every lane ends with
-  // the whole sum, and unlike a shuffle nothing goes through the LDS crossbar
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xf, 0xf, false);
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x124, 0xf, 0xf, false);
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x122, 0xf, 0xf, false);
-  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x121, 0xf, 0xf, false);
-  return x;
-}
 
 DEV void dispatcher_refresh_native(const WorkerArgs& a, DispShared* s) {
   // which programs a run-time kernel serves natively, and which generation of it is wanted
@@ -201,8 +188,7 @@ DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npu
   }
   __syncthreads();
   const uint32_t total = s->ubeg[npub];
-  drain_stores();                                  // the records written before this call are in memory ...
-  __syncthreads();                                 // ... every wave's, before any unit that names them appears
+  // (no wait for the mirror stores of this pass: a worker checks the record it fetches, see mirror_record_valid)
   for (uint32_t u = tid; u < total; u += kThreads) {
     uint32_t lo = 0, hi = npub;                    // ubeg[lo] <= u < ubeg[hi]
     while (hi - lo > 1) {
@@ -213,7 +199,7 @@ DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npu
     const uint64_t g = units_w + u;
     // one 8-byte store publishes the unit: the stamp makes it claimable
     __hip_atomic_store(&ring[g & a.unit_mask],
-                       pack_unit(u - s->ubeg[lo], pe.slot, pe.opinfo & 0xffu, (pe.opinfo >> 8) & 1u, (pe.opinfo >> 9) & 1u,
+                       pack_unit(u - s->ubeg[lo], pe.opinfo >> 16, pe.slot, pe.opinfo & 0xffu, (pe.opinfo >> 8) & 1u, (pe.opinfo >> 9) & 1u,
                                  unit_stamp(g, a.unit_shift)),
                        __ATOMIC_RELAXED, SC_SYSTEM);
   }
@@ -279,7 +265,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   uc.w[0] = __hip_atomic_load(&a.d->tail_units, __ATOMIC_RELAXED, SC_SYSTEM);
   uc.w[1] = __hip_atomic_load(&a.d->tail_units_j, __ATOMIC_RELAXED, SC_SYSTEM);
   for (uint32_t op = tid; op < GPUOS_MAX_OPS; op += kThreads) { s->entry[op] = 0; s->opcnt[op] = 0; }
-  if (tid == 0) s->npend = 0;
+  if (tid == 0) { s->npend = 0; s->lane_counted = 0; }
   __syncthreads();
   uint64_t idle_since = wall_clock64();
   if (tid == 0) {
@@ -320,6 +306,73 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
         ++polls;
         if (tid == 0 && (polls & 63u) == 0) __hip_atomic_store(&a.h->heartbeat, polls, __ATOMIC_RELAXED, SC_SYSTEM);
+        if (t == mirrored + 1 && e == seen_epoch && !stopping && !have_pending) {
+          // ---- short cut for a lone task ----
+          // One new record, whole (its check word holds), no table change, nothing held back: this
+          // wavefront resolves, mirrors and publishes it by itself and polls on.  The other three
+          // stay at the barrier below; the dozen barriers of a batch pass are not on a lone task's
+          // way.  Anything special (a dependency, a fence, many chunks, the second ring, a full
+          // lookahead window) takes the ordinary way.
+          order_loads();
+          const uint32_t x0 = record_piece_sum(q, part);
+          const uint32_t claimed_lo = __builtin_amdgcn_readfirstlane((uint32_t)claimed);
+          const uint32_t claimed_hi = __builtin_amdgcn_readfirstlane((uint32_t)(claimed >> 32));
+          const uint64_t claimed0 = ((uint64_t)claimed_hi << 32) | claimed_lo;       // thread 0 keeps the count
+          bool lone = __builtin_amdgcn_readfirstlane((uint32_t)(x0 == record_check_seed(mirrored))) != 0 &&
+                      !(uc.w[0] > claimed0 && uc.w[0] - claimed0 >= kLookaheadUnits);
+          if (lone) {
+            if (tid < 16) ((v4i*)&s->rec[0])[part] = q;
+            lds_wave_sync();
+            Record& rc = s->rec[0];
+            const uint32_t op = uni(rc.op_id);
+            uint32_t nch = uni(rc.nchunks);
+            const uint64_t ent = op < GPUOS_MAX_OPS ? s->entry[op] : 0ull;
+            const uint32_t impl = uni((uint32_t)ent);
+            lone = (rc.rflags & RF_FENCE) == 0 && (rc.dep[0] | rc.dep[1] | rc.dep[2]) == 0 && nch <= 64u &&
+                   impl < GPUOS_IMPL_PROGRAM_BASE;
+            if (lone) {
+              const int32_t status = ent == 0 ? GPUOS_E_BADOP : GPUOS_OK;        // (covers an op id out of range)
+              if (status != GPUOS_OK || nch == 0) nch = 1;
+              const uint32_t sel = (uint32_t)((ent >> 32) & 1u);
+              const uint64_t tk0 = clock_if(tracing);
+              lds_wave_sync();                                             // every lane has read what lane 0 overwrites
+              if (tid == 0) {
+                rc.impl = impl;
+                rc.version = (uint32_t)(ent >> 32);
+                rc.sel = (uint8_t)sel;
+                rc.status = status;
+                rc.nchunks = nch;
+                rc.ticket = mirrored;
+                if (tracing) {
+                  rc.t_dequeue[0] = (uint32_t)tk0; rc.t_dequeue[1] = (uint32_t)(tk0 >> 32);
+                  if (op < GPUOS_MAX_OPS) { atomicAdd(&s->opcnt[op], 1u); s->lane_counted = 1u; }
+                }
+              }
+              lds_wave_sync();
+              const uint32_t slot0 = (uint32_t)(mirrored & a.cap_mask);
+              if (tid < 16) {
+                v4i w = ((const v4i*)&s->rec[0])[part];
+                if (part == 15u) w[3] = 0;
+                const uint32_t xs = record_piece_sum(w, part);
+                if (part == 15u) w[3] = (int)(record_check_seed(mirrored) - xs);
+                Mem<POL_COHERENT>::st16(rd, slot0 * (uint32_t)sizeof(Record) + part * 16u, w);
+              }
+              if (tid < nch) {
+                const uint64_t gu = uc.w[0] + tid;
+                __hip_atomic_store(&a.units[gu & a.unit_mask],
+                                   pack_unit(tid, (uint32_t)((mirrored >> a.cap_shift) & 0x3ffu), slot0, op, sel, status == GPUOS_OK ? 1u : 0u,
+                                             unit_stamp(gu, a.unit_shift)),
+                                   __ATOMIC_RELAXED, SC_SYSTEM);
+              }
+              mirrored += 1;
+              uc.w[0] += nch;
+              if (tid == 0) __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
+              if (timing || a.idle_exit_ticks != 0) idle_since = wall_clock64();
+              st_batches += 1; st_records += 1; st_units += nch;
+              continue;
+            }
+          }
+        }
         if (t != mirrored || e != seen_epoch || stopping || have_pending) break;
         if (a.idle_exit_ticks != 0 && wall_clock64() - idle_since > a.idle_exit_ticks) {
           e |= 2u;                                  // behave as if the host had asked to stop
@@ -340,11 +393,17 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       if (tid == 0) {
         s->tail = t;
         s->epoch_word = e;
+        s->lane_tickets = mirrored;
+        s->lane_units = uc.w[0];
       }
     }
     __syncthreads();
     const uint64_t tail = s->tail, ew = s->epoch_word;
+    mirrored = s->lane_tickets;                      // the short cut above may have moved both on
+    uc.w[0] = s->lane_units;
+    if (tracing && s->lane_counted) counts_dirty = true;
     __syncthreads();
+    if (tracing && tid == 0) s->lane_counted = 0;  // (read again only after the next poll's barrier)
     if ((ew >> 12) != (seen_epoch >> 12)) {
       const uint32_t hinted = (uint32_t)((ew >> 4) & 0xffu);
       const bool one = ((ew >> 12) - (seen_epoch >> 12)) == 1 && hinted != 0xffu;
@@ -517,7 +576,8 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
           PubEntry pe;
           pe.slot = (uint32_t)((mirrored + tid) & a.cap_mask);
           pe.nchunks = rc.nchunks;
-          pe.opinfo = (rc.op_id & 0xffu) | ((uint32_t)rc.sel << 8) | ((rc.status == GPUOS_OK ? 1u : 0u) << 9);
+          pe.opinfo = (rc.op_id & 0xffu) | ((uint32_t)rc.sel << 8) | ((rc.status == GPUOS_OK ? 1u : 0u) << 9) |
+                      ((uint32_t)(((mirrored + tid) >> a.cap_shift) & 0x3ffu) << 16);
           // tasks of a program that a run-time kernel holds as native code go to that kernel's ring
           const uint32_t prog = rc.impl - GPUOS_IMPL_PROGRAM_BASE;
           pe.route = (rc.status == GPUOS_OK && rc.impl >= GPUOS_IMPL_PROGRAM_BASE && prog < GPUOS_MAX_PROGRAMS && s->native[prog] != 0) ? 1u : 0u;
@@ -557,10 +617,15 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         }
       }
       // write the records into the device mirror (write-through stores), held-back ones included
+      // each record leaves with a check word of its own over what it now holds (resolved fields, ticket)
       for (uint32_t p = tid; p < n * 16u; p += kThreads) {
         const uint32_t rix = p >> 4, part = p & 15u;
         const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
-        Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, ((const v4i*)&s->rec[rix])[part]);
+        v4i q = ((const v4i*)&s->rec[rix])[part];
+        if (part == 15u) q[3] = 0;
+        const uint32_t x = record_piece_sum(q, part);              // the 16 lanes of a record share a row
+        if (part == 15u) q[3] = (int)(record_check_seed(mirrored + rix) - x);
+        Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, q);
       }
       const uint64_t before = uc.w[0] + uc.w[1];
       dispatcher_publish_all(a, s, s->npub, uc, s->npub_second != 0);       // drains the stores above as well

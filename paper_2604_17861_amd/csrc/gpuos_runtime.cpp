@@ -827,6 +827,8 @@ int launch_first_worker(gpuos_ctx* c, int compute_units, size_t n_units) {
   a.unit_mask = (uint32_t)(n_units - 1);
   a.unit_shift = 0;
   while (((size_t)1 << a.unit_shift) < n_units) ++a.unit_shift;
+  a.cap_shift = 0;
+  while ((1u << a.cap_shift) < c->cap) ++a.cap_shift;
   a.idle_exit_ticks = (uint64_t)cfg.idle_exit_ms * 100000ull;     // 100 MHz counter
   a.progs = c->progs;
   a.trace = c->trace; a.opcount = c->opcount; a.trace_mask = c->trace_mask;
