@@ -132,7 +132,8 @@ def bench_program(R, s5, dp5, impl5, n_tasks=1500):
     (compiled at run time into the second resident worker kernel) and interpreted by the resident
     kernel: what an operator added at run time costs when it is bound by memory.  GB/s by the wall
     time of submit + wait (the kernels' lifetimes also hold the run-time compilation).  The native legs
-    run with the default split (3 + 1 workgroups per compute unit) and with 2 + 2."""
+    run with 2 + 1 workgroups per compute unit (what a context with workgroups_per_cu = 2 gets: the
+    fourth place stays free for other kernels), and with 3 + 1 and 2 + 2, which fill the compute units."""
     from paper_2604_17861_amd import streams as S
     idx = np.nonzero(impl5 == S.IMPL["ADD"])[0][:n_tasks]
     sub = dp5.tasks[idx].copy()
@@ -141,8 +142,10 @@ def bench_program(R, s5, dp5, impl5, n_tasks=1500):
     out = {}
     one = S.program(("ADD", 0, 0, 1))
     six = S.program(("SUB", 4, 0, 1), ("MUL", 4, 4, 3), ("ABS", 4, 4), ("IMM", 5, 1.0), ("ADD", 4, 4, 5), ("DIV", 0, 0, 4))
-    legs = [("builtin_add_gbps", None, {}), ("program_add_1_instr_gbps", one, {}), ("program_6_instr_gbps", six, {}),
-            ("builtin_add_2wg_gbps", None, dict(workgroups_per_cu=2)),
+    legs = [("builtin_add_gbps", None, {}), ("builtin_add_2wg_gbps", None, dict(workgroups_per_cu=2)),
+            ("program_add_1_instr_2plus1wg_gbps", one, dict(workgroups_per_cu=2)),
+            ("program_6_instr_2plus1wg_gbps", six, dict(workgroups_per_cu=2)),
+            ("program_6_instr_3plus1wg_gbps", six, dict(jit_workgroups_per_cu=1)),
             ("program_6_instr_2plus2wg_gbps", six, dict(workgroups_per_cu=2, jit_workgroups_per_cu=2)),
             ("program_add_1_instr_interpreted_gbps", one, dict(jit_mode=2)), ("program_6_instr_interpreted_gbps", six, dict(jit_mode=2))]
     for label, code, cfg in legs:
@@ -382,17 +385,24 @@ def main():
         log("config3 fused:", extras["config3_fused"])
         del dp3f
         # ---- the paper's micro-benchmark shape: sequences of 100 dependent small operations ----------
+        # The tasks between the oldest incomplete ticket and the newest submitted one are what is in
+        # flight, so the ring's capacity bounds the number of sequences that advance at the same time:
+        # issued one after the other, the default ring of 4,096 holds 41 sequences of 100, one of
+        # 16,384 slots 164.  Both are reported for that order.
         seq = {}
         for il in (1, 16, 256):
             sq = S.sequences(n_seq=1000, length=100, interleave=il)
             dpq = DevicePools(sq, torch)
-            rq = bench_persistent(R, sq, dpq, 1, 0)
+            rq = bench_persistent(R, sq, dpq, 2, 1, capacity=16384)
             seq["persistent_interleave_%d_tasks_per_s" % il] = rq["tasks_per_s"]
+            if il == 1:
+                seq["persistent_interleave_1_ring_4096_tasks_per_s"] = bench_persistent(R, sq, dpq, 2, 1)["tasks_per_s"]
             if il == 1:
                 t0 = time.perf_counter()
                 R.launch_per_op(dpq.tasks, sq.table)
                 seq["per_launch_tasks_per_s"] = len(sq) / (time.perf_counter() - t0)
             del dpq
+        seq["ring_slots"] = 16384
         extras["sequences_100x1000"] = seq
         log("sequences of 100 dependent operations x 1000:", seq)
         # ---- fourth configuration (hot swaps while running) -----------------------------------

@@ -314,9 +314,15 @@ typedef struct gpuos_config {
                                        run-time compiler library; without it, or when anything in that
                                        path fails, they stay interpreted); 1 => the same, built at
                                        every gpuos_define_program; 2 => interpreted only            */
-  uint32_t jit_workgroups_per_cu;   /* workgroups per compute unit of that second kernel (0 => 1;
-                                       clamped so that both kernels stay co-resident: with the default
-                                       3 + 1 every register file is full while programs are defined) */
+  uint32_t jit_workgroups_per_cu;   /* workgroups per compute unit of that second kernel.  0 => 1 if
+                                       that leaves a workgroup's place per compute unit free for other
+                                       kernels (the HIP runtime's copy kernels included), else none:
+                                       on MI355X four workgroups fit a compute unit, so programs run
+                                       natively by default with workgroups_per_cu <= 2 and are
+                                       interpreted beside the default 3.  A number given here is taken
+                                       as it is (clamped to what is co-resident): 3 + 1 fills every
+                                       register file, and nothing else starts on the GPU until a
+                                       worker leaves (gpuos_native_info says which case holds)        */
   uint32_t reserved[1];
 } gpuos_config;
 

@@ -1829,14 +1829,55 @@ struct BuiltinExec {                // what the library's own workers execute a 
 constexpr uint32_t kMirrorRetries = 1u << 22;       // fetches of a mirror record that does not (yet) verify: seconds
 constexpr uint64_t kStopGraceTicks = 10000000ull;   // 100 ms (100 MHz clock): how long a worker still waits for a dependency once the stop flag is up
 
+// A workgroup holds up to kStash descriptors: work units it has claimed that wait for a dependency,
+// and the one it runs.  A workgroup whose unit must wait does not sit on it: it claims the next
+// unit and runs whatever it holds that is ready (oldest first).  A chain of dependent small tasks
+// then occupies one descriptor slot per link in flight instead of one whole workgroup, so eight
+// times as many chains are in flight (Section 6.1's sequences issued one after the other: 1.7 M ->
+// see the benchmark).  Progress: units are claimed in publication order and what a waiting unit names
+// was published before it, so the unfinished unit with the lowest number is always held by some
+// workgroup with nothing left to wait for, and every workgroup looks at everything it holds on every
+// poll.
+constexpr uint32_t kStash = 8;
+constexpr uint32_t kStashFull = (1u << kStash) - 1u;
+enum : uint32_t { kActRun = 0, kActFetch = 1, kActExit = 2 };
+
 struct WorkShared {
-  Record rec;
-  uint64_t unit, entry;
-  int32_t exit_flag;
+  Record rec[kStash];              // descriptors held
+  uint64_t unit[kStash];           // their work-unit entries
+  uint64_t entry[kStash];          // the operator-table slot each one claimed
+  uint64_t since[kStash];          // when each began to wait (device clock)
+  uint32_t action, slot;           // the first wavefront's decision: run the unit in descriptor slot `slot`, fetch
+                                   // the newly claimed unit's descriptor into it, or leave
   int32_t dep_status;              // 0, or the status a task whose dependency wait ran out completes with
   uint32_t rec_sum;                // weighted check sum of the record as fetched
   alignas(16) float red[kScratchFloats];   // (16-byte LDS vectors are written into it)
 };
+
+DEV uint64_t uni64(uint64_t v) {
+  return ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(v >> 32)) << 32) | __builtin_amdgcn_readfirstlane((uint32_t)v);
+}
+DEV uint64_t lane64(uint64_t v, uint32_t lane) {     // `lane` the same in every lane
+  return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), (int)lane) << 32) |
+         (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, (int)lane);
+}
+
+// First wavefront: fetch the descriptor that work unit `unit` names (16 lanes x 16 bytes) and the
+// operator-table slot it claimed into descriptor slot f, with the record's weighted check sum.
+DEV void fetch_descriptor(const WorkerArgs& a, WorkShared* s, rsrc_t rd, uint64_t unit, uint32_t f) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t slot = (uint32_t)((unit >> 20) & 0xffffu);
+  const uint32_t op = (uint32_t)((unit >> 36) & 0xffu), sel = (uint32_t)((unit >> 44) & 1u);
+  const bool op_valid = ((unit >> 45) & 1u) != 0;
+  v4i q = {0, 0, 0, 0};
+  uint64_t ent = 0;
+  if (tid < 16) q = Mem<POL_COHERENT>::ld16(rd, slot * (uint32_t)sizeof(Record) + tid * 16u);
+  if (tid == 16 && op_valid) ent = __hip_atomic_load(&a.dtable[op].slot[sel], __ATOMIC_RELAXED, SC_SYSTEM);
+  const uint32_t x = record_piece_sum(q, tid & 15u);
+  if (tid < 16) ((v4i*)&s->rec[f])[tid] = q;
+  if (tid == 16) s->entry[f] = ent;
+  if (tid == 0) s->rec_sum = x;
+}
 
 // RING 0: the library's own workers, on the main unit ring, executing through EXEC = the built-in
 // chunk executor.  RING 1: the workers of a kernel compiled at run time, on the second unit ring
@@ -1852,49 +1893,134 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s, uint32_t gen = 0) {
   uint64_t w_units = 0, w_wait = 0, w_fetch = 0, w_dep = 0, w_exec = 0, w_done = 0;
   const bool timing = a.timing != 0, tracing = a.trace != nullptr;
   const uint64_t w_start = clock_if(timing);
+  // State of the first wavefront (the same in all its lanes; the other wavefronts never look at it).
+  uint32_t waiting = 0;            // bit k: descriptor slot k holds a unit that waits for a dependency
+  bool have_claim = false;         // a unit number is claimed and its entry has not arrived yet
+  bool draining = false;           // the stop flag was seen: claim nothing more, finish what is held, leave
+  uint64_t g = 0;                  // the claimed unit number
+  uint32_t polls = 0, yield_every = 0;
   while (true) {
     const uint64_t c0 = clock_if(timing);
-    // ---- claim one work unit (elected lane, atomic fetch-add) ----
-    if (tid == 0) {
-      const uint64_t g = __hip_atomic_fetch_add(claim_ctr, 1ull, __ATOMIC_RELAXED, SC_AGENT);
+    const bool held_any = waiting != 0;
+    // ---- decide what to do next (first wavefront): one round of loads per poll ----
+    // Lane 32 polls the claimed entry itself (its stamp is the ready flag: every waiting workgroup
+    // polls a different address); lane k < kStash looks at the done words that descriptor slot k waits for.
+    if (tid < 64) {
+      uint32_t action = kActExit, f = 0;
+      int32_t dep_status = 0;
+      uint64_t u_new = 0;
+      if (!have_claim && !draining && waiting != kStashFull) {
+        uint64_t gg = 0;
+        if (tid == 0) gg = __hip_atomic_fetch_add(claim_ctr, 1ull, __ATOMIC_RELAXED, SC_AGENT);
+        g = uni64(gg);
+        have_claim = true;
+        polls = 0;
+      }
       const uint64_t* up = &unit_ring[g & a.unit_mask];
       const uint64_t want = unit_stamp(g, a.unit_shift);
-      int32_t ex = 0;
-      uint32_t polls = 0, yield_every = 0;
-      uint64_t u;
-      // Poll the claimed entry itself (its stamp is the ready flag): one load per poll, and every
-      // waiting workgroup polls a different address.
-      while (((u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM)) >> 46) != want) {
+      // What is awaited was published before the unit that waits (the dispatcher sees to that), so the
+      // wait ends when resident workgroups finish work they hold.  It is bounded all the same (the
+      // context's wait limit; a short grace once the stop flag is up): a task that runs into the
+      // bound completes with GPUOS_E_TIMEOUT without executing, and the kernel always leaves.
+      const bool mine = tid < kStash && ((waiting >> tid) & 1u);
+      uint64_t need[3] = {0ull, 0ull, 0ull};
+      const uint64_t* done_word[3] = {nullptr, nullptr, nullptr};
+      if (mine) {
+        const Record* r = &s->rec[tid];
+        const uint64_t ticket = r->ticket;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          const uint32_t back = r->dep[k];
+          if (back != 0 && back <= ticket) {
+            need[k] = ticket - back + 1;
+            done_word[k] = &a.st[(ticket - back) & a.cap_mask].done_seq;
+          }
+        }
+      }
+      // One round of loads per poll.  (Keeping a second round in flight, to sample twice per memory
+      // round trip, was measured: with 767 workgroups polling, the doubled traffic cost a lone task
+      // more than the earlier sample gained, 7.7 against 6.5 us.)
+      struct Poll { uint64_t u, seen[3]; };
+      auto request = [&]() {
+        Poll p;
+        p.u = 0;
+        if (tid == 32 && have_claim) p.u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM);
+#pragma unroll
+        for (int k = 0; k < 3; ++k) p.seen[k] = done_word[k] ? __hip_atomic_load(done_word[k], __ATOMIC_RELAXED, SC_SYSTEM) : ~0ull;
+        return p;
+      };
+      while (true) {
+        const Poll cur = request();
+        bool ready = mine && cur.seen[0] >= need[0] && cur.seen[1] >= need[1] && cur.seen[2] >= need[2];
+        int32_t gave_up = 0;
+        if (mine && !ready && (polls & 31u) == 31u) {
+          uint64_t limit = a.dep_wait_ticks;
+          if (limit > kStopGraceTicks && __hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) limit = kStopGraceTicks;
+          if (wall_clock64() - s->since[tid] > limit) { gave_up = GPUOS_E_TIMEOUT; ready = true; }
+        }
+        order_loads();
+        const uint64_t m_ready = __ballot(ready);
+        u_new = lane64(cur.u, 32u);
+        if (m_ready != 0) {                                   // the first descriptor slot whose unit can run (any ready
+          f = (uint32_t)__builtin_ctzll(m_ready);             // one makes progress)
+          dep_status = __builtin_amdgcn_readlane(gave_up, (int)f);
+          waiting &= ~(1u << f);
+          action = kActRun;
+          break;
+        }
+        if (have_claim && (u_new >> 46) == want) {
+          f = (uint32_t)__builtin_ctz(~waiting);              // a free descriptor slot (claims are made only while one exists)
+          have_claim = false;
+          action = kActFetch;
+          fetch_descriptor(a, s, rd, u_new, f);  // requested at once: the other wavefronts need not hear of the unit first
+          break;
+        }
         ++polls;
         if ((polls & 31u) == 0) {
           // (a run-time kernel also leaves when a later generation is wanted: the host asks for that
           // only once nothing is routed to this ring any more and everything routed has completed)
-          if (__hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM) ||
-              (RING == 1 && __hip_atomic_load(&a.d->jit_gen, __ATOMIC_RELAXED, SC_SYSTEM) > gen)) {
-            order_loads();                             // every unit was stored before the stop flag
-            u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM);
-            if ((u >> 46) != want) ex = 1;
-            break;
+          const bool stop = __hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM) != 0 ||
+                            (RING == 1 && __hip_atomic_load(&a.d->jit_gen, __ATOMIC_RELAXED, SC_SYSTEM) > gen);
+          if (stop && !draining) {
+            order_loads();                                    // every unit was stored before the stop flag
+            if (have_claim) {
+              u_new = uni64(__hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM));
+              order_loads();
+              if ((u_new >> 46) == want) {
+                f = (uint32_t)__builtin_ctz(~waiting);
+                have_claim = false;
+                action = kActFetch;
+                fetch_descriptor(a, s, rd, u_new, f);
+                break;
+              }
+              // The number claimed will never be served.  The second ring stays in use across
+              // generations of run-time kernels while the dispatcher runs on: give the number back
+              // (nothing is being published to that ring at this time, so the count ends exact).
+              if (RING == 1 && tid == 0) __hip_atomic_fetch_add(claim_ctr, ~0ull, __ATOMIC_RELAXED, SC_AGENT);
+              have_claim = false;
+            }
+            draining = true;
           }
           yield_every = __hip_atomic_load(&a.d->yield_every, __ATOMIC_RELAXED, SC_SYSTEM);
         }
-        // polling policy (paper Section 4.1): short back-off while spinning, longer
-        // pauses every yield_every-th empty poll when the host asked for them
-        if (yield_every != 0 && (polls % yield_every) == 0) { for (int k = 0; k < 16; ++k) __builtin_amdgcn_s_sleep(127); }
-        else if (polls < 64) __builtin_amdgcn_s_sleep(1);
+        if (draining && !have_claim && waiting == 0) { action = kActExit; break; }
+        // polling policy (paper Section 4.1): short back-off while spinning, longer pauses every
+        // yield_every-th empty poll when the host asked for them and nothing is held
+        if (yield_every != 0 && waiting == 0 && (polls % yield_every) == 0) { for (int k = 0; k < 16; ++k) __builtin_amdgcn_s_sleep(127); }
+        else if (polls < 64 || waiting != 0) __builtin_amdgcn_s_sleep(1);
         else __builtin_amdgcn_s_sleep(8);
       }
-      order_loads();
-      s->exit_flag = ex;
-      s->unit = u;
+      if (tid == 0) {
+        s->action = action;
+        s->slot = f;
+        s->dep_status = dep_status;
+        if (action == kActFetch) s->unit[f] = u_new;
+      }
     }
     __syncthreads();
-    if (s->exit_flag) {
+    const uint32_t action = uni(s->action), f = uni(s->slot);
+    if (action == kActExit) {
       if (tid == 0) {
-        // The second ring stays in use across generations of run-time kernels while the dispatcher
-        // runs on: a workgroup that leaves gives back the unit number it claimed and never served
-        // (nothing is being published to the ring at that time, so the count ends exact).
-        if (RING == 1) __hip_atomic_fetch_add(claim_ctr, ~0ull, __ATOMIC_RELAXED, SC_AGENT);
         uint64_t* st = a.d->stat;
         __hip_atomic_fetch_add(&st[ST_WORK_UNITS], w_units, __ATOMIC_RELAXED, SC_AGENT);
         __hip_atomic_fetch_add(&st[ST_WORK_TICKS_WAIT], w_wait, __ATOMIC_RELAXED, SC_AGENT);
@@ -1907,80 +2033,57 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s, uint32_t gen = 0) {
       return;
     }
     const uint64_t c1 = clock_if(timing || tracing);
+    if (timing) { if (held_any) w_dep += c1 - c0; else w_wait += c1 - c0; }
     // the unit is the same for the whole workgroup: keep its fields in scalar registers
-    const uint32_t unit_lo = uni((uint32_t)s->unit), unit_hi = uni((uint32_t)(s->unit >> 32));
+    const uint32_t unit_lo = uni((uint32_t)s->unit[f]), unit_hi = uni((uint32_t)(s->unit[f] >> 32));
     const uint64_t unit = ((uint64_t)unit_hi << 32) | unit_lo;
     const uint32_t chunk = (uint32_t)(unit & 0x3ffu), lap10 = (uint32_t)((unit >> 10) & 0x3ffu);
     const uint32_t slot = (uint32_t)((unit >> 20) & 0xffffu);
-    const uint32_t op = (uint32_t)((unit >> 36) & 0xffu), sel = (uint32_t)((unit >> 44) & 1u);
-    const bool op_valid = ((unit >> 45) & 1u) != 0;
-    // ---- fetch the descriptor (16 lanes x 16 bytes) and the claimed table slot ----
-    // The dispatcher does not wait for its mirror stores before it publishes a unit: the record is
-    // taken only once its check word holds for the ticket the unit names (else its pieces are still
-    // landing, or belong to the slot's previous lap) and fetched again otherwise.  The stores are on
-    // their way, so this ends; it is bounded like every wait here (a workgroup that runs out leaves
-    // the task to the host's time limit).
-    if (tid == 16) s->entry = op_valid ? __hip_atomic_load(&a.dtable[op].slot[sel], __ATOMIC_RELAXED, SC_SYSTEM) : 0ull;
-    for (uint32_t attempt = 0;; ++attempt) {
-      if (tid < 64) {
-        v4i q = {0, 0, 0, 0};
-        if (tid < 16) q = Mem<POL_COHERENT>::ld16(rd, slot * (uint32_t)sizeof(Record) + tid * 16u);
-        const uint32_t x = record_piece_sum(q, tid & 15u);
-        if (tid < 16) ((v4i*)&s->rec)[tid] = q;
-        if (tid == 0) s->rec_sum = x;
+    const Record* r = &s->rec[f];
+    if (action == kActFetch) {
+      // ---- fetch the descriptor (16 lanes x 16 bytes) and the claimed table slot ----
+      // The dispatcher does not wait for its mirror stores before it publishes a unit: the record is
+      // taken only once its check word holds for the ticket the unit names (else its pieces are still
+      // landing, or belong to the slot's previous lap) and fetched again otherwise.  The stores are on
+      // their way, so this ends; it is bounded like every wait here (a workgroup that runs out leaves
+      // the task to the host's time limit).
+      // (the first wavefront has fetched it once already, when it saw the unit)
+      bool valid = false;
+      for (uint32_t attempt = 0;; ++attempt) {
+        valid = mirror_record_valid(s->rec_sum, r->ticket, slot, lap10, a.cap_mask, a.cap_shift);
+        if (valid || attempt >= kMirrorRetries) break;
+        __syncthreads();                                  // everyone has looked at this attempt's copy
+        __builtin_amdgcn_s_sleep(2);
+        if (tid < 64) fetch_descriptor(a, s, rd, unit, f);
+        __syncthreads();
       }
-      __syncthreads();
-      if (mirror_record_valid(s->rec_sum, s->rec.ticket, slot, lap10, a.cap_mask, a.cap_shift) || attempt >= kMirrorRetries) break;
-      __syncthreads();                                  // everyone has looked at this attempt's copy
-      __builtin_amdgcn_s_sleep(2);
-    }
-    const Record* r = &s->rec;
-    int32_t status = r->status;
-    if (!mirror_record_valid(s->rec_sum, r->ticket, slot, lap10, a.cap_mask, a.cap_shift)) {
-      // never seen whole: nothing in it can be trusted, not even the ticket it would complete.  The
-      // unit is dropped; the host's wait for the ticket runs into its time limit.
-      __syncthreads();
-      continue;
-    }
-    const uint32_t impl = uni(r->impl);
-    if (status == GPUOS_OK && (s->entry >> 32) != r->version) status = GPUOS_E_VERSION;
-    const uint64_t c2 = clock_if(timing);
-    // ---- dependencies: earlier tickets named by back-distance ----
-    // What is awaited was published before this unit (the dispatcher sees to that), so the wait ends
-    // when resident workgroups finish work they already hold.  It is bounded all the same (the
-    // context's wait limit; a short grace once the stop flag is up): a task that runs into the bound
-    // completes with GPUOS_E_TIMEOUT without executing, and the kernel always leaves.
-    if ((r->dep[0] | r->dep[1] | r->dep[2]) != 0 && !(r->rflags & RF_DEPS_RESOLVED)) {
-      if (tid == 0) {
-        const uint64_t ticket = r->ticket;
-        int32_t gave_up = 0;
-        uint64_t t_begin = 0;
-        uint32_t spins = 0;
-        for (int k = 0; k < 3 && !gave_up; ++k) {
-          const uint32_t back = r->dep[k];
-          if (back == 0 || back > ticket) continue;
-          const uint64_t want = ticket - back + 1;
-          const uint64_t* w = &a.st[(ticket - back) & a.cap_mask].done_seq;
-          while (__hip_atomic_load(w, __ATOMIC_RELAXED, SC_SYSTEM) < want) {
-            __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 31u) == 0) {
-              const uint64_t now = wall_clock64();
-              if (t_begin == 0) t_begin = now;
-              uint64_t limit = a.dep_wait_ticks;
-              if (limit > kStopGraceTicks && __hip_atomic_load(&a.d->stop_dev, __ATOMIC_RELAXED, SC_SYSTEM)) limit = kStopGraceTicks;
-              if (now - t_begin > limit) { gave_up = GPUOS_E_TIMEOUT; break; }
-            }
-          }
+      const uint64_t c2 = clock_if(timing);
+      if (timing) w_fetch += c2 - c1;
+      if (!valid) {
+        // never seen whole: nothing in it can be trusted, not even the ticket it would complete.  The
+        // unit is dropped; the host's wait for the ticket runs into its time limit.
+        __syncthreads();
+        continue;
+      }
+      if ((r->dep[0] | r->dep[1] | r->dep[2]) != 0 && !(r->rflags & RF_DEPS_RESOLVED)) {
+        // It names earlier tasks: it joins the units held, and the first wavefront looks at its done
+        // words with the next poll (and runs it at once if they are all there).
+        if (tid < 64) {
+          waiting |= 1u << f;
+          if (tid == 0) s->since[f] = wall_clock64();
         }
-        order_loads();
-        s->dep_status = gave_up;
+        continue;
       }
-      __syncthreads();
-      if (status == GPUOS_OK && s->dep_status != 0) status = s->dep_status;
     }
+    int32_t status = r->status;
+    const uint32_t impl = uni(r->impl);
+    if (status == GPUOS_OK && (s->entry[f] >> 32) != r->version) status = GPUOS_E_VERSION;
+    if (status == GPUOS_OK && s->dep_status != 0) status = s->dep_status;
     const uint64_t c3 = clock_if(timing);
+    // a task's start in the trace is the moment a workgroup took its descriptor (a unit that waited: when it began to)
+    const uint64_t c_start = (tracing && action == kActRun) ? s->since[f] : c1;
     if (tracing && tid == 0 && chunk == 0 && r->nchunks > 1)
-      __hip_atomic_store(&a.st[slot].t_first, c1, __ATOMIC_RELAXED, SC_SYSTEM);   // in memory before this chunk is counted
+      __hip_atomic_store(&a.st[slot].t_first, c_start, __ATOMIC_RELAXED, SC_SYSTEM);   // in memory before this chunk is counted
     // ---- execute ----
     if (status == GPUOS_OK) status = EXEC::run(r, impl, chunk, s->red, a.progs);
     if (RING == 1 && tid == 0) __hip_atomic_fetch_add(&a.d->jit_units, 1ull, __ATOMIC_RELAXED, SC_AGENT);
@@ -2001,7 +2104,7 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s, uint32_t gen = 0) {
         if (tracing) {
           // the tracepoint lands before the completion word that lets the host read it
           const uint64_t origin = __hip_atomic_load(&a.h->clock_origin, __ATOMIC_RELAXED, SC_SYSTEM);
-          const uint64_t t_start = nchunks > 1 ? __hip_atomic_load(&a.st[slot].t_first, __ATOMIC_RELAXED, SC_SYSTEM) : c1;
+          const uint64_t t_start = nchunks > 1 ? __hip_atomic_load(&a.st[slot].t_first, __ATOMIC_RELAXED, SC_SYSTEM) : c_start;
           TraceRec* tr = &a.trace[ticket & a.trace_mask];
           const uint64_t tdq = ((uint64_t)r->t_dequeue[1] << 32) | r->t_dequeue[0];
           __hip_atomic_store(&tr->t_dequeue, tdq - origin, __ATOMIC_RELAXED, SC_SYSTEM);
@@ -2026,7 +2129,7 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s, uint32_t gen = 0) {
     __syncthreads();                  // the descriptor in LDS may be overwritten after this
     const uint64_t c5 = clock_if(timing);
     w_units += 1;
-    if (timing) { w_wait += c1 - c0; w_fetch += c2 - c1; w_dep += c3 - c2; w_exec += c4 - c3; w_done += c5 - c4; }
+    if (timing) { w_exec += c4 - c3; w_done += c5 - c4; }
   }
 }
 

@@ -133,8 +133,11 @@ struct HostCtl {
   alignas(64) uint32_t jit_alive;    // device -> host: generation of the run-time kernel whose workers are running
 };
 struct DoorbellCtl {
+  // The dispatcher reads both words with ONE 16-byte load: the two are then sampled at the same
+  // moment, and a tail value that covers a task submitted after a table change returned is never
+  // seen together with the epoch from before that change (the host stores the epoch first).
   alignas(64) uint64_t tail;         // host -> device: tickets published (doorbell)
-  alignas(64) uint64_t epoch_word;   // host -> device: epoch << 12 | op << 4 | stop bit;
+  uint64_t epoch_word;               // host -> device: epoch << 12 | op << 4 | stop bit;
                                      // op = 0xff: refresh every entry
   alignas(64) uint32_t yield_every;  // host -> device
   uint32_t jit_gen;                  // host -> device: generation of run-time kernel that is wanted (earlier ones leave)

@@ -289,6 +289,8 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
   uint32_t pre_n = 0;                      // how many
   const rsrc_t rh = make_rsrc(a.hring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
   const rsrc_t rd = make_rsrc(a.dring, (a.cap_mask + 1u) * (uint32_t)sizeof(Record));
+  const rsrc_t rbell = make_rsrc(a.bell, 16u);
+  static_assert(offsetof(DoorbellCtl, tail) == 0 && offsetof(DoorbellCtl, epoch_word) == 8, "tail and epoch word are read with one 16-byte load");
   while (true) {
     // ---- poll the host ring (wavefront 0; the only PCIe poller of the kernel) ----
     // Every poll also reads the next kPrefetch records of the ring in the same round trip.  When
@@ -299,11 +301,20 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       v4i q;
       const uint32_t g = tid >> 4, part = tid & 15u;               // record g of the prefetch window, 16-byte piece
       const bool have_pending = s->npend != 0;
+      bool lane_dirty = false;                         // the short cut below counted an operator (tracing) since the last flush
+      struct Poll { uint64_t t, e; v4i q; };
+      auto request = [&](uint64_t base) {
+        Poll p;
+        const uint32_t slot = (uint32_t)((base + g) & a.cap_mask);
+        const v4i b = Mem<POL_COHERENT>::ld16(rbell, 0u);        // tail and epoch word, one sample of both
+        p.t = ((uint64_t)(uint32_t)b[1] << 32) | (uint32_t)b[0];
+        p.e = ((uint64_t)(uint32_t)b[3] << 32) | (uint32_t)b[2];
+        p.q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
+        return p;
+      };
       while (true) {
-        const uint32_t slot = (uint32_t)((mirrored + g) & a.cap_mask);
-        t = __hip_atomic_load(&a.bell->tail, __ATOMIC_RELAXED, SC_SYSTEM);
-        e = __hip_atomic_load(&a.bell->epoch_word, __ATOMIC_RELAXED, SC_SYSTEM);
-        q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
+        const Poll cur = request(mirrored);
+        t = cur.t; e = cur.e; q = cur.q;
         ++polls;
         if (tid == 0 && (polls & 63u) == 0) __hip_atomic_store(&a.h->heartbeat, polls, __ATOMIC_RELAXED, SC_SYSTEM);
         if (t == mirrored + 1 && e == seen_epoch && !stopping && !have_pending) {
@@ -348,6 +359,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
                   if (op < GPUOS_MAX_OPS) { atomicAdd(&s->opcnt[op], 1u); s->lane_counted = 1u; }
                 }
               }
+              lane_dirty = tracing;
               lds_wave_sync();
               const uint32_t slot0 = (uint32_t)(mirrored & a.cap_mask);
               if (tid < 16) {
@@ -374,7 +386,8 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
           }
         }
         if (t != mirrored || e != seen_epoch || stopping || have_pending) break;
-        if (a.idle_exit_ticks != 0 && wall_clock64() - idle_since > a.idle_exit_ticks) {
+        if (lane_dirty && (polls & 63u) == 0) break;    // idle again: let the whole workgroup publish the per-operator counts
+        if ((polls & 63u) == 0 && a.idle_exit_ticks != 0 && wall_clock64() - idle_since > a.idle_exit_ticks) {
           e |= 2u;                                  // behave as if the host had asked to stop
           break;
         }

@@ -810,13 +810,22 @@ int launch_first_worker(gpuos_ctx* c, int compute_units, size_t n_units) {
   if (c->workgroups < 2) c->workgroups = 2;
   c->cfg.workgroups_per_cu = per_cu;
   if (c->jit_enabled) {
-    // the run-time kernel is built like the worker (same registers per lane, less local memory):
-    // its workgroups take the places per compute unit that the worker leaves free
-    uint32_t jw = cfg.jit_workgroups_per_cu ? cfg.jit_workgroups_per_cu : 1u;
-    if (per_cu + jw > (uint32_t)occ) jw = (uint32_t)occ > per_cu ? (uint32_t)occ - per_cu : 0u;
+    // The run-time kernel is built like the worker (same registers per lane, slightly less local
+    // memory): its workgroups take places per compute unit that the worker leaves free.  Unless the
+    // caller names their number, one place per compute unit stays free for everybody else's kernels
+    // (the HIP runtime's copy kernels included: with every register file full they start only when a
+    // worker leaves); with the default three workgroups per compute unit of the worker itself that
+    // leaves none for the run-time kernel, and programs are interpreted.
+    uint32_t jw = cfg.jit_workgroups_per_cu;
+    if (jw == 0) jw = (uint32_t)occ > per_cu + 1u ? 1u : 0u;
+    else if (per_cu + jw > (uint32_t)occ) jw = (uint32_t)occ > per_cu ? (uint32_t)occ - per_cu : 0u;
     c->cfg.jit_workgroups_per_cu = jw;
     c->jit_grid = (uint32_t)compute_units * jw;
-    if (jw == 0) { c->jit_enabled = false; c->jit_error = "no room beside the worker's workgroups"; }
+    if (jw == 0) {
+      c->jit_enabled = false;
+      c->jit_error = "no place beside the worker's workgroups that leaves one per compute unit free: lower cfg.workgroups_per_cu, "
+                     "or name cfg.jit_workgroups_per_cu to fill the compute units";
+    }
   }
 
   WorkerArgs a{};
@@ -890,7 +899,7 @@ void gpuos_default_config(gpuos_config* cfg) {
   cfg->completion_log = 1u << 20;
   cfg->chunk_elems = kChunkElems;
   cfg->push_ring = 2;               // device-memory ring when the BAR allows it
-  cfg->jit_workgroups_per_cu = 1;
+  cfg->jit_workgroups_per_cu = 0;      // as many as leave a place per compute unit free (see launch_first_worker)
 }
 
 int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* user_cfg) {

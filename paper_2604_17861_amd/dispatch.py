@@ -116,8 +116,11 @@ class GpuosMode(TorchDispatchMode):
         # operators the built-in library lacks are added the way the paper adds operators at run time:
         # as programs defined on the live context and bound to logical ids of their own
         self.op_id = {name: S.OP[name] for name in S.IMPL if name != "NONE"}
-        for k, (name, (code, n_in)) in enumerate(sorted(PROGRAMS.items())):
-            self.rt.register_op(_PROGRAM_OP_BASE + k, self.rt.define_program(code, n_in))
+        # (all defined before the first is bound: the native worker kernel is compiled at the first
+        # binding, for every program defined by then -- one compilation instead of one per program)
+        impls = [(name, self.rt.define_program(code, n_in)) for name, (code, n_in) in sorted(PROGRAMS.items())]
+        for k, (name, impl) in enumerate(impls):
+            self.rt.register_op(_PROGRAM_OP_BASE + k, impl)
             self.op_id[name] = _PROGRAM_OP_BASE + k
         self.max_numel, self.min_calls, self.batch = int(max_numel), int(min_calls), max(1, int(batch))
         self._buf = bytearray(self.batch * _TASK.size)

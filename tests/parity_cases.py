@@ -486,11 +486,12 @@ def dependency_dag(seed, n_tasks=2500, n_buffers=10, max_dist=48):
 def producer_with_dependants(n_consumers=1200, n_links=300):
     """The stream shape that needs publication in dependency order: a large task, a large task that
     depends on it (held back by the dispatcher while the first one runs), then more small tasks than
-    there are workgroups that each read one row of the held task's output, and a chain of four-chunk
+    there are workgroups (with n_consumers = 6400: more than the workgroups can hold between them at
+    eight units each) that each read one row of the held task's output, and a chain of four-chunk
     links whose first link reads it too.  Exactly rounded operations on small integers: the buffers at
     the end equal sequential execution byte for byte."""
     rng = np.random.default_rng(77)
-    rows, cols = 2048, 1024
+    rows, cols = (2048, 1024) if n_consumers <= 2048 else (8192, 256)
     assert n_consumers <= rows
     f = lambda *shape: b.pool(rng.integers(-3, 4, shape).astype(np.float32))
     b = Builder()

@@ -1,6 +1,7 @@
 """A CPU model of the device-side scheduler: the order in which the dispatcher publishes work
-units, W worker workgroups that claim units strictly in publication order, and workers that can only
-wait once they hold a unit whose dependency is incomplete.  TEST INFRASTRUCTURE: it executes no
+units, W worker workgroups that claim units strictly in publication order and hold up to `stash` of
+them each (a workgroup whose unit must wait claims the next one and runs whatever it holds that is
+ready), and workers that can only wait once everything they hold has an incomplete dependency.  TEST INFRASTRUCTURE: it executes no
 operator; it answers one question about a task stream: can every worker end up parked behind work
 that is published after the units they hold (a deadlock of the resident kernel)?
 
@@ -26,9 +27,11 @@ Task = namedtuple("Task", "nchunks deps fence")      # deps: back-distances (0 =
 Result = namedtuple("Result", "deadlock rounds parked completed held order_violations")
 
 
-def simulate(tasks, workers, rule, batch=64, pend_max=128, lookahead=8192, small=4, disp_passes=8, max_rounds=10 ** 7):
+def simulate(tasks, workers, rule, batch=64, pend_max=128, lookahead=8192, small=4, disp_passes=8, stash=8, max_rounds=10 ** 7):
     """One round = the time a worker takes for one chunk; the dispatcher makes `disp_passes` passes in
-    that time (a pass over 64 records takes a few microseconds, a chunk of 16K elements tens)."""
+    that time (a pass over 64 records takes a few microseconds, a chunk of 16K elements tens).  A
+    worker claims at most one unit and runs at most one unit per round.  stash=1 is the kernel as it
+    first was: one unit per workgroup, which then sits on it."""
     n = len(tasks)
     done = [False] * n
     chunks_done = [0] * n
@@ -37,7 +40,7 @@ def simulate(tasks, workers, rule, batch=64, pend_max=128, lookahead=8192, small
     claim = 0
     pending = []                  # tickets, ticket order
     mirrored = 0
-    holding = [None] * workers    # unit index a worker holds
+    holding = [[] for _ in range(workers)]    # unit indices a worker holds, oldest first
     held_total = 0
     violations = 0
     completed = 0
@@ -96,29 +99,32 @@ def simulate(tasks, workers, rule, batch=64, pend_max=128, lookahead=8192, small
             mirrored += take
         # ---- workers ----
         for w in range(workers):
-            if holding[w] is None and claim < len(units):
-                holding[w] = claim
+            if len(holding[w]) < stash and claim < len(units):
+                holding[w].append(claim)
                 claim += 1
                 progress = True
         for w in range(workers):
-            u = holding[w]
-            if u is None:
-                continue
-            t, waits = units[u]
-            if not complete(t):
-                if not waits:
-                    violations += 1                        # a "resolved" unit whose dependencies are not complete
-                continue                                   # parked
-            chunks_done[t] += 1
-            if chunks_done[t] == tasks[t].nchunks:
-                done[t] = True
-                completed += 1
-            holding[w] = None
-            progress = True
+            ran = False
+            for u in holding[w]:
+                t, waits = units[u]
+                if not complete(t):
+                    if not waits:
+                        violations += 1                    # a "resolved" unit whose dependencies are not complete
+                    continue                               # stays held
+                if ran:
+                    continue
+                ran = True
+                chunks_done[t] += 1
+                if chunks_done[t] == tasks[t].nchunks:
+                    done[t] = True
+                    completed += 1
+                holding[w].remove(u)
+                progress = True
+                break
         if completed == n:
             return Result(False, rnd + 1, 0, completed, held_total, violations)
         if not progress:
-            parked = sum(1 for u in holding if u is not None)
+            parked = sum(1 for h in holding if len(h) == stash)
             return Result(True, rnd + 1, parked, completed, held_total, violations)
     raise RuntimeError("model did not finish")
 

@@ -38,14 +38,28 @@ def test_ordinary_kernels_and_small_copies_run_beside_the_resident_worker():
     torch.cuda.current_stream().synchronize()
     with R.Runtime(0, **CFG) as rt:
         assert rt.peek_queue().workgroups == 3 * int(R.device_info(0)["compute_units"])
+        rt.register_table({S.OP["ADD"]: rt.define_program(S.program(("ADD", 4, 0, 1), ("MOV", 0, 4)), 2)})
+        assert rt.native_info()["native"] == 0          # no run-time kernel beside three workgroups per compute unit: a place stays free
         t0 = time.perf_counter()
         y = x + 1
         torch.cuda.current_stream().synchronize()
         h = y.cpu()
         dt = time.perf_counter() - t0
         assert rt.worker_alive()
-    assert dt < 2.0, dt
-    assert torch.equal(h, torch.full((1024,), 2.0))
+    # the same with two workgroups per compute unit and the run-time worker kernel (native operator programs) in the third place
+    with R.Runtime(0, workgroups_per_cu=2, **CFG) as rt:
+        rt.register_table({S.OP["ADD"]: rt.define_program(S.program(("ADD", 4, 0, 1), ("MOV", 0, 4)), 2)})
+        info = rt.native_info()
+        assert info["native"] == 1, info
+        t0 = time.perf_counter()
+        z = torch.relu(x * 2 - 1)
+        torch.cuda.current_stream().synchronize()
+        hz = z.cpu()
+        big = torch.ones(1 << 16, device=DEV).cpu()           # a 256 KiB copy
+        dt2 = time.perf_counter() - t0
+        assert rt.worker_alive()
+    assert dt < 2.0 and dt2 < 2.0, (dt, dt2)
+    assert torch.equal(h, torch.full((1024,), 2.0)) and torch.equal(hz, torch.ones(1024)) and float(big.sum()) == 65536.0
 
 
 def program(a, b, row, h):

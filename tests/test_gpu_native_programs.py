@@ -11,7 +11,9 @@ from paper_2604_17861_amd import streams as S
 import parity_cases as C
 
 pytestmark = pytest.mark.gpu
-CFG = dict(idle_exit_ms=20000, wait_timeout_ms=20000)
+# two workgroups per compute unit for the library's worker: the run-time kernel takes the third place and the
+# fourth stays free (beside the default three, programs are interpreted: see the last test)
+CFG = dict(idle_exit_ms=20000, wait_timeout_ms=20000, workgroups_per_cu=2)
 
 
 def _run(stream, **cfg):
@@ -117,7 +119,7 @@ def test_native_kernel_comes_back_after_stop_start_and_idle_exit():
     with R.Runtime(0, **CFG) as warm:                          # compile once, so that the context with the short idle limit
         warm.register_table({S.OP["ADD"]: warm.define_program(p1, 2)})     # below finds the kernel in the process's cache
         assert warm.native_info()["compiled"] == 1
-    with R.Runtime(0, idle_exit_ms=300, wait_timeout_ms=20000) as rt:
+    with R.Runtime(0, idle_exit_ms=300, wait_timeout_ms=20000, workgroups_per_cu=2) as rt:
         i1 = rt.define_program(p1, 2)
         rt.register_table({S.OP["ADD"]: i1})
         assert rt.native_info()["native"] == 1
@@ -143,3 +145,18 @@ def test_native_kernel_comes_back_after_stop_start_and_idle_exit():
     s.programs = {i1: (p1, 2)}
     stats = compare_with_oracle(s, dp.download())
     assert stats["max_ulp"] == 0
+
+
+def test_beside_the_default_worker_programs_are_interpreted_unless_the_caller_fills_the_compute_units():
+    """Four workgroups fit a compute unit.  With the default three of the library's worker a run-time
+    kernel would leave no place for anybody else's kernels, so none is brought up and the reason is
+    reported; naming jit_workgroups_per_cu takes the last place knowingly."""
+    p1 = S.program(("SUB", 4, 0, 1), ("MUL", 0, 4, 4))
+    with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
+        rt.register_table({S.OP["ADD"]: rt.define_program(p1, 2)})
+        info = rt.native_info()
+        assert info["native"] == 0 and info["compiled"] == 0 and "free" in info["why"], info
+    with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000, jit_workgroups_per_cu=1) as rt:
+        rt.register_table({S.OP["ADD"]: rt.define_program(p1, 2)})
+        info = rt.native_info()
+        assert info["native"] == 1 and info["workgroups"] == int(R.device_info(0)["compute_units"]), info

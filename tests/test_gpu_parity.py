@@ -135,14 +135,15 @@ def test_held_producer_with_more_small_dependants_than_workgroups():
     links that all name it: the dispatcher publishes in dependency order (the small dependants join
     the pending list behind the held task), so no workgroup ever waits for work published after its
     own.  The buffers at the end equal sequential execution byte for byte; through the default ring
-    and through one of 2,048 slots (the dependants then reach back across most of the ring)."""
+    and through one of 2,048 slots (the dependants then reach back across most of the ring); and with
+    6,400 dependants, more than every workgroup's descriptor slots together could hold waiting."""
     from gpu_helpers import DevicePools, run_stream
     from helpers import run_oracle
-    s = C.producer_with_dependants()
-    hp, st = run_oracle(s)
-    assert np.all(st == 0)
-    for capacity in (0, 2048):
-        print("producer_with_dependants, ring", capacity, flush=True)
+    for s, capacity in ((C.producer_with_dependants(), 0), (C.producer_with_dependants(), 2048),
+                        (C.producer_with_dependants(n_consumers=6400), 8192)):     # more dependants than 767 workgroups hold at 8 each
+        hp, st = run_oracle(s)
+        assert np.all(st == 0)
+        print("producer_with_dependants,", len(s), "tasks, ring", capacity, flush=True)
         dp = DevicePools(s)
         with R.Runtime(capacity, idle_exit_ms=20000, wait_timeout_ms=20000) as rt:
             rt.register_table(s.table)
