@@ -259,10 +259,13 @@ def main():
     ap.add_argument("--cfg5-tasks", type=int, default=20000)
     ap.add_argument("--cfg4-tasks", type=int, default=1000000)
     ap.add_argument("--workgroups-per-cu", type=int, default=0, help="0: the library's default")
+    ap.add_argument("--chunk-elems", type=int, default=0, help="0: the library's default")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU time given to the oracle baseline")
     args = ap.parse_args()
     if args.workgroups_per_cu:
         KNOBS["workgroups_per_cu"] = args.workgroups_per_cu
+    if args.chunk_elems:
+        KNOBS["chunk_elems"] = args.chunk_elems
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one ring, one persistent kernel and one operator table "
                  "per GPU; there is no multi-GPU path to measure). Use --gpus 1.")

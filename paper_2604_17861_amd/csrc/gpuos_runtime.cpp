@@ -453,7 +453,17 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
     uint64_t base_per = ((uint64_t)chunk_elems * 12 / traffic + 1023) / 1024 * 1024;
     uint64_t per = ((uint64_t)numel + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
     per = (per + 1023) / 1024 * 1024;
-    if (per < base_per) per = base_per;
+    if (per < base_per) {
+      // A task of at most four regular chunks is cut into (up to) four chunks of at least half the
+      // regular size.  One workgroup streams a chunk at 50-60 GB/s, so a task of 8K-32K elements that
+      // runs alone (or as a link of a chain) is bound by that, not by the GPU: 16K elements take 5 us
+      // in one workgroup, 3 us in four.  It stays within the four chunks up to which a dependent task
+      // is published at once and waits in its workgroups.
+      uint64_t quarter = (((uint64_t)numel + 3) / 4 + 1023) / 1024 * 1024;
+      const uint64_t half = (base_per / 2 + 1023) / 1024 * 1024;
+      if (quarter < half) quarter = half;
+      per = quarter < base_per ? quarter : base_per;
+    }
     rec.chunk = (uint32_t)per;
     rec.nchunks = (uint32_t)(((uint64_t)numel + per - 1) / per);
     *r = rec;

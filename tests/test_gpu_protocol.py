@@ -213,7 +213,9 @@ def test_introspection_yield_policy_and_stats():
         rt.stop_worker()
         assert not rt.worker_alive()
         st = rt.worker_stats()
-        assert st["work_units"] == 200 and st["disp_records"] == 200 and st["work_ticks_exec"] > 0
+        units = sum(R.task_plan(dp.tasks, i, S.IMPL["ADD"])[1] for i in range(200))      # 8,192 elements: two chunks each
+        assert units == 400
+        assert st["work_units"] == units and st["disp_records"] == 200 and st["work_ticks_exec"] > 0
         assert rt.worker_elapsed_ms() > 0
         rc, _ = rt.submit(dp.tasks, 0, 1, check=False)
         assert rc == R.E_DEAD
