@@ -230,19 +230,66 @@ def bench_roofline(R, stream, dp, impls):
     return dict(bytes=nbytes, wall_s=wall, kernel_ms=kernel_ms, workgroups=wg)
 
 
+def source_hash():
+    """A hash of the sources libgpuos.so is built from: a counter profile under profiles/ is only
+    quoted for the kernels it was taken with."""
+    import hashlib
+    h = hashlib.sha1()
+    csrc = os.path.join(ROOT, "paper_2604_17861_amd", "csrc")
+    for path in sorted(os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".cpp", ".h"))) + [
+            os.path.join(ROOT, "include", "gpuos.h")]:
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(n_tasks):
     """HBM bytes of the persistent kernel over the bandwidth stream as measured with rocprofv3
-    counters (summary under profiles/, from two --pmc runs scaled by a copy kernel of known
-    size); None if no measurement for this task count is on file."""
+    counters (summary under profiles/, from two --pmc runs scaled by a copy kernel of known size).
+    Returns (bytes, note): bytes is None unless a measurement for this task count AND for the
+    sources this library was built from is on file (the summary records their hash)."""
     path = os.path.join(ROOT, "profiles", "gpuos_worker_kernel_config5_hbm_traffic.md")
+    here = source_hash()
+    found, taken = None, None
     try:
         for line in open(path):
             f = line.split()
             if len(f) == 4 and f[0] == "tasks:" and f[2] == "hbm_bytes_per_launch:" and int(f[1]) == n_tasks:
-                return int(f[3])
+                found = int(f[3])
+            if len(f) == 2 and f[0] == "source_hash:":
+                taken = f[1]
     except (OSError, ValueError):
         pass
-    return None
+    rel = "profiles/gpuos_worker_kernel_config5_hbm_traffic.md"
+    if found is None:
+        return None, "no counter measurement for %d tasks in %s" % (n_tasks, rel)
+    if taken != here:
+        return None, "%s was taken with sources %s, this library is built from %s: not quoted" % (rel, taken, here)
+    return found, "rocprofv3 FETCH_SIZE + WRITE_SIZE (separate runs, scaled by a copy kernel), %s, sources %s" % (rel, here)
+
+
+def time_oracle_subsample(stream, every, seconds, label):
+    """The CPU oracle on every `every`-th task of a stream (seeded: the stream is), one core, for at
+    most `seconds`: tasks/s and algorithmic GB/s over what it got through."""
+    import oracle
+    from paper_2604_17861_amd import runtime as R
+    host_arrays = [np.array(p.host_image(), dtype=np.uint8, copy=True) for p in stream.pools]
+    tasks = stream.materialize([a.ctypes.data for a in host_arrays])
+    impl = stream.impl_for()
+    idx = np.arange(0, len(stream), every)
+    nbytes = R.task_bytes(tasks[idx], impl[idx])
+    L = oracle.lib()
+    done, moved = 0, 0
+    t0 = time.perf_counter()
+    for k, i in enumerate(idx):
+        L.orc_run_task(tasks.ctypes.data + int(i) * tasks.dtype.itemsize, int(impl[i]), 0)
+        done += 1
+        moved += int(nbytes[k])
+        if time.perf_counter() - t0 > seconds:
+            break
+    dt = time.perf_counter() - t0
+    return dict(tasks_per_s=done / dt, gbps=moved / dt / 1e9, cores=1, kind="oracle",
+                sample="%s: every %dth task, %d of the %d sampled tasks in %.1f s (time-boxed)" % (label, every, done, len(idx), dt))
 
 
 def main():
@@ -254,6 +301,12 @@ def main():
     ap.add_argument("--report", default="", help="directory for one JSON report per configuration")
     ap.add_argument("--only-roofline", action="store_true",
                     help="run nothing but the bandwidth stream through the persistent kernel (for profiler runs)")
+    ap.add_argument("--only-config3", action="store_true",
+                    help="run nothing but the third configuration (chains, then one fused task per chain) through the "
+                         "persistent kernel, one worker lifetime each (for profiler runs)")
+    ap.add_argument("--only-strided", action="store_true",
+                    help="run nothing but 2,000 elementwise tasks over stride-2 inputs (1M elements each) through the "
+                         "persistent kernel (for profiler runs: traffic of the LDS-staged gather path)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run one ordinary COPY kernel over 1 GiB (counter calibration for profiler runs) and exit")
     ap.add_argument("--cfg5-tasks", type=int, default=20000)
@@ -305,6 +358,41 @@ def main():
         print(json.dumps(dict(workload="config5: %d bandwidth tasks" % len(s5), roofline=dict(
             bound="hbm", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
             kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"], algorithmic_bytes=rf["bytes"]))), flush=True)
+        return
+    if args.only_config3:
+        res3 = {}
+        for name, s3 in (("chains", S.config3()), ("fused", S.config3_fused())):
+            dp3 = DevicePools(s3, torch)
+            rf = bench_roofline(R, s3, dp3, s3.impl_for())
+            res3[name] = dict(tasks=len(s3), kernel_ms=rf["kernel_ms"], algorithmic_bytes=rf["bytes"],
+                              gbps=rf["bytes"] / (rf["kernel_ms"] * 1e-3) / 1e9, workgroups=rf["workgroups"])
+            del dp3
+        print(json.dumps(dict(workload="config3: 2,000 softmax chains of six tasks, then the same as one fused task per chain",
+                              **res3)), flush=True)
+        return
+    if args.only_strided:
+        n, numel = 2000, 1 << 20
+        src = torch.randn(8 * 2 * numel + 64, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty(8 * numel, dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        t, pool_of = S.new_tasks(n)
+        for i in range(n):                                     # out[k] = 0.5 * x[2k]: eight input / output regions in turn
+            S.set_head(t, i, S.OP["SCALE"], [numel], 1, alpha=0.5)
+            S.set_tensor(t, pool_of, i, 0, 0, src.data_ptr() + (i % 8) * 2 * numel * 4, [2], S.F32)
+            S.set_tensor(t, pool_of, i, 3, 0, dst.data_ptr() + (i % 8) * numel * 4, [1], S.F32)
+        path = R.task_plan(t, 0, S.IMPL["SCALE"])[0]
+        with R.Runtime(0, idle_exit_ms=60000, **KNOBS) as rt:
+            rt.register_table(S.default_table())
+            t0 = time.perf_counter()
+            rt.submit_from_threads(t, 1, 64, 1)
+            rt.wait()
+            wall = time.perf_counter() - t0
+            rt.stop_worker()
+            kernel_ms = rt.worker_elapsed_ms()
+        # algorithmic bytes: the elements read and the elements written (4 + 4 bytes per output element)
+        print(json.dumps(dict(workload="%d SCALE tasks, %d fp32 elements each, input stride 2" % (n, numel), path=path,
+                              algorithmic_bytes=n * numel * 8, covering_span_bytes=n * numel * 12, kernel_ms=kernel_ms, wall_s=wall,
+                              gbps=n * numel * 8 / (kernel_ms * 1e-3) / 1e9)), flush=True)
         return
     # ---- headline: second configuration --------------------------------------------------
     s2 = S.config2()
@@ -435,8 +523,9 @@ def main():
     extras["config5"] = dict(persistent_gbps_wall=rf["bytes"] / rf["wall_s"] / 1e9, per_launch_gbps=float(pl5),
                              tasks=len(s5), tasks_per_s=len(s5) / rf["wall_s"])
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
-                    traffic=measured_traffic(len(s5)), kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"],
+                    traffic=None, kernel="gpuos_worker_kernel", kernel_ms=rf["kernel_ms"],
                     algorithmic_bytes=rf["bytes"], workload="config5: %d bandwidth tasks" % len(s5))
+    roofline["traffic"], roofline["traffic_note"] = measured_traffic(len(s5))
     if not args.skip_extras:
         # ---- an operator defined at run time as a program against the built-in it re-implements -----
         # (side legs after the figures of record: a failure in one is reported in its place and does
@@ -466,6 +555,13 @@ def main():
                         sample="%d passes over the second configuration's 10,000-task stream (%d tasks, %.1f s)" % (
                             done // len(s2), done, cpu_s))
     log("cpu oracle:", cpu_baseline)
+    if not args.skip_extras:
+        # the oracle on a seeded 1-in-20 subsample of the fourth and fifth configurations (time-boxed: the
+        # fifth one's tasks have up to 16M elements, the oracle walks them one element at a time)
+        del host_arrays, hp_tasks
+        extras["cpu_oracle_config4"] = time_oracle_subsample(S.config4(n_tasks=args.cfg4_tasks), 20, args.cpu_seconds / 2, "config4")
+        extras["cpu_oracle_config5"] = time_oracle_subsample(S.config5(n_tasks=args.cfg5_tasks), 20, args.cpu_seconds, "config5")
+        log("cpu oracle, configs 4 and 5:", extras["cpu_oracle_config4"], extras["cpu_oracle_config5"])
 
     line = dict(metric="small-op tasks/sec and p50 submit->done latency vs per-op launch; HBM GB/s",
                 value=out["value"], unit="tasks/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
