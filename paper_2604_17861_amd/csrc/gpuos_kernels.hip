@@ -183,18 +183,22 @@ DEV uint32_t dispatcher_publish(const WorkerArgs& a, DispShared* s, uint32_t npu
     v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
     v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
     v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
-    if (tid < npub) s->ubeg[tid + 1] = (uint32_t)v;
+    s->ubeg[tid + 1] = (uint32_t)v;                // (entries past npub hold the total: the search below counts them out)
     if (tid == 0) s->ubeg[0] = 0;
   }
   __syncthreads();
   const uint32_t total = s->ubeg[npub];
   // (no wait for the mirror stores of this pass: a worker checks the record it fetches, see mirror_record_valid)
   for (uint32_t u = tid; u < total; u += kThreads) {
-    uint32_t lo = 0, hi = npub;                    // ubeg[lo] <= u < ubeg[hi]
-    while (hi - lo > 1) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (s->ubeg[mid] <= u) lo = mid; else hi = mid;
-    }
+    // The task of unit u is the number of prefix entries 1..64 that are <= u (they only grow).  Counted
+    // in two levels of seven independent reads each, two LDS latencies, where a binary search takes six.
+    static_assert(kDispatchBatch == 64, "two levels of eight");
+    uint32_t oct = 0;
+#pragma unroll
+    for (uint32_t k = 1; k < 8; ++k) oct += s->ubeg[8u * k] <= u ? 1u : 0u;
+    uint32_t lo = 8u * oct;
+#pragma unroll
+    for (uint32_t j = 1; j < 8; ++j) lo += s->ubeg[8u * oct + j] <= u ? 1u : 0u;
     const PubEntry pe = s->pub[lo];
     const uint64_t g = units_w + u;
     // one 8-byte store publishes the unit: the stamp makes it claimable

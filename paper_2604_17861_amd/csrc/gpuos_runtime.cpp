@@ -416,7 +416,12 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
         }
         const uint64_t tiles = (uint64_t)B * ((R + 31) / 32) * ((C + 31) / 32);
         uint64_t per_t = (tiles + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
-        const uint64_t want = chunk_elems / 1024 ? chunk_elems / 1024 : 1;    // tiles of 1024 elements
+        // tiles of 1024 elements.  A workgroup takes a tile at a time (load, transpose through LDS,
+        // store: about 5 us alone), so a task of few tiles is spread over as many workgroups as it
+        // has tiles, up to 64, before chunks grow to the regular size.
+        uint64_t want = chunk_elems / 1024 ? chunk_elems / 1024 : 1;
+        const uint64_t spread = (tiles + 63) / 64;
+        if (spread < want) want = spread;
         if (per_t < want) per_t = want;
         rec.numel = (uint32_t)tiles;
         rec.chunk = (uint32_t)per_t;
@@ -460,7 +465,14 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
       // in one workgroup, 3 us in four.  It stays within the four chunks up to which a dependent task
       // is published at once and waits in its workgroups.
       uint64_t quarter = (((uint64_t)numel + 3) / 4 + 1023) / 1024 * 1024;
-      const uint64_t half = (base_per / 2 + 1023) / 1024 * 1024;
+      uint64_t half = (base_per / 2 + 1023) / 1024 * 1024;
+      if (rec.path == PATH_STAGED) {
+        // the gather path works in rounds of 1,024 elements, each a chain of latencies (load the
+        // covering span, stage, gather, store: 2-3 us): a task of a few dozen rounds is spread
+        // over up to 32 workgroups, two rounds each at least
+        quarter = (((uint64_t)numel + 31) / 32 + 1023) / 1024 * 1024;
+        half = 2048;
+      }
       if (quarter < half) quarter = half;
       per = quarter < base_per ? quarter : base_per;
     }
