@@ -42,6 +42,34 @@ def test_every_elementwise_op_contiguous(code):
     print(stats, flush=True)
 
 
+@pytest.mark.parametrize("trace_entries", [0, 4096])
+def test_lone_tasks_take_the_dispatchers_short_cut(trace_entries):
+    """Tasks submitted one at a time, each after the previous one has completed, are resolved,
+    mirrored and published by the dispatcher's first wavefront alone (no batch pass): contiguous,
+    gathered, transposed and reduction tasks of one to several chunks, every float dtype, with and
+    without tracepoints; then a burst, so that the short cut and the batch pass alternate.  Results
+    against the oracle as for every other case; the dispatcher's counters show one pass per task."""
+    from gpu_helpers import DevicePools, compare_with_oracle
+    streams = [C.elementwise_contiguous(S.F32), C.staged_gathers(), C.transposed_2d(), C.reductions(), C.row_operations()]
+    for stream in streams:
+        n = 2 * len(stream) // 3
+        print("lone tasks of", stream.name, n, flush=True)
+        dp = DevicePools(stream)
+        with R.Runtime(0, idle_exit_ms=20000, wait_timeout_ms=20000, trace_entries=trace_entries) as rt:
+            rt.register_table(stream.table, stream.programs)
+            lat = rt.run_serial(dp.tasks, 0, n)                      # submit + wait, one by one
+            if n < len(stream):
+                rt.submit(dp.tasks, n, len(stream) - n)              # the rest as one burst
+                rt.wait()
+            comps = rt.completions(0, len(stream))
+            rt.stop_worker()
+            st = rt.worker_stats()
+        assert np.all(comps["status"] == 0)
+        assert st["disp_records"] == len(stream) and st["disp_batches"] >= n    # a pass of its own for every lone task
+        stats = compare_with_oracle(stream, dp.download(), versions=comps["op_version"])
+        print(stats, "p50 %.1f us" % (np.median(lat) / 1e3), flush=True)
+
+
 @pytest.mark.parametrize("code", [S.F16, S.BF16])
 def test_all_16bit_patterns_through_unary_ops(code):
     stats, _ = _run_and_check(C.all_16bit_patterns(code))
