@@ -87,6 +87,7 @@ struct DispShared {
   uint32_t bad[kDispatchBatch], ok[kDispatchBatch];   // staging: record still fails its check / passed on this read
   uint32_t nbad;
   uint32_t pre[kPrefetch];                 // prefetched with the poll and valid
+  uint32_t preok[kDispatchBatch];          // requested while the previous batch was written out: arrived whole
   uint32_t opcnt[GPUOS_MAX_OPS];           // tracing: tasks dispatched per operator since the last flush
   uint32_t ready[kPendMax];                // per pending entry: dependencies complete
   uint32_t native[GPUOS_MAX_PROGRAMS];     // per operator program: 1 = its tasks go to the second ring (native code is being served there)
@@ -467,13 +468,20 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       // a record that has not landed completely yet, or is left over from the previous lap,
       // fails the check and is read again; one that never passes is completed with an error
       // instead of being executed.
-      if (tid < kDispatchBatch) s->bad[tid] = (tid < n && !(first_batch && tid < kPrefetch && s->pre[tid])) ? 1u : 0u;
+      // Records requested ahead (with the poll, or while the previous batch was written out) already
+      // lie in s->rec and were checked as they arrived: a batch made of such records only is staged
+      // by one ballot and one barrier.  Everything else is read here, and read again until it checks.
+      static_assert(kDispatchBatch == 64, "one wavefront looks at the whole batch");
+      if (tid < kDispatchBatch) {
+        const bool ahead = (pre_base == mirrored && tid < pre_n && s->preok[tid] != 0) || (first_batch && tid < kPrefetch && s->pre[tid] != 0);
+        const bool bad = tid < n && !ahead;
+        s->bad[tid] = bad ? 1u : 0u;
+        const uint64_t m = __ballot(bad);
+        if (tid == 0) s->nbad = (uint32_t)__popcll(m);
+      }
       first_batch = false;
       __syncthreads();
-      for (uint32_t attempt = 0; attempt < kStageRetries; ++attempt) {
-        // With a backlog, the pieces of this batch were requested while the previous batch was
-        // being written out and already lie in s->rec (below): the first attempt only checks them.
-        const bool preloaded = attempt == 0 && pre_base == mirrored;
+      for (uint32_t attempt = 0; s->nbad != 0 && attempt < kStageRetries; ++attempt) {
 #pragma unroll
         for (uint32_t j = 0; j < kStagePieces; ++j) {
           const uint32_t p = tid + j * kThreads;
@@ -481,10 +489,8 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
             const uint32_t rix = p >> 4, part = p & 15u;
             if (s->bad[rix]) {                                     // uniform over the 16 lanes of a record
               const uint32_t slot = (uint32_t)((mirrored + rix) & a.cap_mask);
-              const bool have = preloaded && p < pre_n * 16u;
-              const v4i q = have ? ((const v4i*)&s->rec[rix])[part]
-                                 : Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
-              if (!have) ((v4i*)&s->rec[rix])[part] = q;
+              const v4i q = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + part * 16u);
+              ((v4i*)&s->rec[rix])[part] = q;
               const uint32_t x = record_piece_sum(q, part);
               if (part == 0) s->ok[rix] = (x == record_check_seed(mirrored + rix)) ? 1u : 0u;
             }
@@ -649,10 +655,15 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       const uint32_t total = (uint32_t)(uc.w[0] + uc.w[1] - before);
       // nothing reads this batch's staging any more (the mirror has it, held-back tasks were copied
       // to the pending list): it takes the records requested ahead
+      // (and each is checked as it arrives: the next pass finds the verdict in s->preok)
 #pragma unroll
       for (uint32_t j = 0; j < kStagePieces; ++j) {
         const uint32_t p = tid + j * kThreads;
-        if (p < pre_n * 16u) ((v4i*)&s->rec[p >> 4])[p & 15u] = pre_q[j];
+        if (p < pre_n * 16u) {                                       // uniform over the 16 lanes of a record
+          ((v4i*)&s->rec[p >> 4])[p & 15u] = pre_q[j];
+          const uint32_t x = record_piece_sum(pre_q[j], p & 15u);
+          if ((p & 15u) == 0) s->preok[p >> 4] = (x == record_check_seed(pre_base + (p >> 4))) ? 1u : 0u;
+        }
       }
       mirrored += n;
       if (tid == 0) __hip_atomic_store(&a.h->dispatched, mirrored, __ATOMIC_RELAXED, SC_SYSTEM);
