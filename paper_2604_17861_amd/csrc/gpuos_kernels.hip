@@ -454,8 +454,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         s->n = take;
       }
       __syncthreads();
-      uint32_t n = s->n;
-      __syncthreads();
+      uint32_t n = s->n;                           // (written again only behind the barriers of staging, or of the next poll)
       if (n == 0) {                                                // throttled: let the workers catch up
         dispatcher_service_pending(a, s, uc);
         if (s->npend == 0) __builtin_amdgcn_s_sleep(8);
@@ -516,6 +515,23 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       }
       __syncthreads();
       n = s->n;
+      // Request the next batch now, if the doorbell value already covers it: the loads travel while
+      // this batch is resolved, written to the mirror and published (2.5 us; behind the mirror and
+      // publish steps alone the copy at the end of the pass still waited for them).  A piece that turns
+      // out incomplete fails its record's check word when it arrives and is read again at staging time.
+      pre_base = mirrored + n;
+      pre_n = tail > pre_base ? (uint32_t)((tail - pre_base) < kDispatchBatch ? (tail - pre_base) : kDispatchBatch) : 0u;
+      v4i pre_q[kStagePieces];
+#pragma unroll
+      for (uint32_t j = 0; j < kStagePieces; ++j) {
+        // No branch round the load: a piece that is not wanted gets an offset past the ring, which the
+        // buffer hardware answers with zero without touching memory.  (With the load under an `if`
+        // the compiler waited for each of the four before it issued the next: four memory round
+        // trips in a row, 1.6 of the pass's 4.4 us.)
+        const uint32_t p = tid + j * kThreads;
+        const uint32_t slot = (uint32_t)((pre_base + (p >> 4)) & a.cap_mask);
+        pre_q[j] = Mem<POL_COHERENT>::ld16(rh, p < pre_n * 16u ? slot * (uint32_t)sizeof(Record) + (p & 15u) * 16u : kNoLoad);
+      }
       // resolve the operator table ("claim time": slot, version, impl, status) and the dependencies
       if (tid < n) {
         Record& rc = s->rec[tid];
@@ -624,21 +640,6 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       }
       __syncthreads();
       const uint64_t tk2 = clock_if(timing);
-      // Request the next batch now, if the doorbell value already covers it: the loads travel while
-      // this batch is written to the mirror and published.  A piece that turns out incomplete fails
-      // its record's check word at staging time and is read again there.
-      pre_base = mirrored + n;
-      pre_n = tail > pre_base ? (uint32_t)((tail - pre_base) < kDispatchBatch ? (tail - pre_base) : kDispatchBatch) : 0u;
-      v4i pre_q[kStagePieces];
-#pragma unroll
-      for (uint32_t j = 0; j < kStagePieces; ++j) {
-        const uint32_t p = tid + j * kThreads;
-        pre_q[j] = v4i{0, 0, 0, 0};
-        if (p < pre_n * 16u) {
-          const uint32_t slot = (uint32_t)((pre_base + (p >> 4)) & a.cap_mask);
-          pre_q[j] = Mem<POL_COHERENT>::ld16(rh, slot * (uint32_t)sizeof(Record) + (p & 15u) * 16u);
-        }
-      }
       // write the records into the device mirror (write-through stores), held-back ones included
       // each record leaves with a check word of its own over what it now holds (resolved fields, ticket)
       for (uint32_t p = tid; p < n * 16u; p += kThreads) {
