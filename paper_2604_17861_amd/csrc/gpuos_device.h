@@ -1941,12 +1941,22 @@ DEV void run_worker(const WorkerArgs& a, WorkShared* s, uint32_t gen = 0) {
       // round trip, was measured: with 767 workgroups polling, the doubled traffic cost a lone task
       // more than the earlier sample gained, 7.7 against 6.5 us.)
       struct Poll { uint64_t u, seen[3]; };
+      // While something is held, every lane issues all four loads, the lanes with nothing to look at from
+      // the unit-ring entry that lane 32 polls anyway (one request for the whole wavefront): loads under
+      // conditions that differ between lanes are waited for one after the other (a poll would take up
+      // to four memory round trips instead of one).
+      const uint64_t* const anyword = up;
       auto request = [&]() {
         Poll p;
-        p.u = 0;
-        if (tid == 32 && have_claim) p.u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM);
+        if (waiting == 0) {
+          p.u = 0;
+          if (tid == 32 && have_claim) p.u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM);
+          p.seen[0] = p.seen[1] = p.seen[2] = ~0ull;
+        } else {
+          p.u = __hip_atomic_load(up, __ATOMIC_RELAXED, SC_SYSTEM);
 #pragma unroll
-        for (int k = 0; k < 3; ++k) p.seen[k] = done_word[k] ? __hip_atomic_load(done_word[k], __ATOMIC_RELAXED, SC_SYSTEM) : ~0ull;
+          for (int k = 0; k < 3; ++k) p.seen[k] = __hip_atomic_load(done_word[k] ? done_word[k] : anyword, __ATOMIC_RELAXED, SC_SYSTEM);
+        }
         return p;
       };
       while (true) {
