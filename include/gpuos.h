@@ -277,8 +277,13 @@ typedef struct gpuos_config {
                                        (0 => 30000)                                 */
   uint32_t completion_log;          /* tickets kept for gpuos_get_completions
                                        (0 => 1<<21; rounded up to a power of two)   */
-  uint32_t chunk_elems;             /* elements of a task one workgroup takes at a time
-                                       (0 => 16384; rounded up to a multiple of 1024)  */
+  uint32_t chunk_elems;             /* elements of a large task one workgroup takes at a time,
+                                       quoted for 12 bytes of traffic per element and scaled for
+                                       other operators (0 => 16384; rounded up to a multiple of
+                                       1024).  Tasks of up to 2^20 elements and links of a chain
+                                       take half of it; a task of at most four such chunks is cut
+                                       into up to four; gathered and transposed inputs are spread
+                                       over up to 32 resp. 64 workgroups (gpuos_task_plan tells) */
   uint32_t push_ring;               /* where the ring, the doorbell and the table source
                                        live: 0 = fine-grained host memory that the device
                                        polls over PCIe; 1 = device memory that the host
