@@ -155,6 +155,45 @@ def test_task_plan_picks_the_execution_path_the_layout_calls_for():
     assert path == "TILE2D" and chunks <= 1024 and (chunks - 1) * per < tiles <= chunks * per
 
 
+def test_small_tasks_are_cut_into_more_chunks_than_their_size_alone_would_give():
+    """How the host cuts a task into work units (gpuos_task_plan -> path, chunks, elements or tiles per
+    chunk): the regular chunk of an fp32 binary operator is 16,384 elements, 8,192 up to 2^20 elements;
+    a task of at most four such chunks becomes up to four of at least 4,096; a gathered task is spread
+    over up to 32 workgroups with two rounds of 1,024 elements each at least; a transposed one over one
+    workgroup per 32 x 32 tile, up to 64.  Every element is covered exactly once."""
+    from helpers import Builder
+    def plan(build):
+        b = Builder()
+        build(b)
+        s = b.stream()
+        return R.task_plan(HostPools(s).tasks, 0, s.impl_for()[0])
+    f32 = lambda b, *shape: b.pool(np.zeros(shape, np.float32))
+    def contig(n):
+        return plan(lambda b: b.add("ADD", f32(b, n), [f32(b, n), f32(b, n)]))
+    want = {1000: (1, 4096), 4096: (1, 4096), 4097: (2, 4096), 16384: (4, 4096), 20000: (4, 5120), 32768: (4, 8192),
+            40000: (5, 8192), 1 << 20: (128, 8192), (1 << 20) + 1: (65, 16384), 1 << 24: (1024, 16384)}
+    for n, (chunks, per) in want.items():
+        path, c, p, _ = contig(n)
+        assert (path, c, p) == ("CONTIG", chunks, per), (n, path, c, p)
+        assert (c - 1) * p < n <= c * p
+    # a unary operator moves 8 bytes per element instead of 12: its chunks hold half as many elements again
+    path, c, p, _ = plan(lambda b: b.add("RELU", f32(b, 1 << 20), [f32(b, 1 << 20)]))
+    assert (path, p) == ("CONTIG", 12288) and (c - 1) * p < (1 << 20) <= c * p
+    def staged(n):
+        return plan(lambda b: b.add("RELU", f32(b, n), [f32(b, 2 * n + 1)[1::2]]))
+    for n, (chunks, per) in {1500: (1, 2048), 5000: (3, 2048), 60000: (30, 2048), 65536: (32, 2048), 100000: (25, 4096),
+                             600000: (49, 12288)}.items():
+        path, c, p, _ = staged(n)
+        assert (path, c, p) == ("STAGED", chunks, per), (n, path, c, p)
+    def tiled(r, cc):
+        return plan(lambda b: b.add("RELU", f32(b, r, cc), [f32(b, cc, r).T]))
+    for (r, cc), (chunks, per) in {(64, 64): (4, 1), (66, 228): (24, 1), (256, 256): (64, 1), (512, 256): (64, 2),
+                                   (1024, 1024): (128, 8)}.items():
+        path, c, p, _ = tiled(r, cc)
+        tiles = ((r + 31) // 32) * ((cc + 31) // 32)
+        assert (path, c, p) == ("TILE2D", chunks, per) and (c - 1) * p < tiles <= c * p, ((r, cc), path, c, p)
+
+
 def test_task_plan_for_row_operations():
     """Rows of whole aligned vectors (at most 256 of them), one dtype, contiguous -> rows in
     registers, with further inputs laid out like x, repeated every `period` rows, or one row;
