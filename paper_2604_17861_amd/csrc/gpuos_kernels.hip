@@ -5,12 +5,15 @@
 //    dispatcher: it is the single reader of the host ring (one PCIe poller
 //    instead of hundreds), mirrors new records into device memory, resolves
 //    each task's operator-table slot and version once ("claim time"), expands
-//    tasks into work units (chunks) and publishes them with an agent-scope
-//    store-release.  Every other workgroup is a worker: one elected lane claims
-//    a work unit with an atomic fetch-add, the 4 wavefronts of the workgroup
-//    execute the chunk together, and the last finisher of a task publishes its
-//    completion (device-side done word for dependants, one 8-byte completion
-//    word to host memory).
+//    tasks into work units (chunks) and publishes each with one 8-byte store
+//    whose stamp makes it claimable (a lone new record takes the first
+//    wavefront's short cut past the batch pass).  Every other workgroup is a
+//    worker (run_worker in gpuos_device.h): its first wavefront claims work
+//    units with an atomic fetch-add and holds up to eight descriptors, running
+//    whichever is ready; the 4 wavefronts of the workgroup execute a chunk
+//    together, and the last finisher of a task publishes its completion
+//    (device-side done word for dependants, one 8-byte completion word to host
+//    memory).
 //  * gpuos_single_task_kernel: the same chunk executor as an ordinary kernel,
 //    one launch per task (the per-op-launch comparison of the paper's Section 6).
 //
@@ -34,19 +37,19 @@ namespace gpuos {
 // dispatcher (workgroup 0)
 //
 // Besides mirroring the host ring it is the scheduler of dependent work.  Units are claimed in
-// publication order, and a worker that holds a unit whose dependency is incomplete can only wait.
-// Two rules keep that from hurting:
+// publication order; a workgroup holds a few units at a time and runs whichever of them is ready, and
+// when none is it can only wait.  Two rules keep that from hurting:
 //  * A task with more than kSmallTaskChunks chunks whose dependencies are incomplete when it is
 //    dequeued is HELD on a pending list and published when the done words say so (otherwise hundreds
-//    of workgroups would park on it while ready work of other chains sits behind it).  Small dependent
-//    tasks are published at once and their few workgroups wait on the done word, the shortest hand-off
-//    for sequential chains of small operations.
+//    of descriptor slots would be taken by it while ready work of other chains sits behind it).  Small
+//    dependent tasks are published at once and wait, in the workgroups that claimed their units, on the
+//    done word: the shortest hand-off for sequential chains of small operations.
 //  * Publication order respects dependency order: a task that names a task which is itself not yet
 //    published (it is on the pending list, or held earlier in the same pass) is held too, whatever its
 //    size.  So whatever a waiting worker waits for lies BEFORE its own unit in the unit ring, its units
 //    were claimed earlier by resident workgroups, and by induction over the ring position the wait
-//    ends.  (Without this rule a held large task followed by more small dependants than there are
-//    workgroups parks every workgroup behind units that come after theirs.)
+//    ends.  (Without this rule a held large task followed by more small dependants than the workgroups
+//    can hold parks every workgroup behind units that come after theirs.)
 // Held tasks are flagged RF_DEPS_RESOLVED: they are published only after their dependencies
 // completed, so their workers never wait.
 // ---------------------------------------------------------------------------
@@ -463,8 +466,8 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
       const uint64_t tk0 = clock_if(timing || tracing);
       // stage: 16 pieces of 16 bytes per record.  System-scope loads: an ordinary load of host
       // memory may hit a line the CU's vector cache kept from the previous lap of the ring.
-      // Every record carries a check word (xor of its other 63 words, its ticket and a constant):
-      // a record that has not landed completely yet, or is left over from the previous lap,
+      // Every record carries a check word (a weighted sum of its 64 words must equal a seed made
+      // from its ticket): a record that has not landed completely yet, or is left over from the previous lap,
       // fails the check and is read again; one that never passes is completed with an error
       // instead of being executed.
       // Records requested ahead (with the poll, or while the previous batch was written out) already
@@ -652,7 +655,7 @@ DEV void run_dispatcher(const WorkerArgs& a, DispShared* s) {
         Mem<POL_COHERENT>::st16(rd, slot * (uint32_t)sizeof(Record) + part * 16u, q);
       }
       const uint64_t before = uc.w[0] + uc.w[1];
-      dispatcher_publish_all(a, s, s->npub, uc, s->npub_second != 0);       // drains the stores above as well
+      dispatcher_publish_all(a, s, s->npub, uc, s->npub_second != 0);       // (no wait for the stores above: see mirror_record_valid)
       const uint32_t total = (uint32_t)(uc.w[0] + uc.w[1] - before);
       // nothing reads this batch's staging any more (the mirror has it, held-back tasks were copied
       // to the pending list): it takes the records requested ahead
