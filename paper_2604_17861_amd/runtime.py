@@ -80,6 +80,7 @@ def lib():
         "gpuos_register_op": (ctypes.c_int, [vp, u32, u32, P(u32)]),
         "gpuos_swap_op": (ctypes.c_int, [vp, u32, u32, P(u32)]),
         "gpuos_submit": (ctypes.c_int, [vp, vp, u32, P(u64)]),
+        "gpuos_submit_flush": (ctypes.c_int, [vp, vp, u32, P(u64)]),
         "gpuos_flush": (ctypes.c_int, [vp]),
         "gpuos_wait": (ctypes.c_int, [vp, u64, u64]),
         "gpuos_get_completions": (ctypes.c_int, [vp, u64, u32, vp]),
@@ -116,7 +117,7 @@ def lib():
     return L
 
 
-EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_init_static", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit",
+EXPORTS = ["gpuos_default_config", "gpuos_init", "gpuos_init_static", "gpuos_register_op", "gpuos_swap_op", "gpuos_submit", "gpuos_submit_flush",
            "gpuos_flush", "gpuos_wait", "gpuos_get_completions", "gpuos_peek_queue",
            "gpuos_worker_alive", "gpuos_set_yield_every", "gpuos_shutdown", "gpuos_stop_worker", "gpuos_start_worker",
            "gpuos_worker_elapsed_ms", "gpuos_worker_stats", "gpuos_run_serial", "gpuos_launch_per_op", "gpuos_task_bytes", "gpuos_task_plan", "gpuos_device_info", "gpuos_define_program", "gpuos_native_info", "gpuos_submit_from_threads", "gpuos_get_trace", "gpuos_op_counts",
@@ -258,9 +259,8 @@ class Runtime:
         (status, first ticket) instead of raising."""
         n = len(tasks) - first if count is None else count
         t0 = ctypes.c_uint64()
-        rc = lib().gpuos_submit(self._ctx, _tasks_ptr(tasks, first), n, ctypes.byref(t0))
-        if rc == OK and flush:
-            rc = lib().gpuos_flush(self._ctx)
+        call = lib().gpuos_submit_flush if flush else lib().gpuos_submit
+        rc = call(self._ctx, _tasks_ptr(tasks, first), n, ctypes.byref(t0))
         if not check:
             return rc, t0.value
         _check(rc, "gpuos_submit")

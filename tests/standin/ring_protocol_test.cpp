@@ -107,7 +107,9 @@ int main() {
             gpuos_task batch[5];
             for (int i = 0; i < m; ++i) batch[i] = add_task(k % 2 ? 7 : 9, 1000 + (uint32_t)i, i > 0 ? 1 : 0);   // chain inside the call
             uint64_t first = ~0ull;
-            if (gpuos_submit(c, batch, (uint32_t)m, &first) != GPUOS_OK) { failures++; return; }
+            // (every third call as submit + flush in one: records and doorbell leave with one flush)
+            const int rc = (s >> 4) % 3u == 0 ? gpuos_submit_flush(c, batch, (uint32_t)m, &first) : gpuos_submit(c, batch, (uint32_t)m, &first);
+            if (rc != GPUOS_OK) { failures++; return; }
             for (int i = 0; i < m; ++i) firsts[k].push_back(first + (uint64_t)i);
             if ((s >> 8) % 7u == 0 && gpuos_wait(c, first + (uint64_t)m - 1, 0) != GPUOS_OK) { failures++; return; }
             if ((s >> 8) % 11u == 0) gpuos_flush(c);
