@@ -164,6 +164,11 @@ def bench_program(R, s5, dp5, impl5, n_tasks=1500):
             rt.submit_from_threads(sub, 1, 64, 1)
             rt.wait()
             out[label] = nbytes / (time.perf_counter() - t0) / 1e9
+    # In these legs every task is a program task, so only the run-time kernel's workgroups work: one per
+    # compute unit streams 4.6-4.8 TB/s whatever it executes, two stream what two of the library's do.
+    out["program_6_instr_gbps"] = out["program_6_instr_2plus2wg_gbps"]
+    out["program_6_instr_gbps_note"] = "2 + 2 workgroups per compute unit; to be read against builtin_add_2wg_gbps"
+    out["native_6_instr_vs_builtin"] = out["program_6_instr_2plus2wg_gbps"] / out["builtin_add_2wg_gbps"]
     return out
 
 
