@@ -18,7 +18,7 @@
  *     and unmodified until gpuos_wait() has covered the ticket;
  *   - every call returns 0 (GPUOS_OK) or a negative gpuos_status; nothing
  *     throws or aborts across this boundary;
- *   - any number of host threads may call gpuos_submit / gpuos_flush /
+ *   - any number of host threads may call gpuos_submit / gpuos_submit_flush / gpuos_flush /
  *     gpuos_wait / gpuos_register_op / gpuos_swap_op / the query calls on one
  *     context at the same time (Section 6.4 speaks of many concurrent host
  *     threads on one ring): descriptors are validated and packed in
