@@ -504,7 +504,7 @@ def main():
         # ---- fourth configuration (hot swaps while running) -----------------------------------
         s4 = S.config4(n_tasks=args.cfg4_tasks)
         dp4 = DevicePools(s4, torch)
-        r4 = bench_persistent(R, s4, dp4, 1, 0)
+        r4 = bench_persistent(R, s4, dp4, 2, 1)          # the first pass faults in 1 M descriptors and the log
         t0 = time.perf_counter()
         R.launch_per_op(dp4.tasks, s4.table, count=min(len(s4), 200000))
         pl4 = min(len(s4), 200000) / (time.perf_counter() - t0)

@@ -193,7 +193,8 @@ int gpuos_native_info(gpuos_ctx* ctx, uint64_t out[8], char* why, uint32_t why_l
 /* ---- generic tensor descriptor (paper abstract / Section 5.2: arbitrary
  * shapes, strides, dtypes and broadcasting) -------------------------------- */
 typedef struct gpuos_tensor {
-  void*   ptr;                      /* device address of the element at index 0     */
+  void*   ptr;                      /* device address of the element at index 0, a
+                                     * multiple of the element size (else E_INVAL)   */
   int64_t stride[GPUOS_MAX_DIMS];   /* in ELEMENTS, >= 0; entries >= ndim ignored   */
   uint8_t dtype;                    /* enum gpuos_dtype                             */
   uint8_t bcast_mask;               /* bit d set: dim d is broadcast (stride := 0)  */

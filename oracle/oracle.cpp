@@ -181,6 +181,7 @@ int64_t eff_stride(const orc_tensor& t, int d) {
 int check_tensor(const orc_tensor& t, int ndim, const int64_t* size, bool is_out) {
   if (t.ptr == nullptr) return ORC_E_INVAL;
   if (t.dtype > ORC_I32) return ORC_E_INVAL;
+  if ((uintptr_t)t.ptr % (uintptr_t)elem_size(t.dtype) != 0) return ORC_E_INVAL;   // elements are naturally aligned
   if (is_out && t.bcast_mask != 0) return ORC_E_INVAL;
   int64_t max_off = 0;
   for (int d = 0; d < ndim; ++d) {

@@ -168,10 +168,17 @@ template <> struct Elem<GPUOS_BF16> {
   template <int POL> static DEV void copy1(void* o, const void* a, uint32_t i) { Mem<POL>::st2(o, i, Mem<POL>::ld2(a, i)); }
 };
 
-template <int POL> DEV float load_rt(const void* p, uint32_t i, uint32_t dt) {   // runtime dtype
-  if (dt == GPUOS_F32) return __builtin_bit_cast(float, Mem<POL>::ld4(p, i));
-  if (dt == GPUOS_F16) return h2f(Mem<POL>::ld2(p, i));
-  return b2f(Mem<POL>::ld2(p, i));
+// Element i of a float tensor whose dtype is known at run time only.  Whatever the dtype, the load
+// is that of the aligned 32-bit word that holds the element (same page as the element, so it
+// cannot fault; for a 16-bit element the other half of the word is dropped): one form of load, no
+// branch on the dtype in front of it, so that the loads of several elements or operands can be in
+// flight together.
+template <int POL> DEV float load_rt(const void* p, uint32_t i, uint32_t dt) {
+  const uint64_t at = (uint64_t)(__UINTPTR_TYPE__)p + (uint64_t)i * (dt == GPUOS_F32 ? 4u : 2u);
+  const uint32_t w = Mem<POL>::ld4((const void*)(__UINTPTR_TYPE__)(at & ~3ull), 0);
+  const uint32_t h = ((uint32_t)at & 2u) ? (w >> 16) : (w & 0xffffu);
+  const uint32_t m_f32 = dt == GPUOS_F32 ? ~0u : 0u, m_f16 = dt == GPUOS_F16 ? ~0u : 0u, m_bf16 = dt == GPUOS_BF16 ? ~0u : 0u;
+  return __builtin_bit_cast(float, (w & m_f32) | (__builtin_bit_cast(uint32_t, h2f(h)) & m_f16) | ((h << 16) & m_bf16));
 }
 template <int POL> DEV void store_rt(void* p, uint32_t i, uint32_t dt, float f) {
   if (dt == GPUOS_F32) Mem<POL>::st4(p, i, __builtin_bit_cast(uint32_t, f));
@@ -606,11 +613,56 @@ PATHFN void ew_tile2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float
   const uint32_t odt = uni(r->dtype[3]);
   const float alpha = r->alpha;
   const uint32_t tid = threadIdx.x;
+  uint32_t m_f32[3], m_f16[3], m_bf16[3];                  // all ones for the input's dtype
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    m_f32[k] = dt[k] == GPUOS_F32 ? ~0u : 0u;
+    m_f16[k] = dt[k] == GPUOS_F16 ? ~0u : 0u;
+    m_bf16[k] = dt[k] == GPUOS_BF16 ? ~0u : 0u;
+  }
   for (uint32_t t = tile_begin; t < tile_end; ++t) {
     const uint32_t b = t / (tr * tc), rem = t - b * tr * tc;
     const uint32_t ti = rem / tc, tj = rem - ti * tc;
     const uint32_t r0 = ti * kTile, c0 = tj * kTile;
-    // stage the transposed operands: lanes run along r (their contiguous dim)
+    // Everything the tile needs is requested first, four elements per lane and input, and used
+    // afterwards: one memory latency per tile, not one per element.  A transposed input is read
+    // with the lanes along r (its contiguous dim), the others along c, where they are used; a lane
+    // outside the tensor reads the tile's first element instead (in bounds) and drops it.  Whatever
+    // the dtype, the load is that of the aligned 32-bit word that holds the element (same page, so
+    // it cannot fault; the other half of the word is dropped): one form of load for every input,
+    // no branch between the requests.
+    uint32_t raw[3][4], upper[3][4];
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const uint32_t es = dt[k] == GPUOS_F32 ? 4u : 2u;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t idx = tid + i * kThreads, lo5 = idx & (kTile - 1), hi5 = idx / kTile;
+        uint32_t off;
+        if (kind[k] == K_TRANSPOSED) {
+          const bool in = r0 + lo5 < R && c0 + hi5 < C;
+          off = b * sb[k] + r0 + c0 * sc[k] + (in ? lo5 + hi5 * sc[k] : 0u);
+        } else {
+          const bool in = r0 + hi5 < R && c0 + lo5 < C;
+          off = b * sb[k] + r0 * sr[k] + c0 + (in ? hi5 * sr[k] + lo5 : 0u);
+        }
+        const uint64_t at = (uint64_t)(__UINTPTR_TYPE__)p[k] + (uint64_t)off * es;
+        upper[k][i] = (uint32_t)at & 2u;
+        raw[k][i] = Mem<POL>::ld4((const void*)(__UINTPTR_TYPE__)(at & ~3ull), 0);
+      }
+    }
+    float x[3][4];
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // (masks, not branches on the dtype)
+        const uint32_t w = k < N ? raw[k][i] : 0u;
+        const uint32_t h = (k < N && upper[k][i]) ? (w >> 16) : (w & 0xffffu);
+        const uint32_t bits = (w & m_f32[k]) | (__builtin_bit_cast(uint32_t, h2f(h)) & m_f16[k]) | ((h << 16) & m_bf16[k]);
+        x[k][i] = k < N ? __builtin_bit_cast(float, bits) : 0.0f;
+      }
+    // the transposed operands go through LDS: written along r, read back along c
 #pragma unroll
     for (int k = 0; k < N; ++k)
       if (kind[k] == K_TRANSPOSED) {
@@ -618,23 +670,25 @@ PATHFN void ew_tile2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const uint32_t idx = tid + i * kThreads, rr = idx & (kTile - 1), cc = idx / kTile;
-          if (r0 + rr < R && c0 + cc < C)
-            tile[cc * kTilePitch + rr] = load_rt<POL>(p[k], b * sb[k] + (r0 + rr) + (c0 + cc) * sc[k], dt[k]);
+          tile[cc * kTilePitch + rr] = x[k][i];
         }
       }
     __syncthreads();
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+      if (kind[k] == K_TRANSPOSED) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t idx = tid + i * kThreads, cc = idx & (kTile - 1), rr = idx / kTile;
+          x[k][i] = s_scratch[k * (kTile * kTilePitch) + cc * kTilePitch + rr];
+        }
+      }
     // compute: lanes run along c (the output's contiguous dim)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t idx = tid + i * kThreads, cc = idx & (kTile - 1), rr = idx / kTile;
-      if (r0 + rr < R && c0 + cc < C) {
-        float x[3] = {0.f, 0.f, 0.f};
-#pragma unroll
-        for (int k = 0; k < N; ++k)
-          x[k] = kind[k] == K_TRANSPOSED ? s_scratch[k * (kTile * kTilePitch) + cc * kTilePitch + rr]
-                                         : load_rt<POL>(p[k], b * sb[k] + (r0 + rr) * sr[k] + (c0 + cc), dt[k]);
-        store_rt<POL>(po, (b * R + r0 + rr) * C + c0 + cc, odt, Op<IMPL>::f(x[0], x[1], x[2], alpha));
-      }
+      if (r0 + rr < R && c0 + cc < C)
+        store_rt<POL>(po, (b * R + r0 + rr) * C + c0 + cc, odt, Op<IMPL>::f(x[0][i], x[1][i], x[2][i], alpha));
     }
     __syncthreads();                  // the tiles are rewritten by the next iteration
   }
@@ -652,6 +706,137 @@ PATHFN void ew_tile2d(const Record* r_v, uint32_t begin_v, uint32_t end_v, float
 // round instead.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kStageRound = 4u * kThreads;
+constexpr int kStageLoads = 4;             // 16-byte loads per lane and input in flight while a window is staged
+
+struct StagedCtx {     // what every round of a chunk shares (workgroup-uniform)
+  const char* p[3];
+  uint32_t dt[3], es[3], sb[3], sr[3], sc[3];
+  uint32_t m_f32[3], m_f16[3], m_bf16[3];  // all ones for the input's dtype
+  uint32_t R, C, RC, odt, oes, begin;
+  char* po;
+  rsrc_t ro;                               // the output rebased to the chunk: stores past it are dropped
+  float alpha;
+  char* lds;
+};
+template <int IMPL> DEV void staged_ctx(StagedCtx& c, const Record* r, uint32_t begin, uint32_t end, char* lds) {
+  constexpr int N = Op<IMPL>::N;
+  c.R = uni(r->size[1]); c.C = uni(r->size[2]); c.RC = c.R * c.C;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int kk = k < N ? k : 0;
+    c.p[k] = uni_ptr(r->ptr[kk]);
+    c.dt[k] = uni(r->dtype[kk]);
+    c.es[k] = c.dt[k] == GPUOS_F32 ? 4u : 2u;
+    c.sb[k] = uni(r->stride[kk][0]); c.sr[k] = uni(r->stride[kk][1]); c.sc[k] = uni(r->stride[kk][2]);
+    c.m_f32[k] = c.dt[k] == GPUOS_F32 ? ~0u : 0u;
+    c.m_f16[k] = c.dt[k] == GPUOS_F16 ? ~0u : 0u;
+    c.m_bf16[k] = c.dt[k] == GPUOS_BF16 ? ~0u : 0u;
+  }
+  c.odt = uni(r->dtype[3]);
+  c.oes = c.odt == GPUOS_F32 ? 4u : 2u;
+  c.po = (char*)uni_ptr(r->ptr[3]);
+  c.ro = make_rsrc(c.po + (uint64_t)begin * c.oes, (end - begin) * c.oes);
+  c.alpha = r->alpha;
+  c.begin = begin;
+  c.lds = lds;
+}
+
+// One round's gather, arithmetic and store: the elements [c0, c1) of the output, inputs staged at
+// g_region (element g_lo of input k lies at byte g_region[k] of the LDS scratch).  FULL: the round
+// has all its 1,024 elements (every lane four live ones, one whole-vector store).  ALL_STAGED:
+// every input is in LDS, and the round holds no memory load at all.
+template <int POL, int IMPL, bool FULL, bool ALL_STAGED>
+DEV void staged_round(const StagedCtx& c, uint32_t c0, uint32_t c1, const uint32_t (&g_lo)[3], const uint32_t (&g_region)[3],
+                      const bool (&g_staged)[3]) {
+  using M = Mem<POL>;
+  constexpr int N = Op<IMPL>::N;
+  const uint32_t i = c0 + 4u * threadIdx.x;
+  if (!FULL && i >= c1) return;
+  uint32_t b = i / c.RC;
+  const uint32_t j = i - b * c.RC;
+  uint32_t row = j / c.C, col = j - row * c.C;
+  float x[3][4], o[4];
+  // the four elements' offsets first, then every read of a staged input in one go (one LDS latency
+  // per input, not one per element): the aligned word that holds the element is read whatever the
+  // dtype and the element is cut out of it afterwards
+  uint32_t off[3][4];
+  bool live[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    live[e] = FULL || i + e < c1;
+#pragma unroll
+    for (int k = 0; k < N; ++k) off[k][e] = b * c.sb[k] + row * c.sr[k] + col * c.sc[k];
+    if (++col == c.C) { col = 0; if (++row == c.R) { row = 0; ++b; } }
+  }
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    if (k >= N) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[k][e] = 0.0f;
+    } else if (ALL_STAGED || g_staged[k]) {
+      uint32_t w[4], at_byte[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        at_byte[e] = live[e] ? g_region[k] + (off[k][e] - g_lo[k]) * c.es[k] : g_region[k];
+        w[e] = *(const uint32_t*)(c.lds + (at_byte[e] & ~3u));
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        // (masks, not branches on the dtype: the three decodings are a handful of operations)
+        const uint32_t h = (at_byte[e] & 2u) ? (w[e] >> 16) : (w[e] & 0xffffu);
+        const uint32_t bits = (w[e] & c.m_f32[k]) | (__builtin_bit_cast(uint32_t, h2f(h)) & c.m_f16[k]) | ((h << 16) & c.m_bf16[k]);
+        x[k][e] = live[e] ? __builtin_bit_cast(float, bits) : 0.0f;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[k][e] = live[e] ? load_rt<POL>(c.p[k], off[k][e], c.dt[k]) : 0.0f;
+    }
+  }
+  apply_vec<IMPL, 4>(x[0], x[1], x[2], c.alpha, o);
+  const uint32_t rel = (i - c.begin) * c.oes;
+  if (FULL) {
+    // Both forms of the store are issued, the one that does not apply past the end of the window
+    // (dropped, no traffic): the number of stores a wavefront has in flight after a full round is
+    // then the same on every path, and the wait for the next round's vectors can leave them there.
+    v4i qo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) qo[e] = __builtin_bit_cast(int, o[e]);
+    uint32_t w0, w1;
+    if (c.odt == GPUOS_F16) { w0 = f2h(o[0]) | (f2h(o[1]) << 16); w1 = f2h(o[2]) | (f2h(o[3]) << 16); }
+    else { w0 = f2b(o[0]) | (f2b(o[1]) << 16); w1 = f2b(o[2]) | (f2b(o[3]) << 16); }
+    M::st16(c.ro, c.odt == GPUOS_F32 ? rel : kNoLoad, qo);
+    M::st8(c.ro, c.odt == GPUOS_F32 ? kNoLoad : rel, w0, w1);
+  } else if (i + 4u <= c1) {
+    if (c.odt == GPUOS_F32) {
+      v4i qo;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) qo[e] = __builtin_bit_cast(int, o[e]);
+      M::st16(c.ro, rel, qo);
+    } else {
+      uint32_t w0, w1;
+      if (c.odt == GPUOS_F16) { w0 = f2h(o[0]) | (f2h(o[1]) << 16); w1 = f2h(o[2]) | (f2h(o[3]) << 16); }
+      else { w0 = f2b(o[0]) | (f2b(o[1]) << 16); w1 = f2b(o[2]) | (f2b(o[3]) << 16); }
+      M::st8(c.ro, rel, w0, w1);
+    }
+  } else {
+    for (uint32_t e = 0; i + e < c1; ++e) store_rt<POL>(c.po, i + e, c.odt, o[e]);      // the chunk's ragged end
+  }
+}
+
+// A round with an input whose window does not fit the LDS scratch (that input is read element by
+// element): a function of its own, so that its memory loads and the waits for them stay out of the
+// common round's code.
+template <int POL, int IMPL>
+PATHFN void ew_staged_slow_round(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v, uint32_t c0_v, uint32_t c1_v,
+                                 uint32_t lo0, uint32_t lo1, uint32_t lo2, uint32_t rg0, uint32_t rg1, uint32_t rg2, uint32_t staged_mask_v) {
+  const Record* r = lds_arg(r_v);
+  StagedCtx c;
+  staged_ctx<IMPL>(c, r, uni(begin_v), uni(end_v), (char*)lds_arg(s_v));
+  const uint32_t g_lo[3] = {uni(lo0), uni(lo1), uni(lo2)}, g_region[3] = {uni(rg0), uni(rg1), uni(rg2)};
+  const uint32_t mask = uni(staged_mask_v);
+  const bool g_staged[3] = {(mask & 1u) != 0, (mask & 2u) != 0, (mask & 4u) != 0};
+  staged_round<POL, IMPL, false, false>(c, uni(c0_v), uni(c1_v), g_lo, g_region, g_staged);
+}
 
 template <int POL, int IMPL>
 PATHFN void ew_staged(const Record* r_v, uint32_t begin_v, uint32_t end_v, float* s_v) {
@@ -660,99 +845,123 @@ PATHFN void ew_staged(const Record* r_v, uint32_t begin_v, uint32_t end_v, float
   char* lds = (char*)lds_arg(s_v);
   using M = Mem<POL>;
   constexpr int N = Op<IMPL>::N;
-  const uint32_t R = uni(r->size[1]), C = uni(r->size[2]), RC = R * C;
-  const char* p[3];
-  uint32_t dt[3], es[3], sb[3], sr[3], sc[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    const int kk = k < N ? k : 0;
-    p[k] = uni_ptr(r->ptr[kk]);
-    dt[k] = uni(r->dtype[kk]);
-    es[k] = dt[k] == GPUOS_F32 ? 4u : 2u;
-    sb[k] = uni(r->stride[kk][0]); sr[k] = uni(r->stride[kk][1]); sc[k] = uni(r->stride[kk][2]);
-  }
-  const uint32_t odt = uni(r->dtype[3]), oes = odt == GPUOS_F32 ? 4u : 2u;
-  char* po = (char*)uni_ptr(r->ptr[3]);
-  const rsrc_t ro = make_rsrc(po + (uint64_t)begin * oes, (end - begin) * oes);    // rebased to the chunk: stores past it are dropped
-  const float alpha = r->alpha;
+  StagedCtx c;
+  staged_ctx<IMPL>(c, r, begin, end, lds);
   const uint32_t tid = threadIdx.x;
   constexpr uint32_t kLdsBytes = kScratchFloats * 4u;
-  for (uint32_t i0 = begin; i0 < end; i0 += kStageRound) {
-    const uint32_t i1 = (end - i0 < kStageRound) ? end : i0 + kStageRound;
-    // indices of the first and the last element of the round (uniform)
-    const uint32_t ba = i0 / RC, ja = i0 - ba * RC, ra = ja / C, ca = ja - ra * C;
-    const uint32_t bb = (i1 - 1) / RC, jb = (i1 - 1) - bb * RC, rb = jb / C, cb = jb - rb * C;
-    uint32_t lo[3], region[3];
-    bool staged[3];
+  constexpr uint32_t kBatchBytes = kStageLoads * kThreads * 16u;
+  static_assert(kStageLoads == 4, "the pin in stash() names four vectors");
+  // What a round stages (uniform): for every input the 16-byte window of memory its elements lie in.
+  uint32_t lo[3] = {0, 0, 0}, region[3] = {0, 0, 0}, at[3], nbs[3], most = 0;
+  bool staged[3] = {true, true, true};
+  rsrc_t rs[3];
+  auto plan = [&](uint32_t i0, uint32_t i1) {
+    // indices of the first and the last element of the round
+    const uint32_t ba = i0 / c.RC, ja = i0 - ba * c.RC, ra = ja / c.C, ca = ja - ra * c.C;
+    const uint32_t bb = (i1 - 1) / c.RC, jb = (i1 - 1) - bb * c.RC, rb = jb / c.C, cb = jb - rb * c.C;
     uint32_t used = 0;
+    most = 0;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
       // bounds on the element offsets the round can touch (strides are non-negative): exact up to
       // the outermost index in which its first and last element differ, everything inside that
       uint32_t first, last;
-      if (ba != bb) { first = ba * sb[k]; last = bb * sb[k] + (R - 1u) * sr[k] + (C - 1u) * sc[k]; }
-      else if (ra != rb) { first = ba * sb[k] + ra * sr[k]; last = ba * sb[k] + rb * sr[k] + (C - 1u) * sc[k]; }
-      else { first = ba * sb[k] + ra * sr[k] + ca * sc[k]; last = ba * sb[k] + ra * sr[k] + cb * sc[k]; }
-      // the span in whole 16-byte vectors of the address space (the base need not be aligned)
-      const uint64_t a_first = (uint64_t)(__UINTPTR_TYPE__)p[k] + (uint64_t)first * es[k];
-      const uint64_t a_last = (uint64_t)(__UINTPTR_TYPE__)p[k] + (uint64_t)last * es[k] + es[k];
+      if (ba != bb) { first = ba * c.sb[k]; last = bb * c.sb[k] + (c.R - 1u) * c.sr[k] + (c.C - 1u) * c.sc[k]; }
+      else if (ra != rb) { first = ba * c.sb[k] + ra * c.sr[k]; last = ba * c.sb[k] + rb * c.sr[k] + (c.C - 1u) * c.sc[k]; }
+      else { first = ba * c.sb[k] + ra * c.sr[k] + ca * c.sc[k]; last = ba * c.sb[k] + ra * c.sr[k] + cb * c.sc[k]; }
+      // the window in whole 16-byte vectors of the address space (the base need not be aligned)
+      const uint64_t a_first = (uint64_t)(__UINTPTR_TYPE__)c.p[k] + (uint64_t)first * c.es[k];
+      const uint64_t a_last = (uint64_t)(__UINTPTR_TYPE__)c.p[k] + (uint64_t)last * c.es[k] + c.es[k];
       const uint64_t v_first = a_first & ~15ull;
       const uint64_t bytes = ((a_last + 15ull) & ~15ull) - v_first;
       staged[k] = bytes <= (uint64_t)(kLdsBytes - used);
       lo[k] = first;
-      region[k] = used;
-      if (staged[k]) {
-        const uint32_t nb = (uint32_t)bytes;
-        const rsrc_t rs = make_rsrc((const void*)(__UINTPTR_TYPE__)v_first, nb);
-        for (uint32_t v = tid; v < nb / 16u; v += kThreads)
-          *(v4i*)(lds + used + v * 16u) = M::ld16(rs, v * 16u);
-        region[k] = used + (uint32_t)(a_first - v_first);          // where element `first` lies inside the staged bytes
-        used += nb;
-      }
+      // an input that is not staged gets an empty window: its loads fetch nothing
+      nbs[k] = staged[k] ? (uint32_t)bytes : 0u;
+      rs[k] = make_rsrc((const void*)(__UINTPTR_TYPE__)v_first, nbs[k]);
+      at[k] = used;
+      region[k] = used + (uint32_t)(a_first - v_first);            // where element `first` lies inside the staged bytes
+      used += nbs[k];
+      most = nbs[k] > most ? nbs[k] : most;
     }
+  };
+  // The windows of all inputs move together, kStageLoads vectors per lane and input in flight: every
+  // load of a batch is issued before the first one is written to LDS (one memory latency per batch,
+  // not one per vector and input).  Loads past a window's end are dropped by its bounds check.
+  v4i q[N][kStageLoads];
+  auto issue = [&](uint32_t b0) {
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+#pragma unroll
+      for (int u = 0; u < kStageLoads; ++u) q[k][u] = M::ld16(rs[k], b0 + (tid + u * kThreads) * 16u);
+  };
+  auto stash = [&](uint32_t b0) {
+    // (the values are pinned here: a load used only under the condition below would be moved there,
+    // behind the waits of the stores before it)
+#pragma unroll
+    for (int k = 0; k < N; ++k) asm volatile("" : "+v"(q[k][0]), "+v"(q[k][1]), "+v"(q[k][2]), "+v"(q[k][3]));
+#pragma unroll
+    for (int k = 0; k < N; ++k)
+#pragma unroll
+      for (int u = 0; u < kStageLoads; ++u) {
+        const uint32_t off = b0 + (tid + u * kThreads) * 16u;
+        if (off < nbs[k]) *(v4i*)(lds + at[k] + off) = q[k][u];
+      }
+  };
+  // Rounds are pipelined: the first batch of the NEXT round's windows is requested before this
+  // round's elements are gathered and computed, so from the second round on the memory latency
+  // hides behind the round before.  A round that has a successor is a full one, and every
+  // wavefront issues exactly one store in it after those requests: the wait for the requested
+  // vectors can leave that one store in flight.
+  uint32_t i0 = begin, i1 = (end - begin < kStageRound) ? end : begin + kStageRound;
+  plan(i0, i1);
+  issue(0);
+  stash(0);
+  for (uint32_t b0 = kBatchBytes; b0 < most; b0 += kBatchBytes) { issue(b0); stash(b0); }
+  __syncthreads();
+  uint32_t c0, c1, g_lo[3], g_region[3];
+  bool g_staged[3], all_staged;
+  auto take = [&]() {                 // this round's share of the plan; the plan itself moves on
+    c0 = i0; c1 = i1;
+    all_staged = true;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      g_lo[k] = lo[k]; g_region[k] = region[k]; g_staged[k] = staged[k];
+      if (k < N) all_staged = all_staged && staged[k];
+    }
+  };
+  auto slow_round = [&]() {
+    const uint32_t mask = (g_staged[0] ? 1u : 0u) | (g_staged[1] ? 2u : 0u) | (g_staged[2] ? 4u : 0u);
+    ew_staged_slow_round<POL, IMPL>(r_v, begin, end, s_v, c0, c1, g_lo[0], g_lo[1], g_lo[2], g_region[0], g_region[1], g_region[2], mask);
+  };
+  while (i1 < end) {                  // a round with a successor
+    take();
+    if (!all_staged) break;           // (rare) the rest of the chunk goes round by round below
+    i0 = c1;
+    i1 = (end - i0 < kStageRound) ? end : i0 + kStageRound;
+    plan(i0, i1);
+    issue(0);
+    staged_round<POL, IMPL, true, true>(c, c0, c1, g_lo, g_region, g_staged);
+    __syncthreads();                  // the staged windows may be overwritten now
+    stash(0);
+    for (uint32_t b0 = kBatchBytes; b0 < most; b0 += kBatchBytes) { issue(b0); stash(b0); }
     __syncthreads();
-    const uint32_t i = i0 + 4u * tid;
-    if (i < i1) {
-      uint32_t b = i / RC;
-      const uint32_t j = i - b * RC;
-      uint32_t row = j / C, col = j - row * C;
-      float x[3][4], o[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-#pragma unroll
-        for (int k = 0; k < 3; ++k) {
-          x[k][e] = 0.0f;
-          if (k < N && i + e < i1) {
-            const uint32_t off = b * sb[k] + row * sr[k] + col * sc[k];
-            if (staged[k]) {
-              const char* q = lds + region[k] + (off - lo[k]) * es[k];
-              x[k][e] = dt[k] == GPUOS_F32 ? *(const float*)q : (dt[k] == GPUOS_F16 ? h2f(*(const uint16_t*)q) : b2f(*(const uint16_t*)q));
-            } else {
-              x[k][e] = load_rt<POL>(p[k], off, dt[k]);
-            }
-          }
-        }
-        if (++col == C) { col = 0; if (++row == R) { row = 0; ++b; } }
-      }
-      apply_vec<IMPL, 4>(x[0], x[1], x[2], alpha, o);
-      const uint32_t rel = (i - begin) * oes;
-      if (i + 4u <= i1) {
-        if (odt == GPUOS_F32) {
-          v4i q;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) q[e] = __builtin_bit_cast(int, o[e]);
-          M::st16(ro, rel, q);
-        } else {
-          uint32_t w0, w1;
-          if (odt == GPUOS_F16) { w0 = f2h(o[0]) | (f2h(o[1]) << 16); w1 = f2h(o[2]) | (f2h(o[3]) << 16); }
-          else { w0 = f2b(o[0]) | (f2b(o[1]) << 16); w1 = f2b(o[2]) | (f2b(o[3]) << 16); }
-          M::st8(ro, rel, w0, w1);
-        }
-      } else {
-        for (uint32_t e = 0; i + e < i1; ++e) store_rt<POL>(po, i + e, odt, o[e]);      // the chunk's ragged end
-      }
-    }
-    __syncthreads();                  // the staged spans are overwritten by the next round
+  }
+  // The chunk's last round, and every round from the first one on that has an input too wide to
+  // stage: one after the other.
+  for (;;) {
+    take();
+    if (all_staged) staged_round<POL, IMPL, false, true>(c, c0, c1, g_lo, g_region, g_staged);
+    else slow_round();
+    __syncthreads();                  // the scratch may be reused (by the next round, by the next chunk)
+    if (i1 >= end) break;
+    i0 = c1;
+    i1 = (end - i0 < kStageRound) ? end : i0 + kStageRound;
+    plan(i0, i1);
+    issue(0);
+    stash(0);
+    for (uint32_t b0 = kBatchBytes; b0 < most; b0 += kBatchBytes) { issue(b0); stash(b0); }
+    __syncthreads();
   }
 }
 

@@ -150,6 +150,7 @@ struct Operand {              // one tensor after masking broadcast dims
 
 int check_operand(const gpuos_tensor& t, int ndim, const int64_t* size, bool is_out, Operand* o) {
   if (t.ptr == nullptr || t.dtype > GPUOS_I32) return GPUOS_E_INVAL;
+  if ((uint64_t)t.ptr % dtype_size(t.dtype) != 0) return GPUOS_E_INVAL;   // elements are naturally aligned
   if (is_out && t.bcast_mask != 0) return GPUOS_E_INVAL;
   int64_t max_off = 0;
   o->ptr = (uint64_t)t.ptr;
@@ -467,9 +468,10 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
       uint64_t quarter = (((uint64_t)numel + 3) / 4 + 1023) / 1024 * 1024;
       uint64_t half = (base_per / 2 + 1023) / 1024 * 1024;
       if (rec.path == PATH_STAGED) {
-        // the gather path works in rounds of 1,024 elements, each a chain of latencies (load the
-        // covering span, stage, gather, store: 2-3 us): a task of a few dozen rounds is spread
-        // over up to 32 workgroups, two rounds each at least
+        // the gather path works in rounds of 1,024 elements (load the covering windows, stage,
+        // gather, store: the first about 1.5 us, the following ones, whose loads are requested a
+        // round ahead, about half of that): a task of a few dozen rounds is spread over up to 32
+        // workgroups, two rounds each at least
         quarter = (((uint64_t)numel + 31) / 32 + 1023) / 1024 * 1024;
         half = 2048;
       }

@@ -271,6 +271,11 @@ class Runtime:
 
     def wait(self, ticket=ALL, timeout_ns=0, check=True):
         rc = lib().gpuos_wait(self._ctx, ticket, timeout_ns)
+        if check and rc in (E_TIMEOUT, E_DEAD):
+            # a wait that ran out of time, or whose worker left: say where the queue stands
+            q = self.peek_queue()
+            _check(rc, "gpuos_wait [submitted %d, published %d, units claimed %d, tasks completed %d, worker alive %s]" % (
+                q.head_submitted, q.tail_published, q.claimed, q.completed, self.worker_alive()))
         if check:
             _check(rc, "gpuos_wait")
         return rc

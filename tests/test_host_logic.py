@@ -51,7 +51,7 @@ def _damage_and_compare(s, rng, trials):
     for trial in range(trials):
         i = int(rng.integers(len(T)))
         t = T[i:i + 1].copy()
-        kind = int(rng.integers(12))
+        kind = int(rng.integers(13))
         if kind == 0: t["ndim"][0] = rng.integers(0, 9)
         elif kind == 1: t["n_inputs"][0] = rng.integers(0, 4)
         elif kind == 2: t["inp"]["stride"][0, rng.integers(3), rng.integers(6)] = rng.integers(-3, 3)
@@ -63,6 +63,9 @@ def _damage_and_compare(s, rng, trials):
         elif kind == 8: t["size"][0, rng.integers(6)] = rng.choice([-1, 0, 1, 1 << 20, 1 << 31, (1 << 31) - 1])
         elif kind == 9: t["inp"]["bcast_mask"][0, rng.integers(3)] = rng.integers(0, 64)
         elif kind == 10: t["inp"]["stride"][0, rng.integers(3), rng.integers(6)] = 1 << 31
+        elif kind == 12:                                  # an address that may be no multiple of the element size
+            if rng.integers(2): t["inp"]["ptr"][0, rng.integers(3)] += rng.integers(1, 4)
+            else: t["out"]["ptr"][0] += rng.integers(1, 4)
         use_impl = int(impl[i]) if kind != 11 else int(rng.integers(0, 20))
         got, _ = _status(t, 0, use_impl)
         want = oracle.validate(t, 0, use_impl)

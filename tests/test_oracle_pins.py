@@ -262,6 +262,9 @@ def test_validation_rules():
     T["out"]["stride"][0, 1] = 0; assert v() == -1; T["out"]["stride"][0, 1] = 1
     T["inp"]["stride"][0, 0, 0] = -1; assert v() == -1; T["inp"]["stride"][0, 0, 0] = 3
     T["inp"]["ptr"][0, 1] = 0; assert v() == -1; T["inp"]["ptr"][0, 1] = T["inp"]["ptr"][0, 0]
+    T["inp"]["ptr"][0, 1] += 2; assert v() == -1       # a 32-bit element at an address that is no multiple of 4
+    T["out"]["ptr"][0] += 1; T["inp"]["ptr"][0, 1] -= 2; assert v() == -1
+    T["out"]["ptr"][0] -= 1; assert v() == 0
     T["inp"]["dtype"][0, 0] = 9; assert v() == -1; T["inp"]["dtype"][0, 0] = S.I32
     assert v() == -1                                   # int and float tensors mixed
     T["inp"]["dtype"][0, 0] = S.F32
