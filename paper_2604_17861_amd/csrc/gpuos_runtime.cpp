@@ -1062,6 +1062,10 @@ int gpuos_init(gpuos_ctx** out, uint32_t queue_capacity, const gpuos_config* use
       !hip_ok(hipMemsetAsync(c->d, 0, sizeof(DevCtl), c->stream), "hipMemsetAsync") ||
       !hip_ok(hipMemsetAsync(c->st, 0, sizeof(SlotState) * cap, c->stream), "hipMemsetAsync") ||
       !hip_ok(hipMemsetAsync(c->units, 0, sizeof(uint64_t) * n_units, c->stream), "hipMemsetAsync") ||
+      // The mirror ring too: a worker takes a mirrored record on the strength of its check word and
+      // ticket alone, and the allocator hands a new context the block an earlier context of this
+      // process freed, where the record of that context's task with the same ticket would pass.
+      !hip_ok(hipMemsetAsync(c->dring, 0, sizeof(Record) * cap, c->stream), "hipMemsetAsync") ||
       !hip_ok(hipMemsetAsync(c->dtable, 0, sizeof(OpSlots) * GPUOS_MAX_OPS, c->stream), "hipMemsetAsync") ||
       (c->units_j && !hip_ok(hipMemsetAsync(c->units_j, 0, sizeof(uint64_t) * n_units, c->stream), "hipMemsetAsync")) ||
       !hip_ok(hipStreamSynchronize(c->stream), "hipStreamSynchronize"))

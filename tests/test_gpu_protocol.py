@@ -235,6 +235,24 @@ def test_shutdown_drains_tasks_in_flight_and_is_idempotent():
     assert compare_with_oracle(s, dp.download())["max_ulp"] == 0
 
 
+def test_a_new_context_takes_nothing_an_earlier_one_left_in_device_memory():
+    """Contexts created one after the other in a process get the same device blocks back from the
+    allocator, and each numbers its tickets from 0: a descriptor the earlier context left in the
+    device-side mirror would carry a valid check word for the same ticket of the later one.  Every
+    task of every context runs, on its own descriptor."""
+    from gpu_helpers import compare_with_oracle
+    for rep in range(6):
+        s = _simple_adds(3000, 3000, seed=10 + rep)
+        dp = _dev(s)
+        with R.Runtime(0, **CFG) as rt:
+            rt.register_table(s.table)
+            for i in range(0, len(s), 500):
+                rt.submit(dp.tasks, i, 500)
+            rt.wait()
+            assert rt.peek_queue().completed == len(s)
+        assert compare_with_oracle(s, dp.download())["max_ulp"] == 0
+
+
 def test_idle_watchdog_exits_the_worker():
     s = _simple_adds(4, 1024)
     dp = _dev(s)
