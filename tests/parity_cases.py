@@ -512,7 +512,8 @@ def staged_gathers():
     """Contiguous outputs whose inputs are stride-2 / 3 / 4 / 9 slices at every phase of a 16-byte
     vector, row vectors of odd lengths, column vectors over few rows, batches of small transposes,
     operands of other dtypes, three gathered operands at once, spans too large for the staging
-    memory (read element by element instead), several chunks with a ragged end, special values: the
+    memory (read element by element instead), also in turn with spans that fit, several chunks with
+    a ragged end, special values: the
     layouts the LDS-staged gather path takes, all float dtypes in and out."""
     rng = np.random.default_rng(31)
     b = Builder()
@@ -556,6 +557,13 @@ def staged_gathers():
         wide = T((130, 2 * 264), code)
         o = b.pool(np.zeros((130, 264), np_dtype(code)))
         b.add("SUB_EXP", o, [wide[:, ::2], wide[:, 1::2]])               # two column-strided matrices (rows do not merge)
+        # rows far apart: a round inside a row stages its window, a round that crosses into the next
+        # row has a window too wide for the staging memory, so both kinds alternate within the chunks
+        far = T((6, 20000), code)[:, :3000:2]
+        o = b.pool(np.zeros((6, 1500), np_dtype(ocode)))
+        b.add("ADD", o, [far, T((6, 1500), code)])
+        o = b.pool(np.zeros((6, 1500), np_dtype(code)))
+        b.add("GELU_TANH", o, [far])
     return b.stream("staged_gathers")
 
 
