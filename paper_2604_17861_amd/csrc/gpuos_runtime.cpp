@@ -418,8 +418,10 @@ int pack_task(const gpuos_task& t, uint32_t impl, Record* r, uint32_t chunk_elem
         const uint64_t tiles = (uint64_t)B * ((R + 31) / 32) * ((C + 31) / 32);
         uint64_t per_t = (tiles + kMaxChunksPerTask - 1) / kMaxChunksPerTask;
         // tiles of 1024 elements.  A workgroup takes a tile at a time (load, transpose through LDS,
-        // store: about 5 us alone), so a task of few tiles is spread over as many workgroups as it
-        // has tiles, up to 64, before chunks grow to the regular size.
+        // store: 1.5-2 us alone), so a task of few tiles is spread over as many workgroups as it
+        // has tiles, up to 64, before chunks grow to the regular size.  (Two tiles per workgroup
+        // at least, measured: config2 within its run-to-run spread, a lone transposed task 1.3 us
+        // slower.)
         uint64_t want = chunk_elems / 1024 ? chunk_elems / 1024 : 1;
         const uint64_t spread = (tiles + 63) / 64;
         if (spread < want) want = spread;
