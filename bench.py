@@ -309,6 +309,8 @@ def main():
     ap.add_argument("--only-config3", action="store_true",
                     help="run nothing but the third configuration (chains, then one fused task per chain) through the "
                          "persistent kernel, one worker lifetime each (for profiler runs)")
+    ap.add_argument("--only-transposed", action="store_true",
+                    help="only a stream of elementwise tasks over transposed matrices (the LDS-tiled path), one worker lifetime")
     ap.add_argument("--only-strided", action="store_true",
                     help="run nothing but 2,000 elementwise tasks over stride-2 inputs (1M elements each) through the "
                          "persistent kernel (for profiler runs: traffic of the LDS-staged gather path)")
@@ -374,6 +376,27 @@ def main():
             del dp3
         print(json.dumps(dict(workload="config3: 2,000 softmax chains of six tasks, then the same as one fused task per chain",
                               **res3)), flush=True)
+        return
+    if args.only_transposed:
+        n, side = 2000, 1024
+        numel = side * side
+        src = torch.randn(8 * numel, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty(8 * numel, dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        t, pool_of = S.new_tasks(n)
+        for i in range(n):                                     # out[r, c] = 0.5 * x[c, r]: eight input / output regions in turn
+            S.set_head(t, i, S.OP["SCALE"], [side, side], 1, alpha=0.5)
+            S.set_tensor(t, pool_of, i, 0, 0, src.data_ptr() + (i % 8) * numel * 4, [1, side], S.F32)
+            S.set_tensor(t, pool_of, i, 3, 0, dst.data_ptr() + (i % 8) * numel * 4, [side, 1], S.F32)
+        path = R.task_plan(t, 0, S.IMPL["SCALE"])[0]
+        with R.Runtime(0, idle_exit_ms=60000, **KNOBS) as rt:
+            rt.register_table(S.default_table())
+            rt.submit_from_threads(t, 1, 64, 1)
+            rt.wait()
+            rt.stop_worker()
+            kernel_ms = rt.worker_elapsed_ms()
+        print(json.dumps(dict(workload="%d SCALE tasks over the transposed view of a %d x %d fp32 matrix" % (n, side, side), path=path,
+                              algorithmic_bytes=n * numel * 8, kernel_ms=kernel_ms, gbps=n * numel * 8 / (kernel_ms * 1e-3) / 1e9)), flush=True)
         return
     if args.only_strided:
         n, numel = 2000, 1 << 20
